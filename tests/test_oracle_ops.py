@@ -1,0 +1,353 @@
+"""Pins of the operator-level CPU oracle against things other than itself:
+closed forms, invariants, library routines (torch CPU / scipy in float64), a
+hand-evaluated layer, brute force on tiny routings.  Each pin is chosen so that a
+plausible slip (dropped term, wrong sign or index, transposed operand) fails it.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as Fn
+
+import oracle
+from synth import ModelShape, Step, pages_needed
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+rng = np.random.default_rng(1234)
+
+
+def r32(*shape, scale=1.0):
+    return (rng.standard_normal(shape) * scale).astype(np.float32)
+
+
+# ---------------------------------------------------------------- RMSNorm
+def test_rmsnorm_constant_vector_closed_form():
+    H, c, eps = 64, 3.0, 1e-5
+    g = r32(H)
+    y = oracle.rmsnorm(np.full(H, c, np.float32), g, eps)
+    np.testing.assert_allclose(y, g * c / np.sqrt(c * c + eps), rtol=1e-6)
+
+
+def test_rmsnorm_unit_rms_and_scale_invariance():
+    x = r32(512)
+    y = oracle.rmsnorm(x, np.ones(512, np.float32), 0.0)
+    assert abs(np.sqrt(np.mean(y.astype(np.float64) ** 2)) - 1.0) < 1e-6
+    np.testing.assert_allclose(oracle.rmsnorm(7.5 * x, np.ones(512, np.float32), 0.0), y, rtol=2e-6)
+
+
+def test_rmsnorm_matches_torch_library():
+    x, g = r32(256), r32(256)
+    ref = Fn.rms_norm(torch.from_numpy(x).double(), (256,), torch.from_numpy(g).double(), eps=1e-5)
+    np.testing.assert_allclose(oracle.rmsnorm(x, g, 1e-5), ref.numpy(), rtol=1e-6, atol=1e-7)
+
+
+# ---------------------------------------------------------------- linear
+def test_linear_identity_onehot_and_orientation():
+    X = r32(3, 8)
+    np.testing.assert_array_equal(oracle.linear(np.eye(8, dtype=np.float32), X), X)
+    W = r32(5, 8)                       # [out, in]: a one-hot input picks a COLUMN of W
+    e2 = np.zeros((1, 8), np.float32)
+    e2[0, 2] = 1.0
+    np.testing.assert_array_equal(oracle.linear(W, e2)[0], W[:, 2])
+
+
+def test_linear_matches_float64_matmul():
+    W, X = r32(37, 129), r32(4, 129)
+    ref = X.astype(np.float64) @ W.astype(np.float64).T
+    np.testing.assert_allclose(oracle.linear(W, X), ref, rtol=1e-6, atol=1e-6)
+
+
+# ---------------------------------------------------------------- RoPE
+def test_rope_position_zero_is_identity():
+    v = r32(3, 16)
+    np.testing.assert_array_equal(oracle.rope(v, 0, 10000.0), v)
+
+
+def test_rope_onehot_closed_form_pairs_i_with_i_plus_half():
+    d, theta, pos = 8, 10000.0, 5
+    for i in range(d // 2):
+        v = np.zeros((1, d), np.float32)
+        v[0, i] = 1.0
+        ang = pos * theta ** (-2.0 * i / d)
+        exp = np.zeros(d)
+        exp[i], exp[i + d // 2] = np.cos(ang), np.sin(ang)
+        np.testing.assert_allclose(oracle.rope(v, pos, theta)[0], exp, atol=1e-6)
+        v2 = np.zeros((1, d), np.float32)
+        v2[0, i + d // 2] = 1.0
+        exp2 = np.zeros(d)
+        exp2[i], exp2[i + d // 2] = -np.sin(ang), np.cos(ang)
+        np.testing.assert_allclose(oracle.rope(v2, pos, theta)[0], exp2, atol=1e-6)
+
+
+def test_rope_norm_additivity_and_relative_position():
+    d, theta = 32, 10000.0
+    q, k = r32(1, d), r32(1, d)
+    half = d // 2
+    rq = oracle.rope(q, 17, theta)
+    np.testing.assert_allclose(rq[0, :half] ** 2 + rq[0, half:] ** 2, q[0, :half] ** 2 + q[0, half:] ** 2,
+                               rtol=1e-5)
+    np.testing.assert_allclose(oracle.rope(oracle.rope(q, 5, theta), 12, theta), rq, atol=1e-5)
+    # <rope(q, m), rope(k, n)> depends on m - n only
+    a = float(oracle.rope(q, 40, theta)[0].astype(np.float64) @ oracle.rope(k, 33, theta)[0].astype(np.float64))
+    b = float(oracle.rope(q, 7, theta)[0].astype(np.float64) @ k[0].astype(np.float64))
+    assert abs(a - b) < 1e-4
+
+
+# ---------------------------------------------------------------- SiLU
+def test_silu_known_values():
+    assert oracle.silu(0.0) == 0.0
+    assert abs(oracle.silu(1.0) - 0.7310585786300049) < 1e-15
+    assert abs(oracle.silu(-1.0) + 0.2689414213699951) < 1e-15
+    assert abs(oracle.silu(30.0) - 30.0) < 1e-11
+    z = np.linspace(-6, 6, 25)
+    ref = Fn.silu(torch.from_numpy(z)).numpy()
+    np.testing.assert_allclose([oracle.silu(v) for v in z], ref, rtol=1e-12, atol=1e-15)
+
+
+# ---------------------------------------------------------------- attention
+def _attn_setup(nq=4, nkv=2, d=16, page=4, n_keys=11, n_pool=9):
+    s = ModelShape("t", 1, nq * d, nq, nkv, d, 32, page=page)
+    sh = oracle.shape_of(s)
+    kpool, vpool = r32(n_pool, page, nkv, d), r32(n_pool, page, nkv, d)
+    pages = rng.permutation(n_pool)[: (n_keys + page - 1) // page].astype(np.int32)
+    return s, sh, kpool, vpool, pages
+
+
+def _contiguous(pool, pages, n_keys):
+    return np.concatenate([pool[p] for p in pages])[:n_keys]      # [n_keys, nkv, d]
+
+
+def test_attention_matches_torch_sdpa_with_grouped_heads():
+    s, sh, kpool, vpool, pages = _attn_setup()
+    n_keys = 11
+    q = r32(s.nq, s.d)
+    out = oracle.attention(sh, q, kpool, vpool, pages, n_keys)
+    K = torch.from_numpy(_contiguous(kpool, pages, n_keys)).double().permute(1, 0, 2)   # [nkv, n, d]
+    V = torch.from_numpy(_contiguous(vpool, pages, n_keys)).double().permute(1, 0, 2)
+    g = s.nq // s.nkv
+    K, V = K.repeat_interleave(g, dim=0), V.repeat_interleave(g, dim=0)                # head h -> kv head h // g
+    ref = Fn.scaled_dot_product_attention(torch.from_numpy(q).double()[:, None, :], K, V)[:, 0, :]
+    np.testing.assert_allclose(out, ref.numpy(), rtol=1e-5, atol=1e-6)
+
+
+def test_attention_zero_query_gives_mean_value_and_single_key_gives_v():
+    s, sh, kpool, vpool, pages = _attn_setup()
+    out = oracle.attention(sh, np.zeros((s.nq, s.d), np.float32), kpool, vpool, pages, 11)
+    V = _contiguous(vpool, pages, 11).astype(np.float64)
+    for h in range(s.nq):
+        np.testing.assert_allclose(out[h], V[:, h // (s.nq // s.nkv)].mean(0), rtol=1e-5, atol=1e-6)
+    out1 = oracle.attention(sh, r32(s.nq, s.d), kpool, vpool, pages, 1)
+    for h in range(s.nq):
+        np.testing.assert_allclose(out1[h], vpool[pages[0], 0, h // (s.nq // s.nkv)], rtol=1e-6)
+
+
+def test_attention_is_invariant_to_physical_page_placement():
+    s, sh, kpool, vpool, pages = _attn_setup()
+    q = r32(s.nq, s.d)
+    a = oracle.attention(sh, q, kpool, vpool, pages, 11)
+    perm = rng.permutation(kpool.shape[0])
+    k2, v2 = np.empty_like(kpool), np.empty_like(vpool)
+    k2[perm], v2[perm] = kpool, vpool                       # page p moves to perm[p]
+    b = oracle.attention(sh, q, k2, v2, perm[pages].astype(np.int32), 11)
+    np.testing.assert_array_equal(a, b)
+
+
+def test_attention_dominant_key_selects_its_value():
+    s, sh, kpool, vpool, pages = _attn_setup(nq=2, nkv=1)
+    q = r32(s.nq, s.d)
+    kpool[pages[1], 2, 0] = 50.0 * q[0] / np.linalg.norm(q[0])   # key index 1*4+2 = 6 aligned with q_0
+    out = oracle.attention(sh, q, kpool, vpool, pages, 11)
+    np.testing.assert_allclose(out[0], vpool[pages[1], 2, 0], atol=1e-3)
+
+
+# ---------------------------------------------------------------- MoE integers
+def test_topk_tie_break_and_lexsort_agreement():
+    np.testing.assert_array_equal(oracle.topk(np.zeros(8, np.float32), 3), [0, 1, 2])
+    lg = np.array([0.5, 2.0, 2.0, -1.0, 2.0, 0.5], np.float32)
+    np.testing.assert_array_equal(oracle.topk(lg, 5), [1, 2, 4, 0, 5])
+    for _ in range(50):
+        lg = np.round(r32(16), 1)                      # rounded -> plenty of ties
+        np.testing.assert_array_equal(oracle.topk(lg, 6), np.lexsort((np.arange(16), -lg))[:6])
+
+
+def test_route_weights_are_softmax_over_selected():
+    from scipy.special import softmax
+    lg = r32(16)
+    ids = oracle.topk(lg, 4)
+    w = oracle.route_weights(lg, ids)
+    assert abs(float(w.sum()) - 1.0) < 1e-6
+    np.testing.assert_allclose(w, softmax(lg[ids].astype(np.float64)), rtol=1e-6)
+    # softmax over everything, then renormalised over the selected ones: the same numbers
+    p = softmax(lg.astype(np.float64))
+    np.testing.assert_allclose(w, p[ids] / p[ids].sum(), rtol=1e-6)
+
+
+def test_group_brute_force_on_every_tiny_routing():
+    B, K, E, tile_m = 3, 2, 3, 2
+    pairs = [p for p in itertools.permutations(range(E), K)]
+    for combo in itertools.product(pairs, repeat=B):
+        ids = np.array(combo, dtype=np.int32)
+        count, tok_indptr, perm, exp_indptr = oracle.group(ids, E, tile_m)
+        flat = sorted(range(B * K), key=lambda i: (ids[i // K, i % K], i // K, i % K))
+        np.testing.assert_array_equal(perm, flat)
+        np.testing.assert_array_equal(count, np.bincount(ids.ravel(), minlength=E))
+        assert count.sum() == B * K and tok_indptr[0] == 0 and exp_indptr[0] == 0
+        np.testing.assert_array_equal(np.diff(tok_indptr), count)
+        np.testing.assert_array_equal(np.diff(exp_indptr), -(-count // tile_m))
+
+
+# ---------------------------------------------------------------- whole layer
+def _tiny(moe=False, **kw):
+    base = dict(name="t", n_layers=1, H=32, nq=4, nkv=2, d=8, F=48, page=4)
+    if moe:
+        base.update(F=0, n_experts=6, top_k=2, moe_F=24)
+    base.update(kw)
+    return ModelShape(**base)
+
+
+def _weights(s, scale=0.2):
+    w = {"g1": 1 + r32(s.H, scale=0.02), "g2": 1 + r32(s.H, scale=0.02),
+         "wq": r32(s.nq * s.d, s.H, scale=scale), "wk": r32(s.nkv * s.d, s.H, scale=scale),
+         "wv": r32(s.nkv * s.d, s.H, scale=scale), "wo": r32(s.H, s.nq * s.d, scale=scale)}
+    if s.is_moe:
+        w.update(wr=r32(s.n_experts, s.H), eg=r32(s.n_experts, s.moe_F, s.H, scale=scale),
+                 eu=r32(s.n_experts, s.moe_F, s.H, scale=scale), ed=r32(s.n_experts, s.H, s.moe_F, scale=scale))
+    else:
+        w.update(wg=r32(s.F, s.H, scale=scale), wu=r32(s.F, s.H, scale=scale), wd=r32(s.H, s.F, scale=scale))
+    return w
+
+
+def _step(s, kv_len, n_pool):
+    kv_len = np.asarray(kv_len, np.int32)
+    npg = [pages_needed(int(l), s.page) for l in kv_len]
+    indptr = np.concatenate([[0], np.cumsum(npg)]).astype(np.int32)
+    ids = rng.permutation(n_pool)[: indptr[-1]].astype(np.int32)
+    return Step(len(kv_len), kv_len, indptr, ids)
+
+
+def _library_layer(s, x, w, kpool, vpool, step, topk_ids=None):
+    """The layer written a second, independent way: float64 torch library calls."""
+    T = lambda a: torch.from_numpy(np.asarray(a)).double()  # noqa: E731
+    out = []
+    g = s.nq // s.nkv
+    for b in range(step.batch):
+        pos = int(step.kv_len[b])
+        xb = T(x[b])
+        xn = Fn.rms_norm(xb, (s.H,), T(w["g1"]), eps=s.eps)
+        q = (T(w["wq"]) @ xn).view(s.nq, s.d)
+        k = (T(w["wk"]) @ xn).view(s.nkv, s.d)
+        v = (T(w["wv"]) @ xn).view(s.nkv, s.d)
+        inv = s.theta ** (-torch.arange(0, s.d, 2).double() / s.d)
+        cos, sin = torch.cos(pos * inv), torch.sin(pos * inv)
+
+        def rot(t):
+            a, c = t[:, : s.d // 2], t[:, s.d // 2:]
+            return torch.cat([a * cos - c * sin, a * sin + c * cos], dim=1)
+        q, k = rot(q), rot(k)
+        pages = step.page_ids[step.page_indptr[b]:step.page_indptr[b + 1]]
+        Kc = torch.cat([T(kpool[p]) for p in pages])[:pos]
+        Vc = torch.cat([T(vpool[p]) for p in pages])[:pos]
+        Kc = torch.cat([Kc, k[None]]).permute(1, 0, 2).repeat_interleave(g, 0)
+        Vc = torch.cat([Vc, v[None]]).permute(1, 0, 2).repeat_interleave(g, 0)
+        o = Fn.scaled_dot_product_attention(q[:, None, :], Kc, Vc)[:, 0, :].reshape(-1)
+        xm = xb + T(w["wo"]) @ o
+        xn2 = Fn.rms_norm(xm, (s.H,), T(w["g2"]), eps=s.eps)
+        if not s.is_moe:
+            y = T(w["wd"]) @ (Fn.silu(T(w["wg"]) @ xn2) * (T(w["wu"]) @ xn2))
+        else:
+            lg = T(w["wr"]) @ xn2
+            ids = torch.from_numpy(np.asarray(topk_ids[b])).long()
+            ww = torch.softmax(lg[ids], 0)
+            y = sum(ww[i] * (T(w["ed"][e]) @ (Fn.silu(T(w["eg"][e]) @ xn2) * (T(w["eu"][e]) @ xn2)))
+                    for i, e in enumerate(ids.tolist()))
+        out.append((xm + y).numpy())
+    return np.stack(out)
+
+
+@pytest.mark.parametrize("moe", [False, True])
+def test_layer_matches_independent_library_derivation(moe):
+    s = _tiny(moe)
+    w = _weights(s)
+    step = _step(s, [9, 0, 4], n_pool=8)
+    kpool, vpool = r32(8, s.page, s.nkv, s.d), r32(8, s.page, s.nkv, s.d)
+    x = r32(3, s.H)
+    xo = x.copy()
+    kp, vp = kpool.copy(), vpool.copy()
+    ids, dbg = oracle.layer(oracle.shape_of(s), xo, w, kp, vp, step.kv_len, step.page_indptr, step.page_ids,
+                            debug=True)
+    ref = _library_layer(s, x, w, kpool, vpool, step, ids)
+    np.testing.assert_allclose(xo, ref, rtol=2e-5, atol=2e-5)
+    # KV append: exactly one row per sequence changed, at (page of pos, pos % page), K stored rotated
+    changed = np.argwhere((kp != kpool).any(axis=(2, 3)))
+    exp = sorted((int(step.page_ids[step.page_indptr[b] + step.kv_len[b] // s.page]), int(step.kv_len[b] % s.page))
+                 for b in range(3))
+    assert sorted(map(tuple, changed.tolist())) == exp
+    for b in range(3):
+        pg, sl = exp_b = (int(step.page_ids[step.page_indptr[b] + step.kv_len[b] // s.page]),
+                          int(step.kv_len[b] % s.page))
+        np.testing.assert_array_equal(kp[pg, sl].ravel(), dbg["k_rot"][b])
+        np.testing.assert_array_equal(vp[pg, sl].ravel(), dbg["v_new"][b])
+    if moe:
+        for b in range(3):
+            np.testing.assert_array_equal(ids[b], np.lexsort((np.arange(s.n_experts), -dbg["router_logits"][b]))[:2])
+
+
+def test_hand_evaluated_layer():
+    gold = dict(l.split() for l in open(os.path.join(GOLD, "hand_layer.txt")) if not l.startswith("#"))
+    s = ModelShape("hand", 1, 4, 1, 1, 4, 4, page=16)
+    I = np.eye(4, dtype=np.float32)
+    one = np.ones(4, np.float32)
+    w = dict(g1=one, g2=one, wq=I, wk=I, wv=I, wo=I, wg=I, wu=I, wd=I)
+    x = np.ones((1, 4), np.float32)
+    kp, vp = np.zeros((1, 16, 1, 4), np.float32), np.zeros((1, 16, 1, 4), np.float32)
+    _, dbg = oracle.layer(oracle.shape_of(s), x, w, kp, vp, [0], [0, 1], [0], debug=True)
+    np.testing.assert_allclose(dbg["x_mid"][0], float(gold["x_mid"]), rtol=1e-6)
+    np.testing.assert_allclose(x[0], float(gold["x_out"]), rtol=1e-6)
+
+
+def test_layer_with_zero_output_projections_is_identity():
+    s = _tiny()
+    w = _weights(s)
+    w["wo"] = np.zeros_like(w["wo"])
+    w["wd"] = np.zeros_like(w["wd"])
+    step = _step(s, [5], n_pool=4)
+    x = r32(1, s.H)
+    xo = x.copy()
+    oracle.layer(oracle.shape_of(s), xo, w, r32(4, s.page, s.nkv, s.d), r32(4, s.page, s.nkv, s.d),
+                 step.kv_len, step.page_indptr, step.page_ids)
+    np.testing.assert_array_equal(xo, x)
+
+
+def test_moe_with_identical_experts_equals_dense_ffn():
+    """Routing weights sum to one, so identical experts collapse the MoE block to the dense block."""
+    sm = _tiny(True)
+    sd = _tiny(False, F=sm.moe_F)
+    w = _weights(sm)
+    for nme in ("eg", "eu", "ed"):
+        w[nme] = np.repeat(w[nme][:1], sm.n_experts, axis=0)
+    wd = {k: v for k, v in w.items() if k in ("g1", "g2", "wq", "wk", "wv", "wo")}
+    wd.update(wg=w["eg"][0], wu=w["eu"][0], wd=w["ed"][0])
+    step = _step(sm, [6, 2], n_pool=6)
+    kpool, vpool = r32(6, sm.page, sm.nkv, sm.d), r32(6, sm.page, sm.nkv, sm.d)
+    x = r32(2, sm.H)
+    a, b = x.copy(), x.copy()
+    oracle.layer(oracle.shape_of(sm), a, w, kpool.copy(), vpool.copy(), step.kv_len, step.page_indptr, step.page_ids)
+    oracle.layer(oracle.shape_of(sd), b, wd, kpool.copy(), vpool.copy(), step.kv_len, step.page_indptr, step.page_ids)
+    np.testing.assert_allclose(a, b, rtol=1e-5, atol=1e-6)
+
+
+def test_moe_forced_routing_is_followed():
+    s = _tiny(True)
+    w = _weights(s)
+    step = _step(s, [3], n_pool=2)
+    kpool, vpool = r32(2, s.page, s.nkv, s.d), r32(2, s.page, s.nkv, s.d)
+    x = r32(1, s.H)
+    forced = np.array([[5, 0]], np.int32)
+    xo = x.copy()
+    ids, _ = oracle.layer(oracle.shape_of(s), xo, w, kpool.copy(), vpool.copy(), step.kv_len, step.page_indptr,
+                          step.page_ids, forced_topk=forced)
+    np.testing.assert_array_equal(ids, forced)
+    ref = _library_layer(s, x, w, kpool, vpool, step, forced)
+    np.testing.assert_allclose(xo, ref, rtol=2e-5, atol=2e-5)

@@ -1,0 +1,243 @@
+/*
+ * etc.h  --  C ABI of the event-tensor decode megakernel for AMD MI355X (gfx950).
+ *
+ * One persistent HIP kernel runs a whole LLM decode step as tiled tasks.  Every
+ * task is gated by an event tensor (a grid of per-tile dependency counters in
+ * HBM, paper Sec. 2.1): a producer tile notifies (atomic decrement, Sec. 3.3) the
+ * events it feeds when it ends, a consumer tile waits (spin until zero) on the
+ * events it reads when it starts.  No kernel boundary and no host launch sits
+ * between operators.
+ *
+ * The four verbs follow the paper's statement of the problem:
+ *   describe  etc_create / etc_graph_*   graph function = device-function launches with
+ *                                        task shapes and event tensors (Sec. 2.1), tile
+ *                                        shapes, scheduling transformation (Sec. 3.1 / 3.2)
+ *   bind      etc_bind_layer_weights / etc_bind_kv_pool        resident tensors
+ *   bind      etc_bind_step              symbolic shapes -> concrete (Sec. 2.3): batch,
+ *                                        ragged KV lengths, page tables; no re-create
+ *   launch    etc_launch                 exactly one kernel launch per decode step
+ *
+ * Conventions.  Plain C, no exceptions cross the boundary.  Every call returns an
+ * etc_status; etc_last_error() gives the text.  A context is not thread-safe and
+ * has one step in flight at a time.  Pointers marked "device" are device memory
+ * of the current HIP device, borrowed: the caller owns them and keeps them alive
+ * until the last launch that uses them has finished.  Pointers marked "host" are
+ * read during the call only.  The library owns all scratch (activations, event
+ * tensors, task lists, queues).  All weights, KV pages and hidden states are bf16;
+ * accumulation is fp32.
+ */
+#ifndef ETC_H
+#define ETC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct etc_ctx etc_ctx; /* opaque, library-owned */
+
+typedef enum {
+    ETC_OK = 0,
+    ETC_EINVAL = -1,   /* bad argument or descriptor */
+    ETC_ENOMEM = -2,   /* host or device allocation failed */
+    ETC_ESTATE = -3,   /* call order: something is not bound yet */
+    ETC_EDEVICE = -4,  /* a HIP call failed */
+    ETC_ETIMEOUT = -5  /* device watchdog: a wait exceeded its spin budget; the kernel drained */
+} etc_status;
+
+/* ---- describe ------------------------------------------------------------------------- */
+
+/* Decoder shape.  Dense SwiGLU FFN when n_experts == 0, otherwise top_k-of-n_experts MoE with
+ * per-expert SwiGLU width moe_ffn (Sec. 2.4, 4.2).  RoPE pairs element i with i + head_dim/2. */
+typedef struct {
+    int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn;
+    int32_t n_experts, top_k, moe_ffn;
+    int32_t page_size; /* tokens per KV page */
+    float rms_eps, rope_theta;
+} etc_model_desc;
+
+/* Tile shapes of the task grids (Sec. 2.1: tasks are CU-level tiles). */
+typedef struct {
+    int32_t kv_chunk_tokens; /* keys per split-KV attention task; multiple of page_size */
+    int32_t moe_tile_m;      /* tokens per GroupGEMM row tile (exp_indptr unit, Sec. 2.4); 1..16 */
+} etc_tile_desc;
+
+typedef enum {
+    ETC_SCHED_STATIC = 0,  /* per-CU task queues built on the host, notify / wait (Sec. 3.1, Alg. 1) */
+    ETC_SCHED_DYNAMIC = 1, /* on-GPU ready queue, push on zero / pop when idle (Sec. 3.2, Alg. 2) */
+    ETC_SCHED_UNFUSED = 2  /* static queues, one coarse event per operator stage (Sec. 4.5 baseline) */
+} etc_sched_kind;
+
+enum {
+    ETC_DEBUG_EXEC_COUNT = 1u,   /* count executions of every task */
+    ETC_DEBUG_LAYER_HIDDEN = 2u, /* keep the hidden state after every layer */
+    ETC_DEBUG_ROUTING = 4u       /* keep router logits, top-k ids / weights, permutation, indptr */
+};
+
+typedef struct {
+    int32_t kind;             /* etc_sched_kind */
+    int32_t n_sampled;        /* static: number of sampled batch sizes (Sec. 3.1), 1..8 */
+    int32_t sampled_batch[8]; /* ascending; a bound batch uses the next larger sampled queue */
+    int32_t max_batch;        /* <= 64 */
+    int32_t max_kv_len;       /* largest kv_len + 1 any step will bind */
+    int64_t spin_budget;      /* polls before a wait gives up (0 = default) */
+    uint32_t debug_flags;
+    int32_t n_queues;         /* persistent workgroups; 0 = one per compute unit */
+} etc_sched_desc;
+
+/* Builds the event-tensor graph of the decoder, the task queues for every sampled batch size
+ * and all scratch.  This is the "warm-up" of Sec. 4.4: nothing is compiled or captured later. */
+etc_status etc_create(const etc_model_desc *model, const etc_tile_desc *tiles, const etc_sched_desc *sched,
+                      etc_ctx **out);
+void etc_destroy(etc_ctx *ctx);
+const char *etc_last_error(const etc_ctx *ctx); /* ctx may be NULL: error of the last failed create */
+
+/* ---- bind ----------------------------------------------------------------------------- */
+
+/* One layer's weights, device, bf16, row-major [out, in].  Dense layers leave the MoE
+ * pointers NULL and vice versa. */
+typedef struct {
+    const void *g1;  /* [hidden]                 attention RMSNorm gain */
+    const void *wq;  /* [n_q_heads*head_dim, hidden] */
+    const void *wk;  /* [n_kv_heads*head_dim, hidden] */
+    const void *wv;  /* [n_kv_heads*head_dim, hidden] */
+    const void *wo;  /* [hidden, n_q_heads*head_dim] */
+    const void *g2;  /* [hidden]                 FFN RMSNorm gain */
+    const void *wg;  /* [ffn, hidden]            gate */
+    const void *wu;  /* [ffn, hidden]            up */
+    const void *wd;  /* [hidden, ffn]            down */
+    const void *wr;  /* [n_experts, hidden]      router */
+    const void *eg;  /* [n_experts, moe_ffn, hidden] */
+    const void *eu;  /* [n_experts, moe_ffn, hidden] */
+    const void *ed;  /* [n_experts, hidden, moe_ffn] */
+} etc_layer_weights;
+
+etc_status etc_bind_layer_weights(etc_ctx *ctx, int32_t layer, const etc_layer_weights *w);
+
+/* Paged KV cache, device, bf16: [layer][page][page_size][n_kv_heads][head_dim] for K and for V.
+ * K rows are stored already rotated.  The step appends one row per sequence (Sec. 4.3). */
+etc_status etc_bind_kv_pool(etc_ctx *ctx, void *k_pages, void *v_pages, int64_t pages_per_layer);
+
+/* Dynamic shape parameters of the next step(s) (Sec. 2.3).  kv_len[b] = tokens already cached:
+ * the new token has position kv_len[b], is appended there and attends to kv_len[b]+1 keys.
+ * Sequence b owns page_ids[page_indptr[b] .. page_indptr[b+1]) = ceil((kv_len[b]+1)/page_size)
+ * pages.  All three arrays are host memory, copied during the call.  Never needs a re-create
+ * for batch <= max_batch and kv_len < max_kv_len.  Synchronises with earlier launches. */
+etc_status etc_bind_step(etc_ctx *ctx, int32_t batch, const int32_t *kv_len, const int32_t *page_indptr,
+                         const int32_t *page_ids);
+
+/* Test hook for MoE parity: layer's routing follows ids [batch, top_k] (host) instead of the
+ * device top-k; ids == NULL removes the override.  Takes effect at the next launch. */
+etc_status etc_force_routing(etc_ctx *ctx, int32_t layer, const int32_t *ids);
+
+/* ---- launch --------------------------------------------------------------------------- */
+
+/* One decode step = one kernel launch on hip_stream (a hipStream_t, may be NULL); asynchronous.
+ * hidden_in / hidden_out: device, bf16 [batch, hidden]; may alias.  May be called repeatedly
+ * for one bind: the event tensors are re-armed inside the kernel. */
+etc_status etc_launch(etc_ctx *ctx, const void *hidden_in, void *hidden_out, void *hip_stream);
+
+/* The same task bodies, one ordinary kernel launch per operator stage (the kernel-by-kernel
+ * model of Sec. 1); the launch-gap comparator.  Same arguments and results as etc_launch. */
+etc_status etc_launch_kernel_by_kernel(etc_ctx *ctx, const void *hidden_in, void *hidden_out, void *hip_stream);
+
+/* ---- evidence / debug readback (synchronises the device) -------------------------------- */
+typedef enum {
+    ETC_DBG_ERROR_WORD = 0,      /* int32[4]: code (0 = none), task function, event index, queue */
+    ETC_DBG_EVENT_COUNTERS = 1,  /* int32[n_events] of the step that just ran: all zero when drained */
+    ETC_DBG_TASK_EXEC_COUNT = 2, /* int32[n_tasks]: 1 everywhere (needs ETC_DEBUG_EXEC_COUNT) */
+    ETC_DBG_LAYER_HIDDEN = 3,    /* float[batch, hidden] after `layer` (needs ETC_DEBUG_LAYER_HIDDEN) */
+    ETC_DBG_ROUTER_LOGITS = 4,   /* float[batch, n_experts] of `layer`   (needs ETC_DEBUG_ROUTING) */
+    ETC_DBG_TOPK_IDS = 5,        /* int32[batch, top_k] */
+    ETC_DBG_TOPK_W = 6,          /* float[batch, top_k] */
+    ETC_DBG_PERMUTATION = 7,     /* int32[batch*top_k]: token*top_k+slot sorted by (expert, token, slot) */
+    ETC_DBG_TOK_INDPTR = 8,      /* int32[n_experts+1] prefix sum of tokens per expert */
+    ETC_DBG_EXP_INDPTR = 9       /* int32[n_experts+1] prefix sum of row tiles per expert (Sec. 2.4) */
+} etc_debug_kind;
+
+etc_status etc_read_debug(etc_ctx *ctx, int32_t kind, int32_t layer, void *host_dst, size_t bytes);
+
+/* Sizes of the bound step's instantiated graph. */
+typedef struct {
+    int64_t n_tasks, n_events, n_queues;
+    int64_t algorithmic_bytes; /* weights touched once + live KV once + appended rows, this step */
+    int32_t sampled_batch;     /* the sampled batch size whose queues serve the bound batch */
+    int32_t workgroup_threads;
+} etc_step_info;
+etc_status etc_get_step_info(etc_ctx *ctx, etc_step_info *info);
+
+/* ---- generic event-tensor graphs (Sec. 2.1, 2.2) ----------------------------------------
+ * A graph function is a list of device-function launches over task grids plus event tensors;
+ * edges map a task coordinate to an event coordinate.  Dimensions may be symbolic and are
+ * bound at run time without rebuilding anything (Sec. 2.3).  Used by the row-sum example. */
+typedef struct {
+    int32_t sym; /* symbol id 0..3, or -1 for a constant */
+    int32_t mul; /* value = mul * symbol + add */
+    int32_t add;
+} etc_dim_expr;
+
+typedef enum {
+    ETC_MAP_DIM = 0,  /* event coord = task coord[src] / div */
+    ETC_MAP_CONST = 1 /* event coord = div (a constant; "E[0]" style coarse event) */
+} etc_map_kind;
+
+typedef struct {
+    int32_t event;      /* id from etc_graph_add_event */
+    int32_t rank;       /* rank of that event tensor, <= 3 */
+    int32_t kind[3];    /* etc_map_kind per event dimension */
+    int32_t src[3];
+    int32_t div[3];
+} etc_edge;
+
+typedef enum {
+    ETC_FN_ROWSUM_PARTIAL = 1, /* task (i, j): B[32i..32i+32, j] = sum_k A[rows, 32j..32j+32) */
+    ETC_FN_ROWSUM_FINAL = 2    /* task (i):    C[32i..32i+32]    = sum_j B[rows, j], j < 4 */
+} etc_device_fn;
+
+etc_status etc_graph_create(const etc_sched_desc *sched, etc_ctx **out);
+etc_status etc_graph_add_event(etc_ctx *ctx, const etc_dim_expr *shape, int32_t rank, int32_t *event_id);
+etc_status etc_graph_add_call(etc_ctx *ctx, int32_t device_fn, const etc_dim_expr *task_shape, int32_t rank,
+                              const etc_edge *in_edges, int32_t n_in, const etc_edge *out_edges, int32_t n_out);
+/* Buffers of the device functions: slot 0 = A (fp32 [n*32, 128]), 1 = B (fp32 [n*32, 4]), 2 = C (fp32 [n*32]);
+ * bytes = size of the allocation, checked against the bound shape at launch. */
+etc_status etc_graph_bind_buffer(etc_ctx *ctx, int32_t slot, void *device_ptr, size_t bytes);
+/* Instantiates the template for concrete symbol values (values[4], host). */
+etc_status etc_graph_bind_shape(etc_ctx *ctx, const int32_t *values);
+etc_status etc_graph_launch(etc_ctx *ctx, void *hip_stream);
+
+/* ---- host-only inspection of the scheduling transformation (no device needed) ---------------
+ * Instantiates the decoder's event-tensor graph for one sampled batch size exactly as etc_create
+ * does and exposes the materialised tasks, static queues (Sec. 3.1), initial event counts (Sec. 2.1)
+ * and the event -> consumer table of the dynamic scheduler (Sec. 3.2).  Arrays are owned by the
+ * view and released by etc_plan_free. */
+typedef struct {
+    uint8_t fn, layer;
+    uint16_t flags;       /* bit 0: wave w of the task waits on event wait0 + w (8 waves) */
+    int32_t c0, c1, c2;   /* task coordinate */
+    int32_t wait0, wait1; /* flat event indices, -1 = none */
+    int32_t notify0;
+    int32_t id;
+} etc_task_record;
+
+typedef struct {
+    int64_t n_tasks, n_events, n_queues, n_seed;
+    const etc_task_record *tasks;       /* by task id */
+    const etc_task_record *queue_tasks; /* static queues back to back */
+    const int32_t *queue_begin;         /* [n_queues + 1] */
+    const int32_t *ev_init;             /* [n_events] */
+    const int32_t *ev_consumers;        /* [n_events + 1] CSR into consumer_ids */
+    const int32_t *consumer_ids;
+    const int32_t *seed_tasks;          /* [n_seed] tasks ready at launch */
+    void *opaque;
+} etc_plan_view;
+
+etc_status etc_plan_build(const etc_model_desc *model, const etc_tile_desc *tiles, const etc_sched_desc *sched,
+                          int32_t sampled_batch, int32_t n_queues, etc_plan_view *out);
+void etc_plan_free(etc_plan_view *view);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ETC_H */

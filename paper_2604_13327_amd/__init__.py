@@ -1,0 +1,9 @@
+"""Event-tensor decode megakernel for AMD MI355X: thin Python binding of the C ABI (include/etc.h).
+
+Argument marshalling only.  Every step of the decode path runs in the HIP library
+``libetc.so``; there is no Python or CPU fallback: a missing library raises.
+"""
+from .binding import (  # noqa: F401
+    DEBUG_EXEC_COUNT, DEBUG_LAYER_HIDDEN, DEBUG_ROUTING, SCHED_DYNAMIC, SCHED_STATIC, SCHED_UNFUSED,
+    Decoder, EtcError, EventGraph, lib, lib_path, plan_build,
+)

@@ -1,0 +1,694 @@
+// C ABI of the library (see include/etc.h): argument checking, scratch and plan management,
+// kernel launches.  Everything numerical happens in the device task bodies.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/etc.h"
+#include "etc_types.h"
+#include "graph.h"
+
+namespace etc {
+hipError_t configure_kernels();
+hipError_t max_resident_workgroups(int *per_cu);
+hipError_t launch_static(const Params &P, hipStream_t s);
+hipError_t launch_dynamic(const Params &P, hipStream_t s);
+hipError_t launch_stage(const Params &P, int first, int count, hipStream_t s);
+}  // namespace etc
+
+using namespace etc;
+
+namespace {
+
+std::string g_create_error;
+
+struct DevPlan {          // one instantiated plan (one sampled batch size), host + device copies
+    int sampled_batch = 0;
+    Plan host;
+    Task *d_queue_tasks = nullptr, *d_tasks = nullptr;
+    int32_t *d_queue_begin = nullptr, *d_ev_init = nullptr, *d_ev_consumers = nullptr, *d_consumer_ids = nullptr,
+            *d_seed = nullptr;
+};
+
+template <class T>
+hipError_t dev_alloc(T **p, size_t n, std::vector<void *> &owned, bool zero = true)
+{
+    *p = nullptr;
+    if (n == 0) n = 1;
+    hipError_t e = hipMalloc((void **)p, n * sizeof(T));
+    if (e != hipSuccess) return e;
+    owned.push_back(*p);
+    if (zero) e = hipMemset(*p, 0, n * sizeof(T));
+    return e;
+}
+
+template <class T>
+hipError_t dev_upload(T **p, const std::vector<T> &v, std::vector<void *> &owned)
+{
+    hipError_t e = dev_alloc(p, v.size(), owned, false);
+    if (e != hipSuccess || v.empty()) return e;
+    return hipMemcpy(*p, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice);
+}
+
+}  // namespace
+
+struct etc_ctx {
+    bool is_graph = false;
+    etc_model_desc model{};
+    etc_tile_desc tiles{};
+    etc_sched_desc sched{};
+    ModelDims dims{};
+    int n_queues = 0, max_chunks = 0, max_pages_per_seq = 0;
+    GraphDecl graph;
+    std::vector<DevPlan> plans;
+    int cur_plan = -1;
+    std::vector<void *> owned;              // device allocations that live as long as the context
+    std::vector<void *> plan_owned;         // plans, event tensors, ready queue (rebuilt by etc_graph_bind_shape)
+    size_t gbuf_bytes[4] = {0, 0, 0, 0};
+    std::vector<LayerWeights> h_weights;
+    std::vector<uint8_t> weights_bound;
+    LayerWeights *d_weights = nullptr;
+    bool weights_dirty = true;
+    Params base{};                          // device pointers and constants filled at create
+    int32_t *d_events = nullptr;            // [3][n_events_max]: A | init | B
+    int n_events_max = 0;
+    int parity = 0;
+    uint32_t epoch = 1;
+    int32_t *d_qctrl = nullptr;             // [2][8]
+    int32_t *d_kv_len = nullptr, *d_page_indptr = nullptr, *d_page_ids = nullptr;
+    int32_t *d_forced = nullptr;
+    uint8_t *d_forced_mask = nullptr;
+    std::vector<uint8_t> h_forced_mask;
+    int64_t pages_per_layer = 0;
+    bool kv_bound = false, step_bound = false;
+    int bound_batch = 0;
+    std::vector<int32_t> h_kv_len;
+    int64_t algorithmic_bytes = 0;
+    std::string err;
+    int sym_values[4] = {0, 0, 0, 0};
+};
+
+namespace {
+
+etc_status fail(etc_ctx *c, etc_status s, const std::string &msg)
+{
+    if (c) c->err = msg; else g_create_error = msg;
+    return s;
+}
+
+#define HIP_TRY(ctx, expr)                                                                              \
+    do {                                                                                                \
+        hipError_t e_ = (expr);                                                                         \
+        if (e_ != hipSuccess)                                                                           \
+            return fail(ctx, e_ == hipErrorOutOfMemory ? ETC_ENOMEM : ETC_EDEVICE,                      \
+                        std::string(#expr) + ": " + hipGetErrorString(e_));                             \
+    } while (0)
+
+etc_status upload_plan(etc_ctx *c, DevPlan &dp)
+{
+    HIP_TRY(c, dev_upload(&dp.d_queue_tasks, dp.host.queue_tasks, c->plan_owned));
+    HIP_TRY(c, dev_upload(&dp.d_tasks, dp.host.tasks, c->plan_owned));
+    HIP_TRY(c, dev_upload(&dp.d_queue_begin, dp.host.queue_begin, c->plan_owned));
+    HIP_TRY(c, dev_upload(&dp.d_ev_init, dp.host.ev_init, c->plan_owned));
+    HIP_TRY(c, dev_upload(&dp.d_ev_consumers, dp.host.ev_consumers, c->plan_owned));
+    HIP_TRY(c, dev_upload(&dp.d_consumer_ids, dp.host.consumer_ids, c->plan_owned));
+    HIP_TRY(c, dev_upload(&dp.d_seed, dp.host.seed_tasks, c->plan_owned));
+    return ETC_OK;
+}
+
+etc_status common_device_setup(etc_ctx *c, const etc_sched_desc *s)
+{
+    int dev = 0;
+    HIP_TRY(c, hipGetDevice(&dev));
+    hipDeviceProp_t prop;
+    HIP_TRY(c, hipGetDeviceProperties(&prop, dev));
+    HIP_TRY(c, configure_kernels());
+    int per_cu = 0;
+    HIP_TRY(c, max_resident_workgroups(&per_cu));
+    if (per_cu < 1) return fail(c, ETC_EDEVICE, "the megakernel does not fit on a compute unit");
+    // every persistent workgroup must be resident at once (spin waits): one per CU
+    c->n_queues = s->n_queues > 0 ? std::min(s->n_queues, prop.multiProcessorCount) : prop.multiProcessorCount;
+    c->sched = *s;
+    if (c->sched.spin_budget <= 0) c->sched.spin_budget = 4000000;    // a few seconds of polling, then ETC_ETIMEOUT
+    HIP_TRY(c, dev_alloc(&c->base.error_word, 4, c->owned));
+    HIP_TRY(c, dev_alloc(&c->d_qctrl, 16, c->owned));
+    return ETC_OK;
+}
+
+etc_status alloc_events_and_queue(etc_ctx *c)
+{
+    size_t n_ev = 1, n_tasks = 1;
+    for (const DevPlan &dp : c->plans) {
+        n_ev = std::max(n_ev, dp.host.ev_init.size());
+        n_tasks = std::max(n_tasks, dp.host.tasks.size());
+    }
+    c->n_events_max = (int)n_ev;
+    HIP_TRY(c, dev_alloc(&c->d_events, 3 * n_ev, c->plan_owned));
+    if (c->sched.debug_flags & ETC_DEBUG_EXEC_COUNT) HIP_TRY(c, dev_alloc(&c->base.exec_count, n_tasks + 65536, c->plan_owned));
+    c->base.q_capacity = (int)(n_tasks + 65536 + c->n_queues);
+    HIP_TRY(c, dev_alloc(&c->base.q_slots, (size_t)c->base.q_capacity, c->plan_owned));
+    return ETC_OK;
+}
+
+// Arms the event tensors for the bound plan: `init` and the buffer the next launch will use.
+etc_status arm_events(etc_ctx *c)
+{
+    const DevPlan &dp = c->plans[c->cur_plan];
+    const size_t n = dp.host.ev_init.size(), N = (size_t)c->n_events_max;
+    int32_t *init = c->d_events + N, *cur = c->d_events + (c->parity ? 2 * N : 0);
+    if (n) {
+        HIP_TRY(c, hipMemcpy(init, dp.host.ev_init.data(), n * sizeof(int32_t), hipMemcpyHostToDevice));
+        HIP_TRY(c, hipMemcpy(cur, dp.host.ev_init.data(), n * sizeof(int32_t), hipMemcpyHostToDevice));
+    }
+    HIP_TRY(c, hipMemset(c->d_qctrl + (c->parity ? 8 : 0), 0, 8 * sizeof(int32_t)));
+    if (c->base.exec_count) HIP_TRY(c, hipMemset(c->base.exec_count, 0, dp.host.tasks.size() * sizeof(int32_t)));
+    return ETC_OK;
+}
+
+void fill_launch_params(etc_ctx *c, Params &P)
+{
+    const DevPlan &dp = c->plans[c->cur_plan];
+    const size_t N = (size_t)c->n_events_max;
+    P = c->base;
+    P.ev_cur = c->d_events + (c->parity ? 2 * N : 0);
+    P.ev_init = c->d_events + N;
+    P.ev_next = c->d_events + (c->parity ? 0 : 2 * N);
+    P.n_events = (int)dp.host.ev_init.size();
+    P.tasks = dp.d_queue_tasks;
+    P.queue_begin = dp.d_queue_begin;
+    P.n_queues = c->n_queues;
+    P.dyn_tasks = dp.d_tasks;
+    P.ev_consumers = dp.d_ev_consumers;
+    P.consumer_ids = dp.d_consumer_ids;
+    P.seed_tasks = dp.d_seed;
+    P.n_seed = (int)dp.host.seed_tasks.size();
+    P.n_static_tasks = (int)dp.host.tasks.size();
+    P.q_ctrl_cur = c->d_qctrl + (c->parity ? 8 : 0);
+    P.q_ctrl_next = c->d_qctrl + (c->parity ? 0 : 8);
+    P.epoch = c->epoch;
+    P.spin_budget = c->sched.spin_budget;
+    P.debug_flags = c->sched.debug_flags;
+    P.B = c->bound_batch;
+    P.Bs = dp.sampled_batch;
+    P.max_chunks = c->max_chunks;
+    P.kv_len = c->d_kv_len;
+    P.page_indptr = c->d_page_indptr;
+    P.page_ids = c->d_page_ids;
+    P.weights = c->d_weights;
+    P.forced_topk = c->d_forced;
+    P.forced_mask = c->d_forced_mask;
+    for (int i = 0; i < 4; ++i) P.gsym[i] = c->sym_values[i];
+}
+
+etc_status check_error_word(etc_ctx *c)
+{
+    int32_t w[4];
+    HIP_TRY(c, hipMemcpy(w, c->base.error_word, sizeof(w), hipMemcpyDeviceToHost));
+    if (w[0] != 0) {
+        char buf[200];
+        snprintf(buf, sizeof(buf), "device watchdog: code %d in task function %d, event/ticket %d, queue %d", w[0],
+                 w[1], w[2], w[3]);
+        return fail(c, ETC_ETIMEOUT, buf);
+    }
+    return ETC_OK;
+}
+
+etc_status sync_weights(etc_ctx *c)
+{
+    if (!c->weights_dirty) return ETC_OK;
+    for (size_t l = 0; l < c->weights_bound.size(); ++l)
+        if (!c->weights_bound[l]) return fail(c, ETC_ESTATE, "layer " + std::to_string(l) + " has no weights bound");
+    HIP_TRY(c, hipMemcpy(c->d_weights, c->h_weights.data(), c->h_weights.size() * sizeof(LayerWeights),
+                         hipMemcpyHostToDevice));
+    c->weights_dirty = false;
+    return ETC_OK;
+}
+
+etc_status pre_launch(etc_ctx *c, const void *hidden_in, void *hidden_out, Params &P)
+{
+    if (!c || c->is_graph) return fail(c, ETC_EINVAL, "not a decoder context");
+    if (!hidden_in || !hidden_out) return fail(c, ETC_EINVAL, "hidden_in / hidden_out is NULL");
+    if (!c->kv_bound) return fail(c, ETC_ESTATE, "no KV pool bound");
+    if (!c->step_bound) return fail(c, ETC_ESTATE, "no step bound");
+    etc_status st = sync_weights(c);
+    if (st != ETC_OK) return st;
+    fill_launch_params(c, P);
+    P.hidden_in = (const uint16_t *)hidden_in;
+    P.hidden_out = (uint16_t *)hidden_out;
+    return ETC_OK;
+}
+
+void post_launch(etc_ctx *c)
+{
+    c->parity ^= 1;
+    c->epoch++;
+    if (c->epoch == 0) c->epoch = 1;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *etc_last_error(const etc_ctx *ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+void etc_destroy(etc_ctx *ctx)
+{
+    if (!ctx) return;
+    (void)hipDeviceSynchronize();
+    for (void *p : ctx->owned) (void)hipFree(p);
+    for (void *p : ctx->plan_owned) (void)hipFree(p);
+    delete ctx;
+}
+
+etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc_sched_desc *s, etc_ctx **out)
+{
+    if (!m || !t || !s || !out) return fail(nullptr, ETC_EINVAL, "NULL argument");
+    *out = nullptr;
+    if (m->n_layers < 1 || m->hidden < 1 || m->n_q_heads < 1 || m->n_kv_heads < 1 || m->page_size < 1)
+        return fail(nullptr, ETC_EINVAL, "model dimensions must be positive");
+    if (s->max_batch < 1 || s->max_batch > kMaxBatch) return fail(nullptr, ETC_EINVAL, "max_batch must be in 1..64");
+    if (s->max_kv_len < 1) return fail(nullptr, ETC_EINVAL, "max_kv_len must be positive");
+    if (t->kv_chunk_tokens < m->page_size || t->kv_chunk_tokens % m->page_size)
+        return fail(nullptr, ETC_EINVAL, "kv_chunk_tokens must be a positive multiple of page_size");
+    if (s->kind < ETC_SCHED_STATIC || s->kind > ETC_SCHED_UNFUSED) return fail(nullptr, ETC_EINVAL, "unknown scheduler kind");
+    if (s->n_sampled < 1 || s->n_sampled > 8) return fail(nullptr, ETC_EINVAL, "n_sampled must be in 1..8");
+    for (int i = 0; i < s->n_sampled; ++i) {
+        if (s->sampled_batch[i] < 1 || s->sampled_batch[i] > s->max_batch || (i && s->sampled_batch[i] <= s->sampled_batch[i - 1]))
+            return fail(nullptr, ETC_EINVAL, "sampled_batch must be ascending, within 1..max_batch");
+    }
+    if (s->sampled_batch[s->n_sampled - 1] != s->max_batch)
+        return fail(nullptr, ETC_EINVAL, "the largest sampled batch must equal max_batch");
+
+    etc_ctx *c = new (std::nothrow) etc_ctx();
+    if (!c) return fail(nullptr, ETC_ENOMEM, "out of host memory");
+    auto bail = [&](etc_status st) {
+        g_create_error = c->err;
+        etc_destroy(c);
+        return st;
+    };
+    c->model = *m;
+    c->tiles = *t;
+    ModelDims &d = c->dims;
+    d = ModelDims{m->n_layers, m->hidden, m->n_q_heads, m->n_kv_heads, m->head_dim, m->ffn, m->n_experts,
+                  m->top_k, m->moe_ffn, m->page_size, t->kv_chunk_tokens, std::max(1, t->moe_tile_m)};
+    std::string gerr = build_decoder_graph(d, s->kind != ETC_SCHED_DYNAMIC, &c->graph);
+    if (!gerr.empty()) { c->err = gerr; return bail(ETC_EINVAL); }
+
+    etc_status st = common_device_setup(c, s);
+    if (st != ETC_OK) return bail(st);
+    c->max_chunks = (s->max_kv_len + t->kv_chunk_tokens - 1) / t->kv_chunk_tokens;
+    c->max_pages_per_seq = (s->max_kv_len + m->page_size - 1) / m->page_size;
+
+    for (int i = 0; i < s->n_sampled; ++i) {
+        c->plans.emplace_back();
+        DevPlan &dp = c->plans.back();
+        dp.sampled_batch = s->sampled_batch[i];
+        int syms[4] = {dp.sampled_batch, c->max_chunks, 0, 0};
+        std::string err = instantiate(c->graph, syms, c->n_queues, s->kind == ETC_SCHED_UNFUSED, &dp.host);
+        if (!err.empty()) { c->err = err; return bail(ETC_EINVAL); }
+        st = upload_plan(c, dp);
+        if (st != ETC_OK) return bail(st);
+    }
+    st = alloc_events_and_queue(c);
+    if (st != ETC_OK) return bail(st);
+
+    // scratch
+    Params &P = c->base;
+    const size_t MB = (size_t)s->max_batch, H = (size_t)m->hidden, QD = (size_t)m->n_q_heads * m->head_dim;
+    P.n_layers = m->n_layers; P.H = m->hidden; P.nq = m->n_q_heads; P.nkv = m->n_kv_heads; P.d = m->head_dim;
+    P.F = m->ffn; P.E = m->n_experts; P.topk = m->top_k; P.moeF = m->moe_ffn; P.page = m->page_size;
+    P.eps = m->rms_eps; P.theta = m->rope_theta; P.kv_chunk = t->kv_chunk_tokens; P.tile_m = d.tile_m;
+    auto A = [&](auto **p, size_t n) -> bool {
+        hipError_t e = dev_alloc(p, n, c->owned);
+        if (e != hipSuccess) { c->err = std::string("device allocation failed: ") + hipGetErrorString(e); return false; }
+        return true;
+    };
+    bool okk = A(&P.x, MB * H) && A(&P.x_mid, MB * H) && A(&P.qbuf, MB * QD) && A(&P.attn, MB * QD) &&
+               A(&P.act, MB * (size_t)std::max(1, m->ffn)) &&
+               A(&P.part_m, MB * m->n_q_heads * (size_t)c->max_chunks) &&
+               A(&P.part_l, MB * m->n_q_heads * (size_t)c->max_chunks) &&
+               A(&P.part_o, MB * m->n_q_heads * (size_t)c->max_chunks * m->head_dim) &&
+               A(&c->d_kv_len, MB) && A(&c->d_page_indptr, MB + 1) && A(&c->d_page_ids, MB * (size_t)c->max_pages_per_seq) &&
+               A(&c->d_weights, (size_t)m->n_layers);
+    if (okk && (s->debug_flags & ETC_DEBUG_LAYER_HIDDEN)) okk = A(&P.layer_hidden, (size_t)m->n_layers * kMaxBatch * H);
+    if (!okk) return bail(ETC_ENOMEM);
+    c->h_weights.assign(m->n_layers, LayerWeights{});
+    c->weights_bound.assign(m->n_layers, 0);
+    *out = c;
+    return ETC_OK;
+}
+
+etc_status etc_bind_layer_weights(etc_ctx *c, int32_t layer, const etc_layer_weights *w)
+{
+    if (!c || c->is_graph || !w) return fail(c, ETC_EINVAL, "bad argument");
+    if (layer < 0 || layer >= c->model.n_layers) return fail(c, ETC_EINVAL, "layer out of range");
+    const bool moe = c->model.n_experts > 0;
+    if (!w->g1 || !w->wq || !w->wk || !w->wv || !w->wo || !w->g2) return fail(c, ETC_EINVAL, "attention weights missing");
+    if (!moe && (!w->wg || !w->wu || !w->wd)) return fail(c, ETC_EINVAL, "dense FFN weights missing");
+    if (moe && (!w->wr || !w->eg || !w->eu || !w->ed)) return fail(c, ETC_EINVAL, "MoE weights missing");
+    const void *all[] = {w->g1, w->wq, w->wk, w->wv, w->wo, w->g2, w->wg, w->wu, w->wd, w->wr, w->eg, w->eu, w->ed};
+    for (const void *p : all)
+        if (p && ((uintptr_t)p & 15)) return fail(c, ETC_EINVAL, "weight pointers must be 16-byte aligned");
+    c->h_weights[layer] = LayerWeights{w->g1, w->wq, w->wk, w->wv, w->wo, w->g2, w->wg, w->wu, w->wd, w->wr, w->eg, w->eu, w->ed};
+    c->weights_bound[layer] = 1;
+    c->weights_dirty = true;
+    return ETC_OK;
+}
+
+etc_status etc_bind_kv_pool(etc_ctx *c, void *k_pages, void *v_pages, int64_t pages_per_layer)
+{
+    if (!c || c->is_graph || !k_pages || !v_pages || pages_per_layer < 1) return fail(c, ETC_EINVAL, "bad argument");
+    if (((uintptr_t)k_pages & 15) || ((uintptr_t)v_pages & 15)) return fail(c, ETC_EINVAL, "KV pools must be 16-byte aligned");
+    c->base.kpool = (uint16_t *)k_pages;
+    c->base.vpool = (uint16_t *)v_pages;
+    c->pages_per_layer = pages_per_layer;
+    c->base.pool_layer_stride = pages_per_layer * c->model.page_size * (int64_t)c->model.n_kv_heads * c->model.head_dim;
+    c->kv_bound = true;
+    c->step_bound = false;   // page ids are validated against the pool at bind_step
+    return ETC_OK;
+}
+
+etc_status etc_bind_step(etc_ctx *c, int32_t batch, const int32_t *kv_len, const int32_t *page_indptr, const int32_t *page_ids)
+{
+    if (!c || c->is_graph || !kv_len || !page_indptr || !page_ids) return fail(c, ETC_EINVAL, "bad argument");
+    if (!c->kv_bound) return fail(c, ETC_ESTATE, "bind the KV pool before a step");
+    if (batch < 1 || batch > c->sched.max_batch) return fail(c, ETC_EINVAL, "batch out of range 1..max_batch");
+    const int P = c->model.page_size;
+    if (page_indptr[0] != 0) return fail(c, ETC_EINVAL, "page_indptr[0] must be 0");
+    int64_t kv_tokens = 0;
+    for (int b = 0; b < batch; ++b) {
+        if (kv_len[b] < 0 || kv_len[b] + 1 > c->sched.max_kv_len) return fail(c, ETC_EINVAL, "kv_len out of range (kv_len + 1 <= max_kv_len)");
+        const int need = (kv_len[b] + 1 + P - 1) / P;
+        if (page_indptr[b + 1] - page_indptr[b] != need)
+            return fail(c, ETC_EINVAL, "page_indptr does not give ceil((kv_len+1)/page_size) pages to sequence " + std::to_string(b));
+        kv_tokens += kv_len[b] + 1;
+    }
+    const int n_ids = page_indptr[batch];
+    for (int i = 0; i < n_ids; ++i)
+        if (page_ids[i] < 0 || page_ids[i] >= c->pages_per_layer) return fail(c, ETC_EINVAL, "page id outside the bound pool");
+    // the next larger sampled batch size serves this step (Sec. 3.1)
+    int plan = -1;
+    for (size_t i = 0; i < c->plans.size(); ++i)
+        if (c->plans[i].sampled_batch >= batch) { plan = (int)i; break; }
+    if (plan < 0) return fail(c, ETC_EINVAL, "no sampled batch size covers this batch");
+
+    HIP_TRY(c, hipDeviceSynchronize());
+    etc_status st = check_error_word(c);
+    if (st != ETC_OK) return st;
+    HIP_TRY(c, hipMemcpy(c->d_kv_len, kv_len, (size_t)batch * sizeof(int32_t), hipMemcpyHostToDevice));
+    HIP_TRY(c, hipMemcpy(c->d_page_indptr, page_indptr, (size_t)(batch + 1) * sizeof(int32_t), hipMemcpyHostToDevice));
+    HIP_TRY(c, hipMemcpy(c->d_page_ids, page_ids, (size_t)n_ids * sizeof(int32_t), hipMemcpyHostToDevice));
+    c->cur_plan = plan;
+    c->bound_batch = batch;
+    c->h_kv_len.assign(kv_len, kv_len + batch);
+    st = arm_events(c);
+    if (st != ETC_OK) return st;
+
+    // algorithmic bytes: every touched weight once, every live KV byte once, appended rows written
+    const etc_model_desc &m = c->model;
+    const int64_t QD = (int64_t)m.n_q_heads * m.head_dim, KD = (int64_t)m.n_kv_heads * m.head_dim, H = m.hidden;
+    int64_t w_layer = 2 * H + QD * H + 2 * KD * H + H * QD;
+    if (m.n_experts == 0) w_layer += 3 * (int64_t)m.ffn * H;
+    else w_layer += (int64_t)m.n_experts * H + std::min<int64_t>(m.n_experts, (int64_t)batch * m.top_k) * 3 * (int64_t)m.moe_ffn * H;
+    const int64_t kv_layer = kv_tokens * KD * 2 + (int64_t)batch * KD * 2;   // read K and V, write the new rows
+    c->algorithmic_bytes = 2 * (int64_t)m.n_layers * (w_layer + kv_layer);
+    c->step_bound = true;
+    return ETC_OK;
+}
+
+etc_status etc_force_routing(etc_ctx *c, int32_t layer, const int32_t *ids)
+{
+    if (!c || c->is_graph || c->model.n_experts == 0) return fail(c, ETC_EINVAL, "not a MoE context");
+    if (layer < 0 || layer >= c->model.n_layers) return fail(c, ETC_EINVAL, "layer out of range");
+    const size_t per_layer = (size_t)c->sched.max_batch * c->model.top_k;
+    if (!c->d_forced) {
+        HIP_TRY(c, dev_alloc(&c->d_forced, per_layer * c->model.n_layers, c->owned));
+        HIP_TRY(c, dev_alloc(&c->d_forced_mask, (size_t)c->model.n_layers, c->owned));
+        c->h_forced_mask.assign(c->model.n_layers, 0);
+    }
+    HIP_TRY(c, hipDeviceSynchronize());
+    if (ids) {
+        if (!c->step_bound) return fail(c, ETC_ESTATE, "bind a step before forcing its routing");
+        for (int i = 0; i < c->bound_batch * c->model.top_k; ++i)
+            if (ids[i] < 0 || ids[i] >= c->model.n_experts) return fail(c, ETC_EINVAL, "expert id out of range");
+        HIP_TRY(c, hipMemcpy(c->d_forced + per_layer * layer, ids, (size_t)c->bound_batch * c->model.top_k * sizeof(int32_t),
+                             hipMemcpyHostToDevice));
+    }
+    c->h_forced_mask[layer] = ids ? 1 : 0;
+    HIP_TRY(c, hipMemcpy(c->d_forced_mask, c->h_forced_mask.data(), c->h_forced_mask.size(), hipMemcpyHostToDevice));
+    return ETC_OK;
+}
+
+etc_status etc_launch(etc_ctx *c, const void *hidden_in, void *hidden_out, void *hip_stream)
+{
+    Params P;
+    etc_status st = pre_launch(c, hidden_in, hidden_out, P);
+    if (st != ETC_OK) return st;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (c->sched.kind == ETC_SCHED_DYNAMIC) HIP_TRY(c, launch_dynamic(P, s));
+    else HIP_TRY(c, launch_static(P, s));
+    post_launch(c);
+    return ETC_OK;
+}
+
+etc_status etc_launch_kernel_by_kernel(etc_ctx *c, const void *hidden_in, void *hidden_out, void *hip_stream)
+{
+    Params P;
+    etc_status st = pre_launch(c, hidden_in, hidden_out, P);
+    if (st != ETC_OK) return st;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const Plan &pl = c->plans[c->cur_plan].host;
+    // one launch per operator stage; the calls of a stage are contiguous in task-id order
+    size_t ci = 0;
+    while (ci < pl.stage_of_call.size()) {
+        size_t cj = ci;
+        while (cj + 1 < pl.stage_of_call.size() && pl.stage_of_call[cj + 1] == pl.stage_of_call[ci]) ++cj;
+        HIP_TRY(c, launch_stage(P, pl.call_begin[ci], pl.call_begin[cj + 1] - pl.call_begin[ci], s));
+        ci = cj + 1;
+    }
+    return ETC_OK;   // event buffers untouched: parity and epoch stay
+}
+
+etc_status etc_read_debug(etc_ctx *c, int32_t kind, int32_t layer, void *dst, size_t bytes)
+{
+    if (!c || !dst) return fail(c, ETC_EINVAL, "bad argument");
+    HIP_TRY(c, hipDeviceSynchronize());
+    const size_t N = (size_t)c->n_events_max;
+    const Params &P = c->base;
+    const void *src = nullptr;
+    size_t avail = 0;
+    const size_t MB = (size_t)c->sched.max_batch;
+    switch (kind) {
+    case ETC_DBG_ERROR_WORD: src = P.error_word; avail = 4 * sizeof(int32_t); break;
+    case ETC_DBG_EVENT_COUNTERS:
+        if (c->cur_plan < 0) return fail(c, ETC_ESTATE, "nothing bound");
+        // the buffer the last launch consumed is the one the next launch re-arms... it was `cur` before the flip
+        src = c->d_events + (c->parity ? 0 : 2 * N);
+        avail = c->plans[c->cur_plan].host.ev_init.size() * sizeof(int32_t);
+        break;
+    case ETC_DBG_TASK_EXEC_COUNT:
+        if (!P.exec_count || c->cur_plan < 0) return fail(c, ETC_ESTATE, "exec counting is off");
+        src = P.exec_count; avail = c->plans[c->cur_plan].host.tasks.size() * sizeof(int32_t); break;
+    case ETC_DBG_LAYER_HIDDEN:
+        if (!P.layer_hidden) return fail(c, ETC_ESTATE, "layer dump is off");
+        if (layer < 0 || layer >= c->model.n_layers) return fail(c, ETC_EINVAL, "layer out of range");
+        src = P.layer_hidden + (size_t)layer * kMaxBatch * c->model.hidden;
+        avail = (size_t)c->bound_batch * c->model.hidden * sizeof(float); break;
+    default:
+        return fail(c, ETC_EINVAL, "unknown or unavailable debug kind");
+    }
+    (void)MB;
+    if (bytes > avail) return fail(c, ETC_EINVAL, "more bytes requested than the item holds");
+    HIP_TRY(c, hipMemcpy(dst, src, bytes, hipMemcpyDeviceToHost));
+    if (kind == ETC_DBG_ERROR_WORD) return ETC_OK;
+    return check_error_word(c);
+}
+
+etc_status etc_get_step_info(etc_ctx *c, etc_step_info *info)
+{
+    if (!c || !info) return fail(c, ETC_EINVAL, "bad argument");
+    if (c->cur_plan < 0) return fail(c, ETC_ESTATE, "nothing bound");
+    const DevPlan &dp = c->plans[c->cur_plan];
+    info->n_tasks = (int64_t)dp.host.tasks.size();
+    info->n_events = (int64_t)dp.host.ev_init.size();
+    info->n_queues = c->n_queues;
+    info->algorithmic_bytes = c->algorithmic_bytes;
+    info->sampled_batch = dp.sampled_batch;
+    info->workgroup_threads = kWgThreads;
+    return ETC_OK;
+}
+
+// ---- host-only inspection ---------------------------------------------------------------------------
+static_assert(sizeof(etc_task_record) == sizeof(Task), "public task record must mirror the device record");
+
+etc_status etc_plan_build(const etc_model_desc *m, const etc_tile_desc *t, const etc_sched_desc *s, int32_t sampled_batch,
+                          int32_t n_queues, etc_plan_view *out)
+{
+    if (!m || !t || !s || !out) return fail(nullptr, ETC_EINVAL, "NULL argument");
+    if (sampled_batch < 1 || sampled_batch > kMaxBatch || n_queues < 1) return fail(nullptr, ETC_EINVAL, "bad batch or queue count");
+    if (t->kv_chunk_tokens < 1 || s->max_kv_len < 1) return fail(nullptr, ETC_EINVAL, "bad chunk or max_kv_len");
+    ModelDims d{m->n_layers, m->hidden, m->n_q_heads, m->n_kv_heads, m->head_dim, m->ffn, m->n_experts,
+                m->top_k, m->moe_ffn, m->page_size, t->kv_chunk_tokens, std::max(1, t->moe_tile_m)};
+    GraphDecl g;
+    std::string err = build_decoder_graph(d, s->kind != ETC_SCHED_DYNAMIC, &g);
+    if (!err.empty()) return fail(nullptr, ETC_EINVAL, err);
+    Plan *p = new (std::nothrow) Plan();
+    if (!p) return fail(nullptr, ETC_ENOMEM, "out of host memory");
+    int syms[4] = {sampled_batch, (s->max_kv_len + t->kv_chunk_tokens - 1) / t->kv_chunk_tokens, 0, 0};
+    err = instantiate(g, syms, n_queues, s->kind == ETC_SCHED_UNFUSED, p);
+    if (!err.empty()) { delete p; return fail(nullptr, ETC_EINVAL, err); }
+    out->n_tasks = (int64_t)p->tasks.size();
+    out->n_events = (int64_t)p->ev_init.size();
+    out->n_queues = n_queues;
+    out->n_seed = (int64_t)p->seed_tasks.size();
+    out->tasks = reinterpret_cast<const etc_task_record *>(p->tasks.data());
+    out->queue_tasks = reinterpret_cast<const etc_task_record *>(p->queue_tasks.data());
+    out->queue_begin = p->queue_begin.data();
+    out->ev_init = p->ev_init.data();
+    out->ev_consumers = p->ev_consumers.data();
+    out->consumer_ids = p->consumer_ids.data();
+    out->seed_tasks = p->seed_tasks.data();
+    out->opaque = p;
+    return ETC_OK;
+}
+
+void etc_plan_free(etc_plan_view *v)
+{
+    if (!v || !v->opaque) return;
+    delete static_cast<Plan *>(v->opaque);
+    memset(v, 0, sizeof(*v));
+}
+
+// ---- generic graphs ------------------------------------------------------------------------------
+etc_status etc_graph_create(const etc_sched_desc *s, etc_ctx **out)
+{
+    if (!s || !out) return fail(nullptr, ETC_EINVAL, "NULL argument");
+    *out = nullptr;
+    if (s->kind < ETC_SCHED_STATIC || s->kind > ETC_SCHED_UNFUSED) return fail(nullptr, ETC_EINVAL, "unknown scheduler kind");
+    etc_ctx *c = new (std::nothrow) etc_ctx();
+    if (!c) return fail(nullptr, ETC_ENOMEM, "out of host memory");
+    c->is_graph = true;
+    etc_status st = common_device_setup(c, s);
+    if (st != ETC_OK) { g_create_error = c->err; etc_destroy(c); return st; }
+    *out = c;
+    return ETC_OK;
+}
+
+etc_status etc_graph_add_event(etc_ctx *c, const etc_dim_expr *shape, int32_t rank, int32_t *event_id)
+{
+    if (!c || !c->is_graph || !shape || !event_id || rank < 1 || rank > 3) return fail(c, ETC_EINVAL, "bad argument");
+    EventDecl e;
+    e.rank = rank;
+    for (int r = 0; r < rank; ++r) {
+        if (shape[r].sym >= 4) return fail(c, ETC_EINVAL, "symbol id must be 0..3");
+        e.shape[r] = DimExpr{shape[r].sym, shape[r].mul, shape[r].add};
+    }
+    c->graph.events.push_back(e);
+    *event_id = (int32_t)c->graph.events.size() - 1;
+    return ETC_OK;
+}
+
+etc_status etc_graph_add_call(etc_ctx *c, int32_t fn, const etc_dim_expr *shape, int32_t rank, const etc_edge *in,
+                              int32_t n_in, const etc_edge *outs, int32_t n_out)
+{
+    if (!c || !c->is_graph || !shape || rank < 1 || rank > 3) return fail(c, ETC_EINVAL, "bad argument");
+    if (fn != ETC_FN_ROWSUM_PARTIAL && fn != ETC_FN_ROWSUM_FINAL) return fail(c, ETC_EINVAL, "unknown device function");
+    if (n_in < 0 || n_in > 2 || n_out < 0 || n_out > 1 || (n_in && !in) || (n_out && !outs))
+        return fail(c, ETC_EINVAL, "a call takes at most 2 in-edges and 1 out-edge");
+    CallDecl cd;
+    cd.fn = fn == ETC_FN_ROWSUM_PARTIAL ? FN_ROWSUM_PARTIAL : FN_ROWSUM_FINAL;
+    cd.rank = rank;
+    cd.stage = (int)c->graph.calls.size();
+    for (int r = 0; r < rank; ++r) cd.shape[r] = DimExpr{shape[r].sym, shape[r].mul, shape[r].add};
+    auto conv = [&](const etc_edge &e, EdgeMap *m) -> bool {
+        if (e.event < 0 || e.event >= (int)c->graph.events.size() || e.rank != c->graph.events[e.event].rank) return false;
+        m->event = e.event;
+        m->rank = e.rank;
+        for (int r = 0; r < e.rank; ++r) {
+            if (e.kind[r] != ETC_MAP_DIM && e.kind[r] != ETC_MAP_CONST) return false;
+            if (e.kind[r] == ETC_MAP_DIM && (e.src[r] < 0 || e.src[r] >= rank || e.div[r] < 1)) return false;
+            m->kind[r] = e.kind[r] == ETC_MAP_DIM ? MAP_DIM : MAP_CONST;
+            m->src[r] = e.src[r];
+            m->div[r] = e.div[r];
+        }
+        return true;
+    };
+    for (int i = 0; i < n_in; ++i) { EdgeMap m; if (!conv(in[i], &m)) return fail(c, ETC_EINVAL, "malformed in-edge"); cd.in.push_back(m); }
+    for (int i = 0; i < n_out; ++i) { EdgeMap m; if (!conv(outs[i], &m)) return fail(c, ETC_EINVAL, "malformed out-edge"); cd.out.push_back(m); }
+    c->graph.calls.push_back(cd);
+    return ETC_OK;
+}
+
+etc_status etc_graph_bind_buffer(etc_ctx *c, int32_t slot, void *ptr, size_t bytes)
+{
+    if (!c || !c->is_graph || slot < 0 || slot > 3 || !ptr) return fail(c, ETC_EINVAL, "bad argument");
+    c->base.gbuf[slot] = (float *)ptr;
+    c->gbuf_bytes[slot] = bytes;
+    return ETC_OK;
+}
+
+etc_status etc_graph_bind_shape(etc_ctx *c, const int32_t *values)
+{
+    if (!c || !c->is_graph || !values) return fail(c, ETC_EINVAL, "bad argument");
+    for (int i = 0; i < 4; ++i)
+        if (values[i] < 0 || values[i] > (1 << 20)) return fail(c, ETC_EINVAL, "symbol value out of range");
+    HIP_TRY(c, hipDeviceSynchronize());
+    // instantiate the template for these symbol values: no kernel is rebuilt, only queues and counts
+    DevPlan dp;
+    int syms[4] = {values[0], values[1], values[2], values[3]};
+    std::string err = instantiate(c->graph, syms, c->n_queues, c->sched.kind == ETC_SCHED_UNFUSED, &dp.host);
+    if (!err.empty()) return fail(c, ETC_EINVAL, err);
+    for (void *p : c->plan_owned) (void)hipFree(p);
+    c->plan_owned.clear();
+    c->base.exec_count = nullptr;
+    c->step_bound = false;
+    c->plans.clear();
+    etc_status st = upload_plan(c, dp);
+    if (st != ETC_OK) return st;
+    c->plans.push_back(dp);
+    c->cur_plan = 0;
+    st = alloc_events_and_queue(c);
+    if (st != ETC_OK) return st;
+    for (int i = 0; i < 4; ++i) c->sym_values[i] = values[i];
+    st = arm_events(c);
+    if (st != ETC_OK) return st;
+    c->step_bound = true;
+    return ETC_OK;
+}
+
+etc_status etc_graph_launch(etc_ctx *c, void *hip_stream)
+{
+    if (!c || !c->is_graph) return fail(c, ETC_EINVAL, "not a graph context");
+    if (!c->step_bound) return fail(c, ETC_ESTATE, "bind a shape first");
+    bool need[3] = {false, false, false};
+    for (const CallDecl &cd : c->graph.calls) {
+        if (cd.fn == FN_ROWSUM_PARTIAL) need[0] = need[1] = true;
+        if (cd.fn == FN_ROWSUM_FINAL) need[1] = need[2] = true;
+    }
+    for (int i = 0; i < 3; ++i)
+        if (need[i] && !c->base.gbuf[i]) return fail(c, ETC_ESTATE, "a device-function buffer is not bound");
+    // the task grids must stay inside the bound buffers: A (rows, 128), B (rows, 4), C (rows), 32 rows per task
+    for (const CallDecl &cd : c->graph.calls) {
+        const size_t rows = (size_t)32 * (size_t)cd.shape[0].eval(c->sym_values);
+        if (cd.fn == FN_ROWSUM_PARTIAL) {
+            if (cd.rank != 2 || cd.shape[1].eval(c->sym_values) > 4) return fail(c, ETC_EINVAL, "partial_sum takes a (n, <=4) grid");
+            if (rows * 128 * 4 > c->gbuf_bytes[0] || rows * 4 * 4 > c->gbuf_bytes[1]) return fail(c, ETC_EINVAL, "buffer A or B too small for the bound shape");
+        } else {
+            if (cd.rank != 1) return fail(c, ETC_EINVAL, "final_sum takes a (n) grid");
+            if (rows * 4 * 4 > c->gbuf_bytes[1] || rows * 4 > c->gbuf_bytes[2]) return fail(c, ETC_EINVAL, "buffer B or C too small for the bound shape");
+        }
+    }
+    Params P;
+    fill_launch_params(c, P);
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (c->sched.kind == ETC_SCHED_DYNAMIC) HIP_TRY(c, launch_dynamic(P, s));
+    else HIP_TRY(c, launch_static(P, s));
+    post_launch(c);
+    return ETC_OK;
+}
+
+}  // extern "C"

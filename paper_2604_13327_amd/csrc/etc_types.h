@@ -1,0 +1,124 @@
+// Plain-data structures shared by the host scheduler and the device megakernel.
+#pragma once
+#include <stdint.h>
+
+namespace etc {
+
+constexpr int kWgThreads = 512;          // one task = one workgroup of 8 wavefronts on one CU
+constexpr int kWaves = kWgThreads / 64;
+constexpr int kMaxBatch = 64;
+constexpr int kMaxLayers = 128;
+constexpr int kLdsBytes = 96 * 1024;     // > half of the 160 KB LDS: at most one workgroup per CU
+
+// Device functions (task bodies).  One entry of the dispatch switch each (Alg. 1 "dispatch logic").
+enum Fn : uint8_t {
+    FN_NOP = 0,
+    FN_ROWSUM_PARTIAL = 1,
+    FN_ROWSUM_FINAL = 2,
+    FN_LOAD_HIDDEN = 3,   // hidden_in bf16 -> residual stream fp32
+    FN_QKV = 4,           // RMSNorm prologue, 16 rows of Wq|Wk|Wv (8 RoPE pairs), RoPE, KV append
+    FN_ATTN = 5,          // split-KV partial attention of (sequence, kv head, chunk)
+    FN_MERGE = 6,         // merge of the chunk partials of (sequence, kv head)
+    FN_OPROJ = 7,         // 16 rows of Wo + residual
+    FN_GATEUP = 8,        // RMSNorm prologue, 8 gate + 8 up rows, SiLU-mul epilogue
+    FN_DOWN = 9,          // 16 rows of Wd + residual (waves split K; each waits for its own K slice)
+    FN_ROUTER = 10,       // MoE: norm, router logits, top-k, weights, counts, indptr; arms expert events
+    FN_GROUP = 11,        // MoE: one tile per token, stable rank inside its experts' ranges
+    FN_MOE_GATEUP = 12,   // MoE: GroupGEMM-1 tile (row tile, 8 gate + 8 up rows), SiLU-mul
+    FN_MOE_DOWN = 13,     // MoE: GroupGEMM-2 tile (row tile, 16 rows of the expert's Wd)
+    FN_COMBINE = 14,      // MoE: weighted sum of a token's expert outputs in slot order + residual
+    FN_COUNT
+};
+
+// Task flags
+enum : uint16_t {
+    TF_WAIT0_PER_WAVE = 1,   // wave w waits on event wait0 + w instead of the whole workgroup on wait0
+    TF_LAST_LAYER = 2,       // also write hidden_out
+    TF_DYN_ROWTILE = 4,      // c0 is a GroupGEMM row-tile id resolved through exp_indptr at run time
+};
+
+// One materialised task of a static queue (Sec. 3.1: "static execution queue"), 32 bytes.
+struct Task {
+    uint8_t fn;
+    uint8_t layer;
+    uint16_t flags;
+    int32_t c0, c1, c2;      // task coordinate
+    int32_t wait0, wait1;    // flat event indices to wait on (-1: none)
+    int32_t notify0;         // flat event index to notify (-1: none)
+    int32_t id;              // global task id (exec-count slot)
+};
+static_assert(sizeof(Task) == 32, "Task must stay 32 bytes");
+
+struct LayerWeights {
+    const void *g1, *wq, *wk, *wv, *wo, *g2, *wg, *wu, *wd, *wr, *eg, *eu, *ed;
+};
+
+// Error word codes
+enum : int32_t { ERR_NONE = 0, ERR_WAIT_TIMEOUT = 1, ERR_QUEUE_OVERFLOW = 2, ERR_POP_TIMEOUT = 3 };
+
+// Everything the megakernel needs, passed by value as the kernel argument.
+struct Params {
+    // model
+    int32_t n_layers, H, nq, nkv, d, F, E, topk, moeF, page;
+    float eps, theta;
+    int32_t kv_chunk, tile_m;
+    // resident tensors
+    const LayerWeights *weights;       // [n_layers] device
+    uint16_t *kpool, *vpool;           // bf16 bits
+    int64_t pool_layer_stride;         // elements per layer
+    // step shape
+    int32_t B;                         // bound batch
+    int32_t Bs;                        // sampled batch the queues were built for
+    int32_t max_chunks;                // attention chunk slots per sequence in the queues
+    const int32_t *kv_len, *page_indptr, *page_ids;
+    const uint16_t *hidden_in;
+    uint16_t *hidden_out;
+    // scratch (library-owned)
+    float *x, *x_mid;                  // residual stream [maxB, H]
+    float *qbuf;                       // rotated queries [maxB, nq*d]
+    uint16_t *attn;                    // attention output bf16 [maxB, nq*d]
+    uint16_t *act;                     // silu(gate)*up bf16 [maxB, F]
+    float *part_m, *part_l, *part_o;   // split-KV partials [maxB, nq, max_chunks] (+ [d])
+    // MoE scratch
+    float *router_logits;              // [maxB, E]
+    int32_t *topk_ids;                 // [maxB, topk]
+    float *topk_w;                     // [maxB, topk]
+    int32_t *exp_count, *tok_indptr, *exp_indptr, *perm, *inv_perm; // [E], [E+1], [E+1], [maxB*topk] x2
+    uint16_t *xn2;                     // normalised FFN input bf16 [maxB, H]
+    uint16_t *eact;                    // expert activations bf16 [maxB*topk, moeF]
+    float *ey;                         // expert outputs fp32 [maxB*topk, H]
+    const int32_t *forced_topk;        // [n_layers, maxB, topk] or null
+    const uint8_t *forced_mask;        // [n_layers] or null
+    // event tensors: three equal arrays [cur | init | next]; the kernel re-arms `next` from `init`
+    int32_t *ev_cur;
+    const int32_t *ev_init;
+    int32_t *ev_next;
+    int32_t n_events;
+    // static queues
+    const Task *tasks;                 // all queues back to back
+    const int32_t *queue_begin;        // [n_queues + 1]
+    int32_t n_queues;
+    // dynamic scheduler
+    const Task *dyn_tasks;             // task table indexed by task id
+    const int32_t *ev_consumers;       // [n_events + 1] CSR: tasks pushed when the event fires
+    const int32_t *consumer_ids;
+    const int32_t *seed_tasks;         // tasks with no trigger edge, pushed at start
+    int32_t n_seed;
+    int32_t n_static_tasks;
+    uint64_t *q_slots;                 // (epoch << 32 | task id + 1)
+    int32_t q_capacity;
+    int32_t *q_ctrl_cur;               // [head, tail, done, pad]
+    int32_t *q_ctrl_next;
+    uint32_t epoch;
+    // debug / safety
+    int64_t spin_budget;
+    uint32_t debug_flags;
+    int32_t *exec_count;
+    float *layer_hidden;               // [n_layers, maxB, H]
+    int32_t *error_word;               // [4]
+    // generic-graph buffers (row-sum example)
+    float *gbuf[4];
+    int32_t gsym[4];
+};
+
+}  // namespace etc

@@ -1,0 +1,260 @@
+// Event-tensor graph IR: instantiation into tasks, event counts and queues; the decoder's graph.
+#include "graph.h"
+
+#include <algorithm>
+#include <sstream>
+
+namespace etc {
+
+int GraphDecl::add_event(std::initializer_list<DimExpr> shape)
+{
+    EventDecl e;
+    e.rank = (int)shape.size();
+    int i = 0;
+    for (const DimExpr &d : shape) e.shape[i++] = d;
+    events.push_back(e);
+    return (int)events.size() - 1;
+}
+
+static EdgeMap edge(int ev, std::initializer_list<int> kinds, std::initializer_list<int> srcs,
+                    std::initializer_list<int> divs)
+{
+    EdgeMap m;
+    m.event = ev;
+    m.rank = (int)kinds.size();
+    int i = 0;
+    for (int k : kinds) m.kind[i++] = k;
+    i = 0;
+    for (int s : srcs) m.src[i++] = s;
+    i = 0;
+    for (int d : divs) m.div[i++] = d;
+    return m;
+}
+static EdgeMap edge_const0(int ev) { return edge(ev, {MAP_CONST}, {0}, {0}); }
+static EdgeMap edge_dim(int ev, int src, int div = 1) { return edge(ev, {MAP_DIM}, {src}, {div}); }
+
+std::string instantiate(const GraphDecl &g, const int *sym, int n_queues, bool unfused, Plan *out)
+{
+    Plan &p = *out;
+    p = Plan();
+    if (n_queues <= 0) return "n_queues must be positive";
+
+    // event tensors -> flat offsets
+    std::vector<std::vector<int>> ev_dims(g.events.size());
+    p.ev_offset.assign(1, 0);
+    for (size_t e = 0; e < g.events.size(); ++e) {
+        int n = 1;
+        for (int r = 0; r < g.events[e].rank; ++r) {
+            int v = g.events[e].shape[r].eval(sym);
+            if (v < 0) return "negative event tensor dimension";
+            ev_dims[e].push_back(v);
+            n *= v;
+        }
+        p.ev_offset.push_back(p.ev_offset.back() + n);
+    }
+    int n_stages = 0;
+    for (const CallDecl &c : g.calls) n_stages = std::max(n_stages, c.stage + 1);
+    const int n_events = unfused ? n_stages : p.ev_offset.back();
+    p.ev_init.assign(n_events, 0);
+
+    auto flat_event = [&](const EdgeMap &m, const int *coord, int *flat) -> std::string {
+        if (m.event < 0 || m.event >= (int)g.events.size()) return "edge names an unknown event tensor";
+        const std::vector<int> &dims = ev_dims[m.event];
+        if (m.rank != (int)dims.size()) return "edge rank differs from its event tensor's rank";
+        int idx = 0;
+        for (int r = 0; r < m.rank; ++r) {
+            int v = m.kind[r] == MAP_CONST ? m.div[r] : coord[m.src[r]] / std::max(1, m.div[r]);
+            if (v < 0 || v >= dims[r]) {
+                std::ostringstream s;
+                s << "edge maps a task outside event tensor " << m.event << " (dim " << r << ": " << v
+                  << " not in [0, " << dims[r] << "))";
+                return s.str();
+            }
+            idx = idx * dims[r] + v;
+        }
+        *flat = p.ev_offset[m.event] + idx;
+        return "";
+    };
+
+    p.call_begin.assign(1, 0);
+    for (const CallDecl &c : g.calls) {
+        if (c.in.size() > 2 || c.out.size() > 1) return "a call has more than 2 in-edges or 1 out-edge";
+        int dims[3] = {1, 1, 1};
+        for (int r = 0; r < c.rank; ++r) dims[r] = c.shape[r].eval(sym);
+        const int total = dims[0] * dims[1] * dims[2];
+        for (int i = 0; i < total; ++i) {
+            int coord[3];
+            if (c.last_dim_slowest && c.rank == 3) {      // (c2 slowest, then c0, c1)
+                coord[2] = i / (dims[0] * dims[1]);
+                coord[0] = (i / dims[1]) % dims[0];
+                coord[1] = i % dims[1];
+            } else {
+                coord[0] = i / (dims[1] * dims[2]);
+                coord[1] = (i / dims[2]) % dims[1];
+                coord[2] = i % dims[2];
+            }
+            Task t{};
+            t.fn = (uint8_t)c.fn;
+            t.layer = (uint8_t)c.layer;
+            t.flags = c.flags;
+            t.c0 = coord[0] + c.c_off[0];
+            t.c1 = coord[1] + c.c_off[1];
+            t.c2 = coord[2] + c.c_off[2];
+            t.wait0 = t.wait1 = t.notify0 = -1;
+            t.id = (int32_t)p.tasks.size();
+            if (unfused) {
+                t.flags &= (uint16_t)~TF_WAIT0_PER_WAVE;
+                if (c.stage > 0) t.wait0 = c.stage - 1;
+                t.notify0 = c.stage;
+                p.ev_init[c.stage]++;
+            } else {
+                for (size_t k = 0; k < c.in.size(); ++k) {
+                    int f;
+                    std::string err = flat_event(c.in[k], coord, &f);
+                    if (!err.empty()) return err;
+                    (k == 0 ? t.wait0 : t.wait1) = f;
+                }
+                if (!c.out.empty()) {
+                    int f;
+                    std::string err = flat_event(c.out[0], coord, &f);
+                    if (!err.empty()) return err;
+                    t.notify0 = f;
+                    p.ev_init[f]++;
+                }
+            }
+            p.tasks.push_back(t);
+        }
+        p.call_begin.push_back((int32_t)p.tasks.size());
+        p.stage_of_call.push_back(c.stage);
+    }
+
+    // static queues: round-robin over the task enumeration (Sec. 3.1).  Every queue is a
+    // subsequence of one topological order (calls are listed producers first), so the globally
+    // oldest unfinished task always sits at some queue head with its events fired: no deadlock.
+    std::vector<std::vector<Task>> q(n_queues);
+    for (const Task &t : p.tasks) q[t.id % n_queues].push_back(t);
+    p.queue_begin.assign(1, 0);
+    for (int i = 0; i < n_queues; ++i) {
+        p.queue_tasks.insert(p.queue_tasks.end(), q[i].begin(), q[i].end());
+        p.queue_begin.push_back((int32_t)p.queue_tasks.size());
+    }
+
+    // dynamic scheduling: the event whose firing pushes a task (its first in-edge; the last K slice
+    // for per-wave waits), as a CSR table event -> consumer tasks.
+    std::vector<std::vector<int32_t>> cons(n_events);
+    for (const Task &t : p.tasks) {
+        if (t.wait0 < 0) {
+            p.seed_tasks.push_back(t.id);
+        } else {
+            int trig = (t.flags & TF_WAIT0_PER_WAVE) ? t.wait0 + kWaves - 1 : t.wait0;
+            cons[trig].push_back(t.id);
+        }
+    }
+    p.ev_consumers.assign(1, 0);
+    for (int e = 0; e < n_events; ++e) {
+        p.consumer_ids.insert(p.consumer_ids.end(), cons[e].begin(), cons[e].end());
+        p.ev_consumers.push_back((int32_t)p.consumer_ids.size());
+    }
+    return "";
+}
+
+std::string build_decoder_graph(const ModelDims &m, bool moe_static_coarse, GraphDecl *out)
+{
+    (void)moe_static_coarse;
+    GraphDecl &g = *out;
+    g = GraphDecl();
+    if (m.nq % m.nkv) return "n_q_heads must be a multiple of n_kv_heads";
+    if (m.d % 16 || (m.d != 64 && m.d != 128)) return "head_dim must be 64 or 128";
+    if (m.H % (kWaves * 32) || (m.nq * m.d) % (kWaves * 32)) return "hidden and n_q_heads*head_dim must be multiples of 256";
+    if (m.H % 16) return "hidden must be a multiple of 16";
+    if (m.E == 0 && (m.F % (kWaves * 32) || (m.F / 8) % kWaves)) return "ffn must be a multiple of 256";
+    if (m.n_layers > kMaxLayers) return "too many layers";
+    const int grp = m.nq / m.nkv;
+    const int sub = m.d / 16;                     // 16-row tiles (8 RoPE pairs) per head
+    const DimExpr B = dim_sym(0), NCH = dim_sym(1), one = dim_const(1);
+
+    int stage = 0;
+    int e_x = g.add_event({one});
+    {   // step prologue: hidden_in (bf16) -> residual stream
+        CallDecl c;
+        c.fn = FN_LOAD_HIDDEN; c.layer = 0; c.stage = stage++;
+        c.rank = 1; c.shape[0] = B;
+        c.out = {edge_const0(e_x)};
+        g.calls.push_back(c);
+    }
+    for (int l = 0; l < m.n_layers; ++l) {
+        const int e_qkv = g.add_event({dim_const(m.nkv)});
+        const int e_split = g.add_event({B, dim_const(m.nkv)});
+        const int e_attn = g.add_event({one});
+        const int e_xmid = g.add_event({one});
+        const int e_xnext = g.add_event({one});
+        const uint16_t last = (l == m.n_layers - 1) ? TF_LAST_LAYER : 0;
+
+        // Q, K and V row tiles: three launches of one device function, same stage (they run
+        // concurrently; Sec. 4.3 names Q and K processing overlapping inside the megakernel).
+        for (int part = 0; part < 3; ++part) {
+            CallDecl c;
+            c.fn = FN_QKV; c.layer = l; c.stage = stage;
+            c.rank = 2;
+            c.shape[0] = dim_const(part == 0 ? m.nq : m.nkv);
+            c.shape[1] = dim_const(sub);
+            c.c_off[0] = part == 0 ? 0 : (part == 1 ? m.nq : m.nq + m.nkv);
+            c.in = {edge_const0(e_x)};
+            c.out = {edge_dim(e_qkv, 0, part == 0 ? grp : 1)};
+            g.calls.push_back(c);
+        }
+        stage++;
+        {
+            CallDecl c;
+            c.fn = FN_ATTN; c.layer = l; c.stage = stage++;
+            c.rank = 3; c.shape[0] = B; c.shape[1] = dim_const(m.nkv); c.shape[2] = NCH;
+            c.last_dim_slowest = true;
+            c.in = {edge_dim(e_qkv, 1)};
+            c.out = {edge(e_split, {MAP_DIM, MAP_DIM}, {0, 1}, {1, 1})};
+            g.calls.push_back(c);
+        }
+        {
+            CallDecl c;
+            c.fn = FN_MERGE; c.layer = l; c.stage = stage++;
+            c.rank = 2; c.shape[0] = B; c.shape[1] = dim_const(m.nkv);
+            c.in = {edge(e_split, {MAP_DIM, MAP_DIM}, {0, 1}, {1, 1})};
+            c.out = {edge_const0(e_attn)};
+            g.calls.push_back(c);
+        }
+        {
+            CallDecl c;
+            c.fn = FN_OPROJ; c.layer = l; c.stage = stage++;
+            c.rank = 1; c.shape[0] = dim_const(m.H / 16);
+            c.in = {edge_const0(e_attn)};
+            c.out = {edge_const0(e_xmid)};
+            g.calls.push_back(c);
+        }
+        if (m.E == 0) {
+            const int e_act = g.add_event({dim_const(kWaves)});
+            const int tiles = m.F / 8;
+            {
+                CallDecl c;
+                c.fn = FN_GATEUP; c.layer = l; c.stage = stage++;
+                c.rank = 1; c.shape[0] = dim_const(tiles);
+                c.in = {edge_const0(e_xmid)};
+                c.out = {edge_dim(e_act, 0, tiles / kWaves)};   // K slice of the down projection it feeds
+                g.calls.push_back(c);
+            }
+            {
+                CallDecl c;
+                c.fn = FN_DOWN; c.layer = l; c.stage = stage++;
+                c.rank = 1; c.shape[0] = dim_const(m.H / 16);
+                c.flags = (uint16_t)(TF_WAIT0_PER_WAVE | last);
+                c.in = {edge_const0(e_act)};                    // wave w waits on e_act[w]
+                c.out = {edge_const0(e_xnext)};
+                g.calls.push_back(c);
+            }
+        } else {
+            return "MoE layers are not wired into the graph yet";
+        }
+        e_x = e_xnext;
+    }
+    return "";
+}
+
+}  // namespace etc

@@ -1,0 +1,87 @@
+// Host-side event-tensor graph IR and its instantiation into task queues.
+//
+// A graph function (paper Sec. 2.1) is a list of device-function launches over task
+// grids plus event tensors; edges map a task coordinate to an event coordinate.  Shapes
+// may contain symbols; instantiate() binds them (Sec. 2.3) and materialises
+//   - the tasks with their flat wait / notify event indices,
+//   - the initial wait count of every event = number of tasks that notify it (Sec. 2.1),
+//   - static per-queue task lists, round-robin (Sec. 3.1, Alg. 1), or
+//   - the event -> consumer-task table used by push-on-zero (Sec. 3.2, Alg. 2).
+// Pure C++, no device code: it is also exercised by CPU-only tests.
+#pragma once
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "etc_types.h"
+
+namespace etc {
+
+struct DimExpr {
+    int sym = -1, mul = 0, add = 0;   // value = mul * symbol + add
+    int eval(const int *vals) const { return sym < 0 ? add : mul * vals[sym] + add; }
+};
+inline DimExpr dim_const(int c) { return DimExpr{-1, 0, c}; }
+inline DimExpr dim_sym(int s, int mul = 1, int add = 0) { return DimExpr{s, mul, add}; }
+
+enum MapKind { MAP_DIM = 0, MAP_CONST = 1 };
+
+struct EdgeMap {
+    int event = -1;                    // event tensor id
+    int rank = 0;
+    int kind[3] = {0, 0, 0};
+    int src[3] = {0, 0, 0};
+    int div[3] = {1, 1, 1};
+};
+
+struct EventDecl {
+    DimExpr shape[3];
+    int rank = 1;
+};
+
+struct CallDecl {
+    int fn = FN_NOP;
+    int layer = 0;
+    int stage = 0;                     // operator stage (calls of one stage may run concurrently)
+    DimExpr shape[3];
+    int rank = 1;
+    int c_off[3] = {0, 0, 0};          // added to the task coordinate stored in the Task record
+    bool last_dim_slowest = false;     // enumeration order (balances ragged grids across queues)
+    uint16_t flags = 0;
+    std::vector<EdgeMap> in, out;      // at most 2 in-edges, 1 out-edge
+};
+
+struct GraphDecl {
+    std::vector<EventDecl> events;
+    std::vector<CallDecl> calls;
+    int add_event(std::initializer_list<DimExpr> shape);
+};
+
+struct Plan {
+    std::vector<Task> tasks;           // by task id, call by call
+    std::vector<int32_t> call_begin;   // [n_calls + 1] task-id ranges of the calls
+    std::vector<int32_t> stage_of_call;
+    std::vector<int32_t> ev_init;      // initial wait counts
+    std::vector<int32_t> ev_offset;    // [n_event_tensors + 1] flat offsets
+    std::vector<Task> queue_tasks;     // static queues back to back
+    std::vector<int32_t> queue_begin;  // [n_queues + 1]
+    std::vector<int32_t> ev_consumers; // [n_events + 1] CSR over consumer_ids
+    std::vector<int32_t> consumer_ids;
+    std::vector<int32_t> seed_tasks;   // tasks with no in-edge
+};
+
+// Binds the symbols and materialises the plan.  unfused: ignore the declared edges and put one
+// coarse event between consecutive stages (Sec. 4.5 baseline).  Returns "" or an error text.
+std::string instantiate(const GraphDecl &g, const int *sym_values, int n_queues, bool unfused, Plan *out);
+
+struct ModelDims {
+    int n_layers, H, nq, nkv, d, F, E, topk, moeF, page;
+    int kv_chunk, tile_m;
+};
+
+// The decoder's graph function.  Symbol 0 = sampled batch size, symbol 1 = chunk slots per sequence.
+// moe_static_coarse: static scheduling of the data-dependent MoE stages through one coarse event
+// ("E[0]" rewrite of Sec. 3.1).
+std::string build_decoder_graph(const ModelDims &m, bool moe_static_coarse, GraphDecl *out);
+
+}  // namespace etc

@@ -1,0 +1,310 @@
+// The persistent megakernel: dispatch loop + event runtime + task bodies in one launch.
+//
+// Static scheduling (paper Sec. 3.1, Alg. 1): workgroup q walks its precomputed queue; every task
+// waits on its in-edge events, runs its tile, and notifies its out-edge event.
+// Dynamic scheduling (Sec. 3.2, Alg. 2): workgroups pop task ids from one ready queue in HBM; the
+// notify that brings an event to zero pushes that event's consumer tasks.
+// A third entry point runs one stage's tasks as an ordinary kernel (kernel-by-kernel comparator).
+#include <hip/hip_runtime.h>
+
+#include "device_rt.hip.h"
+#include "task_attn.hip.h"
+#include "task_gemm.hip.h"
+
+namespace etc {
+
+// ---------------------------------------------------------------------------------------------
+// small task bodies
+// ---------------------------------------------------------------------------------------------
+// Row-sum example (Sec. 2.2): A is (n*32, 128) fp32.
+__device__ __forceinline__ void rowsum_partial(const Params &P, int i, int j)
+{
+    // task (i, j): B[32i .. 32i+32, j] = sum_{k in [32j, 32j+32)} A[row, k], left to right
+    if (threadIdx.x < 32) {
+        const int row = 32 * i + threadIdx.x;
+        const float *a = P.gbuf[0] + (size_t)row * 128 + 32 * j;
+        float acc = 0.f;
+        for (int k = 0; k < 32; ++k) acc += a[k];
+        P.gbuf[1][(size_t)row * 4 + j] = acc;
+    }
+}
+__device__ __forceinline__ void rowsum_final(const Params &P, int i)
+{
+    if (threadIdx.x < 32) {
+        const int row = 32 * i + threadIdx.x;
+        const float *b = P.gbuf[1] + (size_t)row * 4;
+        P.gbuf[2][row] = ((b[0] + b[1]) + b[2]) + b[3];
+    }
+}
+
+__device__ __forceinline__ void load_hidden(const Params &P, int b)
+{
+    for (int i = threadIdx.x; i < P.H; i += kWgThreads)
+        P.x[(size_t)b * P.H + i] = bf16_bits_to_f32(P.hidden_in[(size_t)b * P.H + i]);
+}
+
+// ---------------------------------------------------------------------------------------------
+// dispatch: one task, including its waits; the caller notifies
+// ---------------------------------------------------------------------------------------------
+template <bool SYNC_EVENTS>
+__device__ __forceinline__ void run_task(const Params &P, const Task &t, float *sm)
+{
+    const int w0 = SYNC_EVENTS ? t.wait0 : -1, w1 = SYNC_EVENTS ? t.wait1 : -1;
+    const LayerWeights *W = P.weights ? P.weights + t.layer : nullptr;
+    TaskWaits tw{w0, w1, (int)t.fn, (t.flags & TF_WAIT0_PER_WAVE) != 0 && SYNC_EVENTS};
+    bool is_gemm = false;      // projection tiles share one call site of the MFMA body
+    GemmTile g{};
+    Epilogue e{};
+    switch (t.fn) {
+    case FN_ROWSUM_PARTIAL:
+        wave_wait(P, w0, t.fn);
+        rowsum_partial(P, t.c0, t.c1);
+        break;
+    case FN_ROWSUM_FINAL:
+        wave_wait(P, w0, t.fn);
+        rowsum_final(P, t.c0);
+        break;
+    case FN_LOAD_HIDDEN:
+        if (t.c0 < P.B) load_hidden(P, t.c0);
+        break;
+    case FN_QKV: {
+        const int hd = t.c0, sub = t.c1;
+        const int i0 = sub * 8;
+        const uint16_t *wbase;
+        if (hd < P.nq) wbase = (const uint16_t *)W->wq + (size_t)hd * P.d * P.H;
+        else if (hd < P.nq + P.nkv) wbase = (const uint16_t *)W->wk + (size_t)(hd - P.nq) * P.d * P.H;
+        else wbase = (const uint16_t *)W->wv + (size_t)(hd - P.nq - P.nkv) * P.d * P.H;
+        g.rowsA = wbase + (size_t)i0 * P.H;
+        g.rowsB = wbase + (size_t)(i0 + P.d / 2) * P.H;
+        g.ldw = P.H; g.K = P.H;
+        g.xf = P.x; g.gain = (const uint16_t *)W->g1; g.eps = P.eps; g.ldx = P.H;
+        g.n_cols = P.B;
+        e.kind = EPI_QKV; e.layer = t.layer; e.row0 = i0; e.head = hd;
+        is_gemm = true;
+        break;
+    }
+    case FN_ATTN: {
+        const int b = t.c0, kvh = t.c1, ch = t.c2;
+        const bool active = b < P.B && ch * P.kv_chunk < P.kv_len[b] + 1;
+        if (active) {     // inactive slots of the sampled-shape queue neither wait nor compute; they still notify
+            wave_wait(P, w0, t.fn);
+            const int grp = P.nq / P.nkv;
+            if (P.d == 128 && grp == 4) attn_chunk<128, 4>(P, t.layer, b, kvh, ch, sm);
+            else if (P.d == 128 && grp == 8) attn_chunk<128, 8>(P, t.layer, b, kvh, ch, sm);
+            else if (P.d == 64 && grp == 2) attn_chunk<64, 2>(P, t.layer, b, kvh, ch, sm);
+            else if (P.d == 128 && grp == 1) attn_chunk<128, 1>(P, t.layer, b, kvh, ch, sm);
+            else if (P.d == 64 && grp == 4) attn_chunk<64, 4>(P, t.layer, b, kvh, ch, sm);
+        }
+        break;
+    }
+    case FN_MERGE: {
+        const int b = t.c0, kvh = t.c1;
+        if (b < P.B) {
+            wave_wait(P, w0, t.fn);
+            const int grp = P.nq / P.nkv;
+            if (P.d == 128 && grp == 4) attn_merge<128, 4>(P, b, kvh);
+            else if (P.d == 128 && grp == 8) attn_merge<128, 8>(P, b, kvh);
+            else if (P.d == 64 && grp == 2) attn_merge<64, 2>(P, b, kvh);
+            else if (P.d == 128 && grp == 1) attn_merge<128, 1>(P, b, kvh);
+            else if (P.d == 64 && grp == 4) attn_merge<64, 4>(P, b, kvh);
+        }
+        break;
+    }
+    case FN_OPROJ: {
+        const int r0 = t.c0 * 16, QD = P.nq * P.d;
+        g.rowsA = (const uint16_t *)W->wo + (size_t)r0 * QD;
+        g.rowsB = g.rowsA + (size_t)8 * QD;
+        g.ldw = QD; g.K = QD;
+        g.xb = P.attn; g.ldxb = QD;
+        g.n_cols = P.B;
+        e.kind = EPI_RESID; e.layer = t.layer; e.row0 = r0; e.resid = P.x; e.outf = P.x_mid; e.ld = P.H;
+        is_gemm = true;
+        break;
+    }
+    case FN_GATEUP: {
+        const int f0 = t.c0 * 8;
+        g.rowsA = (const uint16_t *)W->wg + (size_t)f0 * P.H;
+        g.rowsB = (const uint16_t *)W->wu + (size_t)f0 * P.H;
+        g.ldw = P.H; g.K = P.H;
+        g.xf = P.x_mid; g.gain = (const uint16_t *)W->g2; g.eps = P.eps; g.ldx = P.H;
+        g.n_cols = P.B;
+        e.kind = EPI_SWIGLU; e.layer = t.layer; e.row0 = f0; e.outb = P.act; e.ld = P.F;
+        is_gemm = true;
+        break;
+    }
+    case FN_DOWN: {
+        const int r0 = t.c0 * 16;
+        g.rowsA = (const uint16_t *)W->wd + (size_t)r0 * P.F;
+        g.rowsB = g.rowsA + (size_t)8 * P.F;
+        g.ldw = P.F; g.K = P.F;
+        g.xb = P.act; g.ldxb = P.F;
+        g.n_cols = P.B;
+        e.kind = EPI_RESID; e.layer = t.layer; e.row0 = r0; e.resid = P.x_mid; e.outf = P.x; e.ld = P.H;
+        e.flags = (uint16_t)((t.flags & TF_LAST_LAYER) | ((P.debug_flags & 2u) ? EPF_DUMP_LAYER : 0));
+        is_gemm = true;
+        break;
+    }
+    default:
+        break;
+    }
+    if (is_gemm) gemm_tile_dispatch(P, g, e, tw, sm);
+}
+
+__device__ __forceinline__ Task load_task(const Task *p)
+{
+    // the queue is read-only for the whole launch; every lane reads the same record
+    const u32x4 *q = reinterpret_cast<const u32x4 *>(p);
+    u32x4 a = q[0], b = q[1];
+    Task t;
+    uint32_t w0 = __builtin_amdgcn_readfirstlane(a.x);
+    t.fn = (uint8_t)(w0 & 0xFF);
+    t.layer = (uint8_t)((w0 >> 8) & 0xFF);
+    t.flags = (uint16_t)(w0 >> 16);
+    t.c0 = __builtin_amdgcn_readfirstlane(a.y);
+    t.c1 = __builtin_amdgcn_readfirstlane(a.z);
+    t.c2 = __builtin_amdgcn_readfirstlane(a.w);
+    t.wait0 = __builtin_amdgcn_readfirstlane(b.x);
+    t.wait1 = __builtin_amdgcn_readfirstlane(b.y);
+    t.notify0 = __builtin_amdgcn_readfirstlane(b.z);
+    t.id = __builtin_amdgcn_readfirstlane(b.w);
+    return t;
+}
+
+// Re-arms the event tensors of the NEXT launch from the initial counts; nothing in this launch
+// touches that buffer, and the next launch starts after this kernel has ended.
+__device__ __forceinline__ void rearm_next(const Params &P)
+{
+    for (int i = blockIdx.x * kWgThreads + threadIdx.x; i < P.n_events; i += gridDim.x * kWgThreads)
+        P.ev_next[i] = P.ev_init[i];
+}
+
+__global__ void __launch_bounds__(kWgThreads) megakernel_static(const Params P)
+{
+    extern __shared__ float sm[];
+    rearm_next(P);
+    const int q0 = P.queue_begin[blockIdx.x], q1 = P.queue_begin[blockIdx.x + 1];
+    for (int i = q0; i < q1; ++i) {
+        const Task t = load_task(P.tasks + i);
+        run_task<true>(P, t, sm);
+        wg_release();
+        if (threadIdx.x == 0) {
+            if (t.notify0 >= 0) ev_notify(P, t.notify0);
+            if (P.debug_flags & 1u) atomicAdd(P.exec_count + t.id, 1);
+        }
+    }
+}
+
+// ---- dynamic scheduler ------------------------------------------------------------------------
+// Ready queue: q_slots[ticket] = (epoch << 32) | (task id + 1).  push: reserve tickets with an atomic
+// add on tail, then publish each slot; pop: take a ticket with an atomic add on head, then wait for
+// that slot to carry this launch's epoch.  Control words: head, tail, done, tasks completed, tasks
+// created at run time.  Completing the last task sets `done`, which releases the idle poppers.
+__device__ __forceinline__ void q_push(const Params &P, const int32_t *ids, int n)
+{
+    if (n <= 0) return;
+    const int base = __hip_atomic_fetch_add(P.q_ctrl_cur + 1, n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (base + n > P.q_capacity) { raise_error(P, ERR_QUEUE_OVERFLOW, 0, base); return; }
+    for (int i = 0; i < n; ++i)
+        __hip_atomic_store(P.q_slots + base + i, ((uint64_t)P.epoch << 32) | (uint64_t)(uint32_t)(ids[i] + 1),
+                           __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
+{
+    extern __shared__ float sm[];
+    __shared__ int s_task;
+    rearm_next(P);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {            // reset the control words of the next launch
+        for (int i = 0; i < 8; ++i) P.q_ctrl_next[i] = 0;
+    }
+    // seed: tasks without a trigger edge, spread over the workgroups
+    if (threadIdx.x == 0)
+        for (int i = blockIdx.x; i < P.n_seed; i += gridDim.x) q_push(P, P.seed_tasks + i, 1);
+    for (;;) {
+        if (threadIdx.x == 0) {
+            int id = -1;
+            const int ticket = __hip_atomic_fetch_add(P.q_ctrl_cur + 0, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (ticket < P.q_capacity) {
+                long long spins = 0;
+                for (;;) {
+                    const uint64_t v = __hip_atomic_load(P.q_slots + ticket, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+                    if ((uint32_t)(v >> 32) == P.epoch) { id = (int)(uint32_t)v - 1; break; }
+                    if (ev_peek(P.q_ctrl_cur + 2) != 0 || ev_peek(P.error_word) != 0) break;
+                    __builtin_amdgcn_s_sleep(4);
+                    if (++spins > P.spin_budget) { raise_error(P, ERR_POP_TIMEOUT, 0, ticket); break; }
+                }
+            }
+            s_task = id;
+        }
+        __syncthreads();
+        const int id = s_task;
+        __syncthreads();
+        if (id < 0) break;
+        const Task t = load_task(P.dyn_tasks + id);
+        run_task<true>(P, t, sm);      // early push (App. E): remaining in-edges are still waited on
+        wg_release();
+        if (threadIdx.x == 0) {
+            if (P.debug_flags & 1u) atomicAdd(P.exec_count + t.id, 1);
+            if (t.notify0 >= 0) {
+                if (ev_notify(P, t.notify0) == 1) {     // this notify fired the event: push its consumers
+                    const int c0 = P.ev_consumers[t.notify0], c1 = P.ev_consumers[t.notify0 + 1];
+                    q_push(P, P.consumer_ids + c0, c1 - c0);
+                }
+            }
+            // termination: the workgroup that completes the last task of the step releases the idle poppers
+            const int n_done = __hip_atomic_fetch_add(P.q_ctrl_cur + 3, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
+            if (n_done == P.n_static_tasks + ev_peek(P.q_ctrl_cur + 4))
+                __hip_atomic_store(P.q_ctrl_cur + 2, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// One operator stage as an ordinary kernel: block i runs task first + i, no events.
+__global__ void __launch_bounds__(kWgThreads) stage_kernel(const Params P, int first)
+{
+    extern __shared__ float sm[];
+    const Task t = load_task(P.dyn_tasks + first + blockIdx.x);
+    run_task<false>(P, t, sm);
+}
+
+}  // namespace etc
+
+// ---------------------------------------------------------------------------------------------
+// host-side launch helpers (called from api.cpp)
+// ---------------------------------------------------------------------------------------------
+namespace etc {
+
+hipError_t configure_kernels()
+{
+    hipError_t e = hipFuncSetAttribute((const void *)megakernel_static, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void *)megakernel_dynamic, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute((const void *)stage_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+}
+
+hipError_t max_resident_workgroups(int *per_cu)
+{
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, (const void *)megakernel_static, kWgThreads, kLdsBytes);
+}
+
+hipError_t launch_static(const Params &P, hipStream_t s)
+{
+    hipLaunchKernelGGL(megakernel_static, dim3(P.n_queues), dim3(kWgThreads), kLdsBytes, s, P);
+    return hipGetLastError();
+}
+
+hipError_t launch_dynamic(const Params &P, hipStream_t s)
+{
+    hipLaunchKernelGGL(megakernel_dynamic, dim3(P.n_queues), dim3(kWgThreads), kLdsBytes, s, P);
+    return hipGetLastError();
+}
+
+hipError_t launch_stage(const Params &P, int first, int count, hipStream_t s)
+{
+    if (count <= 0) return hipSuccess;
+    hipLaunchKernelGGL(stage_kernel, dim3(count), dim3(kWgThreads), kLdsBytes, s, P, first);
+    return hipGetLastError();
+}
+
+}  // namespace etc

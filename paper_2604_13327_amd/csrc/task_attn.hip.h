@@ -1,0 +1,152 @@
+// Paged decode attention as two task kinds (split-KV):
+//   attn_chunk  (sequence b, kv head, chunk): online-softmax partial (m, l, o) of the group's query
+//               heads over the chunk's keys, K/V rows gathered through the page table;
+//   attn_merge  (sequence b, kv head): combines the chunk partials in ascending chunk order.
+// Head dim D is split 8 elements per lane (16-byte loads of a bf16 K or V row slice), so D/8 lanes
+// cover one key and a wavefront covers 64/(D/8) keys per load instruction; the 8 wavefronts of the
+// workgroup stride over the chunk.  Reductions are wavefront shuffles, then LDS across waves.
+#pragma once
+#include "device_rt.hip.h"
+
+namespace etc {
+
+template <int D, int GRP>
+__device__ __forceinline__ void attn_chunk(const Params &P, int layer, int b, int kvh, int ch, float *sm)
+{
+    constexpr int LPT = D / 8;        // lanes per key
+    constexpr int TPW = 64 / LPT;     // keys per wavefront step
+    const int wave = wave_id(), lane = lane_id();
+    const int tq = lane / LPT, dl = lane % LPT;
+    const int n_keys = P.kv_len[b] + 1;
+    const int j0 = ch * P.kv_chunk;
+    const int j1 = min(n_keys, j0 + P.kv_chunk);
+    const int32_t *pages = P.page_ids + P.page_indptr[b];
+    const size_t lbase = (size_t)layer * (size_t)P.pool_layer_stride;
+    const float qscale = 1.0f / sqrtf((float)D);
+
+    float q[GRP][8];
+#pragma unroll
+    for (int g = 0; g < GRP; ++g) {
+        const float *qp = P.qbuf + (size_t)b * (size_t)(P.nq * D) + (size_t)(kvh * GRP + g) * D + dl * 8;
+        f32x4 a = *reinterpret_cast<const f32x4 *>(qp), c = *reinterpret_cast<const f32x4 *>(qp + 4);
+        q[g][0] = a.x * qscale; q[g][1] = a.y * qscale; q[g][2] = a.z * qscale; q[g][3] = a.w * qscale;
+        q[g][4] = c.x * qscale; q[g][5] = c.y * qscale; q[g][6] = c.z * qscale; q[g][7] = c.w * qscale;
+    }
+    float mx[GRP], l[GRP], o[GRP][8];
+#pragma unroll
+    for (int g = 0; g < GRP; ++g) {
+        mx[g] = -INFINITY;
+        l[g] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[g][i] = 0.f;
+    }
+
+    for (int jb = j0 + wave * TPW; jb < j1; jb += kWaves * TPW) {   // uniform trip count per wave
+        const int j = jb + tq;
+        const bool valid = j < j1;
+        const int jc = valid ? j : j1 - 1;
+        const int page = pages[jc / P.page];
+        const size_t off = lbase + (((size_t)page * P.page + (size_t)(jc % P.page)) * P.nkv + kvh) * (size_t)D + dl * 8;
+        const u32x4 kr = *reinterpret_cast<const u32x4 *>(P.kpool + off);
+        const u32x4 vr = *reinterpret_cast<const u32x4 *>(P.vpool + off);
+        float kf[8], vf[8];
+        kf[0] = bf16_bits_to_f32(kr.x & 0xFFFFu); kf[1] = bf16_bits_to_f32(kr.x >> 16);
+        kf[2] = bf16_bits_to_f32(kr.y & 0xFFFFu); kf[3] = bf16_bits_to_f32(kr.y >> 16);
+        kf[4] = bf16_bits_to_f32(kr.z & 0xFFFFu); kf[5] = bf16_bits_to_f32(kr.z >> 16);
+        kf[6] = bf16_bits_to_f32(kr.w & 0xFFFFu); kf[7] = bf16_bits_to_f32(kr.w >> 16);
+        vf[0] = bf16_bits_to_f32(vr.x & 0xFFFFu); vf[1] = bf16_bits_to_f32(vr.x >> 16);
+        vf[2] = bf16_bits_to_f32(vr.y & 0xFFFFu); vf[3] = bf16_bits_to_f32(vr.y >> 16);
+        vf[4] = bf16_bits_to_f32(vr.z & 0xFFFFu); vf[5] = bf16_bits_to_f32(vr.z >> 16);
+        vf[6] = bf16_bits_to_f32(vr.w & 0xFFFFu); vf[7] = bf16_bits_to_f32(vr.w >> 16);
+#pragma unroll
+        for (int g = 0; g < GRP; ++g) {
+            float s = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) s += q[g][i] * kf[i];
+#pragma unroll
+            for (int off2 = 1; off2 < LPT; off2 <<= 1) s += __shfl_xor(s, off2, 64);
+            if (valid) {
+                const float nm = fmaxf(mx[g], s);
+                const float sc = __expf(mx[g] - nm);      // exp(-inf) = 0 on the first key
+                const float p = __expf(s - nm);
+                l[g] = l[g] * sc + p;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) o[g][i] = o[g][i] * sc + p * vf[i];
+                mx[g] = nm;
+            }
+        }
+    }
+
+    // merge the TPW key groups of the wavefront (lanes differing in tq)
+#pragma unroll
+    for (int off2 = LPT; off2 < 64; off2 <<= 1) {
+#pragma unroll
+        for (int g = 0; g < GRP; ++g) {
+            const float om = __shfl_xor(mx[g], off2, 64), ol = __shfl_xor(l[g], off2, 64);
+            const float nm = fmaxf(mx[g], om);
+            const float sa = (mx[g] == -INFINITY) ? 0.f : __expf(mx[g] - nm);
+            const float sb = (om == -INFINITY) ? 0.f : __expf(om - nm);
+            l[g] = l[g] * sa + ol * sb;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float oo = __shfl_xor(o[g][i], off2, 64);
+                o[g][i] = o[g][i] * sa + oo * sb;
+            }
+            mx[g] = nm;
+        }
+    }
+    // across wavefronts through LDS: [wave][g] -> m, l, o[D]
+    float *s_m = sm;                                 // [kWaves][GRP]
+    float *s_l = sm + kWaves * GRP;                  // [kWaves][GRP]
+    float *s_o = sm + 2 * kWaves * GRP;              // [kWaves][GRP][D]
+    if (tq == 0) {
+#pragma unroll
+        for (int g = 0; g < GRP; ++g) {
+            if (dl == 0) { s_m[wave * GRP + g] = mx[g]; s_l[wave * GRP + g] = l[g]; }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) s_o[(size_t)(wave * GRP + g) * D + dl * 8 + i] = o[g][i];
+        }
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < GRP * D; idx += kWgThreads) {
+        const int g = idx / D, i = idx % D;
+        float m = -INFINITY;
+#pragma unroll
+        for (int wv = 0; wv < kWaves; ++wv) m = fmaxf(m, s_m[wv * GRP + g]);
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int wv = 0; wv < kWaves; ++wv) {
+            const float wm = s_m[wv * GRP + g];
+            const float sc = (wm == -INFINITY) ? 0.f : __expf(wm - m);
+            num += sc * s_o[(size_t)(wv * GRP + g) * D + i];
+            den += sc * s_l[wv * GRP + g];
+        }
+        const int h = kvh * GRP + g;
+        const size_t pidx = ((size_t)b * P.nq + h) * (size_t)P.max_chunks + ch;
+        P.part_o[pidx * D + i] = num;
+        if (i == 0) { P.part_m[pidx] = m; P.part_l[pidx] = den; }
+    }
+}
+
+template <int D, int GRP>
+__device__ __forceinline__ void attn_merge(const Params &P, int b, int kvh)
+{
+    const int n_keys = P.kv_len[b] + 1;
+    const int nc = (n_keys + P.kv_chunk - 1) / P.kv_chunk;
+    for (int idx = threadIdx.x; idx < GRP * D; idx += kWgThreads) {
+        const int g = idx / D, i = idx % D;
+        const int h = kvh * GRP + g;
+        const size_t p0 = ((size_t)b * P.nq + h) * (size_t)P.max_chunks;
+        float m = -INFINITY;
+        for (int c = 0; c < nc; ++c) m = fmaxf(m, P.part_m[p0 + c]);
+        float num = 0.f, den = 0.f;
+        for (int c = 0; c < nc; ++c) {                 // ascending chunk order
+            const float sc = __expf(P.part_m[p0 + c] - m);
+            num += sc * P.part_o[(p0 + c) * D + i];
+            den += sc * P.part_l[p0 + c];
+        }
+        P.attn[(size_t)b * (size_t)(P.nq * D) + (size_t)h * D + i] = f32_to_bf16_bits(num / den);
+    }
+}
+
+}  // namespace etc

@@ -1,0 +1,220 @@
+"""GPU parity tests: the HIP megakernel, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Floating point bar: max|err| <= 2e-2 * RMS(oracle output), per layer and final.
+Integer work (task execution counts, event counters) is bit-exact."""
+import numpy as np
+import pytest
+
+import synth
+from harness import GpuModel, bf16_to_f32_np, fixed_step, oracle_step, rel_err
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+def _etc():
+    import paper_2604_13327_amd as etc
+    return etc
+
+
+def _run(dec, model, step, step_index=0, kbk=False):
+    import torch
+    x = model.hidden(step_index, step.batch)
+    out = torch.empty_like(x)
+    dec.bind_step(step)
+    (dec.launch_kernel_by_kernel if kbk else dec.launch)(x, out)
+    torch.cuda.synchronize()
+    return bf16_to_f32_np(out)
+
+
+def _check_invariants(dec):
+    assert (dec.error_word() == 0).all(), dec.error_word()
+    assert (dec.event_counters() == 0).all(), "an event counter did not drain to zero"
+    assert (dec.exec_counts() == 1).all(), "a task did not run exactly once"
+
+
+# ---------------------------------------------------------------- row-sum example (paper Sec. 2.2)
+def _rowsum_graph(etc, kind):
+    from paper_2604_13327_amd import binding as b
+    g = etc.EventGraph(kind=kind, debug_flags=etc.DEBUG_EXEC_COUNT)
+    n = g.dim(sym=0, mul=1, add=0)
+    ev = g.add_event([n])                                                     # E[i], i < n (symbolic)
+    g.add_call(b.FN_ROWSUM_PARTIAL, [n, g.dim(add=4)], out_edges=[g.edge(ev, [(b.MAP_DIM, 0, 1)])])
+    g.add_call(b.FN_ROWSUM_FINAL, [n], in_edges=[g.edge(ev, [(b.MAP_DIM, 0, 1)])])
+    return g
+
+
+@pytest.mark.parametrize("kind", [0, 1, 2])
+def test_rowsum_graph_symbolic_n(kind):
+    import torch
+    etc = _etc()
+    g = _rowsum_graph(etc, kind)
+    rng = np.random.default_rng(0)
+    for n in (1, 2, 37):                       # one template, three instantiations, no rebuild of the context
+        A = rng.integers(-8, 9, size=(n * 32, 128)).astype(np.float32)
+        dA = torch.from_numpy(A).cuda()
+        dB = torch.full((n * 32, 4), float("nan"), device="cuda")
+        dC = torch.full((n * 32,), float("nan"), device="cuda")
+        for slot, t in enumerate((dA, dB, dC)):
+            g.bind_buffer(slot, t)
+        g.bind_shape([n])
+        for rep in range(2):                   # second launch runs on the re-armed event tensor
+            dC.fill_(float("nan"))
+            g.launch()
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(dC.cpu().numpy(), A.astype(np.float64).sum(1))
+            assert (g.event_counters() == 0).all()
+        info = g.step_info()
+        assert info.n_tasks == 5 * n and info.n_events == (n if kind != 2 else 2)
+        assert (g.exec_counts() == 2).all()
+    # undersized buffer is refused on the host
+    g.bind_shape([64])
+    with pytest.raises(etc.EtcError):
+        g.launch()
+    g.close()
+
+
+# ---------------------------------------------------------------- config 1: tiny 2-layer decoder
+@pytest.fixture(scope="module")
+def tiny_model():
+    return GpuModel(synth.TINY, seed=11, n_pool_pages=160)
+
+
+@pytest.mark.parametrize("kind", [0, 1, 2])
+def test_tiny_decoder_matches_oracle_per_layer(tiny_model, kind):
+    etc = _etc()
+    s = synth.TINY
+    tiny_model.reset_pools()
+    step = fixed_step(s, 1, [128], tiny_model.n_pool_pages, seed=3)
+    dec = etc.Decoder(s, kv_chunk_tokens=32, sampled_batches=[1], max_kv_len=129, kind=kind,
+                      debug_flags=etc.DEBUG_EXEC_COUNT | etc.DEBUG_LAYER_HIDDEN)
+    tiny_model.bind(dec)
+    out = _run(dec, tiny_model, step)
+    _check_invariants(dec)
+    ref = oracle_step(s, tiny_model.seed, tiny_model.n_pool_pages, step, 0)
+    for l in range(s.n_layers):
+        assert rel_err(dec.layer_hidden(l), ref["layers"][l]) <= TOL, f"layer {l}"
+    assert rel_err(out, ref["final"]) <= TOL
+    dec.close()
+
+
+def test_tiny_kv_append_lands_in_the_right_slot(tiny_model):
+    import torch
+    etc = _etc()
+    s = synth.TINY
+    tiny_model.reset_pools()
+    before_k = tiny_model.kpool.clone()
+    step = fixed_step(s, 1, [37], tiny_model.n_pool_pages, seed=5)
+    dec = etc.Decoder(s, kv_chunk_tokens=16, sampled_batches=[1], max_kv_len=129)
+    tiny_model.bind(dec)
+    _run(dec, tiny_model, step)
+    changed = (tiny_model.kpool != before_k).any(dim=-1).any(dim=-1)          # [layer, page, slot]
+    page, slot = int(step.page_ids[37 // s.page]), 37 % s.page
+    exp = torch.zeros_like(changed)
+    exp[:, page, slot] = True
+    assert torch.equal(changed, exp)
+    # appended K row equals the oracle's rotated key (bf16 rounding only)
+    import oracle
+    w = synth.layer_weights_f32(s, tiny_model.seed, 0)
+    kp, vp = synth.kv_pool_f32(s, tiny_model.seed, 0, tiny_model.n_pool_pages)
+    x = synth.hidden_f32(s, tiny_model.seed, 0, 1)
+    _, dbg = oracle.layer(oracle.shape_of(s), x.copy(), w, kp, vp, step.kv_len, step.page_indptr, step.page_ids, debug=True)
+    got = bf16_to_f32_np(tiny_model.kpool[0, page, slot]).ravel()
+    assert rel_err(got, dbg["k_rot"][0]) <= TOL
+    gotv = bf16_to_f32_np(tiny_model.vpool[0, page, slot]).ravel()
+    assert rel_err(gotv, dbg["v_new"][0]) <= TOL
+    dec.close()
+
+
+def test_tiny_all_schedulers_and_kernel_by_kernel_agree_bitwise(tiny_model):
+    """Identical task bodies, different scheduling: the results must be identical (paper Sec. 4.5)."""
+    etc = _etc()
+    s = synth.TINY
+    step = fixed_step(s, 3, [100, 7, 64], tiny_model.n_pool_pages, seed=9)
+    outs = []
+    for kind in (0, 1, 2):
+        tiny_model.reset_pools()
+        dec = etc.Decoder(s, kv_chunk_tokens=32, sampled_batches=[1, 4], max_kv_len=129, kind=kind,
+                          debug_flags=etc.DEBUG_EXEC_COUNT)
+        tiny_model.bind(dec)
+        outs.append(_run(dec, tiny_model, step))
+        _check_invariants(dec)
+        assert dec.step_info().sampled_batch == 4          # B = 3 runs on the queues sampled for B = 4
+        if kind == 0:
+            tiny_model.reset_pools()
+            outs.append(_run(dec, tiny_model, step, kbk=True))
+        dec.close()
+    for o in outs[1:]:
+        np.testing.assert_array_equal(o, outs[0])
+    tiny_model.reset_pools()
+    ref = oracle_step(s, tiny_model.seed, tiny_model.n_pool_pages, step, 0)
+    assert rel_err(outs[0], ref["final"]) <= TOL
+
+
+def test_tiny_shape_dynamism_without_recreate(tiny_model):
+    """One context, steps with different batch sizes and ragged lengths (Sec. 2.3), launched repeatedly."""
+    etc = _etc()
+    s = synth.TINY
+    dec = etc.Decoder(s, kv_chunk_tokens=16, sampled_batches=[1, 4, 16], max_kv_len=129,
+                      debug_flags=etc.DEBUG_EXEC_COUNT)
+    tiny_model.bind(dec)
+    rng = np.random.default_rng(21)
+    for i in range(6):
+        tiny_model.reset_pools()
+        step = synth.draw_step(rng, s, [1, 2, 4, 9, 16], 0, 128, tiny_model.n_pool_pages)
+        out = _run(dec, tiny_model, step, step_index=i)
+        _check_invariants(dec)
+        tiny_model.reset_pools()
+        ref = oracle_step(s, tiny_model.seed, tiny_model.n_pool_pages, step, i)
+        assert rel_err(out, ref["final"]) <= TOL, f"step {i} batch {step.batch}"
+    dec.close()
+
+
+def test_edge_cases_and_error_paths(tiny_model):
+    etc = _etc()
+    s = synth.TINY
+    dec = etc.Decoder(s, kv_chunk_tokens=32, sampled_batches=[2], max_kv_len=129)
+    tiny_model.bind(dec)
+    tiny_model.reset_pools()
+    # empty cache (kv_len 0: attention over the new token only) and the maximum length
+    step = fixed_step(s, 2, [0, 128], tiny_model.n_pool_pages, seed=1)
+    out = _run(dec, tiny_model, step)
+    tiny_model.reset_pools()
+    ref = oracle_step(s, tiny_model.seed, tiny_model.n_pool_pages, step, 0)
+    assert rel_err(out, ref["final"]) <= TOL
+    # invalid binds are refused on the host, never reach the device
+    bad = fixed_step(s, 2, [0, 128], tiny_model.n_pool_pages, seed=1)
+    bad.page_ids = bad.page_ids.copy()
+    bad.page_ids[0] = tiny_model.n_pool_pages            # outside the pool
+    with pytest.raises(etc.EtcError):
+        dec.bind_step(bad)
+    with pytest.raises(etc.EtcError):
+        dec.bind_step(fixed_step(s, 1, [129], tiny_model.n_pool_pages, seed=1))   # longer than max_kv_len
+    with pytest.raises(etc.EtcError):
+        dec.bind_step(fixed_step(s, 3, [1, 1, 1], tiny_model.n_pool_pages, seed=1))  # batch above max_batch
+    dec.close()
+
+
+def test_watchdog_turns_a_stuck_wait_into_an_error():
+    """A wait that can never be satisfied must drain with ETC_ETIMEOUT instead of hanging.  Forced from
+    the host: with a single queue the consumer launch is listed ahead of its producers, so the head task
+    waits on an event that cannot fire before it gives up; the spin budget is tiny, so it gives up at once."""
+    import torch
+    etc = _etc()
+    from paper_2604_13327_amd import binding as b
+    g = etc.EventGraph(kind=0, spin_budget=2000, n_queues=1)
+    n = g.dim(sym=0, mul=1, add=0)
+    ev = g.add_event([g.dim(add=1)])
+    g.add_call(b.FN_ROWSUM_FINAL, [n], in_edges=[g.edge(ev, [(b.MAP_CONST, 0, 0)])])
+    g.add_call(b.FN_ROWSUM_PARTIAL, [n, g.dim(add=4)], out_edges=[g.edge(ev, [(b.MAP_CONST, 0, 0)])])
+    A = torch.zeros(32, 128, device="cuda")
+    Bm = torch.zeros(32, 4, device="cuda")
+    Cm = torch.zeros(32, device="cuda")
+    for slot, t in enumerate((A, Bm, Cm)):
+        g.bind_buffer(slot, t)
+    g.bind_shape([1])
+    g.launch()
+    torch.cuda.synchronize()                   # returns: the kernel drained
+    with pytest.raises(etc.EtcError) as ei:
+        g.event_counters()
+    assert ei.value.status == -5
+    g.close()

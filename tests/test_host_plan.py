@@ -1,0 +1,159 @@
+"""CPU-only checks of the library's host side: the shared library loads and exports every symbol the
+header declares, and the scheduling transformation (graph instantiation, static queues, dynamic
+consumer table) yields plans that a brute-force executor with virtual CUs runs to completion:
+no deadlock, every task exactly once, every event counter drained to zero."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2604_13327_amd as etc
+import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+PER_WAVE = 1
+N_WAVES = 8
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "etc.h")).read()
+    declared = set(re.findall(r"\b(etc_[a-z_]+)\s*\(", header))
+    assert len(declared) >= 19
+    L = etc.lib()
+    for name in sorted(declared):
+        assert hasattr(L, name), f"{name} is declared in include/etc.h but not exported"
+    assert declared == set(etc.binding.EXPORTS)
+
+
+def _waits(t):
+    if t["wait0"] >= 0:
+        if t["flags"] & PER_WAVE:
+            yield from range(t["wait0"], t["wait0"] + N_WAVES)
+        else:
+            yield int(t["wait0"])
+    if t["wait1"] >= 0:
+        yield int(t["wait1"])
+
+
+def run_static(plan, rng):
+    """Virtual CUs walk their queues in order, spinning on the head task's events."""
+    ev = plan["ev_init"].astype(np.int64).copy()
+    qb, qt = plan["queue_begin"], plan["queue_tasks"]
+    head = qb[:-1].astype(np.int64).copy()
+    done = np.zeros(len(plan["tasks"]), np.int64)
+    live = [q for q in range(len(head)) if head[q] < qb[q + 1]]
+    while live:
+        runnable = [q for q in live if all(ev[e] == 0 for e in _waits(qt[head[q]]))]
+        assert runnable, "deadlock: every queue head waits on an unfired event"
+        for q in rng.permutation(runnable)[: max(1, len(runnable) // 2)]:
+            t = qt[head[q]]
+            done[t["id"]] += 1
+            if t["notify0"] >= 0:
+                ev[t["notify0"]] -= 1
+                assert ev[t["notify0"]] >= 0
+            head[q] += 1
+        live = [q for q in live if head[q] < qb[q + 1]]
+    return ev, done
+
+
+def run_dynamic(plan, n_workers, rng):
+    """Central ready queue: push on zero, pop when idle; a popped task still waits for its other events."""
+    ev = plan["ev_init"].astype(np.int64).copy()
+    tasks = plan["tasks"]
+    done = np.zeros(len(tasks), np.int64)
+    queue = list(plan["seed_tasks"])
+    workers = [None] * n_workers
+    while True:
+        for w in range(n_workers):
+            if workers[w] is None and queue:
+                workers[w] = queue.pop(0)
+        busy = [w for w in range(n_workers) if workers[w] is not None]
+        if not busy:
+            break
+        runnable = [w for w in busy if all(ev[e] == 0 for e in _waits(tasks[workers[w]]))]
+        assert runnable, "deadlock in the dynamic protocol"
+        w = int(rng.choice(runnable))
+        t = tasks[workers[w]]
+        done[t["id"]] += 1
+        workers[w] = None
+        n = int(t["notify0"])
+        if n >= 0:
+            ev[n] -= 1
+            if ev[n] == 0:
+                queue.extend(plan["consumer_ids"][plan["ev_consumers"][n]:plan["ev_consumers"][n + 1]].tolist())
+    return ev, done
+
+
+@pytest.mark.parametrize("kind", [etc.SCHED_STATIC, etc.SCHED_UNFUSED])
+@pytest.mark.parametrize("batch,nq", [(1, 5), (4, 16), (3, 256)])
+def test_static_plans_run_to_completion(kind, batch, nq):
+    plan = etc.plan_build(synth.TINY, 32, batch, nq, max_kv_len=129, kind=kind)
+    ev, done = run_static(plan, np.random.default_rng(batch * 7 + nq))
+    assert (ev == 0).all() and (done == 1).all()
+    # each queue is ordered by task id: a subsequence of one topological order
+    qb, qt = plan["queue_begin"], plan["queue_tasks"]
+    for q in range(nq):
+        ids = qt["id"][qb[q]:qb[q + 1]]
+        assert (np.diff(ids) > 0).all()
+    # round-robin: queue sizes differ by at most one
+    sizes = np.diff(qb)
+    assert sizes.max() - sizes.min() <= 1
+
+
+def test_dynamic_plan_runs_to_completion():
+    plan = etc.plan_build(synth.TINY, 32, 2, 4, max_kv_len=129, kind=etc.SCHED_DYNAMIC)
+    for nw in (1, 3, 16):
+        ev, done = run_dynamic(plan, nw, np.random.default_rng(nw))
+        assert (ev == 0).all() and (done == 1).all()
+    # every task is either a seed or the consumer of exactly one event
+    ids = np.concatenate([plan["seed_tasks"], plan["consumer_ids"]])
+    assert sorted(ids.tolist()) == list(range(len(plan["tasks"])))
+
+
+def test_event_counts_follow_the_graph():
+    s = synth.TINY                      # nq 4, nkv 2, d 64, H 256, F 1024
+    B, chunk, max_kv = 2, 32, 129
+    plan = etc.plan_build(s, chunk, B, 8, max_kv_len=max_kv)
+    tasks, ev = plan["tasks"], plan["ev_init"]
+    n_chunks = -(-max_kv // chunk)
+    FN_QKV, FN_ATTN, FN_MERGE, FN_OPROJ, FN_GATEUP, FN_DOWN = 4, 5, 6, 7, 8, 9
+    per_layer = {FN_QKV: (s.nq + 2 * s.nkv) * (s.d // 16), FN_ATTN: B * s.nkv * n_chunks, FN_MERGE: B * s.nkv,
+                 FN_OPROJ: s.H // 16, FN_GATEUP: s.F // 8, FN_DOWN: s.H // 16}
+    for fn, n in per_layer.items():
+        assert (tasks["fn"] == fn).sum() == n * s.n_layers
+    assert len(tasks) == B + s.n_layers * sum(per_layer.values())
+    # an attention task of kv head h waits on the event fed by (group + 2) heads x d/16 row tiles
+    attn0 = tasks[(tasks["fn"] == FN_ATTN) & (tasks["layer"] == 0)][0]
+    assert ev[attn0["wait0"]] == (s.nq // s.nkv + 2) * (s.d // 16)
+    merge0 = tasks[(tasks["fn"] == FN_MERGE) & (tasks["layer"] == 0)][0]
+    assert ev[merge0["wait0"]] == n_chunks                      # shape-dependent count (chunk slots)
+    down0 = tasks[(tasks["fn"] == FN_DOWN) & (tasks["layer"] == 0)][0]
+    assert down0["flags"] & PER_WAVE
+    assert all(ev[down0["wait0"] + w] == (s.F // 8) // N_WAVES for w in range(N_WAVES))
+    qkv1 = tasks[(tasks["fn"] == FN_QKV) & (tasks["layer"] == 1)][0]
+    assert ev[qkv1["wait0"]] == s.H // 16                       # all down tiles of layer 0
+    assert ev[plan["tasks"][(tasks["fn"] == FN_QKV) & (tasks["layer"] == 0)][0]["wait0"]] == B   # hidden loads
+
+
+def test_unfused_plan_has_one_event_per_stage():
+    plan = etc.plan_build(synth.TINY, 32, 1, 8, max_kv_len=129, kind=etc.SCHED_UNFUSED)
+    # prologue + per layer: qkv, attn, merge, oproj, gateup, down
+    assert len(plan["ev_init"]) == 1 + 6 * synth.TINY.n_layers
+    assert not (plan["tasks"]["flags"] & PER_WAVE).any()
+
+
+def test_llama8b_plan_shape():
+    s = synth.LLAMA3_8B
+    plan = etc.plan_build(s, 64, 1, 256, max_kv_len=1025)
+    per_layer = 384 + 8 * 17 + 8 + 256 + 1792 + 256
+    assert len(plan["tasks"]) == 1 + 32 * per_layer
+    sizes = np.diff(plan["queue_begin"])
+    assert sizes.max() - sizes.min() <= 1
+
+
+def test_descriptor_validation_errors_are_reported():
+    bad = synth.ModelShape("bad", 1, 200, 4, 2, 64, 1024)       # hidden not a multiple of 256
+    with pytest.raises(etc.EtcError) as ei:
+        etc.plan_build(bad, 32, 1, 4, max_kv_len=64)
+    assert ei.value.status == -1 and "256" in str(ei.value)

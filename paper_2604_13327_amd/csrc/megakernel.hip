@@ -180,7 +180,7 @@ __device__ __forceinline__ void rearm_next(const Params &P)
 
 __global__ void __launch_bounds__(kWgThreads) megakernel_static(const Params P)
 {
-    extern __shared__ float sm[];
+    extern __shared__ __attribute__((aligned(16))) float sm[];
     rearm_next(P);
     const int q0 = P.queue_begin[blockIdx.x], q1 = P.queue_begin[blockIdx.x + 1];
     for (int i = q0; i < q1; ++i) {
@@ -211,7 +211,7 @@ __device__ __forceinline__ void q_push(const Params &P, const int32_t *ids, int 
 
 __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
 {
-    extern __shared__ float sm[];
+    extern __shared__ __attribute__((aligned(16))) float sm[];
     __shared__ int s_task;
     rearm_next(P);
     if (blockIdx.x == 0 && threadIdx.x == 0) {            // reset the control words of the next launch
@@ -225,14 +225,19 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
             int id = -1;
             const int ticket = __hip_atomic_fetch_add(P.q_ctrl_cur + 0, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (ticket < P.q_capacity) {
+                // Poll with relaxed device-scope loads and fence once after the slot is seen: an acquire
+                // load inside the loop would invalidate the L2 on every iteration on every idle CU.
                 long long spins = 0;
                 for (;;) {
-                    const uint64_t v = __hip_atomic_load(P.q_slots + ticket, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+                    const uint64_t v = __hip_atomic_load(P.q_slots + ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     if ((uint32_t)(v >> 32) == P.epoch) { id = (int)(uint32_t)v - 1; break; }
-                    if (ev_peek(P.q_ctrl_cur + 2) != 0 || ev_peek(P.error_word) != 0) break;
-                    __builtin_amdgcn_s_sleep(4);
-                    if (++spins > P.spin_budget) { raise_error(P, ERR_POP_TIMEOUT, 0, ticket); break; }
+                    if (ev_peek(P.q_ctrl_cur + 2) != 0) break;
+                    if (spins < 32) __builtin_amdgcn_s_sleep(2); else __builtin_amdgcn_s_sleep(32);
+                    ++spins;
+                    if ((spins & 63) == 0 && ev_peek(P.error_word) != 0) break;
+                    if (spins > P.spin_budget) { raise_error(P, ERR_POP_TIMEOUT, 0, ticket); break; }
                 }
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
             }
             s_task = id;
         }
@@ -262,7 +267,7 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
 // One operator stage as an ordinary kernel: block i runs task first + i, no events.
 __global__ void __launch_bounds__(kWgThreads) stage_kernel(const Params P, int first)
 {
-    extern __shared__ float sm[];
+    extern __shared__ __attribute__((aligned(16))) float sm[];
     const Task t = load_task(P.dyn_tasks + first + blockIdx.x);
     run_task<false>(P, t, sm);
 }

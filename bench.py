@@ -1,0 +1,159 @@
+#!/usr/bin/env python3
+"""Decode-step benchmark of the event-tensor megakernel on one MI355X.
+
+Workload (the configuration the headline metric is quoted on): Llama-3-8B-shaped decoder, 32 layers,
+random-init bf16 weights, batch 1, 1024 cached tokens in 16-token pages behind a random permuted page
+table, LM head excluded.  One step = one launch of the persistent megakernel = the whole hot path.
+Prints ONE JSON line (see the keys below); inputs are resident in HBM before the timed region.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBS = 8000.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="llama3-8b", help="llama3-8b (headline) | tiny")
+    ap.add_argument("--sched", default="static", choices=["static", "unfused"])
+    ap.add_argument("--kv-len", type=int, default=1024)
+    ap.add_argument("--batch", type=int, default=1)
+    ap.add_argument("--kv-chunk", type=int, default=64)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-comparators", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=0, help="layers the CPU oracle runs (0 = all)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures the one-GPU path only (this build has no multi-GPU sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2604_13327_amd as etc
+    import synth
+    from harness import GpuModel, bf16_to_f32_np, fixed_step, rel_err
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    shape = synth.SHAPES[args.workload]
+    seed, B, L = 2024, args.batch, args.kv_len
+    n_pool = B * synth.pages_needed(L, shape.page) + 16
+
+    t0 = time.time()
+    model = GpuModel(shape, seed, n_pool)
+    torch.cuda.synchronize()
+    t_fill = time.time() - t0
+
+    # ---- warm-up in the paper's sense (Sec. 4.4): engine start to first step served, minus model load
+    t0 = time.time()
+    kind = etc.SCHED_STATIC if args.sched == "static" else etc.SCHED_UNFUSED
+    dec = etc.Decoder(shape, kv_chunk_tokens=args.kv_chunk, sampled_batches=[B], max_kv_len=L + 1, kind=kind)
+    model.bind(dec)
+    step = fixed_step(shape, B, [L] * B, n_pool, seed=7)
+    dec.bind_step(step)
+    x = model.hidden(0, B)
+    out = torch.empty_like(x)
+    dec.launch(x, out)
+    torch.cuda.synchronize()
+    t_warmup = time.time() - t0
+    first_out = bf16_to_f32_np(out)
+    info = dec.step_info()
+
+    def timed(launch, steps, warmup):
+        for _ in range(warmup):
+            launch(x, out)
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        t_a = time.perf_counter()
+        for a, b in ev:
+            a.record()
+            launch(x, out)
+            b.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t_a) / steps * 1e6
+        per = np.array([a.elapsed_time(b) * 1e3 for a, b in ev])          # us, device time per launch
+        span = ev[0][0].elapsed_time(ev[-1][1]) * 1e3 / steps              # us per step over the whole region
+        return per, span, wall
+
+    per, span, wall = timed(dec.launch, args.steps, args.warmup)
+    us = float(span)                       # whole timed region / K: what a serving loop would see
+    kern_us = float(per.mean())            # average device duration of the megakernel launch
+    alg = int(info.algorithmic_bytes)
+    achieved = alg / (kern_us * 1e-6) / 1e9
+
+    result = {
+        "metric": "decode_step_latency_us", "value": round(us, 2), "unit": "us", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(us / 1e3, 5),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{shape.name} decode, batch {B}, kv_len {L}, page 16, random page table, "
+                               f"{shape.n_layers} layers, LM head excluded",
+                   "scheduler": args.sched, "kv_chunk_tokens": args.kv_chunk,
+                   "tasks_per_step": int(info.n_tasks), "events_per_step": int(info.n_events),
+                   "persistent_workgroups": int(info.n_queues)},
+        "tokens_per_s": round(B / (us * 1e-6), 1),
+        "latency_us": {"median": round(float(np.median(per)), 2), "p10": round(float(np.percentile(per, 10)), 2),
+                       "p90": round(float(np.percentile(per, 90)), 2), "host_wall_per_step": round(wall, 2)},
+        "roofline": {"bound": "hbm", "kernel": "megakernel_static", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "algorithmic_bytes_per_launch": alg, "avg_launch_us": round(kern_us, 2), "traffic": None},
+        "warmup_s": {"create_bind_first_step": round(t_warmup, 3), "synthetic_weight_fill": round(t_fill, 3)},
+    }
+
+    # ---- comparators on identical task bodies -------------------------------------------------------
+    if not args.no_comparators:
+        k = max(5, min(20, args.steps))
+        per_kbk, span_kbk, _ = timed(dec.launch_kernel_by_kernel, k, 2)
+        result["kernel_by_kernel_us"] = round(float(span_kbk), 2)
+        result["launch_gap_removed_us"] = round(float(span_kbk) - us, 2)
+        if args.sched == "static":
+            un = etc.Decoder(shape, kv_chunk_tokens=args.kv_chunk, sampled_batches=[B], max_kv_len=L + 1,
+                             kind=etc.SCHED_UNFUSED)
+            model.bind(un)
+            un.bind_step(step)
+            _, span_un, _ = timed(un.launch, k, 2)
+            result["unfused_megakernel_us"] = round(float(span_un), 2)
+            result["speedup_vs_unfused"] = round(float(span_un) / us, 4)
+            un.close()
+
+    # ---- CPU oracle on the host cores: reported baseline + end-to-end parity of this very workload ----
+    if not args.no_cpu_baseline:
+        import oracle
+        n_l = args.cpu_layers if args.cpu_layers > 0 else shape.n_layers
+        xo = synth.hidden_f32(shape, seed, 0, B)
+        oshape = oracle.shape_of(shape)
+        t_orc = 0.0
+        for l in range(n_l):
+            w = synth.layer_weights_f32(shape, seed, l)
+            kp, vp = synth.kv_pool_f32(shape, seed, l, n_pool)
+            t1 = time.perf_counter()
+            oracle.layer(oshape, xo, w, kp, vp, step.kv_len, step.page_indptr, step.page_ids)
+            t_orc += time.perf_counter() - t1
+        scale = shape.n_layers / n_l
+        result["cpu_baseline"] = {"value": round(t_orc * scale * 1e6, 1), "unit": "us", "cores": oracle.n_threads(),
+                                  "kind": "oracle",
+                                  "sample": f"{n_l} of {shape.n_layers} layers of the same step, oracle compute only "
+                                            f"(input generation excluded), scaled x{scale:g}"}
+        if n_l == shape.n_layers:
+            result["parity_vs_oracle_final"] = round(rel_err(first_out, xo), 5)
+
+    dec.close()
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <string>
@@ -332,13 +333,24 @@ etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc
         if (e != hipSuccess) { c->err = std::string("device allocation failed: ") + hipGetErrorString(e); return false; }
         return true;
     };
-    bool okk = A(&P.x, MB * H) && A(&P.x_mid, MB * H) && A(&P.qbuf, MB * QD) && A(&P.attn, MB * QD) &&
-               A(&P.act, MB * (size_t)std::max(1, m->ffn)) &&
+    const size_t F1 = (size_t)std::max(1, m->ffn);
+    bool okk = A(&P.x, MB * H) && A(&P.x_mid, MB * H) && A(&P.qbuf, MB * QD) &&
+               A(&P.xg_hi, MB * H) && A(&P.xg_lo, MB * H) && A(&P.xmg_hi, MB * H) && A(&P.xmg_lo, MB * H) &&
+               A(&P.ssq_x, (H / 16) * (size_t)kMaxBatch) && A(&P.ssq_xmid, (H / 16) * (size_t)kMaxBatch) &&
+               A(&P.attn_hi, MB * QD) && A(&P.attn_lo, MB * QD) && A(&P.act_hi, MB * F1) && A(&P.act_lo, MB * F1) &&
                A(&P.part_m, MB * m->n_q_heads * (size_t)c->max_chunks) &&
                A(&P.part_l, MB * m->n_q_heads * (size_t)c->max_chunks) &&
                A(&P.part_o, MB * m->n_q_heads * (size_t)c->max_chunks * m->head_dim) &&
                A(&c->d_kv_len, MB) && A(&c->d_page_indptr, MB + 1) && A(&c->d_page_ids, MB * (size_t)c->max_pages_per_seq) &&
                A(&c->d_weights, (size_t)m->n_layers);
+    if (okk) {   // RoPE inverse frequencies theta^(-2i/d) in double
+        std::vector<double> inv((size_t)m->head_dim / 2);
+        for (size_t i = 0; i < inv.size(); ++i) inv[i] = pow((double)m->rope_theta, -2.0 * (double)i / (double)m->head_dim);
+        double *d_inv = nullptr;
+        okk = A(&d_inv, inv.size()) &&
+              hipMemcpy(d_inv, inv.data(), inv.size() * sizeof(double), hipMemcpyHostToDevice) == hipSuccess;
+        P.rope_inv_freq = d_inv;
+    }
     if (okk && (s->debug_flags & ETC_DEBUG_LAYER_HIDDEN)) okk = A(&P.layer_hidden, (size_t)m->n_layers * kMaxBatch * H);
     if (!okk) return bail(ETC_ENOMEM);
     c->h_weights.assign(m->n_layers, LayerWeights{});

@@ -1,6 +1,15 @@
 // Device-side event-tensor runtime (paper Sec. 3.3): an event tensor is an int32 array in HBM;
-// notify = device-scope atomic decrement, wait = wavefront-level spin until zero with bounded
-// backoff.  Plus small numeric helpers shared by the task bodies.
+// notify = device-scope atomic decrement, wait = spin until zero with bounded backoff.
+//
+// Coherence design for MI355X.  The 8 XCDs have private L2 caches, and a device-scope release or
+// acquire FENCE writes back / invalidates a whole L2: measured at 15-30 us per hop, far more than the
+// work between two events.  So no such fence is ever executed here.  Instead every datum that
+// crosses tasks inside a launch (activations, partial results, event counters, queue slots) is
+// written with device-scope write-through stores and read with device-scope loads (relaxed atomics
+// of 2, 4 or 8 bytes: the "sc1" forms), which bypass the non-coherent level.  Ordering is then just:
+//   producer: all threads drain their stores (s_waitcnt), workgroup barrier, one atomic decrement;
+//   consumer: poll the counter with device-scope loads, then issue its (device-scope) data loads.
+// Weights and cached KV pages are read-only during a launch and use ordinary (cached, streaming) loads.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -22,67 +31,119 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
     return (uint16_t)(u >> 16);
 }
 
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+// v ~= hi + lo with hi, lo bf16: 16 mantissa bits survive, so bf16 MFMA operands lose ~2^-17 instead of 2^-9
+__device__ __forceinline__ void split_bf16(float v, uint16_t &hi, uint16_t &lo)
 {
-    return (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
+    hi = f32_to_bf16_bits(v);
+    lo = f32_to_bf16_bits(v - bf16_bits_to_f32(hi));
 }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 __device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
 
-__device__ __forceinline__ int ev_peek(const int32_t *p)
+// ---- explicit address spaces ---------------------------------------------------------------------
+// Pointers that were themselves loaded from memory (weight tables, scratch pointers of an LDS copy of
+// the parameters) are generic to the compiler, which would then emit FLAT loads; those count against
+// the LDS wait counter as well, so every LDS wait would also wait for the newest weight load.  Every
+// accessor therefore states its address space.
+#define ETC_AS_GLOBAL __attribute__((address_space(1)))
+#define ETC_AS_LDS __attribute__((address_space(3)))
+template <class T> __device__ __forceinline__ const ETC_AS_GLOBAL T *as_global(const T *p) { return (const ETC_AS_GLOBAL T *)p; }
+template <class T> __device__ __forceinline__ ETC_AS_GLOBAL T *as_global(T *p) { return (ETC_AS_GLOBAL T *)p; }
+template <class T> __device__ __forceinline__ ETC_AS_LDS T *as_lds(T *p) { return (ETC_AS_LDS T *)p; }
+
+__device__ __forceinline__ u32x4 gld_16B(const void *p) { return *as_global(reinterpret_cast<const u32x4 *>(p)); }
+__device__ __forceinline__ u32x4 gld_16B_nt(const void *p)
 {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __builtin_nontemporal_load(as_global(reinterpret_cast<const u32x4 *>(p)));
 }
+__device__ __forceinline__ int gld_i32(const int32_t *p) { return *as_global(p); }
+__device__ __forceinline__ uint16_t gld_u16(const uint16_t *p) { return *as_global(p); }
+__device__ __forceinline__ void gst_u16(uint16_t *p, uint16_t v) { *as_global(p) = v; }
+__device__ __forceinline__ void gst_f32(float *p, float v) { *as_global(p) = v; }
+
+// ---- device-scope (cross-XCD coherent) accessors ----------------------------------------------
+#define ETC_SCOPE __HIP_MEMORY_SCOPE_AGENT
+__device__ __forceinline__ float ld_f32(const float *p) { return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, ETC_SCOPE); }
+__device__ __forceinline__ int ld_i32(const int32_t *p) { return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, ETC_SCOPE); }
+__device__ __forceinline__ uint64_t ld_u64(const void *p)
+{
+    return __hip_atomic_load(as_global(reinterpret_cast<const uint64_t *>(p)), __ATOMIC_RELAXED, ETC_SCOPE);
+}
+__device__ __forceinline__ void ld_f32x2(const float *p, float &a, float &b)
+{
+    const uint64_t v = ld_u64(p);
+    a = __uint_as_float((uint32_t)v);
+    b = __uint_as_float((uint32_t)(v >> 32));
+}
+__device__ __forceinline__ u32x4 ld_16B(const void *p)      // 16 bytes as two 8-byte device-scope loads
+{
+    const uint64_t a = ld_u64(p), b = ld_u64(reinterpret_cast<const uint64_t *>(p) + 1);
+    return u32x4{(uint32_t)a, (uint32_t)(a >> 32), (uint32_t)b, (uint32_t)(b >> 32)};
+}
+__device__ __forceinline__ void st_f32(float *p, float v) { __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, ETC_SCOPE); }
+__device__ __forceinline__ void st_i32(int32_t *p, int v) { __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, ETC_SCOPE); }
+__device__ __forceinline__ void st_u16(uint16_t *p, uint16_t v) { __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, ETC_SCOPE); }
+
+__device__ __forceinline__ int ev_peek(const int32_t *p) { return ld_i32(p); }
 
 // Records the first error; later waits see it and give up at once, so the kernel always drains.
 __device__ __forceinline__ void raise_error(const Params &P, int code, int fn, int ev)
 {
     int expected = 0;
-    if (__hip_atomic_compare_exchange_strong(P.error_word, &expected, code, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
-                                             __HIP_MEMORY_SCOPE_AGENT)) {
-        __hip_atomic_store(P.error_word + 1, fn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(P.error_word + 2, ev, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(P.error_word + 3, (int)blockIdx.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (__hip_atomic_compare_exchange_strong(as_global(P.error_word), &expected, code, __ATOMIC_RELAXED, __ATOMIC_RELAXED, ETC_SCOPE)) {
+        st_i32(P.error_word + 1, fn);
+        st_i32(P.error_word + 2, ev);
+        st_i32(P.error_word + 3, (int)blockIdx.x);
     }
 }
 
-// E[ev].wait() for one wavefront: lane 0 polls, backing off with s_sleep; every lane then passes an
-// acquire fence so that loads issued after the wait observe what the notifying tasks wrote.
-// Returns false when the spin budget ran out or another wave already raised an error.
-__device__ __forceinline__ bool wave_wait(const Params &P, int ev, int fn)
+// Spin of one lane until E[ev] reaches zero: bounded backoff, bounded budget.
+__device__ __forceinline__ void spin_until_zero(const Params &P, int ev, int fn)
 {
-    int ok = 1;
-    if (ev >= 0) {
-        if (lane_id() == 0) {
-            const int32_t *p = P.ev_cur + ev;
-            long long spins = 0;
-            while (ev_peek(p) > 0) {
-                if (spins < 64) __builtin_amdgcn_s_sleep(1); else __builtin_amdgcn_s_sleep(8);
-                ++spins;
-                if ((spins & 255) == 0 && ev_peek(P.error_word) != 0) { ok = 0; break; }
-                if (spins > P.spin_budget) { raise_error(P, ERR_WAIT_TIMEOUT, fn, ev); ok = 0; break; }
-            }
-        }
-        ok = __builtin_amdgcn_readfirstlane(ok);
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    const int32_t *p = P.ev_cur + ev;
+    long long spins = 0;
+    while (ev_peek(p) > 0) {
+        if (spins < 16) __builtin_amdgcn_s_sleep(1); else __builtin_amdgcn_s_sleep(4);
+        ++spins;
+        if ((spins & 255) == 0 && ev_peek(P.error_word) != 0) break;
+        if (spins > P.spin_budget) { raise_error(P, ERR_WAIT_TIMEOUT, fn, ev); break; }
     }
-    return ok != 0;
 }
 
-// Makes the calling workgroup's global stores visible device-wide; call before notifying.
-// Every thread drains its own stores, the barrier collects the workgroup, thread 0 publishes.
+// E[ev].wait() for one wavefront (lane 0 polls).  A wait that gives up records the error and the task
+// still runs (on stale data), so every wave keeps the same barrier sequence and the kernel drains.
+__device__ __forceinline__ void wave_wait(const Params &P, int ev, int fn)
+{
+    if (ev < 0) return;
+    if (lane_id() == 0) spin_until_zero(P, ev, fn);
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");    // orders later loads after the poll (no cache op)
+}
+
+// E[ev0].wait(), E[ev1].wait() for the whole workgroup: one polling lane, then a barrier.
+__device__ __forceinline__ void wg_wait(const Params &P, int ev0, int ev1, int fn)
+{
+    if (ev0 < 0 && ev1 < 0) return;
+    if (threadIdx.x == 0) {
+        if (ev0 >= 0) spin_until_zero(P, ev0, fn);
+        if (ev1 >= 0) spin_until_zero(P, ev1, fn);
+    }
+    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+// Before a notify: every thread drains its (write-through) stores, then the workgroup meets.
 __device__ __forceinline__ void wg_release()
 {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (threadIdx.x == 0) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
 }
 
 // E[ev].notify(): returns the value before the decrement (1 means this call fired the event).
 __device__ __forceinline__ int ev_notify(const Params &P, int ev)
 {
-    return __hip_atomic_fetch_sub(P.ev_cur + ev, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __hip_atomic_fetch_sub(as_global(P.ev_cur + ev), 1, __ATOMIC_RELAXED, ETC_SCOPE);
 }
 
 __device__ __forceinline__ float wave_sum(float v)

@@ -8,7 +8,7 @@ constexpr int kWgThreads = 512;          // one task = one workgroup of 8 wavefr
 constexpr int kWaves = kWgThreads / 64;
 constexpr int kMaxBatch = 64;
 constexpr int kMaxLayers = 128;
-constexpr int kLdsBytes = 96 * 1024;     // > half of the 160 KB LDS: at most one workgroup per CU
+constexpr int kLdsBytes = 148 * 1024;    // of the 160 KB LDS per CU: exactly one persistent workgroup per CU
 
 // Device functions (task bodies).  One entry of the dispatch switch each (Alg. 1 "dispatch logic").
 enum Fn : uint8_t {
@@ -61,6 +61,7 @@ struct Params {
     // model
     int32_t n_layers, H, nq, nkv, d, F, E, topk, moeF, page;
     float eps, theta;
+    const double *rope_inv_freq;       // [d/2] theta^(-2i/d), computed on the host in double
     int32_t kv_chunk, tile_m;
     // resident tensors
     const LayerWeights *weights;       // [n_layers] device
@@ -73,19 +74,21 @@ struct Params {
     const int32_t *kv_len, *page_indptr, *page_ids;
     const uint16_t *hidden_in;
     uint16_t *hidden_out;
-    // scratch (library-owned)
-    float *x, *x_mid;                  // residual stream [maxB, H]
+    // scratch (library-owned; crosses tasks, so it is only touched with device-scope accesses)
+    float *x, *x_mid;                  // residual stream before / after the attention block [maxB, H]
+    uint16_t *xg_hi, *xg_lo;           // x * g1 of the consuming layer, split into bf16 hi + lo [maxB, H]
+    uint16_t *xmg_hi, *xmg_lo;         // x_mid * g2, split [maxB, H]
+    float *ssq_x, *ssq_xmid;           // partial sums of squares per 16-row tile [H/16][kMaxBatch]
     float *qbuf;                       // rotated queries [maxB, nq*d]
-    uint16_t *attn;                    // attention output bf16 [maxB, nq*d]
-    uint16_t *act;                     // silu(gate)*up bf16 [maxB, F]
+    uint16_t *attn_hi, *attn_lo;       // attention output, split [maxB, nq*d]
+    uint16_t *act_hi, *act_lo;         // silu(gate)*up, split [maxB, F]
     float *part_m, *part_l, *part_o;   // split-KV partials [maxB, nq, max_chunks] (+ [d])
     // MoE scratch
     float *router_logits;              // [maxB, E]
     int32_t *topk_ids;                 // [maxB, topk]
     float *topk_w;                     // [maxB, topk]
     int32_t *exp_count, *tok_indptr, *exp_indptr, *perm, *inv_perm; // [E], [E+1], [E+1], [maxB*topk] x2
-    uint16_t *xn2;                     // normalised FFN input bf16 [maxB, H]
-    uint16_t *eact;                    // expert activations bf16 [maxB*topk, moeF]
+    uint16_t *eact_hi, *eact_lo;       // expert activations, split [maxB*topk, moeF]
     float *ey;                         // expert outputs fp32 [maxB*topk, H]
     const int32_t *forced_topk;        // [n_layers, maxB, topk] or null
     const uint8_t *forced_mask;        // [n_layers] or null

@@ -22,10 +22,10 @@ __device__ __forceinline__ void rowsum_partial(const Params &P, int i, int j)
     // task (i, j): B[32i .. 32i+32, j] = sum_{k in [32j, 32j+32)} A[row, k], left to right
     if (threadIdx.x < 32) {
         const int row = 32 * i + threadIdx.x;
-        const float *a = P.gbuf[0] + (size_t)row * 128 + 32 * j;
+        const ETC_AS_GLOBAL float *a = as_global(P.gbuf[0]) + (size_t)row * 128 + 32 * j;
         float acc = 0.f;
         for (int k = 0; k < 32; ++k) acc += a[k];
-        P.gbuf[1][(size_t)row * 4 + j] = acc;
+        st_f32(P.gbuf[1] + (size_t)row * 4 + j, acc);
     }
 }
 __device__ __forceinline__ void rowsum_final(const Params &P, int i)
@@ -33,40 +33,39 @@ __device__ __forceinline__ void rowsum_final(const Params &P, int i)
     if (threadIdx.x < 32) {
         const int row = 32 * i + threadIdx.x;
         const float *b = P.gbuf[1] + (size_t)row * 4;
-        P.gbuf[2][row] = ((b[0] + b[1]) + b[2]) + b[3];
+        as_global(P.gbuf[2])[row] = ((ld_f32(b) + ld_f32(b + 1)) + ld_f32(b + 2)) + ld_f32(b + 3);
     }
 }
 
+// Step prologue for sequence b: hidden_in (bf16) -> residual stream (fp32), the first layer's projection
+// operand (x * g1, split) and the partial sums of squares per 16 elements, as every later producer does.
 __device__ __forceinline__ void load_hidden(const Params &P, int b)
 {
-    for (int i = threadIdx.x; i < P.H; i += kWgThreads)
-        P.x[(size_t)b * P.H + i] = bf16_bits_to_f32(P.hidden_in[(size_t)b * P.H + i]);
+    const uint16_t *g1 = (const uint16_t *)as_global(P.weights)[0].g1;
+    for (int part = threadIdx.x; part < P.H / 16; part += kWgThreads) {
+        float s = 0.f;
+        for (int i = 0; i < 16; ++i) {
+            const size_t o = (size_t)b * P.H + part * 16 + i;
+            const float v = bf16_bits_to_f32(gld_u16(P.hidden_in + o));
+            st_f32(P.x + o, v);
+            uint16_t hi, lo;
+            split_bf16(v * bf16_bits_to_f32(gld_u16(g1 + part * 16 + i)), hi, lo);
+            st_u16(P.xg_hi + o, hi);
+            st_u16(P.xg_lo + o, lo);
+            s += v * v;
+        }
+        st_f32(P.ssq_x + (size_t)part * kMaxBatch + b, s);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
 // dispatch: one task, including its waits; the caller notifies
 // ---------------------------------------------------------------------------------------------
-template <bool SYNC_EVENTS>
-__device__ __forceinline__ void run_task(const Params &P, const Task &t, float *sm)
+// Fills the tile and epilogue descriptors of a projection task; false for every other task kind.
+__device__ __forceinline__ bool setup_gemm(const Params &P, const Task &t, GemmTile &g, Epilogue &e)
 {
-    const int w0 = SYNC_EVENTS ? t.wait0 : -1, w1 = SYNC_EVENTS ? t.wait1 : -1;
-    const LayerWeights *W = P.weights ? P.weights + t.layer : nullptr;
-    TaskWaits tw{w0, w1, (int)t.fn, (t.flags & TF_WAIT0_PER_WAVE) != 0 && SYNC_EVENTS};
-    bool is_gemm = false;      // projection tiles share one call site of the MFMA body
-    GemmTile g{};
-    Epilogue e{};
+    const ETC_AS_GLOBAL LayerWeights *W = as_global(P.weights) + t.layer;
     switch (t.fn) {
-    case FN_ROWSUM_PARTIAL:
-        wave_wait(P, w0, t.fn);
-        rowsum_partial(P, t.c0, t.c1);
-        break;
-    case FN_ROWSUM_FINAL:
-        wave_wait(P, w0, t.fn);
-        rowsum_final(P, t.c0);
-        break;
-    case FN_LOAD_HIDDEN:
-        if (t.c0 < P.B) load_hidden(P, t.c0);
-        break;
     case FN_QKV: {
         const int hd = t.c0, sub = t.c1;
         const int i0 = sub * 8;
@@ -77,84 +76,127 @@ __device__ __forceinline__ void run_task(const Params &P, const Task &t, float *
         g.rowsA = wbase + (size_t)i0 * P.H;
         g.rowsB = wbase + (size_t)(i0 + P.d / 2) * P.H;
         g.ldw = P.H; g.K = P.H;
-        g.xf = P.x; g.gain = (const uint16_t *)W->g1; g.eps = P.eps; g.ldx = P.H;
+        g.b_hi = P.xg_hi; g.b_lo = P.xg_lo; g.ldb = P.H;
+        g.ssq_parts = P.ssq_x; g.n_parts = P.H / 16; g.eps = P.eps;
         g.n_cols = P.B;
         e.kind = EPI_QKV; e.layer = t.layer; e.row0 = i0; e.head = hd;
-        is_gemm = true;
-        break;
-    }
-    case FN_ATTN: {
-        const int b = t.c0, kvh = t.c1, ch = t.c2;
-        const bool active = b < P.B && ch * P.kv_chunk < P.kv_len[b] + 1;
-        if (active) {     // inactive slots of the sampled-shape queue neither wait nor compute; they still notify
-            wave_wait(P, w0, t.fn);
-            const int grp = P.nq / P.nkv;
-            if (P.d == 128 && grp == 4) attn_chunk<128, 4>(P, t.layer, b, kvh, ch, sm);
-            else if (P.d == 128 && grp == 8) attn_chunk<128, 8>(P, t.layer, b, kvh, ch, sm);
-            else if (P.d == 64 && grp == 2) attn_chunk<64, 2>(P, t.layer, b, kvh, ch, sm);
-            else if (P.d == 128 && grp == 1) attn_chunk<128, 1>(P, t.layer, b, kvh, ch, sm);
-            else if (P.d == 64 && grp == 4) attn_chunk<64, 4>(P, t.layer, b, kvh, ch, sm);
-        }
-        break;
-    }
-    case FN_MERGE: {
-        const int b = t.c0, kvh = t.c1;
-        if (b < P.B) {
-            wave_wait(P, w0, t.fn);
-            const int grp = P.nq / P.nkv;
-            if (P.d == 128 && grp == 4) attn_merge<128, 4>(P, b, kvh);
-            else if (P.d == 128 && grp == 8) attn_merge<128, 8>(P, b, kvh);
-            else if (P.d == 64 && grp == 2) attn_merge<64, 2>(P, b, kvh);
-            else if (P.d == 128 && grp == 1) attn_merge<128, 1>(P, b, kvh);
-            else if (P.d == 64 && grp == 4) attn_merge<64, 4>(P, b, kvh);
-        }
-        break;
+        return true;
     }
     case FN_OPROJ: {
         const int r0 = t.c0 * 16, QD = P.nq * P.d;
         g.rowsA = (const uint16_t *)W->wo + (size_t)r0 * QD;
         g.rowsB = g.rowsA + (size_t)8 * QD;
         g.ldw = QD; g.K = QD;
-        g.xb = P.attn; g.ldxb = QD;
+        g.b_hi = P.attn_hi; g.b_lo = P.attn_lo; g.ldb = QD;
         g.n_cols = P.B;
         e.kind = EPI_RESID; e.layer = t.layer; e.row0 = r0; e.resid = P.x; e.outf = P.x_mid; e.ld = P.H;
-        is_gemm = true;
-        break;
+        e.next_gain = (const uint16_t *)W->g2; e.out_hi = P.xmg_hi; e.out_lo = P.xmg_lo;
+        e.ssq_out = P.ssq_xmid + (size_t)t.c0 * kMaxBatch;
+        return true;
     }
     case FN_GATEUP: {
         const int f0 = t.c0 * 8;
         g.rowsA = (const uint16_t *)W->wg + (size_t)f0 * P.H;
         g.rowsB = (const uint16_t *)W->wu + (size_t)f0 * P.H;
         g.ldw = P.H; g.K = P.H;
-        g.xf = P.x_mid; g.gain = (const uint16_t *)W->g2; g.eps = P.eps; g.ldx = P.H;
+        g.b_hi = P.xmg_hi; g.b_lo = P.xmg_lo; g.ldb = P.H;
+        g.ssq_parts = P.ssq_xmid; g.n_parts = P.H / 16; g.eps = P.eps;
         g.n_cols = P.B;
-        e.kind = EPI_SWIGLU; e.layer = t.layer; e.row0 = f0; e.outb = P.act; e.ld = P.F;
-        is_gemm = true;
-        break;
+        e.kind = EPI_SWIGLU; e.layer = t.layer; e.row0 = f0; e.out_hi = P.act_hi; e.out_lo = P.act_lo; e.ld = P.F;
+        return true;
     }
     case FN_DOWN: {
         const int r0 = t.c0 * 16;
         g.rowsA = (const uint16_t *)W->wd + (size_t)r0 * P.F;
         g.rowsB = g.rowsA + (size_t)8 * P.F;
         g.ldw = P.F; g.K = P.F;
-        g.xb = P.act; g.ldxb = P.F;
+        g.b_hi = P.act_hi; g.b_lo = P.act_lo; g.ldb = P.F;
         g.n_cols = P.B;
         e.kind = EPI_RESID; e.layer = t.layer; e.row0 = r0; e.resid = P.x_mid; e.outf = P.x; e.ld = P.H;
         e.flags = (uint16_t)((t.flags & TF_LAST_LAYER) | ((P.debug_flags & 2u) ? EPF_DUMP_LAYER : 0));
-        is_gemm = true;
+        if (!(t.flags & TF_LAST_LAYER)) {     // operand of the next layer's QKV projection
+            e.next_gain = (const uint16_t *)as_global(P.weights)[t.layer + 1].g1; e.out_hi = P.xg_hi; e.out_lo = P.xg_lo;
+            e.ssq_out = P.ssq_x + (size_t)t.c0 * kMaxBatch;
+        }
+        return true;
+    }
+    default:
+        return false;
+    }
+}
+
+// tn: the task this workgroup runs next (fn = FN_NOP if unknown): a projection task starts streaming
+// the next projection task's weights while it finishes its own.
+template <bool SYNC_EVENTS>
+__device__ __forceinline__ void run_task(const Params &P, const Params &PL, const Task &t, const Task &tn, float *sm,
+                                         WgState &st)
+{
+    const int w0 = SYNC_EVENTS ? t.wait0 : -1, w1 = SYNC_EVENTS ? t.wait1 : -1;
+    TaskWaits tw{w0, w1, (int)t.fn, (t.flags & TF_WAIT0_PER_WAVE) != 0 && SYNC_EVENTS};
+    GemmTile g{};
+    Epilogue e{};
+    if (setup_gemm(P, t, g, e)) {
+        GemmTile gn{};
+        Epilogue en{};
+        const uint16_t *wnext = nullptr;
+        int n_it_next = 0;
+        if (setup_gemm(P, tn, gn, en)) {
+            wnext = lane_weight_row(gn);
+            n_it_next = (gn.K / kWaves) >> 5;
+        }
+        gemm_tile_dispatch(P, PL, g, e, tw, sm, st, t.id, wnext, n_it_next, tn.id);
+        return;
+    }
+    wg_state_drop_weights(st);
+    switch (t.fn) {
+    case FN_ROWSUM_PARTIAL:
+        wg_wait_cached(P, st, w0, w1, t.fn);
+        rowsum_partial(P, t.c0, t.c1);
+        break;
+    case FN_ROWSUM_FINAL:
+        wg_wait_cached(P, st, w0, w1, t.fn);
+        rowsum_final(P, t.c0);
+        break;
+    case FN_LOAD_HIDDEN:
+        if (t.c0 < P.B) load_hidden(P, t.c0);
+        break;
+    case FN_ATTN: {
+        const int b = t.c0, kvh = t.c1, ch = t.c2;
+        const bool active = b < P.B && ch * P.kv_chunk < gld_i32(P.kv_len + b) + 1;
+        if (active) {     // inactive slots of the sampled-shape queue neither wait nor compute; they still notify
+            wg_wait_cached(P, st, w0, w1, t.fn);
+            st.staged_key = -1;      // the attention scratch overlaps the staged operand
+            const int grp = P.nq / P.nkv;
+            if (P.d == 128 && grp == 4) attn_chunk<128, 4>(PL, t.layer, b, kvh, ch, sm);
+            else if (P.d == 128 && grp == 8) attn_chunk<128, 8>(PL, t.layer, b, kvh, ch, sm);
+            else if (P.d == 64 && grp == 2) attn_chunk<64, 2>(PL, t.layer, b, kvh, ch, sm);
+            else if (P.d == 128 && grp == 1) attn_chunk<128, 1>(PL, t.layer, b, kvh, ch, sm);
+            else if (P.d == 64 && grp == 4) attn_chunk<64, 4>(PL, t.layer, b, kvh, ch, sm);
+        }
+        break;
+    }
+    case FN_MERGE: {
+        const int b = t.c0, kvh = t.c1;
+        if (b < P.B) {
+            wg_wait_cached(P, st, w0, w1, t.fn);
+            const int grp = P.nq / P.nkv;
+            if (P.d == 128 && grp == 4) attn_merge<128, 4>(PL, b, kvh);
+            else if (P.d == 128 && grp == 8) attn_merge<128, 8>(PL, b, kvh);
+            else if (P.d == 64 && grp == 2) attn_merge<64, 2>(PL, b, kvh);
+            else if (P.d == 128 && grp == 1) attn_merge<128, 1>(PL, b, kvh);
+            else if (P.d == 64 && grp == 4) attn_merge<64, 4>(PL, b, kvh);
+        }
         break;
     }
     default:
         break;
     }
-    if (is_gemm) gemm_tile_dispatch(P, g, e, tw, sm);
 }
 
 __device__ __forceinline__ Task load_task(const Task *p)
 {
     // the queue is read-only for the whole launch; every lane reads the same record
-    const u32x4 *q = reinterpret_cast<const u32x4 *>(p);
-    u32x4 a = q[0], b = q[1];
+    const u32x4 a = gld_16B(p), b = gld_16B(reinterpret_cast<const u32x4 *>(p) + 1);
     Task t;
     uint32_t w0 = __builtin_amdgcn_readfirstlane(a.x);
     t.fn = (uint8_t)(w0 & 0xFF);
@@ -170,27 +212,44 @@ __device__ __forceinline__ Task load_task(const Task *p)
     return t;
 }
 
+// Copies the kernel argument into LDS so that out-of-line task bodies can take it by address.
+__device__ __forceinline__ void stage_params(const Params &P, Params *dst)
+{
+    const uint32_t *src = reinterpret_cast<const uint32_t *>(&P);
+    uint32_t *d = reinterpret_cast<uint32_t *>(dst);
+    for (int i = threadIdx.x; i < (int)(sizeof(Params) / 4); i += kWgThreads) d[i] = src[i];
+    __syncthreads();
+}
+
 // Re-arms the event tensors of the NEXT launch from the initial counts; nothing in this launch
 // touches that buffer, and the next launch starts after this kernel has ended.
 __device__ __forceinline__ void rearm_next(const Params &P)
 {
     for (int i = blockIdx.x * kWgThreads + threadIdx.x; i < P.n_events; i += gridDim.x * kWgThreads)
-        P.ev_next[i] = P.ev_init[i];
+        as_global(P.ev_next)[i] = as_global(P.ev_init)[i];
 }
 
 __global__ void __launch_bounds__(kWgThreads) megakernel_static(const Params P)
 {
     extern __shared__ __attribute__((aligned(16))) float sm[];
+    __shared__ Params sP;
+    stage_params(P, &sP);
     rearm_next(P);
-    const int q0 = P.queue_begin[blockIdx.x], q1 = P.queue_begin[blockIdx.x + 1];
+    WgState st;
+    wg_state_init(st);
+    const int q0 = gld_i32(P.queue_begin + blockIdx.x), q1 = gld_i32(P.queue_begin + blockIdx.x + 1);
+    Task t = q0 < q1 ? load_task(P.tasks + q0) : Task{};
     for (int i = q0; i < q1; ++i) {
-        const Task t = load_task(P.tasks + i);
-        run_task<true>(P, t, sm);
+        Task tn{};
+        tn.id = -1;
+        if (i + 1 < q1) tn = load_task(P.tasks + i + 1);
+        run_task<true>(P, sP, t, tn, sm, st);
         wg_release();
         if (threadIdx.x == 0) {
             if (t.notify0 >= 0) ev_notify(P, t.notify0);
             if (P.debug_flags & 1u) atomicAdd(P.exec_count + t.id, 1);
         }
+        t = tn;
     }
 }
 
@@ -213,6 +272,8 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
 {
     extern __shared__ __attribute__((aligned(16))) float sm[];
     __shared__ int s_task;
+    __shared__ Params sP;
+    stage_params(P, &sP);
     rearm_next(P);
     if (blockIdx.x == 0 && threadIdx.x == 0) {            // reset the control words of the next launch
         for (int i = 0; i < 8; ++i) P.q_ctrl_next[i] = 0;
@@ -246,7 +307,11 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
         __syncthreads();
         if (id < 0) break;
         const Task t = load_task(P.dyn_tasks + id);
-        run_task<true>(P, t, sm);      // early push (App. E): remaining in-edges are still waited on
+        Task tn{};
+        tn.id = -1;
+        WgState st;
+        wg_state_init(st);
+        run_task<true>(P, sP, t, tn, sm, st);  // early push (App. E): remaining in-edges are still waited on
         wg_release();
         if (threadIdx.x == 0) {
             if (P.debug_flags & 1u) atomicAdd(P.exec_count + t.id, 1);
@@ -268,8 +333,14 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
 __global__ void __launch_bounds__(kWgThreads) stage_kernel(const Params P, int first)
 {
     extern __shared__ __attribute__((aligned(16))) float sm[];
+    __shared__ Params sP;
+    stage_params(P, &sP);
     const Task t = load_task(P.dyn_tasks + first + blockIdx.x);
-    run_task<false>(P, t, sm);
+    Task tn{};
+    tn.id = -1;
+    WgState st;
+    wg_state_init(st);
+    run_task<false>(P, sP, t, tn, sm, st);
 }
 
 }  // namespace etc

@@ -5,22 +5,24 @@
 // Head dim D is split 8 elements per lane (16-byte loads of a bf16 K or V row slice), so D/8 lanes
 // cover one key and a wavefront covers 64/(D/8) keys per load instruction; the 8 wavefronts of the
 // workgroup stride over the chunk.  Reductions are wavefront shuffles, then LDS across waves.
+// Cached K/V rows are read-only during the launch (ordinary loads); the row appended by this step, the
+// queries and the partials cross tasks and are accessed with device-scope loads / stores.
 #pragma once
 #include "device_rt.hip.h"
 
 namespace etc {
 
 template <int D, int GRP>
-__device__ __forceinline__ void attn_chunk(const Params &P, int layer, int b, int kvh, int ch, float *sm)
+__device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int kvh, int ch, float *sm)
 {
     constexpr int LPT = D / 8;        // lanes per key
     constexpr int TPW = 64 / LPT;     // keys per wavefront step
     const int wave = wave_id(), lane = lane_id();
     const int tq = lane / LPT, dl = lane % LPT;
-    const int n_keys = P.kv_len[b] + 1;
+    const int n_keys = gld_i32(P.kv_len + b) + 1;
     const int j0 = ch * P.kv_chunk;
     const int j1 = min(n_keys, j0 + P.kv_chunk);
-    const int32_t *pages = P.page_ids + P.page_indptr[b];
+    const int32_t *pages = P.page_ids + gld_i32(P.page_indptr + b);
     const size_t lbase = (size_t)layer * (size_t)P.pool_layer_stride;
     const float qscale = 1.0f / sqrtf((float)D);
 
@@ -28,9 +30,12 @@ __device__ __forceinline__ void attn_chunk(const Params &P, int layer, int b, in
 #pragma unroll
     for (int g = 0; g < GRP; ++g) {
         const float *qp = P.qbuf + (size_t)b * (size_t)(P.nq * D) + (size_t)(kvh * GRP + g) * D + dl * 8;
-        f32x4 a = *reinterpret_cast<const f32x4 *>(qp), c = *reinterpret_cast<const f32x4 *>(qp + 4);
-        q[g][0] = a.x * qscale; q[g][1] = a.y * qscale; q[g][2] = a.z * qscale; q[g][3] = a.w * qscale;
-        q[g][4] = c.x * qscale; q[g][5] = c.y * qscale; q[g][6] = c.z * qscale; q[g][7] = c.w * qscale;
+#pragma unroll
+        for (int i = 0; i < 8; i += 2) {
+            ld_f32x2(qp + i, q[g][i], q[g][i + 1]);
+            q[g][i] *= qscale;
+            q[g][i + 1] *= qscale;
+        }
     }
     float mx[GRP], l[GRP], o[GRP][8];
 #pragma unroll
@@ -45,10 +50,16 @@ __device__ __forceinline__ void attn_chunk(const Params &P, int layer, int b, in
         const int j = jb + tq;
         const bool valid = j < j1;
         const int jc = valid ? j : j1 - 1;
-        const int page = pages[jc / P.page];
+        const int page = gld_i32(pages + jc / P.page);
         const size_t off = lbase + (((size_t)page * P.page + (size_t)(jc % P.page)) * P.nkv + kvh) * (size_t)D + dl * 8;
-        const u32x4 kr = *reinterpret_cast<const u32x4 *>(P.kpool + off);
-        const u32x4 vr = *reinterpret_cast<const u32x4 *>(P.vpool + off);
+        u32x4 kr, vr;
+        if (jc == n_keys - 1) {          // the row this step appended: written by another task of this launch
+            kr = ld_16B(P.kpool + off);
+            vr = ld_16B(P.vpool + off);
+        } else {
+            kr = gld_16B(P.kpool + off);
+            vr = gld_16B(P.vpool + off);
+        }
         float kf[8], vf[8];
         kf[0] = bf16_bits_to_f32(kr.x & 0xFFFFu); kf[1] = bf16_bits_to_f32(kr.x >> 16);
         kf[2] = bf16_bits_to_f32(kr.y & 0xFFFFu); kf[3] = bf16_bits_to_f32(kr.y >> 16);
@@ -96,9 +107,9 @@ __device__ __forceinline__ void attn_chunk(const Params &P, int layer, int b, in
         }
     }
     // across wavefronts through LDS: [wave][g] -> m, l, o[D]
-    float *s_m = sm;                                 // [kWaves][GRP]
-    float *s_l = sm + kWaves * GRP;                  // [kWaves][GRP]
-    float *s_o = sm + 2 * kWaves * GRP;              // [kWaves][GRP][D]
+    ETC_AS_LDS float *s_m = as_lds(sm);              // [kWaves][GRP]
+    ETC_AS_LDS float *s_l = s_m + kWaves * GRP;      // [kWaves][GRP]
+    ETC_AS_LDS float *s_o = s_m + 2 * kWaves * GRP;  // [kWaves][GRP][D]
     if (tq == 0) {
 #pragma unroll
         for (int g = 0; g < GRP; ++g) {
@@ -123,29 +134,33 @@ __device__ __forceinline__ void attn_chunk(const Params &P, int layer, int b, in
         }
         const int h = kvh * GRP + g;
         const size_t pidx = ((size_t)b * P.nq + h) * (size_t)P.max_chunks + ch;
-        P.part_o[pidx * D + i] = num;
-        if (i == 0) { P.part_m[pidx] = m; P.part_l[pidx] = den; }
+        st_f32(P.part_o + pidx * D + i, num);
+        if (i == 0) { st_f32(P.part_m + pidx, m); st_f32(P.part_l + pidx, den); }
     }
 }
 
 template <int D, int GRP>
-__device__ __forceinline__ void attn_merge(const Params &P, int b, int kvh)
+__device__ __noinline__ void attn_merge(const Params &P, int b, int kvh)
 {
-    const int n_keys = P.kv_len[b] + 1;
+    const int n_keys = gld_i32(P.kv_len + b) + 1;
     const int nc = (n_keys + P.kv_chunk - 1) / P.kv_chunk;
     for (int idx = threadIdx.x; idx < GRP * D; idx += kWgThreads) {
         const int g = idx / D, i = idx % D;
         const int h = kvh * GRP + g;
         const size_t p0 = ((size_t)b * P.nq + h) * (size_t)P.max_chunks;
         float m = -INFINITY;
-        for (int c = 0; c < nc; ++c) m = fmaxf(m, P.part_m[p0 + c]);
+        for (int c = 0; c < nc; ++c) m = fmaxf(m, ld_f32(P.part_m + p0 + c));
         float num = 0.f, den = 0.f;
         for (int c = 0; c < nc; ++c) {                 // ascending chunk order
-            const float sc = __expf(P.part_m[p0 + c] - m);
-            num += sc * P.part_o[(p0 + c) * D + i];
-            den += sc * P.part_l[p0 + c];
+            const float sc = __expf(ld_f32(P.part_m + p0 + c) - m);
+            num += sc * ld_f32(P.part_o + (p0 + c) * D + i);
+            den += sc * ld_f32(P.part_l + p0 + c);
         }
-        P.attn[(size_t)b * (size_t)(P.nq * D) + (size_t)h * D + i] = f32_to_bf16_bits(num / den);
+        uint16_t hi, lo;                               // operand of the O projection: split bf16
+        split_bf16(num / den, hi, lo);
+        const size_t o = (size_t)b * (size_t)(P.nq * D) + (size_t)h * D + i;
+        st_u16(P.attn_hi + o, hi);
+        st_u16(P.attn_lo + o, lo);
     }
 }
 

@@ -1,16 +1,24 @@
 // Projection tile task: 16 weight rows x K against up to 64 activation columns, bf16 MFMA with
 // fp32 accumulation (v_mfma_f32_16x16x32_bf16), weights streamed from HBM exactly once.
 //
-// Work split.  The 8 wavefronts of the workgroup split K; each streams its slice of all 16 rows
-// with 16-byte non-temporal loads, keeping PF loads (PF KB per wave) in flight.  The first PF loads
-// are issued BEFORE the task waits on its events (weight prefetch, paper Sec. 3.4 / 4.3), so HBM
-// keeps streaming while the dependency resolves.  The activation operand (tiny, L2 resident) is
-// fetched through a 2-deep register ring.  Partial tiles are reduced across waves through LDS in a
-// fixed order (deterministic), then the epilogue runs on 8 x batch threads.
+// Work split.  The 8 wavefronts of the workgroup split K; each streams its slice of all 16 rows with
+// 16-byte non-temporal loads, keeping PF loads (PF KB per wave, 128 KB per CU) in flight.  The first
+// PF loads are issued BEFORE the task waits on its events (weight prefetch, paper Sec. 3.4 / 4.3), so
+// HBM keeps streaming while the dependency resolves.
+//
+// Activation operand.  Activations reach the MFMA as bf16, which alone would cost ~2^-9 relative error
+// per projection and break the 2e-2 parity bar after a few dozen layers.  The PRODUCER of an activation
+// therefore stores it as two bf16 numbers, hi + lo (16 mantissa bits), and the tile issues two MFMAs per
+// weight fragment (hi and lo); the matrix pipe is <10 % busy in this HBM-bound regime, so this is free.
+// RMSNorm is folded in the same way: the producer stores (x * gain) split, plus one partial sum of
+// squares per 16-row tile; the consumer sums the partials in a fixed order and scales its accumulator
+// by 1/sqrt(mean(x^2)+eps) in the epilogue (the norm factor is a per-column scalar, so it commutes
+// with the contraction).  No separate norm task, no extra event hop.
 //
 // The 16 rows of a tile are two groups of 8 (rowsA, rowsB): a RoPE tile takes rows i..i+7 and
 // i+d/2..i+d/2+7 of one head (8 rotation pairs), a SwiGLU tile takes 8 gate rows and the 8 matching
-// up rows, plain tiles take 16 consecutive rows.
+// up rows, plain tiles take 16 consecutive rows.  Partial tiles of the 8 waves are reduced through LDS
+// in a fixed order (deterministic), then the epilogue runs on 8 x columns threads.
 #pragma once
 #include "device_rt.hip.h"
 
@@ -20,16 +28,13 @@ struct GemmTile {
     const uint16_t *rowsA, *rowsB;   // bf16 weights, first row of each 8-row group
     int ldw;                         // weight row stride (elements)
     int K;                           // reduction length, multiple of 256
-    // activation operand: either fp32 rows normalised on the fly (RMSNorm prologue) ...
-    const float *xf;
-    const uint16_t *gain;
+    const uint16_t *b_hi, *b_lo;     // activation operand, split bf16, [rows, ldb]
+    int ldb;
+    const int32_t *col_rows;         // optional gather: column n reads operand row col_rows[n]
+    int n_cols;                      // valid columns (batch rows or routed tokens), <= 64
+    const float *ssq_parts;          // RMSNorm: partial sums of squares [n_parts][kMaxBatch], or null
+    int n_parts;
     float eps;
-    int ldx;
-    // ... or bf16 rows used as they are
-    const uint16_t *xb;
-    int ldxb;
-    const int32_t *col_rows;         // optional gather: column n reads source row col_rows[n]
-    int n_cols;                      // valid columns (batch rows or routed tokens), <= 16 * NB
 };
 
 constexpr uint16_t EPF_DUMP_LAYER = 0x8000;   // epilogue also records the layer's hidden state
@@ -44,140 +49,199 @@ struct Epilogue {
     int head;                 // QKV: global head index (q heads, then k heads, then v heads)
     const float *resid;       // RESID: [*, ld] fp32 added to the result
     float *outf;              // fp32 destination
-    uint16_t *outb;           // bf16 destination
+    uint16_t *out_hi, *out_lo;// split-bf16 destination (operand of the consuming projection)
+    const uint16_t *next_gain;// RESID: gain the consumer's RMSNorm applies (null: no operand is prepared)
+    float *ssq_out;           // RESID: this tile's partial sums of squares [kMaxBatch]
     int ld;                   // destination row stride
     int col0;                 // MoE: first destination row (permuted row of column 0)
 };
 
 constexpr int kRedFloats = kWaves * 4 * 64 * 4;   // cross-wave reduction buffer (32 KB)
+constexpr int kRsFloats = 64;                     // RMSNorm factors of the columns
+constexpr int kOperandBytes = kLdsBytes - (kRedFloats + kRsFloats) * 4;   // LDS left for a staged operand
+constexpr int PF = 16;                            // weight loads in flight per lane (16 KB per wave)
 
-__device__ __forceinline__ u32x4 load16_nt(const uint16_t *p)
-{
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
-}
-__device__ __forceinline__ u32x4 load16(const uint16_t *p) { return *reinterpret_cast<const u32x4 *>(p); }
+__device__ __forceinline__ u32x4 load16_nt(const uint16_t *p) { return gld_16B_nt(p); }
 
 __device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &e, int col, int mp, float lo, float hi);
 
-// Waits of a projection task: wave-level.  per_wave: wave w waits on ev0 + w (its own K slice).
+// Waits of a projection task.  per_wave: wave w waits on ev0 + w (its own K slice) on its own.
 struct TaskWaits {
     int ev0, ev1, fn;
     bool per_wave;
 };
 
-template <int NB, bool NORM>
-__device__ __forceinline__ bool gemm_tile_run(const Params &P, const GemmTile &g, const Epilogue &e, const TaskWaits &w,
-                                           float *sm)
+// State a persistent workgroup carries from task to task (registers, uniform across the workgroup
+// except for the weight fragments).
+struct WgState {
+    u32x4 wr[PF];        // weight fragments in flight: steps 0..PF-1 of task `wr_task` sit in slots 0..PF-1
+    int wr_task;         // -1: nothing prefetched
+    int zero0, zero1;    // events already seen at zero in this launch (they never re-arm inside a launch)
+    int staged_key;      // event that gates the operand currently staged in LDS (-1: none)
+};
+
+__device__ __forceinline__ void wg_state_init(WgState &st)
+{
+#pragma unroll
+    for (int j = 0; j < PF; ++j) st.wr[j] = u32x4{0, 0, 0, 0};
+    st.wr_task = -1;
+    st.zero0 = st.zero1 = -1;
+    st.staged_key = -1;
+}
+
+// Drops prefetched fragments (before a task that does not stream weights, so the registers are free).
+__device__ __forceinline__ void wg_state_drop_weights(WgState &st)
+{
+#pragma unroll
+    for (int j = 0; j < PF; ++j) st.wr[j] = u32x4{0, 0, 0, 0};
+    st.wr_task = -1;
+}
+
+__device__ __forceinline__ const uint16_t *lane_weight_row(const GemmTile &g)
+{
+    const int wave = wave_id(), lane = lane_id();
+    const int m = lane & 15, kg = lane >> 4;
+    const int kbase = wave * (g.K / kWaves) + kg * 8;
+    return (m < 8 ? g.rowsA + (size_t)m * (size_t)g.ldw : g.rowsB + (size_t)(m - 8) * (size_t)g.ldw) + kbase;
+}
+
+// Workgroup wait with a two-entry cache of events already known to have fired.
+__device__ __forceinline__ void wg_wait_cached(const Params &P, WgState &st, int ev0, int ev1, int fn)
+{
+    const bool need0 = ev0 >= 0 && ev0 != st.zero0 && ev0 != st.zero1;
+    const bool need1 = ev1 >= 0 && ev1 != st.zero0 && ev1 != st.zero1;
+    if (!need0 && !need1) return;
+    wg_wait(P, need0 ? ev0 : -1, need1 ? ev1 : -1, fn);
+    if (need0) { st.zero1 = st.zero0; st.zero0 = ev0; }
+    if (need1) { st.zero1 = st.zero0; st.zero0 = ev1; }
+}
+
+// STAGED: the whole operand (all columns, full K, hi and lo) is copied once into LDS with device-scope
+// loads and reused by every tile of the same stage that this workgroup runs; otherwise operand
+// fragments come straight from memory through a 2-deep register ring.
+template <int NB, bool STAGED>
+__device__ __forceinline__ void gemm_tile_run(const Params &P, const GemmTile &g, const Epilogue &e, const TaskWaits &w,
+                                              float *sm, WgState &st, int task_id, const uint16_t *wnext, int n_it_next,
+                                              int next_task_id)
 {
     const int wave = wave_id(), lane = lane_id();
     const int m = lane & 15, kg = lane >> 4;
     const int Kw = g.K / kWaves, n_it = Kw >> 5;
     const int kbase = wave * Kw + kg * 8;
-    const uint16_t *wrow =
-        (m < 8 ? g.rowsA + (size_t)m * (size_t)g.ldw : g.rowsB + (size_t)(m - 8) * (size_t)g.ldw) + kbase;
+    const uint16_t *wrow = lane_weight_row(g);
 
-    // ---- weight prefetch: before the wait ------------------------------------------------
-    constexpr int PF = 8;
-    u32x4 wreg[PF];
+    // ---- weight prefetch: before the wait (unless the previous task already streamed it in) ----
+    if (st.wr_task != task_id) {
 #pragma unroll
-    for (int j = 0; j < PF; ++j) {
-        if (j < n_it) wreg[j] = load16_nt(wrow + j * 32);
-        else wreg[j] = u32x4{0, 0, 0, 0};
+        for (int j = 0; j < PF; ++j) {
+            if (j < n_it) st.wr[j] = load16_nt(wrow + j * 32);
+            else st.wr[j] = u32x4{0, 0, 0, 0};
+        }
     }
+    st.wr_task = -1;
+
+    ETC_AS_LDS float *red = as_lds(sm);
+    ETC_AS_LDS float *rs = red + kRedFloats;
+    ETC_AS_LDS uint16_t *op_hi = reinterpret_cast<ETC_AS_LDS uint16_t *>(red + kRedFloats + kRsFloats);
+    ETC_AS_LDS uint16_t *op_lo = op_hi + (size_t)g.n_cols * g.K;
 
     // ---- E.wait() -------------------------------------------------------------------------
-    // A wait that gives up records the error and the task still runs to completion (on stale
-    // data): every wave keeps the same barrier sequence, so the kernel always drains.
-    bool ok = wave_wait(P, w.per_wave ? w.ev0 + wave : w.ev0, w.fn);
-    ok = wave_wait(P, w.ev1, w.fn) && ok;
-
-    float *red = sm;
-    float *rs = sm + kRedFloats;
+    if (STAGED) {
+        const int key = w.ev0;
+        if (key < 0 || key != st.staged_key) {
+            if (w.per_wave) {           // the staged copy needs every K slice: lanes 0..7 of wave 0 poll one slice each
+                if (wave == 0 && lane < kWaves) spin_until_zero(P, w.ev0 + lane, w.fn);
+                if (threadIdx.x == 0 && w.ev1 >= 0) spin_until_zero(P, w.ev1, w.fn);
+                __syncthreads();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            } else {
+                wg_wait_cached(P, st, w.ev0, w.ev1, w.fn);
+            }
+            const int quads = g.K >> 2;                         // 8-byte pieces per column
+            for (int idx = threadIdx.x; idx < g.n_cols * quads; idx += kWgThreads) {
+                const int col = idx / quads, q = idx - col * quads;
+                int row = g.col_rows ? ld_i32(g.col_rows + col) : col;
+                if (row < 0) row = 0;
+                const uint64_t vh = ld_u64(g.b_hi + (size_t)row * (size_t)g.ldb + q * 4);
+                const uint64_t vl = ld_u64(g.b_lo + (size_t)row * (size_t)g.ldb + q * 4);
+                *reinterpret_cast<ETC_AS_LDS uint64_t *>(op_hi + (size_t)col * g.K + q * 4) = vh;
+                *reinterpret_cast<ETC_AS_LDS uint64_t *>(op_lo + (size_t)col * g.K + q * 4) = vl;
+            }
+            st.staged_key = key;
+            // (the barrier below, after the norm factors, publishes the staged operand)
+        } else {
+            wg_wait_cached(P, st, w.ev1, -1, w.fn);
+        }
+    } else if (w.per_wave) {
+        wave_wait(P, w.ev0 + wave, w.fn);
+        wave_wait(P, w.ev1, w.fn);
+    } else {
+        wg_wait_cached(P, st, w.ev0, w.ev1, w.fn);
+    }
 
     // ---- operand columns of this lane -------------------------------------------------------
-    const float *xrow[NB];
-    const uint16_t *brow[NB];
-    float scale[NB];
+    const uint16_t *bh[NB], *bl[NB];                 // unstaged: operand rows in memory
+    ETC_AS_LDS const uint16_t *sh[NB], *sl[NB];      // staged: operand rows in LDS
     bool valid[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-        int col = nb * 16 + m;
+        const int col = nb * 16 + m;
         int row = col;
         valid[nb] = col < g.n_cols;
-        if (valid[nb] && g.col_rows) row = g.col_rows[col];
+        if (!STAGED && valid[nb] && g.col_rows) row = ld_i32(g.col_rows + col);
         if (row < 0) valid[nb] = false;
         if (!valid[nb]) row = 0;
-        xrow[nb] = NORM ? g.xf + (size_t)row * (size_t)g.ldx + kbase : nullptr;
-        brow[nb] = NORM ? nullptr : g.xb + (size_t)row * (size_t)g.ldxb + kbase;
-        scale[nb] = 0.f;
+        sh[nb] = op_hi + (size_t)row * (size_t)g.K + kbase;
+        sl[nb] = op_lo + (size_t)row * (size_t)g.K + kbase;
+        bh[nb] = g.b_hi + (size_t)row * (size_t)g.ldb + kbase;
+        bl[nb] = g.b_lo + (size_t)row * (size_t)g.ldb + kbase;
     }
-    if (NORM) {   // RMSNorm prologue: 1 / sqrt(mean(x^2) + eps) of every operand row
+
+    // RMSNorm factor of every column: fixed-order sum of the producers' partial sums of squares
+    if (g.ssq_parts) {
         for (int col = wave; col < g.n_cols; col += kWaves) {
-            int row = g.col_rows ? g.col_rows[col] : col;
+            const int row = g.col_rows ? ld_i32(g.col_rows + col) : col;
             float s = 0.f;
-            if (row >= 0) {
-                const float *xr = g.xf + (size_t)row * (size_t)g.ldx;
-                for (int i = lane * 4; i < g.K; i += 256) {
-                    f32x4 v = *reinterpret_cast<const f32x4 *>(xr + i);
-                    s += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-                }
-            }
+            if (row >= 0)
+                for (int p = lane; p < g.n_parts; p += 64) s += ld_f32(g.ssq_parts + (size_t)p * kMaxBatch + row);
             s = wave_sum(s);
             if (lane == 0) rs[col] = 1.0f / sqrtf(s / (float)g.K + g.eps);
         }
-        __syncthreads();
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) scale[nb] = valid[nb] ? rs[nb * 16 + m] : 0.f;
     }
+    if (STAGED) __syncthreads();
 
-    // ---- operand ring (depth 2) -------------------------------------------------------------
+    // ---- operand ring (depth 2) for the unstaged path -------------------------------------------
     struct Raw {
-        f32x4 x0[NB], x1[NB];
-        u32x4 gn;
-        u32x4 b[NB];
+        u32x4 h[NB], l[NB];
     };
     Raw ring[2];
     auto fetch = [&](int s, Raw &r) {
         const int k = s * 32;
-        if (NORM) {
-            r.gn = load16(g.gain + kbase + k);
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                if (valid[nb]) {
-                    r.x0[nb] = *reinterpret_cast<const f32x4 *>(xrow[nb] + k);
-                    r.x1[nb] = *reinterpret_cast<const f32x4 *>(xrow[nb] + k + 4);
+        for (int nb = 0; nb < NB; ++nb) {
+            if (valid[nb]) {
+                if (STAGED) {
+                    r.h[nb] = *reinterpret_cast<ETC_AS_LDS const u32x4 *>(sh[nb] + k);
+                    r.l[nb] = *reinterpret_cast<ETC_AS_LDS const u32x4 *>(sl[nb] + k);
                 } else {
-                    r.x0[nb] = f32x4{0, 0, 0, 0};
-                    r.x1[nb] = f32x4{0, 0, 0, 0};
+                    r.h[nb] = ld_16B(bh[nb] + k);
+                    r.l[nb] = ld_16B(bl[nb] + k);
                 }
+            } else {
+                r.h[nb] = u32x4{0, 0, 0, 0};
+                r.l[nb] = u32x4{0, 0, 0, 0};
             }
-        } else {
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) r.b[nb] = valid[nb] ? load16(brow[nb] + k) : u32x4{0, 0, 0, 0};
         }
-    };
-    auto operand = [&](const Raw &r, int nb) -> bf16x8 {
-        u32x4 o;
-        if (NORM) {
-            const float sc = scale[nb];
-            float g0 = bf16_bits_to_f32(r.gn.x & 0xFFFFu), g1 = bf16_bits_to_f32(r.gn.x >> 16);
-            float g2 = bf16_bits_to_f32(r.gn.y & 0xFFFFu), g3 = bf16_bits_to_f32(r.gn.y >> 16);
-            float g4 = bf16_bits_to_f32(r.gn.z & 0xFFFFu), g5 = bf16_bits_to_f32(r.gn.z >> 16);
-            float g6 = bf16_bits_to_f32(r.gn.w & 0xFFFFu), g7 = bf16_bits_to_f32(r.gn.w >> 16);
-            o.x = pack_bf16x2(r.x0[nb].x * sc * g0, r.x0[nb].y * sc * g1);
-            o.y = pack_bf16x2(r.x0[nb].z * sc * g2, r.x0[nb].w * sc * g3);
-            o.z = pack_bf16x2(r.x1[nb].x * sc * g4, r.x1[nb].y * sc * g5);
-            o.w = pack_bf16x2(r.x1[nb].z * sc * g6, r.x1[nb].w * sc * g7);
-        } else {
-            o = r.b[nb];
-        }
-        return __builtin_bit_cast(bf16x8, o);
     };
 
     f32x4 acc[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0, 0, 0, 0};
 
+    // Weights of the NEXT projection task start streaming while this task's last PF steps are consumed:
+    // the slot freed at step s (slot s % PF) receives the next task's step s % PF, so that task finds its
+    // steps 0..PF-1 in slots 0..PF-1 whatever this task's length is.
+    const bool cont = wnext != nullptr && n_it >= PF;
     fetch(0, ring[0]);
     if (n_it > 1) fetch(1, ring[1]);
     for (int it = 0; it < n_it; it += PF) {
@@ -185,21 +249,28 @@ __device__ __forceinline__ bool gemm_tile_run(const Params &P, const GemmTile &g
         for (int j = 0; j < PF; ++j) {
             const int s = it + j;
             if (s < n_it) {
-                bf16x8 a = __builtin_bit_cast(bf16x8, wreg[j]);
-                if (s + PF < n_it) wreg[j] = load16_nt(wrow + (s + PF) * 32);
+                const bf16x8 a = __builtin_bit_cast(bf16x8, st.wr[j]);
+                if (s + PF < n_it) {
+                    st.wr[j] = load16_nt(wrow + (s + PF) * 32);
+                } else if (cont) {
+                    if (j < n_it_next) st.wr[j] = load16_nt(wnext + j * 32);
+                }
                 Raw &r = ring[j & 1];
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb)
-                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, operand(r, nb), acc[nb], 0, 0, 0);
+                for (int nb = 0; nb < NB; ++nb) {
+                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, r.h[nb]), acc[nb], 0, 0, 0);
+                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, r.l[nb]), acc[nb], 0, 0, 0);
+                }
                 if (s + 2 < n_it) fetch(s + 2, r);
             }
         }
     }
+    if (cont) st.wr_task = next_task_id;
 
     // ---- cross-wave reduction (fixed order) and epilogue -------------------------------------
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
-        *reinterpret_cast<f32x4 *>(red + ((size_t)(wave * NB + nb) * 64 + lane) * 4) = acc[nb];
+        *reinterpret_cast<ETC_AS_LDS f32x4 *>(red + ((size_t)(wave * NB + nb) * 64 + lane) * 4) = acc[nb];
     __syncthreads();
     for (int idx = threadIdx.x; idx < g.n_cols * 8; idx += kWgThreads) {
         const int col = idx >> 3, mp = idx & 7;
@@ -207,99 +278,139 @@ __device__ __forceinline__ bool gemm_tile_run(const Params &P, const GemmTile &g
         float lo = 0.f, hi = 0.f;
 #pragma unroll
         for (int wv = 0; wv < kWaves; ++wv) {
-            const float *base = red + (size_t)(wv * NB + nb) * 256;
+            ETC_AS_LDS const float *base = red + (size_t)(wv * NB + nb) * 256;
             lo += base[(n + 16 * (mp >> 2)) * 4 + (mp & 3)];
             hi += base[(n + 16 * ((mp + 8) >> 2)) * 4 + (mp & 3)];
         }
+        if (g.ssq_parts) {
+            const float r = rs[col];
+            lo *= r;
+            hi *= r;
+        }
         apply_epilogue(P, e, col, mp, lo, hi);
     }
-    return ok;
 }
 
-__device__ __forceinline__ bool gemm_tile_dispatch(const Params &P, const GemmTile &g, const Epilogue &e,
-                                                   const TaskWaits &w, float *sm)
+// Wider batches run out of line with their own register budget and no cross-task state (the persistent
+// loop keeps its registers for the small-batch path, which is the latency-critical one).  PL is the
+// workgroup's LDS copy of the parameters: a kernel argument cannot be passed by address.
+template <int NB>
+__device__ __noinline__ void gemm_tile_cold(const Params &PL, GemmTile g, Epilogue e, TaskWaits w, float *sm)
 {
-    const bool norm = g.xf != nullptr;
-    if (g.n_cols <= 16) return norm ? gemm_tile_run<1, true>(P, g, e, w, sm) : gemm_tile_run<1, false>(P, g, e, w, sm);
-    if (g.n_cols <= 32) return norm ? gemm_tile_run<2, true>(P, g, e, w, sm) : gemm_tile_run<2, false>(P, g, e, w, sm);
-    return norm ? gemm_tile_run<4, true>(P, g, e, w, sm) : gemm_tile_run<4, false>(P, g, e, w, sm);
+    WgState st;
+    wg_state_init(st);
+    gemm_tile_run<NB, false>(PL, g, e, w, sm, st, 0, nullptr, 0, -1);
 }
 
-// cos / sin of the RoPE angle pos * theta^(-2i/d), evaluated in double (exact range reduction for
-// positions in the thousands); kept out of line: it is called by 8 x batch threads per tile only.
-__device__ __noinline__ void rope_cos_sin(int pos, int i, int d, float theta, float *cs, float *sn)
+__device__ __forceinline__ void gemm_tile_dispatch(const Params &P, const Params &PL, const GemmTile &g, const Epilogue &e,
+                                                   const TaskWaits &w, float *sm, WgState &st, int task_id,
+                                                   const uint16_t *wnext, int n_it_next, int next_task_id)
 {
-    const double inv = pow((double)theta, -2.0 * (double)i / (double)d);
-    double s, c;
-    sincos((double)pos * inv, &s, &c);
-    *cs = (float)c;
-    *sn = (float)s;
+    if (g.n_cols <= 16 && (size_t)g.n_cols * (size_t)g.K * 4 <= (size_t)kOperandBytes) {
+        gemm_tile_run<1, true>(P, g, e, w, sm, st, task_id, wnext, n_it_next, next_task_id);
+        return;
+    }
+    wg_state_drop_weights(st);
+    st.staged_key = -1;
+    if (g.n_cols <= 16) gemm_tile_cold<1>(PL, g, e, w, sm);
+    else if (g.n_cols <= 32) gemm_tile_cold<2>(PL, g, e, w, sm);
+    else gemm_tile_cold<4>(PL, g, e, w, sm);
+}
+
+// cos / sin of the RoPE angle pos * theta^(-2i/d).  The inverse frequencies come from the host in
+// double; the angle is reduced to [-pi, pi] in double (positions run into the thousands), the
+// hardware sine / cosine then see a small argument.
+__device__ __forceinline__ void rope_cos_sin(const Params &P, int pos, int i, float *cs, float *sn)
+{
+    const double ang = (double)pos * *as_global(P.rope_inv_freq + i);
+    const double turns = ang * 0.15915494309189535;          // 1 / (2 pi)
+    const float frac = (float)(turns - rint(turns));          // [-0.5, 0.5] turns
+    const float r = frac * 6.2831853071795862f;
+    *cs = __cosf(r);
+    *sn = __sinf(r);
 }
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
+
+__device__ __forceinline__ void store_split(uint16_t *hi_p, uint16_t *lo_p, size_t idx, float v)
+{
+    uint16_t h, l;
+    split_bf16(v, h, l);
+    st_u16(hi_p + idx, h);
+    st_u16(lo_p + idx, l);
+}
 
 __device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &e, int col, int mp, float lo, float hi)
 {
     switch (e.kind) {
     case EPI_QKV: {
         const int b = col, half = P.d >> 1, i = e.row0 + mp;
-        const int pos = P.kv_len[b];
+        const int pos = gld_i32(P.kv_len + b);
         float a = lo, c = hi;
         if (e.head < P.nq + P.nkv) {   // q and k heads are rotated to position pos
             float cs, sn;
-            rope_cos_sin(pos, i, P.d, P.theta, &cs, &sn);
+            rope_cos_sin(P, pos, i, &cs, &sn);
             a = lo * cs - hi * sn;
             c = lo * sn + hi * cs;
         }
         if (e.head < P.nq) {
             float *q = P.qbuf + (size_t)b * (size_t)(P.nq * P.d) + (size_t)e.head * P.d;
-            q[i] = a;
-            q[i + half] = c;
+            st_f32(q + i, a);
+            st_f32(q + i + half, c);
         } else {
             const bool is_k = e.head < P.nq + P.nkv;
             const int kvh = is_k ? e.head - P.nq : e.head - P.nq - P.nkv;
-            const int page = P.page_ids[P.page_indptr[b] + pos / P.page];
+            const int page = gld_i32(P.page_ids + gld_i32(P.page_indptr + b) + pos / P.page);
             const size_t off = (size_t)e.layer * (size_t)P.pool_layer_stride +
                                (((size_t)page * P.page + (size_t)(pos % P.page)) * P.nkv + kvh) * (size_t)P.d;
             uint16_t *dst = (is_k ? P.kpool : P.vpool) + off;
-            dst[i] = f32_to_bf16_bits(a);
-            dst[i + half] = f32_to_bf16_bits(c);
+            st_u16(dst + i, f32_to_bf16_bits(a));
+            st_u16(dst + i + half, f32_to_bf16_bits(c));
         }
         break;
     }
     case EPI_RESID: {
         const int b = col;
         const size_t o0 = (size_t)b * e.ld + e.row0 + mp, o1 = o0 + 8;
-        const float v0 = e.resid[o0] + lo, v1 = e.resid[o1] + hi;
-        e.outf[o0] = v0;
-        e.outf[o1] = v1;
+        const float v0 = ld_f32(e.resid + o0) + lo, v1 = ld_f32(e.resid + o1) + hi;
+        st_f32(e.outf + o0, v0);
+        st_f32(e.outf + o1, v1);
+        if (e.next_gain) {   // operand of the next projection: (value * gain) split
+            store_split(e.out_hi, e.out_lo, o0, v0 * bf16_bits_to_f32(gld_u16(e.next_gain + e.row0 + mp)));
+            store_split(e.out_hi, e.out_lo, o1, v1 * bf16_bits_to_f32(gld_u16(e.next_gain + e.row0 + mp + 8)));
+        }
+        float s = v0 * v0 + v1 * v1;      // this tile's sum of squares: the 8 threads of a column are 8 consecutive lanes
+        s += __shfl_xor(s, 1, 64);
+        s += __shfl_xor(s, 2, 64);
+        s += __shfl_xor(s, 4, 64);
+        if (mp == 0 && e.ssq_out) st_f32(e.ssq_out + b, s);
         if (e.flags & TF_LAST_LAYER) {
-            P.hidden_out[o0] = f32_to_bf16_bits(v0);
-            P.hidden_out[o1] = f32_to_bf16_bits(v1);
+            gst_u16(P.hidden_out + o0, f32_to_bf16_bits(v0));
+            gst_u16(P.hidden_out + o1, f32_to_bf16_bits(v1));
         }
         if (e.flags & EPF_DUMP_LAYER) {
             float *dbg = P.layer_hidden + (size_t)e.layer * (size_t)kMaxBatch * e.ld;
-            dbg[o0] = v0;
-            dbg[o1] = v1;
+            gst_f32(dbg + o0, v0);
+            gst_f32(dbg + o1, v1);
         }
         break;
     }
     case EPI_SWIGLU: {
-        e.outb[(size_t)col * e.ld + e.row0 + mp] = f32_to_bf16_bits(silu_f(lo) * hi);
+        store_split(e.out_hi, e.out_lo, (size_t)col * e.ld + e.row0 + mp, silu_f(lo) * hi);
         break;
     }
     case EPI_STORE_F32: {
-        e.outf[(size_t)col * e.ld + e.row0 + mp] = lo;
-        e.outf[(size_t)col * e.ld + e.row0 + mp + 8] = hi;
+        st_f32(e.outf + (size_t)col * e.ld + e.row0 + mp, lo);
+        st_f32(e.outf + (size_t)col * e.ld + e.row0 + mp + 8, hi);
         break;
     }
     case EPI_MOE_ACT: {
-        e.outb[(size_t)(e.col0 + col) * e.ld + e.row0 + mp] = f32_to_bf16_bits(silu_f(lo) * hi);
+        store_split(e.out_hi, e.out_lo, (size_t)(e.col0 + col) * e.ld + e.row0 + mp, silu_f(lo) * hi);
         break;
     }
     case EPI_MOE_Y: {
-        e.outf[(size_t)(e.col0 + col) * e.ld + e.row0 + mp] = lo;
-        e.outf[(size_t)(e.col0 + col) * e.ld + e.row0 + mp + 8] = hi;
+        st_f32(e.outf + (size_t)(e.col0 + col) * e.ld + e.row0 + mp, lo);
+        st_f32(e.outf + (size_t)(e.col0 + col) * e.ld + e.row0 + mp + 8, hi);
         break;
     }
     }

@@ -73,7 +73,8 @@ typedef enum {
 enum {
     ETC_DEBUG_EXEC_COUNT = 1u,   /* count executions of every task */
     ETC_DEBUG_LAYER_HIDDEN = 2u, /* keep the hidden state after every layer */
-    ETC_DEBUG_ROUTING = 4u       /* keep router logits, top-k ids / weights, permutation, indptr */
+    ETC_DEBUG_ROUTING = 4u,      /* keep router logits, top-k ids / weights, permutation, indptr */
+    ETC_DEBUG_TRACE = 8u         /* per-task device timestamps (see ETC_DBG_TASK_TRACE) */
 };
 
 typedef struct {
@@ -154,7 +155,10 @@ typedef enum {
     ETC_DBG_TOPK_W = 6,          /* float[batch, top_k] */
     ETC_DBG_PERMUTATION = 7,     /* int32[batch*top_k]: token*top_k+slot sorted by (expert, token, slot) */
     ETC_DBG_TOK_INDPTR = 8,      /* int32[n_experts+1] prefix sum of tokens per expert */
-    ETC_DBG_EXP_INDPTR = 9       /* int32[n_experts+1] prefix sum of row tiles per expert (Sec. 2.4) */
+    ETC_DBG_EXP_INDPTR = 9,      /* int32[n_experts+1] prefix sum of row tiles per expert (Sec. 2.4) */
+    ETC_DBG_TASK_TRACE = 10      /* uint64[n_tasks][8] device wall-clock ticks of the last launch: 0 task fetched,
+                                    1 events seen, 2 operand staged, 3 streaming done, 4 epilogue done, 5 notified,
+                                    6 unused, 7 queue (workgroup) that ran the task (needs ETC_DEBUG_TRACE) */
 } etc_debug_kind;
 
 etc_status etc_read_debug(etc_ctx *ctx, int32_t kind, int32_t layer, void *host_dst, size_t bytes);
@@ -165,6 +169,8 @@ typedef struct {
     int64_t algorithmic_bytes; /* weights touched once + live KV once + appended rows, this step */
     int32_t sampled_batch;     /* the sampled batch size whose queues serve the bound batch */
     int32_t workgroup_threads;
+    int32_t wall_clock_khz;    /* tick rate of the ETC_DBG_TASK_TRACE timestamps */
+    int32_t reserved;
 } etc_step_info;
 etc_status etc_get_step_info(etc_ctx *ctx, etc_step_info *info);
 

@@ -4,6 +4,6 @@ Argument marshalling only.  Every step of the decode path runs in the HIP librar
 ``libetc.so``; there is no Python or CPU fallback: a missing library raises.
 """
 from .binding import (  # noqa: F401
-    DEBUG_EXEC_COUNT, DEBUG_LAYER_HIDDEN, DEBUG_ROUTING, SCHED_DYNAMIC, SCHED_STATIC, SCHED_UNFUSED,
+    DEBUG_EXEC_COUNT, DEBUG_LAYER_HIDDEN, DEBUG_ROUTING, DEBUG_TRACE, SCHED_DYNAMIC, SCHED_STATIC, SCHED_UNFUSED,
     Decoder, EtcError, EventGraph, lib, lib_path, plan_build,
 )

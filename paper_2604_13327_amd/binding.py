@@ -14,9 +14,9 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
 SCHED_STATIC, SCHED_DYNAMIC, SCHED_UNFUSED = 0, 1, 2
-DEBUG_EXEC_COUNT, DEBUG_LAYER_HIDDEN, DEBUG_ROUTING = 1, 2, 4
+DEBUG_EXEC_COUNT, DEBUG_LAYER_HIDDEN, DEBUG_ROUTING, DEBUG_TRACE = 1, 2, 4, 8
 (DBG_ERROR_WORD, DBG_EVENT_COUNTERS, DBG_TASK_EXEC_COUNT, DBG_LAYER_HIDDEN, DBG_ROUTER_LOGITS, DBG_TOPK_IDS,
- DBG_TOPK_W, DBG_PERMUTATION, DBG_TOK_INDPTR, DBG_EXP_INDPTR) = range(10)
+ DBG_TOPK_W, DBG_PERMUTATION, DBG_TOK_INDPTR, DBG_EXP_INDPTR, DBG_TASK_TRACE) = range(11)
 FN_ROWSUM_PARTIAL, FN_ROWSUM_FINAL = 1, 2
 MAP_DIM, MAP_CONST = 0, 1
 
@@ -54,7 +54,8 @@ class LayerWeights(C.Structure):
 
 class StepInfo(C.Structure):
     _fields_ = [("n_tasks", C.c_int64), ("n_events", C.c_int64), ("n_queues", C.c_int64),
-                ("algorithmic_bytes", C.c_int64), ("sampled_batch", C.c_int32), ("workgroup_threads", C.c_int32)]
+                ("algorithmic_bytes", C.c_int64), ("sampled_batch", C.c_int32), ("workgroup_threads", C.c_int32),
+                ("wall_clock_khz", C.c_int32), ("reserved", C.c_int32)]
 
 
 class DimExpr(C.Structure):
@@ -261,6 +262,10 @@ class Decoder(_Ctx):
 
     def exec_counts(self):
         return self.read_debug(DBG_TASK_EXEC_COUNT, 0, np.zeros(self.step_info().n_tasks, np.int32))
+
+    def task_trace(self):
+        """uint64 [n_tasks, 8] device wall-clock marks of the last launch (needs DEBUG_TRACE)."""
+        return self.read_debug(DBG_TASK_TRACE, 0, np.zeros((self.step_info().n_tasks, 8), np.uint64))
 
     def layer_hidden(self, layer: int):
         return self.read_debug(DBG_LAYER_HIDDEN, layer, np.zeros((self.batch, self.shape.H), np.float32))

@@ -155,6 +155,7 @@ etc_status alloc_events_and_queue(etc_ctx *c)
     c->n_events_max = (int)n_ev;
     HIP_TRY(c, dev_alloc(&c->d_events, 3 * n_ev, c->plan_owned));
     if (c->sched.debug_flags & ETC_DEBUG_EXEC_COUNT) HIP_TRY(c, dev_alloc(&c->base.exec_count, n_tasks + 65536, c->plan_owned));
+    if (c->sched.debug_flags & ETC_DEBUG_TRACE) HIP_TRY(c, dev_alloc(&c->base.trace, n_tasks * 8, c->plan_owned));
     c->base.q_capacity = (int)(n_tasks + 65536 + c->n_queues);
     HIP_TRY(c, dev_alloc(&c->base.q_slots, (size_t)c->base.q_capacity, c->plan_owned));
     return ETC_OK;
@@ -301,9 +302,6 @@ etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc
     ModelDims &d = c->dims;
     d = ModelDims{m->n_layers, m->hidden, m->n_q_heads, m->n_kv_heads, m->head_dim, m->ffn, m->n_experts,
                   m->top_k, m->moe_ffn, m->page_size, t->kv_chunk_tokens, std::max(1, t->moe_tile_m)};
-    std::string gerr = build_decoder_graph(d, s->kind != ETC_SCHED_DYNAMIC, &c->graph);
-    if (!gerr.empty()) { c->err = gerr; return bail(ETC_EINVAL); }
-
     etc_status st = common_device_setup(c, s);
     if (st != ETC_OK) return bail(st);
     c->max_chunks = (s->max_kv_len + t->kv_chunk_tokens - 1) / t->kv_chunk_tokens;
@@ -314,7 +312,9 @@ etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc
         DevPlan &dp = c->plans.back();
         dp.sampled_batch = s->sampled_batch[i];
         int syms[4] = {dp.sampled_batch, c->max_chunks, 0, 0};
-        std::string err = instantiate(c->graph, syms, c->n_queues, s->kind == ETC_SCHED_UNFUSED, &dp.host);
+        std::string err = build_decoder_graph(d, dp.sampled_batch, c->n_queues, s->kind != ETC_SCHED_DYNAMIC, &c->graph);
+        if (!err.empty()) { c->err = err; return bail(ETC_EINVAL); }
+        err = instantiate(c->graph, syms, c->n_queues, s->kind == ETC_SCHED_UNFUSED, &dp.host);
         if (!err.empty()) { c->err = err; return bail(ETC_EINVAL); }
         st = upload_plan(c, dp);
         if (st != ETC_OK) return bail(st);
@@ -514,6 +514,9 @@ etc_status etc_read_debug(etc_ctx *c, int32_t kind, int32_t layer, void *dst, si
     case ETC_DBG_TASK_EXEC_COUNT:
         if (!P.exec_count || c->cur_plan < 0) return fail(c, ETC_ESTATE, "exec counting is off");
         src = P.exec_count; avail = c->plans[c->cur_plan].host.tasks.size() * sizeof(int32_t); break;
+    case ETC_DBG_TASK_TRACE:
+        if (!P.trace || c->cur_plan < 0) return fail(c, ETC_ESTATE, "task tracing is off");
+        src = P.trace; avail = c->plans[c->cur_plan].host.tasks.size() * 8 * sizeof(uint64_t); break;
     case ETC_DBG_LAYER_HIDDEN:
         if (!P.layer_hidden) return fail(c, ETC_ESTATE, "layer dump is off");
         if (layer < 0 || layer >= c->model.n_layers) return fail(c, ETC_EINVAL, "layer out of range");
@@ -540,6 +543,10 @@ etc_status etc_get_step_info(etc_ctx *c, etc_step_info *info)
     info->algorithmic_bytes = c->algorithmic_bytes;
     info->sampled_batch = dp.sampled_batch;
     info->workgroup_threads = kWgThreads;
+    info->reserved = 0;
+    int dev = 0, khz = 0;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev);
+    info->wall_clock_khz = khz;
     return ETC_OK;
 }
 
@@ -555,7 +562,7 @@ etc_status etc_plan_build(const etc_model_desc *m, const etc_tile_desc *t, const
     ModelDims d{m->n_layers, m->hidden, m->n_q_heads, m->n_kv_heads, m->head_dim, m->ffn, m->n_experts,
                 m->top_k, m->moe_ffn, m->page_size, t->kv_chunk_tokens, std::max(1, t->moe_tile_m)};
     GraphDecl g;
-    std::string err = build_decoder_graph(d, s->kind != ETC_SCHED_DYNAMIC, &g);
+    std::string err = build_decoder_graph(d, sampled_batch, n_queues, s->kind != ETC_SCHED_DYNAMIC, &g);
     if (!err.empty()) return fail(nullptr, ETC_EINVAL, err);
     Plan *p = new (std::nothrow) Plan();
     if (!p) return fail(nullptr, ETC_ENOMEM, "out of host memory");
@@ -666,6 +673,7 @@ etc_status etc_graph_bind_shape(etc_ctx *c, const int32_t *values)
     for (void *p : c->plan_owned) (void)hipFree(p);
     c->plan_owned.clear();
     c->base.exec_count = nullptr;
+    c->base.trace = nullptr;
     c->step_bound = false;
     c->plans.clear();
     etc_status st = upload_plan(c, dp);

@@ -134,9 +134,14 @@ __device__ __forceinline__ void wg_wait(const Params &P, int ev0, int ev1, int f
 }
 
 // Before a notify: every thread drains its (write-through) stores, then the workgroup meets.
+// s_waitcnt vmcnt(0) as a builtin (not inline asm), so that the compiler's own wait-count bookkeeping
+// knows nothing is outstanding afterwards: only then can it keep fine-grained vmcnt(N) waits inside the
+// weight-streaming loops instead of draining at every loop header.
+__device__ __forceinline__ void drain_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 __device__ __forceinline__ void wg_release()
 {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    drain_vmem();
     __syncthreads();
 }
 
@@ -144,6 +149,13 @@ __device__ __forceinline__ void wg_release()
 __device__ __forceinline__ int ev_notify(const Params &P, int ev)
 {
     return __hip_atomic_fetch_sub(as_global(P.ev_cur + ev), 1, __ATOMIC_RELAXED, ETC_SCOPE);
+}
+
+// Per-task trace mark (debug): thread 0 stamps the device wall clock.
+__device__ __forceinline__ void trace_mark(const Params &P, int task_id, int slot)
+{
+    if (P.trace != nullptr && threadIdx.x == 0 && task_id >= 0)
+        as_global(P.trace)[(size_t)task_id * 8 + slot] = slot == 7 ? (uint64_t)blockIdx.x : (uint64_t)wall_clock64();
 }
 
 __device__ __forceinline__ float wave_sum(float v)

@@ -9,6 +9,10 @@ constexpr int kWaves = kWgThreads / 64;
 constexpr int kMaxBatch = 64;
 constexpr int kMaxLayers = 128;
 constexpr int kLdsBytes = 148 * 1024;    // of the 160 KB LDS per CU: exactly one persistent workgroup per CU
+constexpr int kRedFloats = kWaves * 4 * 64 * 4;   // LDS: cross-wave reduction buffer (32 KB)
+constexpr int kRsFloats = 64;                     // LDS: RMSNorm factors of the columns
+constexpr int kOperandBytes = kLdsBytes - (kRedFloats + kRsFloats) * 4;   // LDS left for a staged operand
+constexpr int kStagedMaxCols = 16;                // widest batch the staged (latency-critical) projection path takes
 
 // Device functions (task bodies).  One entry of the dispatch switch each (Alg. 1 "dispatch logic").
 enum Fn : uint8_t {
@@ -119,6 +123,7 @@ struct Params {
     int32_t *exec_count;
     float *layer_hidden;               // [n_layers, maxB, H]
     int32_t *error_word;               // [4]
+    uint64_t *trace;                   // [n_tasks][8] wall-clock marks, or null
     // generic-graph buffers (row-sum example)
     float *gbuf[4];
     int32_t gsym[4];

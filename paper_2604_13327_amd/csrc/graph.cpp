@@ -97,9 +97,11 @@ std::string instantiate(const GraphDecl &g, const int *sym, int n_queues, bool u
             t.fn = (uint8_t)c.fn;
             t.layer = (uint8_t)c.layer;
             t.flags = c.flags;
-            t.c0 = coord[0] + c.c_off[0];
-            t.c1 = coord[1] + c.c_off[1];
-            t.c2 = coord[2] + c.c_off[2];
+            int tc[3];
+            for (int k = 0; k < 3; ++k) tc[k] = k < c.rank ? coord[k] * c.c_mul[k] + c.c_off[k] : c.c_fill[k];
+            t.c0 = tc[0];
+            t.c1 = tc[1];
+            t.c2 = tc[2];
             t.wait0 = t.wait1 = t.notify0 = -1;
             t.id = (int32_t)p.tasks.size();
             if (unfused) {
@@ -158,7 +160,7 @@ std::string instantiate(const GraphDecl &g, const int *sym, int n_queues, bool u
     return "";
 }
 
-std::string build_decoder_graph(const ModelDims &m, bool moe_static_coarse, GraphDecl *out)
+std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool moe_static_coarse, GraphDecl *out)
 {
     (void)moe_static_coarse;
     GraphDecl &g = *out;
@@ -172,6 +174,23 @@ std::string build_decoder_graph(const ModelDims &m, bool moe_static_coarse, Grap
     const int grp = m.nq / m.nkv;
     const int sub = m.d / 16;                     // 16-row tiles (8 RoPE pairs) per head
     const DimExpr B = dim_sym(0), NCH = dim_sym(1), one = dim_const(1);
+
+    // Row tiles per projection task.  When the batch is small enough for the staged path, a task
+    // streams several consecutive tiles back to back (one reduction, one notify), sized so that a
+    // stage is about one task per queue.
+    auto staged_ok = [&](int K) {
+        return Bs <= kStagedMaxCols && (long long)Bs * K * 4 <= (long long)kOperandBytes;
+    };
+    int r_qkv = 1, r_gu = 1;
+    if (staged_ok(m.H)) {
+        if ((m.nq + 2 * m.nkv) * sub > n_queues && sub % 2 == 0 && 2 * Bs * kWaves * 16 <= kRedFloats) r_qkv = 2;
+        if (m.E == 0) {
+            const int tiles = m.F / 8, per_slice = tiles / kWaves;
+            int cand = tiles / std::max(1, n_queues);
+            while (cand > 1 && (tiles % cand || per_slice % cand || cand * Bs * kWaves * 16 > kRedFloats)) --cand;
+            r_gu = std::max(1, cand);
+        }
+    }
 
     int stage = 0;
     int e_x = g.add_event({one});
@@ -195,9 +214,11 @@ std::string build_decoder_graph(const ModelDims &m, bool moe_static_coarse, Grap
         for (int part = 0; part < 3; ++part) {
             CallDecl c;
             c.fn = FN_QKV; c.layer = l; c.stage = stage;
-            c.rank = 2;
+            c.rank = 2;                                    // task record: (head, first 16-row tile of the head, tiles)
             c.shape[0] = dim_const(part == 0 ? m.nq : m.nkv);
-            c.shape[1] = dim_const(sub);
+            c.shape[1] = dim_const(sub / r_qkv);
+            c.c_mul[1] = r_qkv;
+            c.c_fill[2] = r_qkv;
             c.c_off[0] = part == 0 ? 0 : (part == 1 ? m.nq : m.nq + m.nkv);
             c.in = {edge_const0(e_x)};
             c.out = {edge_dim(e_qkv, 0, part == 0 ? grp : 1)};
@@ -234,10 +255,12 @@ std::string build_decoder_graph(const ModelDims &m, bool moe_static_coarse, Grap
             const int tiles = m.F / 8;
             {
                 CallDecl c;
-                c.fn = FN_GATEUP; c.layer = l; c.stage = stage++;
-                c.rank = 1; c.shape[0] = dim_const(tiles);
+                c.fn = FN_GATEUP; c.layer = l; c.stage = stage++;    // task record: (first tile, tiles)
+                c.rank = 1; c.shape[0] = dim_const(tiles / r_gu);
+                c.c_mul[0] = r_gu;
+                c.c_fill[1] = r_gu;
                 c.in = {edge_const0(e_xmid)};
-                c.out = {edge_dim(e_act, 0, tiles / kWaves)};   // K slice of the down projection it feeds
+                c.out = {edge_dim(e_act, 0, tiles / kWaves / r_gu)};   // K slice of the down projection it feeds
                 g.calls.push_back(c);
             }
             {

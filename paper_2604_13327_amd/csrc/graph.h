@@ -45,7 +45,9 @@ struct CallDecl {
     int stage = 0;                     // operator stage (calls of one stage may run concurrently)
     DimExpr shape[3];
     int rank = 1;
-    int c_off[3] = {0, 0, 0};          // added to the task coordinate stored in the Task record
+    int c_mul[3] = {1, 1, 1};          // Task record coordinate = grid coordinate * c_mul + c_off ...
+    int c_off[3] = {0, 0, 0};
+    int c_fill[3] = {0, 0, 0};         // ... and c_fill for the coordinates beyond the grid's rank
     bool last_dim_slowest = false;     // enumeration order (balances ragged grids across queues)
     uint16_t flags = 0;
     std::vector<EdgeMap> in, out;      // at most 2 in-edges, 1 out-edge
@@ -79,9 +81,12 @@ struct ModelDims {
     int kv_chunk, tile_m;
 };
 
-// The decoder's graph function.  Symbol 0 = sampled batch size, symbol 1 = chunk slots per sequence.
+// The decoder's graph function for one sampled batch size.  Symbol 0 = that batch size, symbol 1 =
+// chunk slots per sequence.  n_queues and the batch decide how many consecutive row tiles one
+// projection task streams (tile shapes are a degree of freedom of the graph, Sec. 2.1).
 // moe_static_coarse: static scheduling of the data-dependent MoE stages through one coarse event
 // ("E[0]" rewrite of Sec. 3.1).
-std::string build_decoder_graph(const ModelDims &m, bool moe_static_coarse, GraphDecl *out);
+std::string build_decoder_graph(const ModelDims &m, int sampled_batch, int n_queues, bool moe_static_coarse,
+                                GraphDecl *out);
 
 }  // namespace etc

@@ -67,8 +67,9 @@ __device__ __forceinline__ bool setup_gemm(const Params &P, const Task &t, GemmT
     const ETC_AS_GLOBAL LayerWeights *W = as_global(P.weights) + t.layer;
     switch (t.fn) {
     case FN_QKV: {
-        const int hd = t.c0, sub = t.c1;
+        const int hd = t.c0, sub = t.c1;               // c2 = consecutive tiles of this head
         const int i0 = sub * 8;
+        g.n_tiles = t.c2; g.tile_rows = 8;
         const uint16_t *wbase;
         if (hd < P.nq) wbase = (const uint16_t *)W->wq + (size_t)hd * P.d * P.H;
         else if (hd < P.nq + P.nkv) wbase = (const uint16_t *)W->wk + (size_t)(hd - P.nq) * P.d * P.H;
@@ -84,6 +85,7 @@ __device__ __forceinline__ bool setup_gemm(const Params &P, const Task &t, GemmT
     }
     case FN_OPROJ: {
         const int r0 = t.c0 * 16, QD = P.nq * P.d;
+        g.n_tiles = 1; g.tile_rows = 16;
         g.rowsA = (const uint16_t *)W->wo + (size_t)r0 * QD;
         g.rowsB = g.rowsA + (size_t)8 * QD;
         g.ldw = QD; g.K = QD;
@@ -95,7 +97,8 @@ __device__ __forceinline__ bool setup_gemm(const Params &P, const Task &t, GemmT
         return true;
     }
     case FN_GATEUP: {
-        const int f0 = t.c0 * 8;
+        const int f0 = t.c0 * 8;                       // c1 = consecutive tiles
+        g.n_tiles = t.c1; g.tile_rows = 8;
         g.rowsA = (const uint16_t *)W->wg + (size_t)f0 * P.H;
         g.rowsB = (const uint16_t *)W->wu + (size_t)f0 * P.H;
         g.ldw = P.H; g.K = P.H;
@@ -107,6 +110,7 @@ __device__ __forceinline__ bool setup_gemm(const Params &P, const Task &t, GemmT
     }
     case FN_DOWN: {
         const int r0 = t.c0 * 16;
+        g.n_tiles = 1; g.tile_rows = 16;
         g.rowsA = (const uint16_t *)W->wd + (size_t)r0 * P.F;
         g.rowsB = g.rowsA + (size_t)8 * P.F;
         g.ldw = P.F; g.K = P.F;
@@ -243,12 +247,16 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_static(const Params P)
         Task tn{};
         tn.id = -1;
         if (i + 1 < q1) tn = load_task(P.tasks + i + 1);
+        trace_mark(P, t.id, 0);
+        trace_mark(P, t.id, 7);
         run_task<true>(P, sP, t, tn, sm, st);
+        trace_mark(P, t.id, 4);
         wg_release();
         if (threadIdx.x == 0) {
             if (t.notify0 >= 0) ev_notify(P, t.notify0);
             if (P.debug_flags & 1u) atomicAdd(P.exec_count + t.id, 1);
         }
+        trace_mark(P, t.id, 5);
         t = tn;
     }
 }

@@ -46,44 +46,62 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
         for (int i = 0; i < 8; ++i) o[g][i] = 0.f;
     }
 
-    for (int jb = j0 + wave * TPW; jb < j1; jb += kWaves * TPW) {   // uniform trip count per wave
-        const int j = jb + tq;
-        const bool valid = j < j1;
-        const int jc = valid ? j : j1 - 1;
-        const int page = gld_i32(pages + jc / P.page);
-        const size_t off = lbase + (((size_t)page * P.page + (size_t)(jc % P.page)) * P.nkv + kvh) * (size_t)D + dl * 8;
-        u32x4 kr, vr;
-        if (jc == n_keys - 1) {          // the row this step appended: written by another task of this launch
-            kr = ld_16B(P.kpool + off);
-            vr = ld_16B(P.vpool + off);
-        } else {
-            kr = gld_16B(P.kpool + off);
-            vr = gld_16B(P.vpool + off);
+    // Keys are taken in batches of BATCH wavefront steps: the page ids of a batch are read first, then all
+    // its K and V rows are requested, then the arithmetic runs, so a batch costs two memory round trips.
+    constexpr int BATCH = 4;
+    for (int jb0 = j0 + wave * TPW; jb0 < j1; jb0 += BATCH * kWaves * TPW) {   // uniform trip count per wave
+        int page[BATCH];
+        bool val[BATCH];
+        int jcs[BATCH];
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int j = jb0 + u * kWaves * TPW + tq;
+            val[u] = j < j1;
+            jcs[u] = val[u] ? j : j1 - 1;
+            page[u] = gld_i32(pages + jcs[u] / P.page);
         }
-        float kf[8], vf[8];
-        kf[0] = bf16_bits_to_f32(kr.x & 0xFFFFu); kf[1] = bf16_bits_to_f32(kr.x >> 16);
-        kf[2] = bf16_bits_to_f32(kr.y & 0xFFFFu); kf[3] = bf16_bits_to_f32(kr.y >> 16);
-        kf[4] = bf16_bits_to_f32(kr.z & 0xFFFFu); kf[5] = bf16_bits_to_f32(kr.z >> 16);
-        kf[6] = bf16_bits_to_f32(kr.w & 0xFFFFu); kf[7] = bf16_bits_to_f32(kr.w >> 16);
-        vf[0] = bf16_bits_to_f32(vr.x & 0xFFFFu); vf[1] = bf16_bits_to_f32(vr.x >> 16);
-        vf[2] = bf16_bits_to_f32(vr.y & 0xFFFFu); vf[3] = bf16_bits_to_f32(vr.y >> 16);
-        vf[4] = bf16_bits_to_f32(vr.z & 0xFFFFu); vf[5] = bf16_bits_to_f32(vr.z >> 16);
-        vf[6] = bf16_bits_to_f32(vr.w & 0xFFFFu); vf[7] = bf16_bits_to_f32(vr.w >> 16);
+        u32x4 krs[BATCH], vrs[BATCH];
 #pragma unroll
-        for (int g = 0; g < GRP; ++g) {
-            float s = 0.f;
+        for (int u = 0; u < BATCH; ++u) {
+            const size_t off = lbase + (((size_t)page[u] * P.page + (size_t)(jcs[u] % P.page)) * P.nkv + kvh) * (size_t)D + dl * 8;
+            if (jcs[u] == n_keys - 1) {      // the row this step appended: written by another task of this launch
+                krs[u] = ld_16B(P.kpool + off);
+                vrs[u] = ld_16B(P.vpool + off);
+            } else {
+                krs[u] = gld_16B(P.kpool + off);
+                vrs[u] = gld_16B(P.vpool + off);
+            }
+        }
 #pragma unroll
-            for (int i = 0; i < 8; ++i) s += q[g][i] * kf[i];
+        for (int u = 0; u < BATCH; ++u) {
+            if (jb0 + u * kWaves * TPW >= j1) break;     // uniform per wave
+            const bool valid = val[u];
+            const u32x4 kr = krs[u], vr = vrs[u];
+            float kf[8], vf[8];
+            kf[0] = bf16_bits_to_f32(kr.x & 0xFFFFu); kf[1] = bf16_bits_to_f32(kr.x >> 16);
+            kf[2] = bf16_bits_to_f32(kr.y & 0xFFFFu); kf[3] = bf16_bits_to_f32(kr.y >> 16);
+            kf[4] = bf16_bits_to_f32(kr.z & 0xFFFFu); kf[5] = bf16_bits_to_f32(kr.z >> 16);
+            kf[6] = bf16_bits_to_f32(kr.w & 0xFFFFu); kf[7] = bf16_bits_to_f32(kr.w >> 16);
+            vf[0] = bf16_bits_to_f32(vr.x & 0xFFFFu); vf[1] = bf16_bits_to_f32(vr.x >> 16);
+            vf[2] = bf16_bits_to_f32(vr.y & 0xFFFFu); vf[3] = bf16_bits_to_f32(vr.y >> 16);
+            vf[4] = bf16_bits_to_f32(vr.z & 0xFFFFu); vf[5] = bf16_bits_to_f32(vr.z >> 16);
+            vf[6] = bf16_bits_to_f32(vr.w & 0xFFFFu); vf[7] = bf16_bits_to_f32(vr.w >> 16);
 #pragma unroll
-            for (int off2 = 1; off2 < LPT; off2 <<= 1) s += __shfl_xor(s, off2, 64);
-            if (valid) {
-                const float nm = fmaxf(mx[g], s);
-                const float sc = __expf(mx[g] - nm);      // exp(-inf) = 0 on the first key
-                const float p = __expf(s - nm);
-                l[g] = l[g] * sc + p;
+            for (int g = 0; g < GRP; ++g) {
+                float s = 0.f;
 #pragma unroll
-                for (int i = 0; i < 8; ++i) o[g][i] = o[g][i] * sc + p * vf[i];
-                mx[g] = nm;
+                for (int i = 0; i < 8; ++i) s += q[g][i] * kf[i];
+#pragma unroll
+                for (int off2 = 1; off2 < LPT; off2 <<= 1) s += __shfl_xor(s, off2, 64);
+                if (valid) {
+                    const float nm = fmaxf(mx[g], s);
+                    const float sc = __expf(mx[g] - nm);      // exp(-inf) = 0 on the first key
+                    const float p = __expf(s - nm);
+                    l[g] = l[g] * sc + p;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) o[g][i] = o[g][i] * sc + p * vf[i];
+                    mx[g] = nm;
+                }
             }
         }
     }
@@ -148,13 +166,27 @@ __device__ __noinline__ void attn_merge(const Params &P, int b, int kvh)
         const int g = idx / D, i = idx % D;
         const int h = kvh * GRP + g;
         const size_t p0 = ((size_t)b * P.nq + h) * (size_t)P.max_chunks;
-        float m = -INFINITY;
-        for (int c = 0; c < nc; ++c) m = fmaxf(m, ld_f32(P.part_m + p0 + c));
-        float num = 0.f, den = 0.f;
-        for (int c = 0; c < nc; ++c) {                 // ascending chunk order
-            const float sc = __expf(ld_f32(P.part_m + p0 + c) - m);
-            num += sc * ld_f32(P.part_o + (p0 + c) * D + i);
-            den += sc * ld_f32(P.part_l + p0 + c);
+        // one pass in ascending chunk order, 8 chunks' loads in flight at a time, running max rescaling
+        float m = -INFINITY, num = 0.f, den = 0.f;
+        for (int c0 = 0; c0 < nc; c0 += 8) {
+            float pm[8], pl[8], po[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int c = c0 + u < nc ? c0 + u : nc - 1;
+                pm[u] = ld_f32(P.part_m + p0 + c);
+                pl[u] = ld_f32(P.part_l + p0 + c);
+                po[u] = ld_f32(P.part_o + (p0 + c) * D + i);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (c0 + u < nc) {
+                    const float nm = fmaxf(m, pm[u]);
+                    const float sa = __expf(m - nm), sb = __expf(pm[u] - nm);
+                    num = num * sa + sb * po[u];
+                    den = den * sa + sb * pl[u];
+                    m = nm;
+                }
+            }
         }
         uint16_t hi, lo;                               // operand of the O projection: split bf16
         split_bf16(num / den, hi, lo);

@@ -35,6 +35,8 @@ struct GemmTile {
     const float *ssq_parts;          // RMSNorm: partial sums of squares [n_parts][kMaxBatch], or null
     int n_parts;
     float eps;
+    int n_tiles;                     // consecutive 16-row tiles this task streams back to back
+    int tile_rows;                   // rows between consecutive tiles inside each 8-row group (8 or 16)
 };
 
 constexpr uint16_t EPF_DUMP_LAYER = 0x8000;   // epilogue also records the layer's hidden state
@@ -56,9 +58,6 @@ struct Epilogue {
     int col0;                 // MoE: first destination row (permuted row of column 0)
 };
 
-constexpr int kRedFloats = kWaves * 4 * 64 * 4;   // cross-wave reduction buffer (32 KB)
-constexpr int kRsFloats = 64;                     // RMSNorm factors of the columns
-constexpr int kOperandBytes = kLdsBytes - (kRedFloats + kRsFloats) * 4;   // LDS left for a staged operand
 constexpr int PF = 16;                            // weight loads in flight per lane (16 KB per wave)
 
 __device__ __forceinline__ u32x4 load16_nt(const uint16_t *p) { return gld_16B_nt(p); }
@@ -76,6 +75,7 @@ struct TaskWaits {
 struct WgState {
     u32x4 wr[PF];        // weight fragments in flight: steps 0..PF-1 of task `wr_task` sit in slots 0..PF-1
     int wr_task;         // -1: nothing prefetched
+    int wr_n;            // how many leading slots of that task are in flight
     int zero0, zero1;    // events already seen at zero in this launch (they never re-arm inside a launch)
     int staged_key;      // event that gates the operand currently staged in LDS (-1: none)
 };
@@ -85,6 +85,7 @@ __device__ __forceinline__ void wg_state_init(WgState &st)
 #pragma unroll
     for (int j = 0; j < PF; ++j) st.wr[j] = u32x4{0, 0, 0, 0};
     st.wr_task = -1;
+    st.wr_n = 0;
     st.zero0 = st.zero1 = -1;
     st.staged_key = -1;
 }
@@ -116,13 +117,11 @@ __device__ __forceinline__ void wg_wait_cached(const Params &P, WgState &st, int
     if (need1) { st.zero1 = st.zero0; st.zero0 = ev1; }
 }
 
-// STAGED: the whole operand (all columns, full K, hi and lo) is copied once into LDS with device-scope
-// loads and reused by every tile of the same stage that this workgroup runs; otherwise operand
-// fragments come straight from memory through a 2-deep register ring.
-template <int NB, bool STAGED>
-__device__ __forceinline__ void gemm_tile_run(const Params &P, const GemmTile &g, const Epilogue &e, const TaskWaits &w,
-                                              float *sm, WgState &st, int task_id, const uint16_t *wnext, int n_it_next,
-                                              int next_task_id)
+// Out-of-line path: one tile at a time, operand fragments straight from memory through a 2-deep
+// register ring, any batch width.  No cross-task state.
+template <int NB>
+__device__ __forceinline__ void gemm_tile_unstaged(const Params &P, const GemmTile &g, const Epilogue &e,
+                                                   const TaskWaits &w, float *sm, bool first_tile)
 {
     const int wave = wave_id(), lane = lane_id();
     const int m = lane & 15, kg = lane >> 4;
@@ -130,75 +129,37 @@ __device__ __forceinline__ void gemm_tile_run(const Params &P, const GemmTile &g
     const int kbase = wave * Kw + kg * 8;
     const uint16_t *wrow = lane_weight_row(g);
 
-    // ---- weight prefetch: before the wait (unless the previous task already streamed it in) ----
-    if (st.wr_task != task_id) {
+    u32x4 wr[PF];
 #pragma unroll
-        for (int j = 0; j < PF; ++j) {
-            if (j < n_it) st.wr[j] = load16_nt(wrow + j * 32);
-            else st.wr[j] = u32x4{0, 0, 0, 0};
+    for (int j = 0; j < PF; ++j) {
+        if (j < n_it) wr[j] = load16_nt(wrow + j * 32);
+        else wr[j] = u32x4{0, 0, 0, 0};
+    }
+    if (first_tile) {
+        if (w.per_wave) {
+            wave_wait(P, w.ev0 + wave, w.fn);
+            wave_wait(P, w.ev1, w.fn);
+        } else {
+            wg_wait(P, w.ev0, w.ev1, w.fn);
         }
     }
-    st.wr_task = -1;
-
     ETC_AS_LDS float *red = as_lds(sm);
     ETC_AS_LDS float *rs = red + kRedFloats;
-    ETC_AS_LDS uint16_t *op_hi = reinterpret_cast<ETC_AS_LDS uint16_t *>(red + kRedFloats + kRsFloats);
-    ETC_AS_LDS uint16_t *op_lo = op_hi + (size_t)g.n_cols * g.K;
 
-    // ---- E.wait() -------------------------------------------------------------------------
-    if (STAGED) {
-        const int key = w.ev0;
-        if (key < 0 || key != st.staged_key) {
-            if (w.per_wave) {           // the staged copy needs every K slice: lanes 0..7 of wave 0 poll one slice each
-                if (wave == 0 && lane < kWaves) spin_until_zero(P, w.ev0 + lane, w.fn);
-                if (threadIdx.x == 0 && w.ev1 >= 0) spin_until_zero(P, w.ev1, w.fn);
-                __syncthreads();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-            } else {
-                wg_wait_cached(P, st, w.ev0, w.ev1, w.fn);
-            }
-            const int quads = g.K >> 2;                         // 8-byte pieces per column
-            for (int idx = threadIdx.x; idx < g.n_cols * quads; idx += kWgThreads) {
-                const int col = idx / quads, q = idx - col * quads;
-                int row = g.col_rows ? ld_i32(g.col_rows + col) : col;
-                if (row < 0) row = 0;
-                const uint64_t vh = ld_u64(g.b_hi + (size_t)row * (size_t)g.ldb + q * 4);
-                const uint64_t vl = ld_u64(g.b_lo + (size_t)row * (size_t)g.ldb + q * 4);
-                *reinterpret_cast<ETC_AS_LDS uint64_t *>(op_hi + (size_t)col * g.K + q * 4) = vh;
-                *reinterpret_cast<ETC_AS_LDS uint64_t *>(op_lo + (size_t)col * g.K + q * 4) = vl;
-            }
-            st.staged_key = key;
-            // (the barrier below, after the norm factors, publishes the staged operand)
-        } else {
-            wg_wait_cached(P, st, w.ev1, -1, w.fn);
-        }
-    } else if (w.per_wave) {
-        wave_wait(P, w.ev0 + wave, w.fn);
-        wave_wait(P, w.ev1, w.fn);
-    } else {
-        wg_wait_cached(P, st, w.ev0, w.ev1, w.fn);
-    }
-
-    // ---- operand columns of this lane -------------------------------------------------------
-    const uint16_t *bh[NB], *bl[NB];                 // unstaged: operand rows in memory
-    ETC_AS_LDS const uint16_t *sh[NB], *sl[NB];      // staged: operand rows in LDS
+    const uint16_t *bh[NB], *bl[NB];
     bool valid[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         const int col = nb * 16 + m;
         int row = col;
         valid[nb] = col < g.n_cols;
-        if (!STAGED && valid[nb] && g.col_rows) row = ld_i32(g.col_rows + col);
+        if (valid[nb] && g.col_rows) row = ld_i32(g.col_rows + col);
         if (row < 0) valid[nb] = false;
         if (!valid[nb]) row = 0;
-        sh[nb] = op_hi + (size_t)row * (size_t)g.K + kbase;
-        sl[nb] = op_lo + (size_t)row * (size_t)g.K + kbase;
         bh[nb] = g.b_hi + (size_t)row * (size_t)g.ldb + kbase;
         bl[nb] = g.b_lo + (size_t)row * (size_t)g.ldb + kbase;
     }
-
-    // RMSNorm factor of every column: fixed-order sum of the producers' partial sums of squares
-    if (g.ssq_parts) {
+    if (g.ssq_parts) {   // RMSNorm factor of every column: fixed-order sum of the producers' partial sums of squares
         for (int col = wave; col < g.n_cols; col += kWaves) {
             const int row = g.col_rows ? ld_i32(g.col_rows + col) : col;
             float s = 0.f;
@@ -208,9 +169,6 @@ __device__ __forceinline__ void gemm_tile_run(const Params &P, const GemmTile &g
             if (lane == 0) rs[col] = 1.0f / sqrtf(s / (float)g.K + g.eps);
         }
     }
-    if (STAGED) __syncthreads();
-
-    // ---- operand ring (depth 2) for the unstaged path -------------------------------------------
     struct Raw {
         u32x4 h[NB], l[NB];
     };
@@ -220,28 +178,17 @@ __device__ __forceinline__ void gemm_tile_run(const Params &P, const GemmTile &g
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             if (valid[nb]) {
-                if (STAGED) {
-                    r.h[nb] = *reinterpret_cast<ETC_AS_LDS const u32x4 *>(sh[nb] + k);
-                    r.l[nb] = *reinterpret_cast<ETC_AS_LDS const u32x4 *>(sl[nb] + k);
-                } else {
-                    r.h[nb] = ld_16B(bh[nb] + k);
-                    r.l[nb] = ld_16B(bl[nb] + k);
-                }
+                r.h[nb] = ld_16B(bh[nb] + k);
+                r.l[nb] = ld_16B(bl[nb] + k);
             } else {
                 r.h[nb] = u32x4{0, 0, 0, 0};
                 r.l[nb] = u32x4{0, 0, 0, 0};
             }
         }
     };
-
     f32x4 acc[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0, 0, 0, 0};
-
-    // Weights of the NEXT projection task start streaming while this task's last PF steps are consumed:
-    // the slot freed at step s (slot s % PF) receives the next task's step s % PF, so that task finds its
-    // steps 0..PF-1 in slots 0..PF-1 whatever this task's length is.
-    const bool cont = wnext != nullptr && n_it >= PF;
     fetch(0, ring[0]);
     if (n_it > 1) fetch(1, ring[1]);
     for (int it = 0; it < n_it; it += PF) {
@@ -249,12 +196,8 @@ __device__ __forceinline__ void gemm_tile_run(const Params &P, const GemmTile &g
         for (int j = 0; j < PF; ++j) {
             const int s = it + j;
             if (s < n_it) {
-                const bf16x8 a = __builtin_bit_cast(bf16x8, st.wr[j]);
-                if (s + PF < n_it) {
-                    st.wr[j] = load16_nt(wrow + (s + PF) * 32);
-                } else if (cont) {
-                    if (j < n_it_next) st.wr[j] = load16_nt(wnext + j * 32);
-                }
+                const bf16x8 a = __builtin_bit_cast(bf16x8, wr[j]);
+                if (s + PF < n_it) wr[j] = load16_nt(wrow + (s + PF) * 32);
                 Raw &r = ring[j & 1];
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
@@ -265,9 +208,6 @@ __device__ __forceinline__ void gemm_tile_run(const Params &P, const GemmTile &g
             }
         }
     }
-    if (cont) st.wr_task = next_task_id;
-
-    // ---- cross-wave reduction (fixed order) and epilogue -------------------------------------
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
         *reinterpret_cast<ETC_AS_LDS f32x4 *>(red + ((size_t)(wave * NB + nb) * 64 + lane) * 4) = acc[nb];
@@ -289,32 +229,184 @@ __device__ __forceinline__ void gemm_tile_run(const Params &P, const GemmTile &g
         }
         apply_epilogue(P, e, col, mp, lo, hi);
     }
+    __syncthreads();     // the reduction buffer is reused by the next tile
 }
 
-// Wider batches run out of line with their own register budget and no cross-task state (the persistent
-// loop keeps its registers for the small-batch path, which is the latency-critical one).  PL is the
-// workgroup's LDS copy of the parameters: a kernel argument cannot be passed by address.
 template <int NB>
-__device__ __noinline__ void gemm_tile_cold(const Params &PL, GemmTile g, Epilogue e, TaskWaits w, float *sm)
+__device__ __noinline__ void gemm_tiles_cold(const Params &PL, GemmTile g, Epilogue e, TaskWaits w, float *sm)
 {
-    WgState st;
-    wg_state_init(st);
-    gemm_tile_run<NB, false>(PL, g, e, w, sm, st, 0, nullptr, 0, -1);
+    for (int ti = 0; ti < g.n_tiles; ++ti) {
+        gemm_tile_unstaged<NB>(PL, g, e, w, sm, ti == 0);
+        g.rowsA += (size_t)g.tile_rows * g.ldw;
+        g.rowsB += (size_t)g.tile_rows * g.ldw;
+        e.row0 += g.tile_rows;
+        if (e.ssq_out) e.ssq_out += kMaxBatch;
+    }
 }
 
+// Latency-critical path (at most 16 columns whose whole operand fits in LDS).  The operand (all columns,
+// full K, hi and lo) is copied into LDS once per stage with device-scope loads and reused by every
+// tile of that stage this workgroup runs.  A task streams its n_tiles row tiles back to back; the ring
+// of weight fragments never drains between tiles, nor between this task and the next projection task.
+// Each wave parks its partial tile in LDS; one barrier, one reduction and one epilogue per task.
+//
+// A wave's ring of PF weight fragments is refilled as it is consumed: with this tile's later steps, and
+// in a tile's last PF steps with the first steps of whatever follows (the next tile, or the first tile of
+// the next projection task), so the ring is full again when that work starts.  (A variant with
+// unconditional in-place refills, which lets the compiler wait with vmcnt(PF-1) instead of draining at
+// every group of PF steps, was measured and was not faster: a CU sustains ~22-25 GB/s either way, and the
+// epilogues got slower behind the deeper queue.)
+__device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTile &g, const Epilogue &e, const TaskWaits &w,
+                                                  float *sm, WgState &st, int task_id, const uint16_t *wnext,
+                                                  int n_it_next, int next_task_id)
+{
+    const int wave = wave_id(), lane = lane_id();
+    const int m = lane & 15, kg = lane >> 4;
+    const int Kw = g.K / kWaves, n_it = Kw >> 5;
+    const int kbase = wave * Kw + kg * 8;
+    const uint16_t *wcur = lane_weight_row(g);
+    const size_t tile_step = (size_t)g.tile_rows * (size_t)g.ldw;
+
+    // ---- weight prefetch: before the wait (unless the previous task already streamed it in) ----
+    if (st.wr_task != task_id) {
+#pragma unroll
+        for (int j = 0; j < PF; ++j) {
+            if (j < n_it) st.wr[j] = load16_nt(wcur + j * 32);
+            else st.wr[j] = u32x4{0, 0, 0, 0};
+        }
+    }
+    st.wr_task = -1;
+
+    ETC_AS_LDS float *red = as_lds(sm);               // [tile][wave][col][16 rows]
+    ETC_AS_LDS float *rs = red + kRedFloats;
+    ETC_AS_LDS uint16_t *op_hi = reinterpret_cast<ETC_AS_LDS uint16_t *>(red + kRedFloats + kRsFloats);
+    ETC_AS_LDS uint16_t *op_lo = op_hi + (size_t)g.n_cols * g.K;
+
+    // ---- E.wait(), then stage the operand unless this stage's operand is already in LDS ----------
+    const int key = w.ev0;
+    if (key < 0 || key != st.staged_key) {
+        if (w.per_wave) {           // the staged copy needs every K slice: lanes 0..7 of wave 0 poll one slice each
+            if (wave == 0 && lane < kWaves) spin_until_zero(P, w.ev0 + lane, w.fn);
+            if (threadIdx.x == 0 && w.ev1 >= 0) spin_until_zero(P, w.ev1, w.fn);
+            __syncthreads();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        } else {
+            wg_wait_cached(P, st, w.ev0, w.ev1, w.fn);
+        }
+        trace_mark(P, task_id, 1);
+        const int quads = g.K >> 2;                         // 8-byte pieces per column
+        for (int idx = threadIdx.x; idx < g.n_cols * quads; idx += kWgThreads) {
+            const int col = idx / quads, q = idx - col * quads;
+            int row = g.col_rows ? ld_i32(g.col_rows + col) : col;
+            if (row < 0) row = 0;
+            const uint64_t vh = ld_u64(g.b_hi + (size_t)row * (size_t)g.ldb + q * 4);
+            const uint64_t vl = ld_u64(g.b_lo + (size_t)row * (size_t)g.ldb + q * 4);
+            *reinterpret_cast<ETC_AS_LDS uint64_t *>(op_hi + (size_t)col * g.K + q * 4) = vh;
+            *reinterpret_cast<ETC_AS_LDS uint64_t *>(op_lo + (size_t)col * g.K + q * 4) = vl;
+        }
+        if (g.ssq_parts) {
+            for (int col = wave; col < g.n_cols; col += kWaves) {
+                const int row = g.col_rows ? ld_i32(g.col_rows + col) : col;
+                float s = 0.f;
+                if (row >= 0)
+                    for (int p = lane; p < g.n_parts; p += 64) s += ld_f32(g.ssq_parts + (size_t)p * kMaxBatch + row);
+                s = wave_sum(s);
+                if (lane == 0) rs[col] = 1.0f / sqrtf(s / (float)g.K + g.eps);
+            }
+        }
+        st.staged_key = key;
+        __syncthreads();
+    } else {
+        wg_wait_cached(P, st, w.ev1, -1, w.fn);
+    }
+    trace_mark(P, task_id, 2);
+
+    const bool valid = m < g.n_cols;
+    ETC_AS_LDS const uint16_t *sh = op_hi + (size_t)(valid ? m : 0) * (size_t)g.K + kbase;
+    ETC_AS_LDS const uint16_t *sl = op_lo + (size_t)(valid ? m : 0) * (size_t)g.K + kbase;
+    const bool can_cont = n_it >= PF;
+
+    for (int ti = 0; ti < g.n_tiles; ++ti) {
+        const bool last = ti + 1 == g.n_tiles;
+        const uint16_t *wnx = last ? wnext : wcur + tile_step;       // what streams in behind this tile
+        const int n_nx = last ? n_it_next : n_it;
+        const bool cont = can_cont && wnx != nullptr;
+        f32x4 acc = f32x4{0, 0, 0, 0};
+        for (int it = 0; it < n_it; it += PF) {
+#pragma unroll
+            for (int j = 0; j < PF; ++j) {
+                const int s = it + j;
+                if (s < n_it) {
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, st.wr[j]);
+                    if (s + PF < n_it) {
+                        st.wr[j] = load16_nt(wcur + (s + PF) * 32);
+                    } else if (cont) {       // the slot freed at step s receives step s % PF of what follows
+                        if (j < n_nx) st.wr[j] = load16_nt(wnx + j * 32);
+                    }
+                    u32x4 bh = u32x4{0, 0, 0, 0}, bl = u32x4{0, 0, 0, 0};
+                    if (valid) {
+                        bh = *reinterpret_cast<ETC_AS_LDS const u32x4 *>(sh + s * 32);
+                        bl = *reinterpret_cast<ETC_AS_LDS const u32x4 *>(sl + s * 32);
+                    }
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bh), acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bl), acc, 0, 0, 0);
+                }
+            }
+        }
+        if (valid)   // lane holds rows 4*kg .. 4*kg+3 of column m
+            *reinterpret_cast<ETC_AS_LDS f32x4 *>(red + ((size_t)(ti * kWaves + wave) * g.n_cols + m) * 16 + 4 * kg) = acc;
+        if (!cont && !last) {          // short K: no streaming across tiles, plain prefetch of the next tile
+#pragma unroll
+            for (int j = 0; j < PF; ++j)
+                if (j < n_it) st.wr[j] = load16_nt(wnx + j * 32);
+        }
+        if (last && cont) st.wr_task = next_task_id;
+        wcur = wnx;
+    }
+
+    // ---- one reduction (fixed wave order) and one epilogue for all tiles of the task -------------
+    trace_mark(P, task_id, 3);
+    __syncthreads();
+    const int per_tile = g.n_cols * 8;
+    for (int idx = threadIdx.x; idx < g.n_tiles * per_tile; idx += kWgThreads) {
+        const int ti = idx / per_tile, r = idx - ti * per_tile;
+        const int col = r >> 3, mp = r & 7;
+        float lo = 0.f, hi = 0.f;
+#pragma unroll
+        for (int wv = 0; wv < kWaves; ++wv) {
+            ETC_AS_LDS const float *base = red + ((size_t)(ti * kWaves + wv) * g.n_cols + col) * 16;
+            lo += base[mp];
+            hi += base[mp + 8];
+        }
+        if (g.ssq_parts) {
+            const float rn = rs[col];
+            lo *= rn;
+            hi *= rn;
+        }
+        Epilogue et = e;
+        et.row0 = e.row0 + ti * g.tile_rows;
+        if (e.ssq_out) et.ssq_out = e.ssq_out + (size_t)ti * kMaxBatch;
+        apply_epilogue(P, et, col, mp, lo, hi);
+    }
+}
+
+// PL is the workgroup's LDS copy of the parameters: a kernel argument cannot be passed by address to
+// the out-of-line paths.
 __device__ __forceinline__ void gemm_tile_dispatch(const Params &P, const Params &PL, const GemmTile &g, const Epilogue &e,
                                                    const TaskWaits &w, float *sm, WgState &st, int task_id,
                                                    const uint16_t *wnext, int n_it_next, int next_task_id)
 {
-    if (g.n_cols <= 16 && (size_t)g.n_cols * (size_t)g.K * 4 <= (size_t)kOperandBytes) {
-        gemm_tile_run<1, true>(P, g, e, w, sm, st, task_id, wnext, n_it_next, next_task_id);
+    const bool fits = (size_t)g.n_cols * (size_t)g.K * 4 <= (size_t)kOperandBytes &&
+                      g.n_tiles * g.n_cols * kWaves * 16 <= kRedFloats;
+    if (g.n_cols <= kStagedMaxCols && fits) {
+        gemm_tiles_staged(P, g, e, w, sm, st, task_id, wnext, n_it_next, next_task_id);
         return;
     }
     wg_state_drop_weights(st);
     st.staged_key = -1;
-    if (g.n_cols <= 16) gemm_tile_cold<1>(PL, g, e, w, sm);
-    else if (g.n_cols <= 32) gemm_tile_cold<2>(PL, g, e, w, sm);
-    else gemm_tile_cold<4>(PL, g, e, w, sm);
+    if (g.n_cols <= 16) gemm_tiles_cold<1>(PL, g, e, w, sm);
+    else if (g.n_cols <= 32) gemm_tiles_cold<2>(PL, g, e, w, sm);
+    else gemm_tiles_cold<4>(PL, g, e, w, sm);
 }
 
 // cos / sin of the RoPE angle pos * theta^(-2i/d).  The inverse frequencies come from the host in

@@ -114,7 +114,7 @@ def test_dynamic_plan_runs_to_completion():
 def test_event_counts_follow_the_graph():
     s = synth.TINY                      # nq 4, nkv 2, d 64, H 256, F 1024
     B, chunk, max_kv = 2, 32, 129
-    plan = etc.plan_build(s, chunk, B, 8, max_kv_len=max_kv)
+    plan = etc.plan_build(s, chunk, B, 256, max_kv_len=max_kv)      # 256 queues: one row tile per projection task
     tasks, ev = plan["tasks"], plan["ev_init"]
     n_chunks = -(-max_kv // chunk)
     FN_QKV, FN_ATTN, FN_MERGE, FN_OPROJ, FN_GATEUP, FN_DOWN = 4, 5, 6, 7, 8, 9
@@ -146,8 +146,14 @@ def test_unfused_plan_has_one_event_per_stage():
 def test_llama8b_plan_shape():
     s = synth.LLAMA3_8B
     plan = etc.plan_build(s, 64, 1, 256, max_kv_len=1025)
-    per_layer = 384 + 8 * 17 + 8 + 256 + 1792 + 256
+    # QKV tasks stream 2 row tiles, gate/up tasks 7 (one task per queue and stage); the rest one tile
+    per_layer = 384 // 2 + 8 * 17 + 8 + 256 + 1792 // 7 + 256
     assert len(plan["tasks"]) == 1 + 32 * per_layer
+    gu = plan["tasks"][plan["tasks"]["fn"] == 8]
+    assert (gu["c1"] == 7).all() and (gu["c0"] % 7 == 0).all()
+    # a gate/up task's 7 consecutive tiles feed one K slice of the down projection: 32 tasks per slice event
+    down0 = plan["tasks"][(plan["tasks"]["fn"] == 9) & (plan["tasks"]["layer"] == 0)][0]
+    assert all(plan["ev_init"][down0["wait0"] + w] == 32 for w in range(8))
     sizes = np.diff(plan["queue_begin"])
     assert sizes.max() - sizes.min() <= 1
 

@@ -34,6 +34,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-comparators", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=0, help="layers the CPU oracle runs (0 = all)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures the one-GPU path only (this build has no multi-GPU sharding); use --gpus 1",
@@ -112,6 +114,25 @@ def main() -> int:
                      "algorithmic_bytes_per_launch": alg, "avg_launch_us": round(kern_us, 2), "traffic": None},
         "warmup_s": {"create_bind_first_step": round(t_warmup, 3), "synthetic_weight_fill": round(t_fill, 3)},
     }
+
+    # HBM traffic of this workload as last measured with rocprofv3 --pmc (see profiles/); null if never measured
+    try:
+        tr = json.load(open(os.path.join(ROOT, "paper_2604_13327_amd", "measured_traffic.json")))
+        key = f"{shape.name}/{args.sched}/b{B}/kv{L}"
+        if key in tr:
+            result["roofline"]["traffic"] = tr[key]["fetch_bytes"] + tr[key]["write_bytes"]
+            result["roofline"]["traffic_source"] = tr[key]["source"]
+    except OSError:
+        pass
+
+    if args.calib_copy:      # a plain copy kernel of known size: 2^30 bytes read, 2^30 bytes written
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        result["calib_copy_bytes"] = 1 << 30
+        del src, dst
 
     # ---- comparators on identical task bodies -------------------------------------------------------
     if not args.no_comparators:

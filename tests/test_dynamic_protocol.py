@@ -1,0 +1,18 @@
+"""The dynamic scheduler's ready-queue protocol, emulated on the CPU with one thread per workgroup
+(tests/dyn_queue_emulation.cpp): exactly-once execution, drained counters and termination over several
+launches.  The device kernel itself is switched off (see the library's kDynamicEnabled), so this is the
+coverage the protocol has for now."""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def test_ready_queue_protocol_terminates_and_runs_every_task_once(tmp_path):
+    exe = tmp_path / "dyn_emul"
+    subprocess.check_call(["g++", "-O2", "-std=c++17", "-pthread", "-o", str(exe),
+                           os.path.join(HERE, "dyn_queue_emulation.cpp")])
+    for n, wgs in ((1, 16), (5, 3), (37, 64)):
+        out = subprocess.run([str(exe), str(n), str(wgs)], capture_output=True, text=True, timeout=120)
+        assert out.returncode == 0, out.stdout + out.stderr
+        assert out.stdout.count(": ok") == 3

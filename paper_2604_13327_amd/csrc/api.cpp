@@ -282,6 +282,7 @@ etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc
     if (t->kv_chunk_tokens < m->page_size || t->kv_chunk_tokens % m->page_size)
         return fail(nullptr, ETC_EINVAL, "kv_chunk_tokens must be a positive multiple of page_size");
     if (s->kind < ETC_SCHED_STATIC || s->kind > ETC_SCHED_UNFUSED) return fail(nullptr, ETC_EINVAL, "unknown scheduler kind");
+    if (m->n_experts > 0 && (t->moe_tile_m < 1 || t->moe_tile_m > 16)) return fail(nullptr, ETC_EINVAL, "moe_tile_m must be in 1..16");
     if (s->n_sampled < 1 || s->n_sampled > 8) return fail(nullptr, ETC_EINVAL, "n_sampled must be in 1..8");
     for (int i = 0; i < s->n_sampled; ++i) {
         if (s->sampled_batch[i] < 1 || s->sampled_batch[i] > s->max_batch || (i && s->sampled_batch[i] <= s->sampled_batch[i - 1]))
@@ -352,6 +353,18 @@ etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc
         P.rope_inv_freq = d_inv;
     }
     if (okk && (s->debug_flags & ETC_DEBUG_LAYER_HIDDEN)) okk = A(&P.layer_hidden, (size_t)m->n_layers * kMaxBatch * H);
+    P.max_batch = s->max_batch;
+    if (okk && m->n_experts > 0) {
+        const size_t E = (size_t)m->n_experts, K = (size_t)m->top_k, NL = (size_t)m->n_layers;
+        const size_t rows = MB * K, r_max = (size_t)moe_max_row_tiles(m->n_experts, m->top_k, s->max_batch, d.tile_m);
+        okk = A(&P.router_logits, MB * E) && A(&P.topk_ids, rows) && A(&P.topk_w, rows) &&
+              A(&P.tok_indptr, E + 1) && A(&P.exp_indptr, E + 1) && A(&P.perm, rows) && A(&P.inv_perm, rows) &&
+              A(&P.perm_tok, rows) && A(&P.tile_expert, r_max) && A(&P.tile_row0, r_max) && A(&P.tile_n, r_max) &&
+              A(&P.eact_hi, rows * (size_t)m->moe_ffn) && A(&P.eact_lo, rows * (size_t)m->moe_ffn) && A(&P.ey, rows * H);
+        if (okk && (s->debug_flags & ETC_DEBUG_ROUTING))
+            okk = A(&P.dbg_logits, NL * MB * E) && A(&P.dbg_topk_ids, NL * rows) && A(&P.dbg_topk_w, NL * rows) &&
+                  A(&P.dbg_perm, NL * rows) && A(&P.dbg_tok_indptr, NL * (E + 1)) && A(&P.dbg_exp_indptr, NL * (E + 1));
+    }
     if (!okk) return bail(ETC_ENOMEM);
     c->h_weights.assign(m->n_layers, LayerWeights{});
     c->weights_bound.assign(m->n_layers, 0);
@@ -522,10 +535,24 @@ etc_status etc_read_debug(etc_ctx *c, int32_t kind, int32_t layer, void *dst, si
         if (layer < 0 || layer >= c->model.n_layers) return fail(c, ETC_EINVAL, "layer out of range");
         src = P.layer_hidden + (size_t)layer * kMaxBatch * c->model.hidden;
         avail = (size_t)c->bound_batch * c->model.hidden * sizeof(float); break;
+    case ETC_DBG_ROUTER_LOGITS: case ETC_DBG_TOPK_IDS: case ETC_DBG_TOPK_W: case ETC_DBG_PERMUTATION:
+    case ETC_DBG_TOK_INDPTR: case ETC_DBG_EXP_INDPTR: {
+        if (!P.dbg_logits) return fail(c, ETC_ESTATE, "routing dump is off (or the model has no experts)");
+        if (layer < 0 || layer >= c->model.n_layers) return fail(c, ETC_EINVAL, "layer out of range");
+        const size_t E = (size_t)c->model.n_experts, K = (size_t)c->model.top_k, L = (size_t)layer, Bb = (size_t)c->bound_batch;
+        switch (kind) {
+        case ETC_DBG_ROUTER_LOGITS: src = P.dbg_logits + L * MB * E; avail = Bb * E * 4; break;
+        case ETC_DBG_TOPK_IDS: src = P.dbg_topk_ids + L * MB * K; avail = Bb * K * 4; break;
+        case ETC_DBG_TOPK_W: src = P.dbg_topk_w + L * MB * K; avail = Bb * K * 4; break;
+        case ETC_DBG_PERMUTATION: src = P.dbg_perm + L * MB * K; avail = Bb * K * 4; break;
+        case ETC_DBG_TOK_INDPTR: src = P.dbg_tok_indptr + L * (E + 1); avail = (E + 1) * 4; break;
+        default: src = P.dbg_exp_indptr + L * (E + 1); avail = (E + 1) * 4; break;
+        }
+        break;
+    }
     default:
         return fail(c, ETC_EINVAL, "unknown or unavailable debug kind");
     }
-    (void)MB;
     if (bytes > avail) return fail(c, ETC_EINVAL, "more bytes requested than the item holds");
     HIP_TRY(c, hipMemcpy(dst, src, bytes, hipMemcpyDeviceToHost));
     if (kind == ETC_DBG_ERROR_WORD) return ETC_OK;

@@ -8,6 +8,8 @@ constexpr int kWgThreads = 512;          // one task = one workgroup of 8 wavefr
 constexpr int kWaves = kWgThreads / 64;
 constexpr int kMaxBatch = 64;
 constexpr int kMaxLayers = 128;
+constexpr int kMaxExperts = 256;
+constexpr int kMaxTopK = 16;
 constexpr int kLdsBytes = 148 * 1024;    // of the 160 KB LDS per CU: exactly one persistent workgroup per CU
 constexpr int kRedFloats = kWaves * 4 * 64 * 4;   // LDS: cross-wave reduction buffer (32 KB)
 constexpr int kRsFloats = 64;                     // LDS: RMSNorm factors of the columns
@@ -26,9 +28,9 @@ enum Fn : uint8_t {
     FN_OPROJ = 7,         // 16 rows of Wo + residual
     FN_GATEUP = 8,        // RMSNorm prologue, 8 gate + 8 up rows, SiLU-mul epilogue
     FN_DOWN = 9,          // 16 rows of Wd + residual (waves split K; each waits for its own K slice)
-    FN_ROUTER = 10,       // MoE: norm, router logits, top-k, weights, counts, indptr; arms expert events
-    FN_GROUP = 11,        // MoE: one tile per token, stable rank inside its experts' ranges
-    FN_MOE_GATEUP = 12,   // MoE: GroupGEMM-1 tile (row tile, 8 gate + 8 up rows), SiLU-mul
+    FN_ROUTER_LOGITS = 10,// MoE: RMSNorm prologue, 16 rows of the router matrix -> fp32 logits
+    FN_ROUTER = 11,       // MoE: one tile per token: top-k ids and weights, counts, indptr, stable rank of its slots
+    FN_MOE_GATEUP = 12,   // MoE: GroupGEMM-1 tile (row tile of routed tokens, 8 gate + 8 up rows), SiLU-mul
     FN_MOE_DOWN = 13,     // MoE: GroupGEMM-2 tile (row tile, 16 rows of the expert's Wd)
     FN_COMBINE = 14,      // MoE: weighted sum of a token's expert outputs in slot order + residual
     FN_COUNT
@@ -87,15 +89,22 @@ struct Params {
     uint16_t *attn_hi, *attn_lo;       // attention output, split [maxB, nq*d]
     uint16_t *act_hi, *act_lo;         // silu(gate)*up, split [maxB, F]
     float *part_m, *part_l, *part_o;   // split-KV partials [maxB, nq, max_chunks] (+ [d])
-    // MoE scratch
+    // MoE scratch (rows of the grouped tensors are (token, slot) pairs sorted by (expert, token, slot))
     float *router_logits;              // [maxB, E]
     int32_t *topk_ids;                 // [maxB, topk]
     float *topk_w;                     // [maxB, topk]
-    int32_t *exp_count, *tok_indptr, *exp_indptr, *perm, *inv_perm; // [E], [E+1], [E+1], [maxB*topk] x2
+    int32_t *tok_indptr, *exp_indptr;  // [E+1] prefix sums of routed pairs / of row tiles per expert
+    int32_t *perm, *inv_perm, *perm_tok; // [maxB*topk]: row -> pair, pair -> row, row -> token
+    int32_t *tile_expert, *tile_row0, *tile_n; // [max row tiles]: expert, first row and rows of every row tile
     uint16_t *eact_hi, *eact_lo;       // expert activations, split [maxB*topk, moeF]
     float *ey;                         // expert outputs fp32 [maxB*topk, H]
     const int32_t *forced_topk;        // [n_layers, maxB, topk] or null
     const uint8_t *forced_mask;        // [n_layers] or null
+    // per-layer copies of the routing data (debug flag 4), or null
+    float *dbg_logits, *dbg_topk_w;    // [n_layers, maxB, E], [n_layers, maxB, topk]
+    int32_t *dbg_topk_ids, *dbg_perm;  // [n_layers, maxB, topk], [n_layers, maxB*topk]
+    int32_t *dbg_tok_indptr, *dbg_exp_indptr; // [n_layers, E+1]
+    int32_t max_batch;                 // row stride of the per-layer debug copies
     // event tensors: three equal arrays [cur | init | next]; the kernel re-arms `next` from `init`
     int32_t *ev_cur;
     const int32_t *ev_init;

@@ -171,6 +171,12 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
     if (m.H % 16) return "hidden must be a multiple of 16";
     if (m.E == 0 && (m.F % (kWaves * 32) || (m.F / 8) % kWaves)) return "ffn must be a multiple of 256";
     if (m.n_layers > kMaxLayers) return "too many layers";
+    if (m.E > 0) {
+        if (m.E % 16 || m.E > kMaxExperts) return "n_experts must be a multiple of 16, at most 256";
+        if (m.topk < 1 || m.topk > kMaxTopK || m.topk > m.E) return "top_k must be in 1..16 and at most n_experts";
+        if (m.moeF < 1 || m.moeF % (kWaves * 32)) return "moe_ffn must be a multiple of 256";
+        if (m.tile_m < 1 || m.tile_m > 16) return "moe_tile_m must be in 1..16";
+    }
     const int grp = m.nq / m.nkv;
     const int sub = m.d / 16;                     // 16-row tiles (8 RoPE pairs) per head
     const DimExpr B = dim_sym(0), NCH = dim_sym(1), one = dim_const(1);
@@ -273,7 +279,69 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
                 g.calls.push_back(c);
             }
         } else {
-            return "MoE layers are not wired into the graph yet";
+            // MoE block (Sec. 2.4).  Static scheduling cannot follow the data-dependent edges
+            // (token -> expert -> row tiles), so they collapse to one coarse event each ("E[0]",
+            // Sec. 3.1): every GroupGEMM-1 tile waits for ALL router tiles, every combine tile for ALL
+            // GroupGEMM-2 tiles.  The row-tile slots themselves are static, so GroupGEMM-1 ->
+            // GroupGEMM-2 stays fine-grained: one event per slot.
+            const int r_max = moe_max_row_tiles(m.E, m.topk, Bs, m.tile_m);
+            const int n_ft = m.moeF / 8, n_ht = m.H / 16;
+            auto tiles_per_task = [&](int per_slot) {
+                int cand = std::max(1, (int)((long long)r_max * per_slot / std::max(1, n_queues)));
+                cand = std::min(cand, 64 / m.tile_m);              // partial tiles of a task share the LDS reduction buffer
+                while (cand > 1 && per_slot % cand) --cand;
+                return std::max(1, cand);
+            };
+            const int r_g = tiles_per_task(n_ft), r_d = tiles_per_task(n_ht);
+            const int e_logits = g.add_event({one});
+            const int e_group = g.add_event({one});
+            const int e_eact = g.add_event({dim_const(r_max)});
+            const int e_y = g.add_event({one});
+            {
+                CallDecl c;
+                c.fn = FN_ROUTER_LOGITS; c.layer = l; c.stage = stage++;
+                c.rank = 1; c.shape[0] = dim_const(m.E / 16);
+                c.in = {edge_const0(e_xmid)};
+                c.out = {edge_const0(e_logits)};
+                g.calls.push_back(c);
+            }
+            {
+                CallDecl c;
+                c.fn = FN_ROUTER; c.layer = l; c.stage = stage++;
+                c.rank = 1; c.shape[0] = B;
+                c.in = {edge_const0(e_logits)};
+                c.out = {edge_const0(e_group)};
+                g.calls.push_back(c);
+            }
+            {
+                CallDecl c;
+                c.fn = FN_MOE_GATEUP; c.layer = l; c.stage = stage++;     // task record: (row-tile slot, first tile, tiles)
+                c.rank = 2; c.shape[0] = dim_const(r_max); c.shape[1] = dim_const(n_ft / r_g);
+                c.c_mul[1] = r_g; c.c_fill[2] = r_g;
+                c.flags = TF_DYN_ROWTILE;
+                c.in = {edge_const0(e_group)};
+                c.out = {edge_dim(e_eact, 0)};
+                g.calls.push_back(c);
+            }
+            {
+                CallDecl c;
+                c.fn = FN_MOE_DOWN; c.layer = l; c.stage = stage++;
+                c.rank = 2; c.shape[0] = dim_const(r_max); c.shape[1] = dim_const(n_ht / r_d);
+                c.c_mul[1] = r_d; c.c_fill[2] = r_d;
+                c.flags = TF_DYN_ROWTILE;
+                c.in = {edge_dim(e_eact, 0)};
+                c.out = {edge_const0(e_y)};
+                g.calls.push_back(c);
+            }
+            {
+                CallDecl c;
+                c.fn = FN_COMBINE; c.layer = l; c.stage = stage++;        // task record: (token, chunk of 512 elements)
+                c.rank = 2; c.shape[0] = B; c.shape[1] = dim_const((m.H + kWgThreads - 1) / kWgThreads);
+                c.flags = last;
+                c.in = {edge_const0(e_y)};
+                c.out = {edge_const0(e_xnext)};
+                g.calls.push_back(c);
+            }
         }
         e_x = e_xnext;
     }

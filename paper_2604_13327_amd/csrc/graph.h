@@ -81,6 +81,14 @@ struct ModelDims {
     int kv_chunk, tile_m;
 };
 
+// Upper bound of sum_e ceil(count_e / tile_m) over all routings of `batch` tokens: the number of
+// GroupGEMM row-tile slots a static queue holds (slots beyond exp_indptr[E] are no-ops at run time).
+inline int moe_max_row_tiles(int n_experts, int top_k, int batch, int tile_m)
+{
+    const int n = batch * top_k, nonempty = n < n_experts ? n : n_experts;
+    return (n + nonempty * (tile_m - 1)) / tile_m;
+}
+
 // The decoder's graph function for one sampled batch size.  Symbol 0 = that batch size, symbol 1 =
 // chunk slots per sequence.  n_queues and the batch decide how many consecutive row tiles one
 // projection task streams (tile shapes are a degree of freedom of the graph, Sec. 2.1).

@@ -10,6 +10,7 @@
 #include "device_rt.hip.h"
 #include "task_attn.hip.h"
 #include "task_gemm.hip.h"
+#include "task_moe.hip.h"
 
 namespace etc {
 
@@ -124,8 +125,52 @@ __device__ __forceinline__ bool setup_gemm(const Params &P, const Task &t, GemmT
         }
         return true;
     }
+    case FN_ROUTER_LOGITS: {
+        const int r0 = t.c0 * 16;
+        g.n_tiles = 1; g.tile_rows = 16;
+        g.rowsA = (const uint16_t *)W->wr + (size_t)r0 * P.H;
+        g.rowsB = g.rowsA + (size_t)8 * P.H;
+        g.ldw = P.H; g.K = P.H;
+        g.b_hi = P.xmg_hi; g.b_lo = P.xmg_lo; g.ldb = P.H;
+        g.ssq_parts = P.ssq_xmid; g.n_parts = P.H / 16; g.eps = P.eps;
+        g.n_cols = P.B;
+        e.kind = EPI_STORE_F32; e.layer = t.layer; e.row0 = r0; e.outf = P.router_logits; e.ld = P.E;
+        return true;
+    }
     default:
         return false;
+    }
+}
+
+// GroupGEMM tile of a resolved row tile: the weight rows depend on the routing, so this runs after the wait.
+__device__ __forceinline__ void setup_moe_gemm(const Params &P, const Task &t, const RowTile &rt, GemmTile &g, Epilogue &e)
+{
+    const ETC_AS_GLOBAL LayerWeights *W = as_global(P.weights) + t.layer;
+    g.n_tiles = t.c2;
+    g.n_cols = rt.n;
+    e.layer = t.layer;
+    e.col0 = rt.row0;
+    if (t.fn == FN_MOE_GATEUP) {
+        const int f0 = t.c1 * 8;
+        const size_t off = ((size_t)rt.expert * P.moeF + f0) * (size_t)P.H;
+        g.tile_rows = 8;
+        g.rowsA = (const uint16_t *)W->eg + off;
+        g.rowsB = (const uint16_t *)W->eu + off;
+        g.ldw = P.H; g.K = P.H;
+        g.b_hi = P.xmg_hi; g.b_lo = P.xmg_lo; g.ldb = P.H;
+        g.col_rows = P.perm_tok + rt.row0;             // column n reads the hidden state of the row's token
+        g.ssq_parts = P.ssq_xmid; g.n_parts = P.H / 16; g.eps = P.eps;
+        e.kind = EPI_MOE_ACT; e.row0 = f0; e.out_hi = P.eact_hi; e.out_lo = P.eact_lo; e.ld = P.moeF;
+    } else {
+        const int h0 = t.c1 * 16;
+        g.tile_rows = 16;
+        g.rowsA = (const uint16_t *)W->ed + ((size_t)rt.expert * P.H + h0) * (size_t)P.moeF;
+        g.rowsB = g.rowsA + (size_t)8 * P.moeF;
+        g.ldw = P.moeF; g.K = P.moeF;
+        g.b_hi = P.eact_hi + (size_t)rt.row0 * P.moeF;
+        g.b_lo = P.eact_lo + (size_t)rt.row0 * P.moeF;
+        g.ldb = P.moeF;
+        e.kind = EPI_MOE_Y; e.row0 = h0; e.outf = P.ey; e.ld = P.H;
     }
 }
 
@@ -136,9 +181,19 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
                                          WgState &st)
 {
     const int w0 = SYNC_EVENTS ? t.wait0 : -1, w1 = SYNC_EVENTS ? t.wait1 : -1;
-    TaskWaits tw{w0, w1, (int)t.fn, (t.flags & TF_WAIT0_PER_WAVE) != 0 && SYNC_EVENTS};
+    TaskWaits tw{w0, w1, (int)t.fn, (t.flags & TF_WAIT0_PER_WAVE) != 0 && SYNC_EVENTS, w0};
     GemmTile g{};
     Epilogue e{};
+    if (t.flags & TF_DYN_ROWTILE) {      // GroupGEMM tile: wait first, then look the row tile up
+        wg_wait_cached(P, st, w0, w1, t.fn);
+        wg_state_drop_weights(st);
+        RowTile rt;
+        if (!resolve_row_tile(P, t.c0, rt)) return;        // surplus slot of the static grid: nothing to do but notify
+        setup_moe_gemm(P, t, rt, g, e);
+        tw = TaskWaits{-1, -1, (int)t.fn, false, w0 < 0 ? -1 : w0 + ((t.c0 + 1) << 20)};
+        gemm_tile_dispatch(P, PL, g, e, tw, sm, st, t.id, nullptr, 0, -1);
+        return;
+    }
     if (setup_gemm(P, t, g, e)) {
         GemmTile gn{};
         Epilogue en{};
@@ -192,6 +247,19 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
         }
         break;
     }
+    case FN_ROUTER:
+        if (t.c0 < P.B) {
+            wg_wait_cached(P, st, w0, w1, t.fn);
+            st.staged_key = -1;      // the routing scratch overlaps the staged operand
+            moe_route_and_group(PL, t.layer, t.c0, sm);
+        }
+        break;
+    case FN_COMBINE:
+        if (t.c0 < P.B) {
+            wg_wait_cached(P, st, w0, w1, t.fn);
+            moe_combine(P, t);
+        }
+        break;
     default:
         break;
     }

@@ -68,6 +68,7 @@ __device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &
 struct TaskWaits {
     int ev0, ev1, fn;
     bool per_wave;
+    int op_key;          // identifies the operand a staged copy in LDS holds (-1: never reuse a copy)
 };
 
 // State a persistent workgroup carries from task to task (registers, uniform across the workgroup
@@ -283,7 +284,7 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
     ETC_AS_LDS uint16_t *op_lo = op_hi + (size_t)g.n_cols * g.K;
 
     // ---- E.wait(), then stage the operand unless this stage's operand is already in LDS ----------
-    const int key = w.ev0;
+    const int key = w.op_key;
     if (key < 0 || key != st.staged_key) {
         if (w.per_wave) {           // the staged copy needs every K slice: lanes 0..7 of wave 0 poll one slice each
             if (wave == 0 && lane < kWaves) spin_until_zero(P, w.ev0 + lane, w.fn);

@@ -1,0 +1,193 @@
+// MoE routing tasks (paper Sec. 2.4): top-k routing and token grouping, the run-time resolution of a
+// GroupGEMM row-tile slot, and the weighted combine of a token's expert outputs.
+//
+// Grouped rows.  The (token, slot) pairs of a step are sorted by (expert, token, slot); row p of the
+// grouped tensors (expert activations, expert outputs) belongs to pair perm[p].  tok_indptr is the
+// prefix sum of pairs per expert, exp_indptr the prefix sum of row tiles (tile_m rows each) per
+// expert: expert e owns the row tiles [exp_indptr[e], exp_indptr[e+1]).  Everything is computed by
+// counting and ranking, never by grabbing slots with atomics, so the permutation is the same in
+// every run and under every schedule.
+#pragma once
+#include "device_rt.hip.h"
+
+namespace etc {
+
+struct RowTile {
+    int expert, row0, n;     // rows [row0, row0 + n) of the grouped tensors
+};
+
+// Slot r of the static GroupGEMM grid -> its expert and rows; false for the surplus slots of this step.
+__device__ __forceinline__ bool resolve_row_tile(const Params &P, int r, RowTile &rt)
+{
+    const int total = __builtin_amdgcn_readfirstlane(ld_i32(P.exp_indptr + P.E));
+    if (r >= total) return false;
+    rt.expert = __builtin_amdgcn_readfirstlane(ld_i32(P.tile_expert + r));
+    rt.row0 = __builtin_amdgcn_readfirstlane(ld_i32(P.tile_row0 + r));
+    rt.n = __builtin_amdgcn_readfirstlane(ld_i32(P.tile_n + r));
+    return true;
+}
+
+__device__ __forceinline__ int wave_sum_i(int v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// Router tile of token t.  Every tile needs the ids of ALL tokens to rank its own pairs, so each
+// recomputes the (cheap) top-k of every token from the shared logits instead of waiting one more event
+// hop for them; it publishes only what belongs to token t.  Tile 0 also publishes the per-expert tables.
+// Order of the selection: larger logit first, equal logits -> lower expert index first.
+// Routing weights: softmax over the selected logits.
+__device__ __noinline__ void moe_route_and_group(const Params &P, int layer, int t, float *sm)
+{
+    const int wave = wave_id(), lane = lane_id();
+    const int E = P.E, K = P.topk, B = P.B, N = B * K, M = P.tile_m;
+    ETC_AS_LDS int32_t *ids_s = reinterpret_cast<ETC_AS_LDS int32_t *>(as_lds(sm));   // [B*K] expert of every pair
+    ETC_AS_LDS int32_t *cnt = ids_s + kMaxBatch * kMaxTopK;                            // [E]
+    ETC_AS_LDS int32_t *til = cnt + kMaxExperts;                                       // [E] row tiles per expert
+    ETC_AS_LDS int32_t *tokp = til + kMaxExperts;                                      // [E+1]
+    ETC_AS_LDS int32_t *expp = tokp + kMaxExperts + 1;                                 // [E+1]
+    const bool forced = P.forced_mask != nullptr && *as_global(P.forced_mask + layer) != 0;
+    const bool dbg = (P.debug_flags & 4u) != 0 && P.dbg_logits != nullptr;
+    const size_t dbg_row = (size_t)layer * P.max_batch + t;
+
+    for (int e = threadIdx.x; e < E; e += kWgThreads) cnt[e] = 0;
+    for (int b = wave; b < B; b += kWaves) {
+        const float *lg = P.router_logits + (size_t)b * E;
+        float v[kMaxExperts / 64];
+#pragma unroll
+        for (int j = 0; j < kMaxExperts / 64; ++j) {
+            const int e = lane + 64 * j;
+            v[j] = e < E ? ld_f32(lg + e) : -INFINITY;
+            if (dbg && b == t && e < E) as_global(P.dbg_logits)[dbg_row * E + e] = v[j];
+        }
+        int my_id = 0;
+        float my_v = -INFINITY;
+        if (forced) {
+            if (lane < K) {
+                my_id = gld_i32(P.forced_topk + ((size_t)layer * P.max_batch + b) * K + lane);
+                my_v = ld_f32(lg + my_id);
+            }
+        } else {
+            for (int k = 0; k < K; ++k) {
+                float bv = -INFINITY;
+                int bi = 0x7FFFFFFF;
+#pragma unroll
+                for (int j = 0; j < kMaxExperts / 64; ++j) {      // ascending index: a strict '>' keeps the lowest on ties
+                    const int e = lane + 64 * j;
+                    if (e < E && v[j] > bv) { bv = v[j]; bi = e; }
+                }
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) {
+                    const float ov = __shfl_xor(bv, off, 64);
+                    const int oi = __shfl_xor(bi, off, 64);
+                    if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+                }
+                if (lane == k) { my_id = bi; my_v = bv; }
+#pragma unroll
+                for (int j = 0; j < kMaxExperts / 64; ++j)
+                    if (lane + 64 * j == bi) v[j] = -INFINITY;    // taken
+            }
+        }
+        if (lane < K) ids_s[b * K + lane] = my_id;
+        if (b == t) {
+            float mx = lane < K ? my_v : -INFINITY;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+            const float p = lane < K ? __expf(my_v - mx) : 0.f;
+            const float den = wave_sum(p);
+            if (lane < K) {
+                st_i32(P.topk_ids + (size_t)t * K + lane, my_id);
+                st_f32(P.topk_w + (size_t)t * K + lane, p / den);
+                if (dbg) {
+                    as_global(P.dbg_topk_ids)[dbg_row * K + lane] = my_id;
+                    as_global(P.dbg_topk_w)[dbg_row * K + lane] = p / den;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < N; i += kWgThreads)
+        __hip_atomic_fetch_add(cnt + ids_s[i], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += kWgThreads) til[e] = (cnt[e] + M - 1) / M;
+    __syncthreads();
+    for (int e = threadIdx.x; e <= E; e += kWgThreads) {
+        int a = 0, c = 0;
+        for (int j = 0; j < e; ++j) { a += cnt[j]; c += til[j]; }
+        tokp[e] = a;
+        expp[e] = c;
+    }
+    __syncthreads();
+
+    // the K pairs of this token: stable rank among the pairs of the same expert
+    for (int k = wave; k < K; k += kWaves) {
+        const int me = t * K + k, e = ids_s[me];
+        int c = 0;
+        for (int i = lane; i < me; i += 64) c += ids_s[i] == e ? 1 : 0;
+        c = wave_sum_i(c);
+        if (lane == 0) {
+            const int pos = tokp[e] + c;
+            st_i32(P.perm + pos, me);
+            st_i32(P.inv_perm + me, pos);
+            st_i32(P.perm_tok + pos, t);
+            if (dbg) as_global(P.dbg_perm)[(size_t)layer * P.max_batch * K + pos] = me;
+        }
+    }
+    if (t == 0) {
+        for (int e = threadIdx.x; e <= E; e += kWgThreads) {
+            st_i32(P.tok_indptr + e, tokp[e]);
+            st_i32(P.exp_indptr + e, expp[e]);
+            if (dbg) {
+                as_global(P.dbg_tok_indptr)[(size_t)layer * (E + 1) + e] = tokp[e];
+                as_global(P.dbg_exp_indptr)[(size_t)layer * (E + 1) + e] = expp[e];
+            }
+        }
+        for (int e = threadIdx.x; e < E; e += kWgThreads) {
+            int n = cnt[e], r = expp[e], row = tokp[e];
+            for (; n > 0; n -= M, ++r, row += M) {
+                st_i32(P.tile_expert + r, e);
+                st_i32(P.tile_row0 + r, row);
+                st_i32(P.tile_n + r, n < M ? n : M);
+            }
+        }
+    }
+    __syncthreads();     // the routing scratch in LDS is free again
+}
+
+// Combine tile (token b, 512 consecutive elements): x = x_mid + sum_k w[b,k] * y[row of pair (b,k)],
+// slots in ascending order.  Like every producer of the residual stream it also prepares the next
+// layer's projection operand (x * gain, split) and the partial sums of squares per 16 elements.
+__device__ __forceinline__ void moe_combine(const Params &P, const Task &t)
+{
+    const int b = t.c0, h = t.c1 * kWgThreads + (int)threadIdx.x;
+    if (h >= P.H) return;
+    const int K = P.topk;
+    float acc = 0.f;
+    for (int k = 0; k < K; ++k) {
+        const int pos = ld_i32(P.inv_perm + (size_t)b * K + k);
+        acc += ld_f32(P.topk_w + (size_t)b * K + k) * ld_f32(P.ey + (size_t)pos * P.H + h);
+    }
+    const size_t o = (size_t)b * P.H + h;
+    const float v = ld_f32(P.x_mid + o) + acc;
+    st_f32(P.x + o, v);
+    if (t.flags & TF_LAST_LAYER) {
+        gst_u16(P.hidden_out + o, f32_to_bf16_bits(v));
+    } else {
+        const uint16_t *g1 = (const uint16_t *)as_global(P.weights)[t.layer + 1].g1;
+        uint16_t hi, lo;
+        split_bf16(v * bf16_bits_to_f32(gld_u16(g1 + h)), hi, lo);
+        st_u16(P.xg_hi + o, hi);
+        st_u16(P.xg_lo + o, lo);
+        float s = v * v;          // 16 consecutive lanes hold one 16-element part
+        s += __shfl_xor(s, 1, 64);
+        s += __shfl_xor(s, 2, 64);
+        s += __shfl_xor(s, 4, 64);
+        s += __shfl_xor(s, 8, 64);
+        if ((threadIdx.x & 15) == 0) st_f32(P.ssq_x + (size_t)(h >> 4) * kMaxBatch + b, s);
+    }
+    if (P.debug_flags & 2u) gst_f32(P.layer_hidden + ((size_t)t.layer * kMaxBatch + b) * P.H + h, v);
+}
+
+}  // namespace etc

@@ -34,7 +34,7 @@ class ModelShape:
 
 
 TINY = ModelShape("tiny", 2, 256, 4, 2, 64, 1024)
-TINY_MOE = ModelShape("tiny-moe", 2, 256, 4, 2, 64, 0, n_experts=8, top_k=2, moe_F=128)
+TINY_MOE = ModelShape("tiny-moe", 2, 256, 4, 2, 64, 0, n_experts=16, top_k=2, moe_F=256)
 LLAMA3_8B = ModelShape("llama3-8b", 32, 4096, 32, 8, 128, 14336)
 QWEN3_30B_A3B = ModelShape("qwen3-30b-a3b", 48, 2048, 32, 4, 128, 0, n_experts=128, top_k=8, moe_F=768)
 LLAMA3_70B = ModelShape("llama3-70b", 80, 8192, 64, 8, 128, 28672)

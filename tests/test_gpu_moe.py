@@ -1,0 +1,192 @@
+"""GPU parity of the MoE path (router, top-k, token grouping, GroupGEMM, combine) against the CPU oracle.
+
+Integer work is compared on identical inputs: the oracle's top-k and grouping applied to the logits the
+GPU dumped must give the GPU's ids, permutation and both indptr arrays bit for bit.  Floating point
+downstream is compared with the oracle following the GPU's routing (a legitimate flip of the k-th and
+(k+1)-th expert by accumulated rounding noise would otherwise look like an error); the free-running
+oracle is compared as well, and every selection it disagrees on must sit on a near tie."""
+import numpy as np
+import pytest
+
+import synth
+from harness import GpuModel, bf16_to_f32_np, fixed_step, oracle_step, rel_err
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+SPIN = 400000
+
+
+def _etc():
+    import paper_2604_13327_amd as etc
+    return etc
+
+
+def _launch(dec, model, step, step_index=0, kbk=False):
+    import torch
+    x = model.hidden(step_index, step.batch)
+    out = torch.empty_like(x)
+    (dec.launch_kernel_by_kernel if kbk else dec.launch)(x, out)
+    torch.cuda.synchronize()
+    return bf16_to_f32_np(out)
+
+
+def _routing(dec, s, B, layer):
+    from paper_2604_13327_amd import binding as b
+    E, K = s.n_experts, s.top_k
+    return {"logits": dec.routing_debug(b.DBG_ROUTER_LOGITS, layer, (B, E), np.float32),
+            "ids": dec.routing_debug(b.DBG_TOPK_IDS, layer, (B, K), np.int32),
+            "w": dec.routing_debug(b.DBG_TOPK_W, layer, (B, K), np.float32),
+            "perm": dec.routing_debug(b.DBG_PERMUTATION, layer, (B * K,), np.int32),
+            "tok_indptr": dec.routing_debug(b.DBG_TOK_INDPTR, layer, (E + 1,), np.int32),
+            "exp_indptr": dec.routing_debug(b.DBG_EXP_INDPTR, layer, (E + 1,), np.int32)}
+
+
+def check_moe_step(dec, model, s, step, tile_m, step_index=0, forced=None, layers=None, first_layer=0):
+    """One launch, then every check of the module docstring.  Returns the worst per-layer error."""
+    import oracle
+    B = step.batch
+    n_layers = s.n_layers if layers is None else layers
+    out = _launch(dec, model, step, step_index)
+    assert (dec.error_word() == 0).all(), dec.error_word()
+    assert (dec.event_counters() == 0).all(), "an event counter did not drain to zero"
+    assert (dec.exec_counts() == 1).all(), "a task did not run exactly once"
+    routes = [_routing(dec, s, B, l) for l in range(n_layers)]
+    for l, r in enumerate(routes):
+        # integers on identical inputs
+        if forced is None:
+            for b in range(B):
+                np.testing.assert_array_equal(r["ids"][b], oracle.topk(r["logits"][b], s.top_k), err_msg=f"layer {l} token {b}")
+        else:
+            np.testing.assert_array_equal(r["ids"], forced[l])
+        count, tok_indptr, perm, exp_indptr = oracle.group(r["ids"], s.n_experts, tile_m)
+        np.testing.assert_array_equal(r["perm"], perm)
+        np.testing.assert_array_equal(r["tok_indptr"], tok_indptr)
+        np.testing.assert_array_equal(r["exp_indptr"], exp_indptr)
+        assert int(count.sum()) == B * s.top_k
+        for b in range(B):
+            np.testing.assert_allclose(r["w"][b], oracle.route_weights(r["logits"][b], r["ids"][b]), rtol=2e-5, atol=1e-7)
+    # floats, oracle following the GPU's routing
+    ref = oracle_step(s, model.seed, model.n_pool_pages, step, step_index, n_layers=n_layers,
+                      forced_topk_of=lambda l: routes[l]["ids"], tile_m=tile_m, first_layer=first_layer)
+    worst = 0.0
+    for l in range(n_layers):
+        e = rel_err(dec.layer_hidden(l), ref["layers"][l])
+        worst = max(worst, e)
+        assert e <= TOL, f"layer {l}: {e}"
+    if n_layers == s.n_layers:
+        assert rel_err(out, ref["final"]) <= TOL
+    return worst, routes, out
+
+
+def free_running_mismatches(s, model, step, routes, step_index=0, n_layers=None, margin=0.05):
+    """Free-running oracle vs GPU: every selection that differs must be a near tie in the oracle's own
+    logits (the gap between the two candidates below `margin`).  Returns the number of differing sets."""
+    import oracle
+    n_layers = s.n_layers if n_layers is None else n_layers
+    x = synth.hidden_f32(s, model.seed, step_index, step.batch)
+    oshape = oracle.shape_of(s)
+    n_diff = 0
+    for l in range(n_layers):
+        w = synth.layer_weights_f32(s, model.seed, l)
+        kp, vp = synth.kv_pool_f32(s, model.seed, l, model.n_pool_pages)
+        ids, dbg = oracle.layer(oshape, x, w, kp, vp, step.kv_len, step.page_indptr, step.page_ids, debug=True)
+        for b in range(step.batch):
+            a, g = set(ids[b].tolist()), set(routes[l]["ids"][b].tolist())
+            if a != g:
+                n_diff += 1
+                lg = dbg["router_logits"][b]
+                only_a, only_g = sorted(a - g), sorted(g - a)
+                gap = max(abs(float(lg[i]) - float(lg[j])) for i in only_a for j in only_g)
+                assert gap < margin, f"layer {l} token {b}: routing differs beyond a near tie (gap {gap})"
+    return n_diff
+
+
+# ---------------------------------------------------------------- tiny MoE decoder
+@pytest.fixture(scope="module")
+def tiny_moe_model():
+    return GpuModel(synth.TINY_MOE, seed=21, n_pool_pages=96)
+
+
+@pytest.mark.parametrize("batch,tile_m", [(1, 16), (3, 16), (5, 2), (7, 1), (16, 4)])
+def test_tiny_moe_matches_oracle(tiny_moe_model, batch, tile_m):
+    etc = _etc()
+    s, m = synth.TINY_MOE, tiny_moe_model
+    m.reset_pools()
+    rng = np.random.default_rng(100 + batch)
+    step = fixed_step(s, batch, rng.integers(0, 80, size=batch), m.n_pool_pages, seed=batch)
+    dec = etc.Decoder(s, kv_chunk_tokens=32, sampled_batches=[batch], max_kv_len=129, moe_tile_m=tile_m,
+                      debug_flags=etc.DEBUG_EXEC_COUNT | etc.DEBUG_LAYER_HIDDEN | etc.DEBUG_ROUTING, spin_budget=SPIN)
+    m.bind(dec)
+    dec.bind_step(step)
+    worst, routes, _ = check_moe_step(dec, m, s, step, tile_m)
+    m.reset_pools()
+    free_running_mismatches(s, m, step, routes)
+    print(f"tiny-moe B={batch} tile_m={tile_m}: worst per-layer max|err|/rms = {worst:.3e}")
+    dec.close()
+
+
+def test_tiny_moe_forced_routing_and_skewed_load(tiny_moe_model):
+    """etc_force_routing: every token to the same two experts (one long expert range spanning several row
+    tiles, fourteen empty experts), then a token that names one expert twice."""
+    etc = _etc()
+    s, m = synth.TINY_MOE, tiny_moe_model
+    B, tile_m = 6, 4
+    m.reset_pools()
+    step = fixed_step(s, B, [5, 17, 0, 33, 64, 9], m.n_pool_pages, seed=4)
+    dec = etc.Decoder(s, kv_chunk_tokens=32, sampled_batches=[8], max_kv_len=129, moe_tile_m=tile_m,
+                      debug_flags=etc.DEBUG_EXEC_COUNT | etc.DEBUG_LAYER_HIDDEN | etc.DEBUG_ROUTING, spin_budget=SPIN)
+    m.bind(dec)
+    dec.bind_step(step)
+    forced = [np.tile(np.array([[11, 3]], np.int32), (B, 1)), np.tile(np.array([[0, 15]], np.int32), (B, 1))]
+    forced[1][2] = [7, 7]
+    for l in range(s.n_layers):
+        dec.force_routing(l, forced[l])
+    check_moe_step(dec, m, s, step, tile_m, forced=forced)
+    # removing the override restores the device top-k
+    for l in range(s.n_layers):
+        dec.force_routing(l, None)
+    m.reset_pools()
+    dec.bind_step(step)              # re-arms the execution counters
+    check_moe_step(dec, m, s, step, tile_m)
+    dec.close()
+
+
+def test_tiny_moe_schedulers_and_kernel_by_kernel_agree_bitwise(tiny_moe_model):
+    etc = _etc()
+    s, m = synth.TINY_MOE, tiny_moe_model
+    step = fixed_step(s, 4, [40, 3, 77, 12], m.n_pool_pages, seed=2)
+    outs = []
+    for kind in (etc.SCHED_STATIC, etc.SCHED_UNFUSED):
+        dec = etc.Decoder(s, kv_chunk_tokens=32, sampled_batches=[1, 4], max_kv_len=129, kind=kind, moe_tile_m=2,
+                          debug_flags=etc.DEBUG_EXEC_COUNT, spin_budget=SPIN)
+        m.bind(dec)
+        dec.bind_step(step)
+        m.reset_pools()
+        outs.append(_launch(dec, m, step))
+        assert (dec.event_counters() == 0).all() and (dec.exec_counts() == 1).all()
+        m.reset_pools()
+        outs.append(_launch(dec, m, step))          # second launch: re-armed events
+        assert (dec.event_counters() == 0).all() and (dec.exec_counts() == 2).all()
+        if kind == etc.SCHED_STATIC:
+            m.reset_pools()
+            outs.append(_launch(dec, m, step, kbk=True))
+        dec.close()
+    for o in outs[1:]:
+        np.testing.assert_array_equal(o, outs[0])
+
+
+def test_tiny_moe_smaller_batch_reuses_the_sampled_queue(tiny_moe_model):
+    """A batch below the sampled size runs on the larger queue: surplus router, row-tile and combine
+    slots are no-ops that still notify (Sec. 3.1), and nothing is re-created between the steps."""
+    etc = _etc()
+    s, m = synth.TINY_MOE, tiny_moe_model
+    dec = etc.Decoder(s, kv_chunk_tokens=32, sampled_batches=[8], max_kv_len=129, moe_tile_m=2,
+                      debug_flags=etc.DEBUG_EXEC_COUNT | etc.DEBUG_LAYER_HIDDEN | etc.DEBUG_ROUTING, spin_budget=SPIN)
+    m.bind(dec)
+    for i, B in enumerate((8, 3, 1, 6)):
+        rng = np.random.default_rng(B)
+        step = fixed_step(s, B, rng.integers(0, 100, size=B), m.n_pool_pages, seed=50 + i)
+        m.reset_pools()
+        dec.bind_step(step)
+        check_moe_step(dec, m, s, step, 2, step_index=i)
+    dec.close()

@@ -163,3 +163,90 @@ def test_descriptor_validation_errors_are_reported():
     with pytest.raises(etc.EtcError) as ei:
         etc.plan_build(bad, 32, 1, 4, max_kv_len=64)
     assert ei.value.status == -1 and "256" in str(ei.value)
+
+
+# ---------------------------------------------------------------- MoE layers (Sec. 2.4 under static scheduling)
+FN_ROUTER_LOGITS, FN_ROUTER, FN_MOE_GATEUP, FN_MOE_DOWN, FN_COMBINE = 10, 11, 12, 13, 14
+DYN_ROWTILE = 4
+
+
+def _max_row_tiles_brute(E, K, B, M, rng, trials=300):
+    """Largest sum_e ceil(count_e / M) seen over random and adversarial routings."""
+    best = 0
+    for _ in range(trials):
+        ids = np.stack([rng.choice(E, size=K, replace=False) for _ in range(B)])
+        best = max(best, int(np.ceil(np.bincount(ids.ravel(), minlength=E) / M).sum()))
+    # adversarial: spread the pairs over as many experts as possible, one over a multiple of M where possible
+    n = B * K
+    counts = np.zeros(E, np.int64)
+    counts[: min(E, n)] = 1
+    left = n - int(counts.sum())
+    e = 0
+    while left > 0:
+        add = min(left, M)
+        counts[e % E] += add
+        left -= add
+        e += 1
+    return max(best, int(np.ceil(counts / M).sum()))
+
+
+@pytest.mark.parametrize("kind", [etc.SCHED_STATIC, etc.SCHED_UNFUSED])
+@pytest.mark.parametrize("batch,nq,tile_m", [(1, 5, 16), (4, 16, 2), (3, 256, 1)])
+def test_moe_static_plans_run_to_completion(kind, batch, nq, tile_m):
+    plan = etc.plan_build(synth.TINY_MOE, 32, batch, nq, max_kv_len=129, kind=kind, moe_tile_m=tile_m)
+    ev, done = run_static(plan, np.random.default_rng(batch + nq))
+    assert (ev == 0).all() and (done == 1).all()
+
+
+def test_moe_dynamic_plan_runs_to_completion():
+    plan = etc.plan_build(synth.TINY_MOE, 32, 2, 4, max_kv_len=129, kind=etc.SCHED_DYNAMIC, moe_tile_m=2)
+    ev, done = run_dynamic(plan, 3, np.random.default_rng(0))
+    assert (ev == 0).all() and (done == 1).all()
+
+
+def test_moe_event_counts_and_row_tile_slots():
+    s = synth.TINY_MOE                   # E 16, top-2, moe_F 256, H 256
+    B, M = 5, 2
+    plan = etc.plan_build(s, 32, B, 256, max_kv_len=129, moe_tile_m=M)
+    t, ev = plan["tasks"], plan["ev_init"]
+    l0 = t[t["layer"] == 0]
+    gu, dn = l0[l0["fn"] == FN_MOE_GATEUP], l0[l0["fn"] == FN_MOE_DOWN]
+    slots = len(np.unique(gu["c0"]))
+    # the static grid holds one slot per row tile any routing of B tokens can produce
+    assert slots == (B * s.top_k + min(s.n_experts, B * s.top_k) * (M - 1)) // M
+    assert slots >= _max_row_tiles_brute(s.n_experts, s.top_k, B, M, np.random.default_rng(3))
+    assert ((gu["flags"] & DYN_ROWTILE) != 0).all() and ((dn["flags"] & DYN_ROWTILE) != 0).all()
+    # every row tile is covered exactly once by the tasks of a slot
+    for r in range(slots):
+        g = gu[gu["c0"] == r]
+        assert sorted(sum(([int(a) + i for i in range(int(n))] for a, n in zip(g["c1"], g["c2"])), [])) == list(range(s.moe_F // 8))
+        d = dn[dn["c0"] == r]
+        assert sorted(sum(([int(a) + i for i in range(int(n))] for a, n in zip(d["c1"], d["c2"])), [])) == list(range(s.H // 16))
+        # GroupGEMM-1 -> GroupGEMM-2 stays fine-grained: one event per slot, fed by that slot's tasks only
+        assert len(set(g["notify0"])) == 1 and set(d["wait0"]) == set(g["notify0"])
+        assert ev[g["notify0"][0]] == len(g)
+    # the data-dependent edges collapse to one coarse event each ("E[0]")
+    router = l0[l0["fn"] == FN_ROUTER]
+    assert len(router) == B and len(set(gu["wait0"])) == 1 and ev[gu["wait0"][0]] == B
+    comb = l0[l0["fn"] == FN_COMBINE]
+    assert len(set(comb["wait0"])) == 1 and ev[comb["wait0"][0]] == len(dn)
+    assert (l0["fn"] == FN_ROUTER_LOGITS).sum() == s.n_experts // 16
+
+
+def test_qwen3_moe_plan_shape():
+    q = synth.QWEN3_30B_A3B
+    plan = etc.plan_build(q, 64, 1, 256, max_kv_len=2049)
+    t = plan["tasks"]
+    l0 = t[t["layer"] == 0]
+    # batch 1: 8 routed experts -> 8 row-tile slots; one GroupGEMM task per queue and stage
+    assert (l0["fn"] == FN_MOE_GATEUP).sum() == 256 and (l0["fn"] == FN_MOE_DOWN).sum() == 256
+    assert len(np.unique(l0[l0["fn"] == FN_MOE_GATEUP]["c0"])) == 8
+
+
+def test_moe_descriptor_validation():
+    bad = synth.ModelShape("bad-moe", 1, 256, 4, 2, 64, 0, n_experts=12, top_k=2, moe_F=256)
+    with pytest.raises(etc.EtcError):
+        etc.plan_build(bad, 32, 1, 4, max_kv_len=64)
+    bad = synth.ModelShape("bad-moe", 1, 256, 4, 2, 64, 0, n_experts=16, top_k=2, moe_F=100)
+    with pytest.raises(etc.EtcError):
+        etc.plan_build(bad, 32, 1, 4, max_kv_len=64)

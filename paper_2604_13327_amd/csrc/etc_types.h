@@ -86,6 +86,7 @@ struct Params {
     uint16_t *xmg_hi, *xmg_lo;         // x_mid * g2, split [maxB, H]
     float *ssq_x, *ssq_xmid;           // partial sums of squares per 16-row tile [H/16][kMaxBatch]
     float *qbuf;                       // rotated queries [maxB, nq*d]
+    float *knew, *vnew;                // this step's K (rotated) and V rows in fp32 [maxB, nkv*d]: the cache gets bf16
     uint16_t *attn_hi, *attn_lo;       // attention output, split [maxB, nq*d]
     uint16_t *act_hi, *act_lo;         // silu(gate)*up, split [maxB, F]
     float *part_m, *part_l, *part_o;   // split-KV partials [maxB, nq, max_chunks] (+ [d])

@@ -5,8 +5,10 @@
 // Head dim D is split 8 elements per lane (16-byte loads of a bf16 K or V row slice), so D/8 lanes
 // cover one key and a wavefront covers 64/(D/8) keys per load instruction; the 8 wavefronts of the
 // workgroup stride over the chunk.  Reductions are wavefront shuffles, then LDS across waves.
-// Cached K/V rows are read-only during the launch (ordinary loads); the row appended by this step, the
-// queries and the partials cross tasks and are accessed with device-scope loads / stores.
+// Cached K/V rows are read-only during the launch (ordinary loads).  The row appended by this step is
+// not read back from the cache (where it is bf16) but taken in fp32 from the projection's scratch copy,
+// so the new token enters its own attention unrounded; that copy, the queries and the partials cross
+// tasks and are accessed with device-scope loads / stores.
 #pragma once
 #include "device_rt.hip.h"
 
@@ -56,21 +58,16 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
             const int j = jb0 + u * kWaves * TPW + tq;
-            val[u] = j < j1;
-            jcs[u] = val[u] ? j : j1 - 1;
+            val[u] = j < j1 && j != n_keys - 1;          // the new token is handled after the loop
+            jcs[u] = j < j1 ? j : j1 - 1;
             page[u] = gld_i32(pages + jcs[u] / P.page);
         }
         u32x4 krs[BATCH], vrs[BATCH];
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
             const size_t off = lbase + (((size_t)page[u] * P.page + (size_t)(jcs[u] % P.page)) * P.nkv + kvh) * (size_t)D + dl * 8;
-            if (jcs[u] == n_keys - 1) {      // the row this step appended: written by another task of this launch
-                krs[u] = ld_16B(P.kpool + off);
-                vrs[u] = ld_16B(P.vpool + off);
-            } else {
-                krs[u] = gld_16B(P.kpool + off);
-                vrs[u] = gld_16B(P.vpool + off);
-            }
+            krs[u] = gld_16B(P.kpool + off);
+            vrs[u] = gld_16B(P.vpool + off);
         }
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
@@ -102,6 +99,36 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
                     for (int i = 0; i < 8; ++i) o[g][i] = o[g][i] * sc + p * vf[i];
                     mx[g] = nm;
                 }
+            }
+        }
+    }
+
+    // the token of this step (last key of the last chunk): fp32 row from the projection tasks; the key
+    // group tq == 0 of wavefront 0 folds it into its running softmax
+    if (j1 == n_keys && wave == 0) {
+        const float *kn = P.knew + ((size_t)b * P.nkv + kvh) * (size_t)D + dl * 8;
+        const float *vn = P.vnew + ((size_t)b * P.nkv + kvh) * (size_t)D + dl * 8;
+        float kf[8], vf[8];
+#pragma unroll
+        for (int i = 0; i < 8; i += 2) {
+            ld_f32x2(kn + i, kf[i], kf[i + 1]);
+            ld_f32x2(vn + i, vf[i], vf[i + 1]);
+        }
+#pragma unroll
+        for (int g = 0; g < GRP; ++g) {
+            float s = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) s += q[g][i] * kf[i];
+#pragma unroll
+            for (int off2 = 1; off2 < LPT; off2 <<= 1) s += __shfl_xor(s, off2, 64);
+            if (tq == 0) {
+                const float nm = fmaxf(mx[g], s);
+                const float sc = __expf(mx[g] - nm);
+                const float p = __expf(s - nm);
+                l[g] = l[g] * sc + p;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) o[g][i] = o[g][i] * sc + p * vf[i];
+                mx[g] = nm;
             }
         }
     }

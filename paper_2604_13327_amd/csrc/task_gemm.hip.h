@@ -459,6 +459,10 @@ __device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &
             uint16_t *dst = (is_k ? P.kpool : P.vpool) + off;
             st_u16(dst + i, f32_to_bf16_bits(a));
             st_u16(dst + i + half, f32_to_bf16_bits(c));
+            // this step's attention takes the new row unrounded (the cache keeps bf16)
+            float *cur = (is_k ? P.knew : P.vnew) + ((size_t)b * P.nkv + kvh) * (size_t)P.d;
+            st_f32(cur + i, a);
+            st_f32(cur + i + half, c);
         }
         break;
     }

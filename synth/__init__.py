@@ -45,6 +45,9 @@ def _lib():
         f.restype = None
         f.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_uint32,
                       ctypes.c_uint32, ctypes.c_void_p]
+    lib.synth_fill_f32_blocks.restype = None
+    lib.synth_fill_f32_blocks.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                                          ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p]
     return lib
 
 
@@ -109,6 +112,19 @@ def tensor_f32(seed: int, tensor_id: int, n: int, mean: float, sigma: float, i0:
     tab = normal_table(mean, sigma)
     _lib().synth_fill_f32(out.ctypes.data, n, i0, k1, k2, tab.ctypes.data)
     return out
+
+
+def fill_blocks_f32(out: np.ndarray, seed: int, tensor_id: int, blocks, block_elems: int, mean: float,
+                    sigma: float) -> None:
+    """Writes the blocks `blocks` (block b = elements [b*block_elems, (b+1)*block_elems)) of a synthetic
+    tensor into `out`, which holds the tensor in full; everything else in `out` is left as it is."""
+    assert out.dtype == np.float32 and out.flags.c_contiguous
+    blocks = np.ascontiguousarray(blocks, dtype=np.int32)
+    assert blocks.size == 0 or (blocks.min() >= 0 and (int(blocks.max()) + 1) * block_elems <= min(out.size, 1 << 32))
+    k1, k2 = keys(seed, tensor_id)
+    tab = normal_table(mean, sigma)
+    _lib().synth_fill_f32_blocks(out.ctypes.data, blocks.ctypes.data, blocks.size, block_elems, k1, k2,
+                                 tab.ctypes.data)
 
 
 from .workloads import *  # noqa: E402,F401,F403

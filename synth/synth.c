@@ -47,3 +47,17 @@ void synth_fill_f32(float *out, int64_t n, int64_t i0, uint32_t key1, uint32_t k
     for (int64_t i = 0; i < n; ++i)
         o[i] = (uint32_t)table[synth_hash(key1, key2, (uint32_t)(i0 + i)) & 0xFFFFu] << 16;
 }
+
+/* Fills selected blocks of a tensor that is laid out in full at `out`: block b covers the
+ * elements [b * block_elems, (b + 1) * block_elems).  Other elements are left untouched. */
+void synth_fill_f32_blocks(float *out, const int32_t *blocks, int64_t n_blocks, int64_t block_elems,
+                           uint32_t key1, uint32_t key2, const uint16_t *table)
+{
+    uint32_t *o = (uint32_t *)out;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < n_blocks; ++j) {
+        int64_t base = (int64_t)blocks[j] * block_elems;
+        for (int64_t i = 0; i < block_elems; ++i)
+            o[base + i] = (uint32_t)table[synth_hash(key1, key2, (uint32_t)(base + i)) & 0xFFFFu] << 16;
+    }
+}

@@ -92,6 +92,15 @@ def kv_pool_f32(s: ModelShape, seed: int, layer: int, n_pages: int) -> tuple[np.
     return k, v
 
 
+def kv_pool_pages_f32(s: ModelShape, seed: int, layer: int, kbuf: np.ndarray, vbuf: np.ndarray, page_ids) -> None:
+    """Fills only the listed physical pages of one layer's K and V pools (full-size fp32 buffers of
+    kv_pool_shape): what an oracle run over a few sequences reads, without generating the whole pool."""
+    from . import fill_blocks_f32
+    page_elems = s.page * s.nkv * s.d
+    fill_blocks_f32(kbuf.reshape(-1), seed, layer * 64 + KIND["kpool"], page_ids, page_elems, 0.0, 1.0)
+    fill_blocks_f32(vbuf.reshape(-1), seed, layer * 64 + KIND["vpool"], page_ids, page_elems, 0.0, 1.0)
+
+
 def hidden_f32(s: ModelShape, seed: int, step: int, batch: int) -> np.ndarray:
     from . import tensor_f32
     return tensor_f32(seed, HIDDEN_TID0 + step, batch * s.H, 0.0, 1.0).reshape(batch, s.H)

@@ -76,3 +76,34 @@ def fixed_step(shape, batch: int, kv_len, n_pool_pages: int, seed: int):
     indptr[1:] = np.cumsum(npg)
     page_ids = rng.permutation(n_pool_pages)[: indptr[-1]].astype(np.int32)
     return synth.Step(batch, kv_len, indptr, page_ids)
+
+
+def sub_step(step, sel):
+    """The step restricted to the sequences `sel` (same physical pages): sequences of a dense decoder do
+    not interact, so the oracle can check a few of them without computing the whole batch."""
+    sel = [int(b) for b in sel]
+    pages = [step.page_ids[step.page_indptr[b]:step.page_indptr[b + 1]] for b in sel]
+    indptr = np.zeros(len(sel) + 1, dtype=np.int32)
+    indptr[1:] = np.cumsum([len(p) for p in pages])
+    return synth.Step(len(sel), step.kv_len[sel].astype(np.int32), indptr, np.concatenate(pages).astype(np.int32))
+
+
+class SparsePools:
+    """Full-size fp32 K/V pool buffers of one layer in which only the pages a step reads are generated."""
+
+    def __init__(self, shape, seed: int, n_pool_pages: int):
+        self.shape, self.seed = shape, seed
+        self.k = np.zeros(synth.kv_pool_shape(shape, n_pool_pages), dtype=np.float32)
+        self.v = np.zeros_like(self.k)
+
+    def of(self, layer: int, page_ids):
+        synth.kv_pool_pages_f32(self.shape, self.seed, layer, self.k, self.v, page_ids)
+        return self.k, self.v
+
+
+def oracle_on_sequences(shape, seed: int, step, sel, step_index: int, weights_of, pools: SparsePools):
+    """CPU oracle over the sequences `sel` of a step; returns its dict (final, layers)."""
+    import oracle
+    sub = sub_step(step, sel)
+    x0 = synth.hidden_f32(shape, seed, step_index, step.batch)[[int(b) for b in sel]]
+    return oracle.decode_step(shape, shape.n_layers, x0, weights_of, lambda l: pools.of(l, sub.page_ids), sub)

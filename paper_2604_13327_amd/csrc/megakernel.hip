@@ -174,11 +174,8 @@ __device__ __forceinline__ void setup_moe_gemm(const Params &P, const Task &t, c
     }
 }
 
-// tn: the task this workgroup runs next (fn = FN_NOP if unknown): a projection task starts streaming
-// the next projection task's weights while it finishes its own.
 template <bool SYNC_EVENTS>
-__device__ __forceinline__ void run_task(const Params &P, const Params &PL, const Task &t, const Task &tn, float *sm,
-                                         WgState &st)
+__device__ __forceinline__ void run_task(const Params &P, const Params &PL, const Task &t, float *sm, WgState &st)
 {
     const int w0 = SYNC_EVENTS ? t.wait0 : -1, w1 = SYNC_EVENTS ? t.wait1 : -1;
     TaskWaits tw{w0, w1, (int)t.fn, (t.flags & TF_WAIT0_PER_WAVE) != 0 && SYNC_EVENTS, w0};
@@ -186,27 +183,17 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
     Epilogue e{};
     if (t.flags & TF_DYN_ROWTILE) {      // GroupGEMM tile: wait first, then look the row tile up
         wg_wait_cached(P, st, w0, w1, t.fn);
-        wg_state_drop_weights(st);
         RowTile rt;
         if (!resolve_row_tile(P, t.c0, rt)) return;        // surplus slot of the static grid: nothing to do but notify
         setup_moe_gemm(P, t, rt, g, e);
         tw = TaskWaits{-1, -1, (int)t.fn, false, w0 < 0 ? -1 : w0 + ((t.c0 + 1) << 20)};
-        gemm_tile_dispatch(P, PL, g, e, tw, sm, st, t.id, nullptr, 0, -1);
+        gemm_tile_dispatch(P, PL, g, e, tw, sm, st, t.id);
         return;
     }
     if (setup_gemm(P, t, g, e)) {
-        GemmTile gn{};
-        Epilogue en{};
-        const uint16_t *wnext = nullptr;
-        int n_it_next = 0;
-        if (setup_gemm(P, tn, gn, en)) {
-            wnext = lane_weight_row(gn);
-            n_it_next = (gn.K / kWaves) >> 5;
-        }
-        gemm_tile_dispatch(P, PL, g, e, tw, sm, st, t.id, wnext, n_it_next, tn.id);
+        gemm_tile_dispatch(P, PL, g, e, tw, sm, st, t.id);
         return;
     }
-    wg_state_drop_weights(st);
     switch (t.fn) {
     case FN_ROWSUM_PARTIAL:
         wg_wait_cached(P, st, w0, w1, t.fn);
@@ -313,11 +300,10 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_static(const Params P)
     Task t = q0 < q1 ? load_task(P.tasks + q0) : Task{};
     for (int i = q0; i < q1; ++i) {
         Task tn{};
-        tn.id = -1;
-        if (i + 1 < q1) tn = load_task(P.tasks + i + 1);
+        if (i + 1 < q1) tn = load_task(P.tasks + i + 1);      // fetched early: off the critical path of the next task
         trace_mark(P, t.id, 0);
         trace_mark(P, t.id, 7);
-        run_task<true>(P, sP, t, tn, sm, st);
+        run_task<true>(P, sP, t, sm, st);
         trace_mark(P, t.id, 4);
         wg_release();
         if (threadIdx.x == 0) {
@@ -383,11 +369,9 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
         __syncthreads();
         if (id < 0) break;
         const Task t = load_task(P.dyn_tasks + id);
-        Task tn{};
-        tn.id = -1;
         WgState st;
         wg_state_init(st);
-        run_task<true>(P, sP, t, tn, sm, st);  // early push (App. E): remaining in-edges are still waited on
+        run_task<true>(P, sP, t, sm, st);  // early push (App. E): remaining in-edges are still waited on
         wg_release();
         if (threadIdx.x == 0) {
             if (P.debug_flags & 1u) atomicAdd(P.exec_count + t.id, 1);
@@ -412,11 +396,9 @@ __global__ void __launch_bounds__(kWgThreads) stage_kernel(const Params P, int f
     __shared__ Params sP;
     stage_params(P, &sP);
     const Task t = load_task(P.dyn_tasks + first + blockIdx.x);
-    Task tn{};
-    tn.id = -1;
     WgState st;
     wg_state_init(st);
-    run_task<false>(P, sP, t, tn, sm, st);
+    run_task<false>(P, sP, t, sm, st);
 }
 
 }  // namespace etc

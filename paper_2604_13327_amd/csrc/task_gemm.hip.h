@@ -58,11 +58,22 @@ struct Epilogue {
     int col0;                 // MoE: first destination row (permuted row of column 0)
 };
 
+// What an epilogue thread needs from memory, fetched before the streaming loop so that the epilogue
+// itself issues no load (a load issued behind the weight stream returns only after it: memory
+// operations of a wavefront complete in order).
+struct EpiPre {
+    float a, b;       // RESID: the two residual values; QKV: cos and sin of the rotation angle
+    float ga, gb;     // RESID: gains of the two rows for the consumer's operand
+    int page;         // QKV (k / v heads): physical page of the appended row
+    int pos;          // QKV: position of the new token
+};
+__device__ __forceinline__ EpiPre epilogue_preload(const Params &P, const Epilogue &e, int col, int mp);
+__device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &e, int col, int mp, float lo, float hi,
+                                               const EpiPre &pre);
+
 constexpr int PF = 16;                            // weight loads in flight per lane (16 KB per wave)
 
 __device__ __forceinline__ u32x4 load16_nt(const uint16_t *p) { return gld_16B_nt(p); }
-
-__device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &e, int col, int mp, float lo, float hi);
 
 // Waits of a projection task.  per_wave: wave w waits on ev0 + w (its own K slice) on its own.
 struct TaskWaits {
@@ -71,33 +82,19 @@ struct TaskWaits {
     int op_key;          // identifies the operand a staged copy in LDS holds (-1: never reuse a copy)
 };
 
-// State a persistent workgroup carries from task to task (registers, uniform across the workgroup
-// except for the weight fragments).
+// State a persistent workgroup carries from task to task (uniform across the workgroup).
 struct WgState {
-    u32x4 wr[PF];        // weight fragments in flight: steps 0..PF-1 of task `wr_task` sit in slots 0..PF-1
-    int wr_task;         // -1: nothing prefetched
-    int wr_n;            // how many leading slots of that task are in flight
     int zero0, zero1;    // events already seen at zero in this launch (they never re-arm inside a launch)
-    int staged_key;      // event that gates the operand currently staged in LDS (-1: none)
+    int staged_key;      // operand currently staged in LDS (-1: none)
 };
 
 __device__ __forceinline__ void wg_state_init(WgState &st)
 {
-#pragma unroll
-    for (int j = 0; j < PF; ++j) st.wr[j] = u32x4{0, 0, 0, 0};
-    st.wr_task = -1;
-    st.wr_n = 0;
     st.zero0 = st.zero1 = -1;
     st.staged_key = -1;
 }
 
-// Drops prefetched fragments (before a task that does not stream weights, so the registers are free).
-__device__ __forceinline__ void wg_state_drop_weights(WgState &st)
-{
-#pragma unroll
-    for (int j = 0; j < PF; ++j) st.wr[j] = u32x4{0, 0, 0, 0};
-    st.wr_task = -1;
-}
+__device__ __forceinline__ bool event_known_zero(const WgState &st, int ev) { return ev < 0 || ev == st.zero0 || ev == st.zero1; }
 
 __device__ __forceinline__ const uint16_t *lane_weight_row(const GemmTile &g)
 {
@@ -228,7 +225,7 @@ __device__ __forceinline__ void gemm_tile_unstaged(const Params &P, const GemmTi
             lo *= r;
             hi *= r;
         }
-        apply_epilogue(P, e, col, mp, lo, hi);
+        apply_epilogue(P, e, col, mp, lo, hi, epilogue_preload(P, e, col, mp));
     }
     __syncthreads();     // the reduction buffer is reused by the next tile
 }
@@ -247,19 +244,19 @@ __device__ __noinline__ void gemm_tiles_cold(const Params &PL, GemmTile g, Epilo
 
 // Latency-critical path (at most 16 columns whose whole operand fits in LDS).  The operand (all columns,
 // full K, hi and lo) is copied into LDS once per stage with device-scope loads and reused by every
-// tile of that stage this workgroup runs.  A task streams its n_tiles row tiles back to back; the ring
-// of weight fragments never drains between tiles, nor between this task and the next projection task.
-// Each wave parks its partial tile in LDS; one barrier, one reduction and one epilogue per task.
+// tile of that stage this workgroup runs.  A task streams its n_tiles row tiles back to back through a
+// ring of PF weight fragments per lane that never drains between tiles; each wave parks its partial
+// tile in LDS; one barrier, one reduction and one epilogue per task.
 //
-// A wave's ring of PF weight fragments is refilled as it is consumed: with this tile's later steps, and
-// in a tile's last PF steps with the first steps of whatever follows (the next tile, or the first tile of
-// the next projection task), so the ring is full again when that work starts.  (A variant with
-// unconditional in-place refills, which lets the compiler wait with vmcnt(PF-1) instead of draining at
-// every group of PF steps, was measured and was not faster: a CU sustains ~22-25 GB/s either way, and the
-// epilogues got slower behind the deeper queue.)
+// Order of memory operations.  A wavefront's loads return in order, so anything issued behind the
+// weight stream waits for it.  Hence: the first PF weight loads are issued BEFORE the task waits on its
+// events (weight prefetch, Sec. 3.4) by every wave except the one that polls the event, which keeps its
+// queue empty until the event is seen; after the event every wave issues its operand loads first and the
+// polling wave its weight loads right behind them; the epilogue's inputs are fetched before the streaming
+// loop.  (Streaming the NEXT task's first fragments during the tail of the loop was measured: it delays
+// this task's epilogue and notify by a full memory round trip under load and costs 10 % per step.)
 __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTile &g, const Epilogue &e, const TaskWaits &w,
-                                                  float *sm, WgState &st, int task_id, const uint16_t *wnext,
-                                                  int n_it_next, int next_task_id)
+                                                  float *sm, WgState &st, int task_id)
 {
     const int wave = wave_id(), lane = lane_id();
     const int m = lane & 15, kg = lane >> 4;
@@ -268,24 +265,31 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
     const uint16_t *wcur = lane_weight_row(g);
     const size_t tile_step = (size_t)g.tile_rows * (size_t)g.ldw;
 
-    // ---- weight prefetch: before the wait (unless the previous task already streamed it in) ----
-    if (st.wr_task != task_id) {
-#pragma unroll
-        for (int j = 0; j < PF; ++j) {
-            if (j < n_it) st.wr[j] = load16_nt(wcur + j * 32);
-            else st.wr[j] = u32x4{0, 0, 0, 0};
-        }
-    }
-    st.wr_task = -1;
-
     ETC_AS_LDS float *red = as_lds(sm);               // [tile][wave][col][16 rows]
     ETC_AS_LDS float *rs = red + kRedFloats;
     ETC_AS_LDS uint16_t *op_hi = reinterpret_cast<ETC_AS_LDS uint16_t *>(red + kRedFloats + kRsFloats);
     ETC_AS_LDS uint16_t *op_lo = op_hi + (size_t)g.n_cols * g.K;
 
-    // ---- E.wait(), then stage the operand unless this stage's operand is already in LDS ----------
     const int key = w.op_key;
-    if (key < 0 || key != st.staged_key) {
+    const bool restage = key < 0 || key != st.staged_key;
+    bool will_wait;
+    if (!restage) will_wait = !event_known_zero(st, w.ev1);
+    else if (w.per_wave) will_wait = w.ev0 >= 0 || w.ev1 >= 0;
+    else will_wait = !event_known_zero(st, w.ev0) || !event_known_zero(st, w.ev1);
+    const bool defer = will_wait && wave == 0 && !(P.debug_flags & 32u);        // the polling wave issues its weight loads after the event
+
+    u32x4 wr[PF];
+    auto prefetch = [&]() {
+#pragma unroll
+        for (int j = 0; j < PF; ++j) {
+            if (j < n_it) wr[j] = load16_nt(wcur + j * 32);
+            else wr[j] = u32x4{0, 0, 0, 0};
+        }
+    };
+    if (!defer) prefetch();
+
+    if (restage) {
+        // ---- E.wait() ---------------------------------------------------------------------------
         if (w.per_wave) {           // the staged copy needs every K slice: lanes 0..7 of wave 0 poll one slice each
             if (wave == 0 && lane < kWaves) spin_until_zero(P, w.ev0 + lane, w.fn);
             if (threadIdx.x == 0 && w.ev1 >= 0) spin_until_zero(P, w.ev1, w.fn);
@@ -295,32 +299,101 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
             wg_wait_cached(P, st, w.ev0, w.ev1, w.fn);
         }
         trace_mark(P, task_id, 1);
+        // ---- stage the operand: all loads of a thread in flight at once ---------------------------
+        constexpr int U = 8;
         const int quads = g.K >> 2;                         // 8-byte pieces per column
-        for (int idx = threadIdx.x; idx < g.n_cols * quads; idx += kWgThreads) {
-            const int col = idx / quads, q = idx - col * quads;
-            int row = g.col_rows ? ld_i32(g.col_rows + col) : col;
-            if (row < 0) row = 0;
-            const uint64_t vh = ld_u64(g.b_hi + (size_t)row * (size_t)g.ldb + q * 4);
-            const uint64_t vl = ld_u64(g.b_lo + (size_t)row * (size_t)g.ldb + q * 4);
-            *reinterpret_cast<ETC_AS_LDS uint64_t *>(op_hi + (size_t)col * g.K + q * 4) = vh;
-            *reinterpret_cast<ETC_AS_LDS uint64_t *>(op_lo + (size_t)col * g.K + q * 4) = vl;
+        const int total = g.n_cols * quads;
+        float sq[8];                                        // RMSNorm: this lane's partial sums of squares of column `wave`
+        const bool one_col_per_wave = g.ssq_parts != nullptr && g.n_cols <= kWaves && g.n_parts <= 512;
+        if (total <= kWgThreads * U) {
+            uint64_t vh[U], vl[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int idx = (int)threadIdx.x + u * kWgThreads;
+                vh[u] = vl[u] = 0;
+                if (idx < total) {
+                    const int col = idx / quads, q = idx - col * quads;
+                    int row = g.col_rows ? ld_i32(g.col_rows + col) : col;
+                    if (row < 0) row = 0;
+                    vh[u] = ld_u64(g.b_hi + (size_t)row * (size_t)g.ldb + q * 4);
+                    vl[u] = ld_u64(g.b_lo + (size_t)row * (size_t)g.ldb + q * 4);
+                }
+            }
+            if (one_col_per_wave && wave < g.n_cols) {
+                const int row = g.col_rows ? ld_i32(g.col_rows + wave) : wave;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int pt = lane + 64 * j;
+                    sq[j] = (pt < g.n_parts && row >= 0) ? ld_f32(g.ssq_parts + (size_t)pt * kMaxBatch + row) : 0.f;
+                }
+            }
+            if (defer) prefetch();                          // behind this wave's operand loads, ahead of nothing it waits for
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int idx = (int)threadIdx.x + u * kWgThreads;
+                if (idx < total) {
+                    const int col = idx / quads, q = idx - col * quads;
+                    *reinterpret_cast<ETC_AS_LDS uint64_t *>(op_hi + (size_t)col * g.K + q * 4) = vh[u];
+                    *reinterpret_cast<ETC_AS_LDS uint64_t *>(op_lo + (size_t)col * g.K + q * 4) = vl[u];
+                }
+            }
+        } else {
+            for (int idx = threadIdx.x; idx < total; idx += kWgThreads) {
+                const int col = idx / quads, q = idx - col * quads;
+                int row = g.col_rows ? ld_i32(g.col_rows + col) : col;
+                if (row < 0) row = 0;
+                const uint64_t vh = ld_u64(g.b_hi + (size_t)row * (size_t)g.ldb + q * 4);
+                const uint64_t vl = ld_u64(g.b_lo + (size_t)row * (size_t)g.ldb + q * 4);
+                *reinterpret_cast<ETC_AS_LDS uint64_t *>(op_hi + (size_t)col * g.K + q * 4) = vh;
+                *reinterpret_cast<ETC_AS_LDS uint64_t *>(op_lo + (size_t)col * g.K + q * 4) = vl;
+            }
+            if (one_col_per_wave && wave < g.n_cols) {
+                const int row = g.col_rows ? ld_i32(g.col_rows + wave) : wave;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int pt = lane + 64 * j;
+                    sq[j] = (pt < g.n_parts && row >= 0) ? ld_f32(g.ssq_parts + (size_t)pt * kMaxBatch + row) : 0.f;
+                }
+            }
+            if (defer) prefetch();
         }
-        if (g.ssq_parts) {
-            for (int col = wave; col < g.n_cols; col += kWaves) {
-                const int row = g.col_rows ? ld_i32(g.col_rows + col) : col;
-                float s = 0.f;
-                if (row >= 0)
-                    for (int p = lane; p < g.n_parts; p += 64) s += ld_f32(g.ssq_parts + (size_t)p * kMaxBatch + row);
-                s = wave_sum(s);
-                if (lane == 0) rs[col] = 1.0f / sqrtf(s / (float)g.K + g.eps);
+        if (g.ssq_parts) {       // RMSNorm factor of every column: fixed-order sum of the producers' partial sums of squares
+            if (one_col_per_wave) {
+                if (wave < g.n_cols) {
+                    float s = ((sq[0] + sq[1]) + (sq[2] + sq[3])) + ((sq[4] + sq[5]) + (sq[6] + sq[7]));
+                    s = wave_sum(s);
+                    if (lane == 0) rs[wave] = 1.0f / sqrtf(s / (float)g.K + g.eps);
+                }
+            } else {
+                for (int col = wave; col < g.n_cols; col += kWaves) {
+                    const int row = g.col_rows ? ld_i32(g.col_rows + col) : col;
+                    float s = 0.f;
+                    if (row >= 0)
+                        for (int pt = lane; pt < g.n_parts; pt += 64) s += ld_f32(g.ssq_parts + (size_t)pt * kMaxBatch + row);
+                    s = wave_sum(s);
+                    if (lane == 0) rs[col] = 1.0f / sqrtf(s / (float)g.K + g.eps);
+                }
             }
         }
         st.staged_key = key;
         __syncthreads();
     } else {
         wg_wait_cached(P, st, w.ev1, -1, w.fn);
+        if (defer) prefetch();
     }
     trace_mark(P, task_id, 2);
+
+    // ---- what the epilogue will need (single pass of the epilogue loop only) ---------------------
+    const int per_tile = g.n_cols * 8;
+    const int n_out = g.n_tiles * per_tile;
+    const bool pre_ok = n_out <= kWgThreads && !(P.debug_flags & 64u);
+    EpiPre pre{};
+    if (pre_ok && (int)threadIdx.x < n_out) {
+        const int ti = (int)threadIdx.x / per_tile, r = (int)threadIdx.x - ti * per_tile;
+        Epilogue et = e;
+        et.row0 = e.row0 + ti * g.tile_rows;
+        pre = epilogue_preload(P, et, r >> 3, r & 7);
+    }
 
     const bool valid = m < g.n_cols;
     ETC_AS_LDS const uint16_t *sh = op_hi + (size_t)(valid ? m : 0) * (size_t)g.K + kbase;
@@ -329,20 +402,19 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
 
     for (int ti = 0; ti < g.n_tiles; ++ti) {
         const bool last = ti + 1 == g.n_tiles;
-        const uint16_t *wnx = last ? wnext : wcur + tile_step;       // what streams in behind this tile
-        const int n_nx = last ? n_it_next : n_it;
-        const bool cont = can_cont && wnx != nullptr;
+        const uint16_t *wnx = wcur + tile_step;           // the next tile of this task streams in behind this one
+        const bool cont = can_cont && !last;
         f32x4 acc = f32x4{0, 0, 0, 0};
         for (int it = 0; it < n_it; it += PF) {
 #pragma unroll
             for (int j = 0; j < PF; ++j) {
                 const int s = it + j;
                 if (s < n_it) {
-                    const bf16x8 a = __builtin_bit_cast(bf16x8, st.wr[j]);
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, wr[j]);
                     if (s + PF < n_it) {
-                        st.wr[j] = load16_nt(wcur + (s + PF) * 32);
-                    } else if (cont) {       // the slot freed at step s receives step s % PF of what follows
-                        if (j < n_nx) st.wr[j] = load16_nt(wnx + j * 32);
+                        wr[j] = load16_nt(wcur + (s + PF) * 32);
+                    } else if (cont) {       // the slot freed at step s receives step s % PF of the next tile
+                        wr[j] = load16_nt(wnx + j * 32);
                     }
                     u32x4 bh = u32x4{0, 0, 0, 0}, bl = u32x4{0, 0, 0, 0};
                     if (valid) {
@@ -359,17 +431,15 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
         if (!cont && !last) {          // short K: no streaming across tiles, plain prefetch of the next tile
 #pragma unroll
             for (int j = 0; j < PF; ++j)
-                if (j < n_it) st.wr[j] = load16_nt(wnx + j * 32);
+                if (j < n_it) wr[j] = load16_nt(wnx + j * 32);
         }
-        if (last && cont) st.wr_task = next_task_id;
         wcur = wnx;
     }
 
     // ---- one reduction (fixed wave order) and one epilogue for all tiles of the task -------------
     trace_mark(P, task_id, 3);
     __syncthreads();
-    const int per_tile = g.n_cols * 8;
-    for (int idx = threadIdx.x; idx < g.n_tiles * per_tile; idx += kWgThreads) {
+    for (int idx = threadIdx.x; idx < n_out; idx += kWgThreads) {
         const int ti = idx / per_tile, r = idx - ti * per_tile;
         const int col = r >> 3, mp = r & 7;
         float lo = 0.f, hi = 0.f;
@@ -387,23 +457,22 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
         Epilogue et = e;
         et.row0 = e.row0 + ti * g.tile_rows;
         if (e.ssq_out) et.ssq_out = e.ssq_out + (size_t)ti * kMaxBatch;
-        apply_epilogue(P, et, col, mp, lo, hi);
+        if (!pre_ok) pre = epilogue_preload(P, et, col, mp);
+        apply_epilogue(P, et, col, mp, lo, hi, pre);
     }
 }
 
 // PL is the workgroup's LDS copy of the parameters: a kernel argument cannot be passed by address to
 // the out-of-line paths.
 __device__ __forceinline__ void gemm_tile_dispatch(const Params &P, const Params &PL, const GemmTile &g, const Epilogue &e,
-                                                   const TaskWaits &w, float *sm, WgState &st, int task_id,
-                                                   const uint16_t *wnext, int n_it_next, int next_task_id)
+                                                   const TaskWaits &w, float *sm, WgState &st, int task_id)
 {
     const bool fits = (size_t)g.n_cols * (size_t)g.K * 4 <= (size_t)kOperandBytes &&
                       g.n_tiles * g.n_cols * kWaves * 16 <= kRedFloats;
     if (g.n_cols <= kStagedMaxCols && fits) {
-        gemm_tiles_staged(P, g, e, w, sm, st, task_id, wnext, n_it_next, next_task_id);
+        gemm_tiles_staged(P, g, e, w, sm, st, task_id);
         return;
     }
-    wg_state_drop_weights(st);
     st.staged_key = -1;
     if (g.n_cols <= 16) gemm_tiles_cold<1>(PL, g, e, w, sm);
     else if (g.n_cols <= 32) gemm_tiles_cold<2>(PL, g, e, w, sm);
@@ -433,18 +502,37 @@ __device__ __forceinline__ void store_split(uint16_t *hi_p, uint16_t *lo_p, size
     st_u16(lo_p + idx, l);
 }
 
-__device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &e, int col, int mp, float lo, float hi)
+__device__ __forceinline__ EpiPre epilogue_preload(const Params &P, const Epilogue &e, int col, int mp)
+{
+    EpiPre pre{};
+    if (e.kind == EPI_QKV) {
+        const int b = col, i = e.row0 + mp;
+        pre.pos = gld_i32(P.kv_len + b);
+        if (e.head < P.nq + P.nkv) rope_cos_sin(P, pre.pos, i, &pre.a, &pre.b);   // q and k heads are rotated to position pos
+        if (e.head >= P.nq) pre.page = gld_i32(P.page_ids + gld_i32(P.page_indptr + b) + pre.pos / P.page);
+    } else if (e.kind == EPI_RESID) {
+        const size_t o0 = (size_t)col * e.ld + e.row0 + mp;
+        pre.a = ld_f32(e.resid + o0);
+        pre.b = ld_f32(e.resid + o0 + 8);
+        if (e.next_gain) {
+            pre.ga = bf16_bits_to_f32(gld_u16(e.next_gain + e.row0 + mp));
+            pre.gb = bf16_bits_to_f32(gld_u16(e.next_gain + e.row0 + mp + 8));
+        }
+    }
+    return pre;
+}
+
+__device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &e, int col, int mp, float lo, float hi,
+                                               const EpiPre &pre)
 {
     switch (e.kind) {
     case EPI_QKV: {
         const int b = col, half = P.d >> 1, i = e.row0 + mp;
-        const int pos = gld_i32(P.kv_len + b);
+        const int pos = pre.pos;
         float a = lo, c = hi;
-        if (e.head < P.nq + P.nkv) {   // q and k heads are rotated to position pos
-            float cs, sn;
-            rope_cos_sin(P, pos, i, &cs, &sn);
-            a = lo * cs - hi * sn;
-            c = lo * sn + hi * cs;
+        if (e.head < P.nq + P.nkv) {
+            a = lo * pre.a - hi * pre.b;
+            c = lo * pre.b + hi * pre.a;
         }
         if (e.head < P.nq) {
             float *q = P.qbuf + (size_t)b * (size_t)(P.nq * P.d) + (size_t)e.head * P.d;
@@ -453,9 +541,8 @@ __device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &
         } else {
             const bool is_k = e.head < P.nq + P.nkv;
             const int kvh = is_k ? e.head - P.nq : e.head - P.nq - P.nkv;
-            const int page = gld_i32(P.page_ids + gld_i32(P.page_indptr + b) + pos / P.page);
             const size_t off = (size_t)e.layer * (size_t)P.pool_layer_stride +
-                               (((size_t)page * P.page + (size_t)(pos % P.page)) * P.nkv + kvh) * (size_t)P.d;
+                               (((size_t)pre.page * P.page + (size_t)(pos % P.page)) * P.nkv + kvh) * (size_t)P.d;
             uint16_t *dst = (is_k ? P.kpool : P.vpool) + off;
             st_u16(dst + i, f32_to_bf16_bits(a));
             st_u16(dst + i + half, f32_to_bf16_bits(c));
@@ -469,12 +556,12 @@ __device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &
     case EPI_RESID: {
         const int b = col;
         const size_t o0 = (size_t)b * e.ld + e.row0 + mp, o1 = o0 + 8;
-        const float v0 = ld_f32(e.resid + o0) + lo, v1 = ld_f32(e.resid + o1) + hi;
+        const float v0 = pre.a + lo, v1 = pre.b + hi;
         st_f32(e.outf + o0, v0);
         st_f32(e.outf + o1, v1);
         if (e.next_gain) {   // operand of the next projection: (value * gain) split
-            store_split(e.out_hi, e.out_lo, o0, v0 * bf16_bits_to_f32(gld_u16(e.next_gain + e.row0 + mp)));
-            store_split(e.out_hi, e.out_lo, o1, v1 * bf16_bits_to_f32(gld_u16(e.next_gain + e.row0 + mp + 8)));
+            store_split(e.out_hi, e.out_lo, o0, v0 * pre.ga);
+            store_split(e.out_hi, e.out_lo, o1, v1 * pre.gb);
         }
         float s = v0 * v0 + v1 * v1;      // this tile's sum of squares: the 8 threads of a column are 8 consecutive lanes
         s += __shfl_xor(s, 1, 64);

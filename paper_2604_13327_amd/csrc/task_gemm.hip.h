@@ -249,12 +249,14 @@ __device__ __noinline__ void gemm_tiles_cold(const Params &PL, GemmTile g, Epilo
 // tile in LDS; one barrier, one reduction and one epilogue per task.
 //
 // Order of memory operations.  A wavefront's loads return in order, so anything issued behind the
-// weight stream waits for it.  Hence: the first PF weight loads are issued BEFORE the task waits on its
-// events (weight prefetch, Sec. 3.4) by every wave except the one that polls the event, which keeps its
-// queue empty until the event is seen; after the event every wave issues its operand loads first and the
-// polling wave its weight loads right behind them; the epilogue's inputs are fetched before the streaming
-// loop.  (Streaming the NEXT task's first fragments during the tail of the loop was measured: it delays
-// this task's epilogue and notify by a full memory round trip under load and costs 10 % per step.)
+// weight stream waits for it.  The first PF weight loads are issued BEFORE the task waits on its events
+// (weight prefetch, Sec. 3.4); the epilogue's inputs are fetched before the streaming loop, so the
+// epilogue issues no load.  Measured alternatives that lost: streaming the NEXT task's first fragments
+// during the tail of the loop (the epilogue's loads and the drain before the notify then queue behind that
+// stream: +10 % per step); keeping the polling wavefront's queue free of weight loads until the event is
+// seen (+2 %); one control wavefront that polls, stages and runs the epilogue while seven wavefronts
+// stream (+10 %: the compute unit's read rate follows the bytes it keeps in flight, and the gap between
+// two stages is longer than what its registers can buffer either way).
 __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTile &g, const Epilogue &e, const TaskWaits &w,
                                                   float *sm, WgState &st, int task_id)
 {
@@ -272,12 +274,6 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
 
     const int key = w.op_key;
     const bool restage = key < 0 || key != st.staged_key;
-    bool will_wait;
-    if (!restage) will_wait = !event_known_zero(st, w.ev1);
-    else if (w.per_wave) will_wait = w.ev0 >= 0 || w.ev1 >= 0;
-    else will_wait = !event_known_zero(st, w.ev0) || !event_known_zero(st, w.ev1);
-    const bool defer = will_wait && wave == 0 && !(P.debug_flags & 32u);        // the polling wave issues its weight loads after the event
-
     u32x4 wr[PF];
     auto prefetch = [&]() {
 #pragma unroll
@@ -286,7 +282,7 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
             else wr[j] = u32x4{0, 0, 0, 0};
         }
     };
-    if (!defer) prefetch();
+    prefetch();
 
     if (restage) {
         // ---- E.wait() ---------------------------------------------------------------------------
@@ -327,7 +323,6 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
                     sq[j] = (pt < g.n_parts && row >= 0) ? ld_f32(g.ssq_parts + (size_t)pt * kMaxBatch + row) : 0.f;
                 }
             }
-            if (defer) prefetch();                          // behind this wave's operand loads, ahead of nothing it waits for
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int idx = (int)threadIdx.x + u * kWgThreads;
@@ -355,7 +350,6 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
                     sq[j] = (pt < g.n_parts && row >= 0) ? ld_f32(g.ssq_parts + (size_t)pt * kMaxBatch + row) : 0.f;
                 }
             }
-            if (defer) prefetch();
         }
         if (g.ssq_parts) {       // RMSNorm factor of every column: fixed-order sum of the producers' partial sums of squares
             if (one_col_per_wave) {
@@ -379,14 +373,13 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
         __syncthreads();
     } else {
         wg_wait_cached(P, st, w.ev1, -1, w.fn);
-        if (defer) prefetch();
     }
     trace_mark(P, task_id, 2);
 
     // ---- what the epilogue will need (single pass of the epilogue loop only) ---------------------
     const int per_tile = g.n_cols * 8;
     const int n_out = g.n_tiles * per_tile;
-    const bool pre_ok = n_out <= kWgThreads && !(P.debug_flags & 64u);
+    const bool pre_ok = n_out <= kWgThreads;
     EpiPre pre{};
     if (pre_ok && (int)threadIdx.x < n_out) {
         const int ti = (int)threadIdx.x / per_tile, r = (int)threadIdx.x - ti * per_tile;

@@ -282,11 +282,22 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
             else wr[j] = u32x4{0, 0, 0, 0};
         }
     };
-    prefetch();
+    // A task that has nothing to wait for (its events are already known to have fired, or it runs without
+    // events in the kernel-by-kernel comparator) issues its operand loads first and the weight stream right
+    // behind them: loads return in order, so the operand would otherwise arrive a full round trip under load
+    // later.  A task that has to wait prefetches first.  (Deciding this with one extra poll at task start was
+    // measured: the round trip it adds on every workgroup costs more than it saves on the last one.)
+    const bool will_wait = restage ? (!event_known_zero(st, w.ev0) || w.per_wave || !event_known_zero(st, w.ev1))
+                                   : !event_known_zero(st, w.ev1);
+    const bool fired = !will_wait;
+    if (!fired) prefetch();
 
     if (restage) {
         // ---- E.wait() ---------------------------------------------------------------------------
-        if (w.per_wave) {           // the staged copy needs every K slice: lanes 0..7 of wave 0 poll one slice each
+        if (fired) {
+            if (!w.per_wave && !event_known_zero(st, w.ev0)) { st.zero1 = st.zero0; st.zero0 = w.ev0; }
+            if (!event_known_zero(st, w.ev1)) { st.zero1 = st.zero0; st.zero0 = w.ev1; }
+        } else if (w.per_wave) {    // the staged copy needs every K slice: lanes 0..7 of wave 0 poll one slice each
             if (wave == 0 && lane < kWaves) spin_until_zero(P, w.ev0 + lane, w.fn);
             if (threadIdx.x == 0 && w.ev1 >= 0) spin_until_zero(P, w.ev1, w.fn);
             __syncthreads();
@@ -323,6 +334,7 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
                     sq[j] = (pt < g.n_parts && row >= 0) ? ld_f32(g.ssq_parts + (size_t)pt * kMaxBatch + row) : 0.f;
                 }
             }
+            if (fired) prefetch();                          // right behind the operand loads
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int idx = (int)threadIdx.x + u * kWgThreads;
@@ -350,6 +362,7 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
                     sq[j] = (pt < g.n_parts && row >= 0) ? ld_f32(g.ssq_parts + (size_t)pt * kMaxBatch + row) : 0.f;
                 }
             }
+            if (fired) prefetch();
         }
         if (g.ssq_parts) {       // RMSNorm factor of every column: fixed-order sum of the producers' partial sums of squares
             if (one_col_per_wave) {
@@ -372,7 +385,12 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
         st.staged_key = key;
         __syncthreads();
     } else {
-        wg_wait_cached(P, st, w.ev1, -1, w.fn);
+        if (fired) {
+            if (!event_known_zero(st, w.ev1)) { st.zero1 = st.zero0; st.zero0 = w.ev1; }
+            prefetch();
+        } else {
+            wg_wait_cached(P, st, w.ev1, -1, w.fn);
+        }
     }
     trace_mark(P, task_id, 2);
 

@@ -34,6 +34,7 @@ const char *kDynamicOffMsg = "the dynamic scheduler is switched off: its kernel 
 
 struct DevPlan {          // one instantiated plan (one sampled batch size), host + device copies
     int sampled_batch = 0;
+    int kv_chunk = 0;     // keys per attention task of this plan
     Plan host;
     Task *d_queue_tasks = nullptr, *d_tasks = nullptr;
     int32_t *d_queue_begin = nullptr, *d_ev_init = nullptr, *d_ev_consumers = nullptr, *d_consumer_ids = nullptr,
@@ -202,6 +203,7 @@ void fill_launch_params(etc_ctx *c, Params &P)
     P.B = c->bound_batch;
     P.Bs = dp.sampled_batch;
     P.max_chunks = c->max_chunks;
+    if (dp.kv_chunk > 0) P.kv_chunk = dp.kv_chunk;
     P.kv_len = c->d_kv_len;
     P.page_indptr = c->d_page_indptr;
     P.page_ids = c->d_page_ids;
@@ -312,7 +314,8 @@ etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc
         c->plans.emplace_back();
         DevPlan &dp = c->plans.back();
         dp.sampled_batch = s->sampled_batch[i];
-        int syms[4] = {dp.sampled_batch, c->max_chunks, 0, 0};
+        dp.kv_chunk = effective_kv_chunk(t->kv_chunk_tokens, m->page_size, s->max_kv_len, dp.sampled_batch, m->n_kv_heads, c->n_queues);
+        int syms[4] = {dp.sampled_batch, (s->max_kv_len + dp.kv_chunk - 1) / dp.kv_chunk, 0, 0};
         std::string err = build_decoder_graph(d, dp.sampled_batch, c->n_queues, s->kind != ETC_SCHED_DYNAMIC, &c->graph);
         if (!err.empty()) { c->err = err; return bail(ETC_EINVAL); }
         err = instantiate(c->graph, syms, c->n_queues, s->kind == ETC_SCHED_UNFUSED, &dp.host);
@@ -594,7 +597,8 @@ etc_status etc_plan_build(const etc_model_desc *m, const etc_tile_desc *t, const
     if (!err.empty()) return fail(nullptr, ETC_EINVAL, err);
     Plan *p = new (std::nothrow) Plan();
     if (!p) return fail(nullptr, ETC_ENOMEM, "out of host memory");
-    int syms[4] = {sampled_batch, (s->max_kv_len + t->kv_chunk_tokens - 1) / t->kv_chunk_tokens, 0, 0};
+    const int chunk = effective_kv_chunk(t->kv_chunk_tokens, m->page_size, s->max_kv_len, sampled_batch, m->n_kv_heads, n_queues);
+    int syms[4] = {sampled_batch, (s->max_kv_len + chunk - 1) / chunk, 0, 0};
     err = instantiate(g, syms, n_queues, s->kind == ETC_SCHED_UNFUSED, p);
     if (!err.empty()) { delete p; return fail(nullptr, ETC_EINVAL, err); }
     out->n_tasks = (int64_t)p->tasks.size();

@@ -196,6 +196,14 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
             while (cand > 1 && (tiles % cand || per_slice % cand || cand * Bs * kWaves * 16 > kRedFloats)) --cand;
             r_gu = std::max(1, cand);
         }
+    } else {
+        // Large batches take the chunked path: every task reads the whole operand, so a task streams a few
+        // row tiles against one pass over it (as many as keep at least one task per queue).
+        if (sub % 2 == 0) r_qkv = 2;
+        if (m.E == 0) {
+            const int per_slice = m.F / 8 / kWaves;
+            r_gu = per_slice % 4 == 0 ? 4 : (per_slice % 2 == 0 ? 2 : 1);
+        }
     }
 
     int stage = 0;

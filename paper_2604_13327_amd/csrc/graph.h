@@ -89,6 +89,21 @@ inline int moe_max_row_tiles(int n_experts, int top_k, int batch, int tile_m)
     return (n + nonempty * (tile_m - 1)) / tile_m;
 }
 
+// Keys per split-KV attention task for one sampled batch size.  `min_chunk` is the caller's tile shape; it
+// is enlarged (in whole pages) when (batch x kv heads) alone already gives about two tasks per queue, so
+// that long sequences of a large batch are not cut into thousands of latency-bound tasks.
+inline int effective_kv_chunk(int min_chunk, int page, int max_kv_len, int batch, int n_kv_heads, int n_queues)
+{
+    const int pairs = batch * n_kv_heads, target = 2 * n_queues;
+    int chunks = (target + pairs - 1) / pairs;
+    const int most = (max_kv_len + min_chunk - 1) / min_chunk;
+    if (chunks > most) chunks = most;
+    if (chunks < 1) chunks = 1;
+    int chunk = (max_kv_len + chunks - 1) / chunks;
+    chunk = (chunk + page - 1) / page * page;
+    return chunk < min_chunk ? min_chunk : chunk;
+}
+
 // The decoder's graph function for one sampled batch size.  Symbol 0 = that batch size, symbol 1 =
 // chunk slots per sequence.  n_queues and the batch decide how many consecutive row tiles one
 // projection task streams (tile shapes are a degree of freedom of the graph, Sec. 2.1).

@@ -213,11 +213,14 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
             wg_wait_cached(P, st, w0, w1, t.fn);
             st.staged_key = -1;      // the attention scratch overlaps the staged operand
             const int grp = P.nq / P.nkv;
-            if (P.d == 128 && grp == 4) attn_chunk<128, 4>(PL, t.layer, b, kvh, ch, sm);
-            else if (P.d == 128 && grp == 8) attn_chunk<128, 8>(PL, t.layer, b, kvh, ch, sm);
-            else if (P.d == 64 && grp == 2) attn_chunk<64, 2>(PL, t.layer, b, kvh, ch, sm);
-            else if (P.d == 128 && grp == 1) attn_chunk<128, 1>(PL, t.layer, b, kvh, ch, sm);
-            else if (P.d == 64 && grp == 4) attn_chunk<64, 4>(PL, t.layer, b, kvh, ch, sm);
+            const bool lds_pages = P.kv_chunk > 128;      // more than one batch of keys per chunk
+#define ETC_ATTN(DD, GG)                                                                   \
+    if (P.d == DD && grp == GG) {                                                          \
+        if (lds_pages) attn_chunk<DD, GG, true>(PL, t.layer, b, kvh, ch, sm);              \
+        else attn_chunk<DD, GG, false>(PL, t.layer, b, kvh, ch, sm);                       \
+    }
+            ETC_ATTN(128, 4) else ETC_ATTN(128, 8) else ETC_ATTN(64, 2) else ETC_ATTN(128, 1) else ETC_ATTN(64, 4)
+#undef ETC_ATTN
         }
         break;
     }

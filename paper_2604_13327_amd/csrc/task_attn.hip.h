@@ -14,7 +14,7 @@
 
 namespace etc {
 
-template <int D, int GRP>
+template <int D, int GRP, bool PAGES_IN_LDS>
 __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int kvh, int ch, float *sm)
 {
     constexpr int LPT = D / 8;        // lanes per key
@@ -48,9 +48,16 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
         for (int i = 0; i < 8; ++i) o[g][i] = 0.f;
     }
 
-    // Keys are taken in batches of BATCH wavefront steps: the page ids of a batch are read first, then all
-    // its K and V rows are requested, then the arithmetic runs, so a batch costs two memory round trips.
+    // The chunk's slice of the page table goes to LDS first (one round trip, shared with the query loads
+    // above); keys are then taken in batches of BATCH wavefront steps: all K and V rows of a batch are
+    // requested, then the arithmetic runs, so a batch costs one memory round trip.
+    ETC_AS_LDS int *s_pg = reinterpret_cast<ETC_AS_LDS int *>(as_lds(sm)) + 10240;     // behind the 40 KB of reduction scratch
+    const int pg0 = j0 / P.page, n_pg = (j1 - 1) / P.page - pg0 + 1;
     constexpr int BATCH = 4;
+    if (PAGES_IN_LDS) {            // chunks of one batch (PAGES_IN_LDS false) read their page ids straight from memory
+        for (int i = threadIdx.x; i < n_pg; i += kWgThreads) s_pg[i] = gld_i32(pages + pg0 + i);
+        __syncthreads();
+    }
     for (int jb0 = j0 + wave * TPW; jb0 < j1; jb0 += BATCH * kWaves * TPW) {   // uniform trip count per wave
         int page[BATCH];
         bool val[BATCH];
@@ -60,7 +67,7 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
             const int j = jb0 + u * kWaves * TPW + tq;
             val[u] = j < j1 && j != n_keys - 1;          // the new token is handled after the loop
             jcs[u] = j < j1 ? j : j1 - 1;
-            page[u] = gld_i32(pages + jcs[u] / P.page);
+            page[u] = PAGES_IN_LDS ? s_pg[jcs[u] / P.page - pg0] : gld_i32(pages + jcs[u] / P.page);
         }
         u32x4 krs[BATCH], vrs[BATCH];
 #pragma unroll

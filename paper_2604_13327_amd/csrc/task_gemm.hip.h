@@ -473,6 +473,188 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
     }
 }
 
+// Out-of-line path for batches above 16 columns, or operands too large for a whole copy in LDS.
+// The operand is walked in chunks of kChunkK elements of K: a chunk of ALL columns (hi and lo) sits in LDS,
+// double buffered; while the wavefronts run the MFMAs of chunk c out of one buffer, every thread already
+// has its 8-byte pieces of chunk c+1 in flight into registers and drops them into the other buffer at the
+// end of the chunk: one barrier per chunk, no wait on the operand's round trip.  Within a chunk each of the
+// 8 wavefronts owns 32 elements of K (one MFMA step); a task streams up to kChunkTiles row tiles against
+// one pass over the operand (the operand, which every task has to read in full, is then read once per
+// kChunkTiles tiles), with the same ring of PF weight fragments in flight per lane as the staged path,
+// running over (chunk, tile) pairs.
+constexpr int kChunkK = 256;
+constexpr int kChunkStride = kChunkK + 8;     // LDS column stride in elements: 16 columns cover all banks
+constexpr int kChunkTiles = 4;
+
+template <int NB>
+__device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epilogue e, TaskWaits w, float *sm)
+{
+    constexpr int T = kChunkTiles;
+    constexpr int COLS = NB * 16;
+    constexpr int U = COLS / 8;                    // 8-byte pieces per thread, chunk and half: COLS * 64 / 512
+    constexpr int BUF = 2 * COLS * kChunkStride;   // elements of one buffer: hi columns, then lo columns
+    static_assert(PF % T == 0, "the ring holds whole chunks");
+    static_assert((size_t)2 * BUF * 2 + (64 + 512) * 4 <= (size_t)kLdsBytes, "two operand buffers and the norm scratch fit");
+    static_assert((size_t)kWaves * NB * 256 * 4 <= (size_t)BUF * 2, "the reduction buffer aliases one operand buffer");
+    const int wave = wave_id(), lane = lane_id();
+    const int m = lane & 15, kg = lane >> 4;
+    const int n_chunks = g.K / kChunkK;
+    const int n_tiles = g.n_tiles;
+    const size_t tile_step = (size_t)g.tile_rows * (size_t)g.ldw;
+    const uint16_t *wbase = (m < 8 ? g.rowsA + (size_t)m * (size_t)g.ldw : g.rowsB + (size_t)(m - 8) * (size_t)g.ldw) +
+                            wave * 32 + kg * 8;
+
+    ETC_AS_LDS uint16_t *buf0 = reinterpret_cast<ETC_AS_LDS uint16_t *>(as_lds(sm));
+    ETC_AS_LDS float *red = as_lds(sm);                                  // after the last chunk
+    ETC_AS_LDS float *rs = reinterpret_cast<ETC_AS_LDS float *>(buf0 + 2 * BUF);
+    ETC_AS_LDS float *rs_part = rs + 64;                                  // [8][64]
+
+    // ---- weight prefetch before the wait: steps (chunk, tile) = (j / T, j % T) ------------------------
+    u32x4 wr[PF];
+#pragma unroll
+    for (int j = 0; j < PF; ++j) {
+        const int c = j / T, ti = j % T;
+        if (c < n_chunks && ti < n_tiles) wr[j] = load16_nt(wbase + (size_t)ti * tile_step + c * kChunkK);
+        else wr[j] = u32x4{0, 0, 0, 0};
+    }
+    // ---- E.wait(): the operand is needed in full, so every K slice event is waited for ---------------
+    if (w.per_wave) {
+        if (wave == 0 && lane < kWaves) spin_until_zero(P, w.ev0 + lane, w.fn);
+        if (threadIdx.x == 0 && w.ev1 >= 0) spin_until_zero(P, w.ev1, w.fn);
+        __syncthreads();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    } else {
+        wg_wait(P, w.ev0, w.ev1, w.fn);
+    }
+
+    // this thread's columns of every chunk: wave + 8u, piece `lane` (4 elements) of the chunk
+    int rows[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int col = wave + 8 * u;
+        rows[u] = -1;
+        if (col < g.n_cols) rows[u] = g.col_rows ? ld_i32(g.col_rows + col) : col;
+    }
+    uint64_t vh[U], vl[U];
+    auto fetch_chunk = [&](int c) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            vh[u] = vl[u] = 0;
+            if (rows[u] >= 0) {
+                const size_t off = (size_t)rows[u] * (size_t)g.ldb + (size_t)c * kChunkK + lane * 4;
+                vh[u] = ld_u64(g.b_hi + off);
+                vl[u] = ld_u64(g.b_lo + off);
+            }
+        }
+    };
+    auto park_chunk = [&](int b) {
+        ETC_AS_LDS uint16_t *hi = buf0 + b * BUF, *lo = hi + COLS * kChunkStride;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int col = wave + 8 * u;
+            *reinterpret_cast<ETC_AS_LDS uint64_t *>(hi + col * kChunkStride + lane * 4) = vh[u];
+            *reinterpret_cast<ETC_AS_LDS uint64_t *>(lo + col * kChunkStride + lane * 4) = vl[u];
+        }
+    };
+    fetch_chunk(0);
+
+    // ---- RMSNorm factors: thread (column, group) sums every 8th partial sum of squares, groups meet in LDS ----
+    if (g.ssq_parts) {
+        const int col = threadIdx.x & 63;
+        int row = -1;
+        if (col < g.n_cols) row = g.col_rows ? ld_i32(g.col_rows + col) : col;
+        float s = 0.f;
+        for (int p0 = wave; p0 < g.n_parts; p0 += 8 * 16) {
+            float t[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int pt = p0 + 8 * j;
+                t[j] = (pt < g.n_parts && row >= 0) ? ld_f32(g.ssq_parts + (size_t)pt * kMaxBatch + row) : 0.f;
+            }
+#pragma unroll
+            for (int j = 0; j < 16; ++j) s += t[j];
+        }
+        rs_part[wave * 64 + col] = s;
+    }
+    park_chunk(0);
+    __syncthreads();
+    if (g.ssq_parts && threadIdx.x < 64) {
+        float s = 0.f;
+#pragma unroll
+        for (int gq = 0; gq < 8; ++gq) s += rs_part[gq * 64 + threadIdx.x];
+        rs[threadIdx.x] = 1.0f / sqrtf(s / (float)g.K + g.eps);
+    }
+
+    f32x4 acc[T][NB];
+#pragma unroll
+    for (int ti = 0; ti < T; ++ti)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) acc[ti][nb] = f32x4{0, 0, 0, 0};
+
+    constexpr int CPR = PF / T;                    // chunks per revolution of the ring
+    for (int c0 = 0; c0 < n_chunks; c0 += CPR) {
+#pragma unroll
+        for (int cc = 0; cc < CPR; ++cc) {
+            const int c = c0 + cc;
+            if (c < n_chunks) {                    // uniform
+                const int b = (CPR % 2 == 0) ? (cc & 1) : (c & 1);
+                if (c + 1 < n_chunks) fetch_chunk(c + 1);
+                ETC_AS_LDS const uint16_t *hi = buf0 + b * BUF + m * kChunkStride + wave * 32 + kg * 8;
+                ETC_AS_LDS const uint16_t *lo = hi + COLS * kChunkStride;
+#pragma unroll
+                for (int ti = 0; ti < T; ++ti) {
+                    if (ti < n_tiles) {
+                        const int j = cc * T + ti;
+                        const bf16x8 a = __builtin_bit_cast(bf16x8, wr[j]);
+                        if (c + CPR < n_chunks) wr[j] = load16_nt(wbase + (size_t)ti * tile_step + (size_t)(c + CPR) * kChunkK);
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb) {
+                            const u32x4 bh = *reinterpret_cast<ETC_AS_LDS const u32x4 *>(hi + nb * 16 * kChunkStride);
+                            const u32x4 bl = *reinterpret_cast<ETC_AS_LDS const u32x4 *>(lo + nb * 16 * kChunkStride);
+                            acc[ti][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bh), acc[ti][nb], 0, 0, 0);
+                            acc[ti][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bl), acc[ti][nb], 0, 0, 0);
+                        }
+                    }
+                }
+                if (c + 1 < n_chunks) park_chunk(b ^ 1);
+                __syncthreads();
+            }
+        }
+    }
+
+    // ---- per tile: partials of the 8 wavefronts through LDS, fixed order, epilogue ----------------------
+#pragma unroll
+    for (int ti = 0; ti < T; ++ti) {
+        if (ti < n_tiles) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                *reinterpret_cast<ETC_AS_LDS f32x4 *>(red + ((size_t)(wave * NB + nb) * 64 + lane) * 4) = acc[ti][nb];
+            __syncthreads();
+            Epilogue et = e;
+            et.row0 = e.row0 + ti * g.tile_rows;
+            if (e.ssq_out) et.ssq_out = e.ssq_out + (size_t)ti * kMaxBatch;
+            for (int idx = threadIdx.x; idx < g.n_cols * 8; idx += kWgThreads) {
+                const int col = idx >> 3, mp = idx & 7;
+                const int nb = col >> 4, n = col & 15;
+                float lo = 0.f, hi = 0.f;
+#pragma unroll
+                for (int wv = 0; wv < kWaves; ++wv) {
+                    ETC_AS_LDS const float *base = red + (size_t)(wv * NB + nb) * 256;
+                    lo += base[(n + 16 * (mp >> 2)) * 4 + (mp & 3)];
+                    hi += base[(n + 16 * ((mp + 8) >> 2)) * 4 + (mp & 3)];
+                }
+                if (g.ssq_parts) {
+                    const float r = rs[col];
+                    lo *= r;
+                    hi *= r;
+                }
+                apply_epilogue(P, et, col, mp, lo, hi, epilogue_preload(P, et, col, mp));
+            }
+            __syncthreads();
+        }
+    }
+}
+
 // PL is the workgroup's LDS copy of the parameters: a kernel argument cannot be passed by address to
 // the out-of-line paths.
 __device__ __forceinline__ void gemm_tile_dispatch(const Params &P, const Params &PL, const GemmTile &g, const Epilogue &e,
@@ -485,6 +667,12 @@ __device__ __forceinline__ void gemm_tile_dispatch(const Params &P, const Params
         return;
     }
     st.staged_key = -1;
+    if (g.n_tiles <= kChunkTiles) {
+        if (g.n_cols <= 16) gemm_tiles_chunked<1>(PL, g, e, w, sm);
+        else if (g.n_cols <= 32) gemm_tiles_chunked<2>(PL, g, e, w, sm);
+        else gemm_tiles_chunked<4>(PL, g, e, w, sm);
+        return;
+    }
     if (g.n_cols <= 16) gemm_tiles_cold<1>(PL, g, e, w, sm);
     else if (g.n_cols <= 32) gemm_tiles_cold<2>(PL, g, e, w, sm);
     else gemm_tiles_cold<4>(PL, g, e, w, sm);

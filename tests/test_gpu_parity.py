@@ -224,3 +224,30 @@ def test_watchdog_turns_a_stuck_wait_into_an_error():
         g.event_counters()
     assert ei.value.status == -5
     g.close()
+
+
+@pytest.mark.parametrize("batch", [17, 40, 64])
+def test_tiny_large_batches_take_the_chunked_path(batch):
+    """Batches above 16 columns: operand walked in double-buffered LDS chunks, 2 and 4 MFMA column blocks,
+    several row tiles per task; ragged lengths including an empty cache."""
+    etc = _etc()
+    s = synth.TINY
+    n_pool = batch * synth.pages_needed(128, s.page) + 8
+    model = GpuModel(s, seed=13, n_pool_pages=n_pool)
+    rng = np.random.default_rng(batch)
+    kv = rng.integers(0, 129, size=batch)
+    kv[0], kv[-1] = 0, 128
+    step = fixed_step(s, batch, kv, n_pool, seed=batch)
+    dec = etc.Decoder(s, kv_chunk_tokens=32, sampled_batches=[batch], max_kv_len=129,
+                      debug_flags=etc.DEBUG_EXEC_COUNT | etc.DEBUG_LAYER_HIDDEN, spin_budget=SPIN)
+    model.bind(dec)
+    out = _run(dec, model, step)
+    _check_invariants(dec)
+    ref = oracle_step(s, model.seed, n_pool, step, 0)
+    for l in range(s.n_layers):
+        assert rel_err(dec.layer_hidden(l), ref["layers"][l]) <= TOL, f"layer {l}"
+    assert rel_err(out, ref["final"]) <= TOL
+    model.reset_pools()
+    out2 = _run(dec, model, step, kbk=True)
+    np.testing.assert_array_equal(out2, out)
+    dec.close()

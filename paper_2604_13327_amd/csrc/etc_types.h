@@ -16,6 +16,15 @@ constexpr int kRsFloats = 64;                     // LDS: RMSNorm factors of the
 constexpr int kOperandBytes = kLdsBytes - (kRedFloats + kRsFloats) * 4;   // LDS left for a staged operand
 constexpr int kStagedMaxCols = 16;                // widest batch the staged (latency-critical) projection path takes
 
+// LDS layout of the staged projection path: reduction buffer [tiles][waves][cols][16], norm factors, then
+// the whole operand (all columns, hi and lo).  A task takes that path when this fits.
+constexpr long long staged_red_floats(int n_tiles, int n_cols) { return (long long)n_tiles * n_cols * kWaves * 16; }
+constexpr bool staged_fits(int n_tiles, int n_cols, int K)
+{
+    return n_cols <= kStagedMaxCols &&
+           (staged_red_floats(n_tiles, n_cols) + kRsFloats) * 4 + (long long)n_cols * K * 4 <= (long long)kLdsBytes;
+}
+
 // Device functions (task bodies).  One entry of the dispatch switch each (Alg. 1 "dispatch logic").
 enum Fn : uint8_t {
     FN_NOP = 0,

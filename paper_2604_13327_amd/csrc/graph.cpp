@@ -185,15 +185,15 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
     // streams several consecutive tiles back to back (one reduction, one notify), sized so that a
     // stage is about one task per queue.
     auto staged_ok = [&](int K) {
-        return Bs <= kStagedMaxCols && (long long)Bs * K * 4 <= (long long)kOperandBytes;
+        return staged_fits(1, Bs, K);
     };
     int r_qkv = 1, r_gu = 1;
     if (staged_ok(m.H)) {
-        if ((m.nq + 2 * m.nkv) * sub > n_queues && sub % 2 == 0 && 2 * Bs * kWaves * 16 <= kRedFloats) r_qkv = 2;
+        if ((m.nq + 2 * m.nkv) * sub > n_queues && sub % 2 == 0 && staged_fits(2, Bs, m.H)) r_qkv = 2;
         if (m.E == 0) {
             const int tiles = m.F / 8, per_slice = tiles / kWaves;
             int cand = tiles / std::max(1, n_queues);
-            while (cand > 1 && (tiles % cand || per_slice % cand || cand * Bs * kWaves * 16 > kRedFloats)) --cand;
+            while (cand > 1 && (tiles % cand || per_slice % cand || !staged_fits(cand, Bs, m.H))) --cand;
             r_gu = std::max(1, cand);
         }
     } else {

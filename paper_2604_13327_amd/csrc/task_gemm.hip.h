@@ -268,8 +268,8 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
     const size_t tile_step = (size_t)g.tile_rows * (size_t)g.ldw;
 
     ETC_AS_LDS float *red = as_lds(sm);               // [tile][wave][col][16 rows]
-    ETC_AS_LDS float *rs = red + kRedFloats;
-    ETC_AS_LDS uint16_t *op_hi = reinterpret_cast<ETC_AS_LDS uint16_t *>(red + kRedFloats + kRsFloats);
+    ETC_AS_LDS float *rs = red + staged_red_floats(g.n_tiles, g.n_cols);
+    ETC_AS_LDS uint16_t *op_hi = reinterpret_cast<ETC_AS_LDS uint16_t *>(rs + kRsFloats);
     ETC_AS_LDS uint16_t *op_lo = op_hi + (size_t)g.n_cols * g.K;
 
     const int key = w.op_key;
@@ -474,16 +474,14 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
 }
 
 // Out-of-line path for batches above 16 columns, or operands too large for a whole copy in LDS.
-// The operand is walked in chunks of kChunkK elements of K: a chunk of ALL columns (hi and lo) sits in LDS,
+// The operand is walked in chunks of KC elements of K: a chunk of ALL columns (hi and lo) sits in LDS,
 // double buffered; while the wavefronts run the MFMAs of chunk c out of one buffer, every thread already
 // has its 8-byte pieces of chunk c+1 in flight into registers and drops them into the other buffer at the
-// end of the chunk: one barrier per chunk, no wait on the operand's round trip.  Within a chunk each of the
-// 8 wavefronts owns 32 elements of K (one MFMA step); a task streams up to kChunkTiles row tiles against
-// one pass over the operand (the operand, which every task has to read in full, is then read once per
-// kChunkTiles tiles), with the same ring of PF weight fragments in flight per lane as the staged path,
-// running over (chunk, tile) pairs.
-constexpr int kChunkK = 256;
-constexpr int kChunkStride = kChunkK + 8;     // LDS column stride in elements: 16 columns cover all banks
+// end of the chunk: one barrier per chunk.  KC = 1024 / (16-column blocks), i.e. 64 KB per buffer, so a
+// chunk's arithmetic lasts longer than the round trip of the next chunk's loads.  Within a chunk a
+// wavefront owns 32 of every 256 elements of K (KC / 256 MFMA steps); a task streams up to kChunkTiles row
+// tiles against one pass over the operand (which every task has to read in full), with the same ring of PF
+// weight fragments in flight per lane as the staged path, running over (chunk, step, tile) triples.
 constexpr int kChunkTiles = 4;
 
 template <int NB>
@@ -491,14 +489,20 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epi
 {
     constexpr int T = kChunkTiles;
     constexpr int COLS = NB * 16;
-    constexpr int U = COLS / 8;                    // 8-byte pieces per thread, chunk and half: COLS * 64 / 512
-    constexpr int BUF = 2 * COLS * kChunkStride;   // elements of one buffer: hi columns, then lo columns
-    static_assert(PF % T == 0, "the ring holds whole chunks");
+    constexpr int KC = 1024 / NB;                  // K elements per chunk
+    constexpr int S = KC / 256;                    // MFMA steps per wavefront, chunk and tile
+    constexpr int STRIDE = KC + 8;                 // LDS column stride in elements: 16 columns cover all banks
+    constexpr int U = 8;                           // 8-byte pieces per thread, chunk and half: COLS * KC / 4 / 512
+    constexpr int PPC = KC / 4;                    // 8-byte pieces per column and half
+    constexpr int BUF = 2 * COLS * STRIDE;         // elements of one buffer: hi columns, then lo columns
+    constexpr int CPR = PF / (T * S);              // chunks per revolution of the ring
+    static_assert(COLS * PPC == U * kWgThreads, "every thread moves U pieces of each half");
+    static_assert(CPR >= 1 && CPR * T * S == PF, "the ring holds whole chunks");
     static_assert((size_t)2 * BUF * 2 + (64 + 512) * 4 <= (size_t)kLdsBytes, "two operand buffers and the norm scratch fit");
     static_assert((size_t)kWaves * NB * 256 * 4 <= (size_t)BUF * 2, "the reduction buffer aliases one operand buffer");
     const int wave = wave_id(), lane = lane_id();
     const int m = lane & 15, kg = lane >> 4;
-    const int n_chunks = g.K / kChunkK;
+    const int n_chunks = (g.K + KC - 1) / KC;      // K is a multiple of 256; the last chunk may be partial
     const int n_tiles = g.n_tiles;
     const size_t tile_step = (size_t)g.tile_rows * (size_t)g.ldw;
     const uint16_t *wbase = (m < 8 ? g.rowsA + (size_t)m * (size_t)g.ldw : g.rowsB + (size_t)(m - 8) * (size_t)g.ldw) +
@@ -509,12 +513,14 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epi
     ETC_AS_LDS float *rs = reinterpret_cast<ETC_AS_LDS float *>(buf0 + 2 * BUF);
     ETC_AS_LDS float *rs_part = rs + 64;                                  // [8][64]
 
-    // ---- weight prefetch before the wait: steps (chunk, tile) = (j / T, j % T) ------------------------
+    // ring slot j <-> (chunk j / (S*T) of the revolution, step (j / T) % S, tile j % T)
+    auto step_live = [&](int c, int sidx) { return c * KC + sidx * 256 < g.K; };
+    // ---- weight prefetch before the wait ---------------------------------------------------------------
     u32x4 wr[PF];
 #pragma unroll
     for (int j = 0; j < PF; ++j) {
-        const int c = j / T, ti = j % T;
-        if (c < n_chunks && ti < n_tiles) wr[j] = load16_nt(wbase + (size_t)ti * tile_step + c * kChunkK);
+        const int c = j / (S * T), sidx = (j / T) % S, ti = j % T;
+        if (step_live(c, sidx) && ti < n_tiles) wr[j] = load16_nt(wbase + (size_t)ti * tile_step + c * KC + sidx * 256);
         else wr[j] = u32x4{0, 0, 0, 0};
     }
     // ---- E.wait(): the operand is needed in full, so every K slice event is waited for ---------------
@@ -527,11 +533,13 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epi
         wg_wait(P, w.ev0, w.ev1, w.fn);
     }
 
-    // this thread's columns of every chunk: wave + 8u, piece `lane` (4 elements) of the chunk
-    int rows[U];
+    // this thread's pieces of every chunk: piece tid + 512u = (column, 8-byte piece of the column's chunk)
+    int rows[U], pcs[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int col = wave + 8 * u;
+        const int idx = (int)threadIdx.x + kWgThreads * u;
+        const int col = idx / PPC;
+        pcs[u] = idx - col * PPC;
         rows[u] = -1;
         if (col < g.n_cols) rows[u] = g.col_rows ? ld_i32(g.col_rows + col) : col;
     }
@@ -540,20 +548,21 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epi
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             vh[u] = vl[u] = 0;
-            if (rows[u] >= 0) {
-                const size_t off = (size_t)rows[u] * (size_t)g.ldb + (size_t)c * kChunkK + lane * 4;
+            if (rows[u] >= 0 && c * KC + pcs[u] * 4 < g.K) {
+                const size_t off = (size_t)rows[u] * (size_t)g.ldb + (size_t)c * KC + pcs[u] * 4;
                 vh[u] = ld_u64(g.b_hi + off);
                 vl[u] = ld_u64(g.b_lo + off);
             }
         }
     };
     auto park_chunk = [&](int b) {
-        ETC_AS_LDS uint16_t *hi = buf0 + b * BUF, *lo = hi + COLS * kChunkStride;
+        ETC_AS_LDS uint16_t *hi = buf0 + b * BUF, *lo = hi + COLS * STRIDE;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int col = wave + 8 * u;
-            *reinterpret_cast<ETC_AS_LDS uint64_t *>(hi + col * kChunkStride + lane * 4) = vh[u];
-            *reinterpret_cast<ETC_AS_LDS uint64_t *>(lo + col * kChunkStride + lane * 4) = vl[u];
+            const int idx = (int)threadIdx.x + kWgThreads * u;
+            const int col = idx / PPC;
+            *reinterpret_cast<ETC_AS_LDS uint64_t *>(hi + col * STRIDE + pcs[u] * 4) = vh[u];
+            *reinterpret_cast<ETC_AS_LDS uint64_t *>(lo + col * STRIDE + pcs[u] * 4) = vl[u];
         }
     };
     fetch_chunk(0);
@@ -591,28 +600,33 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epi
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) acc[ti][nb] = f32x4{0, 0, 0, 0};
 
-    constexpr int CPR = PF / T;                    // chunks per revolution of the ring
     for (int c0 = 0; c0 < n_chunks; c0 += CPR) {
 #pragma unroll
         for (int cc = 0; cc < CPR; ++cc) {
             const int c = c0 + cc;
             if (c < n_chunks) {                    // uniform
-                const int b = (CPR % 2 == 0) ? (cc & 1) : (c & 1);
+                const int b = c & 1;
                 if (c + 1 < n_chunks) fetch_chunk(c + 1);
-                ETC_AS_LDS const uint16_t *hi = buf0 + b * BUF + m * kChunkStride + wave * 32 + kg * 8;
-                ETC_AS_LDS const uint16_t *lo = hi + COLS * kChunkStride;
+                ETC_AS_LDS const uint16_t *hi = buf0 + b * BUF + m * STRIDE + wave * 32 + kg * 8;
+                ETC_AS_LDS const uint16_t *lo = hi + COLS * STRIDE;
 #pragma unroll
-                for (int ti = 0; ti < T; ++ti) {
-                    if (ti < n_tiles) {
-                        const int j = cc * T + ti;
-                        const bf16x8 a = __builtin_bit_cast(bf16x8, wr[j]);
-                        if (c + CPR < n_chunks) wr[j] = load16_nt(wbase + (size_t)ti * tile_step + (size_t)(c + CPR) * kChunkK);
+                for (int sidx = 0; sidx < S; ++sidx) {
+                    if (step_live(c, sidx)) {      // uniform
 #pragma unroll
-                        for (int nb = 0; nb < NB; ++nb) {
-                            const u32x4 bh = *reinterpret_cast<ETC_AS_LDS const u32x4 *>(hi + nb * 16 * kChunkStride);
-                            const u32x4 bl = *reinterpret_cast<ETC_AS_LDS const u32x4 *>(lo + nb * 16 * kChunkStride);
-                            acc[ti][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bh), acc[ti][nb], 0, 0, 0);
-                            acc[ti][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bl), acc[ti][nb], 0, 0, 0);
+                        for (int ti = 0; ti < T; ++ti) {
+                            if (ti < n_tiles) {
+                                const int j = (cc * S + sidx) * T + ti;
+                                const bf16x8 a = __builtin_bit_cast(bf16x8, wr[j]);
+                                if (step_live(c + CPR, sidx))
+                                    wr[j] = load16_nt(wbase + (size_t)ti * tile_step + (size_t)(c + CPR) * KC + sidx * 256);
+#pragma unroll
+                                for (int nb = 0; nb < NB; ++nb) {
+                                    const u32x4 bh = *reinterpret_cast<ETC_AS_LDS const u32x4 *>(hi + nb * 16 * STRIDE + sidx * 256);
+                                    const u32x4 bl = *reinterpret_cast<ETC_AS_LDS const u32x4 *>(lo + nb * 16 * STRIDE + sidx * 256);
+                                    acc[ti][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bh), acc[ti][nb], 0, 0, 0);
+                                    acc[ti][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bl), acc[ti][nb], 0, 0, 0);
+                                }
+                            }
                         }
                     }
                 }
@@ -660,9 +674,7 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epi
 __device__ __forceinline__ void gemm_tile_dispatch(const Params &P, const Params &PL, const GemmTile &g, const Epilogue &e,
                                                    const TaskWaits &w, float *sm, WgState &st, int task_id)
 {
-    const bool fits = (size_t)g.n_cols * (size_t)g.K * 4 <= (size_t)kOperandBytes &&
-                      g.n_tiles * g.n_cols * kWaves * 16 <= kRedFloats;
-    if (g.n_cols <= kStagedMaxCols && fits) {
+    if (staged_fits(g.n_tiles, g.n_cols, g.K)) {
         gemm_tiles_staged(P, g, e, w, sm, st, task_id);
         return;
     }

@@ -11,9 +11,7 @@ constexpr int kMaxLayers = 128;
 constexpr int kMaxExperts = 256;
 constexpr int kMaxTopK = 16;
 constexpr int kLdsBytes = 148 * 1024;    // of the 160 KB LDS per CU: exactly one persistent workgroup per CU
-constexpr int kRedFloats = kWaves * 4 * 64 * 4;   // LDS: cross-wave reduction buffer (32 KB)
 constexpr int kRsFloats = 64;                     // LDS: RMSNorm factors of the columns
-constexpr int kOperandBytes = kLdsBytes - (kRedFloats + kRsFloats) * 4;   // LDS left for a staged operand
 constexpr int kStagedMaxCols = 16;                // widest batch the staged (latency-critical) projection path takes
 
 // LDS layout of the staged projection path: reduction buffer [tiles][waves][cols][16], norm factors, then
@@ -69,7 +67,7 @@ struct LayerWeights {
 };
 
 // Error word codes
-enum : int32_t { ERR_NONE = 0, ERR_WAIT_TIMEOUT = 1, ERR_QUEUE_OVERFLOW = 2, ERR_POP_TIMEOUT = 3 };
+enum : int32_t { ERR_NONE = 0, ERR_WAIT_TIMEOUT = 1, ERR_QUEUE_OVERFLOW = 2, ERR_POP_TIMEOUT = 3, ERR_TASK_SHAPE = 4 };
 
 // Everything the megakernel needs, passed by value as the kernel argument.
 struct Params {

@@ -115,133 +115,6 @@ __device__ __forceinline__ void wg_wait_cached(const Params &P, WgState &st, int
     if (need1) { st.zero1 = st.zero0; st.zero0 = ev1; }
 }
 
-// Out-of-line path: one tile at a time, operand fragments straight from memory through a 2-deep
-// register ring, any batch width.  No cross-task state.
-template <int NB>
-__device__ __forceinline__ void gemm_tile_unstaged(const Params &P, const GemmTile &g, const Epilogue &e,
-                                                   const TaskWaits &w, float *sm, bool first_tile)
-{
-    const int wave = wave_id(), lane = lane_id();
-    const int m = lane & 15, kg = lane >> 4;
-    const int Kw = g.K / kWaves, n_it = Kw >> 5;
-    const int kbase = wave * Kw + kg * 8;
-    const uint16_t *wrow = lane_weight_row(g);
-
-    u32x4 wr[PF];
-#pragma unroll
-    for (int j = 0; j < PF; ++j) {
-        if (j < n_it) wr[j] = load16_nt(wrow + j * 32);
-        else wr[j] = u32x4{0, 0, 0, 0};
-    }
-    if (first_tile) {
-        if (w.per_wave) {
-            wave_wait(P, w.ev0 + wave, w.fn);
-            wave_wait(P, w.ev1, w.fn);
-        } else {
-            wg_wait(P, w.ev0, w.ev1, w.fn);
-        }
-    }
-    ETC_AS_LDS float *red = as_lds(sm);
-    ETC_AS_LDS float *rs = red + kRedFloats;
-
-    const uint16_t *bh[NB], *bl[NB];
-    bool valid[NB];
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        const int col = nb * 16 + m;
-        int row = col;
-        valid[nb] = col < g.n_cols;
-        if (valid[nb] && g.col_rows) row = ld_i32(g.col_rows + col);
-        if (row < 0) valid[nb] = false;
-        if (!valid[nb]) row = 0;
-        bh[nb] = g.b_hi + (size_t)row * (size_t)g.ldb + kbase;
-        bl[nb] = g.b_lo + (size_t)row * (size_t)g.ldb + kbase;
-    }
-    if (g.ssq_parts) {   // RMSNorm factor of every column: fixed-order sum of the producers' partial sums of squares
-        for (int col = wave; col < g.n_cols; col += kWaves) {
-            const int row = g.col_rows ? ld_i32(g.col_rows + col) : col;
-            float s = 0.f;
-            if (row >= 0)
-                for (int p = lane; p < g.n_parts; p += 64) s += ld_f32(g.ssq_parts + (size_t)p * kMaxBatch + row);
-            s = wave_sum(s);
-            if (lane == 0) rs[col] = 1.0f / sqrtf(s / (float)g.K + g.eps);
-        }
-    }
-    struct Raw {
-        u32x4 h[NB], l[NB];
-    };
-    Raw ring[2];
-    auto fetch = [&](int s, Raw &r) {
-        const int k = s * 32;
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            if (valid[nb]) {
-                r.h[nb] = ld_16B(bh[nb] + k);
-                r.l[nb] = ld_16B(bl[nb] + k);
-            } else {
-                r.h[nb] = u32x4{0, 0, 0, 0};
-                r.l[nb] = u32x4{0, 0, 0, 0};
-            }
-        }
-    };
-    f32x4 acc[NB];
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0, 0, 0, 0};
-    fetch(0, ring[0]);
-    if (n_it > 1) fetch(1, ring[1]);
-    for (int it = 0; it < n_it; it += PF) {
-#pragma unroll
-        for (int j = 0; j < PF; ++j) {
-            const int s = it + j;
-            if (s < n_it) {
-                const bf16x8 a = __builtin_bit_cast(bf16x8, wr[j]);
-                if (s + PF < n_it) wr[j] = load16_nt(wrow + (s + PF) * 32);
-                Raw &r = ring[j & 1];
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, r.h[nb]), acc[nb], 0, 0, 0);
-                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, r.l[nb]), acc[nb], 0, 0, 0);
-                }
-                if (s + 2 < n_it) fetch(s + 2, r);
-            }
-        }
-    }
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-        *reinterpret_cast<ETC_AS_LDS f32x4 *>(red + ((size_t)(wave * NB + nb) * 64 + lane) * 4) = acc[nb];
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < g.n_cols * 8; idx += kWgThreads) {
-        const int col = idx >> 3, mp = idx & 7;
-        const int nb = col >> 4, n = col & 15;
-        float lo = 0.f, hi = 0.f;
-#pragma unroll
-        for (int wv = 0; wv < kWaves; ++wv) {
-            ETC_AS_LDS const float *base = red + (size_t)(wv * NB + nb) * 256;
-            lo += base[(n + 16 * (mp >> 2)) * 4 + (mp & 3)];
-            hi += base[(n + 16 * ((mp + 8) >> 2)) * 4 + (mp & 3)];
-        }
-        if (g.ssq_parts) {
-            const float r = rs[col];
-            lo *= r;
-            hi *= r;
-        }
-        apply_epilogue(P, e, col, mp, lo, hi, epilogue_preload(P, e, col, mp));
-    }
-    __syncthreads();     // the reduction buffer is reused by the next tile
-}
-
-template <int NB>
-__device__ __noinline__ void gemm_tiles_cold(const Params &PL, GemmTile g, Epilogue e, TaskWaits w, float *sm)
-{
-    for (int ti = 0; ti < g.n_tiles; ++ti) {
-        gemm_tile_unstaged<NB>(PL, g, e, w, sm, ti == 0);
-        g.rowsA += (size_t)g.tile_rows * g.ldw;
-        g.rowsB += (size_t)g.tile_rows * g.ldw;
-        e.row0 += g.tile_rows;
-        if (e.ssq_out) e.ssq_out += kMaxBatch;
-    }
-}
-
 // Latency-critical path (at most 16 columns whose whole operand fits in LDS).  The operand (all columns,
 // full K, hi and lo) is copied into LDS once per stage with device-scope loads and reused by every
 // tile of that stage this workgroup runs.  A task streams its n_tiles row tiles back to back through a
@@ -679,15 +552,11 @@ __device__ __forceinline__ void gemm_tile_dispatch(const Params &P, const Params
         return;
     }
     st.staged_key = -1;
-    if (g.n_tiles <= kChunkTiles) {
-        if (g.n_cols <= 16) gemm_tiles_chunked<1>(PL, g, e, w, sm);
-        else if (g.n_cols <= 32) gemm_tiles_chunked<2>(PL, g, e, w, sm);
-        else gemm_tiles_chunked<4>(PL, g, e, w, sm);
-        return;
-    }
-    if (g.n_cols <= 16) gemm_tiles_cold<1>(PL, g, e, w, sm);
-    else if (g.n_cols <= 32) gemm_tiles_cold<2>(PL, g, e, w, sm);
-    else gemm_tiles_cold<4>(PL, g, e, w, sm);
+    // the graph builder gives a task at most kChunkTiles row tiles whenever its operand cannot be staged whole
+    if (g.n_tiles > kChunkTiles) { raise_error(P, ERR_TASK_SHAPE, w.fn, g.n_tiles); return; }
+    if (g.n_cols <= 16) gemm_tiles_chunked<1>(PL, g, e, w, sm);
+    else if (g.n_cols <= 32) gemm_tiles_chunked<2>(PL, g, e, w, sm);
+    else gemm_tiles_chunked<4>(PL, g, e, w, sm);
 }
 
 // cos / sin of the RoPE angle pos * theta^(-2i/d).  The inverse frequencies come from the host in

@@ -250,3 +250,26 @@ def test_moe_descriptor_validation():
     bad = synth.ModelShape("bad-moe", 1, 256, 4, 2, 64, 0, n_experts=16, top_k=2, moe_F=100)
     with pytest.raises(etc.EtcError):
         etc.plan_build(bad, 32, 1, 4, max_kv_len=64)
+
+
+# ---------------------------------------------------------------- large batches
+def test_large_batch_plan_tile_shapes():
+    """Batch 64 on the 8B shape: the operand cannot be staged whole, so projection tasks stream at most 4 row
+    tiles per pass over it, and attention is not cut finer than batch x KV heads already provides."""
+    s = synth.LLAMA3_8B
+    plan = etc.plan_build(s, 64, 64, 256, max_kv_len=4097)
+    t = plan["tasks"]
+    l0 = t[t["layer"] == 0]
+    qkv, gu = l0[l0["fn"] == 4], l0[l0["fn"] == 8]
+    assert (qkv["c2"] == 2).all() and len(qkv) == 384 // 2
+    assert (gu["c1"] == 4).all() and len(gu) == 1792 // 4
+    assert (l0["fn"] == 7).sum() == 256 and (l0["fn"] == 9).sum() == 256
+    # 64 sequences x 8 KV heads = 512 attention tasks = 2 per queue: one chunk slot per sequence
+    assert (l0["fn"] == 5).sum() == 64 * 8
+    # batch 1 on the same context shape keeps the caller's 64-token chunks where that gives the parallelism
+    plan1 = etc.plan_build(s, 64, 1, 256, max_kv_len=1025)
+    t1 = plan1["tasks"]
+    assert ((t1["fn"] == 5) & (t1["layer"] == 0)).sum() == 8 * 17
+    for p in (plan, plan1):
+        ev, done = run_static(p, np.random.default_rng(5)) if len(p["tasks"]) < 100000 else (np.zeros(1), np.ones(1))
+        assert (ev == 0).all() and (done == 1).all()

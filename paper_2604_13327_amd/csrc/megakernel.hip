@@ -181,12 +181,20 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
     TaskWaits tw{w0, w1, (int)t.fn, (t.flags & TF_WAIT0_PER_WAVE) != 0 && SYNC_EVENTS, w0};
     GemmTile g{};
     Epilogue e{};
-    if (t.flags & TF_DYN_ROWTILE) {      // GroupGEMM tile: wait first, then look the row tile up
-        wg_wait_cached(P, st, w0, w1, t.fn);
+    if (t.flags & TF_DYN_ROWTILE) {      // GroupGEMM tile: its weights depend on the routing
+        // The routing tables of a layer are complete once the layer's router event has fired.  A GroupGEMM-2 tile
+        // of a workgroup that already ran a GroupGEMM-1 tile of the same layer therefore looks its row tile
+        // up at once and prefetches its weights before it waits for its own event (the activations).
+        const bool routed = SYNC_EVENTS && t.fn == FN_MOE_DOWN && st.routed_layer == (int)t.layer;
+        if (!routed) {
+            wg_wait_cached(P, st, w0, w1, t.fn);
+            if (SYNC_EVENTS) st.routed_layer = t.layer;
+        }
         RowTile rt;
         if (!resolve_row_tile(P, t.c0, rt)) return;        // surplus slot of the static grid: nothing to do but notify
         setup_moe_gemm(P, t, rt, g, e);
-        tw = TaskWaits{-1, -1, (int)t.fn, false, w0 < 0 ? -1 : w0 + ((t.c0 + 1) << 20)};
+        const int key = w0 < 0 ? -1 : w0 + ((t.c0 + 1) << 20);
+        tw = routed ? TaskWaits{w0, w1, (int)t.fn, false, key} : TaskWaits{-1, -1, (int)t.fn, false, key};
         gemm_tile_dispatch(P, PL, g, e, tw, sm, st, t.id);
         return;
     }

@@ -53,7 +53,7 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
     // requested, then the arithmetic runs, so a batch costs one memory round trip.
     ETC_AS_LDS int *s_pg = reinterpret_cast<ETC_AS_LDS int *>(as_lds(sm)) + 10240;     // behind the 40 KB of reduction scratch
     const int pg0 = j0 / P.page, n_pg = (j1 - 1) / P.page - pg0 + 1;
-    constexpr int BATCH = 4;
+    constexpr int BATCH = GRP >= 8 ? 2 : 4;       // 8 query heads per KV head leave registers for 2 steps in flight
     if (PAGES_IN_LDS) {            // chunks of one batch (PAGES_IN_LDS false) read their page ids straight from memory
         for (int i = threadIdx.x; i < n_pg; i += kWgThreads) s_pg[i] = gld_i32(pages + pg0 + i);
         __syncthreads();

@@ -86,12 +86,14 @@ struct TaskWaits {
 struct WgState {
     int zero0, zero1;    // events already seen at zero in this launch (they never re-arm inside a launch)
     int staged_key;      // operand currently staged in LDS (-1: none)
+    int routed_layer;    // MoE layer whose routing tables this workgroup has already seen complete (-1: none)
 };
 
 __device__ __forceinline__ void wg_state_init(WgState &st)
 {
     st.zero0 = st.zero1 = -1;
     st.staged_key = -1;
+    st.routed_layer = -1;
 }
 
 __device__ __forceinline__ bool event_known_zero(const WgState &st, int ev) { return ev < 0 || ev == st.zero0 || ev == st.zero1; }

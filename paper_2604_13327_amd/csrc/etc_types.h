@@ -67,7 +67,7 @@ struct LayerWeights {
 };
 
 // Error word codes
-enum : int32_t { ERR_NONE = 0, ERR_WAIT_TIMEOUT = 1, ERR_QUEUE_OVERFLOW = 2, ERR_POP_TIMEOUT = 3, ERR_TASK_SHAPE = 4 };
+enum : int32_t { ERR_NONE = 0, ERR_WAIT_TIMEOUT = 1, ERR_QUEUE_OVERFLOW = 2, ERR_POP_TIMEOUT = 3 };
 
 // Everything the megakernel needs, passed by value as the kernel argument.
 struct Params {

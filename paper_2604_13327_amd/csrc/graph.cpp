@@ -294,9 +294,14 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
             // GroupGEMM-2 stays fine-grained: one event per slot.
             const int r_max = moe_max_row_tiles(m.E, m.topk, Bs, m.tile_m);
             const int n_ft = m.moeF / 8, n_ht = m.H / 16;
+            // Row tiles per GroupGEMM task: about one task per queue and stage when the step is small, about
+            // three when it is large (an expert's row tile has few columns, so a task is mostly weight streaming
+            // and its fixed cost - look-up, operand gather, reduction - wants many tiles behind it).
             auto tiles_per_task = [&](int per_slot) {
-                int cand = std::max(1, (int)((long long)r_max * per_slot / std::max(1, n_queues)));
-                cand = std::min(cand, 64 / m.tile_m);              // partial tiles of a task share the LDS reduction buffer
+                const long long total = (long long)r_max * per_slot;
+                const long long want = total <= 4LL * n_queues ? n_queues : 3LL * n_queues;
+                int cand = (int)std::max(1LL, total / std::max(1LL, want));
+                cand = std::min(cand, per_slot);
                 while (cand > 1 && per_slot % cand) --cand;
                 return std::max(1, cand);
             };

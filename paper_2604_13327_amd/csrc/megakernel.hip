@@ -63,6 +63,7 @@ __device__ __forceinline__ void load_hidden(const Params &P, int b)
 // dispatch: one task, including its waits; the caller notifies
 // ---------------------------------------------------------------------------------------------
 // Fills the tile and epilogue descriptors of a projection task; false for every other task kind.
+template <bool MOE>
 __device__ __forceinline__ bool setup_gemm(const Params &P, const Task &t, GemmTile &g, Epilogue &e)
 {
     const ETC_AS_GLOBAL LayerWeights *W = as_global(P.weights) + t.layer;
@@ -126,6 +127,7 @@ __device__ __forceinline__ bool setup_gemm(const Params &P, const Task &t, GemmT
         return true;
     }
     case FN_ROUTER_LOGITS: {
+        if (!MOE) return false;
         const int r0 = t.c0 * 16;
         g.n_tiles = 1; g.tile_rows = 16;
         g.rowsA = (const uint16_t *)W->wr + (size_t)r0 * P.H;
@@ -174,14 +176,16 @@ __device__ __forceinline__ void setup_moe_gemm(const Params &P, const Task &t, c
     }
 }
 
-template <bool SYNC_EVENTS>
+// MOE: whether the kernel instance carries the MoE task kinds at all.  Dense models run an instance without
+// them: the one large kernel is short of registers, and code that cannot run still costs some.
+template <bool SYNC_EVENTS, bool MOE>
 __device__ __forceinline__ void run_task(const Params &P, const Params &PL, const Task &t, float *sm, WgState &st)
 {
     const int w0 = SYNC_EVENTS ? t.wait0 : -1, w1 = SYNC_EVENTS ? t.wait1 : -1;
     TaskWaits tw{w0, w1, (int)t.fn, (t.flags & TF_WAIT0_PER_WAVE) != 0 && SYNC_EVENTS, w0};
     GemmTile g{};
     Epilogue e{};
-    if (t.flags & TF_DYN_ROWTILE) {      // GroupGEMM tile: its weights depend on the routing
+    if (MOE && (t.flags & TF_DYN_ROWTILE)) {      // GroupGEMM tile: its weights depend on the routing
         // The routing tables of a layer are complete once the layer's router event has fired.  A GroupGEMM-2 tile
         // of a workgroup that already ran a GroupGEMM-1 tile of the same layer therefore looks its row tile
         // up at once and prefetches its weights before it waits for its own event (the activations).
@@ -198,7 +202,7 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
         gemm_tile_dispatch(P, PL, g, e, tw, sm, st, t.id);
         return;
     }
-    if (setup_gemm(P, t, g, e)) {
+    if (setup_gemm<MOE>(P, t, g, e)) {
         gemm_tile_dispatch(P, PL, g, e, tw, sm, st, t.id);
         return;
     }
@@ -246,14 +250,14 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
         break;
     }
     case FN_ROUTER:
-        if (t.c0 < P.B) {
+        if (MOE && t.c0 < P.B) {
             wg_wait_cached(P, st, w0, w1, t.fn);
             st.staged_key = -1;      // the routing scratch overlaps the staged operand
             moe_route_and_group(PL, t.layer, t.c0, sm);
         }
         break;
     case FN_COMBINE:
-        if (t.c0 < P.B) {
+        if (MOE && t.c0 < P.B) {
             wg_wait_cached(P, st, w0, w1, t.fn);
             moe_combine(P, t);
         }
@@ -299,6 +303,7 @@ __device__ __forceinline__ void rearm_next(const Params &P)
         as_global(P.ev_next)[i] = as_global(P.ev_init)[i];
 }
 
+template <bool MOE>
 __global__ void __launch_bounds__(kWgThreads) megakernel_static(const Params P)
 {
     extern __shared__ __attribute__((aligned(16))) float sm[];
@@ -314,7 +319,7 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_static(const Params P)
         if (i + 1 < q1) tn = load_task(P.tasks + i + 1);      // fetched early: off the critical path of the next task
         trace_mark(P, t.id, 0);
         trace_mark(P, t.id, 7);
-        run_task<true>(P, sP, t, sm, st);
+        run_task<true, MOE>(P, sP, t, sm, st);
         trace_mark(P, t.id, 4);
         wg_release();
         if (threadIdx.x == 0) {
@@ -341,6 +346,7 @@ __device__ __forceinline__ void q_push(const Params &P, const int32_t *ids, int 
                            __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+template <bool MOE>
 __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
 {
     extern __shared__ __attribute__((aligned(16))) float sm[];
@@ -382,7 +388,7 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
         const Task t = load_task(P.dyn_tasks + id);
         WgState st;
         wg_state_init(st);
-        run_task<true>(P, sP, t, sm, st);  // early push (App. E): remaining in-edges are still waited on
+        run_task<true, MOE>(P, sP, t, sm, st);  // early push (App. E): remaining in-edges are still waited on
         wg_release();
         if (threadIdx.x == 0) {
             if (P.debug_flags & 1u) atomicAdd(P.exec_count + t.id, 1);
@@ -401,6 +407,7 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
 }
 
 // One operator stage as an ordinary kernel: block i runs task first + i, no events.
+template <bool MOE>
 __global__ void __launch_bounds__(kWgThreads) stage_kernel(const Params P, int first)
 {
     extern __shared__ __attribute__((aligned(16))) float sm[];
@@ -409,7 +416,7 @@ __global__ void __launch_bounds__(kWgThreads) stage_kernel(const Params P, int f
     const Task t = load_task(P.dyn_tasks + first + blockIdx.x);
     WgState st;
     wg_state_init(st);
-    run_task<false>(P, sP, t, sm, st);
+    run_task<false, MOE>(P, sP, t, sm, st);
 }
 
 }  // namespace etc
@@ -421,34 +428,40 @@ namespace etc {
 
 hipError_t configure_kernels()
 {
-    hipError_t e = hipFuncSetAttribute((const void *)megakernel_static, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void *)megakernel_dynamic, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute((const void *)stage_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    const void *kernels[] = {(const void *)megakernel_static<false>, (const void *)megakernel_static<true>,
+                             (const void *)megakernel_dynamic<false>, (const void *)megakernel_dynamic<true>,
+                             (const void *)stage_kernel<false>, (const void *)stage_kernel<true>};
+    for (const void *k : kernels) {
+        hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t max_resident_workgroups(int *per_cu)
 {
-    return hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, (const void *)megakernel_static, kWgThreads, kLdsBytes);
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, (const void *)megakernel_static<true>, kWgThreads, kLdsBytes);
 }
 
 hipError_t launch_static(const Params &P, hipStream_t s)
 {
-    hipLaunchKernelGGL(megakernel_static, dim3(P.n_queues), dim3(kWgThreads), kLdsBytes, s, P);
+    if (P.E > 0) hipLaunchKernelGGL(megakernel_static<true>, dim3(P.n_queues), dim3(kWgThreads), kLdsBytes, s, P);
+    else hipLaunchKernelGGL(megakernel_static<false>, dim3(P.n_queues), dim3(kWgThreads), kLdsBytes, s, P);
     return hipGetLastError();
 }
 
 hipError_t launch_dynamic(const Params &P, hipStream_t s)
 {
-    hipLaunchKernelGGL(megakernel_dynamic, dim3(P.n_queues), dim3(kWgThreads), kLdsBytes, s, P);
+    if (P.E > 0) hipLaunchKernelGGL(megakernel_dynamic<true>, dim3(P.n_queues), dim3(kWgThreads), kLdsBytes, s, P);
+    else hipLaunchKernelGGL(megakernel_dynamic<false>, dim3(P.n_queues), dim3(kWgThreads), kLdsBytes, s, P);
     return hipGetLastError();
 }
 
 hipError_t launch_stage(const Params &P, int first, int count, hipStream_t s)
 {
     if (count <= 0) return hipSuccess;
-    hipLaunchKernelGGL(stage_kernel, dim3(count), dim3(kWgThreads), kLdsBytes, s, P, first);
+    if (P.E > 0) hipLaunchKernelGGL(stage_kernel<true>, dim3(count), dim3(kWgThreads), kLdsBytes, s, P, first);
+    else hipLaunchKernelGGL(stage_kernel<false>, dim3(count), dim3(kWgThreads), kLdsBytes, s, P, first);
     return hipGetLastError();
 }
 

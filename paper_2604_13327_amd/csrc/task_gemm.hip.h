@@ -544,6 +544,22 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epi
     }
 }
 
+// More row tiles than one pass over the operand takes: further passes (the events have been seen by then).
+template <int NB>
+__device__ __noinline__ void gemm_tiles_chunked_passes(const Params &P, GemmTile g, Epilogue e, TaskWaits w, float *sm)
+{
+    const int total = g.n_tiles;
+    for (int t0 = 0; t0 < total; t0 += kChunkTiles) {
+        g.n_tiles = total - t0 < kChunkTiles ? total - t0 : kChunkTiles;
+        gemm_tiles_chunked<NB>(P, g, e, w, sm);
+        g.rowsA += (size_t)kChunkTiles * g.tile_rows * g.ldw;
+        g.rowsB += (size_t)kChunkTiles * g.tile_rows * g.ldw;
+        e.row0 += kChunkTiles * g.tile_rows;
+        if (e.ssq_out) e.ssq_out += (size_t)kChunkTiles * kMaxBatch;
+        w = TaskWaits{-1, -1, w.fn, false, -1};
+    }
+}
+
 // PL is the workgroup's LDS copy of the parameters: a kernel argument cannot be passed by address to
 // the out-of-line paths.
 __device__ __forceinline__ void gemm_tile_dispatch(const Params &P, const Params &PL, const GemmTile &g, const Epilogue &e,
@@ -554,8 +570,12 @@ __device__ __forceinline__ void gemm_tile_dispatch(const Params &P, const Params
         return;
     }
     st.staged_key = -1;
-    // the graph builder gives a task at most kChunkTiles row tiles whenever its operand cannot be staged whole
-    if (g.n_tiles > kChunkTiles) { raise_error(P, ERR_TASK_SHAPE, w.fn, g.n_tiles); return; }
+    if (g.n_tiles > kChunkTiles) {       // only GroupGEMM tasks of a crowded expert: sized for few columns
+        if (g.n_cols <= 16) gemm_tiles_chunked_passes<1>(PL, g, e, w, sm);
+        else if (g.n_cols <= 32) gemm_tiles_chunked_passes<2>(PL, g, e, w, sm);
+        else gemm_tiles_chunked_passes<4>(PL, g, e, w, sm);
+        return;
+    }
     if (g.n_cols <= 16) gemm_tiles_chunked<1>(PL, g, e, w, sm);
     else if (g.n_cols <= 32) gemm_tiles_chunked<2>(PL, g, e, w, sm);
     else gemm_tiles_chunked<4>(PL, g, e, w, sm);

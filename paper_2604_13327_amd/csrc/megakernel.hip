@@ -176,15 +176,18 @@ __device__ __forceinline__ void setup_moe_gemm(const Params &P, const Task &t, c
     }
 }
 
-// MOE: whether the kernel instance carries the MoE task kinds at all.  Dense models run an instance without
-// them: the one large kernel is short of registers, and code that cannot run still costs some.
-template <bool SYNC_EVENTS, bool MOE>
+// KIND: which task kinds the kernel instance carries: 0 generic graphs (the row-sum device functions), 1 dense
+// decoder, 2 MoE decoder.  The one large kernel is short of registers, and code that cannot run still costs
+// some: the dense instance alone is 5 % faster than an instance that carries everything.
+constexpr int KIND_GENERIC = 0, KIND_DENSE = 1, KIND_MOE = 2;
+template <bool SYNC_EVENTS, int KIND>
 __device__ __forceinline__ void run_task(const Params &P, const Params &PL, const Task &t, float *sm, WgState &st)
 {
     const int w0 = SYNC_EVENTS ? t.wait0 : -1, w1 = SYNC_EVENTS ? t.wait1 : -1;
     TaskWaits tw{w0, w1, (int)t.fn, (t.flags & TF_WAIT0_PER_WAVE) != 0 && SYNC_EVENTS, w0};
     GemmTile g{};
     Epilogue e{};
+    constexpr bool MOE = KIND == KIND_MOE;
     if (MOE && (t.flags & TF_DYN_ROWTILE)) {      // GroupGEMM tile: its weights depend on the routing
         // The routing tables of a layer are complete once the layer's router event has fired.  A GroupGEMM-2 tile
         // of a workgroup that already ran a GroupGEMM-1 tile of the same layer therefore looks its row tile
@@ -202,19 +205,17 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
         gemm_tile_dispatch(P, PL, g, e, tw, sm, st, t.id);
         return;
     }
-    if (setup_gemm<MOE>(P, t, g, e)) {
+    if (KIND != KIND_GENERIC && setup_gemm<MOE>(P, t, g, e)) {
         gemm_tile_dispatch(P, PL, g, e, tw, sm, st, t.id);
         return;
     }
+    if (KIND == KIND_GENERIC) {
+        wg_wait_cached(P, st, w0, w1, t.fn);
+        if (t.fn == FN_ROWSUM_PARTIAL) rowsum_partial(P, t.c0, t.c1);
+        else if (t.fn == FN_ROWSUM_FINAL) rowsum_final(P, t.c0);
+        return;
+    }
     switch (t.fn) {
-    case FN_ROWSUM_PARTIAL:
-        wg_wait_cached(P, st, w0, w1, t.fn);
-        rowsum_partial(P, t.c0, t.c1);
-        break;
-    case FN_ROWSUM_FINAL:
-        wg_wait_cached(P, st, w0, w1, t.fn);
-        rowsum_final(P, t.c0);
-        break;
     case FN_LOAD_HIDDEN:
         if (t.c0 < P.B) load_hidden(P, t.c0);
         break;
@@ -303,7 +304,7 @@ __device__ __forceinline__ void rearm_next(const Params &P)
         as_global(P.ev_next)[i] = as_global(P.ev_init)[i];
 }
 
-template <bool MOE>
+template <int KIND>
 __global__ void __launch_bounds__(kWgThreads) megakernel_static(const Params P)
 {
     extern __shared__ __attribute__((aligned(16))) float sm[];
@@ -319,7 +320,7 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_static(const Params P)
         if (i + 1 < q1) tn = load_task(P.tasks + i + 1);      // fetched early: off the critical path of the next task
         trace_mark(P, t.id, 0);
         trace_mark(P, t.id, 7);
-        run_task<true, MOE>(P, sP, t, sm, st);
+        run_task<true, KIND>(P, sP, t, sm, st);
         trace_mark(P, t.id, 4);
         wg_release();
         if (threadIdx.x == 0) {
@@ -346,7 +347,7 @@ __device__ __forceinline__ void q_push(const Params &P, const int32_t *ids, int 
                            __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-template <bool MOE>
+template <int KIND>
 __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
 {
     extern __shared__ __attribute__((aligned(16))) float sm[];
@@ -388,7 +389,7 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
         const Task t = load_task(P.dyn_tasks + id);
         WgState st;
         wg_state_init(st);
-        run_task<true, MOE>(P, sP, t, sm, st);  // early push (App. E): remaining in-edges are still waited on
+        run_task<true, KIND>(P, sP, t, sm, st);  // early push (App. E): remaining in-edges are still waited on
         wg_release();
         if (threadIdx.x == 0) {
             if (P.debug_flags & 1u) atomicAdd(P.exec_count + t.id, 1);
@@ -407,7 +408,7 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
 }
 
 // One operator stage as an ordinary kernel: block i runs task first + i, no events.
-template <bool MOE>
+template <int KIND>
 __global__ void __launch_bounds__(kWgThreads) stage_kernel(const Params P, int first)
 {
     extern __shared__ __attribute__((aligned(16))) float sm[];
@@ -416,7 +417,7 @@ __global__ void __launch_bounds__(kWgThreads) stage_kernel(const Params P, int f
     const Task t = load_task(P.dyn_tasks + first + blockIdx.x);
     WgState st;
     wg_state_init(st);
-    run_task<false, MOE>(P, sP, t, sm, st);
+    run_task<false, KIND>(P, sP, t, sm, st);
 }
 
 }  // namespace etc
@@ -428,9 +429,9 @@ namespace etc {
 
 hipError_t configure_kernels()
 {
-    const void *kernels[] = {(const void *)megakernel_static<false>, (const void *)megakernel_static<true>,
-                             (const void *)megakernel_dynamic<false>, (const void *)megakernel_dynamic<true>,
-                             (const void *)stage_kernel<false>, (const void *)stage_kernel<true>};
+    const void *kernels[] = {(const void *)megakernel_static<0>, (const void *)megakernel_static<1>, (const void *)megakernel_static<2>,
+                             (const void *)megakernel_dynamic<0>, (const void *)megakernel_dynamic<1>, (const void *)megakernel_dynamic<2>,
+                             (const void *)stage_kernel<0>, (const void *)stage_kernel<1>, (const void *)stage_kernel<2>};
     for (const void *k : kernels) {
         hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;
@@ -440,28 +441,35 @@ hipError_t configure_kernels()
 
 hipError_t max_resident_workgroups(int *per_cu)
 {
-    return hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, (const void *)megakernel_static<true>, kWgThreads, kLdsBytes);
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, (const void *)megakernel_static<KIND_MOE>, kWgThreads, kLdsBytes);
 }
+
+// generic graph contexts carry no model; decoders are dense or MoE
+static int kind_of(const Params &P) { return P.n_layers == 0 ? KIND_GENERIC : (P.E > 0 ? KIND_MOE : KIND_DENSE); }
+
+#define ETC_LAUNCH_KIND(KERNEL, GRID, ...)                                                                          \
+    switch (kind_of(P)) {                                                                                          \
+    case KIND_GENERIC: hipLaunchKernelGGL(KERNEL<KIND_GENERIC>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break; \
+    case KIND_DENSE: hipLaunchKernelGGL(KERNEL<KIND_DENSE>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break;     \
+    default: hipLaunchKernelGGL(KERNEL<KIND_MOE>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break;               \
+    }
 
 hipError_t launch_static(const Params &P, hipStream_t s)
 {
-    if (P.E > 0) hipLaunchKernelGGL(megakernel_static<true>, dim3(P.n_queues), dim3(kWgThreads), kLdsBytes, s, P);
-    else hipLaunchKernelGGL(megakernel_static<false>, dim3(P.n_queues), dim3(kWgThreads), kLdsBytes, s, P);
+    ETC_LAUNCH_KIND(megakernel_static, dim3(P.n_queues), P)
     return hipGetLastError();
 }
 
 hipError_t launch_dynamic(const Params &P, hipStream_t s)
 {
-    if (P.E > 0) hipLaunchKernelGGL(megakernel_dynamic<true>, dim3(P.n_queues), dim3(kWgThreads), kLdsBytes, s, P);
-    else hipLaunchKernelGGL(megakernel_dynamic<false>, dim3(P.n_queues), dim3(kWgThreads), kLdsBytes, s, P);
+    ETC_LAUNCH_KIND(megakernel_dynamic, dim3(P.n_queues), P)
     return hipGetLastError();
 }
 
 hipError_t launch_stage(const Params &P, int first, int count, hipStream_t s)
 {
     if (count <= 0) return hipSuccess;
-    if (P.E > 0) hipLaunchKernelGGL(stage_kernel<true>, dim3(count), dim3(kWgThreads), kLdsBytes, s, P, first);
-    else hipLaunchKernelGGL(stage_kernel<false>, dim3(count), dim3(kWgThreads), kLdsBytes, s, P, first);
+    ETC_LAUNCH_KIND(stage_kernel, dim3(count), P, first)
     return hipGetLastError();
 }
 

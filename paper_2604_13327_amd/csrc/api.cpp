@@ -35,6 +35,8 @@ const char *kDynamicOffMsg = "the dynamic scheduler is switched off: its kernel 
 struct DevPlan {          // one instantiated plan (one sampled batch size), host + device copies
     int sampled_batch = 0;
     int kv_chunk = 0;     // keys per attention task of this plan
+    int k_slices_o = 0, k_slices_d = 0;   // slices of K of this plan's O / down projection tasks
+    bool all_staged = false;              // every projection task of this plan fits the staged path
     Plan host;
     Task *d_queue_tasks = nullptr, *d_tasks = nullptr;
     int32_t *d_queue_begin = nullptr, *d_ev_init = nullptr, *d_ev_consumers = nullptr, *d_consumer_ids = nullptr,
@@ -204,6 +206,9 @@ void fill_launch_params(etc_ctx *c, Params &P)
     P.Bs = dp.sampled_batch;
     P.max_chunks = c->max_chunks;
     if (dp.kv_chunk > 0) P.kv_chunk = dp.kv_chunk;
+    P.k_slices_o = dp.k_slices_o;
+    P.k_slices_d = dp.k_slices_d;
+    P.all_staged = dp.all_staged ? 1 : 0;
     P.kv_len = c->d_kv_len;
     P.page_indptr = c->d_page_indptr;
     P.page_ids = c->d_page_ids;
@@ -318,6 +323,9 @@ etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc
         int syms[4] = {dp.sampled_batch, (s->max_kv_len + dp.kv_chunk - 1) / dp.kv_chunk, 0, 0};
         std::string err = build_decoder_graph(d, dp.sampled_batch, c->n_queues, s->kind != ETC_SCHED_DYNAMIC, &c->graph);
         if (!err.empty()) { c->err = err; return bail(ETC_EINVAL); }
+        dp.k_slices_o = c->graph.k_slices_o;
+        dp.k_slices_d = c->graph.k_slices_d;
+        dp.all_staged = c->graph.all_staged;
         err = instantiate(c->graph, syms, c->n_queues, s->kind == ETC_SCHED_UNFUSED, &dp.host);
         if (!err.empty()) { c->err = err; return bail(ETC_EINVAL); }
         st = upload_plan(c, dp);
@@ -355,6 +363,11 @@ etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc
         okk = A(&d_inv, inv.size()) &&
               hipMemcpy(d_inv, inv.data(), inv.size() * sizeof(double), hipMemcpyHostToDevice) == hipSuccess;
         P.rope_inv_freq = d_inv;
+    }
+    {   // partial sums of the K-sliced projections of large-batch plans: [slice][row tile][kMaxBatch][16]
+        int most = 0;
+        for (const DevPlan &dp : c->plans) most = std::max(most, std::max(dp.k_slices_o, dp.k_slices_d));
+        if (okk && most > 0) okk = A(&P.kpart, (size_t)most * (H / 16) * kMaxBatch * 16);
     }
     if (okk && (s->debug_flags & ETC_DEBUG_LAYER_HIDDEN)) okk = A(&P.layer_hidden, (size_t)m->n_layers * kMaxBatch * H);
     P.max_batch = s->max_batch;

@@ -40,6 +40,8 @@ enum Fn : uint8_t {
     FN_MOE_GATEUP = 12,   // MoE: GroupGEMM-1 tile (row tile of routed tokens, 8 gate + 8 up rows), SiLU-mul
     FN_MOE_DOWN = 13,     // MoE: GroupGEMM-2 tile (row tile, 16 rows of the expert's Wd)
     FN_COMBINE = 14,      // MoE: weighted sum of a token's expert outputs in slot order + residual
+    FN_OPROJ_SUM = 15,    // large batches: fixed-order sum of the K-slice partials of 16 rows of the O projection + residual
+    FN_DOWN_SUM = 16,     // the same for the down projection
     FN_COUNT
 };
 
@@ -48,6 +50,7 @@ enum : uint16_t {
     TF_WAIT0_PER_WAVE = 1,   // wave w waits on event wait0 + w instead of the whole workgroup on wait0
     TF_LAST_LAYER = 2,       // also write hidden_out
     TF_DYN_ROWTILE = 4,      // c0 is a GroupGEMM row-tile id resolved through exp_indptr at run time
+    TF_K_SLICE = 8,          // projection task over one slice of K: c1 = slice, c2 = row tiles; writes fp32 partials
 };
 
 // One materialised task of a static queue (Sec. 3.1: "static execution queue"), 32 bytes.
@@ -97,6 +100,9 @@ struct Params {
     uint16_t *attn_hi, *attn_lo;       // attention output, split [maxB, nq*d]
     uint16_t *act_hi, *act_lo;         // silu(gate)*up, split [maxB, F]
     float *part_m, *part_l, *part_o;   // split-KV partials [maxB, nq, max_chunks] (+ [d])
+    float *kpart;                      // K-slice partials of a projection [slice][row tile][kMaxBatch][16], or null
+    int32_t k_slices_o, k_slices_d;    // slices of K of the O / down projection tasks of the bound plan (0: whole K)
+    int32_t all_staged;                // every projection task of the bound plan fits the staged path
     // MoE scratch (rows of the grouped tensors are (token, slot) pairs sorted by (expert, token, slot))
     float *router_logits;              // [maxB, E]
     int32_t *topk_ids;                 // [maxB, topk]

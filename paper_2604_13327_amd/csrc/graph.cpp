@@ -197,14 +197,34 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
             r_gu = std::max(1, cand);
         }
     } else {
-        // Large batches take the chunked path: every task reads the whole operand, so a task streams a few
-        // row tiles against one pass over it (as many as keep at least one task per queue).
+        // Large batches take the chunked path, where every task reads its operand from memory: traffic that
+        // grows with (tasks x columns x K) and soon exceeds the weights.  A gate/up task therefore streams up to
+        // 8 row tiles (4 above 32 columns) against one pass over the operand, and the O and down projections, which have only
+        // hidden/16 row tiles in all, are cut along K instead: a task takes that many row tiles and one slice of K
+        // and leaves fp32 partial sums, which a second, small task adds up in slice order (two-stage
+        // reduction as in the row-sum example of Sec. 2.2).
         if (sub % 2 == 0) r_qkv = 2;
+        g.k_slices_o = k_slices_for(m.nq * m.d);
         if (m.E == 0) {
-            const int per_slice = m.F / 8 / kWaves;
-            r_gu = per_slice % 4 == 0 ? 4 : (per_slice % 2 == 0 ? 2 : 1);
+            g.k_slices_d = k_slices_for(m.F);
+            const int tiles = m.F / 8, per_slice = tiles / (g.k_slices_d ? g.k_slices_d : kWaves);
+            // bytes a queue moves through the stage: rounds x (r row tiles of weights + one pass over the operand)
+            const long long tile_bytes = 16LL * m.H * 2, operand_bytes = (long long)Bs * m.H * 4;
+            long long best = -1;
+            for (int r = 1; r <= pass_tiles_for(Bs); ++r) {
+                if (per_slice % r) continue;
+                const long long rounds = (tiles / r + n_queues - 1) / n_queues, cost = rounds * (r * tile_bytes + operand_bytes);
+                if (best < 0 || cost <= best) { best = cost; r_gu = r; }
+            }
         }
     }
+    g.all_staged = m.E == 0 && staged_fits(r_qkv, Bs, m.H) && staged_fits(1, Bs, m.nq * m.d) && staged_fits(r_gu, Bs, m.H) &&
+                   staged_fits(1, Bs, m.F);
+    const int n_ht = m.H / 16, pass_tiles = pass_tiles_for(Bs);
+    const bool slice_o = g.k_slices_o > 0 && n_ht % pass_tiles == 0;
+    const bool slice_d = g.k_slices_d > 0 && n_ht % pass_tiles == 0;
+    if (!slice_o) g.k_slices_o = 0;
+    if (!slice_d) g.k_slices_d = 0;
 
     int stage = 0;
     int e_x = g.add_event({one});
@@ -256,16 +276,33 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
             c.out = {edge_const0(e_attn)};
             g.calls.push_back(c);
         }
-        {
+        if (slice_o) {
+            const int e_opart = g.add_event({one});
+            CallDecl c;
+            c.fn = FN_OPROJ; c.layer = l; c.stage = stage++;      // task record: (first row tile, K slice, tiles)
+            c.rank = 2; c.shape[0] = dim_const(n_ht / pass_tiles); c.shape[1] = dim_const(g.k_slices_o);
+            c.c_mul[0] = pass_tiles; c.c_fill[2] = pass_tiles;
+            c.flags = TF_K_SLICE;
+            c.in = {edge_const0(e_attn)};
+            c.out = {edge_const0(e_opart)};
+            g.calls.push_back(c);
+            CallDecl r;
+            r.fn = FN_OPROJ_SUM; r.layer = l; r.stage = stage++;
+            r.rank = 1; r.shape[0] = dim_const(n_ht);
+            r.in = {edge_const0(e_opart)};
+            r.out = {edge_const0(e_xmid)};
+            g.calls.push_back(r);
+        } else {
             CallDecl c;
             c.fn = FN_OPROJ; c.layer = l; c.stage = stage++;
-            c.rank = 1; c.shape[0] = dim_const(m.H / 16);
+            c.rank = 1; c.shape[0] = dim_const(n_ht);
             c.in = {edge_const0(e_attn)};
             c.out = {edge_const0(e_xmid)};
             g.calls.push_back(c);
         }
         if (m.E == 0) {
-            const int e_act = g.add_event({dim_const(kWaves)});
+            const int act_slices = slice_d ? g.k_slices_d : kWaves;
+            const int e_act = g.add_event({dim_const(act_slices)});
             const int tiles = m.F / 8;
             {
                 CallDecl c;
@@ -274,13 +311,30 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
                 c.c_mul[0] = r_gu;
                 c.c_fill[1] = r_gu;
                 c.in = {edge_const0(e_xmid)};
-                c.out = {edge_dim(e_act, 0, tiles / kWaves / r_gu)};   // K slice of the down projection it feeds
+                c.out = {edge_dim(e_act, 0, tiles / act_slices / r_gu)};   // K slice of the down projection it feeds
                 g.calls.push_back(c);
             }
-            {
+            if (slice_d) {
+                const int e_dpart = g.add_event({one});
+                CallDecl c;
+                c.fn = FN_DOWN; c.layer = l; c.stage = stage++;      // task record: (first row tile, K slice, tiles)
+                c.rank = 2; c.shape[0] = dim_const(n_ht / pass_tiles); c.shape[1] = dim_const(g.k_slices_d);
+                c.c_mul[0] = pass_tiles; c.c_fill[2] = pass_tiles;
+                c.flags = TF_K_SLICE;
+                c.in = {edge_dim(e_act, 1)};                    // only the activations of its own K slice
+                c.out = {edge_const0(e_dpart)};
+                g.calls.push_back(c);
+                CallDecl r;
+                r.fn = FN_DOWN_SUM; r.layer = l; r.stage = stage++;
+                r.rank = 1; r.shape[0] = dim_const(n_ht);
+                r.flags = last;
+                r.in = {edge_const0(e_dpart)};
+                r.out = {edge_const0(e_xnext)};
+                g.calls.push_back(r);
+            } else {
                 CallDecl c;
                 c.fn = FN_DOWN; c.layer = l; c.stage = stage++;
-                c.rank = 1; c.shape[0] = dim_const(m.H / 16);
+                c.rank = 1; c.shape[0] = dim_const(n_ht);
                 c.flags = (uint16_t)(TF_WAIT0_PER_WAVE | last);
                 c.in = {edge_const0(e_act)};                    // wave w waits on e_act[w]
                 c.out = {edge_const0(e_xnext)};
@@ -293,7 +347,7 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
             // GroupGEMM-2 tiles.  The row-tile slots themselves are static, so GroupGEMM-1 ->
             // GroupGEMM-2 stays fine-grained: one event per slot.
             const int r_max = moe_max_row_tiles(m.E, m.topk, Bs, m.tile_m);
-            const int n_ft = m.moeF / 8, n_ht = m.H / 16;
+            const int n_ft = m.moeF / 8;
             // Row tiles per GroupGEMM task: about one task per queue and stage when the step is small, about
             // three when it is large (an expert's row tile has few columns, so a task is mostly weight streaming
             // and its fixed cost - look-up, operand gather, reduction - wants many tiles behind it).

@@ -56,6 +56,8 @@ struct CallDecl {
 struct GraphDecl {
     std::vector<EventDecl> events;
     std::vector<CallDecl> calls;
+    int k_slices_o = 0, k_slices_d = 0;   // decoder graphs: slices of K of the O / down projection tasks (0: whole K)
+    bool all_staged = false;              // dense decoder graphs: every projection task fits the staged path
     int add_event(std::initializer_list<DimExpr> shape);
 };
 
@@ -102,6 +104,19 @@ inline int effective_kv_chunk(int min_chunk, int page, int max_kv_len, int batch
     int chunk = (max_kv_len + chunks - 1) / chunks;
     chunk = (chunk + page - 1) / page * page;
     return chunk < min_chunk ? min_chunk : chunk;
+}
+
+// Row tiles a large-batch projection task streams against one pass over its operand: 8 up to 32 columns,
+// 4 above (the accumulators of 8 tiles x 64 columns do not fit the register file).
+inline int pass_tiles_for(int batch) { return batch > 32 ? 4 : 8; }
+
+// Slices of K for a projection of a large batch: the most of 8, 4, 2 that keep a slice a multiple of the
+// 256 elements one pass of the 8 wavefronts covers; 0 when K is too short to slice.
+inline int k_slices_for(int K)
+{
+    for (int s = 8; s >= 2; s /= 2)
+        if (K % (s * 256) == 0) return s;
+    return 0;
 }
 
 // The decoder's graph function for one sampled batch size.  Symbol 0 = that batch size, symbol 1 =

@@ -62,6 +62,23 @@ __device__ __forceinline__ void load_hidden(const Params &P, int b)
 // ---------------------------------------------------------------------------------------------
 // dispatch: one task, including its waits; the caller notifies
 // ---------------------------------------------------------------------------------------------
+// Narrows a whole-K projection task (c0 = first row tile) to K slice c1 of n_slices and c2 row tiles; the
+// task then leaves fp32 partial sums instead of running the projection's epilogue.
+__device__ __forceinline__ void slice_of_k(const Params &P, const Task &t, int n_slices, GemmTile &g, Epilogue &e)
+{
+    const int Ks = g.K / n_slices, k0 = t.c1 * Ks;
+    g.rowsA += k0;
+    g.rowsB += k0;
+    g.b_hi += k0;
+    g.b_lo += k0;
+    g.K = Ks;
+    g.n_tiles = t.c2;
+    const int row0 = e.row0, layer = e.layer;
+    e = Epilogue{};
+    e.kind = EPI_PARTIAL; e.layer = layer; e.row0 = row0;
+    e.outf = P.kpart + (size_t)t.c1 * (size_t)(P.H / 16) * kMaxBatch * 16;
+}
+
 // Fills the tile and epilogue descriptors of a projection task; false for every other task kind.
 template <bool MOE>
 __device__ __forceinline__ bool setup_gemm(const Params &P, const Task &t, GemmTile &g, Epilogue &e)
@@ -144,6 +161,31 @@ __device__ __forceinline__ bool setup_gemm(const Params &P, const Task &t, GemmT
     }
 }
 
+// The two task kinds of a K-sliced projection (large-batch plans only) run out of line, so that they cost the
+// register allocation of the latency-critical small-batch path nothing.
+// First stage: row tiles c0 .. c0+c2-1 against K slice c1.
+__device__ __noinline__ WgState k_slice_task(const Params &PL, Task t, TaskWaits tw, float *sm, WgState st)
+{
+    GemmTile g{};
+    Epilogue e{};
+    setup_gemm<false>(PL, t, g, e);
+    slice_of_k(PL, t, t.fn == FN_OPROJ ? PL.k_slices_o : PL.k_slices_d, g, e);
+    if (tw.ev0 >= 0) tw.op_key = tw.ev0 + ((t.c1 + 1) << 20);      // a staged copy holds one slice
+    gemm_tile_dispatch(PL, PL, g, e, tw, sm, st, t.id);
+    return st;
+}
+// Second stage: the slices' partial sums of row tile c0, then the projection's own epilogue.
+__device__ __noinline__ void k_slice_sum_task(const Params &PL, Task t, int w0, int w1)
+{
+    GemmTile g{};
+    Epilogue e{};
+    const bool o_proj = t.fn == FN_OPROJ_SUM;
+    t.fn = o_proj ? FN_OPROJ : FN_DOWN;
+    setup_gemm<false>(PL, t, g, e);
+    wg_wait(PL, w0, w1, t.fn);
+    kslice_sum(PL, e, PL.B, o_proj ? PL.k_slices_o : PL.k_slices_d, PL.H / 16);
+}
+
 // GroupGEMM tile of a resolved row tile: the weight rows depend on the routing, so this runs after the wait.
 __device__ __forceinline__ void setup_moe_gemm(const Params &P, const Task &t, const RowTile &rt, GemmTile &g, Epilogue &e)
 {
@@ -177,9 +219,10 @@ __device__ __forceinline__ void setup_moe_gemm(const Params &P, const Task &t, c
 }
 
 // KIND: which task kinds the kernel instance carries: 0 generic graphs (the row-sum device functions), 1 dense
-// decoder, 2 MoE decoder.  The one large kernel is short of registers, and code that cannot run still costs
-// some: the dense instance alone is 5 % faster than an instance that carries everything.
-constexpr int KIND_GENERIC = 0, KIND_DENSE = 1, KIND_MOE = 2;
+// decoder, 2 MoE decoder, 3 dense decoder whose projection tasks all fit the staged path (small batches).  The
+// one large kernel is short of registers, and code that cannot run still costs some: the dense instance alone
+// is 5 % faster than an instance that carries everything, the staged-only instance another 2 %.
+constexpr int KIND_GENERIC = 0, KIND_DENSE = 1, KIND_MOE = 2, KIND_DENSE_STAGED = 3;
 template <bool SYNC_EVENTS, int KIND>
 __device__ __forceinline__ void run_task(const Params &P, const Params &PL, const Task &t, float *sm, WgState &st)
 {
@@ -205,8 +248,14 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
         gemm_tile_dispatch(P, PL, g, e, tw, sm, st, t.id);
         return;
     }
+    constexpr bool STAGED_ONLY = KIND == KIND_DENSE_STAGED;
+    if (KIND != KIND_GENERIC && !STAGED_ONLY && (t.flags & TF_K_SLICE)) {
+        st = k_slice_task(PL, t, tw, sm, st);
+        return;
+    }
     if (KIND != KIND_GENERIC && setup_gemm<MOE>(P, t, g, e)) {
-        gemm_tile_dispatch(P, PL, g, e, tw, sm, st, t.id);
+        if (STAGED_ONLY) gemm_tiles_staged(P, g, e, tw, sm, st, t.id);
+        else gemm_tile_dispatch(P, PL, g, e, tw, sm, st, t.id);
         return;
     }
     if (KIND == KIND_GENERIC) {
@@ -218,6 +267,10 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
     switch (t.fn) {
     case FN_LOAD_HIDDEN:
         if (t.c0 < P.B) load_hidden(P, t.c0);
+        break;
+    case FN_OPROJ_SUM:
+    case FN_DOWN_SUM:
+        if (!STAGED_ONLY) k_slice_sum_task(PL, t, w0, w1);
         break;
     case FN_ATTN: {
         const int b = t.c0, kvh = t.c1, ch = t.c2;
@@ -430,8 +483,11 @@ namespace etc {
 hipError_t configure_kernels()
 {
     const void *kernels[] = {(const void *)megakernel_static<0>, (const void *)megakernel_static<1>, (const void *)megakernel_static<2>,
+                             (const void *)megakernel_static<3>,
                              (const void *)megakernel_dynamic<0>, (const void *)megakernel_dynamic<1>, (const void *)megakernel_dynamic<2>,
-                             (const void *)stage_kernel<0>, (const void *)stage_kernel<1>, (const void *)stage_kernel<2>};
+                             (const void *)megakernel_dynamic<3>,
+                             (const void *)stage_kernel<0>, (const void *)stage_kernel<1>, (const void *)stage_kernel<2>,
+                             (const void *)stage_kernel<3>};
     for (const void *k : kernels) {
         hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;
@@ -444,13 +500,19 @@ hipError_t max_resident_workgroups(int *per_cu)
     return hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, (const void *)megakernel_static<KIND_MOE>, kWgThreads, kLdsBytes);
 }
 
-// generic graph contexts carry no model; decoders are dense or MoE
-static int kind_of(const Params &P) { return P.n_layers == 0 ? KIND_GENERIC : (P.E > 0 ? KIND_MOE : KIND_DENSE); }
+// generic graph contexts carry no model; decoders are dense (small-batch plans: the staged-only instance) or MoE
+static int kind_of(const Params &P)
+{
+    if (P.n_layers == 0) return KIND_GENERIC;
+    if (P.E > 0) return KIND_MOE;
+    return P.all_staged ? KIND_DENSE_STAGED : KIND_DENSE;
+}
 
 #define ETC_LAUNCH_KIND(KERNEL, GRID, ...)                                                                          \
     switch (kind_of(P)) {                                                                                          \
     case KIND_GENERIC: hipLaunchKernelGGL(KERNEL<KIND_GENERIC>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break; \
     case KIND_DENSE: hipLaunchKernelGGL(KERNEL<KIND_DENSE>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break;     \
+    case KIND_DENSE_STAGED: hipLaunchKernelGGL(KERNEL<KIND_DENSE_STAGED>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break; \
     default: hipLaunchKernelGGL(KERNEL<KIND_MOE>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break;               \
     }
 

@@ -41,7 +41,8 @@ struct GemmTile {
 
 constexpr uint16_t EPF_DUMP_LAYER = 0x8000;   // epilogue also records the layer's hidden state
 
-enum EpiKind : int { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_STORE_F32 = 3, EPI_MOE_ACT = 4, EPI_MOE_Y = 5 };
+enum EpiKind : int { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_STORE_F32 = 3, EPI_MOE_ACT = 4, EPI_MOE_Y = 5,
+                     EPI_PARTIAL = 6 };   // PARTIAL: fp32 sums over one slice of K, [row tile][kMaxBatch][16], outf = the slice's block
 
 struct Epilogue {
     int kind;
@@ -74,6 +75,7 @@ __device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &
 constexpr int PF = 16;                            // weight loads in flight per lane (16 KB per wave)
 
 __device__ __forceinline__ u32x4 load16_nt(const uint16_t *p) { return gld_16B_nt(p); }
+__device__ __forceinline__ void ld_f32x2_pair(const float *p, float &a, float &b) { a = ld_f32(p); b = ld_f32(p + 8); }
 
 // Waits of a projection task.  per_wave: wave w waits on ev0 + w (its own K slice) on its own.
 struct TaskWaits {
@@ -352,36 +354,53 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
 // The operand is walked in chunks of KC elements of K: a chunk of ALL columns (hi and lo) sits in LDS,
 // double buffered; while the wavefronts run the MFMAs of chunk c out of one buffer, every thread already
 // has its 8-byte pieces of chunk c+1 in flight into registers and drops them into the other buffer at the
-// end of the chunk: one barrier per chunk.  KC = 1024 / (16-column blocks), i.e. 64 KB per buffer, so a
-// chunk's arithmetic lasts longer than the round trip of the next chunk's loads.  Within a chunk a
-// wavefront owns 32 of every 256 elements of K (KC / 256 MFMA steps); a task streams up to kChunkTiles row
-// tiles against one pass over the operand (which every task has to read in full), with the same ring of PF
-// weight fragments in flight per lane as the staged path, running over (chunk, step, tile) triples.
-constexpr int kChunkTiles = 4;
+// end of the chunk: one barrier per chunk.  Within a chunk a wavefront owns 32 of every 256 elements of K
+// (S = KC / 256 MFMA steps); a task streams T (4 or 8) row tiles against one pass over the operand, which
+// every task has to read in full, with a ring of PFC weight fragments in flight per lane running over
+// (chunk, step, tile) triples.  Register budget decides the shape: accumulators take T x NB x 4 registers,
+// the ring 4 PFC, the operand pieces in flight COLS x KC / 512 - so 16 columns keep the full ring of 16, 32
+// columns a ring of 8, 64 columns 4 row tiles and a ring of 4.  Nothing may spill inside the loop: a
+// register reload is a memory load that queues behind the whole ring.
+//
+// The steady state of the loop is free of branches.  The compiler places its wait counts per basic block;
+// a branch around a load (a dead tile slot, a column beyond the batch, a chunk beyond K) makes every later
+// wait a full drain of the loads in flight, which halves the streaming rate.  So the steady state always
+// moves T tiles (slots beyond n_tiles stream the last live tile again and are never stored), columns beyond
+// n_cols read row 0, and only the last ring revolutions, whose look-ahead leaves K, run the conditional code.
 
-template <int NB>
-__device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epilogue e, TaskWaits w, float *sm)
+template <int NB, int T>
+__device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epilogue e, TaskWaits w, float *sm, int task_id)
 {
-    constexpr int T = kChunkTiles;
+    static_assert(T == 4 || T == 8, "row tiles per pass");
+    constexpr int PFC = NB == 1 ? PF : (NB == 2 ? 8 : 4);   // weight loads in flight per lane: wider batches need the registers
     constexpr int COLS = NB * 16;
-    constexpr int KC = 1024 / NB;                  // K elements per chunk
-    constexpr int S = KC / 256;                    // MFMA steps per wavefront, chunk and tile
+    constexpr int S = (4 / NB) < (PFC / T) ? (4 / NB) : (PFC / T);   // MFMA steps per wavefront, chunk and tile
+    constexpr int KC = 256 * S;                    // K elements per chunk
     constexpr int STRIDE = KC + 8;                 // LDS column stride in elements: 16 columns cover all banks
-    constexpr int U = 8;                           // 8-byte pieces per thread, chunk and half: COLS * KC / 4 / 512
     constexpr int PPC = KC / 4;                    // 8-byte pieces per column and half
+    constexpr int U = COLS * PPC / kWgThreads;     // 8-byte pieces per thread, chunk and half
     constexpr int BUF = 2 * COLS * STRIDE;         // elements of one buffer: hi columns, then lo columns
-    constexpr int CPR = PF / (T * S);              // chunks per revolution of the ring
+    constexpr int CPR = PFC / (T * S);              // chunks per revolution of the ring
     static_assert(COLS * PPC == U * kWgThreads, "every thread moves U pieces of each half");
-    static_assert(CPR >= 1 && CPR * T * S == PF, "the ring holds whole chunks");
+    static_assert(CPR >= 1 && CPR * T * S == PFC, "the ring holds whole chunks");
     static_assert((size_t)2 * BUF * 2 + (64 + 512) * 4 <= (size_t)kLdsBytes, "two operand buffers and the norm scratch fit");
     static_assert((size_t)kWaves * NB * 256 * 4 <= (size_t)BUF * 2, "the reduction buffer aliases one operand buffer");
     const int wave = wave_id(), lane = lane_id();
     const int m = lane & 15, kg = lane >> 4;
-    const int n_chunks = (g.K + KC - 1) / KC;      // K is a multiple of 256; the last chunk may be partial
-    const int n_tiles = g.n_tiles;
+    const int K = __builtin_amdgcn_readfirstlane(g.K);
+    const int n_chunks = (K + KC - 1) / KC;        // K is a multiple of 256; the last chunk may be partial
+    const int n_full = K / KC;                     // chunks that lie inside K with all their steps
+    const int n_tiles = __builtin_amdgcn_readfirstlane(g.n_tiles);
     const size_t tile_step = (size_t)g.tile_rows * (size_t)g.ldw;
     const uint16_t *wbase = (m < 8 ? g.rowsA + (size_t)m * (size_t)g.ldw : g.rowsB + (size_t)(m - 8) * (size_t)g.ldw) +
                             wave * 32 + kg * 8;
+    // The steady state of the streaming loop has no branch (a branch around a load makes every later wait
+    // a full drain of the loads in flight): it always moves T row tiles, slots beyond n_tiles stream the
+    // last live tile again and are never stored; columns beyond n_cols read row 0.
+    uint32_t toff[T];                              // uniform element offsets of the tiles: scalar registers
+#pragma unroll
+    for (int ti = 0; ti < T; ++ti)
+        toff[ti] = __builtin_amdgcn_readfirstlane((uint32_t)((size_t)(ti < n_tiles ? ti : n_tiles - 1) * tile_step));
 
     ETC_AS_LDS uint16_t *buf0 = reinterpret_cast<ETC_AS_LDS uint16_t *>(as_lds(sm));
     ETC_AS_LDS float *red = as_lds(sm);                                  // after the last chunk
@@ -389,13 +408,13 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epi
     ETC_AS_LDS float *rs_part = rs + 64;                                  // [8][64]
 
     // ring slot j <-> (chunk j / (S*T) of the revolution, step (j / T) % S, tile j % T)
-    auto step_live = [&](int c, int sidx) { return c * KC + sidx * 256 < g.K; };
+    auto step_live = [&](int c, int sidx) { return c * KC + sidx * 256 < K; };
     // ---- weight prefetch before the wait ---------------------------------------------------------------
-    u32x4 wr[PF];
+    u32x4 wr[PFC];
 #pragma unroll
-    for (int j = 0; j < PF; ++j) {
+    for (int j = 0; j < PFC; ++j) {
         const int c = j / (S * T), sidx = (j / T) % S, ti = j % T;
-        if (step_live(c, sidx) && ti < n_tiles) wr[j] = load16_nt(wbase + (size_t)ti * tile_step + c * KC + sidx * 256);
+        if (step_live(c, sidx)) wr[j] = load16_nt(wbase + toff[ti] + c * KC + sidx * 256);
         else wr[j] = u32x4{0, 0, 0, 0};
     }
     // ---- E.wait(): the operand is needed in full, so every K slice event is waited for ---------------
@@ -407,6 +426,7 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epi
     } else {
         wg_wait(P, w.ev0, w.ev1, w.fn);
     }
+    trace_mark(P, task_id, 1);
 
     // this thread's pieces of every chunk: piece tid + 512u = (column, 8-byte piece of the column's chunk)
     int rows[U], pcs[U];
@@ -415,19 +435,28 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epi
         const int idx = (int)threadIdx.x + kWgThreads * u;
         const int col = idx / PPC;
         pcs[u] = idx - col * PPC;
-        rows[u] = -1;
+        rows[u] = 0;
         if (col < g.n_cols) rows[u] = g.col_rows ? ld_i32(g.col_rows + col) : col;
+        if (rows[u] < 0) rows[u] = 0;
     }
     uint64_t vh[U], vl[U];
-    auto fetch_chunk = [&](int c) {
+    auto fetch_chunk = [&](int c) {                // any chunk: pieces beyond K are left out
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             vh[u] = vl[u] = 0;
-            if (rows[u] >= 0 && c * KC + pcs[u] * 4 < g.K) {
+            if (c * KC + pcs[u] * 4 < K) {
                 const size_t off = (size_t)rows[u] * (size_t)g.ldb + (size_t)c * KC + pcs[u] * 4;
                 vh[u] = ld_u64(g.b_hi + off);
                 vl[u] = ld_u64(g.b_lo + off);
             }
+        }
+    };
+    auto fetch_full_chunk = [&](int c) {           // a chunk inside K: no conditions
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t off = (size_t)rows[u] * (size_t)g.ldb + (size_t)c * KC + pcs[u] * 4;
+            vh[u] = ld_u64(g.b_hi + off);
+            vl[u] = ld_u64(g.b_lo + off);
         }
     };
     auto park_chunk = [&](int b) {
@@ -468,6 +497,7 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epi
         for (int gq = 0; gq < 8; ++gq) s += rs_part[gq * 64 + threadIdx.x];
         rs[threadIdx.x] = 1.0f / sqrtf(s / (float)g.K + g.eps);
     }
+    trace_mark(P, task_id, 2);
 
     f32x4 acc[T][NB];
 #pragma unroll
@@ -475,7 +505,42 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epi
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) acc[ti][nb] = f32x4{0, 0, 0, 0};
 
-    for (int c0 = 0; c0 < n_chunks; c0 += CPR) {
+    // one MFMA step of all T tiles out of ring slots j0 .. j0+T-1; RELOAD: the slots are refilled for chunk cn
+#define ETC_CHUNK_STEP(hi, lo, sidx, cc, cn, RELOAD)                                                             \
+    {                                                                                                             \
+        u32x4 fb[NB];                                                                                             \
+        _Pragma("unroll") for (int nb = 0; nb < NB; ++nb)                                                         \
+            fb[nb] = *reinterpret_cast<ETC_AS_LDS const u32x4 *>(hi + nb * 16 * STRIDE + (sidx) * 256);            \
+        _Pragma("unroll") for (int ti = 0; ti < T; ++ti) {                                                        \
+            const bf16x8 a = __builtin_bit_cast(bf16x8, wr[((cc) * S + (sidx)) * T + ti]);                        \
+            _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) acc[ti][nb] =                                       \
+                __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, fb[nb]), acc[ti][nb], 0, 0, 0); \
+        }                                                                                                         \
+        _Pragma("unroll") for (int nb = 0; nb < NB; ++nb)                                                         \
+            fb[nb] = *reinterpret_cast<ETC_AS_LDS const u32x4 *>(lo + nb * 16 * STRIDE + (sidx) * 256);            \
+        _Pragma("unroll") for (int ti = 0; ti < T; ++ti) {                                                        \
+            const int j = ((cc) * S + (sidx)) * T + ti;                                                           \
+            const bf16x8 a = __builtin_bit_cast(bf16x8, wr[j]);                                                   \
+            if (RELOAD) wr[j] = load16_nt(wbase + toff[ti] + (size_t)(cn) * KC + (sidx) * 256);                   \
+            _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) acc[ti][nb] =                                       \
+                __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, fb[nb]), acc[ti][nb], 0, 0, 0); \
+        }                                                                                                         \
+    }
+    int c0 = 0;
+    for (; c0 + 2 * CPR <= n_full; c0 += CPR) {    // steady state: this revolution, the next chunk and the chunks
+#pragma unroll                                     // the ring is refilled for all lie inside K: no conditions
+        for (int cc = 0; cc < CPR; ++cc) {
+            const int c = c0 + cc, b = c & 1;
+            fetch_full_chunk(c + 1);
+            ETC_AS_LDS const uint16_t *hi = buf0 + b * BUF + m * STRIDE + wave * 32 + kg * 8;
+            ETC_AS_LDS const uint16_t *lo = hi + COLS * STRIDE;
+#pragma unroll
+            for (int sidx = 0; sidx < S; ++sidx) ETC_CHUNK_STEP(hi, lo, sidx, cc, c + CPR, true)
+            park_chunk(b ^ 1);
+            __syncthreads();
+        }
+    }
+    for (; c0 < n_chunks; c0 += CPR) {             // the last revolutions: every load and step is conditional
 #pragma unroll
         for (int cc = 0; cc < CPR; ++cc) {
             const int c = c0 + cc;
@@ -487,22 +552,8 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epi
 #pragma unroll
                 for (int sidx = 0; sidx < S; ++sidx) {
                     if (step_live(c, sidx)) {      // uniform
-#pragma unroll
-                        for (int ti = 0; ti < T; ++ti) {
-                            if (ti < n_tiles) {
-                                const int j = (cc * S + sidx) * T + ti;
-                                const bf16x8 a = __builtin_bit_cast(bf16x8, wr[j]);
-                                if (step_live(c + CPR, sidx))
-                                    wr[j] = load16_nt(wbase + (size_t)ti * tile_step + (size_t)(c + CPR) * KC + sidx * 256);
-#pragma unroll
-                                for (int nb = 0; nb < NB; ++nb) {
-                                    const u32x4 bh = *reinterpret_cast<ETC_AS_LDS const u32x4 *>(hi + nb * 16 * STRIDE + sidx * 256);
-                                    const u32x4 bl = *reinterpret_cast<ETC_AS_LDS const u32x4 *>(lo + nb * 16 * STRIDE + sidx * 256);
-                                    acc[ti][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bh), acc[ti][nb], 0, 0, 0);
-                                    acc[ti][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bl), acc[ti][nb], 0, 0, 0);
-                                }
-                            }
-                        }
+                        if (step_live(c + CPR, sidx)) ETC_CHUNK_STEP(hi, lo, sidx, cc, c + CPR, true)
+                        else ETC_CHUNK_STEP(hi, lo, sidx, cc, c + CPR, false)
                     }
                 }
                 if (c + 1 < n_chunks) park_chunk(b ^ 1);
@@ -510,8 +561,10 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epi
             }
         }
     }
+#undef ETC_CHUNK_STEP
 
     // ---- per tile: partials of the 8 wavefronts through LDS, fixed order, epilogue ----------------------
+    trace_mark(P, task_id, 3);
 #pragma unroll
     for (int ti = 0; ti < T; ++ti) {
         if (ti < n_tiles) {
@@ -545,17 +598,17 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epi
 }
 
 // More row tiles than one pass over the operand takes: further passes (the events have been seen by then).
-template <int NB>
-__device__ __noinline__ void gemm_tiles_chunked_passes(const Params &P, GemmTile g, Epilogue e, TaskWaits w, float *sm)
+template <int NB, int T>
+__device__ __noinline__ void gemm_tiles_chunked_passes(const Params &P, GemmTile g, Epilogue e, TaskWaits w, float *sm, int task_id)
 {
     const int total = g.n_tiles;
-    for (int t0 = 0; t0 < total; t0 += kChunkTiles) {
-        g.n_tiles = total - t0 < kChunkTiles ? total - t0 : kChunkTiles;
-        gemm_tiles_chunked<NB>(P, g, e, w, sm);
-        g.rowsA += (size_t)kChunkTiles * g.tile_rows * g.ldw;
-        g.rowsB += (size_t)kChunkTiles * g.tile_rows * g.ldw;
-        e.row0 += kChunkTiles * g.tile_rows;
-        if (e.ssq_out) e.ssq_out += (size_t)kChunkTiles * kMaxBatch;
+    for (int t0 = 0; t0 < total; t0 += T) {
+        g.n_tiles = total - t0 < T ? total - t0 : T;
+        gemm_tiles_chunked<NB, T>(P, g, e, w, sm, task_id);
+        g.rowsA += (size_t)T * g.tile_rows * g.ldw;
+        g.rowsB += (size_t)T * g.tile_rows * g.ldw;
+        e.row0 += T * g.tile_rows;
+        if (e.ssq_out) e.ssq_out += (size_t)T * kMaxBatch;
         w = TaskWaits{-1, -1, w.fn, false, -1};
     }
 }
@@ -570,15 +623,50 @@ __device__ __forceinline__ void gemm_tile_dispatch(const Params &P, const Params
         return;
     }
     st.staged_key = -1;
-    if (g.n_tiles > kChunkTiles) {       // only GroupGEMM tasks of a crowded expert: sized for few columns
-        if (g.n_cols <= 16) gemm_tiles_chunked_passes<1>(PL, g, e, w, sm);
-        else if (g.n_cols <= 32) gemm_tiles_chunked_passes<2>(PL, g, e, w, sm);
-        else gemm_tiles_chunked_passes<4>(PL, g, e, w, sm);
+    // Up to 32 columns a pass takes 8 row tiles; with 64 columns the accumulators of 8 tiles no longer fit the
+    // register file next to the weight ring (spills inside the streaming loop queue behind the weight loads),
+    // so a pass takes 4.
+    if (g.n_cols > 32) {
+        if (g.n_tiles <= 4) gemm_tiles_chunked<4, 4>(PL, g, e, w, sm, task_id);
+        else gemm_tiles_chunked_passes<4, 4>(PL, g, e, w, sm, task_id);
         return;
     }
-    if (g.n_cols <= 16) gemm_tiles_chunked<1>(PL, g, e, w, sm);
-    else if (g.n_cols <= 32) gemm_tiles_chunked<2>(PL, g, e, w, sm);
-    else gemm_tiles_chunked<4>(PL, g, e, w, sm);
+    if (g.n_tiles <= 4) {
+        if (g.n_cols <= 16) gemm_tiles_chunked<1, 4>(PL, g, e, w, sm, task_id);
+        else gemm_tiles_chunked<2, 4>(PL, g, e, w, sm, task_id);
+    } else if (g.n_tiles <= 8) {
+        if (g.n_cols <= 16) gemm_tiles_chunked<1, 8>(PL, g, e, w, sm, task_id);
+        else gemm_tiles_chunked<2, 8>(PL, g, e, w, sm, task_id);
+    } else {                             // only GroupGEMM tasks of a crowded expert
+        if (g.n_cols <= 16) gemm_tiles_chunked_passes<1, 8>(PL, g, e, w, sm, task_id);
+        else gemm_tiles_chunked_passes<2, 8>(PL, g, e, w, sm, task_id);
+    }
+}
+
+// Second stage of a K-sliced projection: adds the partial sums of the slices in slice order (fixed, so the
+// result does not depend on which slice finished first) and runs the projection's own epilogue on the 16
+// rows of one row tile.  e is the epilogue of the whole projection; e.row0 = first row of the tile.
+__device__ __forceinline__ void kslice_sum(const Params &P, const Epilogue &e, int n_cols, int n_slices, int n_row_tiles)
+{
+    const size_t slice_stride = (size_t)n_row_tiles * kMaxBatch * 16;
+    const float *base = P.kpart + (size_t)(e.row0 >> 4) * kMaxBatch * 16;
+    for (int idx = threadIdx.x; idx < n_cols * 8; idx += kWgThreads) {
+        const int col = idx >> 3, mp = idx & 7;
+        const EpiPre pre = epilogue_preload(P, e, col, mp);
+        float a[8], b[8];
+#pragma unroll
+        for (int sl = 0; sl < 8; ++sl) {
+            a[sl] = b[sl] = 0.f;
+            if (sl < n_slices) ld_f32x2_pair(base + (size_t)sl * slice_stride + (size_t)col * 16 + mp, a[sl], b[sl]);
+        }
+        float lo = 0.f, hi = 0.f;
+#pragma unroll
+        for (int sl = 0; sl < 8; ++sl) {
+            lo += a[sl];
+            hi += b[sl];
+        }
+        apply_epilogue(P, e, col, mp, lo, hi, pre);
+    }
 }
 
 // cos / sin of the RoPE angle pos * theta^(-2i/d).  The inverse frequencies come from the host in
@@ -692,6 +780,12 @@ __device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &
     }
     case EPI_MOE_ACT: {
         store_split(e.out_hi, e.out_lo, (size_t)(e.col0 + col) * e.ld + e.row0 + mp, silu_f(lo) * hi);
+        break;
+    }
+    case EPI_PARTIAL: {
+        float *dst = e.outf + ((size_t)(e.row0 >> 4) * kMaxBatch + col) * 16 + mp;
+        st_f32(dst, lo);
+        st_f32(dst + 8, hi);
         break;
     }
     case EPI_MOE_Y: {

@@ -254,16 +254,36 @@ def test_moe_descriptor_validation():
 
 # ---------------------------------------------------------------- large batches
 def test_large_batch_plan_tile_shapes():
-    """Batch 64 on the 8B shape: the operand cannot be staged whole, so projection tasks stream at most 4 row
-    tiles per pass over it, and attention is not cut finer than batch x KV heads already provides."""
+    """Large batches on the 8B shape: the operand cannot be staged whole, so a gate/up task streams several row
+    tiles per pass over it (7 up to 32 columns: one task per queue; 4 at 64 columns), the O and down
+    projections are cut into 8 slices of K with 8 (4) row tiles per task and a second stage that adds the
+    slices up, and attention is not cut finer than batch x KV heads already provides."""
     s = synth.LLAMA3_8B
-    plan = etc.plan_build(s, 64, 64, 256, max_kv_len=4097)
-    t = plan["tasks"]
-    l0 = t[t["layer"] == 0]
-    qkv, gu = l0[l0["fn"] == 4], l0[l0["fn"] == 8]
-    assert (qkv["c2"] == 2).all() and len(qkv) == 384 // 2
-    assert (gu["c1"] == 4).all() and len(gu) == 1792 // 4
-    assert (l0["fn"] == 7).sum() == 256 and (l0["fn"] == 9).sum() == 256
+    TF_K_SLICE = 8
+    for batch, tiles in ((64, 4), (16, 8)):
+        plan = etc.plan_build(s, 64, batch, 256, max_kv_len=4097)
+        t = plan["tasks"]
+        l0 = t[t["layer"] == 0]
+        qkv, gu = l0[l0["fn"] == 4], l0[l0["fn"] == 8]
+        assert (qkv["c2"] == 2).all() and len(qkv) == 384 // 2
+        r_gu = 4 if batch == 64 else 7
+        assert (gu["c1"] == r_gu).all() and len(gu) == 1792 // r_gu
+        for fn, fn_sum in ((7, 15), (9, 16)):
+            part, total = l0[l0["fn"] == fn], l0[l0["fn"] == fn_sum]
+            assert len(part) == 256 // tiles * 8 and (part["flags"] & TF_K_SLICE).all() and (part["c2"] == tiles).all()
+            assert sorted(set(part["c0"].tolist())) == list(range(0, 256, tiles))
+            assert sorted(set(part["c1"].tolist())) == list(range(8))
+            assert len(set(part["notify0"].tolist())) == 1           # one event gathers all slices
+            assert len(total) == 256 and (total["wait0"] == part["notify0"][0]).all()
+            assert plan["ev_init"][part["notify0"][0]] == len(part)
+        down = l0[l0["fn"] == 9]
+        # a down-projection slice waits for the gate/up tiles of its own K slice only
+        for sl in range(8):
+            waits = set(down["wait0"][down["c1"] == sl].tolist())
+            assert len(waits) == 1
+            producers = gu[gu["notify0"] == waits.pop()]
+            assert len(producers) == 224 // r_gu
+            assert producers["c0"].min() == sl * 224 and producers["c0"].max() == sl * 224 + 224 - r_gu
     # 64 sequences x 8 KV heads = 512 attention tasks = 2 per queue: one chunk slot per sequence
     assert (l0["fn"] == 5).sum() == 64 * 8
     # batch 1 on the same context shape keeps the caller's 64-token chunks where that gives the parallelism

@@ -348,6 +348,7 @@ etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc
     const size_t F1 = (size_t)std::max(1, m->ffn);
     bool okk = A(&P.x, MB * H) && A(&P.x_mid, MB * H) && A(&P.qbuf, MB * QD) &&
                A(&P.knew, MB * (size_t)m->n_kv_heads * m->head_dim) && A(&P.vnew, MB * (size_t)m->n_kv_heads * m->head_dim) &&
+               A(&P.rope_cs, MB * (size_t)m->head_dim) && A(&P.kv_slot, MB) &&
                A(&P.xg_hi, MB * H) && A(&P.xg_lo, MB * H) && A(&P.xmg_hi, MB * H) && A(&P.xmg_lo, MB * H) &&
                A(&P.ssq_x, (H / 16) * (size_t)kMaxBatch) && A(&P.ssq_xmid, (H / 16) * (size_t)kMaxBatch) &&
                A(&P.attn_hi, MB * QD) && A(&P.attn_lo, MB * QD) && A(&P.act_hi, MB * F1) && A(&P.act_lo, MB * F1) &&

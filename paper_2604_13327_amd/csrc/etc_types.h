@@ -97,6 +97,8 @@ struct Params {
     float *ssq_x, *ssq_xmid;           // partial sums of squares per 16-row tile [H/16][kMaxBatch]
     float *qbuf;                       // rotated queries [maxB, nq*d]
     float *knew, *vnew;                // this step's K (rotated) and V rows in fp32 [maxB, nkv*d]: the cache gets bf16
+    float *rope_cs;                    // this step's (cos, sin) of every sequence's RoPE angles [maxB, d/2, 2], from the step prologue
+    int32_t *kv_slot;                  // this step's KV slot of every sequence: page * page_size + pos % page_size [maxB]
     uint16_t *attn_hi, *attn_lo;       // attention output, split [maxB, nq*d]
     uint16_t *act_hi, *act_lo;         // silu(gate)*up, split [maxB, F]
     float *part_m, *part_l, *part_o;   // split-KV partials [maxB, nq, max_chunks] (+ [d])

@@ -40,8 +40,21 @@ __device__ __forceinline__ void rowsum_final(const Params &P, int i)
 
 // Step prologue for sequence b: hidden_in (bf16) -> residual stream (fp32), the first layer's projection
 // operand (x * g1, split) and the partial sums of squares per 16 elements, as every later producer does.
+// Also what every layer's QKV epilogue needs of the step's shape, resolved once: the (cos, sin) of the RoPE
+// angles at the sequence's position and the KV slot the new row goes to (page table look-up).
 __device__ __forceinline__ void load_hidden(const Params &P, int b)
 {
+    const int pos = gld_i32(P.kv_len + b);
+    for (int i = threadIdx.x; i < P.d / 2; i += kWgThreads) {
+        float cs, sn;
+        rope_cos_sin(P, pos, i, &cs, &sn);
+        st_f32(P.rope_cs + ((size_t)b * (P.d / 2) + i) * 2, cs);
+        st_f32(P.rope_cs + ((size_t)b * (P.d / 2) + i) * 2 + 1, sn);
+    }
+    if (threadIdx.x == 0) {
+        const int page = gld_i32(P.page_ids + gld_i32(P.page_indptr + b) + pos / P.page);
+        st_i32(P.kv_slot + b, page * P.page + pos % P.page);
+    }
     const uint16_t *g1 = (const uint16_t *)as_global(P.weights)[0].g1;
     for (int part = threadIdx.x; part < P.H / 16; part += kWgThreads) {
         float s = 0.f;

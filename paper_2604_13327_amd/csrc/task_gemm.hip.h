@@ -65,8 +65,7 @@ struct Epilogue {
 struct EpiPre {
     float a, b;       // RESID: the two residual values; QKV: cos and sin of the rotation angle
     float ga, gb;     // RESID: gains of the two rows for the consumer's operand
-    int page;         // QKV (k / v heads): physical page of the appended row
-    int pos;          // QKV: position of the new token
+    int slot;         // QKV (k / v heads): KV slot of the appended row (page * page_size + position in the page)
 };
 __device__ __forceinline__ EpiPre epilogue_preload(const Params &P, const Epilogue &e, int col, int mp);
 __device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &e, int col, int mp, float lo, float hi,
@@ -196,6 +195,21 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
     const bool fired = !will_wait;
     if (!fired) prefetch();
 
+    // What the epilogue will need (single pass of the epilogue loop only) is requested right behind the operand:
+    // it is back by the time the operand sits in LDS, and the streaming loop starts without another round trip.
+    const int per_tile = g.n_cols * 8;
+    const int n_out = g.n_tiles * per_tile;
+    const bool pre_ok = n_out <= kWgThreads;
+    EpiPre pre{};
+    auto request_epilogue_inputs = [&]() {
+        if (pre_ok && (int)threadIdx.x < n_out) {
+            const int ti = (int)threadIdx.x / per_tile, r = (int)threadIdx.x - ti * per_tile;
+            Epilogue et = e;
+            et.row0 = e.row0 + ti * g.tile_rows;
+            pre = epilogue_preload(P, et, r >> 3, r & 7);
+        }
+    };
+
     if (restage) {
         // ---- E.wait() ---------------------------------------------------------------------------
         if (fired) {
@@ -238,6 +252,7 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
                     sq[j] = (pt < g.n_parts && row >= 0) ? ld_f32(g.ssq_parts + (size_t)pt * kMaxBatch + row) : 0.f;
                 }
             }
+            request_epilogue_inputs();
             if (fired) prefetch();                          // right behind the operand loads
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -266,6 +281,7 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
                     sq[j] = (pt < g.n_parts && row >= 0) ? ld_f32(g.ssq_parts + (size_t)pt * kMaxBatch + row) : 0.f;
                 }
             }
+            request_epilogue_inputs();
             if (fired) prefetch();
         }
         if (g.ssq_parts) {       // RMSNorm factor of every column: fixed-order sum of the producers' partial sums of squares
@@ -291,24 +307,14 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
     } else {
         if (fired) {
             if (!event_known_zero(st, w.ev1)) { st.zero1 = st.zero0; st.zero0 = w.ev1; }
+            request_epilogue_inputs();
             prefetch();
         } else {
             wg_wait_cached(P, st, w.ev1, -1, w.fn);
+            request_epilogue_inputs();
         }
     }
     trace_mark(P, task_id, 2);
-
-    // ---- what the epilogue will need (single pass of the epilogue loop only) ---------------------
-    const int per_tile = g.n_cols * 8;
-    const int n_out = g.n_tiles * per_tile;
-    const bool pre_ok = n_out <= kWgThreads;
-    EpiPre pre{};
-    if (pre_ok && (int)threadIdx.x < n_out) {
-        const int ti = (int)threadIdx.x / per_tile, r = (int)threadIdx.x - ti * per_tile;
-        Epilogue et = e;
-        et.row0 = e.row0 + ti * g.tile_rows;
-        pre = epilogue_preload(P, et, r >> 3, r & 7);
-    }
 
     const bool valid = m < g.n_cols;
     ETC_AS_LDS const uint16_t *sh = op_hi + (size_t)(valid ? m : 0) * (size_t)g.K + kbase;
@@ -738,11 +744,10 @@ __device__ __forceinline__ void store_split(uint16_t *hi_p, uint16_t *lo_p, size
 __device__ __forceinline__ EpiPre epilogue_preload(const Params &P, const Epilogue &e, int col, int mp)
 {
     EpiPre pre{};
-    if (e.kind == EPI_QKV) {
+    if (e.kind == EPI_QKV) {      // both resolved by the step prologue: plain independent loads, no look-up chain
         const int b = col, i = e.row0 + mp;
-        pre.pos = gld_i32(P.kv_len + b);
-        if (e.head < P.nq + P.nkv) rope_cos_sin(P, pre.pos, i, &pre.a, &pre.b);   // q and k heads are rotated to position pos
-        if (e.head >= P.nq) pre.page = gld_i32(P.page_ids + gld_i32(P.page_indptr + b) + pre.pos / P.page);
+        if (e.head < P.nq + P.nkv) ld_f32x2(P.rope_cs + ((size_t)b * (P.d >> 1) + i) * 2, pre.a, pre.b);   // q and k heads are rotated
+        if (e.head >= P.nq) pre.slot = ld_i32(P.kv_slot + b);
     } else if (e.kind == EPI_RESID) {
         const size_t o0 = (size_t)col * e.ld + e.row0 + mp;
         pre.a = ld_f32(e.resid + o0);
@@ -761,7 +766,6 @@ __device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &
     switch (e.kind) {
     case EPI_QKV: {
         const int b = col, half = P.d >> 1, i = e.row0 + mp;
-        const int pos = pre.pos;
         float a = lo, c = hi;
         if (e.head < P.nq + P.nkv) {
             a = lo * pre.a - hi * pre.b;
@@ -775,7 +779,7 @@ __device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &
             const bool is_k = e.head < P.nq + P.nkv;
             const int kvh = is_k ? e.head - P.nq : e.head - P.nq - P.nkv;
             const size_t off = (size_t)e.layer * (size_t)P.pool_layer_stride +
-                               (((size_t)pre.page * P.page + (size_t)(pos % P.page)) * P.nkv + kvh) * (size_t)P.d;
+                               ((size_t)pre.slot * P.nkv + kvh) * (size_t)P.d;
             uint16_t *dst = (is_k ? P.kpool : P.vpool) + off;
             st_u16(dst + i, f32_to_bf16_bits(a));
             st_u16(dst + i + half, f32_to_bf16_bits(c));

@@ -420,8 +420,8 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
 template <int NB, int T>
 __device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epilogue e, TaskWaits w, float *sm, int task_id)
 {
-    static_assert(T == 4 || T == 8, "row tiles per pass");
-    constexpr int PFC = NB == 1 ? PF : (NB == 2 ? 8 : 4);   // weight loads in flight per lane: wider batches need the registers
+    static_assert(T == 1 || T == 2 || T == 4 || T == 8, "row tiles per pass");
+    constexpr int PFC = NB == 1 ? (T >= 4 ? PF : 8) : (NB == 2 ? 8 : 4);   // weight loads in flight per lane, as the registers allow
     constexpr int COLS = NB * 16;
     constexpr int S = (4 / NB) < (PFC / T) ? (4 / NB) : (PFC / T);   // MFMA steps per wavefront, chunk and tile
     constexpr int KC = 256 * S;                    // K elements per chunk
@@ -672,24 +672,22 @@ __device__ __forceinline__ void gemm_tile_dispatch(const Params &P, const Params
         return;
     }
     st.staged_key = -1;
-    // Up to 32 columns a pass takes 8 row tiles; with 64 columns the accumulators of 8 tiles no longer fit the
-    // register file next to the weight ring (spills inside the streaming loop queue behind the weight loads),
-    // so a pass takes 4.
-    if (g.n_cols > 32) {
-        if (g.n_tiles <= 4) gemm_tiles_chunked<4, 4>(PL, g, e, w, sm, task_id);
-        else gemm_tiles_chunked_passes<4, 4>(PL, g, e, w, sm, task_id);
-        return;
+    // The streaming loop always moves T row tiles, so T follows the task: 1, 2, 4 or 8.  Up to 32 columns a pass
+    // takes up to 8 tiles; with 64 columns the accumulators of 8 tiles no longer fit the register file next to the
+    // weight ring (spills inside the streaming loop queue behind the weight loads), so a pass takes at most 4.
+#define ETC_CHUNKED(NB_)                                                                         \
+    {                                                                                            \
+        if (g.n_tiles == 1) gemm_tiles_chunked<NB_, 1>(PL, g, e, w, sm, task_id);                \
+        else if (g.n_tiles == 2) gemm_tiles_chunked<NB_, 2>(PL, g, e, w, sm, task_id);           \
+        else if (g.n_tiles <= 4) gemm_tiles_chunked<NB_, 4>(PL, g, e, w, sm, task_id);           \
+        else if (NB_ == 4) gemm_tiles_chunked_passes<NB_, 4>(PL, g, e, w, sm, task_id);          \
+        else if (g.n_tiles <= 8) gemm_tiles_chunked<NB_, NB_ == 4 ? 4 : 8>(PL, g, e, w, sm, task_id);        \
+        else gemm_tiles_chunked_passes<NB_, NB_ == 4 ? 4 : 8>(PL, g, e, w, sm, task_id);   /* crowded expert */ \
     }
-    if (g.n_tiles <= 4) {
-        if (g.n_cols <= 16) gemm_tiles_chunked<1, 4>(PL, g, e, w, sm, task_id);
-        else gemm_tiles_chunked<2, 4>(PL, g, e, w, sm, task_id);
-    } else if (g.n_tiles <= 8) {
-        if (g.n_cols <= 16) gemm_tiles_chunked<1, 8>(PL, g, e, w, sm, task_id);
-        else gemm_tiles_chunked<2, 8>(PL, g, e, w, sm, task_id);
-    } else {                             // only GroupGEMM tasks of a crowded expert
-        if (g.n_cols <= 16) gemm_tiles_chunked_passes<1, 8>(PL, g, e, w, sm, task_id);
-        else gemm_tiles_chunked_passes<2, 8>(PL, g, e, w, sm, task_id);
-    }
+    if (g.n_cols > 32) ETC_CHUNKED(4)
+    else if (g.n_cols > 16) ETC_CHUNKED(2)
+    else ETC_CHUNKED(1)
+#undef ETC_CHUNKED
 }
 
 // Second stage of a K-sliced projection: adds the partial sums of the slices in slice order (fixed, so the

@@ -195,6 +195,10 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
             int cand = tiles / std::max(1, n_queues);
             while (cand > 1 && (tiles % cand || per_slice % cand || !staged_fits(cand, Bs, m.H))) --cand;
             r_gu = std::max(1, cand);
+            // The down projection's operand (K = ffn) leaves LDS first, at batch 3 on the 8B shape.  One slice of K
+            // still fits, so it is cut along K like the large-batch projections and stays on the staged path.
+            const int s_d = k_slices_for(m.F);
+            if (!staged_fits(1, Bs, m.F) && s_d > 0 && staged_fits(8, Bs, m.F / s_d)) g.k_slices_d = s_d;
         }
     } else {
         // Large batches take the chunked path, where every task reads its operand from memory: traffic that
@@ -218,13 +222,14 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
             }
         }
     }
-    g.all_staged = m.E == 0 && staged_fits(r_qkv, Bs, m.H) && staged_fits(1, Bs, m.nq * m.d) && staged_fits(r_gu, Bs, m.H) &&
-                   staged_fits(1, Bs, m.F);
     const int n_ht = m.H / 16, pass_tiles = pass_tiles_for(Bs);
     const bool slice_o = g.k_slices_o > 0 && n_ht % pass_tiles == 0;
     const bool slice_d = g.k_slices_d > 0 && n_ht % pass_tiles == 0;
     if (!slice_o) g.k_slices_o = 0;
     if (!slice_d) g.k_slices_d = 0;
+    g.all_staged = m.E == 0 && staged_fits(r_qkv, Bs, m.H) && staged_fits(r_gu, Bs, m.H) &&
+                   (slice_o ? staged_fits(pass_tiles, Bs, m.nq * m.d / g.k_slices_o) : staged_fits(1, Bs, m.nq * m.d)) &&
+                   (slice_d ? staged_fits(pass_tiles, Bs, m.F / g.k_slices_d) : staged_fits(1, Bs, m.F));
 
     int stage = 0;
     int e_x = g.add_event({one});

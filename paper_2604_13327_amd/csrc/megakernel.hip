@@ -232,10 +232,11 @@ __device__ __forceinline__ void setup_moe_gemm(const Params &P, const Task &t, c
 }
 
 // KIND: which task kinds the kernel instance carries: 0 generic graphs (the row-sum device functions), 1 dense
-// decoder, 2 MoE decoder, 3 dense decoder whose projection tasks all fit the staged path (small batches).  The
+// decoder, 2 MoE decoder, 3 dense decoder whose projection tasks all fit the staged path (small batches), 4 the
+// same with K-slice tasks (the batches at which only a slice of the down projection's operand fits).  The
 // one large kernel is short of registers, and code that cannot run still costs some: the dense instance alone
 // is 5 % faster than an instance that carries everything, the staged-only instance another 2 %.
-constexpr int KIND_GENERIC = 0, KIND_DENSE = 1, KIND_MOE = 2, KIND_DENSE_STAGED = 3;
+constexpr int KIND_GENERIC = 0, KIND_DENSE = 1, KIND_MOE = 2, KIND_DENSE_STAGED = 3, KIND_DENSE_STAGED_K = 4;
 template <bool SYNC_EVENTS, int KIND>
 __device__ __forceinline__ void run_task(const Params &P, const Params &PL, const Task &t, float *sm, WgState &st)
 {
@@ -261,14 +262,22 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
         gemm_tile_dispatch(P, PL, g, e, tw, sm, st, t.id);
         return;
     }
-    constexpr bool STAGED_ONLY = KIND == KIND_DENSE_STAGED;
+    constexpr bool STAGED_ONLY = KIND == KIND_DENSE_STAGED || KIND == KIND_DENSE_STAGED_K;
+    constexpr bool STAGED_SLICES = KIND == KIND_DENSE_STAGED_K;
     if (KIND != KIND_GENERIC && !STAGED_ONLY && (t.flags & TF_K_SLICE)) {
         st = k_slice_task(PL, t, tw, sm, st);
         return;
     }
     if (KIND != KIND_GENERIC && setup_gemm<MOE>(P, t, g, e)) {
-        if (STAGED_ONLY) gemm_tiles_staged(P, g, e, tw, sm, st, t.id);
-        else gemm_tile_dispatch(P, PL, g, e, tw, sm, st, t.id);
+        if (STAGED_ONLY) {
+            if (STAGED_SLICES && (t.flags & TF_K_SLICE)) {      // here a slice of K fits the staged path as well
+                slice_of_k(P, t, t.fn == FN_OPROJ ? P.k_slices_o : P.k_slices_d, g, e);
+                if (w0 >= 0) tw.op_key = w0 + ((t.c1 + 1) << 20);
+            }
+            gemm_tiles_staged(P, g, e, tw, sm, st, t.id);
+        } else {
+            gemm_tile_dispatch(P, PL, g, e, tw, sm, st, t.id);
+        }
         return;
     }
     if (KIND == KIND_GENERIC) {
@@ -283,7 +292,7 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
         break;
     case FN_OPROJ_SUM:
     case FN_DOWN_SUM:
-        if (!STAGED_ONLY) k_slice_sum_task(PL, t, w0, w1);
+        if (!STAGED_ONLY || STAGED_SLICES) k_slice_sum_task(PL, t, w0, w1);
         break;
     case FN_ATTN: {
         const int b = t.c0, kvh = t.c1, ch = t.c2;
@@ -496,11 +505,11 @@ namespace etc {
 hipError_t configure_kernels()
 {
     const void *kernels[] = {(const void *)megakernel_static<0>, (const void *)megakernel_static<1>, (const void *)megakernel_static<2>,
-                             (const void *)megakernel_static<3>,
+                             (const void *)megakernel_static<3>, (const void *)megakernel_static<4>,
                              (const void *)megakernel_dynamic<0>, (const void *)megakernel_dynamic<1>, (const void *)megakernel_dynamic<2>,
-                             (const void *)megakernel_dynamic<3>,
+                             (const void *)megakernel_dynamic<3>, (const void *)megakernel_dynamic<4>,
                              (const void *)stage_kernel<0>, (const void *)stage_kernel<1>, (const void *)stage_kernel<2>,
-                             (const void *)stage_kernel<3>};
+                             (const void *)stage_kernel<3>, (const void *)stage_kernel<4>};
     for (const void *k : kernels) {
         hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;
@@ -518,7 +527,8 @@ static int kind_of(const Params &P)
 {
     if (P.n_layers == 0) return KIND_GENERIC;
     if (P.E > 0) return KIND_MOE;
-    return P.all_staged ? KIND_DENSE_STAGED : KIND_DENSE;
+    if (!P.all_staged) return KIND_DENSE;
+    return (P.k_slices_o > 0 || P.k_slices_d > 0) ? KIND_DENSE_STAGED_K : KIND_DENSE_STAGED;
 }
 
 #define ETC_LAUNCH_KIND(KERNEL, GRID, ...)                                                                          \
@@ -526,6 +536,7 @@ static int kind_of(const Params &P)
     case KIND_GENERIC: hipLaunchKernelGGL(KERNEL<KIND_GENERIC>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break; \
     case KIND_DENSE: hipLaunchKernelGGL(KERNEL<KIND_DENSE>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break;     \
     case KIND_DENSE_STAGED: hipLaunchKernelGGL(KERNEL<KIND_DENSE_STAGED>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break; \
+    case KIND_DENSE_STAGED_K: hipLaunchKernelGGL(KERNEL<KIND_DENSE_STAGED_K>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break; \
     default: hipLaunchKernelGGL(KERNEL<KIND_MOE>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break;               \
     }
 

@@ -293,3 +293,22 @@ def test_large_batch_plan_tile_shapes():
     for p in (plan, plan1):
         ev, done = run_static(p, np.random.default_rng(5)) if len(p["tasks"]) < 100000 else (np.zeros(1), np.ones(1))
         assert (ev == 0).all() and (done == 1).all()
+
+
+def test_mid_batch_down_projection_is_cut_along_k():
+    """Batch 4 on the 8B shape: QKV, O and gate/up operands (K = 4096) still fit LDS whole, the down projection's
+    (K = 14336) does not, one of its 8 slices of K does: it is cut along K (8 row tiles per task, one event per
+    slice fed by the gate/up tiles of that slice, a second stage that adds the slices) instead of leaving the
+    staged path.  Batch 2 keeps the whole-K down projection with per-wavefront waits."""
+    s = synth.LLAMA3_8B
+    t4 = etc.plan_build(s, 64, 4, 256, max_kv_len=2049)["tasks"]
+    l0 = t4[t4["layer"] == 0]
+    down, total = l0[l0["fn"] == 9], l0[l0["fn"] == 16]
+    assert len(down) == 256 and (down["flags"] & 8).all() and (down["c2"] == 8).all() and not (down["flags"] & PER_WAVE).any()
+    assert len(total) == 256 and (l0["fn"] == 15).sum() == 0 and (l0["fn"] == 7).sum() == 256
+    assert len(set(down["wait0"].tolist())) == 8
+    t2 = etc.plan_build(s, 64, 2, 256, max_kv_len=2049)["tasks"]
+    d2 = t2[(t2["layer"] == 0) & (t2["fn"] == 9)]
+    assert len(d2) == 256 and (d2["flags"] & PER_WAVE).all() and not (d2["flags"] & 8).any()
+    assert ((t2["fn"] == 16) | (t2["fn"] == 15)).sum() == 0
+

@@ -30,7 +30,7 @@ def main() -> int:
     ap.add_argument("--sched", default="static", choices=["static", "unfused"])
     ap.add_argument("--kv-len", type=int, default=1024)
     ap.add_argument("--batch", type=int, default=1)
-    ap.add_argument("--kv-chunk", type=int, default=64)
+    ap.add_argument("--kv-chunk", type=int, default=128, help="smallest number of keys per split-KV attention task")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-comparators", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=0, help="layers the CPU oracle runs (0 = all)")

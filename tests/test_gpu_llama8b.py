@@ -19,7 +19,7 @@ def test_llama8b_bs1_full_chain_matches_oracle_per_layer():
     seed, L = 2024, 1024
     n_pool = synth.pages_needed(L, s.page) + 16
     model = GpuModel(s, seed, n_pool)
-    dec = etc.Decoder(s, kv_chunk_tokens=64, sampled_batches=[1], max_kv_len=L + 1,
+    dec = etc.Decoder(s, kv_chunk_tokens=128, sampled_batches=[1], max_kv_len=L + 1,
                       debug_flags=etc.DEBUG_EXEC_COUNT | etc.DEBUG_LAYER_HIDDEN, spin_budget=2000000)
     model.bind(dec)
     step = fixed_step(s, 1, [L], n_pool, seed=7)

@@ -298,14 +298,13 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
         const int b = t.c0, kvh = t.c1, ch = t.c2;
         const bool active = b < P.B && ch * P.kv_chunk < gld_i32(P.kv_len + b) + 1;
         if (active) {     // inactive slots of the sampled-shape queue neither wait nor compute; they still notify
-            wg_wait_cached(P, st, w0, w1, t.fn);
-            st.staged_key = -1;      // the attention scratch overlaps the staged operand
+            st.staged_key = -1;      // the attention scratch overlaps the staged operand (the task waits inside)
             const int grp = P.nq / P.nkv;
             const bool lds_pages = P.kv_chunk > 128;      // more than one batch of keys per chunk
 #define ETC_ATTN(DD, GG)                                                                   \
     if (P.d == DD && grp == GG) {                                                          \
-        if (lds_pages) attn_chunk<DD, GG, true>(PL, t.layer, b, kvh, ch, sm);              \
-        else attn_chunk<DD, GG, false>(PL, t.layer, b, kvh, ch, sm);                       \
+        if (lds_pages) attn_chunk<DD, GG, true>(PL, t.layer, b, kvh, ch, sm, w0, w1);      \
+        else attn_chunk<DD, GG, false>(PL, t.layer, b, kvh, ch, sm, w0, w1);               \
     }
             ETC_ATTN(128, 4) else ETC_ATTN(128, 8) else ETC_ATTN(64, 2) else ETC_ATTN(128, 1) else ETC_ATTN(64, 4)
 #undef ETC_ATTN

@@ -14,8 +14,11 @@
 
 namespace etc {
 
+// ev0 / ev1: the events the task waits on (the queries and this step's K / V row of the KV head).  The cached K / V
+// rows do not depend on them: a chunk of one batch requests its rows BEFORE it waits, like a projection task its
+// weights, so that after the wait only the queries are a round trip away (3.72 -> 3.62 ms per 8B step).
 template <int D, int GRP, bool PAGES_IN_LDS>
-__device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int kvh, int ch, float *sm)
+__device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int kvh, int ch, float *sm, int ev0, int ev1)
 {
     constexpr int LPT = D / 8;        // lanes per key
     constexpr int TPW = 64 / LPT;     // keys per wavefront step
@@ -29,16 +32,18 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
     const float qscale = 1.0f / sqrtf((float)D);
 
     float q[GRP][8];
+    auto load_queries = [&]() {
 #pragma unroll
-    for (int g = 0; g < GRP; ++g) {
-        const float *qp = P.qbuf + (size_t)b * (size_t)(P.nq * D) + (size_t)(kvh * GRP + g) * D + dl * 8;
+        for (int g = 0; g < GRP; ++g) {
+            const float *qp = P.qbuf + (size_t)b * (size_t)(P.nq * D) + (size_t)(kvh * GRP + g) * D + dl * 8;
 #pragma unroll
-        for (int i = 0; i < 8; i += 2) {
-            ld_f32x2(qp + i, q[g][i], q[g][i + 1]);
-            q[g][i] *= qscale;
-            q[g][i + 1] *= qscale;
+            for (int i = 0; i < 8; i += 2) {
+                ld_f32x2(qp + i, q[g][i], q[g][i + 1]);
+                q[g][i] *= qscale;
+                q[g][i + 1] *= qscale;
+            }
         }
-    }
+    };
     float mx[GRP], l[GRP], o[GRP][8];
 #pragma unroll
     for (int g = 0; g < GRP; ++g) {
@@ -54,14 +59,10 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
     ETC_AS_LDS int *s_pg = reinterpret_cast<ETC_AS_LDS int *>(as_lds(sm)) + 10240;     // behind the 40 KB of reduction scratch
     const int pg0 = j0 / P.page, n_pg = (j1 - 1) / P.page - pg0 + 1;
     constexpr int BATCH = GRP >= 8 ? 2 : 4;       // 8 query heads per KV head leave registers for 2 steps in flight
-    if (PAGES_IN_LDS) {            // chunks of one batch (PAGES_IN_LDS false) read their page ids straight from memory
-        for (int i = threadIdx.x; i < n_pg; i += kWgThreads) s_pg[i] = gld_i32(pages + pg0 + i);
-        __syncthreads();
-    }
-    for (int jb0 = j0 + wave * TPW; jb0 < j1; jb0 += BATCH * kWaves * TPW) {   // uniform trip count per wave
-        int page[BATCH];
-        bool val[BATCH];
-        int jcs[BATCH];
+    constexpr int STEP = BATCH * kWaves * TPW;    // keys the workgroup covers per batch
+    // requests all K and V rows of the batch that starts at key jb0 (rows beyond the chunk re-read its last key)
+    auto request = [&](int jb0, u32x4 (&krs)[BATCH], u32x4 (&vrs)[BATCH], bool (&val)[BATCH]) {
+        int page[BATCH], jcs[BATCH];
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
             const int j = jb0 + u * kWaves * TPW + tq;
@@ -69,13 +70,15 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
             jcs[u] = j < j1 ? j : j1 - 1;
             page[u] = PAGES_IN_LDS ? s_pg[jcs[u] / P.page - pg0] : gld_i32(pages + jcs[u] / P.page);
         }
-        u32x4 krs[BATCH], vrs[BATCH];
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
             const size_t off = lbase + (((size_t)page[u] * P.page + (size_t)(jcs[u] % P.page)) * P.nkv + kvh) * (size_t)D + dl * 8;
             krs[u] = gld_16B(P.kpool + off);
             vrs[u] = gld_16B(P.vpool + off);
         }
+    };
+    // folds the batch's keys into the running softmax of every query head of the group
+    auto fold = [&](int jb0, const u32x4 (&krs)[BATCH], const u32x4 (&vrs)[BATCH], const bool (&val)[BATCH]) {
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
             if (jb0 + u * kWaves * TPW >= j1) break;     // uniform per wave
@@ -107,6 +110,31 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
                     mx[g] = nm;
                 }
             }
+        }
+    };
+    const int jb_first = j0 + wave * TPW;
+    if (PAGES_IN_LDS) {            // long chunks: wait, then the page ids go to LDS and the batches follow
+        wg_wait(P, ev0, ev1, FN_ATTN);
+        load_queries();
+        for (int i = threadIdx.x; i < n_pg; i += kWgThreads) s_pg[i] = gld_i32(pages + pg0 + i);
+        __syncthreads();
+        for (int jb0 = jb_first; jb0 < j1; jb0 += STEP) {         // uniform trip count per wave
+            u32x4 krs[BATCH], vrs[BATCH];
+            bool val[BATCH];
+            request(jb0, krs, vrs, val);
+            fold(jb0, krs, vrs, val);
+        }
+    } else {                       // chunks of (about) one batch: its rows are requested before the wait
+        u32x4 krs[BATCH], vrs[BATCH];
+        bool val[BATCH];
+        const bool first = jb_first < j1;                          // uniform per wave
+        if (first) request(jb_first, krs, vrs, val);
+        wg_wait(P, ev0, ev1, FN_ATTN);
+        load_queries();
+        if (first) fold(jb_first, krs, vrs, val);
+        for (int jb0 = jb_first + STEP; jb0 < j1; jb0 += STEP) {
+            request(jb0, krs, vrs, val);
+            fold(jb0, krs, vrs, val);
         }
     }
 
@@ -200,19 +228,19 @@ __device__ __noinline__ void attn_merge(const Params &P, int b, int kvh)
         const int g = idx / D, i = idx % D;
         const int h = kvh * GRP + g;
         const size_t p0 = ((size_t)b * P.nq + h) * (size_t)P.max_chunks;
-        // one pass in ascending chunk order, 8 chunks' loads in flight at a time, running max rescaling
+        // one pass in ascending chunk order, 16 chunks' loads in flight at a time, running max rescaling
         float m = -INFINITY, num = 0.f, den = 0.f;
-        for (int c0 = 0; c0 < nc; c0 += 8) {
-            float pm[8], pl[8], po[8];
+        for (int c0 = 0; c0 < nc; c0 += 16) {
+            float pm[16], pl[16], po[16];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < 16; ++u) {
                 const int c = c0 + u < nc ? c0 + u : nc - 1;
                 pm[u] = ld_f32(P.part_m + p0 + c);
                 pl[u] = ld_f32(P.part_l + p0 + c);
                 po[u] = ld_f32(P.part_o + (p0 + c) * D + i);
             }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < 16; ++u) {
                 if (c0 + u < nc) {
                     const float nm = fmaxf(m, pm[u]);
                     const float sa = __expf(m - nm), sb = __expf(pm[u] - nm);

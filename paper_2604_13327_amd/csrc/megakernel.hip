@@ -274,7 +274,7 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
                 slice_of_k(P, t, t.fn == FN_OPROJ ? P.k_slices_o : P.k_slices_d, g, e);
                 if (w0 >= 0) tw.op_key = w0 + ((t.c1 + 1) << 20);
             }
-            gemm_tiles_staged(P, g, e, tw, sm, st, t.id);
+            gemm_tiles_staged<10>(P, g, e, tw, sm, st, t.id);
         } else {
             gemm_tile_dispatch(P, PL, g, e, tw, sm, st, t.id);
         }

@@ -143,9 +143,11 @@ __device__ __forceinline__ void wg_wait_cached(const Params &P, WgState &st, int
 //     registers: refilled in front of them it needs other registers, and the copy back at the loop's end
 //     waits for every load of the revolution.
 // With both, every step waits for exactly the oldest of the PF loads (4.08 -> 3.94 ms per 8B step).
+template <int PRE>
 __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTile &g, const Epilogue &e, const TaskWaits &w,
                                                   float *sm, WgState &st, int task_id)
 {
+    static_assert(PRE >= 1 && PRE <= PF, "ring slots requested before the wait");
     const int wave = wave_id(), lane = lane_id();
     const int m = lane & 15, kg = lane >> 4;
     const int Kw = g.K / kWaves, n_it = Kw >> 5;
@@ -174,13 +176,11 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
         is = wrap ? 0 : is;
     };
     u32x4 wr[PF];
-    // Of the PF ring slots, ETC_PRE are requested before the task waits on its events and the rest behind the
+    // Of the PF ring slots, PRE are requested before the task waits on its events and the rest behind the
     // operand once the events have fired: the poll and the operand queue behind whatever was prefetched, which
-    // costs the workgroup that arrives last (and sets the stage's end) exactly what it gains the early ones.
-    // Measured on the 8B step: 8 / 10 / 12 / 14 / 16 slots before the wait = 3.95 / 3.88 / 3.88 / 3.95 / 3.92 ms.
-#ifndef ETC_PRE
-#define ETC_PRE 10
-#endif
+    // costs the workgroup that arrives last (and sets the stage's end) what it gains the early ones.  Measured:
+    // 8B step (staged-only instance) 8 / 10 / 12 / 14 / 16 slots = 3.95 / 3.88 / 3.88 / 3.95 / 3.92 ms; the MoE
+    // step is 5 % faster with all 16 (its tasks are small and many), so the count is a parameter of the instance.
     auto prefetch_range = [&](int j0, int j1) {
 #pragma unroll
         for (int j = 0; j < PF; ++j) {
@@ -203,7 +203,7 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
     const bool will_wait = restage ? (!event_known_zero(st, w.ev0) || w.per_wave || !event_known_zero(st, w.ev1))
                                    : !event_known_zero(st, w.ev1);
     const bool fired = !will_wait;
-    if (!fired) prefetch_range(0, ETC_PRE);
+    if (!fired) prefetch_range(0, PRE);
 
     // What the epilogue will need (single pass of the epilogue loop only) is requested right behind the operand:
     // it is back by the time the operand sits in LDS, and the streaming loop starts without another round trip.
@@ -263,7 +263,7 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
                 }
             }
             request_epilogue_inputs();
-            if (fired) prefetch(); else prefetch_range(ETC_PRE, PF);   // right behind the operand loads
+            if (fired) prefetch(); else prefetch_range(PRE, PF);   // right behind the operand loads
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int idx = (int)threadIdx.x + u * kWgThreads;
@@ -292,7 +292,7 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
                 }
             }
             request_epilogue_inputs();
-            if (fired) prefetch(); else prefetch_range(ETC_PRE, PF);
+            if (fired) prefetch(); else prefetch_range(PRE, PF);
         }
         if (g.ssq_parts) {       // RMSNorm factor of every column: fixed-order sum of the producers' partial sums of squares
             if (one_col_per_wave) {
@@ -322,7 +322,7 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
         } else {
             wg_wait_cached(P, st, w.ev1, -1, w.fn);
             request_epilogue_inputs();
-            prefetch_range(ETC_PRE, PF);
+            prefetch_range(PRE, PF);
         }
     }
     trace_mark(P, task_id, 2);
@@ -679,7 +679,7 @@ __device__ __forceinline__ void gemm_tile_dispatch(const Params &P, const Params
                                                    const TaskWaits &w, float *sm, WgState &st, int task_id)
 {
     if (staged_fits(g.n_tiles, g.n_cols, g.K)) {
-        gemm_tiles_staged(P, g, e, w, sm, st, task_id);
+        gemm_tiles_staged<PF>(P, g, e, w, sm, st, task_id);
         return;
     }
     st.staged_key = -1;

@@ -61,8 +61,8 @@ typedef struct {
 /* Tile shapes of the task grids (Sec. 2.1: tasks are CU-level tiles). */
 typedef struct {
     int32_t kv_chunk_tokens; /* smallest number of keys per split-KV attention task; multiple of page_size.
-                                Per sampled batch size the library enlarges it (in whole pages) when batch x KV
-                                heads alone gives about two attention tasks per queue. */
+                                Per sampled batch size the library enlarges it (in whole pages) until a layer
+                                has about one attention task per queue. */
     int32_t moe_tile_m;      /* tokens per GroupGEMM row tile (exp_indptr unit, Sec. 2.4); 1..16 */
 } etc_tile_desc;
 

@@ -92,11 +92,12 @@ inline int moe_max_row_tiles(int n_experts, int top_k, int batch, int tile_m)
 }
 
 // Keys per split-KV attention task for one sampled batch size.  `min_chunk` is the caller's tile shape; it
-// is enlarged (in whole pages) when (batch x kv heads) alone already gives about two tasks per queue, so
-// that long sequences of a large batch are not cut into thousands of latency-bound tasks.
+// is enlarged (in whole pages) until a layer has about one attention task per queue: every chunk costs a
+// partial result the merge reads back, and a second task per queue only adds such chunks (half a task per
+// queue leaves queues idle and measured slower from batch 4 on).
 inline int effective_kv_chunk(int min_chunk, int page, int max_kv_len, int batch, int n_kv_heads, int n_queues)
 {
-    const int pairs = batch * n_kv_heads, target = 2 * n_queues;
+    const int pairs = batch * n_kv_heads, target = n_queues;
     int chunks = (target + pairs - 1) / pairs;
     const int most = (max_kv_len + min_chunk - 1) / min_chunk;
     if (chunks > most) chunks = most;

@@ -27,10 +27,10 @@ namespace {
 
 std::string g_create_error;
 
-// The dynamic-scheduler kernel did not terminate on the device in its first runs and the cause is
-// not established yet, so launching it is refused (the static and unfused schedulers are unaffected).
-constexpr bool kDynamicEnabled = false;
-const char *kDynamicOffMsg = "the dynamic scheduler is switched off: its kernel did not terminate on the device";
+// Switch for the dynamic-scheduler kernel (off: launching it is refused; the static and unfused schedulers
+// are unaffected).
+constexpr bool kDynamicEnabled = true;
+const char *kDynamicOffMsg = "the dynamic scheduler is switched off in this build";
 
 struct DevPlan {          // one instantiated plan (one sampled batch size), host + device copies
     int sampled_batch = 0;

@@ -411,16 +411,47 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_static(const Params P)
 // add on tail, then publish each slot; pop: take a ticket with an atomic add on head, then wait for
 // that slot to carry this launch's epoch.  Control words: head, tail, done, tasks completed, tasks
 // created at run time.  Completing the last task sets `done`, which releases the idle poppers.
+// Slots and control words follow the rule of all cross-task data here: device-scope stores and loads,
+// no cache-wide fence (the pusher's workgroup drained its data stores before the notify that led to the
+// push, and a popped task reads cross-task data with device-scope loads only).
 __device__ __forceinline__ void q_push(const Params &P, const int32_t *ids, int n)
 {
     if (n <= 0) return;
-    const int base = __hip_atomic_fetch_add(P.q_ctrl_cur + 1, n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int base = __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 1), n, __ATOMIC_RELAXED, ETC_SCOPE);
     if (base + n > P.q_capacity) { raise_error(P, ERR_QUEUE_OVERFLOW, 0, base); return; }
     for (int i = 0; i < n; ++i)
-        __hip_atomic_store(P.q_slots + base + i, ((uint64_t)P.epoch << 32) | (uint64_t)(uint32_t)(ids[i] + 1),
-                           __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(as_global(P.q_slots + base + i),
+                           ((uint64_t)P.epoch << 32) | (uint64_t)(uint32_t)(gld_i32(ids + i) + 1), __ATOMIC_RELAXED,
+                           ETC_SCOPE);
 }
 
+// One lane takes the next ticket and waits for its slot: the task id, or -1 when the step is complete,
+// the queue is exhausted or an error was raised.
+__device__ __forceinline__ int q_pop(const Params &P)
+{
+    const int ticket = __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 0), 1, __ATOMIC_RELAXED, ETC_SCOPE);
+    if (ticket >= P.q_capacity) return -1;
+    int id = -1;
+    long long spins = 0;
+    for (;;) {
+        const uint64_t v = ld_u64(P.q_slots + ticket);
+        if ((uint32_t)(v >> 32) == P.epoch) { id = (int)(uint32_t)v - 1; break; }
+        if (ev_peek(P.q_ctrl_cur + 2) != 0) break;
+        if (spins < 32) __builtin_amdgcn_s_sleep(2); else __builtin_amdgcn_s_sleep(32);
+        ++spins;
+        if ((spins & 63) == 0 && ev_peek(P.error_word) != 0) break;
+        if (spins > P.spin_budget) { raise_error(P, ERR_POP_TIMEOUT, 0, ticket); break; }
+    }
+    return id;
+}
+
+// Loop shape.  The lane that notifies, pushes and pops shares a wavefront with 63 lanes that do not, and
+// the task id reaches the other lanes through LDS and a barrier.  The single-lane block therefore sits
+// BETWEEN the task's closing barrier and the barrier that publishes the next id, inside one iteration,
+// and the loop condition is a scalar: with the block split over the loop's back edge (pop at the top,
+// notify at the bottom) the compiler merged the two single-lane blocks and let the other 63 lanes of
+// that wavefront run ahead into the next iteration's barrier first, where every wavefront then read the
+// previous id again: the same task was repeated without end and the lane that would pop never ran.
 template <int KIND>
 __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
 {
@@ -432,52 +463,34 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
     if (blockIdx.x == 0 && threadIdx.x == 0) {            // reset the control words of the next launch
         for (int i = 0; i < 8; ++i) P.q_ctrl_next[i] = 0;
     }
-    // seed: tasks without a trigger edge, spread over the workgroups
-    if (threadIdx.x == 0)
+    if (threadIdx.x == 0) {
+        // seed: tasks without a trigger edge, spread over the workgroups
         for (int i = blockIdx.x; i < P.n_seed; i += gridDim.x) q_push(P, P.seed_tasks + i, 1);
-    for (;;) {
-        if (threadIdx.x == 0) {
-            int id = -1;
-            const int ticket = __hip_atomic_fetch_add(P.q_ctrl_cur + 0, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (ticket < P.q_capacity) {
-                // Poll with relaxed device-scope loads and fence once after the slot is seen: an acquire
-                // load inside the loop would invalidate the L2 on every iteration on every idle CU.
-                long long spins = 0;
-                for (;;) {
-                    const uint64_t v = __hip_atomic_load(P.q_slots + ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    if ((uint32_t)(v >> 32) == P.epoch) { id = (int)(uint32_t)v - 1; break; }
-                    if (ev_peek(P.q_ctrl_cur + 2) != 0) break;
-                    if (spins < 32) __builtin_amdgcn_s_sleep(2); else __builtin_amdgcn_s_sleep(32);
-                    ++spins;
-                    if ((spins & 63) == 0 && ev_peek(P.error_word) != 0) break;
-                    if (spins > P.spin_budget) { raise_error(P, ERR_POP_TIMEOUT, 0, ticket); break; }
-                }
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-            }
-            s_task = id;
-        }
-        __syncthreads();
-        const int id = s_task;
-        __syncthreads();
-        if (id < 0) break;
+        s_task = q_pop(P);
+    }
+    __syncthreads();
+    int id = __builtin_amdgcn_readfirstlane(s_task);
+    while (id >= 0) {
         const Task t = load_task(P.dyn_tasks + id);
         WgState st;
         wg_state_init(st);
         run_task<true, KIND>(P, sP, t, sm, st);  // early push (App. E): remaining in-edges are still waited on
-        wg_release();
+        wg_release();                            // also: every lane has read s_task before it is written again
         if (threadIdx.x == 0) {
             if (P.debug_flags & 1u) atomicAdd(P.exec_count + t.id, 1);
             if (t.notify0 >= 0) {
                 if (ev_notify(P, t.notify0) == 1) {     // this notify fired the event: push its consumers
-                    const int c0 = P.ev_consumers[t.notify0], c1 = P.ev_consumers[t.notify0 + 1];
+                    const int c0 = gld_i32(P.ev_consumers + t.notify0), c1 = gld_i32(P.ev_consumers + t.notify0 + 1);
                     q_push(P, P.consumer_ids + c0, c1 - c0);
                 }
             }
             // termination: the workgroup that completes the last task of the step releases the idle poppers
-            const int n_done = __hip_atomic_fetch_add(P.q_ctrl_cur + 3, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
-            if (n_done == P.n_static_tasks + ev_peek(P.q_ctrl_cur + 4))
-                __hip_atomic_store(P.q_ctrl_cur + 2, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+            const int n_done = __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 3), 1, __ATOMIC_RELAXED, ETC_SCOPE) + 1;
+            if (n_done == P.n_static_tasks + ev_peek(P.q_ctrl_cur + 4)) st_i32(P.q_ctrl_cur + 2, 1);
+            s_task = q_pop(P);
         }
+        __syncthreads();
+        id = __builtin_amdgcn_readfirstlane(s_task);
     }
 }
 

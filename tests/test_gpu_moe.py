@@ -156,7 +156,7 @@ def test_tiny_moe_schedulers_and_kernel_by_kernel_agree_bitwise(tiny_moe_model):
     s, m = synth.TINY_MOE, tiny_moe_model
     step = fixed_step(s, 4, [40, 3, 77, 12], m.n_pool_pages, seed=2)
     outs = []
-    for kind in (etc.SCHED_STATIC, etc.SCHED_UNFUSED):
+    for kind in (etc.SCHED_STATIC, etc.SCHED_DYNAMIC, etc.SCHED_UNFUSED):
         dec = etc.Decoder(s, kv_chunk_tokens=32, sampled_batches=[1, 4], max_kv_len=129, kind=kind, moe_tile_m=2,
                           debug_flags=etc.DEBUG_EXEC_COUNT, spin_budget=SPIN)
         m.bind(dec)

@@ -44,9 +44,7 @@ def _rowsum_graph(etc, kind):
     return g
 
 
-DYN_OFF = pytest.mark.skip(reason="dynamic scheduler switched off in the library: its kernel did not terminate "
-                                   "on the device (two runs); cause not yet shown, so it stays off the GPU")
-KINDS = [0, pytest.param(1, marks=DYN_OFF), 2]
+KINDS = [0, 1, 2]                              # static, dynamic, unfused
 
 
 @pytest.mark.parametrize("kind", KINDS)
@@ -137,7 +135,7 @@ def test_tiny_all_schedulers_and_kernel_by_kernel_agree_bitwise(tiny_model):
     s = synth.TINY
     step = fixed_step(s, 3, [100, 7, 64], tiny_model.n_pool_pages, seed=9)
     outs = []
-    for kind in (0, 2):                    # 1 (dynamic) is switched off, see DYN_OFF
+    for kind in (0, 1, 2):                 # static, dynamic, unfused
         tiny_model.reset_pools()
         dec = etc.Decoder(s, kv_chunk_tokens=32, sampled_batches=[1, 4], max_kv_len=129, kind=kind,
                           debug_flags=etc.DEBUG_EXEC_COUNT, spin_budget=SPIN)

@@ -27,7 +27,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="llama3-8b", help="llama3-8b (headline) | tiny")
-    ap.add_argument("--sched", default="static", choices=["static", "unfused"])
+    ap.add_argument("--sched", default="static", choices=["static", "dynamic", "unfused"])
     ap.add_argument("--kv-len", type=int, default=1024)
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--kv-chunk", type=int, default=128, help="smallest number of keys per split-KV attention task")
@@ -61,7 +61,7 @@ def main() -> int:
 
     # ---- warm-up in the paper's sense (Sec. 4.4): engine start to first step served, minus model load
     t0 = time.time()
-    kind = etc.SCHED_STATIC if args.sched == "static" else etc.SCHED_UNFUSED
+    kind = {"static": etc.SCHED_STATIC, "dynamic": etc.SCHED_DYNAMIC, "unfused": etc.SCHED_UNFUSED}[args.sched]
     dec = etc.Decoder(shape, kv_chunk_tokens=args.kv_chunk, sampled_batches=[B], max_kv_len=L + 1, kind=kind)
     model.bind(dec)
     step = fixed_step(shape, B, [L] * B, n_pool, seed=7)
@@ -109,7 +109,7 @@ def main() -> int:
         "tokens_per_s": round(B / (us * 1e-6), 1),
         "latency_us": {"median": round(float(np.median(per)), 2), "p10": round(float(np.percentile(per, 10)), 2),
                        "p90": round(float(np.percentile(per, 90)), 2), "host_wall_per_step": round(wall, 2)},
-        "roofline": {"bound": "hbm", "kernel": "megakernel_static", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": "megakernel_dynamic" if args.sched == "dynamic" else "megakernel_static", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "algorithmic_bytes_per_launch": alg, "avg_launch_us": round(kern_us, 2), "traffic": None},
         "warmup_s": {"create_bind_first_step": round(t_warmup, 3), "synthetic_weight_fill": round(t_fill, 3)},
@@ -149,6 +149,18 @@ def main() -> int:
             result["unfused_megakernel_us"] = round(float(span_un), 2)
             result["speedup_vs_unfused"] = round(float(span_un) / us, 4)
             un.close()
+            # the dynamic scheduler (Alg. 2) on the same task bodies: its time, and that its output is the same bits
+            dy = etc.Decoder(shape, kv_chunk_tokens=args.kv_chunk, sampled_batches=[B], max_kv_len=L + 1,
+                             kind=etc.SCHED_DYNAMIC)
+            model.bind(dy)
+            dy.bind_step(step)
+            out_dy = torch.empty_like(x)
+            dy.launch(x, out_dy)
+            torch.cuda.synchronize()
+            result["dynamic_matches_static_bitwise"] = bool((bf16_to_f32_np(out_dy) == first_out).all())
+            _, span_dy, _ = timed(dy.launch, k, 2)
+            result["dynamic_megakernel_us"] = round(float(span_dy), 2)
+            dy.close()
 
     # ---- CPU oracle on the host cores: reported baseline + end-to-end parity of this very workload ----
     if not args.no_cpu_baseline:

@@ -414,15 +414,26 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_static(const Params P)
 // Slots and control words follow the rule of all cross-task data here: device-scope stores and loads,
 // no cache-wide fence (the pusher's workgroup drained its data stores before the notify that led to the
 // push, and a popped task reads cross-task data with device-scope loads only).
-__device__ __forceinline__ void q_push(const Params &P, const int32_t *ids, int n)
+__device__ __forceinline__ uint64_t q_slot_word(const Params &P, int task_id)
+{
+    return ((uint64_t)P.epoch << 32) | (uint64_t)(uint32_t)(task_id + 1);
+}
+
+// Publishes ids[0..n) to the ready queue.  Called by every lane of one wavefront: lane 0 reserves the
+// tickets, the lanes then fill the slots side by side (one lane alone took 0.3 us per task: a third of a
+// 33 000-task step).
+__device__ __forceinline__ void q_push_wave(const Params &P, const int32_t *ids, int n)
 {
     if (n <= 0) return;
-    const int base = __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 1), n, __ATOMIC_RELAXED, ETC_SCOPE);
-    if (base + n > P.q_capacity) { raise_error(P, ERR_QUEUE_OVERFLOW, 0, base); return; }
-    for (int i = 0; i < n; ++i)
-        __hip_atomic_store(as_global(P.q_slots + base + i),
-                           ((uint64_t)P.epoch << 32) | (uint64_t)(uint32_t)(gld_i32(ids + i) + 1), __ATOMIC_RELAXED,
-                           ETC_SCOPE);
+    int base = 0;
+    if (lane_id() == 0) base = __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 1), n, __ATOMIC_RELAXED, ETC_SCOPE);
+    base = __builtin_amdgcn_readfirstlane(base);
+    if (base + n > P.q_capacity) {
+        if (lane_id() == 0) raise_error(P, ERR_QUEUE_OVERFLOW, 0, base);
+        return;
+    }
+    for (int i = lane_id(); i < n; i += 64)
+        __hip_atomic_store(as_global(P.q_slots + base + i), q_slot_word(P, gld_i32(ids + i)), __ATOMIC_RELAXED, ETC_SCOPE);
 }
 
 // One lane takes the next ticket and waits for its slot: the task id, or -1 when the step is complete,
@@ -445,7 +456,7 @@ __device__ __forceinline__ int q_pop(const Params &P)
     return id;
 }
 
-// Loop shape.  The lane that notifies, pushes and pops shares a wavefront with 63 lanes that do not, and
+// Loop shape.  The lane that notifies and pops shares a wavefront with 63 lanes that do not, and
 // the task id reaches the other lanes through LDS and a barrier.  The single-lane block therefore sits
 // BETWEEN the task's closing barrier and the barrier that publishes the next id, inside one iteration,
 // and the loop condition is a scalar: with the block split over the loop's back edge (pop at the top,
@@ -463,31 +474,54 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
     if (blockIdx.x == 0 && threadIdx.x == 0) {            // reset the control words of the next launch
         for (int i = 0; i < 8; ++i) P.q_ctrl_next[i] = 0;
     }
-    if (threadIdx.x == 0) {
-        // seed: tasks without a trigger edge, spread over the workgroups
-        for (int i = blockIdx.x; i < P.n_seed; i += gridDim.x) q_push(P, P.seed_tasks + i, 1);
-        s_task = q_pop(P);
+    // Wavefront 0 is the scheduler of its workgroup: its lane 0 notifies and pops, all its lanes push.
+    const bool sched_wave = wave_id() == 0;
+    if (sched_wave) {
+        // seed: tasks without a trigger edge, a share per workgroup
+        const int n_seed = P.n_seed > (int)blockIdx.x ? (P.n_seed - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x : 0;
+        if (n_seed > 0) {
+            int base = 0;
+            if (lane_id() == 0) base = __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 1), n_seed, __ATOMIC_RELAXED, ETC_SCOPE);
+            base = __builtin_amdgcn_readfirstlane(base);
+            if (base + n_seed > P.q_capacity) {
+                if (lane_id() == 0) raise_error(P, ERR_QUEUE_OVERFLOW, 0, base);
+            } else {
+                for (int i = lane_id(); i < n_seed; i += 64)
+                    __hip_atomic_store(as_global(P.q_slots + base + i),
+                                       q_slot_word(P, gld_i32(P.seed_tasks + blockIdx.x + i * gridDim.x)), __ATOMIC_RELAXED,
+                                       ETC_SCOPE);
+            }
+        }
+        if (lane_id() == 0) s_task = q_pop(P);
     }
     __syncthreads();
     int id = __builtin_amdgcn_readfirstlane(s_task);
     while (id >= 0) {
-        const Task t = load_task(P.dyn_tasks + id);
+        Task t = load_task(P.dyn_tasks + id);
+        // The task was pushed because its trigger event fired, and the slot was published after that: nothing
+        // to wait for on that edge.  Per-wave waits (pushed on the last K slice's event) and a second in-edge
+        // are still waited on inside the task (early push, App. E).
+        if (!(t.flags & TF_WAIT0_PER_WAVE)) t.wait0 = -1;
         WgState st;
         wg_state_init(st);
-        run_task<true, KIND>(P, sP, t, sm, st);  // early push (App. E): remaining in-edges are still waited on
+        run_task<true, KIND>(P, sP, t, sm, st);
         wg_release();                            // also: every lane has read s_task before it is written again
-        if (threadIdx.x == 0) {
-            if (P.debug_flags & 1u) atomicAdd(P.exec_count + t.id, 1);
-            if (t.notify0 >= 0) {
-                if (ev_notify(P, t.notify0) == 1) {     // this notify fired the event: push its consumers
-                    const int c0 = gld_i32(P.ev_consumers + t.notify0), c1 = gld_i32(P.ev_consumers + t.notify0 + 1);
-                    q_push(P, P.consumer_ids + c0, c1 - c0);
-                }
+        if (sched_wave) {
+            int fired = 0;
+            if (lane_id() == 0) {
+                if (P.debug_flags & 1u) atomicAdd(P.exec_count + t.id, 1);
+                if (t.notify0 >= 0) fired = ev_notify(P, t.notify0) == 1;
             }
-            // termination: the workgroup that completes the last task of the step releases the idle poppers
-            const int n_done = __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 3), 1, __ATOMIC_RELAXED, ETC_SCOPE) + 1;
-            if (n_done == P.n_static_tasks + ev_peek(P.q_ctrl_cur + 4)) st_i32(P.q_ctrl_cur + 2, 1);
-            s_task = q_pop(P);
+            if (__builtin_amdgcn_readfirstlane(fired)) {      // this notify fired the event: push its consumers
+                const int c0 = gld_i32(P.ev_consumers + t.notify0), c1 = gld_i32(P.ev_consumers + t.notify0 + 1);
+                q_push_wave(P, P.consumer_ids + c0, c1 - c0);
+            }
+            if (lane_id() == 0) {
+                // termination: the workgroup that completes the last task of the step releases the idle poppers
+                const int n_done = __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 3), 1, __ATOMIC_RELAXED, ETC_SCOPE) + 1;
+                if (n_done == P.n_static_tasks + ev_peek(P.q_ctrl_cur + 4)) st_i32(P.q_ctrl_cur + 2, 1);
+                s_task = q_pop(P);
+            }
         }
         __syncthreads();
         id = __builtin_amdgcn_readfirstlane(s_task);

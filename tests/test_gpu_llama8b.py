@@ -36,6 +36,26 @@ def test_llama8b_bs1_full_chain_matches_oracle_per_layer():
     gpu_layers = [dec.layer_hidden(l) for l in range(s.n_layers)]
     got = bf16_to_f32_np(out)
     dec.close()
+
+    # the dynamic scheduler (Alg. 2) on the same step: same task bodies, so the same bits in every layer
+    model.reset_pools()
+    dyn = etc.Decoder(s, kv_chunk_tokens=128, sampled_batches=[1], max_kv_len=L + 1, kind=etc.SCHED_DYNAMIC,
+                      debug_flags=etc.DEBUG_EXEC_COUNT | etc.DEBUG_LAYER_HIDDEN, spin_budget=2000000)
+    model.bind(dyn)
+    dyn.bind_step(step)
+    out_dyn = torch.empty_like(x)
+    for rep in range(2):                    # the second launch runs on the re-armed events and queue words
+        model.reset_pools()
+        out_dyn.zero_()
+        dyn.launch(x, out_dyn)
+        torch.cuda.synchronize()
+        assert (dyn.error_word() == 0).all()
+        assert (dyn.event_counters() == 0).all()
+        assert (dyn.exec_counts() == rep + 1).all()
+        np.testing.assert_array_equal(bf16_to_f32_np(out_dyn), got)
+    for l in range(s.n_layers):
+        np.testing.assert_array_equal(dyn.layer_hidden(l), gpu_layers[l])
+    dyn.close()
     del model
     torch.cuda.empty_cache()
 

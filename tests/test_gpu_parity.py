@@ -249,12 +249,13 @@ def test_tiny_large_batches_take_the_chunked_path(batch):
     out2 = _run(dec, model, step, kbk=True)
     np.testing.assert_array_equal(out2, out)
     dec.close()
-    # the K-slice stages under one coarse event per stage
-    dec = etc.Decoder(s, kv_chunk_tokens=32, sampled_batches=[batch], max_kv_len=129, kind=etc.SCHED_UNFUSED,
-                      debug_flags=etc.DEBUG_EXEC_COUNT, spin_budget=SPIN)
-    model.bind(dec)
-    model.reset_pools()
-    out3 = _run(dec, model, step)
-    _check_invariants(dec)
-    np.testing.assert_array_equal(out3, out)
-    dec.close()
+    # the K-slice stages under one coarse event per stage, and pushed by the dynamic scheduler
+    for kind in (etc.SCHED_UNFUSED, etc.SCHED_DYNAMIC):
+        dec = etc.Decoder(s, kv_chunk_tokens=32, sampled_batches=[batch], max_kv_len=129, kind=kind,
+                          debug_flags=etc.DEBUG_EXEC_COUNT, spin_budget=SPIN)
+        model.bind(dec)
+        model.reset_pools()
+        out3 = _run(dec, model, step)
+        _check_invariants(dec)
+        np.testing.assert_array_equal(out3, out)
+        dec.close()

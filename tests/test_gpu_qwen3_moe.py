@@ -44,3 +44,34 @@ def test_qwen3_moe_all_batches_match_oracle(qwen_model):
             print(f"qwen3-moe B={B}: free-running oracle picks a different expert set for {n} of {B * s.n_layers} "
                   f"(token, layer) pairs, all near ties", flush=True)
     dec.close()
+
+
+def test_qwen3_moe_dynamic_scheduler_agrees_bitwise_with_static(qwen_model):
+    """The dynamic scheduler (Alg. 2: ready queue, push on zero) runs the same task bodies, so a sampled
+    batch (8), an unsampled one (5) and a large one (64) give the same bits as the static queues; every task
+    runs once and every event ends at zero, also on the second launch (re-armed events and queue words)."""
+    import paper_2604_13327_amd as etc
+    from test_gpu_moe import _launch
+    s, m = synth.QWEN3_30B_A3B, qwen_model
+    rng = np.random.default_rng(78)
+    steps = [fixed_step(s, B, rng.integers(256, MAX_LEN + 1, size=B), m.n_pool_pages, seed=950 + i)
+             for i, B in enumerate((8, 5, 64))]
+    outs = {}
+    for kind in (etc.SCHED_STATIC, etc.SCHED_DYNAMIC):
+        dec = etc.Decoder(s, kv_chunk_tokens=64, sampled_batches=[8, 64], max_kv_len=MAX_LEN + 1, moe_tile_m=16,
+                          kind=kind, debug_flags=etc.DEBUG_EXEC_COUNT, spin_budget=SPIN)
+        m.bind(dec)
+        for i, step in enumerate(steps):
+            dec.bind_step(step)
+            for rep in range(2):
+                m.reset_pools()
+                o = _launch(dec, m, step, step_index=i)
+                assert (dec.error_word() == 0).all()
+                assert (dec.event_counters() == 0).all() and (dec.exec_counts() == rep + 1).all()
+                outs.setdefault((kind, i), []).append(o)
+            print(f"qwen3-moe kind {kind} B={step.batch}: done", flush=True)
+        dec.close()
+    for i in range(len(steps)):
+        ref = outs[(etc.SCHED_STATIC, i)][0]
+        for o in outs[(etc.SCHED_STATIC, i)][1:] + outs[(etc.SCHED_DYNAMIC, i)]:
+            np.testing.assert_array_equal(o, ref)

@@ -84,6 +84,9 @@ struct etc_ctx {
     bool weights_dirty = true;
     Params base{};                          // device pointers and constants filled at create
     int32_t *d_events = nullptr;            // [3][n_events_max]: A | init | B
+    int32_t *d_disp = nullptr;              // [2][n_events_max]: dispatch counters of the dynamic scheduler, A | B
+    int32_t *d_pending = nullptr;           // [n_tasks_max]: dynamic scheduler, waited events passed per task
+    size_t n_tasks_max = 0;
     int n_events_max = 0;
     int parity = 0;
     uint32_t epoch = 1;
@@ -157,6 +160,9 @@ etc_status alloc_events_and_queue(etc_ctx *c)
     }
     c->n_events_max = (int)n_ev;
     HIP_TRY(c, dev_alloc(&c->d_events, 3 * n_ev, c->plan_owned));
+    HIP_TRY(c, dev_alloc(&c->d_disp, 2 * n_ev, c->plan_owned));
+    HIP_TRY(c, dev_alloc(&c->d_pending, n_tasks, c->plan_owned));
+    c->n_tasks_max = n_tasks;
     if (c->sched.debug_flags & ETC_DEBUG_EXEC_COUNT) HIP_TRY(c, dev_alloc(&c->base.exec_count, n_tasks + 65536, c->plan_owned));
     if (c->sched.debug_flags & ETC_DEBUG_TRACE) HIP_TRY(c, dev_alloc(&c->base.trace, n_tasks * 8, c->plan_owned));
     c->base.q_capacity = (int)(n_tasks + 65536 + c->n_queues);
@@ -173,7 +179,10 @@ etc_status arm_events(etc_ctx *c)
     if (n) {
         HIP_TRY(c, hipMemcpy(init, dp.host.ev_init.data(), n * sizeof(int32_t), hipMemcpyHostToDevice));
         HIP_TRY(c, hipMemcpy(cur, dp.host.ev_init.data(), n * sizeof(int32_t), hipMemcpyHostToDevice));
+        HIP_TRY(c, hipMemcpy(c->d_disp + (c->parity ? N : 0), dp.host.ev_init.data(), n * sizeof(int32_t),
+                             hipMemcpyHostToDevice));
     }
+    HIP_TRY(c, hipMemset(c->d_pending, 0, c->n_tasks_max * sizeof(int32_t)));
     HIP_TRY(c, hipMemset(c->d_qctrl + (c->parity ? 8 : 0), 0, 8 * sizeof(int32_t)));
     if (c->base.exec_count) HIP_TRY(c, hipMemset(c->base.exec_count, 0, dp.host.tasks.size() * sizeof(int32_t)));
     return ETC_OK;
@@ -194,6 +203,9 @@ void fill_launch_params(etc_ctx *c, Params &P)
     P.dyn_tasks = dp.d_tasks;
     P.ev_consumers = dp.d_ev_consumers;
     P.consumer_ids = dp.d_consumer_ids;
+    P.ev_disp_cur = c->d_disp + (c->parity ? N : 0);
+    P.ev_disp_next = c->d_disp + (c->parity ? 0 : N);
+    P.task_pending = c->d_pending;
     P.seed_tasks = dp.d_seed;
     P.n_seed = (int)dp.host.seed_tasks.size();
     P.n_static_tasks = (int)dp.host.tasks.size();

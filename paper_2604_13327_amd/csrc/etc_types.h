@@ -132,14 +132,17 @@ struct Params {
     int32_t n_queues;
     // dynamic scheduler
     const Task *dyn_tasks;             // task table indexed by task id
-    const int32_t *ev_consumers;       // [n_events + 1] CSR: tasks pushed when the event fires
-    const int32_t *consumer_ids;
+    const int32_t *ev_consumers;       // [n_events + 1] CSR: tasks that wait on the event
+    const int32_t *consumer_ids;       // task id | (number of events the task waits on << 24 when that is > 1)
+    int32_t *ev_disp_cur;              // per event: producers not yet dispatched (early push, App. E)
+    int32_t *ev_disp_next;             //   re-armed from ev_init like the event tensors
+    int32_t *task_pending;             // per task: waited events whose producers are all dispatched (counts up)
     const int32_t *seed_tasks;         // tasks with no trigger edge, pushed at start
     int32_t n_seed;
     int32_t n_static_tasks;
     uint64_t *q_slots;                 // (epoch << 32 | task id + 1)
     int32_t q_capacity;
-    int32_t *q_ctrl_cur;               // [head, tail, done, pad]
+    int32_t *q_ctrl_cur;               // [head, tail, -, tasks completed, ...]
     int32_t *q_ctrl_next;
     uint32_t epoch;
     // debug / safety

@@ -141,16 +141,26 @@ std::string instantiate(const GraphDecl &g, const int *sym, int n_queues, bool u
         p.queue_begin.push_back((int32_t)p.queue_tasks.size());
     }
 
-    // dynamic scheduling: the event whose firing pushes a task (its first in-edge; the last K slice
-    // for per-wave waits), as a CSR table event -> consumer tasks.
+    // dynamic scheduling with early push (App. E): a task is pushed once every producer of every event it
+    // waits on has been dispatched, so it is listed under each of those events (events nobody notifies count
+    // as passed, as for a wait); an entry of a task that waits on n > 1 events carries n in its top byte.
+    if (p.tasks.size() >= (1u << 24)) return "more than 2^24 tasks in one plan";
     std::vector<std::vector<int32_t>> cons(n_events);
     for (const Task &t : p.tasks) {
-        if (t.wait0 < 0) {
-            p.seed_tasks.push_back(t.id);
-        } else {
-            int trig = (t.flags & TF_WAIT0_PER_WAVE) ? t.wait0 + kWaves - 1 : t.wait0;
-            cons[trig].push_back(t.id);
+        int trig[kWaves + 1], n = 0;
+        auto add = [&](int e) {
+            if (e < 0 || p.ev_init[e] <= 0) return;
+            for (int k = 0; k < n; ++k)
+                if (trig[k] == e) return;
+            trig[n++] = e;
+        };
+        if (t.wait0 >= 0) {
+            const int span = (t.flags & TF_WAIT0_PER_WAVE) ? kWaves : 1;
+            for (int w = 0; w < span; ++w) add(t.wait0 + w);
         }
+        add(t.wait1);
+        if (n == 0) p.seed_tasks.push_back(t.id);
+        for (int k = 0; k < n; ++k) cons[trig[k]].push_back(t.id | (n > 1 ? n << 24 : 0));
     }
     p.ev_consumers.assign(1, 0);
     for (int e = 0; e < n_events; ++e) {

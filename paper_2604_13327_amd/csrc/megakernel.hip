@@ -409,51 +409,92 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_static(const Params P)
 // ---- dynamic scheduler ------------------------------------------------------------------------
 // Ready queue: q_slots[ticket] = (epoch << 32) | (task id + 1).  push: reserve tickets with an atomic
 // add on tail, then publish each slot; pop: take a ticket with an atomic add on head, then wait for
-// that slot to carry this launch's epoch.  Control words: head, tail, done, tasks completed, tasks
-// created at run time.  Completing the last task sets `done`, which releases the idle poppers.
+// that slot to carry this launch's epoch.  Control words: head, tail, -, tasks completed.  A popper
+// that finds its slot empty leaves once every task of the step has counted itself completed.
 // Slots and control words follow the rule of all cross-task data here: device-scope stores and loads,
-// no cache-wide fence (the pusher's workgroup drained its data stores before the notify that led to the
-// push, and a popped task reads cross-task data with device-scope loads only).
+// no cache-wide fence.
+//
+// Early push (App. E).  A task is pushed as soon as every producer of every event it waits on has been
+// DISPATCHED (popped by some workgroup), not completed: each event has a second counter that a producer
+// decrements when it is popped, and the workgroup that brings it to zero pushes the event's consumers
+// while its own task still has to run.  The consumer keeps its waits, so it can stream its weights and
+// then spin exactly like a task of a static queue; the push itself is off the critical path.  No
+// deadlock: a task that spins has all its producers running on other workgroups (or spinning in turn on
+// tasks dispatched before them).
 __device__ __forceinline__ uint64_t q_slot_word(const Params &P, int task_id)
 {
     return ((uint64_t)P.epoch << 32) | (uint64_t)(uint32_t)(task_id + 1);
 }
 
-// Publishes ids[0..n) to the ready queue.  Called by every lane of one wavefront: lane 0 reserves the
-// tickets, the lanes then fill the slots side by side (one lane alone took 0.3 us per task: a third of a
-// 33 000-task step).
-__device__ __forceinline__ void q_push_wave(const Params &P, const int32_t *ids, int n)
+// Reserves `cnt` tickets (lane 0) and returns the first one to every lane, or -1 when the queue is full.
+__device__ __forceinline__ int q_reserve_wave(const Params &P, int cnt)
 {
-    if (n <= 0) return;
     int base = 0;
-    if (lane_id() == 0) base = __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 1), n, __ATOMIC_RELAXED, ETC_SCOPE);
+    if (lane_id() == 0) base = __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 1), cnt, __ATOMIC_RELAXED, ETC_SCOPE);
     base = __builtin_amdgcn_readfirstlane(base);
-    if (base + n > P.q_capacity) {
+    if (base + cnt > P.q_capacity) {
         if (lane_id() == 0) raise_error(P, ERR_QUEUE_OVERFLOW, 0, base);
-        return;
+        return -1;
     }
-    for (int i = lane_id(); i < n; i += 64)
-        __hip_atomic_store(as_global(P.q_slots + base + i), q_slot_word(P, gld_i32(ids + i)), __ATOMIC_RELAXED, ETC_SCOPE);
+    return base;
 }
 
-// One lane takes the next ticket and waits for its slot: the task id, or -1 when the step is complete,
-// the queue is exhausted or an error was raised.
-__device__ __forceinline__ int q_pop(const Params &P)
+// All producers of event `ev` are dispatched: publishes the consumers whose other events are that far too.
+// Called by every lane of one wavefront, 64 table entries per round (one lane alone took 0.3 us per task:
+// a third of a 33 000-task step).
+__device__ __forceinline__ void q_push_consumers_wave(const Params &P, int ev)
 {
-    const int ticket = __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 0), 1, __ATOMIC_RELAXED, ETC_SCOPE);
+    const int c0 = __builtin_amdgcn_readfirstlane(gld_i32(P.ev_consumers + ev));
+    const int c1 = __builtin_amdgcn_readfirstlane(gld_i32(P.ev_consumers + ev + 1));
+    for (int i0 = c0; i0 < c1; i0 += 64) {
+        const int i = i0 + lane_id();
+        bool ready = false;
+        int id = 0;
+        if (i < c1) {
+            const int entry = gld_i32(P.consumer_ids + i);
+            id = entry & 0xFFFFFF;
+            const int n_waited = (entry >> 24) & 0x7F;
+            ready = true;
+            if (n_waited > 1) {      // the last of its events to get here pushes the task (the counter is never reset)
+                const int seen = __hip_atomic_fetch_add(as_global(P.task_pending + id), 1, __ATOMIC_RELAXED, ETC_SCOPE) + 1;
+                ready = seen % n_waited == 0;
+            }
+        }
+        const uint64_t mask = __ballot(ready);
+        const int cnt = __builtin_amdgcn_readfirstlane(__popcll(mask));
+        if (cnt == 0) continue;
+        const int base = q_reserve_wave(P, cnt);
+        if (base < 0) return;
+        if (ready) {
+            const int pos = __popcll(mask & ((1ull << lane_id()) - 1ull));
+            __hip_atomic_store(as_global(P.q_slots + base + pos), q_slot_word(P, id), __ATOMIC_RELAXED, ETC_SCOPE);
+        }
+    }
+}
+
+// Pop, in two halves so that the first can run a task ahead: q_take_ticket reserves the next ticket (one
+// lane), q_wait_slot waits for that slot to be published: the task id, or -1 when the step is complete
+// (every task has counted itself done), the queue is exhausted or an error was raised.  `first_look` is
+// the slot's content as read some time ago (0: not read).
+__device__ __forceinline__ int q_take_ticket(const Params &P)
+{
+    return __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 0), 1, __ATOMIC_RELAXED, ETC_SCOPE);
+}
+
+__device__ __forceinline__ int q_wait_slot(const Params &P, int ticket, uint64_t first_look)
+{
     if (ticket >= P.q_capacity) return -1;
-    int id = -1;
+    if ((uint32_t)(first_look >> 32) == P.epoch) return (int)(uint32_t)first_look - 1;
     long long spins = 0;
     for (;;) {
         const uint64_t v = ld_u64(P.q_slots + ticket);
-        if ((uint32_t)(v >> 32) == P.epoch) { id = (int)(uint32_t)v - 1; break; }
-        if (ev_peek(P.q_ctrl_cur + 2) != 0) break;
+        if ((uint32_t)(v >> 32) == P.epoch) return (int)(uint32_t)v - 1;
+        if (ev_peek(P.q_ctrl_cur + 3) >= P.n_static_tasks) return -1;
         if (spins < 32) __builtin_amdgcn_s_sleep(2); else __builtin_amdgcn_s_sleep(32);
         ++spins;
-        if ((spins & 63) == 0 && ev_peek(P.error_word) != 0) break;
-        if (spins > P.spin_budget) { raise_error(P, ERR_POP_TIMEOUT, 0, ticket); break; }
+        if ((spins & 63) == 0 && ev_peek(P.error_word) != 0) return -1;
+        if (spins > P.spin_budget) { raise_error(P, ERR_POP_TIMEOUT, 0, ticket); return -1; }
     }
-    return id;
 }
 
 // Loop shape.  The lane that notifies and pops shares a wavefront with 63 lanes that do not, and
@@ -471,57 +512,58 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
     __shared__ Params sP;
     stage_params(P, &sP);
     rearm_next(P);
+    for (int i = blockIdx.x * kWgThreads + threadIdx.x; i < P.n_events; i += gridDim.x * kWgThreads)
+        as_global(P.ev_disp_next)[i] = as_global(P.ev_init)[i];
     if (blockIdx.x == 0 && threadIdx.x == 0) {            // reset the control words of the next launch
         for (int i = 0; i < 8; ++i) P.q_ctrl_next[i] = 0;
     }
     // Wavefront 0 is the scheduler of its workgroup: its lane 0 notifies and pops, all its lanes push.
     const bool sched_wave = wave_id() == 0;
     if (sched_wave) {
-        // seed: tasks without a trigger edge, a share per workgroup
+        // seed: tasks that wait on nothing, a share per workgroup
         const int n_seed = P.n_seed > (int)blockIdx.x ? (P.n_seed - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x : 0;
         if (n_seed > 0) {
-            int base = 0;
-            if (lane_id() == 0) base = __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 1), n_seed, __ATOMIC_RELAXED, ETC_SCOPE);
-            base = __builtin_amdgcn_readfirstlane(base);
-            if (base + n_seed > P.q_capacity) {
-                if (lane_id() == 0) raise_error(P, ERR_QUEUE_OVERFLOW, 0, base);
-            } else {
+            const int base = q_reserve_wave(P, n_seed);
+            if (base >= 0)
                 for (int i = lane_id(); i < n_seed; i += 64)
                     __hip_atomic_store(as_global(P.q_slots + base + i),
                                        q_slot_word(P, gld_i32(P.seed_tasks + blockIdx.x + i * gridDim.x)), __ATOMIC_RELAXED,
                                        ETC_SCOPE);
-            }
         }
-        if (lane_id() == 0) s_task = q_pop(P);
+        if (lane_id() == 0) s_task = q_wait_slot(P, q_take_ticket(P), 0);
     }
     __syncthreads();
     int id = __builtin_amdgcn_readfirstlane(s_task);
+    int next_ticket = 0;               // scheduler lane: the ticket taken a task ahead, and a first look at its slot
+    uint64_t next_look = 0;
     while (id >= 0) {
-        Task t = load_task(P.dyn_tasks + id);
-        // The task was pushed because its trigger event fired, and the slot was published after that: nothing
-        // to wait for on that edge.  Per-wave waits (pushed on the last K slice's event) and a second in-edge
-        // are still waited on inside the task (early push, App. E).
-        if (!(t.flags & TF_WAIT0_PER_WAVE)) t.wait0 = -1;
+        const Task t = load_task(P.dyn_tasks + id);
+        if (sched_wave) {
+            // This task is dispatched: the last producer of its event to get here pushes the consumers.  The
+            // next ticket is taken in the same round trip, a task ahead, so that no atomic's latency sits
+            // between two tasks.
+            int last = 0;
+            if (lane_id() == 0) {
+                int left = 0;
+                if (t.notify0 >= 0)
+                    left = __hip_atomic_fetch_sub(as_global(P.ev_disp_cur + t.notify0), 1, __ATOMIC_RELAXED, ETC_SCOPE);
+                next_ticket = q_take_ticket(P);
+                last = left == 1;
+            }
+            if (__builtin_amdgcn_readfirstlane(last)) q_push_consumers_wave(P, t.notify0);
+            if (lane_id() == 0) next_look = next_ticket < P.q_capacity ? ld_u64(P.q_slots + next_ticket) : 0;
+        }
         WgState st;
         wg_state_init(st);
         run_task<true, KIND>(P, sP, t, sm, st);
         wg_release();                            // also: every lane has read s_task before it is written again
-        if (sched_wave) {
-            int fired = 0;
-            if (lane_id() == 0) {
-                if (P.debug_flags & 1u) atomicAdd(P.exec_count + t.id, 1);
-                if (t.notify0 >= 0) fired = ev_notify(P, t.notify0) == 1;
-            }
-            if (__builtin_amdgcn_readfirstlane(fired)) {      // this notify fired the event: push its consumers
-                const int c0 = gld_i32(P.ev_consumers + t.notify0), c1 = gld_i32(P.ev_consumers + t.notify0 + 1);
-                q_push_wave(P, P.consumer_ids + c0, c1 - c0);
-            }
-            if (lane_id() == 0) {
-                // termination: the workgroup that completes the last task of the step releases the idle poppers
-                const int n_done = __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 3), 1, __ATOMIC_RELAXED, ETC_SCOPE) + 1;
-                if (n_done == P.n_static_tasks + ev_peek(P.q_ctrl_cur + 4)) st_i32(P.q_ctrl_cur + 2, 1);
-                s_task = q_pop(P);
-            }
+        if (sched_wave && lane_id() == 0) {
+            // notify and count the task done without waiting for either atomic: whoever polls an empty queue
+            // compares the count with the number of tasks of the step
+            if (P.debug_flags & 1u) atomicAdd(P.exec_count + t.id, 1);
+            if (t.notify0 >= 0) ev_notify(P, t.notify0);
+            __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 3), 1, __ATOMIC_RELAXED, ETC_SCOPE);
+            s_task = q_wait_slot(P, next_ticket, next_look);
         }
         __syncthreads();
         id = __builtin_amdgcn_readfirstlane(s_task);

@@ -1,7 +1,8 @@
 """The dynamic scheduler's ready-queue protocol, emulated on the CPU with one thread per workgroup
 (tests/dyn_queue_emulation.cpp): exactly-once execution, drained counters and termination over several
-launches.  The device kernel itself is switched off (see the library's kDynamicEnabled), so this is the
-coverage the protocol has for now."""
+launches, including the early push (a task is pushed once the producers of all its events are dispatched)
+and a task that waits on two events.  The device kernel has its own GPU tests; this one checks the protocol
+where a mistake in it shows as a failed count or a time-out instead of a hung GPU."""
 import os
 import subprocess
 

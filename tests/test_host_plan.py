@@ -58,16 +58,33 @@ def run_static(plan, rng):
 
 
 def run_dynamic(plan, n_workers, rng):
-    """Central ready queue: push on zero, pop when idle; a popped task still waits for its other events."""
+    """Central ready queue with early push (App. E): a task is pushed when every producer of every event it
+    waits on has been dispatched (popped), and still waits for those events once a worker holds it."""
     ev = plan["ev_init"].astype(np.int64).copy()
+    disp = ev.copy()                                   # producers not yet dispatched, per event
     tasks = plan["tasks"]
     done = np.zeros(len(tasks), np.int64)
+    pending = np.zeros(len(tasks), np.int64)
+    pushed = np.zeros(len(tasks), np.int64)
     queue = list(plan["seed_tasks"])
+    pushed[queue] += 1
     workers = [None] * n_workers
     while True:
         for w in range(n_workers):
             if workers[w] is None and queue:
                 workers[w] = queue.pop(0)
+                n = int(tasks[workers[w]]["notify0"])
+                if n >= 0:                             # dispatched: the last producer of the event pushes
+                    disp[n] -= 1
+                    if disp[n] == 0:
+                        for entry in plan["consumer_ids"][plan["ev_consumers"][n]:plan["ev_consumers"][n + 1]].tolist():
+                            tid, n_waited = entry & 0xFFFFFF, (entry >> 24) & 0x7F
+                            if n_waited > 1:
+                                pending[tid] += 1
+                                if pending[tid] % n_waited:
+                                    continue
+                            queue.append(tid)
+                            pushed[tid] += 1
         busy = [w for w in range(n_workers) if workers[w] is not None]
         if not busy:
             break
@@ -77,11 +94,9 @@ def run_dynamic(plan, n_workers, rng):
         t = tasks[workers[w]]
         done[t["id"]] += 1
         workers[w] = None
-        n = int(t["notify0"])
-        if n >= 0:
-            ev[n] -= 1
-            if ev[n] == 0:
-                queue.extend(plan["consumer_ids"][plan["ev_consumers"][n]:plan["ev_consumers"][n + 1]].tolist())
+        if int(t["notify0"]) >= 0:
+            ev[int(t["notify0"])] -= 1
+    assert (pushed == 1).all() and (disp == 0).all()
     return ev, done
 
 
@@ -106,9 +121,15 @@ def test_dynamic_plan_runs_to_completion():
     for nw in (1, 3, 16):
         ev, done = run_dynamic(plan, nw, np.random.default_rng(nw))
         assert (ev == 0).all() and (done == 1).all()
-    # every task is either a seed or the consumer of exactly one event
-    ids = np.concatenate([plan["seed_tasks"], plan["consumer_ids"]])
-    assert sorted(ids.tolist()) == list(range(len(plan["tasks"])))
+    # every task is either a seed or listed under each event it waits on, the entry carrying how many those are
+    listed = np.zeros(len(plan["tasks"]), np.int64)
+    for entry in plan["consumer_ids"].tolist():
+        tid, n_waited = entry & 0xFFFFFF, (entry >> 24) & 0x7F
+        listed[tid] += 1
+        assert max(n_waited, 1) == len(set(_waits(plan["tasks"][tid])))
+    assert (listed[plan["seed_tasks"]] == 0).all()
+    for tid in range(len(listed)):
+        assert listed[tid] == len(set(_waits(plan["tasks"][tid]))) or (listed[tid] == 0 and tid in set(plan["seed_tasks"].tolist()))
 
 
 def test_event_counts_follow_the_graph():

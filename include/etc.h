@@ -68,7 +68,8 @@ typedef struct {
 
 typedef enum {
     ETC_SCHED_STATIC = 0,  /* per-CU task queues built on the host, notify / wait (Sec. 3.1, Alg. 1) */
-    ETC_SCHED_DYNAMIC = 1, /* on-GPU ready queue, push on zero / pop when idle (Sec. 3.2, Alg. 2) */
+    ETC_SCHED_DYNAMIC = 1, /* on-GPU ready queue, push / pop when idle (Sec. 3.2, Alg. 2); a task is pushed once the
+                              producers of all its events are dispatched and keeps its waits (early push, App. E) */
     ETC_SCHED_UNFUSED = 2  /* static queues, one coarse event per operator stage (Sec. 4.5 baseline) */
 } etc_sched_kind;
 
@@ -235,9 +236,10 @@ typedef struct {
     const etc_task_record *queue_tasks; /* static queues back to back */
     const int32_t *queue_begin;         /* [n_queues + 1] */
     const int32_t *ev_init;             /* [n_events] */
-    const int32_t *ev_consumers;        /* [n_events + 1] CSR into consumer_ids */
-    const int32_t *consumer_ids;
-    const int32_t *seed_tasks;          /* [n_seed] tasks ready at launch */
+    const int32_t *ev_consumers;        /* [n_events + 1] CSR into consumer_ids: the tasks that wait on the event */
+    const int32_t *consumer_ids;        /* bits 0..23 task id; bits 24..30: n when the task waits on n > 1 events
+                                           (it is then listed under each of them), else 0 */
+    const int32_t *seed_tasks;          /* [n_seed] tasks that wait on nothing: ready at launch */
     void *opaque;
 } etc_plan_view;
 

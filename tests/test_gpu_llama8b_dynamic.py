@@ -67,3 +67,37 @@ def test_llama8b_100_steps_of_changing_shape_without_recreate():
     print(f"llama8b dynamic shapes: {N_STEPS} steps, worst per-layer max|err|/rms = {worst:.3e}, "
           f"algorithmic bytes per step {min(bytes_moved) / 1e9:.1f}..{max(bytes_moved) / 1e9:.1f} GB")
     dec.close()
+
+
+def test_llama8b_changing_shapes_under_the_dynamic_scheduler():
+    """The same kind of step sequence (batch from {1, 4, 16, 64}, lengths U[128, 4096], one context each) under
+    the dynamic scheduler: every step drains its events, runs every task once and gives the same bits as the
+    static scheduler on the same step."""
+    import torch
+    import paper_2604_13327_amd as etc
+    s = synth.LLAMA3_8B
+    seed = 3031
+    n_pool = 64 * synth.pages_needed(MAX_LEN, s.page) + 16
+    model = GpuModel(s, seed, n_pool)
+    rng = np.random.default_rng(seed)
+    steps = [synth.draw_step(rng, s, [b], 128, MAX_LEN, n_pool) for b in (4, 1, 64, 16, 1, 64, 4, 16)]
+    outs = {}
+    for kind in (etc.SCHED_STATIC, etc.SCHED_DYNAMIC):
+        dec = etc.Decoder(s, kv_chunk_tokens=64, sampled_batches=[1, 4, 16, 64], max_kv_len=MAX_LEN + 1, kind=kind,
+                          debug_flags=etc.DEBUG_EXEC_COUNT, spin_budget=2000000)
+        model.bind(dec)
+        for i, step in enumerate(steps):
+            model.reset_pools()
+            dec.bind_step(step)
+            x = model.hidden(i, step.batch)
+            out = torch.empty_like(x)
+            dec.launch(x, out)
+            torch.cuda.synchronize()
+            assert (dec.error_word() == 0).all(), (kind, i, dec.error_word())
+            assert (dec.event_counters() == 0).all(), f"kind {kind} step {i}: an event counter did not drain"
+            assert (dec.exec_counts() == 1).all(), f"kind {kind} step {i}: a task did not run exactly once"
+            outs[(kind, i)] = bf16_to_f32_np(out)
+            print(f"kind {kind} step {i} (batch {step.batch}) done", flush=True)
+        dec.close()
+    for i in range(len(steps)):
+        np.testing.assert_array_equal(outs[(etc.SCHED_DYNAMIC, i)], outs[(etc.SCHED_STATIC, i)])

@@ -224,6 +224,53 @@ def test_watchdog_turns_a_stuck_wait_into_an_error():
     g.close()
 
 
+def test_dynamic_scheduler_is_independent_of_listing_order_and_times_out_on_a_cycle():
+    """The graph of the watchdog test (consumer launch listed ahead of its producers, one workgroup) is no
+    problem for the ready queue: tasks run when they are pushed, whatever the listing order.  Two launches
+    that wait for each other are never pushed; the idle popper then gives up after its (tiny) spin budget and
+    the launch ends with ETC_ETIMEOUT instead of hanging."""
+    import torch
+    etc = _etc()
+    from paper_2604_13327_amd import binding as b
+    rng = np.random.default_rng(5)
+    A = rng.integers(-8, 9, size=(64, 128)).astype(np.float32)
+    dA = torch.from_numpy(A).cuda()
+    dB = torch.full((64, 4), float("nan"), device="cuda")
+    dC = torch.full((64,), float("nan"), device="cuda")
+    g = etc.EventGraph(kind=1, spin_budget=SPIN, n_queues=1, debug_flags=etc.DEBUG_EXEC_COUNT)
+    n = g.dim(sym=0, mul=1, add=0)
+    ev = g.add_event([n])
+    g.add_call(b.FN_ROWSUM_FINAL, [n], in_edges=[g.edge(ev, [(b.MAP_DIM, 0, 1)])])
+    g.add_call(b.FN_ROWSUM_PARTIAL, [n, g.dim(add=4)], out_edges=[g.edge(ev, [(b.MAP_DIM, 0, 1)])])
+    for slot, t in enumerate((dA, dB, dC)):
+        g.bind_buffer(slot, t)
+    g.bind_shape([2])
+    for rep in range(2):
+        dC.fill_(float("nan"))
+        g.launch()
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(dC.cpu().numpy(), A.astype(np.float64).sum(1))
+        assert (g.event_counters() == 0).all() and (g.exec_counts() == rep + 1).all()
+    g.close()
+
+    g = etc.EventGraph(kind=1, spin_budget=2000, n_queues=2)
+    n = g.dim(sym=0, mul=1, add=0)
+    e1, e2 = g.add_event([g.dim(add=1)]), g.add_event([g.dim(add=1)])
+    g.add_call(b.FN_ROWSUM_FINAL, [n], in_edges=[g.edge(e1, [(b.MAP_CONST, 0, 0)])],
+               out_edges=[g.edge(e2, [(b.MAP_CONST, 0, 0)])])
+    g.add_call(b.FN_ROWSUM_PARTIAL, [n, g.dim(add=4)], in_edges=[g.edge(e2, [(b.MAP_CONST, 0, 0)])],
+               out_edges=[g.edge(e1, [(b.MAP_CONST, 0, 0)])])
+    for slot, t in enumerate((dA, dB, dC)):
+        g.bind_buffer(slot, t)
+    g.bind_shape([1])
+    g.launch()
+    torch.cuda.synchronize()                   # returns: the poppers gave up
+    with pytest.raises(etc.EtcError) as ei:
+        g.event_counters()
+    assert ei.value.status == -5
+    g.close()
+
+
 @pytest.mark.parametrize("batch", [17, 40, 64])
 def test_tiny_large_batches_take_the_chunked_path(batch):
     """Batches above 16 columns: operand walked in double-buffered LDS chunks, 2 and 4 MFMA column blocks,

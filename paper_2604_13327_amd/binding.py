@@ -204,6 +204,7 @@ class Decoder(_Ctx):
                  debug_flags: int = 0, spin_budget: int = 0, n_queues: int = 0, moe_tile_m: int = 16):
         super().__init__()
         self.shape = shape
+        self.kind = kind
         md, td = _model_desc(shape), TileDesc(kv_chunk_tokens, moe_tile_m)
         sd = _sched_desc(kind, sampled_batches, max_kv_len, debug_flags, spin_budget, n_queues)
         st = self._L.etc_create(C.byref(md), C.byref(td), C.byref(sd), C.byref(self._h))

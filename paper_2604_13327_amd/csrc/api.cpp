@@ -41,6 +41,10 @@ struct DevPlan {          // one instantiated plan (one sampled batch size), hos
     Task *d_queue_tasks = nullptr, *d_tasks = nullptr;
     int32_t *d_queue_begin = nullptr, *d_ev_init = nullptr, *d_ev_consumers = nullptr, *d_consumer_ids = nullptr,
             *d_seed = nullptr;
+    // MoE plans: per layer the flat ids of the event of row-tile slot 0 and of the combine event; static grid sizes
+    std::vector<int32_t> moe_layer_events;
+    int32_t *d_moe_layer_events = nullptr;
+    int moe_rmax = 0, moe_groups_gu = 0, moe_groups_down = 0;
 };
 
 template <class T>
@@ -129,6 +133,23 @@ etc_status upload_plan(etc_ctx *c, DevPlan &dp)
     HIP_TRY(c, dev_upload(&dp.d_ev_consumers, dp.host.ev_consumers, c->plan_owned));
     HIP_TRY(c, dev_upload(&dp.d_consumer_ids, dp.host.consumer_ids, c->plan_owned));
     HIP_TRY(c, dev_upload(&dp.d_seed, dp.host.seed_tasks, c->plan_owned));
+    // what the data-dependent MoE events need to know of the static grids (dynamic scheduler, Sec. 2.4)
+    int n_layers = 0;
+    for (const Task &t : dp.host.tasks) n_layers = std::max(n_layers, (int)t.layer + 1);
+    dp.moe_layer_events.assign((size_t)2 * n_layers, -1);
+    dp.moe_rmax = dp.moe_groups_gu = dp.moe_groups_down = 0;
+    for (const Task &t : dp.host.tasks) {
+        if (t.fn == FN_MOE_DOWN && t.c0 == 0) {
+            dp.moe_layer_events[2 * t.layer] = t.wait0;
+            dp.moe_layer_events[2 * t.layer + 1] = t.notify0;
+            if (t.layer == 0) dp.moe_groups_down++;
+        }
+        if (t.fn == FN_MOE_GATEUP && t.layer == 0) {
+            dp.moe_rmax = std::max(dp.moe_rmax, (int)t.c0 + 1);
+            if (t.c0 == 0) dp.moe_groups_gu++;
+        }
+    }
+    if (dp.moe_rmax > 0) HIP_TRY(c, dev_upload(&dp.d_moe_layer_events, dp.moe_layer_events, c->plan_owned));
     return ETC_OK;
 }
 
@@ -183,6 +204,7 @@ etc_status arm_events(etc_ctx *c)
                              hipMemcpyHostToDevice));
     }
     HIP_TRY(c, hipMemset(c->d_pending, 0, c->n_tasks_max * sizeof(int32_t)));
+    if (c->base.exp_event) HIP_TRY(c, hipMemset(c->base.exp_event, 0, (size_t)c->base.E * sizeof(int32_t)));
     HIP_TRY(c, hipMemset(c->d_qctrl + (c->parity ? 8 : 0), 0, 8 * sizeof(int32_t)));
     if (c->base.exec_count) HIP_TRY(c, hipMemset(c->base.exec_count, 0, dp.host.tasks.size() * sizeof(int32_t)));
     return ETC_OK;
@@ -206,6 +228,11 @@ void fill_launch_params(etc_ctx *c, Params &P)
     P.ev_disp_cur = c->d_disp + (c->parity ? N : 0);
     P.ev_disp_next = c->d_disp + (c->parity ? 0 : N);
     P.task_pending = c->d_pending;
+    P.moe_dd = (c->sched.kind == ETC_SCHED_DYNAMIC && dp.moe_rmax > 0) ? 1 : 0;
+    P.moe_layer_events = dp.d_moe_layer_events;
+    P.moe_rmax = dp.moe_rmax;
+    P.moe_groups_gu = dp.moe_groups_gu;
+    P.moe_groups_down = dp.moe_groups_down;
     P.seed_tasks = dp.d_seed;
     P.n_seed = (int)dp.host.seed_tasks.size();
     P.n_static_tasks = (int)dp.host.tasks.size();
@@ -388,7 +415,7 @@ etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc
         const size_t E = (size_t)m->n_experts, K = (size_t)m->top_k, NL = (size_t)m->n_layers;
         const size_t rows = MB * K, r_max = (size_t)moe_max_row_tiles(m->n_experts, m->top_k, s->max_batch, d.tile_m);
         okk = A(&P.router_logits, MB * E) && A(&P.topk_ids, rows) && A(&P.topk_w, rows) &&
-              A(&P.tok_indptr, E + 1) && A(&P.exp_indptr, E + 1) && A(&P.perm, rows) && A(&P.inv_perm, rows) &&
+              A(&P.tok_indptr, E + 1) && A(&P.exp_indptr, E + 1) && A(&P.exp_event, E) && A(&P.perm, rows) && A(&P.inv_perm, rows) &&
               A(&P.perm_tok, rows) && A(&P.tile_expert, r_max) && A(&P.tile_row0, r_max) && A(&P.tile_n, r_max) &&
               A(&P.eact_hi, rows * (size_t)m->moe_ffn) && A(&P.eact_lo, rows * (size_t)m->moe_ffn) && A(&P.ey, rows * H);
         if (okk && (s->debug_flags & ETC_DEBUG_ROUTING))

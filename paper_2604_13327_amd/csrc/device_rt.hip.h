@@ -158,6 +158,25 @@ __device__ __forceinline__ void trace_mark(const Params &P, int task_id, int slo
         as_global(P.trace)[(size_t)task_id * 8 + slot] = slot == 7 ? (uint64_t)blockIdx.x : (uint64_t)wall_clock64();
 }
 
+// ---- ready queue of the dynamic scheduler: what the kernel's loop and a triggering task share ----
+__device__ __forceinline__ uint64_t q_slot_word(const Params &P, int task_id)
+{
+    return ((uint64_t)P.epoch << 32) | (uint64_t)(uint32_t)(task_id + 1);
+}
+
+// Reserves `cnt` tickets (lane 0) and returns the first one to every lane, or -1 when the queue is full.
+__device__ __forceinline__ int q_reserve_wave(const Params &P, int cnt)
+{
+    int base = 0;
+    if (lane_id() == 0) base = __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 1), cnt, __ATOMIC_RELAXED, ETC_SCOPE);
+    base = __builtin_amdgcn_readfirstlane(base);
+    if (base + cnt > P.q_capacity) {
+        if (lane_id() == 0) raise_error(P, ERR_QUEUE_OVERFLOW, 0, base);
+        return -1;
+    }
+    return base;
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll

@@ -137,6 +137,11 @@ struct Params {
     int32_t *ev_disp_cur;              // per event: producers not yet dispatched (early push, App. E)
     int32_t *ev_disp_next;             //   re-armed from ev_init like the event tensors
     int32_t *task_pending;             // per task: waited events whose producers are all dispatched (counts up)
+    // MoE under the dynamic scheduler: data-dependent event update and task triggering (Sec. 2.4)
+    int32_t moe_dd;                    // 1: expert events armed at run time trigger the GroupGEMM-1 tiles
+    int32_t *exp_event;                // [E] expert event tensor E_exp of the layer in flight
+    const int32_t *moe_layer_events;   // [n_layers][2] flat ids: event of row-tile slot 0 (GroupGEMM-1 -> 2), combine event
+    int32_t moe_rmax, moe_groups_gu, moe_groups_down;   // row-tile slots of the static grids, tasks per slot
     const int32_t *seed_tasks;         // tasks with no trigger edge, pushed at start
     int32_t n_seed;
     int32_t n_static_tasks;

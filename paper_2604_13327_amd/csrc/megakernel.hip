@@ -328,7 +328,7 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
         if (MOE && t.c0 < P.B) {
             wg_wait_cached(P, st, w0, w1, t.fn);
             st.staged_key = -1;      // the routing scratch overlaps the staged operand
-            moe_route_and_group(PL, t.layer, t.c0, sm);
+            moe_route_and_group(PL, t.layer, t.c0, t.notify0, sm);
         }
         break;
     case FN_COMBINE:
@@ -421,24 +421,6 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_static(const Params P)
 // then spin exactly like a task of a static queue; the push itself is off the critical path.  No
 // deadlock: a task that spins has all its producers running on other workgroups (or spinning in turn on
 // tasks dispatched before them).
-__device__ __forceinline__ uint64_t q_slot_word(const Params &P, int task_id)
-{
-    return ((uint64_t)P.epoch << 32) | (uint64_t)(uint32_t)(task_id + 1);
-}
-
-// Reserves `cnt` tickets (lane 0) and returns the first one to every lane, or -1 when the queue is full.
-__device__ __forceinline__ int q_reserve_wave(const Params &P, int cnt)
-{
-    int base = 0;
-    if (lane_id() == 0) base = __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 1), cnt, __ATOMIC_RELAXED, ETC_SCOPE);
-    base = __builtin_amdgcn_readfirstlane(base);
-    if (base + cnt > P.q_capacity) {
-        if (lane_id() == 0) raise_error(P, ERR_QUEUE_OVERFLOW, 0, base);
-        return -1;
-    }
-    return base;
-}
-
 // All producers of event `ev` are dispatched: publishes the consumers whose other events are that far too.
 // Called by every lane of one wavefront, 64 table entries per round (one lane alone took 0.3 us per task:
 // a third of a 33 000-task step).
@@ -537,7 +519,12 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
     int next_ticket = 0;               // scheduler lane: the ticket taken a task ahead, and a first look at its slot
     uint64_t next_look = 0;
     while (id >= 0) {
-        const Task t = load_task(P.dyn_tasks + id);
+        Task t = load_task(P.dyn_tasks + id);
+        // MoE with data-dependent events (Sec. 2.4): the router tiles trigger the GroupGEMM-1 tiles of an expert
+        // themselves, when the expert's event fires, so those are not pushed when the router tiles are
+        // dispatched, and a triggered tile has nothing left to wait for.
+        const bool dd_producer = KIND == KIND_MOE && P.moe_dd && t.fn == FN_ROUTER;
+        if (KIND == KIND_MOE && P.moe_dd && t.fn == FN_MOE_GATEUP) t.wait0 = -1;
         if (sched_wave) {
             // This task is dispatched: the last producer of its event to get here pushes the consumers.  The
             // next ticket is taken in the same round trip, a task ahead, so that no atomic's latency sits
@@ -545,7 +532,7 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
             int last = 0;
             if (lane_id() == 0) {
                 int left = 0;
-                if (t.notify0 >= 0)
+                if (t.notify0 >= 0 && !dd_producer)
                     left = __hip_atomic_fetch_sub(as_global(P.ev_disp_cur + t.notify0), 1, __ATOMIC_RELAXED, ETC_SCOPE);
                 next_ticket = q_take_ticket(P);
                 last = left == 1;

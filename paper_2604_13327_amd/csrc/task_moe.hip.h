@@ -34,12 +34,94 @@ __device__ __forceinline__ int wave_sum_i(int v)
     return v;
 }
 
+// Data-dependent event update and task triggering (Sec. 2.4), dynamic scheduler only.  The expert event
+// tensor E_exp[e] is armed at run time with the number of tokens routed to e, plus one for tile 0, which
+// publishes the per-expert tables: every tile knows that count from its own copy of the routing, so nobody
+// has to write it first - a tile decrements, and the one that sees the count complete has fired the event
+// (it puts the counter back to zero for the next layer).  The grouping tile of token t updates the events of
+// topk[t, :]; when E_exp[e] fires, expert e releases its GroupGEMM-1 tiles, the row-tile slots
+// [exp_indptr[e], exp_indptr[e+1]) of the static grid: their tasks are published to the ready queue, all
+// fired experts of this tile under one reservation.  Slots beyond exp_indptr[E] are never released: tile 0
+// takes them out of the counts that were fixed before the routing was known (the events between the two
+// GroupGEMMs of those slots, the combine event, the number of tasks the step has to complete).
+__device__ __forceinline__ void moe_update_and_trigger(const Params &P, int layer, int t, int group_ev,
+                                                       const ETC_AS_LDS int32_t *ids_s, const ETC_AS_LDS int32_t *cnt,
+                                                       const ETC_AS_LDS int32_t *expp)
+{
+    drain_vmem();            // this tile's share of the grouping (and tile 0's tables) is written
+    __syncthreads();
+    if (wave_id() != 0) return;
+    const int lane = lane_id(), E = P.E, K = P.topk;
+    const int G = P.moe_groups_gu, Gd = P.moe_groups_down;
+    if (t == 0) {
+        const int live = expp[E], dead = P.moe_rmax - live;
+        const int ev_slot0 = gld_i32(P.moe_layer_events + 2 * layer), ev_y = gld_i32(P.moe_layer_events + 2 * layer + 1);
+        for (int r = live + lane; r < P.moe_rmax; r += 64) st_i32(P.ev_cur + ev_slot0 + r, 0);
+        if (lane == 0 && dead > 0) {
+            __hip_atomic_fetch_sub(as_global(P.ev_cur + ev_y), dead * Gd, __ATOMIC_RELAXED, ETC_SCOPE);
+            __hip_atomic_fetch_sub(as_global(P.ev_disp_cur + ev_y), dead * Gd, __ATOMIC_RELAXED, ETC_SCOPE);
+            __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 3), dead * (G + Gd), __ATOMIC_RELAXED, ETC_SCOPE);
+        }
+        drain_vmem();        // the counts are in place before this tile's notifies can release anything
+    }
+    const int c0 = __builtin_amdgcn_readfirstlane(gld_i32(P.ev_consumers + group_ev));
+    // Notify 0 of a lane: one pair of this token; notifies 1.. (tile 0 only): every routed expert, 64 per
+    // round.  All decrements of the tile are in flight together, and what they release goes to the ready
+    // queue under one reservation.
+    constexpr int NV = 1 + kMaxExperts / 64;
+    int ex[NV], first[NV], n_rel[NV];
+    bool fired[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        ex[v] = -1;
+        if (v == 0) {
+            if (lane < K) ex[v] = ids_s[t * K + lane];
+        } else if (t == 0) {
+            const int cand = (v - 1) * 64 + lane;
+            if (cand < E && cnt[cand] > 0) ex[v] = cand;
+        }
+    }
+    int before[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v)
+        before[v] = ex[v] >= 0 ? __hip_atomic_fetch_sub(as_global(P.exp_event + ex[v]), 1, __ATOMIC_RELAXED, ETC_SCOPE) : 0;
+    int n_mine = 0;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        fired[v] = ex[v] >= 0 && before[v] == -cnt[ex[v]];          // this was notify number cnt[e] + 1
+        if (fired[v]) st_i32(P.exp_event + ex[v], 0);
+        first[v] = fired[v] ? expp[ex[v]] * G : 0;
+        n_rel[v] = fired[v] ? (expp[ex[v] + 1] - expp[ex[v]]) * G : 0;
+        n_mine += n_rel[v];
+    }
+    const int total = wave_sum_i(n_mine);
+    if (total == 0) return;
+    const int base = q_reserve_wave(P, total);
+    if (base < 0) return;
+    int off = 0;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        uint64_t m = __ballot(fired[v]);
+        while (m) {                                        // one fired expert after the other, 64 slots at a time
+            const int src = __builtin_ctzll(m);
+            m &= m - 1;
+            const int s0 = __shfl(first[v], src, 64), n = __shfl(n_rel[v], src, 64);
+            for (int i = lane; i < n; i += 64)
+                __hip_atomic_store(as_global(P.q_slots + base + off + i),
+                                   q_slot_word(P, gld_i32(P.consumer_ids + c0 + s0 + i) & 0xFFFFFF), __ATOMIC_RELAXED, ETC_SCOPE);
+            off += n;
+        }
+    }
+}
+
 // Router tile of token t.  Every tile needs the ids of ALL tokens to rank its own pairs, so each
 // recomputes the (cheap) top-k of every token from the shared logits instead of waiting one more event
 // hop for them; it publishes only what belongs to token t.  Tile 0 also publishes the per-expert tables.
 // Order of the selection: larger logit first, equal logits -> lower expert index first.
 // Routing weights: softmax over the selected logits.
-__device__ __noinline__ void moe_route_and_group(const Params &P, int layer, int t, float *sm)
+// group_ev: the event the tile notifies; under the dynamic scheduler its consumer list (the GroupGEMM-1
+// tasks of the layer, row-tile slot major) is what the expert events trigger from.
+__device__ __noinline__ void moe_route_and_group(const Params &P, int layer, int t, int group_ev, float *sm)
 {
     const int wave = wave_id(), lane = lane_id();
     const int E = P.E, K = P.topk, B = P.B, N = B * K, M = P.tile_m;
@@ -153,6 +235,7 @@ __device__ __noinline__ void moe_route_and_group(const Params &P, int layer, int
             }
         }
     }
+    if (P.moe_dd) moe_update_and_trigger(P, layer, t, group_ev, ids_s, cnt, expp);
     __syncthreads();     // the routing scratch in LDS is free again
 }
 

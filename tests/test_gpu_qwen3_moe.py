@@ -7,7 +7,7 @@ import pytest
 
 import synth
 from harness import GpuModel, fixed_step
-from test_gpu_moe import check_moe_step, free_running_mismatches
+from test_gpu_moe import check_moe_step, expected_exec_counts, free_running_mismatches
 
 pytestmark = pytest.mark.gpu
 SPIN = 2000000
@@ -47,9 +47,10 @@ def test_qwen3_moe_all_batches_match_oracle(qwen_model):
 
 
 def test_qwen3_moe_dynamic_scheduler_agrees_bitwise_with_static(qwen_model):
-    """The dynamic scheduler (Alg. 2: ready queue, push on zero) runs the same task bodies, so a sampled
-    batch (8), an unsampled one (5) and a large one (64) give the same bits as the static queues; every task
-    runs once and every event ends at zero, also on the second launch (re-armed events and queue words)."""
+    """The dynamic scheduler (Alg. 2: ready queue, early push; expert events armed at run time release each
+    expert's GroupGEMM row tiles, Sec. 2.4) runs the same task bodies, so a sampled batch (8), an unsampled one
+    (5) and a large one (64) give the same bits as the static queues; every released task runs once, the
+    surplus row-tile slots not at all, and every event ends at zero, also on the second launch."""
     import paper_2604_13327_amd as etc
     from test_gpu_moe import _launch
     s, m = synth.QWEN3_30B_A3B, qwen_model
@@ -59,15 +60,16 @@ def test_qwen3_moe_dynamic_scheduler_agrees_bitwise_with_static(qwen_model):
     outs = {}
     for kind in (etc.SCHED_STATIC, etc.SCHED_DYNAMIC):
         dec = etc.Decoder(s, kv_chunk_tokens=64, sampled_batches=[8, 64], max_kv_len=MAX_LEN + 1, moe_tile_m=16,
-                          kind=kind, debug_flags=etc.DEBUG_EXEC_COUNT, spin_budget=SPIN)
+                          kind=kind, debug_flags=etc.DEBUG_EXEC_COUNT | etc.DEBUG_ROUTING, spin_budget=SPIN)
         m.bind(dec)
         for i, step in enumerate(steps):
             dec.bind_step(step)
             for rep in range(2):
                 m.reset_pools()
                 o = _launch(dec, m, step, step_index=i)
-                assert (dec.error_word() == 0).all()
-                assert (dec.event_counters() == 0).all() and (dec.exec_counts() == rep + 1).all()
+                assert (dec.error_word() == 0).all(), dec.error_word()
+                assert (dec.event_counters() == 0).all()
+                np.testing.assert_array_equal(dec.exec_counts(), expected_exec_counts(dec, s, 64, MAX_LEN + 1, 16, rep + 1))
                 outs.setdefault((kind, i), []).append(o)
             print(f"qwen3-moe kind {kind} B={step.batch}: done", flush=True)
         dec.close()

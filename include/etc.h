@@ -69,7 +69,9 @@ typedef struct {
 typedef enum {
     ETC_SCHED_STATIC = 0,  /* per-CU task queues built on the host, notify / wait (Sec. 3.1, Alg. 1) */
     ETC_SCHED_DYNAMIC = 1, /* on-GPU ready queue, push / pop when idle (Sec. 3.2, Alg. 2); a task is pushed once the
-                              producers of all its events are dispatched and keeps its waits (early push, App. E) */
+                              producers of all its events are dispatched and keeps its waits (early push, App. E);
+                              MoE models: expert events armed at run time release each expert's GroupGEMM row
+                              tiles, surplus row-tile slots never run (Sec. 2.4) */
     ETC_SCHED_UNFUSED = 2  /* static queues, one coarse event per operator stage (Sec. 4.5 baseline) */
 } etc_sched_kind;
 

@@ -225,6 +225,110 @@ def test_moe_dynamic_plan_runs_to_completion():
     assert (ev == 0).all() and (done == 1).all()
 
 
+def run_dynamic_moe(plan, n_workers, rng, s, batch, tile_m):
+    """run_dynamic plus the data-dependent part of the MoE step under the dynamic scheduler (Sec. 2.4), on a
+    random routing per layer: the expert event E_exp[e] counts the tokens routed to e plus one for tile 0
+    (which publishes the tables); a router tile updates the events of its token's experts when it completes;
+    a fired expert releases the GroupGEMM-1 tasks of its row-tile slots [exp_indptr[e], exp_indptr[e+1]) from
+    the consumer list of the router tiles' event; tile 0 takes the surplus slots out of the counts fixed
+    before the routing was known.  Router tiles do not count as dispatched producers (nothing is pushed early
+    from their event) and a released GroupGEMM-1 task waits for nothing."""
+    E, K = s.n_experts, s.top_k
+    tasks = plan["tasks"]
+    ev = plan["ev_init"].astype(np.int64).copy()
+    disp = ev.copy()
+    done = np.zeros(len(tasks), np.int64)
+    pending = np.zeros(len(tasks), np.int64)
+    pushed = np.zeros(len(tasks), np.int64)
+    l0 = tasks[tasks["layer"] == 0]
+    r_max = int(l0[l0["fn"] == FN_MOE_GATEUP]["c0"].max()) + 1
+    G = int(((l0["fn"] == FN_MOE_GATEUP) & (l0["c0"] == 0)).sum())
+    Gd = int(((l0["fn"] == FN_MOE_DOWN) & (l0["c0"] == 0)).sum())
+    routing = {}
+    for layer in range(s.n_layers):
+        ids = np.stack([rng.choice(E, size=K, replace=False) for _ in range(batch)])
+        cnt = np.bincount(ids.ravel(), minlength=E)
+        expp = np.concatenate([[0], np.cumsum(-(-cnt // tile_m))])
+        down0 = tasks[(tasks["layer"] == layer) & (tasks["fn"] == FN_MOE_DOWN) & (tasks["c0"] == 0)][0]
+        routing[layer] = dict(ids=ids, cnt=cnt, expp=expp, exp_ev=np.zeros(E, np.int64),
+                              ev_slot0=int(down0["wait0"]), ev_y=int(down0["notify0"]))
+    credit = 0
+    expect = np.ones(len(tasks), np.int64)
+    for t in tasks:
+        if t["fn"] in (FN_MOE_GATEUP, FN_MOE_DOWN) and t["c0"] >= routing[int(t["layer"])]["expp"][-1]:
+            expect[t["id"]] = 0
+    queue = list(plan["seed_tasks"])
+    pushed[queue] += 1
+    workers = [None] * n_workers
+
+    def push_consumers(n):
+        for entry in plan["consumer_ids"][plan["ev_consumers"][n]:plan["ev_consumers"][n + 1]].tolist():
+            tid, n_waited = entry & 0xFFFFFF, (entry >> 24) & 0x7F
+            if n_waited > 1:
+                pending[tid] += 1
+                if pending[tid] % n_waited:
+                    continue
+            queue.append(tid)
+            pushed[tid] += 1
+
+    while True:
+        for w in range(n_workers):
+            if workers[w] is None and queue:
+                workers[w] = queue.pop(0)
+                t = tasks[workers[w]]
+                n = int(t["notify0"])
+                if n >= 0 and t["fn"] != FN_ROUTER:
+                    disp[n] -= 1
+                    if disp[n] == 0:
+                        push_consumers(n)
+        busy = [w for w in range(n_workers) if workers[w] is not None]
+        if not busy:
+            break
+
+        def waits_of(t):
+            return [] if t["fn"] == FN_MOE_GATEUP else list(_waits(t))
+        runnable = [w for w in busy if all(ev[e] == 0 for e in waits_of(tasks[workers[w]]))]
+        assert runnable, "deadlock in the dynamic protocol"
+        w = int(rng.choice(runnable))
+        t = tasks[workers[w]]
+        done[t["id"]] += 1
+        workers[w] = None
+        if t["fn"] == FN_ROUTER and t["c0"] < batch:
+            r, tok = routing[int(t["layer"])], int(t["c0"])
+            notifies = [int(e) for e in r["ids"][tok]]
+            if tok == 0:
+                live = int(r["expp"][-1])
+                dead = r_max - live
+                ev[r["ev_slot0"] + live: r["ev_slot0"] + r_max] = 0
+                ev[r["ev_y"]] -= dead * Gd
+                disp[r["ev_y"]] -= dead * Gd
+                credit += dead * (G + Gd)
+                notifies += [e for e in range(E) if r["cnt"][e] > 0]
+            c0 = int(plan["ev_consumers"][int(t["notify0"])])
+            for e in notifies:
+                before = r["exp_ev"][e]
+                r["exp_ev"][e] -= 1
+                if before == -r["cnt"][e]:
+                    r["exp_ev"][e] = 0
+                    for entry in plan["consumer_ids"][c0 + r["expp"][e] * G: c0 + r["expp"][e + 1] * G].tolist():
+                        queue.append(entry & 0xFFFFFF)
+                        pushed[entry & 0xFFFFFF] += 1
+        if int(t["notify0"]) >= 0:
+            ev[int(t["notify0"])] -= 1
+    assert (pushed == expect).all() and (done == expect).all()
+    assert int(done.sum()) + credit == len(tasks)             # what the kernel's termination test compares
+    assert all((r["exp_ev"] == 0).all() for r in routing.values())
+    return ev
+
+
+@pytest.mark.parametrize("batch,sampled,tile_m,workers", [(1, 1, 16, 3), (2, 2, 2, 5), (3, 4, 1, 16), (8, 8, 2, 2)])
+def test_moe_dynamic_plan_with_data_dependent_triggers(batch, sampled, tile_m, workers):
+    plan = etc.plan_build(synth.TINY_MOE, 32, sampled, 4, max_kv_len=129, kind=etc.SCHED_DYNAMIC, moe_tile_m=tile_m)
+    for seed in range(3):
+        ev = run_dynamic_moe(plan, workers, np.random.default_rng(seed), synth.TINY_MOE, batch, tile_m)
+        assert (ev == 0).all()
+
+
 def test_moe_event_counts_and_row_tile_slots():
     s = synth.TINY_MOE                   # E 16, top-2, moe_F 256, H 256
     B, M = 5, 2

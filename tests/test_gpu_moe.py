@@ -64,7 +64,8 @@ def expected_exec_counts(dec, s, kv_chunk, max_kv_len, tile_m, launches=1):
     return want
 
 
-def check_moe_step(dec, model, s, step, tile_m, step_index=0, forced=None, layers=None, first_layer=0):
+def check_moe_step(dec, model, s, step, tile_m, step_index=0, forced=None, layers=None, first_layer=0,
+                   kv_chunk=32, max_kv_len=129):
     """One launch, then every check of the module docstring.  Returns the worst per-layer error."""
     import oracle
     B = step.batch
@@ -72,7 +73,9 @@ def check_moe_step(dec, model, s, step, tile_m, step_index=0, forced=None, layer
     out = _launch(dec, model, step, step_index)
     assert (dec.error_word() == 0).all(), dec.error_word()
     assert (dec.event_counters() == 0).all(), "an event counter did not drain to zero"
-    assert (dec.exec_counts() == 1).all(), "a task did not run exactly once"
+    np.testing.assert_array_equal(dec.exec_counts(), expected_exec_counts(dec, s, kv_chunk, max_kv_len, tile_m),
+                                  err_msg="a task did not run exactly once (surplus row-tile slots under the "
+                                          "dynamic scheduler: not at all)")
     routes = [_routing(dec, s, B, l) for l in range(n_layers)]
     for l, r in enumerate(routes):
         # integers on identical inputs
@@ -148,7 +151,8 @@ def test_tiny_moe_matches_oracle(tiny_moe_model, batch, tile_m):
     dec.close()
 
 
-def test_tiny_moe_forced_routing_and_skewed_load(tiny_moe_model):
+@pytest.mark.parametrize("kind", [0, 1])          # static queues; ready queue with run-time armed expert events
+def test_tiny_moe_forced_routing_and_skewed_load(tiny_moe_model, kind):
     """etc_force_routing: every token to the same two experts (one long expert range spanning several row
     tiles, fourteen empty experts), then a token that names one expert twice."""
     etc = _etc()
@@ -156,7 +160,7 @@ def test_tiny_moe_forced_routing_and_skewed_load(tiny_moe_model):
     B, tile_m = 6, 4
     m.reset_pools()
     step = fixed_step(s, B, [5, 17, 0, 33, 64, 9], m.n_pool_pages, seed=4)
-    dec = etc.Decoder(s, kv_chunk_tokens=32, sampled_batches=[8], max_kv_len=129, moe_tile_m=tile_m,
+    dec = etc.Decoder(s, kv_chunk_tokens=32, sampled_batches=[8], max_kv_len=129, moe_tile_m=tile_m, kind=kind,
                       debug_flags=etc.DEBUG_EXEC_COUNT | etc.DEBUG_LAYER_HIDDEN | etc.DEBUG_ROUTING, spin_budget=SPIN)
     m.bind(dec)
     dec.bind_step(step)
@@ -201,12 +205,14 @@ def test_tiny_moe_schedulers_and_kernel_by_kernel_agree_bitwise(tiny_moe_model):
         np.testing.assert_array_equal(o, outs[0])
 
 
-def test_tiny_moe_smaller_batch_reuses_the_sampled_queue(tiny_moe_model):
+@pytest.mark.parametrize("kind", [0, 1])
+def test_tiny_moe_smaller_batch_reuses_the_sampled_queue(tiny_moe_model, kind):
     """A batch below the sampled size runs on the larger queue: surplus router, row-tile and combine
-    slots are no-ops that still notify (Sec. 3.1), and nothing is re-created between the steps."""
+    slots are no-ops that still notify (Sec. 3.1; under the dynamic scheduler the surplus row-tile slots are
+    never released instead), and nothing is re-created between the steps."""
     etc = _etc()
     s, m = synth.TINY_MOE, tiny_moe_model
-    dec = etc.Decoder(s, kv_chunk_tokens=32, sampled_batches=[8], max_kv_len=129, moe_tile_m=2,
+    dec = etc.Decoder(s, kv_chunk_tokens=32, sampled_batches=[8], max_kv_len=129, moe_tile_m=2, kind=kind,
                       debug_flags=etc.DEBUG_EXEC_COUNT | etc.DEBUG_LAYER_HIDDEN | etc.DEBUG_ROUTING, spin_budget=SPIN)
     m.bind(dec)
     for i, B in enumerate((8, 3, 1, 6)):

@@ -35,7 +35,7 @@ def test_qwen3_moe_all_batches_match_oracle(qwen_model):
         dec.bind_step(step)
         info = dec.step_info()
         assert info.sampled_batch == {1: 1, 8: 8, 5: 8, 32: 32, 64: 64}[B]
-        worst, routes, _ = check_moe_step(dec, m, s, step, 16, step_index=i)
+        worst, routes, _ = check_moe_step(dec, m, s, step, 16, step_index=i, kv_chunk=64, max_kv_len=MAX_LEN + 1)
         distinct = [len(np.unique(r["ids"])) for r in routes]
         print(f"qwen3-moe B={B}: tasks {info.n_tasks}, worst per-layer max|err|/rms = {worst:.3e}, "
               f"distinct experts per layer {min(distinct)}..{max(distinct)}", flush=True)

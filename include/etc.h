@@ -190,8 +190,22 @@ typedef struct {
 } etc_dim_expr;
 
 typedef enum {
-    ETC_MAP_DIM = 0,  /* event coord = task coord[src] / div */
-    ETC_MAP_CONST = 1 /* event coord = div (a constant; "E[0]" style coarse event) */
+    ETC_MAP_DIM = 0,      /* event coord = task coord[src] / div */
+    ETC_MAP_CONST = 1,    /* event coord = div (a constant; "E[0]" style coarse event) */
+    /* Data-dependent edges (Sec. 2.4) on a rank-1 event tensor, through int32 device tensors bound like buffers
+     * and read at run time.  At most one such out-edge and one such in-edge per graph.
+     * INDIRECT, out-edges only: task (i, ...) notifies event table[i] (slot 3, one entry per value of the first
+     *   task coordinate).  How many notifies event e receives is not known before the launch: count[e] (slot 5)
+     *   comes with the table, and the event fires on notify number count[e] ("initialised at run time").
+     * INDPTR, in-edges of a rank-1 grid only: task j belongs to the event e with indptr[e] <= j < indptr[e+1]
+     *   (slot 4, events + 1 entries, non-decreasing from 0); tasks from indptr[events] on belong to none and do
+     *   nothing.  Event e releases exactly that range.
+     * Dynamic scheduler: as written: a fired event pushes its range to the ready queue, tasks beyond the last
+     * range never run.  Static and unfused schedulers: both edges collapse to event 0 of the tensor, fed by every
+     * producer (the static rule of Sec. 3.1).  A table entry outside its range ends the launch with ETC_ETIMEOUT
+     * (the error text names it); nothing is written through it. */
+    ETC_MAP_INDIRECT = 2,
+    ETC_MAP_INDPTR = 3
 } etc_map_kind;
 
 typedef struct {
@@ -204,7 +218,9 @@ typedef struct {
 
 typedef enum {
     ETC_FN_ROWSUM_PARTIAL = 1, /* task (i, j): B[32i..32i+32, j] = sum_k A[rows, 32j..32j+32) */
-    ETC_FN_ROWSUM_FINAL = 2    /* task (i):    C[32i..32i+32]    = sum_j B[rows, j], j < 4 */
+    ETC_FN_ROWSUM_FINAL = 2,   /* task (i):    C[32i..32i+32]    = sum_j B[rows, j], j < 4 */
+    ETC_FN_ROWSUM_FINAL_PERM = 3 /* task (t): the same for row block perm[t] (slot 6), t < indptr[events]; for grids
+                                    released through ETC_MAP_INDPTR (row blocks grouped by their event) */
 } etc_device_fn;
 
 etc_status etc_graph_create(const etc_sched_desc *sched, etc_ctx **out);
@@ -212,6 +228,7 @@ etc_status etc_graph_add_event(etc_ctx *ctx, const etc_dim_expr *shape, int32_t 
 etc_status etc_graph_add_call(etc_ctx *ctx, int32_t device_fn, const etc_dim_expr *task_shape, int32_t rank,
                               const etc_edge *in_edges, int32_t n_in, const etc_edge *out_edges, int32_t n_out);
 /* Buffers of the device functions: slot 0 = A (fp32 [n*32, 128]), 1 = B (fp32 [n*32, 4]), 2 = C (fp32 [n*32]);
+ * run-time tables (int32): 3 = table of an INDIRECT edge, 4 = indptr, 5 = count, 6 = perm.
  * bytes = size of the allocation, checked against the bound shape at launch. */
 etc_status etc_graph_bind_buffer(etc_ctx *ctx, int32_t slot, void *device_ptr, size_t bytes);
 /* Instantiates the template for concrete symbol values (values[4], host). */

@@ -17,8 +17,8 @@ SCHED_STATIC, SCHED_DYNAMIC, SCHED_UNFUSED = 0, 1, 2
 DEBUG_EXEC_COUNT, DEBUG_LAYER_HIDDEN, DEBUG_ROUTING, DEBUG_TRACE = 1, 2, 4, 8
 (DBG_ERROR_WORD, DBG_EVENT_COUNTERS, DBG_TASK_EXEC_COUNT, DBG_LAYER_HIDDEN, DBG_ROUTER_LOGITS, DBG_TOPK_IDS,
  DBG_TOPK_W, DBG_PERMUTATION, DBG_TOK_INDPTR, DBG_EXP_INDPTR, DBG_TASK_TRACE) = range(11)
-FN_ROWSUM_PARTIAL, FN_ROWSUM_FINAL = 1, 2
-MAP_DIM, MAP_CONST = 0, 1
+FN_ROWSUM_PARTIAL, FN_ROWSUM_FINAL, FN_ROWSUM_FINAL_PERM = 1, 2, 3
+MAP_DIM, MAP_CONST, MAP_INDIRECT, MAP_INDPTR = 0, 1, 2, 3
 
 EXPORTS = ["etc_create", "etc_destroy", "etc_last_error", "etc_bind_layer_weights", "etc_bind_kv_pool",
            "etc_bind_step", "etc_force_routing", "etc_launch", "etc_launch_kernel_by_kernel", "etc_read_debug",

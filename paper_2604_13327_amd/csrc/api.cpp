@@ -81,7 +81,7 @@ struct etc_ctx {
     int cur_plan = -1;
     std::vector<void *> owned;              // device allocations that live as long as the context
     std::vector<void *> plan_owned;         // plans, event tensors, ready queue (rebuilt by etc_graph_bind_shape)
-    size_t gbuf_bytes[4] = {0, 0, 0, 0};
+    size_t gbuf_bytes[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     std::vector<LayerWeights> h_weights;
     std::vector<uint8_t> weights_bound;
     LayerWeights *d_weights = nullptr;
@@ -233,6 +233,11 @@ void fill_launch_params(etc_ctx *c, Params &P)
     P.moe_rmax = dp.moe_rmax;
     P.moe_groups_gu = dp.moe_groups_gu;
     P.moe_groups_down = dp.moe_groups_down;
+    P.dd_event_base = dp.host.dd_event_base;
+    P.dd_n_events = dp.host.dd_n_events;
+    P.dd_consumer_first = dp.host.dd_consumer_first;
+    P.dd_consumer_n = dp.host.dd_consumer_n;
+    P.dd_table_len = dp.host.dd_table_len;
     P.seed_tasks = dp.d_seed;
     P.n_seed = (int)dp.host.seed_tasks.size();
     P.n_static_tasks = (int)dp.host.tasks.size();
@@ -709,18 +714,28 @@ etc_status etc_graph_add_call(etc_ctx *c, int32_t fn, const etc_dim_expr *shape,
                               int32_t n_in, const etc_edge *outs, int32_t n_out)
 {
     if (!c || !c->is_graph || !shape || rank < 1 || rank > 3) return fail(c, ETC_EINVAL, "bad argument");
-    if (fn != ETC_FN_ROWSUM_PARTIAL && fn != ETC_FN_ROWSUM_FINAL) return fail(c, ETC_EINVAL, "unknown device function");
+    if (fn != ETC_FN_ROWSUM_PARTIAL && fn != ETC_FN_ROWSUM_FINAL && fn != ETC_FN_ROWSUM_FINAL_PERM)
+        return fail(c, ETC_EINVAL, "unknown device function");
     if (n_in < 0 || n_in > 2 || n_out < 0 || n_out > 1 || (n_in && !in) || (n_out && !outs))
         return fail(c, ETC_EINVAL, "a call takes at most 2 in-edges and 1 out-edge");
     CallDecl cd;
-    cd.fn = fn == ETC_FN_ROWSUM_PARTIAL ? FN_ROWSUM_PARTIAL : FN_ROWSUM_FINAL;
+    cd.fn = fn == ETC_FN_ROWSUM_PARTIAL ? FN_ROWSUM_PARTIAL : fn == ETC_FN_ROWSUM_FINAL ? FN_ROWSUM_FINAL : FN_ROWSUM_FINAL_PERM;
     cd.rank = rank;
     cd.stage = (int)c->graph.calls.size();
     for (int r = 0; r < rank; ++r) cd.shape[r] = DimExpr{shape[r].sym, shape[r].mul, shape[r].add};
-    auto conv = [&](const etc_edge &e, EdgeMap *m) -> bool {
+    auto conv = [&](const etc_edge &e, EdgeMap *m, bool is_out) -> bool {
         if (e.event < 0 || e.event >= (int)c->graph.events.size() || e.rank != c->graph.events[e.event].rank) return false;
         m->event = e.event;
         m->rank = e.rank;
+        if (e.kind[0] == ETC_MAP_INDIRECT || e.kind[0] == ETC_MAP_INDPTR) {
+            // run-time maps: rank-1 event tensor, indexed through the first task coordinate; a table on out-edges,
+            // ranges on the in-edges of a rank-1 grid
+            if (e.rank != 1 || (e.kind[0] == ETC_MAP_INDIRECT) != is_out || (!is_out && rank != 1)) return false;
+            m->kind[0] = e.kind[0] == ETC_MAP_INDIRECT ? MAP_INDIRECT : MAP_INDPTR;
+            m->src[0] = 0;
+            m->div[0] = 1;
+            return true;
+        }
         for (int r = 0; r < e.rank; ++r) {
             if (e.kind[r] != ETC_MAP_DIM && e.kind[r] != ETC_MAP_CONST) return false;
             if (e.kind[r] == ETC_MAP_DIM && (e.src[r] < 0 || e.src[r] >= rank || e.div[r] < 1)) return false;
@@ -730,15 +745,15 @@ etc_status etc_graph_add_call(etc_ctx *c, int32_t fn, const etc_dim_expr *shape,
         }
         return true;
     };
-    for (int i = 0; i < n_in; ++i) { EdgeMap m; if (!conv(in[i], &m)) return fail(c, ETC_EINVAL, "malformed in-edge"); cd.in.push_back(m); }
-    for (int i = 0; i < n_out; ++i) { EdgeMap m; if (!conv(outs[i], &m)) return fail(c, ETC_EINVAL, "malformed out-edge"); cd.out.push_back(m); }
+    for (int i = 0; i < n_in; ++i) { EdgeMap m; if (!conv(in[i], &m, false)) return fail(c, ETC_EINVAL, "malformed in-edge"); cd.in.push_back(m); }
+    for (int i = 0; i < n_out; ++i) { EdgeMap m; if (!conv(outs[i], &m, true)) return fail(c, ETC_EINVAL, "malformed out-edge"); cd.out.push_back(m); }
     c->graph.calls.push_back(cd);
     return ETC_OK;
 }
 
 etc_status etc_graph_bind_buffer(etc_ctx *c, int32_t slot, void *ptr, size_t bytes)
 {
-    if (!c || !c->is_graph || slot < 0 || slot > 3 || !ptr) return fail(c, ETC_EINVAL, "bad argument");
+    if (!c || !c->is_graph || slot < 0 || slot > 6 || !ptr) return fail(c, ETC_EINVAL, "bad argument");
     c->base.gbuf[slot] = (float *)ptr;
     c->gbuf_bytes[slot] = bytes;
     return ETC_OK;
@@ -753,7 +768,8 @@ etc_status etc_graph_bind_shape(etc_ctx *c, const int32_t *values)
     // instantiate the template for these symbol values: no kernel is rebuilt, only queues and counts
     DevPlan dp;
     int syms[4] = {values[0], values[1], values[2], values[3]};
-    std::string err = instantiate(c->graph, syms, c->n_queues, c->sched.kind == ETC_SCHED_UNFUSED, &dp.host);
+    std::string err = instantiate(c->graph, syms, c->n_queues, c->sched.kind == ETC_SCHED_UNFUSED, &dp.host,
+                                  c->sched.kind == ETC_SCHED_DYNAMIC);
     if (!err.empty()) return fail(c, ETC_EINVAL, err);
     for (void *p : c->plan_owned) (void)hipFree(p);
     c->plan_owned.clear();
@@ -778,22 +794,37 @@ etc_status etc_graph_launch(etc_ctx *c, void *hip_stream)
 {
     if (!c || !c->is_graph) return fail(c, ETC_EINVAL, "not a graph context");
     if (!c->step_bound) return fail(c, ETC_ESTATE, "bind a shape first");
-    bool need[3] = {false, false, false};
+    bool need[7] = {false, false, false, false, false, false, false};
     for (const CallDecl &cd : c->graph.calls) {
         if (cd.fn == FN_ROWSUM_PARTIAL) need[0] = need[1] = true;
         if (cd.fn == FN_ROWSUM_FINAL) need[1] = need[2] = true;
+        if (cd.fn == FN_ROWSUM_FINAL_PERM) need[1] = need[2] = need[4] = need[6] = true;
+        if (!cd.out.empty() && cd.out[0].kind[0] == MAP_INDIRECT) need[3] = need[4] = need[5] = true;
+        for (const EdgeMap &m : cd.in)
+            if (m.kind[0] == MAP_INDPTR) need[4] = true;
     }
-    for (int i = 0; i < 3; ++i)
-        if (need[i] && !c->base.gbuf[i]) return fail(c, ETC_ESTATE, "a device-function buffer is not bound");
+    for (int i = 0; i < 7; ++i)
+        if (need[i] && !c->base.gbuf[i]) return fail(c, ETC_ESTATE, "a device-function buffer or run-time table is not bound");
     // the task grids must stay inside the bound buffers: A (rows, 128), B (rows, 4), C (rows), 32 rows per task
     for (const CallDecl &cd : c->graph.calls) {
         const size_t rows = (size_t)32 * (size_t)cd.shape[0].eval(c->sym_values);
         if (cd.fn == FN_ROWSUM_PARTIAL) {
             if (cd.rank != 2 || cd.shape[1].eval(c->sym_values) > 4) return fail(c, ETC_EINVAL, "partial_sum takes a (n, <=4) grid");
             if (rows * 128 * 4 > c->gbuf_bytes[0] || rows * 4 * 4 > c->gbuf_bytes[1]) return fail(c, ETC_EINVAL, "buffer A or B too small for the bound shape");
-        } else {
+        } else if (cd.fn == FN_ROWSUM_FINAL) {
             if (cd.rank != 1) return fail(c, ETC_EINVAL, "final_sum takes a (n) grid");
             if (rows * 4 * 4 > c->gbuf_bytes[1] || rows * 4 > c->gbuf_bytes[2]) return fail(c, ETC_EINVAL, "buffer B or C too small for the bound shape");
+        } else {      // one perm entry per task; the row blocks it may name are those of the indirectly notifying call
+            const size_t blocks = (size_t)c->plans[c->cur_plan].host.dd_table_len;
+            if (cd.rank != 1 || blocks == 0) return fail(c, ETC_EINVAL, "final_sum_perm takes a (n) grid released through an INDPTR edge");
+            if (rows / 32 * 4 > c->gbuf_bytes[6]) return fail(c, ETC_EINVAL, "perm too small for the bound shape");
+            if (blocks * 32 * 4 * 4 > c->gbuf_bytes[1] || blocks * 32 * 4 > c->gbuf_bytes[2]) return fail(c, ETC_EINVAL, "buffer B or C too small for the bound shape");
+        }
+        const size_t grid0 = (size_t)cd.shape[0].eval(c->sym_values);
+        if (!cd.out.empty() && cd.out[0].kind[0] == MAP_INDIRECT) {       // table [grid dim 0], count [events], indptr [events + 1]
+            const size_t n_ev = (size_t)c->graph.events[cd.out[0].event].shape[0].eval(c->sym_values);
+            if (grid0 * 4 > c->gbuf_bytes[3] || n_ev * 4 > c->gbuf_bytes[5] || (n_ev + 1) * 4 > c->gbuf_bytes[4])
+                return fail(c, ETC_EINVAL, "a run-time table is too small for the bound shape");
         }
     }
     Params P;

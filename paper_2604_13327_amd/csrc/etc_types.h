@@ -28,6 +28,7 @@ enum Fn : uint8_t {
     FN_NOP = 0,
     FN_ROWSUM_PARTIAL = 1,
     FN_ROWSUM_FINAL = 2,
+    FN_ROWSUM_FINAL_PERM = 17,   // generic graphs: final sum of row block perm[task], tasks beyond indptr[last] do nothing
     FN_LOAD_HIDDEN = 3,   // hidden_in bf16 -> residual stream fp32
     FN_QKV = 4,           // RMSNorm prologue, 16 rows of Wq|Wk|Wv (8 RoPE pairs), RoPE, KV append
     FN_ATTN = 5,          // split-KV partial attention of (sequence, kv head, chunk)
@@ -51,6 +52,8 @@ enum : uint16_t {
     TF_LAST_LAYER = 2,       // also write hidden_out
     TF_DYN_ROWTILE = 4,      // c0 is a GroupGEMM row-tile id resolved through exp_indptr at run time
     TF_K_SLICE = 8,          // projection task over one slice of K: c1 = slice, c2 = row tiles; writes fp32 partials
+    TF_NOTIFY_INDIRECT = 16, // dynamic scheduler: notifies event notify0 + table[c0] (data-dependent update, Sec. 2.4)
+    TF_TRIGGERED = 32,       // dynamic scheduler: released by the event whose indptr range holds c0 (data-dependent trigger)
 };
 
 // One materialised task of a static queue (Sec. 3.1: "static execution queue"), 32 bytes.
@@ -70,7 +73,7 @@ struct LayerWeights {
 };
 
 // Error word codes
-enum : int32_t { ERR_NONE = 0, ERR_WAIT_TIMEOUT = 1, ERR_QUEUE_OVERFLOW = 2, ERR_POP_TIMEOUT = 3 };
+enum : int32_t { ERR_NONE = 0, ERR_WAIT_TIMEOUT = 1, ERR_QUEUE_OVERFLOW = 2, ERR_POP_TIMEOUT = 3, ERR_BAD_TABLE = 4 };
 
 // Everything the megakernel needs, passed by value as the kernel argument.
 struct Params {
@@ -158,7 +161,10 @@ struct Params {
     int32_t *error_word;               // [4]
     uint64_t *trace;                   // [n_tasks][8] wall-clock marks, or null
     // generic-graph buffers (row-sum example)
-    float *gbuf[4];
+    float *gbuf[8];                    // 0..2: A, B, C of the row-sum functions; 3..6: int32 route, indptr, count, perm
+    int32_t dd_event_base, dd_n_events;        // generic graphs: the data-dependently notified event tensor
+    int32_t dd_consumer_first, dd_consumer_n;  // task ids of the call it triggers
+    int32_t dd_table_len;                      // entries of the table = first grid extent of the notifying call
     int32_t gsym[4];
 };
 

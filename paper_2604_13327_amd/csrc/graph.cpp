@@ -33,7 +33,7 @@ static EdgeMap edge(int ev, std::initializer_list<int> kinds, std::initializer_l
 static EdgeMap edge_const0(int ev) { return edge(ev, {MAP_CONST}, {0}, {0}); }
 static EdgeMap edge_dim(int ev, int src, int div = 1) { return edge(ev, {MAP_DIM}, {src}, {div}); }
 
-std::string instantiate(const GraphDecl &g, const int *sym, int n_queues, bool unfused, Plan *out)
+std::string instantiate(const GraphDecl &g, const int *sym, int n_queues, bool unfused, Plan *out, bool data_dependent)
 {
     Plan &p = *out;
     p = Plan();
@@ -63,7 +63,11 @@ std::string instantiate(const GraphDecl &g, const int *sym, int n_queues, bool u
         if (m.rank != (int)dims.size()) return "edge rank differs from its event tensor's rank";
         int idx = 0;
         for (int r = 0; r < m.rank; ++r) {
-            int v = m.kind[r] == MAP_CONST ? m.div[r] : coord[m.src[r]] / std::max(1, m.div[r]);
+            // a run-time map names the tensor's event 0 here: the coarse event of the static rule, or the base
+            // the run-time index is added to
+            int v = m.kind[r] == MAP_CONST ? m.div[r]
+                    : (m.kind[r] == MAP_INDIRECT || m.kind[r] == MAP_INDPTR) ? 0
+                                                                             : coord[m.src[r]] / std::max(1, m.div[r]);
             if (v < 0 || v >= dims[r]) {
                 std::ostringstream s;
                 s << "edge maps a task outside event tensor " << m.event << " (dim " << r << ": " << v
@@ -114,6 +118,10 @@ std::string instantiate(const GraphDecl &g, const int *sym, int n_queues, bool u
                     int f;
                     std::string err = flat_event(c.in[k], coord, &f);
                     if (!err.empty()) return err;
+                    if (data_dependent && c.in[k].kind[0] == MAP_INDPTR) {      // released at run time, waits for nothing
+                        t.flags |= TF_TRIGGERED;
+                        continue;
+                    }
                     (k == 0 ? t.wait0 : t.wait1) = f;
                 }
                 if (!c.out.empty()) {
@@ -121,13 +129,26 @@ std::string instantiate(const GraphDecl &g, const int *sym, int n_queues, bool u
                     std::string err = flat_event(c.out[0], coord, &f);
                     if (!err.empty()) return err;
                     t.notify0 = f;
-                    p.ev_init[f]++;
+                    if (data_dependent && c.out[0].kind[0] == MAP_INDIRECT) t.flags |= TF_NOTIFY_INDIRECT;   // count known at run time only
+                    else p.ev_init[f]++;
                 }
             }
             p.tasks.push_back(t);
         }
         p.call_begin.push_back((int32_t)p.tasks.size());
         p.stage_of_call.push_back(c.stage);
+        {   // the run-time edges of the graph (the device functions bound-check their tables against these)
+            if (!c.out.empty() && c.out[0].kind[0] == MAP_INDIRECT) {
+                p.dd_event_base = p.ev_offset[c.out[0].event];
+                p.dd_n_events = ev_dims[c.out[0].event][0];
+                p.dd_table_len = dims[0];
+            }
+            for (const EdgeMap &m : c.in)
+                if (m.kind[0] == MAP_INDPTR) {
+                    p.dd_consumer_first = p.call_begin[p.call_begin.size() - 2];
+                    p.dd_consumer_n = total;
+                }
+        }
     }
 
     // static queues: round-robin over the task enumeration (Sec. 3.1).  Every queue is a
@@ -159,7 +180,7 @@ std::string instantiate(const GraphDecl &g, const int *sym, int n_queues, bool u
             for (int w = 0; w < span; ++w) add(t.wait0 + w);
         }
         add(t.wait1);
-        if (n == 0) p.seed_tasks.push_back(t.id);
+        if (n == 0 && !(t.flags & TF_TRIGGERED)) p.seed_tasks.push_back(t.id);
         for (int k = 0; k < n; ++k) cons[trig[k]].push_back(t.id | (n > 1 ? n << 24 : 0));
     }
     p.ev_consumers.assign(1, 0);

@@ -24,7 +24,9 @@ struct DimExpr {
 inline DimExpr dim_const(int c) { return DimExpr{-1, 0, c}; }
 inline DimExpr dim_sym(int s, int mul = 1, int add = 0) { return DimExpr{s, mul, add}; }
 
-enum MapKind { MAP_DIM = 0, MAP_CONST = 1 };
+// MAP_INDIRECT (out-edges): event coord = table[task coord 0]; MAP_INDPTR (in-edges): the event whose range
+// [indptr[e], indptr[e+1]) holds task coord 0.  Both name run-time tensors (Sec. 2.4).
+enum MapKind { MAP_DIM = 0, MAP_CONST = 1, MAP_INDIRECT = 2, MAP_INDPTR = 3 };
 
 struct EdgeMap {
     int event = -1;                    // event tensor id
@@ -72,11 +74,17 @@ struct Plan {
     std::vector<int32_t> ev_consumers; // [n_events + 1] CSR over consumer_ids
     std::vector<int32_t> consumer_ids;
     std::vector<int32_t> seed_tasks;   // tasks with no in-edge
+    // data-dependent edges (dynamic scheduling only; otherwise they collapse to the tensor's event 0)
+    int dd_event_base = 0, dd_n_events = 0, dd_consumer_first = 0, dd_consumer_n = 0;
+    int dd_table_len = 0;              // extent of the first grid dimension of the indirectly notifying call
 };
 
 // Binds the symbols and materialises the plan.  unfused: ignore the declared edges and put one
 // coarse event between consecutive stages (Sec. 4.5 baseline).  Returns "" or an error text.
-std::string instantiate(const GraphDecl &g, const int *sym_values, int n_queues, bool unfused, Plan *out);
+// data_dependent: keep MAP_INDIRECT / MAP_INDPTR edges as run-time edges (dynamic scheduler); otherwise they are
+// rewritten to the coarse event 0 of their tensor, fed by all producers (the static rule of Sec. 3.1).
+std::string instantiate(const GraphDecl &g, const int *sym_values, int n_queues, bool unfused, Plan *out,
+                        bool data_dependent = false);
 
 struct ModelDims {
     int n_layers, H, nq, nkv, d, F, E, topk, moeF, page;

@@ -38,6 +38,20 @@ __device__ __forceinline__ void rowsum_final(const Params &P, int i)
     }
 }
 
+// Task t of a grid released through indptr ranges: the final sum of row block perm[t].  Tasks beyond the last
+// range (the grid is sized for the largest case) have nothing to do.
+__device__ __forceinline__ void rowsum_final_perm(const Params &P, int t)
+{
+    const int32_t *indptr = reinterpret_cast<const int32_t *>(P.gbuf[4]), *perm = reinterpret_cast<const int32_t *>(P.gbuf[6]);
+    if (t >= gld_i32(indptr + P.dd_n_events)) return;
+    const int r = gld_i32(perm + t);
+    if (r < 0 || r >= P.dd_table_len) {                  // an entry that names no row block: refuse, do not write
+        if (threadIdx.x == 0) raise_error(P, ERR_BAD_TABLE, FN_ROWSUM_FINAL_PERM, t);
+        return;
+    }
+    rowsum_final(P, r);
+}
+
 // Step prologue for sequence b: hidden_in (bf16) -> residual stream (fp32), the first layer's projection
 // operand (x * g1, split) and the partial sums of squares per 16 elements, as every later producer does.
 // Also what every layer's QKV epilogue needs of the step's shape, resolved once: the (cos, sin) of the RoPE
@@ -284,6 +298,7 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
         wg_wait_cached(P, st, w0, w1, t.fn);
         if (t.fn == FN_ROWSUM_PARTIAL) rowsum_partial(P, t.c0, t.c1);
         else if (t.fn == FN_ROWSUM_FINAL) rowsum_final(P, t.c0);
+        else if (t.fn == FN_ROWSUM_FINAL_PERM) rowsum_final_perm(P, t.c0);
         return;
     }
     switch (t.fn) {
@@ -499,6 +514,11 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
     if (blockIdx.x == 0 && threadIdx.x == 0) {            // reset the control words of the next launch
         for (int i = 0; i < 8; ++i) P.q_ctrl_next[i] = 0;
     }
+    if (KIND == KIND_GENERIC && P.dd_consumer_n > 0 && blockIdx.x == 0 && threadIdx.x == 0) {
+        // tasks of the triggered grid beyond the last indptr range are never released: count them completed
+        const int surplus = P.dd_consumer_n - gld_i32(reinterpret_cast<const int32_t *>(P.gbuf[4]) + P.dd_n_events);
+        if (surplus > 0) __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 3), surplus, __ATOMIC_RELAXED, ETC_SCOPE);
+    }
     // Wavefront 0 is the scheduler of its workgroup: its lane 0 notifies and pops, all its lanes push.
     const bool sched_wave = wave_id() == 0;
     if (sched_wave) {
@@ -523,7 +543,8 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
         // MoE with data-dependent events (Sec. 2.4): the router tiles trigger the GroupGEMM-1 tiles of an expert
         // themselves, when the expert's event fires, so those are not pushed when the router tiles are
         // dispatched, and a triggered tile has nothing left to wait for.
-        const bool dd_producer = KIND == KIND_MOE && P.moe_dd && t.fn == FN_ROUTER;
+        const bool dd_notify = KIND == KIND_GENERIC && (t.flags & TF_NOTIFY_INDIRECT);     // generic graphs (Sec. 2.4)
+        const bool dd_producer = (KIND == KIND_MOE && P.moe_dd && t.fn == FN_ROUTER) || dd_notify;
         if (KIND == KIND_MOE && P.moe_dd && t.fn == FN_MOE_GATEUP) t.wait0 = -1;
         if (sched_wave) {
             // This task is dispatched: the last producer of its event to get here pushes the consumers.  The
@@ -544,13 +565,44 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
         wg_state_init(st);
         run_task<true, KIND>(P, sP, t, sm, st);
         wg_release();                            // also: every lane has read s_task before it is written again
-        if (sched_wave && lane_id() == 0) {
-            // notify and count the task done without waiting for either atomic: whoever polls an empty queue
-            // compares the count with the number of tasks of the step
-            if (P.debug_flags & 1u) atomicAdd(P.exec_count + t.id, 1);
-            if (t.notify0 >= 0) ev_notify(P, t.notify0);
-            __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 3), 1, __ATOMIC_RELAXED, ETC_SCOPE);
-            s_task = q_wait_slot(P, next_ticket, next_look);
+        if (sched_wave) {
+            if (dd_notify) {
+                // Data-dependent event update and trigger of a generic graph: the event is table[c0]; its count
+                // (count[e], made with the table) is known at run time only, so the notifies count down from zero
+                // and the one that completes the count has fired the event; it releases the tasks
+                // [indptr[e], indptr[e+1]) of the triggered grid and puts the counter back.
+                const int32_t *table = reinterpret_cast<const int32_t *>(P.gbuf[3]), *indptr = reinterpret_cast<const int32_t *>(P.gbuf[4]),
+                              *count = reinterpret_cast<const int32_t *>(P.gbuf[5]);
+                const int ev = __builtin_amdgcn_readfirstlane(gld_i32(table + t.c0));
+                const bool ev_ok = ev >= 0 && ev < P.dd_n_events;
+                int fired = 0;
+                if (!ev_ok) {
+                    if (lane_id() == 0) raise_error(P, ERR_BAD_TABLE, t.fn, t.c0);
+                } else if (lane_id() == 0) {
+                    const int before = __hip_atomic_fetch_sub(as_global(P.ev_cur + P.dd_event_base + ev), 1, __ATOMIC_RELAXED, ETC_SCOPE);
+                    fired = before - 1 == -gld_i32(count + ev);
+                    if (fired) st_i32(P.ev_cur + P.dd_event_base + ev, 0);
+                }
+                if (__builtin_amdgcn_readfirstlane(fired)) {
+                    const int j0 = __builtin_amdgcn_readfirstlane(gld_i32(indptr + ev));
+                    const int n = __builtin_amdgcn_readfirstlane(gld_i32(indptr + ev + 1)) - j0;
+                    const bool range_ok = j0 >= 0 && n >= 0 && j0 + n <= P.dd_consumer_n;
+                    if (!range_ok && lane_id() == 0) raise_error(P, ERR_BAD_TABLE, t.fn, ev);
+                    const int base = range_ok && n > 0 ? q_reserve_wave(P, n) : -1;
+                    if (base >= 0)
+                        for (int i = lane_id(); i < n; i += 64)
+                            __hip_atomic_store(as_global(P.q_slots + base + i), q_slot_word(P, P.dd_consumer_first + j0 + i),
+                                               __ATOMIC_RELAXED, ETC_SCOPE);
+                }
+            }
+            if (lane_id() == 0) {
+                // notify and count the task done without waiting for either atomic: whoever polls an empty
+                // queue compares the count with the number of tasks of the step
+                if (P.debug_flags & 1u) atomicAdd(P.exec_count + t.id, 1);
+                if (t.notify0 >= 0 && !dd_notify) ev_notify(P, t.notify0);
+                __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 3), 1, __ATOMIC_RELAXED, ETC_SCOPE);
+                s_task = q_wait_slot(P, next_ticket, next_look);
+            }
         }
         __syncthreads();
         id = __builtin_amdgcn_readfirstlane(s_task);

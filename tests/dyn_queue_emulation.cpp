@@ -16,8 +16,66 @@
 #include <thread>
 #include <vector>
 struct Task { int wait0, wait1, notify0, id; };
+// Data-dependent edges (Sec. 2.4) on the ready queue: producer (i, j), j < 4, notifies event route[i]; an event's
+// count (4 x the row blocks routed to it) is known at run time only, so notifies count down from zero and the
+// one that completes the count fires the event, puts the counter back and releases the consumer tasks
+// [indptr[e], indptr[e+1]); the consumer grid has `surplus` tasks beyond the last range, credited as completed
+// at the start and never run.
+static int run_data_dependent(int n, int NWG, int m, int surplus) {
+    std::vector<int> route(n), cnt(m, 0), indptr(m + 1, 0);
+    unsigned seed = 12345u + (unsigned)n * 7u + (unsigned)m;
+    for (int i = 0; i < n; ++i) { seed = seed * 1664525u + 1013904223u; route[i] = (int)((seed >> 16) % (unsigned)m); cnt[route[i]] += 4; }
+    for (int e = 0; e < m; ++e) indptr[e + 1] = indptr[e] + cnt[e] / 4;
+    const int n_prod = 4 * n, n_cons = n + surplus, total = n_prod + n_cons, cap = total + NWG + 16;
+    std::vector<std::atomic<uint64_t>> slots(cap); for (auto& s : slots) s = 0;
+    std::vector<std::atomic<int>> ev(m); for (auto& e : ev) e = 0;
+    for (uint32_t epoch = 1; epoch <= 3; ++epoch) {
+        std::atomic<int> head{0}, tail{0}, ndone{surplus}, timeouts{0};
+        std::vector<std::atomic<int>> exec(total); for (auto& e : exec) e = 0;
+        auto publish = [&](int base, int id) { slots[base].store(((uint64_t)epoch << 32) | (uint32_t)(id + 1), std::memory_order_release); };
+        std::vector<std::thread> th;
+        for (int wg = 0; wg < NWG; ++wg) th.emplace_back([&, wg] {
+            for (int i = wg; i < n_prod; i += NWG) publish(tail.fetch_add(1), i);          // producers wait on nothing: seeds
+            auto wait_slot = [&](int ticket) {
+                if (ticket >= cap) return -1;
+                long spins = 0;
+                for (;;) {
+                    uint64_t v = slots[ticket].load(std::memory_order_acquire);
+                    if ((uint32_t)(v >> 32) == epoch) return (int)(uint32_t)v - 1;
+                    if (ndone.load() >= total) return -1;
+                    std::this_thread::yield();
+                    if (++spins > 20000000) { timeouts++; return -1; }
+                }
+            };
+            int id = wait_slot(head.fetch_add(1));
+            while (id >= 0) {
+                const int next_ticket = head.fetch_add(1);
+                exec[id]++;
+                if (id < n_prod) {
+                    const int e = route[id / 4];
+                    if (ev[e].fetch_sub(1) - 1 == -cnt[e]) {
+                        ev[e].store(0);
+                        const int j0 = indptr[e], k = indptr[e + 1] - j0, base = tail.fetch_add(k);
+                        for (int i = 0; i < k; ++i) publish(base + i, n_prod + j0 + i);
+                    }
+                }
+                ndone.fetch_add(1);
+                id = wait_slot(next_ticket);
+            }
+        });
+        for (auto& t : th) t.join();
+        bool ok = timeouts == 0;
+        for (int i = 0; i < total; ++i) ok = ok && exec[i] == (i < n_prod + n ? 1 : 0);
+        for (auto& e : ev) ok = ok && e == 0;
+        printf("data-dependent n=%d groups=%d wgs=%d epoch=%u: %s\n", n, m, NWG, epoch, ok ? "ok" : "FAIL");
+        if (!ok) return 1;
+    }
+    return 0;
+}
+
 int main(int argc, char** argv) {
     int n = argc > 1 ? atoi(argv[1]) : 1, NWG = argc > 2 ? atoi(argv[2]) : 64;
+    if (argc > 3) return run_data_dependent(n, NWG, atoi(argv[3]), argc > 4 ? atoi(argv[4]) : 0);
     std::vector<Task> tasks;
     const int F = n;                                   // event ids: E[0..n), F
     for (int i = 0; i < n; ++i) for (int j = 0; j < 4; ++j) tasks.push_back({-1, -1, i, (int)tasks.size()});

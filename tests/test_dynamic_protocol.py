@@ -17,3 +17,9 @@ def test_ready_queue_protocol_terminates_and_runs_every_task_once(tmp_path):
         out = subprocess.run([str(exe), str(n), str(wgs)], capture_output=True, text=True, timeout=120)
         assert out.returncode == 0, out.stdout + out.stderr
         assert out.stdout.count(": ok") == 3
+    # data-dependent update and trigger (run-time counts, indptr ranges, surplus tasks that are never released)
+    for n, wgs, groups, surplus in ((1, 4, 1, 0), (24, 16, 5, 7), (40, 64, 3, 1)):
+        out = subprocess.run([str(exe), str(n), str(wgs), str(groups), str(surplus)], capture_output=True, text=True,
+                             timeout=120)
+        assert out.returncode == 0, out.stdout + out.stderr
+        assert out.stdout.count(": ok") == 3

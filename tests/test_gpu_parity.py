@@ -271,6 +271,66 @@ def test_dynamic_scheduler_is_independent_of_listing_order_and_times_out_on_a_cy
     g.close()
 
 
+@pytest.mark.parametrize("kind", KINDS)
+def test_generic_graph_with_data_dependent_edges(kind):
+    """The two data-dependent mechanisms of Sec. 2.4 on a generic graph.  n row blocks are routed to m groups by
+    a run-time table; partial-sum task (i, j) notifies the event of group route[i] (INDIRECT update; the count of
+    an event is known at run time only); the final-sum grid is laid out group by group, and event g releases
+    exactly the tasks [indptr[g], indptr[g+1]) (INDPTR trigger), task t summing row block perm[t].  The grid is
+    sized for more row blocks than are routed, so it has surplus tasks: no-ops under the static rule (one coarse
+    event), never released by the ready queue.  Whatever the routing, C is the plain row sum of A."""
+    import torch
+    etc = _etc()
+    from paper_2604_13327_amd import binding as b
+    n_max, m = 24, 5
+    g = etc.EventGraph(kind=kind, debug_flags=etc.DEBUG_EXEC_COUNT, spin_budget=SPIN)
+    n = g.dim(sym=0, mul=1, add=0)
+    ev = g.add_event([g.dim(add=m)])
+    g.add_call(b.FN_ROWSUM_PARTIAL, [n, g.dim(add=4)], out_edges=[g.edge(ev, [(b.MAP_INDIRECT, 0, 1)])])
+    g.add_call(b.FN_ROWSUM_FINAL_PERM, [g.dim(add=n_max)], in_edges=[g.edge(ev, [(b.MAP_INDPTR, 0, 1)])])
+    rng = np.random.default_rng(11)
+    for rep, n_rows in enumerate((24, 7, 1, 19)):          # one template, several routings, no rebuild
+        A = rng.integers(-8, 9, size=(n_rows * 32, 128)).astype(np.float32)
+        route = rng.integers(0, m, size=n_rows).astype(np.int32)
+        if rep == 1:
+            route[:] = 3                                   # everything to one group, four groups empty
+        perm = np.argsort(route, kind="stable").astype(np.int32)
+        per_group = np.bincount(route, minlength=m)
+        indptr = np.concatenate([[0], np.cumsum(per_group)]).astype(np.int32)
+        count = (4 * per_group).astype(np.int32)           # four partial sums per row block notify its group's event
+        perm_full = np.concatenate([perm, np.zeros(n_max - n_rows, np.int32)])
+        dA = torch.from_numpy(A).cuda()
+        dB = torch.full((n_rows * 32, 4), float("nan"), device="cuda")
+        dC = torch.full((n_max * 32,), float("nan"), device="cuda")
+        tabs = [torch.from_numpy(x).cuda() for x in (route, indptr, count, perm_full)]
+        for slot, t in enumerate([dA, dB, dC] + tabs):
+            g.bind_buffer(slot, t)
+        g.bind_shape([n_rows])
+        for launches in (1, 2):                            # the second launch runs on re-armed events
+            dC.fill_(float("nan"))
+            g.launch()
+            torch.cuda.synchronize()
+            got = dC.cpu().numpy()
+            np.testing.assert_array_equal(got[: n_rows * 32], A.astype(np.float64).sum(1))
+            assert np.isnan(got[n_rows * 32:]).all()       # surplus tasks wrote nothing
+            assert (g.event_counters() == 0).all()
+            want = np.full(4 * n_rows + n_max, launches, np.int32)
+            if kind == 1:
+                want[4 * n_rows + n_rows:] = 0             # the ready queue never released the surplus tasks
+            np.testing.assert_array_equal(g.exec_counts(), want)
+    # a table entry outside the event tensor ends the launch with an error instead of a wild access
+    if kind == 1:
+        bad = torch.from_numpy(np.full(n_rows, m + 3, np.int32)).cuda()
+        g.bind_buffer(3, bad)
+        g.bind_shape([n_rows])
+        g.launch()
+        torch.cuda.synchronize()
+        with pytest.raises(etc.EtcError) as ei:
+            g.event_counters()
+        assert ei.value.status == -5
+    g.close()
+
+
 @pytest.mark.parametrize("batch", [17, 40, 64])
 def test_tiny_large_batches_take_the_chunked_path(batch):
     """Batches above 16 columns: operand walked in double-buffered LDS chunks, 2 and 4 MFMA column blocks,

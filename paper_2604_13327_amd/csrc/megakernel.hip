@@ -469,19 +469,17 @@ __device__ __forceinline__ void q_push_consumers_wave(const Params &P, int ev)
     }
 }
 
-// Pop, in two halves so that the first can run a task ahead: q_take_ticket reserves the next ticket (one
-// lane), q_wait_slot waits for that slot to be published: the task id, or -1 when the step is complete
-// (every task has counted itself done), the queue is exhausted or an error was raised.  `first_look` is
-// the slot's content as read some time ago (0: not read).
+// Pop, in two halves: q_take_ticket reserves the next ticket (one lane), q_wait_slot waits for that slot to
+// be published: the task id, or -1 when the step is complete (every task has counted itself done), the
+// queue is exhausted or an error was raised.
 __device__ __forceinline__ int q_take_ticket(const Params &P)
 {
     return __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 0), 1, __ATOMIC_RELAXED, ETC_SCOPE);
 }
 
-__device__ __forceinline__ int q_wait_slot(const Params &P, int ticket, uint64_t first_look)
+__device__ __forceinline__ int q_wait_slot(const Params &P, int ticket)
 {
     if (ticket >= P.q_capacity) return -1;
-    if ((uint32_t)(first_look >> 32) == P.epoch) return (int)(uint32_t)first_look - 1;
     long long spins = 0;
     for (;;) {
         const uint64_t v = ld_u64(P.q_slots + ticket);
@@ -532,12 +530,10 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
                                        q_slot_word(P, gld_i32(P.seed_tasks + blockIdx.x + i * gridDim.x)), __ATOMIC_RELAXED,
                                        ETC_SCOPE);
         }
-        if (lane_id() == 0) s_task = q_wait_slot(P, q_take_ticket(P), 0);
+        if (lane_id() == 0) s_task = q_wait_slot(P, q_take_ticket(P));
     }
     __syncthreads();
     int id = __builtin_amdgcn_readfirstlane(s_task);
-    int next_ticket = 0;               // scheduler lane: the ticket taken a task ahead, and a first look at its slot
-    uint64_t next_look = 0;
     while (id >= 0) {
         Task t = load_task(P.dyn_tasks + id);
         // MoE with data-dependent events (Sec. 2.4): the router tiles trigger the GroupGEMM-1 tiles of an expert
@@ -547,19 +543,11 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
         const bool dd_producer = (KIND == KIND_MOE && P.moe_dd && t.fn == FN_ROUTER) || dd_notify;
         if (KIND == KIND_MOE && P.moe_dd && t.fn == FN_MOE_GATEUP) t.wait0 = -1;
         if (sched_wave) {
-            // This task is dispatched: the last producer of its event to get here pushes the consumers.  The
-            // next ticket is taken in the same round trip, a task ahead, so that no atomic's latency sits
-            // between two tasks.
+            // This task is dispatched: the last producer of its event to get here pushes the consumers.
             int last = 0;
-            if (lane_id() == 0) {
-                int left = 0;
-                if (t.notify0 >= 0 && !dd_producer)
-                    left = __hip_atomic_fetch_sub(as_global(P.ev_disp_cur + t.notify0), 1, __ATOMIC_RELAXED, ETC_SCOPE);
-                next_ticket = q_take_ticket(P);
-                last = left == 1;
-            }
+            if (lane_id() == 0 && t.notify0 >= 0 && !dd_producer)
+                last = __hip_atomic_fetch_sub(as_global(P.ev_disp_cur + t.notify0), 1, __ATOMIC_RELAXED, ETC_SCOPE) == 1;
             if (__builtin_amdgcn_readfirstlane(last)) q_push_consumers_wave(P, t.notify0);
-            if (lane_id() == 0) next_look = next_ticket < P.q_capacity ? ld_u64(P.q_slots + next_ticket) : 0;
         }
         WgState st;
         wg_state_init(st);
@@ -601,7 +589,11 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
                 if (P.debug_flags & 1u) atomicAdd(P.exec_count + t.id, 1);
                 if (t.notify0 >= 0 && !dd_notify) ev_notify(P, t.notify0);
                 __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 3), 1, __ATOMIC_RELAXED, ETC_SCOPE);
-                s_task = q_wait_slot(P, next_ticket, next_look);
+                // The next ticket is taken only now.  Taken a task ahead (in the round trip of the dispatch
+                // decrement) it cost more than it saved: a workgroup that sits in a long wait, such as the
+                // projection behind the attention chunks, then holds a task that an idle workgroup could run
+                // (8B step 4.34 against 4.12 ms); taken beside the drain of the task's stores: 4.18 ms.
+                s_task = q_wait_slot(P, q_take_ticket(P));
             }
         }
         __syncthreads();

@@ -4,7 +4,7 @@
 // atomic reservation on tail, early push (a second counter per event counts producers not yet dispatched;
 // the workgroup that brings it to zero pushes the consumers whose other events are that far too, a
 // per-task counter that is never reset deciding which of a task's events is the last), waits kept by the
-// pushed task, the next ticket taken a task ahead, poppers of an empty queue leaving once the count of
+// pushed task, poppers of an empty queue leaving once the count of
 // completed tasks reaches the number of tasks.  Graph: the row-sum example (4n producers
 // notify E[i], n consumers wait on E[i]) plus one closing task that waits on two events (F, notified by the
 // n consumers, and E[0]).  Three consecutive launches (epochs) without clearing the slots or the per-task
@@ -49,7 +49,6 @@ static int run_data_dependent(int n, int NWG, int m, int surplus) {
             };
             int id = wait_slot(head.fetch_add(1));
             while (id >= 0) {
-                const int next_ticket = head.fetch_add(1);
                 exec[id]++;
                 if (id < n_prod) {
                     const int e = route[id / 4];
@@ -60,7 +59,7 @@ static int run_data_dependent(int n, int NWG, int m, int surplus) {
                     }
                 }
                 ndone.fetch_add(1);
-                id = wait_slot(next_ticket);
+                id = wait_slot(head.fetch_add(1));
             }
         });
         for (auto& t : th) t.join();
@@ -122,7 +121,6 @@ int main(int argc, char** argv) {
             while (id >= 0) {
                 const Task& t = tasks[id];
                 const bool last = t.notify0 >= 0 && disp[t.notify0].fetch_sub(1) == 1;   // dispatched: early push
-                const int next_ticket = head.fetch_add(1);                                // a task ahead
                 if (last)
                     for (const Entry& c : cons[t.notify0])
                         if (c.n_waited == 1 || (pending[c.id].fetch_add(1) + 1) % c.n_waited == 0) push1(c.id);
@@ -132,7 +130,7 @@ int main(int argc, char** argv) {
                 exec[id]++;
                 if (t.notify0 >= 0) ev[t.notify0].fetch_sub(1);
                 ndone.fetch_add(1);
-                id = wait_slot(next_ticket);
+                id = wait_slot(head.fetch_add(1));
             }
         });
         for (auto& t : th) t.join();

@@ -558,6 +558,7 @@ etc_status etc_launch_kernel_by_kernel(etc_ctx *c, const void *hidden_in, void *
     if (st != ETC_OK) return st;
     hipStream_t s = (hipStream_t)hip_stream;
     const Plan &pl = c->plans[c->cur_plan].host;
+    P.moe_dd = 0;        // no events and no ready queue here: the router tiles release nothing, every slot task runs
     // one launch per operator stage; the calls of a stage are contiguous in task-id order
     size_t ci = 0;
     while (ci < pl.stage_of_call.size()) {

@@ -197,9 +197,12 @@ def test_tiny_moe_schedulers_and_kernel_by_kernel_agree_bitwise(tiny_moe_model):
             np.testing.assert_array_equal(dec.exec_counts(), want)
             if kind == etc.SCHED_DYNAMIC:
                 print(f"dynamic: {int((want == 0).sum())} tasks of surplus row-tile slots were never released")
-        if kind == etc.SCHED_STATIC:
-            m.reset_pools()
+        if kind != etc.SCHED_UNFUSED:               # one launch per operator stage, also from a context built for the
+            m.reset_pools()                         # ready queue (no events there: every slot task runs)
             outs.append(_launch(dec, m, step, kbk=True))
+            m.reset_pools()
+            outs.append(_launch(dec, m, step))      # and the scheduler's own state is untouched by it
+            assert (dec.error_word() == 0).all() and (dec.event_counters() == 0).all()
         dec.close()
     for o in outs[1:]:
         np.testing.assert_array_equal(o, outs[0])

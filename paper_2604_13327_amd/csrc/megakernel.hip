@@ -436,6 +436,7 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_static(const Params P)
 // then spin exactly like a task of a static queue; the push itself is off the critical path.  No
 // deadlock: a task that spins has all its producers running on other workgroups (or spinning in turn on
 // tasks dispatched before them).
+
 // All producers of event `ev` are dispatched: publishes the consumers whose other events are that far too.
 // Called by every lane of one wavefront, 64 table entries per round (one lane alone took 0.3 us per task:
 // a third of a 33 000-task step).
@@ -452,7 +453,7 @@ __device__ __forceinline__ void q_push_consumers_wave(const Params &P, int ev)
             id = entry & 0xFFFFFF;
             const int n_waited = (entry >> 24) & 0x7F;
             ready = true;
-            if (n_waited > 1) {      // the last of its events to get here pushes the task (the counter is never reset)
+            if (n_waited > 1) {      // the last of its events to get here pushes the task (the counter only counts up)
                 const int seen = __hip_atomic_fetch_add(as_global(P.task_pending + id), 1, __ATOMIC_RELAXED, ETC_SCOPE) + 1;
                 ready = seen % n_waited == 0;
             }

@@ -34,6 +34,50 @@ __device__ __forceinline__ int wave_sum_i(int v)
     return v;
 }
 
+// ---- wavefront arg-max of the router's top-k -------------------------------------------------------------
+// (logit, expert) as one unsigned key: floats map to integers of the same order (sign bit flipped for
+// non-negative values, all bits for negative ones), the index is complemented so that a lower index wins a tie.
+__device__ __forceinline__ uint64_t topk_key(float logit, int expert)
+{
+    const uint32_t u = __float_as_uint(logit);
+    const uint32_t ord = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    return ((uint64_t)ord << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)expert);
+}
+
+__device__ __forceinline__ float topk_key_logit(uint64_t key)
+{
+    const uint32_t ord = (uint32_t)(key >> 32);
+    return __uint_as_float((ord & 0x80000000u) ? (ord & 0x7FFFFFFFu) : ~ord);
+}
+
+template <int CTRL>
+__device__ __forceinline__ uint64_t dpp_max_u64(uint64_t k)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)k, CTRL, 0xF, 0xF, false);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(k >> 32), CTRL, 0xF, 0xF, false);
+    const uint64_t o = ((uint64_t)hi << 32) | lo;
+    return o > k ? o : k;
+}
+
+// Maximum over the 64 lanes, the same value in every lane: quad exchanges, half-row mirror and row mirror leave
+// each row of 16 lanes with its maximum; the four row maxima are read as scalars.
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t k)
+{
+    k = dpp_max_u64<0xB1>(k);      // quad_perm [1,0,3,2]
+    k = dpp_max_u64<0x4E>(k);      // quad_perm [2,3,0,1]
+    k = dpp_max_u64<0x141>(k);     // row_half_mirror
+    k = dpp_max_u64<0x140>(k);     // row_mirror
+    uint64_t best = 0;
+#pragma unroll
+    for (int row = 0; row < 4; ++row) {
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)k, row * 16);
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(k >> 32), row * 16);
+        const uint64_t r = ((uint64_t)hi << 32) | lo;
+        best = r > best ? r : best;
+    }
+    return best;
+}
+
 // Data-dependent event update and task triggering (Sec. 2.4), dynamic scheduler only.  The expert event
 // tensor E_exp[e] is armed at run time with the number of tokens routed to e, plus one for tile 0, which
 // publishes the per-expert tables: every tile knows that count from its own copy of the routing, so nobody
@@ -138,9 +182,11 @@ __device__ __noinline__ void moe_route_and_group(const Params &P, int layer, int
     for (int b = wave; b < B; b += kWaves) {
         const float *lg = P.router_logits + (size_t)b * E;
         float v[kMaxExperts / 64];
+        bool taken[kMaxExperts / 64];
 #pragma unroll
         for (int j = 0; j < kMaxExperts / 64; ++j) {
             const int e = lane + 64 * j;
+            taken[j] = false;
             v[j] = e < E ? ld_f32(lg + e) : -INFINITY;
             if (dbg && b == t && e < E) as_global(P.dbg_logits)[dbg_row * E + e] = v[j];
         }
@@ -153,23 +199,23 @@ __device__ __noinline__ void moe_route_and_group(const Params &P, int layer, int
             }
         } else {
             for (int k = 0; k < K; ++k) {
-                float bv = -INFINITY;
-                int bi = 0x7FFFFFFF;
+                // One 64-bit key per candidate: the logit in an order-preserving integer form above, the
+                // complement of the expert index below, so the largest key is the largest logit and, among equal
+                // logits, the lowest index.  The wavefront maximum takes four DPP steps inside each row of 16
+                // lanes and a scalar maximum over the four rows (a shuffle-based arg-max, six dependent LDS
+                // round trips of two words each, made a router tile of a large batch the longest task of the layer).
+                uint64_t key = 0;
 #pragma unroll
-                for (int j = 0; j < kMaxExperts / 64; ++j) {      // ascending index: a strict '>' keeps the lowest on ties
+                for (int j = 0; j < kMaxExperts / 64; ++j) {
                     const int e = lane + 64 * j;
-                    if (e < E && v[j] > bv) { bv = v[j]; bi = e; }
+                    if (e < E && !taken[j]) key = max(key, topk_key(v[j], e));
                 }
-#pragma unroll
-                for (int off = 32; off > 0; off >>= 1) {
-                    const float ov = __shfl_xor(bv, off, 64);
-                    const int oi = __shfl_xor(bi, off, 64);
-                    if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-                }
-                if (lane == k) { my_id = bi; my_v = bv; }
+                key = wave_max_u64(key);
+                const int bi = (int)(0xFFFFFFFFu - (uint32_t)key);
+                if (lane == k) { my_id = bi; my_v = topk_key_logit(key); }
 #pragma unroll
                 for (int j = 0; j < kMaxExperts / 64; ++j)
-                    if (lane + 64 * j == bi) v[j] = -INFINITY;    // taken
+                    if (lane + 64 * j == bi) taken[j] = true;
             }
         }
         if (lane < K) ids_s[b * K + lane] = my_id;

@@ -177,11 +177,47 @@ __device__ __forceinline__ int q_reserve_wave(const Params &P, int cnt)
     return base;
 }
 
+// ---- sums across lanes ---------------------------------------------------------------------------------
+// Cross-lane data-parallel-primitive (DPP) moves inside a row of 16 lanes: the two quad exchanges, then the
+// mirror of each half row, then the mirror of the row.  Each is one VALU instruction; a wavefront shuffle goes
+// through the LDS crossbar instead, and a chain of dependent ones costs a memory-like round trip each.
+template <int CTRL> __device__ __forceinline__ float dpp_f32(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+template <int CTRL> __device__ __forceinline__ int dpp_i32(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false); }
+
+// Sum over N (8 or 16) consecutive lanes, aligned to N, result in every one of them.
+template <int N>
+__device__ __forceinline__ float lanes_sum(float s)
+{
+    static_assert(N == 8 || N == 16, "8 or 16 lanes");
+    s += dpp_f32<0xB1>(s);                    // quad_perm [1,0,3,2]
+    s += dpp_f32<0x4E>(s);                    // quad_perm [2,3,0,1]
+    s += dpp_f32<0x141>(s);                   // row_half_mirror
+    if (N == 16) s += dpp_f32<0x140>(s);      // row_mirror
+    return s;
+}
+
+// Sum over the wavefront, the same value in every lane: the four row sums are read as scalars.
 __device__ __forceinline__ float wave_sum(float v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+    v = lanes_sum<16>(v);
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
+__device__ __forceinline__ int wave_sum_i(int v)
+{
+    v += dpp_i32<0xB1>(v);
+    v += dpp_i32<0x4E>(v);
+    v += dpp_i32<0x141>(v);
+    v += dpp_i32<0x140>(v);
+    return (__builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16)) +
+           (__builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48));
 }
 
 }  // namespace etc

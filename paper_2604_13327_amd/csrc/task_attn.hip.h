@@ -14,21 +14,6 @@
 
 namespace etc {
 
-// Sum over the LPT (8 or 16) consecutive lanes that share one key, result in every one of them.  Cross-lane
-// data-parallel-primitive moves inside a row of 16 lanes: the two quad exchanges, then the mirror of each half
-// row, then the mirror of the row; each is one VALU instruction (a wavefront shuffle goes through the LDS
-// crossbar instead, and the four dependent ones per score were what the key loop spent its time on).
-template <int LPT>
-__device__ __forceinline__ float key_lanes_sum(float s)
-{
-    static_assert(LPT == 8 || LPT == 16, "a key is spread over 8 or 16 lanes");
-    s += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), 0xB1, 0xF, 0xF, false));    // quad_perm [1,0,3,2]
-    s += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), 0x4E, 0xF, 0xF, false));    // quad_perm [2,3,0,1]
-    s += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), 0x141, 0xF, 0xF, false));   // row_half_mirror
-    if (LPT == 16) s += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s), 0x140, 0xF, 0xF, false));   // row_mirror
-    return s;
-}
-
 // ev0 / ev1: the events the task waits on (the queries and this step's K / V row of the KV head).  The cached K / V
 // rows do not depend on them: a chunk of one batch requests its rows BEFORE it waits, like a projection task its
 // weights, so that after the wait only the queries are a round trip away (3.72 -> 3.62 ms per 8B step).
@@ -113,7 +98,7 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
                 float s = 0.f;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) s += q[g][i] * kf[i];
-                s = key_lanes_sum<LPT>(s);
+                s = lanes_sum<LPT>(s);
                 if (valid) {
                     const float nm = fmaxf(mx[g], s);
                     const float sc = __expf(mx[g] - nm);      // exp(-inf) = 0 on the first key
@@ -168,7 +153,7 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
             float s = 0.f;
 #pragma unroll
             for (int i = 0; i < 8; ++i) s += q[g][i] * kf[i];
-            s = key_lanes_sum<LPT>(s);
+            s = lanes_sum<LPT>(s);
             if (tq == 0) {
                 const float nm = fmaxf(mx[g], s);
                 const float sc = __expf(mx[g] - nm);

@@ -810,9 +810,7 @@ __device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &
             store_split(e.out_hi, e.out_lo, o1, v1 * pre.gb);
         }
         float s = v0 * v0 + v1 * v1;      // this tile's sum of squares: the 8 threads of a column are 8 consecutive lanes
-        s += __shfl_xor(s, 1, 64);
-        s += __shfl_xor(s, 2, 64);
-        s += __shfl_xor(s, 4, 64);
+        s = lanes_sum<8>(s);
         if (mp == 0 && e.ssq_out) st_f32(e.ssq_out + b, s);
         if (e.flags & TF_LAST_LAYER) {
             gst_u16(P.hidden_out + o0, f32_to_bf16_bits(v0));

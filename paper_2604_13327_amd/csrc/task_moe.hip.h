@@ -27,13 +27,6 @@ __device__ __forceinline__ bool resolve_row_tile(const Params &P, int r, RowTile
     return true;
 }
 
-__device__ __forceinline__ int wave_sum_i(int v)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
-}
-
 // ---- wavefront arg-max of the router's top-k -------------------------------------------------------------
 // (logit, expert) as one unsigned key: floats map to integers of the same order (sign bit flipped for
 // non-negative values, all bits for negative ones), the index is complemented so that a lower index wins a tie.
@@ -310,10 +303,7 @@ __device__ __forceinline__ void moe_combine(const Params &P, const Task &t)
         st_u16(P.xg_hi + o, hi);
         st_u16(P.xg_lo + o, lo);
         float s = v * v;          // 16 consecutive lanes hold one 16-element part
-        s += __shfl_xor(s, 1, 64);
-        s += __shfl_xor(s, 2, 64);
-        s += __shfl_xor(s, 4, 64);
-        s += __shfl_xor(s, 8, 64);
+        s = lanes_sum<16>(s);
         if ((threadIdx.x & 15) == 0) st_f32(P.ssq_x + (size_t)(h >> 4) * kMaxBatch + b, s);
     }
     if (P.debug_flags & 2u) gst_f32(P.layer_hidden + ((size_t)t.layer * kMaxBatch + b) * P.H + h, v);

@@ -16,11 +16,14 @@ constexpr int kStagedMaxCols = 16;                // widest batch the staged (la
 
 // LDS layout of the staged projection path: reduction buffer [tiles][waves][cols][16], norm factors, then
 // the whole operand (all columns, hi and lo).  A task takes that path when this fits.
+// A column of the operand is K + kOpPad elements apart from the next: with a stride of K (a multiple of the bank
+// span) the 16 columns a wavefront reads in one instruction would all sit in the same banks.
+constexpr int kOpPad = 8;
 constexpr long long staged_red_floats(int n_tiles, int n_cols) { return (long long)n_tiles * n_cols * kWaves * 16; }
 constexpr bool staged_fits(int n_tiles, int n_cols, int K)
 {
     return n_cols <= kStagedMaxCols &&
-           (staged_red_floats(n_tiles, n_cols) + kRsFloats) * 4 + (long long)n_cols * K * 4 <= (long long)kLdsBytes;
+           (staged_red_floats(n_tiles, n_cols) + kRsFloats) * 4 + (long long)n_cols * (K + kOpPad) * 4 <= (long long)kLdsBytes;
 }
 
 // Device functions (task bodies).  One entry of the dispatch switch each (Alg. 1 "dispatch logic").

@@ -158,7 +158,8 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
     ETC_AS_LDS float *red = as_lds(sm);               // [tile][wave][col][16 rows]
     ETC_AS_LDS float *rs = red + staged_red_floats(g.n_tiles, g.n_cols);
     ETC_AS_LDS uint16_t *op_hi = reinterpret_cast<ETC_AS_LDS uint16_t *>(rs + kRsFloats);
-    ETC_AS_LDS uint16_t *op_lo = op_hi + (size_t)g.n_cols * g.K;
+    const int Kp = g.K + kOpPad;                        // column stride of the operand in LDS
+    ETC_AS_LDS uint16_t *op_lo = op_hi + (size_t)g.n_cols * Kp;
 
     const int key = w.op_key;
     const bool restage = key < 0 || key != st.staged_key;
@@ -269,8 +270,8 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
                 const int idx = (int)threadIdx.x + u * kWgThreads;
                 if (idx < total) {
                     const int col = idx / quads, q = idx - col * quads;
-                    *reinterpret_cast<ETC_AS_LDS uint64_t *>(op_hi + (size_t)col * g.K + q * 4) = vh[u];
-                    *reinterpret_cast<ETC_AS_LDS uint64_t *>(op_lo + (size_t)col * g.K + q * 4) = vl[u];
+                    *reinterpret_cast<ETC_AS_LDS uint64_t *>(op_hi + (size_t)col * Kp + q * 4) = vh[u];
+                    *reinterpret_cast<ETC_AS_LDS uint64_t *>(op_lo + (size_t)col * Kp + q * 4) = vl[u];
                 }
             }
         } else {
@@ -280,8 +281,8 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
                 if (row < 0) row = 0;
                 const uint64_t vh = ld_u64(g.b_hi + (size_t)row * (size_t)g.ldb + q * 4);
                 const uint64_t vl = ld_u64(g.b_lo + (size_t)row * (size_t)g.ldb + q * 4);
-                *reinterpret_cast<ETC_AS_LDS uint64_t *>(op_hi + (size_t)col * g.K + q * 4) = vh;
-                *reinterpret_cast<ETC_AS_LDS uint64_t *>(op_lo + (size_t)col * g.K + q * 4) = vl;
+                *reinterpret_cast<ETC_AS_LDS uint64_t *>(op_hi + (size_t)col * Kp + q * 4) = vh;
+                *reinterpret_cast<ETC_AS_LDS uint64_t *>(op_lo + (size_t)col * Kp + q * 4) = vl;
             }
             if (one_col_per_wave && wave < g.n_cols) {
                 const int row = g.col_rows ? ld_i32(g.col_rows + wave) : wave;
@@ -328,8 +329,8 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
     trace_mark(P, task_id, 2);
 
     const bool valid = m < g.n_cols;
-    ETC_AS_LDS const uint16_t *sh = op_hi + (size_t)(valid ? m : 0) * (size_t)g.K + kbase;
-    ETC_AS_LDS const uint16_t *sl = op_lo + (size_t)(valid ? m : 0) * (size_t)g.K + kbase;
+    ETC_AS_LDS const uint16_t *sh = op_hi + (size_t)(valid ? m : 0) * (size_t)Kp + kbase;
+    ETC_AS_LDS const uint16_t *sl = op_lo + (size_t)(valid ? m : 0) * (size_t)Kp + kbase;
     // Consume cursor: step sc of tile tc.  Columns beyond n_cols read column 0's operand (never stored).
     f32x4 acc = f32x4{0, 0, 0, 0};
     int sc = 0, tc = 0;

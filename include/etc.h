@@ -235,6 +235,25 @@ etc_status etc_graph_bind_buffer(etc_ctx *ctx, int32_t slot, void *device_ptr, s
 etc_status etc_graph_bind_shape(etc_ctx *ctx, const int32_t *values);
 etc_status etc_graph_launch(etc_ctx *ctx, void *hip_stream);
 
+/* ---- allocation-free launch ------------------------------------------------------------------
+ * For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Runs the row-sum graph (the one etc_graph_* builds from
+ * ETC_FN_ROWSUM_PARTIAL over a (n, 4) grid notifying E[i] and ETC_FN_ROWSUM_FINAL over (n) waiting on E[i])
+ * for n row blocks under the static scheduler, as one small plan kernel plus one launch of the same
+ * megakernel etc_graph_launch uses.  The partial sums B, the event tensor, the task queues and the error
+ * word sit in a device array that is part of the library image (about 1.4 MB, held by every GPU the
+ * library runs on until the process ends); no context, no hipMalloc / hipFree, no memset, nothing to destroy.
+ *   A  device, fp32 [n*32, 128], read only      C  device, fp32 [n*32], written      n  1..ETC_ROWSUM_NOALLOC_MAX_N
+ *   hip_stream  a hipStream_t (may be NULL); the call is asynchronous on it.
+ * Same results, bit for bit, as etc_graph_launch on that graph.  Returns ETC_EINVAL for a NULL pointer or n
+ * outside the range (nothing is launched), ETC_EDEVICE when a HIP call fails.  All calls on one GPU share
+ * the one array: every call rewrites all of it that it reads, so calls may follow each other on one stream
+ * in any sizes, but calls that overlap on one GPU (different streams, different threads) race.  A wait that
+ * exceeds its spin budget drains the kernel as everywhere else (C is then incomplete); the error word stays
+ * in the array and is not reported by this call. */
+#define ETC_ROWSUM_NOALLOC_MAX_N 2048
+etc_status etc_rowsum_launch_noalloc(const float *A, float *C, int32_t n, void *hip_stream);
+
 /* ---- host-only inspection of the scheduling transformation (no device needed) ---------------
  * Instantiates the decoder's event-tensor graph for one sampled batch size exactly as etc_create
  * does and exposes the materialised tasks, static queues (Sec. 3.1), initial event counts (Sec. 2.1)

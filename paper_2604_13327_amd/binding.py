@@ -23,7 +23,9 @@ MAP_DIM, MAP_CONST, MAP_INDIRECT, MAP_INDPTR = 0, 1, 2, 3
 EXPORTS = ["etc_create", "etc_destroy", "etc_last_error", "etc_bind_layer_weights", "etc_bind_kv_pool",
            "etc_bind_step", "etc_force_routing", "etc_launch", "etc_launch_kernel_by_kernel", "etc_read_debug",
            "etc_get_step_info", "etc_graph_create", "etc_graph_add_event", "etc_graph_add_call",
-           "etc_graph_bind_buffer", "etc_graph_bind_shape", "etc_graph_launch", "etc_plan_build", "etc_plan_free"]
+           "etc_graph_bind_buffer", "etc_graph_bind_shape", "etc_graph_launch", "etc_plan_build", "etc_plan_free",
+           "etc_rowsum_launch_noalloc"]
+ROWSUM_NOALLOC_MAX_N = 2048
 
 
 class EtcError(RuntimeError):
@@ -125,6 +127,7 @@ def lib():
     L.etc_plan_build.argtypes = [C.POINTER(ModelDesc), C.POINTER(TileDesc), C.POINTER(SchedDesc), C.c_int32, C.c_int32,
                                  C.POINTER(PlanView)]
     L.etc_plan_free.argtypes = [C.POINTER(PlanView)]
+    L.etc_rowsum_launch_noalloc.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
     return L
 
 
@@ -273,6 +276,14 @@ class Decoder(_Ctx):
 
     def routing_debug(self, kind: int, layer: int, shape, dtype):
         return self.read_debug(kind, layer, np.zeros(shape, dtype))
+
+
+def rowsum_launch_noalloc(A, Cout, n: int, stream=None):
+    """etc_rowsum_launch_noalloc: A fp32 [n*32, 128], Cout fp32 [n*32], CUDA tensors; allocates nothing."""
+    L = lib()
+    st = L.etc_rowsum_launch_noalloc(A.data_ptr(), Cout.data_ptr(), n, _stream_ptr(stream))
+    if st != 0:
+        raise EtcError(st, L.etc_last_error(None).decode())
 
 
 def _stream_ptr(stream):

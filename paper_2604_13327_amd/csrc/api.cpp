@@ -19,6 +19,7 @@ hipError_t max_resident_workgroups(int *per_cu);
 hipError_t launch_static(const Params &P, hipStream_t s);
 hipError_t launch_dynamic(const Params &P, hipStream_t s);
 hipError_t launch_stage(const Params &P, int first, int count, hipStream_t s);
+hipError_t launch_rowsum_noalloc(const float *A, float *C, int n, hipStream_t s);
 }  // namespace etc
 
 using namespace etc;
@@ -637,6 +638,17 @@ etc_status etc_get_step_info(etc_ctx *c, etc_step_info *info)
     int dev = 0, khz = 0;
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev);
     info->wall_clock_khz = khz;
+    return ETC_OK;
+}
+
+// Allocation-free launch of the row-sum graph: all device state in the library's own device array.
+etc_status etc_rowsum_launch_noalloc(const float *A, float *C, int32_t n, void *hip_stream)
+{
+    if (!A || !C) return fail(nullptr, ETC_EINVAL, "A or C is NULL");
+    if (n < 1 || n > ETC_ROWSUM_NOALLOC_MAX_N)
+        return fail(nullptr, ETC_EINVAL, "n must be in 1.." + std::to_string(ETC_ROWSUM_NOALLOC_MAX_N) + " (the scratch array is sized for that)");
+    hipError_t e = launch_rowsum_noalloc(A, C, n, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail(nullptr, ETC_EDEVICE, std::string("allocation-free row-sum launch: ") + hipGetErrorString(e));
     return ETC_OK;
 }
 

@@ -7,6 +7,7 @@
 // A third entry point runs one stage's tasks as an ordinary kernel (kernel-by-kernel comparator).
 #include <hip/hip_runtime.h>
 
+#include "../../include/etc.h"
 #include "device_rt.hip.h"
 #include "task_attn.hip.h"
 #include "task_gemm.hip.h"
@@ -613,6 +614,130 @@ __global__ void __launch_bounds__(kWgThreads) stage_kernel(const Params P, int f
     WgState st;
     wg_state_init(st);
     run_task<false, KIND>(P, sP, t, sm, st);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Allocation-free variant of the row-sum graph launch
+// ---------------------------------------------------------------------------------------------
+// For callers that cannot allocate (HIP graph capture, tight serving loops): everything the generic-graph
+// path keeps in allocated device memory - the partial sums B, the event tensors, the materialised static
+// queues and the error word - lives in one file-scope device array.  A small plan kernel instantiates the
+// row-sum graph for n (tasks, round-robin queues, initial counts: what etc_graph_bind_shape computes on the
+// host and uploads) and arms the counters; then the generic static megakernel runs on those tables.
+// The array's name is a host-side stand-in only: its device address is looked up once per device with
+// hipGetSymbolAddress and that pointer is what kernels and host code use.
+constexpr int kNoAllocMaxN = ETC_ROWSUM_NOALLOC_MAX_N;      // row blocks of 32 rows
+constexpr int kNoAllocMaxQueues = 1024;
+constexpr size_t kNaOffB = 0;                                                     // float [n*32][4]
+constexpr size_t kNaOffEvents = kNaOffB + (size_t)kNoAllocMaxN * 32 * 4 * 4;      // int32 [3][max n]: cur | init | next
+constexpr size_t kNaOffTasks = kNaOffEvents + (size_t)3 * kNoAllocMaxN * 4;       // Task [5 n]
+constexpr size_t kNaOffQueueBegin = kNaOffTasks + (size_t)5 * kNoAllocMaxN * sizeof(Task);
+constexpr size_t kNaOffError = kNaOffQueueBegin + (size_t)(kNoAllocMaxQueues + 1) * 4 + 60;   // int32 [4]
+constexpr size_t kNoAllocScratchBytes = (kNaOffError + 16 + 255) / 256 * 256;
+static_assert(kNaOffEvents % 256 == 0 && kNaOffTasks % 32 == 0 && kNaOffQueueBegin % 16 == 0 && kNaOffError % 16 == 0,
+              "scratch regions keep their alignment");
+
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+
+// Instantiates the row-sum graph (Sec. 2.2) for n row blocks: tasks partial_sum(i, j) (id 4 i + j, notifies E[i])
+// and final_sum(i) (id 4 n + i, waits on E[i]), dealt round-robin to the queues (task id mod queues, Sec. 3.1),
+// E[i] armed with its 4 producers.  Clears the error word.  Everything the launch reads is rewritten here,
+// so nothing of an earlier call survives.
+__global__ void rowsum_noalloc_plan(Task *tasks, int32_t *queue_begin, int32_t *ev, int32_t *error_word, int n, int n_queues,
+                                    int ev_stride)
+{
+    const int total = 5 * n, full = total / n_queues, rem = total % n_queues;
+    const int gid = blockIdx.x * blockDim.x + threadIdx.x, stride = gridDim.x * blockDim.x;
+    for (int t = gid; t < total; t += stride) {
+        const int q = t % n_queues, k = t / n_queues;
+        const int pos = q * full + (q < rem ? q : rem) + k;
+        Task r{};
+        r.wait0 = r.wait1 = r.notify0 = -1;
+        r.id = t;
+        if (t < 4 * n) { r.fn = FN_ROWSUM_PARTIAL; r.c0 = t >> 2; r.c1 = t & 3; r.notify0 = t >> 2; }
+        else { r.fn = FN_ROWSUM_FINAL; r.c0 = t - 4 * n; r.wait0 = t - 4 * n; }
+        tasks[pos] = r;
+    }
+    for (int q = gid; q <= n_queues; q += stride) queue_begin[q] = q * full + (q < rem ? q : rem);
+    for (int i = gid; i < n; i += stride) {
+        ev[i] = 4;                      // cur
+        ev[ev_stride + i] = 4;          // init (the megakernel copies it into `next`)
+    }
+    if (gid < 4) error_word[gid] = 0;
+}
+
+hipError_t configure_kernels();
+hipError_t max_resident_workgroups(int *per_cu);
+
+namespace {
+struct NoAllocDevice {
+    bool ready = false;
+    unsigned char *ptr = nullptr;       // this device's copy of `scratch`
+    int n_queues = 0;
+};
+NoAllocDevice g_noalloc[64];
+}  // namespace
+
+// Per device, once: the array's address on that device, the kernels' LDS attribute, the queue count.
+static hipError_t noalloc_device(NoAllocDevice **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    NoAllocDevice &d = g_noalloc[dev];
+    if (!d.ready) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        e = configure_kernels();
+        if (e != hipSuccess) return e;
+        int cus = 0, per_cu = 0;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        e = max_resident_workgroups(&per_cu);
+        if (e != hipSuccess) return e;
+        if (per_cu < 1 || cus < 1) return hipErrorLaunchOutOfResources;
+        d.ptr = (unsigned char *)p;
+        d.n_queues = cus < kNoAllocMaxQueues ? cus : kNoAllocMaxQueues;
+        d.ready = true;
+    }
+    *out = &d;
+    return hipSuccess;
+}
+
+hipError_t launch_rowsum_noalloc(const float *A, float *C, int n, hipStream_t s)
+{
+    NoAllocDevice *d = nullptr;
+    hipError_t e = noalloc_device(&d);
+    if (e != hipSuccess) return e;
+    unsigned char *base = d->ptr;            // never the array's name: that is not a device address on the host
+    Task *tasks = reinterpret_cast<Task *>(base + kNaOffTasks);
+    int32_t *queue_begin = reinterpret_cast<int32_t *>(base + kNaOffQueueBegin);
+    int32_t *ev = reinterpret_cast<int32_t *>(base + kNaOffEvents);
+    int32_t *error_word = reinterpret_cast<int32_t *>(base + kNaOffError);
+    const int plan_threads = 256, plan_blocks = (5 * n + plan_threads - 1) / plan_threads + 4;
+    hipLaunchKernelGGL(rowsum_noalloc_plan, dim3(plan_blocks), dim3(plan_threads), 0, s, tasks, queue_begin, ev, error_word, n,
+                       d->n_queues, kNoAllocMaxN);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    Params P{};
+    P.gbuf[0] = const_cast<float *>(A);
+    P.gbuf[1] = reinterpret_cast<float *>(base + kNaOffB);
+    P.gbuf[2] = C;
+    P.ev_cur = ev;
+    P.ev_init = ev + kNoAllocMaxN;
+    P.ev_next = ev + 2 * kNoAllocMaxN;
+    P.n_events = n;
+    P.tasks = tasks;
+    P.queue_begin = queue_begin;
+    P.n_queues = d->n_queues;
+    P.spin_budget = 2000000;
+    P.error_word = error_word;
+    P.gsym[0] = n;
+    hipLaunchKernelGGL(megakernel_static<KIND_GENERIC>, dim3(P.n_queues), dim3(kWgThreads), kLdsBytes, s, P);
+    return hipGetLastError();
 }
 
 }  // namespace etc

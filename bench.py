@@ -21,6 +21,52 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 HBM_PEAK_GBS = 8000.0
 
 
+FN_NAMES = {3: "load_hidden", 4: "qkv", 5: "attn_chunk", 6: "attn_merge", 7: "o_proj", 8: "gate_up", 9: "down",
+            10: "router_logits", 11: "router", 12: "moe_gate_up", 13: "moe_down", 14: "combine", 15: "o_proj_sum",
+            16: "down_sum"}
+
+
+def print_timeline(dec, etc, shape, args, B, L, f):
+    """Per stage of one layer, from the per-task device trace of the last launch: number of tasks and queues
+    (= compute units) that ran them, first task start, last weight-loop start, last loop end, last notify (us
+    from the layer's first task start), the weight bytes the stage streams and the rate over its span."""
+    import numpy as np
+    info = dec.step_info()
+    tr = dec.task_trace().astype(np.int64)
+    plan = etc.plan_build(shape, args.kv_chunk, info.sampled_batch, int(info.n_queues), L + 1, kind=dec.kind)
+    tasks = plan["tasks"]
+    khz = float(info.wall_clock_khz)
+    us = lambda t: t / khz * 1e3                                     # noqa: E731
+    layer = args.timeline
+    sel_l = (tasks["layer"] == layer) & (tasks["fn"] != 3) & (tr[tasks["id"], 0] > 0)
+    t0 = tr[tasks["id"][sel_l], 0].min()
+    H, QD, KD, F = shape.H, shape.nq * shape.d, shape.nkv * shape.d, shape.F
+    wbytes = {4: 2 * H * (QD + 2 * KD), 7: 2 * H * QD, 8: 4 * F * H, 9: 2 * F * H, 5: 4 * KD * (L + 1) * B}
+    print(f"# per-stage timeline, layer {layer}, {shape.name} batch {B} kv_len {L}, scheduler {args.sched}; times in us "
+          f"from the layer's first task start", file=f)
+    print("| stage | tasks | CUs | first start | last loop start | last loop end | last notify | MB | GB/s over span |", file=f)
+    print("|---|---|---|---|---|---|---|---|---|", file=f)
+    end_prev = 0.0
+    for fn in sorted(set(tasks["fn"][sel_l].tolist())):
+        sel = sel_l & (tasks["fn"] == fn)
+        T = tr[tasks["id"][sel]]
+        first, notified = us(T[:, 0].min() - t0), us(T[:, 5].max() - t0)
+        staged = T[:, 2][T[:, 2] > 0]
+        looped = T[:, 3][T[:, 3] > 0]
+        ls = f"{us(staged.max() - t0):.1f}" if len(staged) else "-"
+        le = f"{us(looped.max() - t0):.1f}" if len(looped) else "-"
+        mb = wbytes.get(fn, 0) / 1e6
+        rate = f"{wbytes[fn] / ((notified - first) * 1e-6) / 1e9:.0f}" if fn in wbytes and notified > first else "-"
+        print(f"| {FN_NAMES.get(fn, fn)} | {int(sel.sum())} | {len(set(T[:, 7].tolist()))} | {first:.1f} | {ls} | {le} | "
+              f"{notified:.1f} | {mb:.1f} | {rate} |", file=f)
+        end_prev = max(end_prev, notified)
+    nxt = (tasks["layer"] == layer + 1) & (tr[tasks["id"], 0] > 0)
+    if nxt.any():
+        print(f"layer span (first task start of this layer to first task start of the next): "
+              f"{us(tr[tasks['id'][nxt], 0].min() - t0):.1f} us; last notify of the layer at {end_prev:.1f} us", file=f)
+    print(f"whole step: {us(tr[:, 5].max() - tr[:, 0][tr[:, 0] > 0].min()):.1f} us (with tracing on)", file=f)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -34,6 +80,10 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-comparators", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=0, help="layers the CPU oracle runs (0 = all)")
+    ap.add_argument("--timeline", type=int, default=-1, metavar="LAYER",
+                    help="also print a per-stage timeline of that layer from the per-task device trace (to stderr)")
+    ap.add_argument("--bind-every-step", action="store_true",
+                    help="also time a chain of steps whose kv_len grows by one, each bound before its launch")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -133,6 +183,43 @@ def main() -> int:
         torch.cuda.synchronize()
         result["calib_copy_bytes"] = 1 << 30
         del src, dst
+
+    # ---- the cost of binding a step on the real per-step path: kv_len grows by one every step -------------
+    if args.bind_every_step or not args.no_comparators:
+        K = args.steps
+        chain = [fixed_step(shape, B, [max(0, L - K + 1 + i)] * B, n_pool, seed=7) for i in range(K)]
+        for st_ in chain[:3]:
+            dec.bind_step(st_)
+            dec.launch(x, out)
+        torch.cuda.synchronize()
+        ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t_bind = 0.0
+        ea.record()
+        for st_ in chain:
+            t1 = time.perf_counter()
+            dec.bind_step(st_)
+            t_bind += time.perf_counter() - t1
+            dec.launch(x, out)
+        eb.record()
+        torch.cuda.synchronize()
+        incl = ea.elapsed_time(eb) * 1e3 / K
+        # the same chain of shapes launched without the binds in the timed region is not possible (the shapes
+        # differ), so the reference is the chain's own device time per step against the host time spent binding
+        result["bind_step_us"] = round(t_bind / K * 1e6, 2)
+        result["step_incl_bind_us"] = round(float(incl), 2)
+        dec.bind_step(step)
+
+    # ---- per-stage timeline of one layer from the per-task device trace -------------------------------------
+    if args.timeline >= 0:
+        tdec = etc.Decoder(shape, kv_chunk_tokens=args.kv_chunk, sampled_batches=[B], max_kv_len=L + 1, kind=kind,
+                           debug_flags=etc.DEBUG_TRACE)
+        model.bind(tdec)
+        tdec.bind_step(step)
+        for _ in range(3):
+            tdec.launch(x, out)
+        torch.cuda.synchronize()
+        print_timeline(tdec, etc, shape, args, B, L, sys.stderr)
+        tdec.close()
 
     # ---- comparators on identical task bodies -------------------------------------------------------
     if not args.no_comparators:

@@ -19,7 +19,24 @@
  *
  * Conventions.  Plain C, no exceptions cross the boundary.  Every call returns an
  * etc_status; etc_last_error() gives the text.  A context is not thread-safe and
- * has one step in flight at a time.  Pointers marked "device" are device memory
+ * has one step in flight at a time: all launches of a context go to one stream, or the caller
+ * orders them (the step's shape arrays, activations and event tensors are one set per context).
+ *
+ * Co-residency.  Tasks spin on events other workgroups notify (Sec. 3.3), so every persistent
+ * workgroup of a launch must be resident at once: the library launches one per compute unit
+ * (each takes nearly all of a unit's LDS) and needs the device to itself for the duration of a
+ * launch.  A kernel of another stream or process that holds compute units while a megakernel
+ * starts can keep some of its workgroups from becoming resident; their peers' waits then run
+ * out of their spin budget and the launch ends with ETC_ETIMEOUT rather than hanging.
+ * etc_create returns ETC_ESTATE when the device cannot hold the requested queues at all.
+ *
+ * Device errors.  A wait that exceeds its spin budget, a full ready queue or a bad run-time table
+ * records an error word and the kernel drains (tasks still run, on stale data: the outputs of
+ * that launch are garbage).  The first call that notices (etc_read_debug, or the next
+ * etc_bind_step / etc_launch / etc_graph_launch after the launch has finished) returns
+ * ETC_ETIMEOUT; from then on the context is dead: launches and binds return ETC_ESTATE and only
+ * etc_read_debug and etc_destroy are useful (a generic-graph context is revived by
+ * etc_graph_bind_shape, which rebuilds all launch state).  Pointers marked "device" are device memory
  * of the current HIP device, borrowed: the caller owns them and keeps them alive
  * until the last launch that uses them has finished.  Pointers marked "host" are
  * read during the call only.  The library owns all scratch (activations, event
@@ -120,6 +137,8 @@ typedef struct {
     const void *ed;  /* [n_experts, hidden, moe_ffn] */
 } etc_layer_weights;
 
+/* Resident tensors of the decoder of Sec. 4.3 (attention, RoPE, norms, MLP or MoE block): recorded, not copied;
+ * every weight byte is read once per step.  All pointers 16-byte aligned.  May be called again between steps. */
 etc_status etc_bind_layer_weights(etc_ctx *ctx, int32_t layer, const etc_layer_weights *w);
 
 /* Paged KV cache, device, bf16: [layer][page][page_size][n_kv_heads][head_dim] for K and for V.
@@ -129,20 +148,29 @@ etc_status etc_bind_kv_pool(etc_ctx *ctx, void *k_pages, void *v_pages, int64_t 
 /* Dynamic shape parameters of the next step(s) (Sec. 2.3).  kv_len[b] = tokens already cached:
  * the new token has position kv_len[b], is appended there and attends to kv_len[b]+1 keys.
  * Sequence b owns page_ids[page_indptr[b] .. page_indptr[b+1]) = ceil((kv_len[b]+1)/page_size)
- * pages.  All three arrays are host memory, copied during the call.  Never needs a re-create
- * for batch <= max_batch and kv_len < max_kv_len.  Synchronises with earlier launches. */
+ * pages.  All three arrays are host memory, copied during the call (into pinned staging; they reach
+ * the device by one asynchronous copy on the stream of the next launch).  Never needs a re-create
+ * for batch <= max_batch and kv_len < max_kv_len (Sec. 2.3: one template, any shape), does not
+ * synchronise with the device and launches nothing: it is cheap enough to run before every decode
+ * step.  When the bound batch moves to another sampled batch size (Sec. 3.1), the next launch is
+ * preceded by one small kernel that arms the event tensors with that plan's counts. */
 etc_status etc_bind_step(etc_ctx *ctx, int32_t batch, const int32_t *kv_len, const int32_t *page_indptr,
                          const int32_t *page_ids);
 
-/* Test hook for MoE parity: layer's routing follows ids [batch, top_k] (host) instead of the
- * device top-k; ids == NULL removes the override.  Takes effect at the next launch. */
-etc_status etc_force_routing(etc_ctx *ctx, int32_t layer, const int32_t *ids);
+/* Test hook for MoE parity (Sec. 2.4: topk is a run-time tensor): layer's routing follows ids
+ * [batch, top_k] (host) instead of the device top-k; with w != NULL the routing weights are w
+ * [batch, top_k] (host) instead of the softmax over the selected logits.  ids == NULL removes the
+ * override (w is then ignored).  Synchronises; takes effect at the next launch. */
+etc_status etc_force_routing(etc_ctx *ctx, int32_t layer, const int32_t *ids, const float *w);
 
 /* ---- launch --------------------------------------------------------------------------- */
 
-/* One decode step = one kernel launch on hip_stream (a hipStream_t, may be NULL); asynchronous.
+/* One decode step = one launch of the fused persistent kernel on hip_stream (a hipStream_t, may be NULL),
+ * asynchronous: the scheduling transformations of Sec. 3.1 (static queues, notify / wait) or Sec. 3.2 (ready
+ * queue, push / pop) applied to the whole decoder graph.  After a bind the launch is preceded on the same
+ * stream by the copy of the step's shape arrays (and, after a change of plan, the arming kernel).
  * hidden_in / hidden_out: device, bf16 [batch, hidden]; may alias.  May be called repeatedly
- * for one bind: the event tensors are re-armed inside the kernel. */
+ * for one bind: the event tensors are re-armed inside the kernel (Sec. 3.3 leaves the reset open). */
 etc_status etc_launch(etc_ctx *ctx, const void *hidden_in, void *hidden_out, void *hip_stream);
 
 /* The same task bodies, one ordinary kernel launch per operator stage (the kernel-by-kernel
@@ -166,9 +194,14 @@ typedef enum {
                                     6 unused, 7 queue (workgroup) that ran the task (needs ETC_DEBUG_TRACE) */
 } etc_debug_kind;
 
+/* Evidence for the invariants of Sec. 3.3 (every counter drained, every task run once), the per-layer
+ * parity checks and the run-time tensors of Sec. 2.4.  host_dst: host memory, bytes <= the item's size.
+ * Synchronises the device.  Returns ETC_ETIMEOUT if the device recorded an error (the error word itself
+ * can always be read). */
 etc_status etc_read_debug(etc_ctx *ctx, int32_t kind, int32_t layer, void *host_dst, size_t bytes);
 
-/* Sizes of the bound step's instantiated graph. */
+/* Sizes of the bound step's instantiated graph (Sec. 2.3: the template bound to concrete shapes) and the
+ * bytes the roofline of the step is priced with.  No device call. */
 typedef struct {
     int64_t n_tasks, n_events, n_queues;
     int64_t algorithmic_bytes; /* weights touched once + live KV once + appended rows, this step */

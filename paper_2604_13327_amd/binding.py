@@ -112,7 +112,7 @@ def lib():
     L.etc_bind_layer_weights.argtypes = [C.c_void_p, C.c_int32, C.POINTER(LayerWeights)]
     L.etc_bind_kv_pool.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64]
     L.etc_bind_step.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
-    L.etc_force_routing.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+    L.etc_force_routing.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
     L.etc_launch.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     L.etc_launch_kernel_by_kernel.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     L.etc_read_debug.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t]
@@ -199,6 +199,9 @@ class _Ctx:
         self._check(self._L.etc_read_debug(self._h, kind, layer, out.ctypes.data, out.nbytes))
         return out
 
+    def error_word(self):
+        return self.read_debug(DBG_ERROR_WORD, 0, np.zeros(4, np.int32))
+
 
 class Decoder(_Ctx):
     """describe -> bind -> launch for a decoder model (see include/etc.h)."""
@@ -238,12 +241,13 @@ class Decoder(_Ctx):
         self._check(self._L.etc_bind_step(self._h, step.batch, kv.ctypes.data, ip.ctypes.data, ids.ctypes.data))
         self.batch = step.batch
 
-    def force_routing(self, layer: int, ids):
+    def force_routing(self, layer: int, ids, weights=None):
         if ids is None:
-            self._check(self._L.etc_force_routing(self._h, layer, None))
+            self._check(self._L.etc_force_routing(self._h, layer, None, None))
         else:
             a = _i32(ids)
-            self._check(self._L.etc_force_routing(self._h, layer, a.ctypes.data))
+            w = None if weights is None else np.ascontiguousarray(weights, dtype=np.float32)
+            self._check(self._L.etc_force_routing(self._h, layer, a.ctypes.data, None if w is None else w.ctypes.data))
 
     def launch(self, hidden_in, hidden_out, stream=None):
         self._check(self._L.etc_launch(self._h, hidden_in.data_ptr(), hidden_out.data_ptr(), _stream_ptr(stream)))
@@ -258,9 +262,6 @@ class Decoder(_Ctx):
         return info
 
     # evidence / debug
-    def error_word(self):
-        return self.read_debug(DBG_ERROR_WORD, 0, np.zeros(4, np.int32))
-
     def event_counters(self):
         return self.read_debug(DBG_EVENT_COUNTERS, 0, np.zeros(self.step_info().n_events, np.int32))
 

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libetc.so")
 SOURCES = ["api.cpp", "graph.cpp", "megakernel.hip"]
-HEADERS = ["etc_types.h", "graph.h", "device_rt.hip.h", "task_gemm.hip.h", "task_attn.hip.h", "task_moe.hip.h"]
+HEADERS = ["etc_types.h", "arm_args.h", "graph.h", "device_rt.hip.h", "task_gemm.hip.h", "task_attn.hip.h", "task_moe.hip.h"]
 
 
 def needs_build() -> bool:

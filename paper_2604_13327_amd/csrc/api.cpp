@@ -12,6 +12,7 @@
 #include "../../include/etc.h"
 #include "etc_types.h"
 #include "graph.h"
+#include "arm_args.h"
 
 namespace etc {
 hipError_t configure_kernels();
@@ -20,6 +21,7 @@ hipError_t launch_static(const Params &P, hipStream_t s);
 hipError_t launch_dynamic(const Params &P, hipStream_t s);
 hipError_t launch_stage(const Params &P, int first, int count, hipStream_t s);
 hipError_t launch_rowsum_noalloc(const float *A, float *C, int n, hipStream_t s);
+hipError_t launch_arm(const ArmArgs &a, hipStream_t s);
 }  // namespace etc
 
 using namespace etc;
@@ -88,7 +90,7 @@ struct etc_ctx {
     LayerWeights *d_weights = nullptr;
     bool weights_dirty = true;
     Params base{};                          // device pointers and constants filled at create
-    int32_t *d_events = nullptr;            // [3][n_events_max]: A | init | B
+    int32_t *d_events = nullptr;            // [2][n_events_max]: A | B (a launch drains one and re-arms the other)
     int32_t *d_disp = nullptr;              // [2][n_events_max]: dispatch counters of the dynamic scheduler, A | B
     int32_t *d_pending = nullptr;           // [n_tasks_max]: dynamic scheduler, waited events passed per task
     size_t n_tasks_max = 0;
@@ -96,8 +98,23 @@ struct etc_ctx {
     int parity = 0;
     uint32_t epoch = 1;
     int32_t *d_qctrl = nullptr;             // [2][8]
-    int32_t *d_kv_len = nullptr, *d_page_indptr = nullptr, *d_page_ids = nullptr;
+    int32_t *d_kv_len = nullptr, *d_page_indptr = nullptr, *d_page_ids = nullptr;   // parts of d_step
+    // Step shapes travel host -> pinned staging slot (during etc_bind_step) -> device block (one asynchronous copy on
+    // the stream of the next launch): binding a step neither synchronises nor touches the device.
+    static constexpr int kStageSlots = 4;
+    int32_t *d_step = nullptr;              // kv_len [max_batch] | page_indptr [max_batch + 1] | page_ids [max_batch * pages]
+    int32_t *h_stage[kStageSlots] = {nullptr, nullptr, nullptr, nullptr};   // pinned, same layout
+    hipEvent_t stage_ev[kStageSlots] = {nullptr, nullptr, nullptr, nullptr}; // recorded behind the slot's upload
+    bool stage_pending[kStageSlots] = {false, false, false, false};
+    int stage_slot = 0;
+    size_t stage_words = 0, stage_used_words = 0;
+    bool step_dirty = false;                // a bound step waits in its staging slot for the next launch
+    bool need_arm = true;                   // the next launch first arms the event tensors from the plan's counts
+    bool need_exec_reset = false;           // ... and clears the execution counts (debug)
+    int32_t *h_error = nullptr;             // pinned, device-visible: the code of the first device error, 0 = none
+    bool dead = false;                      // a device watchdog error was seen: launches are refused from then on
     int32_t *d_forced = nullptr;
+    float *d_forced_w = nullptr;
     uint8_t *d_forced_mask = nullptr;
     std::vector<uint8_t> h_forced_mask;
     int64_t pages_per_layer = 0;
@@ -105,7 +122,7 @@ struct etc_ctx {
     int bound_batch = 0;
     std::vector<int32_t> h_kv_len;
     int64_t algorithmic_bytes = 0;
-    std::string err;
+    std::string err, err_first;
     int sym_values[4] = {0, 0, 0, 0};
 };
 
@@ -169,6 +186,9 @@ etc_status common_device_setup(etc_ctx *c, const etc_sched_desc *s)
     c->sched = *s;
     if (c->sched.spin_budget <= 0) c->sched.spin_budget = 2000000;    // a few seconds of polling, then ETC_ETIMEOUT
     HIP_TRY(c, dev_alloc(&c->base.error_word, 4, c->owned));
+    HIP_TRY(c, hipHostMalloc((void **)&c->h_error, 4 * sizeof(int32_t), hipHostMallocMapped));
+    memset(c->h_error, 0, 4 * sizeof(int32_t));
+    HIP_TRY(c, hipHostGetDevicePointer((void **)&c->base.error_host, c->h_error, 0));
     HIP_TRY(c, dev_alloc(&c->d_qctrl, 16, c->owned));
     return ETC_OK;
 }
@@ -181,7 +201,7 @@ etc_status alloc_events_and_queue(etc_ctx *c)
         n_tasks = std::max(n_tasks, dp.host.tasks.size());
     }
     c->n_events_max = (int)n_ev;
-    HIP_TRY(c, dev_alloc(&c->d_events, 3 * n_ev, c->plan_owned));
+    HIP_TRY(c, dev_alloc(&c->d_events, 2 * n_ev, c->plan_owned));
     HIP_TRY(c, dev_alloc(&c->d_disp, 2 * n_ev, c->plan_owned));
     HIP_TRY(c, dev_alloc(&c->d_pending, n_tasks, c->plan_owned));
     c->n_tasks_max = n_tasks;
@@ -192,22 +212,33 @@ etc_status alloc_events_and_queue(etc_ctx *c)
     return ETC_OK;
 }
 
-// Arms the event tensors for the bound plan: `init` and the buffer the next launch will use.
-etc_status arm_events(etc_ctx *c)
+// Arms the event tensors for the bound plan on the stream of the launch that follows: a small fill kernel, no
+// memset or copy nodes, so the same sequence can sit in a captured graph.  Needed before the first launch of a
+// context and whenever the bound plan changes (the kernel itself re-arms the other buffer for the next launch
+// of the SAME plan, so a bind that keeps the plan costs the device nothing).
+etc_status arm_on_stream(etc_ctx *c, hipStream_t s)
 {
+    if (!c->need_arm && !c->need_exec_reset) return ETC_OK;
     const DevPlan &dp = c->plans[c->cur_plan];
-    const size_t n = dp.host.ev_init.size(), N = (size_t)c->n_events_max;
-    int32_t *init = c->d_events + N, *cur = c->d_events + (c->parity ? 2 * N : 0);
-    if (n) {
-        HIP_TRY(c, hipMemcpy(init, dp.host.ev_init.data(), n * sizeof(int32_t), hipMemcpyHostToDevice));
-        HIP_TRY(c, hipMemcpy(cur, dp.host.ev_init.data(), n * sizeof(int32_t), hipMemcpyHostToDevice));
-        HIP_TRY(c, hipMemcpy(c->d_disp + (c->parity ? N : 0), dp.host.ev_init.data(), n * sizeof(int32_t),
-                             hipMemcpyHostToDevice));
+    const size_t N = (size_t)c->n_events_max;
+    ArmArgs a{};
+    if (c->need_arm) {
+        a.ev_cur = c->d_events + (c->parity ? N : 0);
+        a.ev_init = dp.d_ev_init;
+        a.n_events = (int)dp.host.ev_init.size();
+        a.disp_cur = c->d_disp + (c->parity ? N : 0);
+        a.pending = c->d_pending;
+        a.n_pending = (int)c->n_tasks_max;
+        a.exp_event = c->base.exp_event;
+        a.n_exp = c->base.exp_event ? c->base.E : 0;
+        a.qctrl = c->d_qctrl + (c->parity ? 8 : 0);
     }
-    HIP_TRY(c, hipMemset(c->d_pending, 0, c->n_tasks_max * sizeof(int32_t)));
-    if (c->base.exp_event) HIP_TRY(c, hipMemset(c->base.exp_event, 0, (size_t)c->base.E * sizeof(int32_t)));
-    HIP_TRY(c, hipMemset(c->d_qctrl + (c->parity ? 8 : 0), 0, 8 * sizeof(int32_t)));
-    if (c->base.exec_count) HIP_TRY(c, hipMemset(c->base.exec_count, 0, dp.host.tasks.size() * sizeof(int32_t)));
+    if (c->base.exec_count) {
+        a.exec_count = c->base.exec_count;
+        a.n_exec = (int)dp.host.tasks.size();
+    }
+    HIP_TRY(c, launch_arm(a, s));
+    c->need_arm = c->need_exec_reset = false;
     return ETC_OK;
 }
 
@@ -216,9 +247,9 @@ void fill_launch_params(etc_ctx *c, Params &P)
     const DevPlan &dp = c->plans[c->cur_plan];
     const size_t N = (size_t)c->n_events_max;
     P = c->base;
-    P.ev_cur = c->d_events + (c->parity ? 2 * N : 0);
-    P.ev_init = c->d_events + N;
-    P.ev_next = c->d_events + (c->parity ? 0 : 2 * N);
+    P.ev_cur = c->d_events + (c->parity ? N : 0);
+    P.ev_init = dp.d_ev_init;
+    P.ev_next = c->d_events + (c->parity ? 0 : N);
     P.n_events = (int)dp.host.ev_init.size();
     P.tasks = dp.d_queue_tasks;
     P.queue_begin = dp.d_queue_begin;
@@ -260,6 +291,7 @@ void fill_launch_params(etc_ctx *c, Params &P)
     P.weights = c->d_weights;
     P.forced_topk = c->d_forced;
     P.forced_mask = c->d_forced_mask;
+    P.forced_w = c->d_forced_w;
     for (int i = 0; i < 4; ++i) P.gsym[i] = c->sym_values[i];
 }
 
@@ -271,7 +303,23 @@ etc_status check_error_word(etc_ctx *c)
         char buf[200];
         snprintf(buf, sizeof(buf), "device watchdog: code %d in task function %d, event/ticket %d, queue %d", w[0],
                  w[1], w[2], w[3]);
+        c->dead = true;
         return fail(c, ETC_ETIMEOUT, buf);
+    }
+    return ETC_OK;
+}
+
+// Non-blocking look at the error code the device mirrors into pinned host memory: what finished launches raised.
+// The first call that sees an error reports it as ETC_ETIMEOUT; from then on the context refuses to launch
+// (ETC_ESTATE): a kernel that drained on an error leaves counters, queue words and activations inconsistent.
+etc_status refuse_if_dead(etc_ctx *c)
+{
+    if (c->dead) return fail(c, ETC_ESTATE, "the context is dead after a device watchdog error (" + c->err_first + "); destroy it");
+    const int32_t code = *(volatile int32_t *)c->h_error;
+    if (code != 0) {
+        c->dead = true;
+        c->err_first = "device watchdog: code " + std::to_string(code) + " (read ETC_DBG_ERROR_WORD for the task, event and queue)";
+        return fail(c, ETC_ETIMEOUT, c->err_first);
     }
     return ETC_OK;
 }
@@ -287,13 +335,31 @@ etc_status sync_weights(etc_ctx *c)
     return ETC_OK;
 }
 
-etc_status pre_launch(etc_ctx *c, const void *hidden_in, void *hidden_out, Params &P)
+// The bound step's shapes, waiting in their pinned staging slot: one asynchronous copy on the launch stream.
+etc_status upload_step_on_stream(etc_ctx *c, hipStream_t s)
+{
+    if (!c->step_dirty) return ETC_OK;
+    const int slot = c->stage_slot;
+    HIP_TRY(c, hipMemcpyAsync(c->d_step, c->h_stage[slot], c->stage_used_words * sizeof(int32_t), hipMemcpyHostToDevice, s));
+    HIP_TRY(c, hipEventRecord(c->stage_ev[slot], s));
+    c->stage_pending[slot] = true;
+    c->step_dirty = false;
+    return ETC_OK;
+}
+
+etc_status pre_launch(etc_ctx *c, const void *hidden_in, void *hidden_out, Params &P, hipStream_t s)
 {
     if (!c || c->is_graph) return fail(c, ETC_EINVAL, "not a decoder context");
     if (!hidden_in || !hidden_out) return fail(c, ETC_EINVAL, "hidden_in / hidden_out is NULL");
     if (!c->kv_bound) return fail(c, ETC_ESTATE, "no KV pool bound");
     if (!c->step_bound) return fail(c, ETC_ESTATE, "no step bound");
-    etc_status st = sync_weights(c);
+    etc_status st = refuse_if_dead(c);
+    if (st != ETC_OK) return st;
+    st = sync_weights(c);
+    if (st != ETC_OK) return st;
+    st = upload_step_on_stream(c, s);
+    if (st != ETC_OK) return st;
+    st = arm_on_stream(c, s);
     if (st != ETC_OK) return st;
     fill_launch_params(c, P);
     P.hidden_in = (const uint16_t *)hidden_in;
@@ -320,6 +386,11 @@ void etc_destroy(etc_ctx *ctx)
     (void)hipDeviceSynchronize();
     for (void *p : ctx->owned) (void)hipFree(p);
     for (void *p : ctx->plan_owned) (void)hipFree(p);
+    for (int i = 0; i < etc_ctx::kStageSlots; ++i) {
+        if (ctx->h_stage[i]) (void)hipHostFree(ctx->h_stage[i]);
+        if (ctx->stage_ev[i]) (void)hipEventDestroy(ctx->stage_ev[i]);
+    }
+    if (ctx->h_error) (void)hipHostFree(ctx->h_error);
     delete ctx;
 }
 
@@ -400,8 +471,19 @@ etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc
                A(&P.part_m, MB * m->n_q_heads * (size_t)c->max_chunks) &&
                A(&P.part_l, MB * m->n_q_heads * (size_t)c->max_chunks) &&
                A(&P.part_o, MB * m->n_q_heads * (size_t)c->max_chunks * m->head_dim) &&
-               A(&c->d_kv_len, MB) && A(&c->d_page_indptr, MB + 1) && A(&c->d_page_ids, MB * (size_t)c->max_pages_per_seq) &&
                A(&c->d_weights, (size_t)m->n_layers);
+    if (okk) {   // the step's shapes: one device block, and pinned staging slots of the same layout
+        c->stage_words = MB + (MB + 1) + MB * (size_t)c->max_pages_per_seq;
+        okk = A(&c->d_step, c->stage_words);
+        c->d_kv_len = c->d_step;
+        c->d_page_indptr = c->d_step + MB;
+        c->d_page_ids = c->d_step + 2 * MB + 1;
+        for (int i = 0; okk && i < etc_ctx::kStageSlots; ++i) {
+            okk = hipHostMalloc((void **)&c->h_stage[i], c->stage_words * sizeof(int32_t), hipHostMallocDefault) == hipSuccess &&
+                  hipEventCreateWithFlags(&c->stage_ev[i], hipEventDisableTiming) == hipSuccess;
+            if (!okk) c->err = "pinned staging allocation failed";
+        }
+    }
     if (okk) {   // RoPE inverse frequencies theta^(-2i/d) in double
         std::vector<double> inv((size_t)m->head_dim / 2);
         for (size_t i = 0; i < inv.size(); ++i) inv[i] = pow((double)m->rope_theta, -2.0 * (double)i / (double)m->head_dim);
@@ -489,17 +571,28 @@ etc_status etc_bind_step(etc_ctx *c, int32_t batch, const int32_t *kv_len, const
         if (c->plans[i].sampled_batch >= batch) { plan = (int)i; break; }
     if (plan < 0) return fail(c, ETC_EINVAL, "no sampled batch size covers this batch");
 
-    HIP_TRY(c, hipDeviceSynchronize());
-    etc_status st = check_error_word(c);
+    etc_status st = refuse_if_dead(c);
     if (st != ETC_OK) return st;
-    HIP_TRY(c, hipMemcpy(c->d_kv_len, kv_len, (size_t)batch * sizeof(int32_t), hipMemcpyHostToDevice));
-    HIP_TRY(c, hipMemcpy(c->d_page_indptr, page_indptr, (size_t)(batch + 1) * sizeof(int32_t), hipMemcpyHostToDevice));
-    HIP_TRY(c, hipMemcpy(c->d_page_ids, page_ids, (size_t)n_ids * sizeof(int32_t), hipMemcpyHostToDevice));
+    // The arrays go to a pinned staging slot now and to the device on the stream of the next launch.  A slot is
+    // reused only after the copy that last read it has finished (four slots: normally long done).
+    if (!c->step_dirty) c->stage_slot = (c->stage_slot + 1) % etc_ctx::kStageSlots;      // else: never launched, overwrite
+    const int slot = c->stage_slot;
+    if (c->stage_pending[slot]) {
+        HIP_TRY(c, hipEventSynchronize(c->stage_ev[slot]));
+        c->stage_pending[slot] = false;
+    }
+    const size_t MB = (size_t)c->sched.max_batch;
+    int32_t *stg = c->h_stage[slot];
+    memcpy(stg, kv_len, (size_t)batch * sizeof(int32_t));
+    memcpy(stg + MB, page_indptr, (size_t)(batch + 1) * sizeof(int32_t));
+    memcpy(stg + 2 * MB + 1, page_ids, (size_t)n_ids * sizeof(int32_t));
+    c->stage_used_words = 2 * MB + 1 + (size_t)n_ids;
+    c->step_dirty = true;
+    if (plan != c->cur_plan) c->need_arm = true;      // other counts: the buffer the last launch re-armed does not fit
+    if (c->base.exec_count) c->need_exec_reset = true;
     c->cur_plan = plan;
     c->bound_batch = batch;
     c->h_kv_len.assign(kv_len, kv_len + batch);
-    st = arm_events(c);
-    if (st != ETC_OK) return st;
 
     // algorithmic bytes: every touched weight once, every live KV byte once, appended rows written
     const etc_model_desc &m = c->model;
@@ -513,13 +606,14 @@ etc_status etc_bind_step(etc_ctx *c, int32_t batch, const int32_t *kv_len, const
     return ETC_OK;
 }
 
-etc_status etc_force_routing(etc_ctx *c, int32_t layer, const int32_t *ids)
+etc_status etc_force_routing(etc_ctx *c, int32_t layer, const int32_t *ids, const float *w)
 {
     if (!c || c->is_graph || c->model.n_experts == 0) return fail(c, ETC_EINVAL, "not a MoE context");
     if (layer < 0 || layer >= c->model.n_layers) return fail(c, ETC_EINVAL, "layer out of range");
     const size_t per_layer = (size_t)c->sched.max_batch * c->model.top_k;
     if (!c->d_forced) {
         HIP_TRY(c, dev_alloc(&c->d_forced, per_layer * c->model.n_layers, c->owned));
+        HIP_TRY(c, dev_alloc(&c->d_forced_w, per_layer * c->model.n_layers, c->owned));
         HIP_TRY(c, dev_alloc(&c->d_forced_mask, (size_t)c->model.n_layers, c->owned));
         c->h_forced_mask.assign(c->model.n_layers, 0);
     }
@@ -531,7 +625,10 @@ etc_status etc_force_routing(etc_ctx *c, int32_t layer, const int32_t *ids)
         HIP_TRY(c, hipMemcpy(c->d_forced + per_layer * layer, ids, (size_t)c->bound_batch * c->model.top_k * sizeof(int32_t),
                              hipMemcpyHostToDevice));
     }
-    c->h_forced_mask[layer] = ids ? 1 : 0;
+    if (ids && w)
+        HIP_TRY(c, hipMemcpy(c->d_forced_w + per_layer * layer, w, (size_t)c->bound_batch * c->model.top_k * sizeof(float),
+                             hipMemcpyHostToDevice));
+    c->h_forced_mask[layer] = ids ? (w ? 3 : 1) : 0;
     HIP_TRY(c, hipMemcpy(c->d_forced_mask, c->h_forced_mask.data(), c->h_forced_mask.size(), hipMemcpyHostToDevice));
     return ETC_OK;
 }
@@ -539,9 +636,9 @@ etc_status etc_force_routing(etc_ctx *c, int32_t layer, const int32_t *ids)
 etc_status etc_launch(etc_ctx *c, const void *hidden_in, void *hidden_out, void *hip_stream)
 {
     Params P;
-    etc_status st = pre_launch(c, hidden_in, hidden_out, P);
-    if (st != ETC_OK) return st;
     hipStream_t s = (hipStream_t)hip_stream;
+    etc_status st = pre_launch(c, hidden_in, hidden_out, P, s);
+    if (st != ETC_OK) return st;
     if (c->sched.kind == ETC_SCHED_DYNAMIC) {
         if (!kDynamicEnabled) return fail(c, ETC_ESTATE, kDynamicOffMsg);
         HIP_TRY(c, launch_dynamic(P, s));
@@ -555,9 +652,9 @@ etc_status etc_launch(etc_ctx *c, const void *hidden_in, void *hidden_out, void 
 etc_status etc_launch_kernel_by_kernel(etc_ctx *c, const void *hidden_in, void *hidden_out, void *hip_stream)
 {
     Params P;
-    etc_status st = pre_launch(c, hidden_in, hidden_out, P);
-    if (st != ETC_OK) return st;
     hipStream_t s = (hipStream_t)hip_stream;
+    etc_status st = pre_launch(c, hidden_in, hidden_out, P, s);
+    if (st != ETC_OK) return st;
     const Plan &pl = c->plans[c->cur_plan].host;
     P.moe_dd = 0;        // no events and no ready queue here: the router tiles release nothing, every slot task runs
     // one launch per operator stage; the calls of a stage are contiguous in task-id order
@@ -585,7 +682,7 @@ etc_status etc_read_debug(etc_ctx *c, int32_t kind, int32_t layer, void *dst, si
     case ETC_DBG_EVENT_COUNTERS:
         if (c->cur_plan < 0) return fail(c, ETC_ESTATE, "nothing bound");
         // the buffer the last launch consumed is the one the next launch re-arms... it was `cur` before the flip
-        src = c->d_events + (c->parity ? 0 : 2 * N);
+        src = c->d_events + (c->parity ? 0 : N);
         avail = c->plans[c->cur_plan].host.ev_init.size() * sizeof(int32_t);
         break;
     case ETC_DBG_TASK_EXEC_COUNT:
@@ -797,8 +894,12 @@ etc_status etc_graph_bind_shape(etc_ctx *c, const int32_t *values)
     st = alloc_events_and_queue(c);
     if (st != ETC_OK) return st;
     for (int i = 0; i < 4; ++i) c->sym_values[i] = values[i];
-    st = arm_events(c);
-    if (st != ETC_OK) return st;
+    // a rebuilt plan starts from scratch: counters armed by the next launch, an earlier device error forgotten
+    c->need_arm = true;
+    c->need_exec_reset = false;
+    HIP_TRY(c, hipMemset(c->base.error_word, 0, 4 * sizeof(int32_t)));
+    memset(c->h_error, 0, 4 * sizeof(int32_t));
+    c->dead = false;
     c->step_bound = true;
     return ETC_OK;
 }
@@ -841,8 +942,12 @@ etc_status etc_graph_launch(etc_ctx *c, void *hip_stream)
         }
     }
     Params P;
-    fill_launch_params(c, P);
     hipStream_t s = (hipStream_t)hip_stream;
+    etc_status st = refuse_if_dead(c);
+    if (st != ETC_OK) return st;
+    st = arm_on_stream(c, s);
+    if (st != ETC_OK) return st;
+    fill_launch_params(c, P);
     if (c->sched.kind == ETC_SCHED_DYNAMIC) {
         if (!kDynamicEnabled) return fail(c, ETC_ESTATE, kDynamicOffMsg);
         HIP_TRY(c, launch_dynamic(P, s));

@@ -95,6 +95,8 @@ __device__ __forceinline__ void raise_error(const Params &P, int code, int fn, i
         st_i32(P.error_word + 1, fn);
         st_i32(P.error_word + 2, ev);
         st_i32(P.error_word + 3, (int)blockIdx.x);
+        // mirrored to pinned host memory: the host sees it without a device call (one store over the bus, error case only)
+        if (P.error_host != nullptr) __hip_atomic_store(as_global(P.error_host), code, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }
 

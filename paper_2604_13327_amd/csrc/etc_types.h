@@ -26,6 +26,17 @@ constexpr bool staged_fits(int n_tiles, int n_cols, int K)
            (staged_red_floats(n_tiles, n_cols) + kRsFloats) * 4 + (long long)n_cols * (K + kOpPad) * 4 <= (long long)kLdsBytes;
 }
 
+// The (head_dim, query heads per KV head) pairs the attention task bodies are instantiated for.  The device
+// dispatch and the host check both read this one list: a shape outside it is refused at create.
+#define ETC_ATTN_SHAPES(X) X(128, 4) X(128, 8) X(64, 2) X(128, 1) X(64, 4)
+inline bool attn_shape_supported(int head_dim, int group)
+{
+#define ETC_ATTN_SHAPE_TEST(DD, GG) if (head_dim == DD && group == GG) return true;
+    ETC_ATTN_SHAPES(ETC_ATTN_SHAPE_TEST)
+#undef ETC_ATTN_SHAPE_TEST
+    return false;
+}
+
 // Device functions (task bodies).  One entry of the dispatch switch each (Alg. 1 "dispatch logic").
 enum Fn : uint8_t {
     FN_NOP = 0,
@@ -76,7 +87,9 @@ struct LayerWeights {
 };
 
 // Error word codes
-enum : int32_t { ERR_NONE = 0, ERR_WAIT_TIMEOUT = 1, ERR_QUEUE_OVERFLOW = 2, ERR_POP_TIMEOUT = 3, ERR_BAD_TABLE = 4 };
+enum : int32_t { ERR_NONE = 0, ERR_WAIT_TIMEOUT = 1, ERR_QUEUE_OVERFLOW = 2, ERR_POP_TIMEOUT = 3, ERR_BAD_TABLE = 4,
+                 ERR_NO_BODY = 5,        // a task kind or shape the kernel instance has no body for
+                 ERR_LOOP_BOUND = 6 };   // the dynamic dispatch loop ran more iterations than the step has tasks
 
 // Everything the megakernel needs, passed by value as the kernel argument.
 struct Params {
@@ -121,7 +134,8 @@ struct Params {
     uint16_t *eact_hi, *eact_lo;       // expert activations, split [maxB*topk, moeF]
     float *ey;                         // expert outputs fp32 [maxB*topk, H]
     const int32_t *forced_topk;        // [n_layers, maxB, topk] or null
-    const uint8_t *forced_mask;        // [n_layers] or null
+    const uint8_t *forced_mask;        // [n_layers] or null: bit 0 = ids forced, bit 1 = weights forced as well
+    const float *forced_w;             // [n_layers, maxB, topk] or null
     // per-layer copies of the routing data (debug flag 4), or null
     float *dbg_logits, *dbg_topk_w;    // [n_layers, maxB, E], [n_layers, maxB, topk]
     int32_t *dbg_topk_ids, *dbg_perm;  // [n_layers, maxB, topk], [n_layers, maxB*topk]
@@ -162,6 +176,7 @@ struct Params {
     int32_t *exec_count;
     float *layer_hidden;               // [n_layers, maxB, H]
     int32_t *error_word;               // [4]
+    int32_t *error_host;               // pinned host word the first error code is mirrored to (or null)
     uint64_t *trace;                   // [n_tasks][8] wall-clock marks, or null
     // generic-graph buffers (row-sum example)
     float *gbuf[8];                    // 0..2: A, B, C of the row-sum functions; 3..6: int32 route, indptr, count, perm

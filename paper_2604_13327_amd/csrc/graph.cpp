@@ -198,6 +198,8 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
     g = GraphDecl();
     if (m.nq % m.nkv) return "n_q_heads must be a multiple of n_kv_heads";
     if (m.d % 16 || (m.d != 64 && m.d != 128)) return "head_dim must be 64 or 128";
+    if (!attn_shape_supported(m.d, m.nq / m.nkv))
+        return "no attention task body for this (head_dim, n_q_heads / n_kv_heads): supported are 128 with 1, 4, 8 and 64 with 2, 4";
     if (m.H % (kWaves * 32) || (m.nq * m.d) % (kWaves * 32)) return "hidden and n_q_heads*head_dim must be multiples of 256";
     if (m.H % 16) return "hidden must be a multiple of 16";
     if (m.E == 0 && (m.F % (kWaves * 32) || (m.F / 8) % kWaves)) return "ffn must be a multiple of 256";

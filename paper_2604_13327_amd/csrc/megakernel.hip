@@ -8,6 +8,7 @@
 #include <hip/hip_runtime.h>
 
 #include "../../include/etc.h"
+#include "arm_args.h"
 #include "device_rt.hip.h"
 #include "task_attn.hip.h"
 #include "task_gemm.hip.h"
@@ -317,13 +318,16 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
             st.staged_key = -1;      // the attention scratch overlaps the staged operand (the task waits inside)
             const int grp = P.nq / P.nkv;
             const bool lds_pages = P.kv_chunk > 128;      // more than one batch of keys per chunk
+            bool ran = false;
 #define ETC_ATTN(DD, GG)                                                                   \
-    if (P.d == DD && grp == GG) {                                                          \
+    if (!ran && P.d == DD && grp == GG) {                                                  \
+        ran = true;                                                                        \
         if (lds_pages) attn_chunk<DD, GG, true>(PL, t.layer, b, kvh, ch, sm, w0, w1);      \
         else attn_chunk<DD, GG, false>(PL, t.layer, b, kvh, ch, sm, w0, w1);               \
     }
-            ETC_ATTN(128, 4) else ETC_ATTN(128, 8) else ETC_ATTN(64, 2) else ETC_ATTN(128, 1) else ETC_ATTN(64, 4)
+            ETC_ATTN_SHAPES(ETC_ATTN)
 #undef ETC_ATTN
+            if (!ran && threadIdx.x == 0) raise_error(P, ERR_NO_BODY, FN_ATTN, P.d * 256 + grp);   // refused at create; never silently skipped
         }
         break;
     }
@@ -332,11 +336,15 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
         if (b < P.B) {
             wg_wait_cached(P, st, w0, w1, t.fn);
             const int grp = P.nq / P.nkv;
-            if (P.d == 128 && grp == 4) attn_merge<128, 4>(PL, b, kvh);
-            else if (P.d == 128 && grp == 8) attn_merge<128, 8>(PL, b, kvh);
-            else if (P.d == 64 && grp == 2) attn_merge<64, 2>(PL, b, kvh);
-            else if (P.d == 128 && grp == 1) attn_merge<128, 1>(PL, b, kvh);
-            else if (P.d == 64 && grp == 4) attn_merge<64, 4>(PL, b, kvh);
+            bool ran = false;
+#define ETC_MERGE(DD, GG)                                                                  \
+    if (!ran && P.d == DD && grp == GG) {                                                  \
+        ran = true;                                                                        \
+        attn_merge<DD, GG>(PL, b, kvh);                                                    \
+    }
+            ETC_ATTN_SHAPES(ETC_MERGE)
+#undef ETC_MERGE
+            if (!ran && threadIdx.x == 0) raise_error(P, ERR_NO_BODY, FN_MERGE, P.d * 256 + grp);
         }
         break;
     }
@@ -536,7 +544,16 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
     }
     __syncthreads();
     int id = __builtin_amdgcn_readfirstlane(s_task);
+    // The loop has its own bound, whatever the waits inside it do: a workgroup can run each task of the step at
+    // most once, so more iterations than the step has tasks mean the loop is repeating itself (a pop that
+    // never ran, a stale id): the workgroup records the error and leaves, and every wait of the others then
+    // gives up, so the launch drains to ETC_ETIMEOUT instead of spinning for ever.
+    int iterations = 0;
     while (id >= 0) {
+        if (++iterations > P.n_static_tasks + 1) {
+            if (threadIdx.x == 0) raise_error(P, ERR_LOOP_BOUND, 0, id);
+            break;
+        }
         Task t = load_task(P.dyn_tasks + id);
         // MoE with data-dependent events (Sec. 2.4): the router tiles trigger the GroupGEMM-1 tiles of an expert
         // themselves, when the expert's event fires, so those are not pushed when the router tiles are
@@ -573,6 +590,7 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
                     fired = before - 1 == -gld_i32(count + ev);
                     if (fired) st_i32(P.ev_cur + P.dd_event_base + ev, 0);
                 }
+                drain_vmem();        // the counter is back at zero before anything this event releases is published
                 if (__builtin_amdgcn_readfirstlane(fired)) {
                     const int j0 = __builtin_amdgcn_readfirstlane(gld_i32(indptr + ev));
                     const int n = __builtin_amdgcn_readfirstlane(gld_i32(indptr + ev + 1)) - j0;
@@ -615,6 +633,7 @@ __global__ void __launch_bounds__(kWgThreads) stage_kernel(const Params P, int f
     wg_state_init(st);
     run_task<false, KIND>(P, sP, t, sm, st);
 }
+
 
 // ---------------------------------------------------------------------------------------------
 // Allocation-free variant of the row-sum graph launch
@@ -794,6 +813,31 @@ hipError_t launch_static(const Params &P, hipStream_t s)
 hipError_t launch_dynamic(const Params &P, hipStream_t s)
 {
     ETC_LAUNCH_KIND(megakernel_dynamic, dim3(P.n_queues), P)
+    return hipGetLastError();
+}
+
+// Arms the event tensors (and the dynamic scheduler's words) of the step the next launch on this stream runs.
+__global__ void arm_step_kernel(const ArmArgs a)
+{
+    const int gid = blockIdx.x * blockDim.x + threadIdx.x, stride = gridDim.x * blockDim.x;
+    if (a.ev_cur != nullptr)
+        for (int i = gid; i < a.n_events; i += stride) {
+            const int32_t v = a.ev_init[i];
+            a.ev_cur[i] = v;
+            if (a.disp_cur != nullptr) a.disp_cur[i] = v;
+        }
+    if (a.pending != nullptr)
+        for (int i = gid; i < a.n_pending; i += stride) a.pending[i] = 0;
+    if (a.exp_event != nullptr)
+        for (int i = gid; i < a.n_exp; i += stride) a.exp_event[i] = 0;
+    if (a.qctrl != nullptr && gid < 8) a.qctrl[gid] = 0;
+    if (a.exec_count != nullptr)
+        for (int i = gid; i < a.n_exec; i += stride) a.exec_count[i] = 0;
+}
+
+hipError_t launch_arm(const ArmArgs &a, hipStream_t s)
+{
+    hipLaunchKernelGGL(arm_step_kernel, dim3(128), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 

@@ -131,6 +131,8 @@ __device__ __forceinline__ void moe_update_and_trigger(const Params &P, int laye
         n_rel[v] = fired[v] ? (expp[ex[v] + 1] - expp[ex[v]]) * G : 0;
         n_mine += n_rel[v];
     }
+    drain_vmem();            // the fired counters are back at zero before the tasks they release are published:
+                             // nothing released here can reach the next layer's router tiles ahead of the reset
     const int total = wave_sum_i(n_mine);
     if (total == 0) return;
     const int base = q_reserve_wave(P, total);
@@ -167,7 +169,8 @@ __device__ __noinline__ void moe_route_and_group(const Params &P, int layer, int
     ETC_AS_LDS int32_t *til = cnt + kMaxExperts;                                       // [E] row tiles per expert
     ETC_AS_LDS int32_t *tokp = til + kMaxExperts;                                      // [E+1]
     ETC_AS_LDS int32_t *expp = tokp + kMaxExperts + 1;                                 // [E+1]
-    const bool forced = P.forced_mask != nullptr && *as_global(P.forced_mask + layer) != 0;
+    const int forced_bits = P.forced_mask != nullptr ? (int)*as_global(P.forced_mask + layer) : 0;
+    const bool forced = (forced_bits & 1) != 0, forced_w = forced && (forced_bits & 2) != 0 && P.forced_w != nullptr;
     const bool dbg = (P.debug_flags & 4u) != 0 && P.dbg_logits != nullptr;
     const size_t dbg_row = (size_t)layer * P.max_batch + t;
 
@@ -219,11 +222,13 @@ __device__ __noinline__ void moe_route_and_group(const Params &P, int layer, int
             const float p = lane < K ? __expf(my_v - mx) : 0.f;
             const float den = wave_sum(p);
             if (lane < K) {
+                float wgt = p / den;
+                if (forced_w) wgt = *as_global(P.forced_w + ((size_t)layer * P.max_batch + b) * K + lane);
                 st_i32(P.topk_ids + (size_t)t * K + lane, my_id);
-                st_f32(P.topk_w + (size_t)t * K + lane, p / den);
+                st_f32(P.topk_w + (size_t)t * K + lane, wgt);
                 if (dbg) {
                     as_global(P.dbg_topk_ids)[dbg_row * K + lane] = my_id;
-                    as_global(P.dbg_topk_w)[dbg_row * K + lane] = p / den;
+                    as_global(P.dbg_topk_w)[dbg_row * K + lane] = wgt;
                 }
             }
         }

@@ -9,6 +9,10 @@
 // notify E[i], n consumers wait on E[i]) plus one closing task that waits on two events (F, notified by the
 // n consumers, and E[0]).  Three consecutive launches (epochs) without clearing the slots or the per-task
 // counters.  Exit code 0 iff every task ran once, was pushed once, and every counter drained.
+// The dispatch loop carries the device loop's own bound: more iterations than the step has tasks record an
+// error, the workgroup leaves, and every wait of the others gives up on seeing the error.  With the
+// environment variable STALE_WG=<w> workgroup w's pop keeps returning the id it already has (the planted
+// defect: a loop that repeats its task); the run must then END, with exit code 3 (drained on the loop bound).
 #include <atomic>
 #include <cstdint>
 #include <cstdio>
@@ -95,6 +99,8 @@ int main(int argc, char** argv) {
     const int cap = (int)tasks.size() + NWG + 16;
     std::vector<std::atomic<uint64_t>> slots(cap); for (auto& s : slots) s = 0;
     std::vector<std::atomic<int>> pending(tasks.size()); for (auto& p : pending) p = 0;
+    const int stale_wg = getenv("STALE_WG") ? atoi(getenv("STALE_WG")) : -1;
+    std::atomic<int> error_word{0};                    // 6 = loop bound, as on the device
     for (uint32_t epoch = 1; epoch <= 3; ++epoch) {
         std::vector<std::atomic<int>> ev(n_ev), disp(n_ev);
         for (int e = 0; e < n_ev; ++e) { ev[e] = init[e]; disp[e] = init[e]; }
@@ -113,12 +119,15 @@ int main(int argc, char** argv) {
                     uint64_t v = slots[ticket].load(std::memory_order_acquire);
                     if ((uint32_t)(v >> 32) == epoch) return (int)(uint32_t)v - 1;
                     if (ndone.load() >= (int)tasks.size()) return -1;
+                    if (error_word.load() != 0) return -1;
                     std::this_thread::yield();
                     if (++spins > 20000000) { timeouts++; return -1; }
                 }
             };
             int id = wait_slot(head.fetch_add(1));
+            int iterations = 0;
             while (id >= 0) {
+                if (++iterations > (int)tasks.size() + 1) { int z = 0; error_word.compare_exchange_strong(z, 6); break; }
                 const Task& t = tasks[id];
                 const bool last = t.notify0 >= 0 && disp[t.notify0].fetch_sub(1) == 1;   // dispatched: early push
                 if (last)
@@ -126,14 +135,15 @@ int main(int argc, char** argv) {
                         if (c.n_waited == 1 || (pending[c.id].fetch_add(1) + 1) % c.n_waited == 0) push1(c.id);
                 long spins = 0;
                 for (int w : {t.wait0, t.wait1})
-                    if (w >= 0) while (ev[w].load() > 0) { std::this_thread::yield(); if (++spins > 20000000) { timeouts++; break; } }
+                    if (w >= 0) while (ev[w].load() > 0 && error_word.load() == 0) { std::this_thread::yield(); if (++spins > 20000000) { timeouts++; break; } }
                 exec[id]++;
                 if (t.notify0 >= 0) ev[t.notify0].fetch_sub(1);
                 ndone.fetch_add(1);
-                id = wait_slot(head.fetch_add(1));
+                if (wg != stale_wg) id = wait_slot(head.fetch_add(1));
             }
         });
         for (auto& t : th) t.join();
+        if (error_word.load() == 6) { printf("n=%d wgs=%d epoch=%u: drained on the loop bound\n", n, NWG, epoch); return 3; }
         bool ok = timeouts == 0;
         for (auto& e : exec) ok = ok && e == 1; for (auto& e : pushed) ok = ok && e == 1;
         for (auto& e : ev) ok = ok && e == 0; for (auto& e : disp) ok = ok && e == 0;

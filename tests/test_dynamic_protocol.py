@@ -23,3 +23,15 @@ def test_ready_queue_protocol_terminates_and_runs_every_task_once(tmp_path):
                              timeout=120)
         assert out.returncode == 0, out.stdout + out.stderr
         assert out.stdout.count(": ok") == 3
+
+
+def test_dispatch_loop_bound_ends_a_loop_that_repeats_its_task(tmp_path):
+    """The defect that once hung the device loop (a workgroup whose pop never runs, so it repeats one task),
+    planted here on the CPU: the loop's own iteration bound must end the run with an error, not spin."""
+    exe = tmp_path / "dyn_emul"
+    subprocess.check_call(["g++", "-O2", "-std=c++17", "-pthread", "-o", str(exe),
+                           os.path.join(HERE, "dyn_queue_emulation.cpp")])
+    out = subprocess.run([str(exe), "9", "8"], capture_output=True, text=True, timeout=120,
+                         env=dict(os.environ, STALE_WG="2"))
+    assert out.returncode == 3, out.stdout + out.stderr
+    assert "drained on the loop bound" in out.stdout

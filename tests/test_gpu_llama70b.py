@@ -1,7 +1,7 @@
 """Config 5: Llama-3-70B-shaped decoder on ONE GPU (about 137 GB of weights and up to 86 GB of KV pool
 resident in the 288 GB of HBM), batch 32, KV lengths from U[2048, 8192], random permuted page table.
-The whole 80-layer chain runs in one launch; the oracle follows sampled sequences through all layers
-(sequences of a dense decoder do not interact) and is compared per layer and at the end."""
+The whole 80-layer chain runs in one launch; the oracle runs all 32 sequences through all 80 layers and
+is compared per layer and at the end, every row."""
 import numpy as np
 import pytest
 
@@ -14,7 +14,7 @@ MAX_LEN = 8192
 BATCH = 32
 
 
-def test_llama70b_b32_full_chain_matches_oracle_on_sampled_sequences():
+def test_llama70b_b32_full_chain_matches_oracle_on_every_sequence():
     import torch
     import paper_2604_13327_amd as etc
     s = synth.LLAMA3_70B
@@ -47,7 +47,7 @@ def test_llama70b_b32_full_chain_matches_oracle_on_sampled_sequences():
     assert (dec.exec_counts() == 1).all()
     got = bf16_to_f32_np(out)
     gpu_layers = [None] * s.n_layers
-    sel = sorted(rng.choice(BATCH, size=3, replace=False).tolist())
+    sel = list(range(BATCH))
     for l in range(s.n_layers):
         gpu_layers[l] = dec.layer_hidden(l)[sel]
     dec.close()
@@ -63,10 +63,11 @@ def test_llama70b_b32_full_chain_matches_oracle_on_sampled_sequences():
 
     ref = oracle_on_sequences(s, seed, step, sel, 0, weights_of, pools)
     errs = np.array([[rel_err(gpu_layers[l][j], ref["layers"][l][j]) for j in range(len(sel))] for l in range(s.n_layers)])
-    print("kv_len of the sampled sequences:", step.kv_len[sel].tolist())
-    for l in range(0, s.n_layers, 4):
-        print(f"layer {l}: max|err|/rms per sequence {np.array2string(errs[l], precision=5)}", flush=True)
+    print("kv_len of the sequences:", step.kv_len[sel].tolist())
+    for l in range(0, s.n_layers, 8):
+        print(f"layer {l}: max|err|/rms over the sequences: worst {errs[l].max():.3e} (sequence {int(errs[l].argmax())}), "
+              f"median {np.median(errs[l]):.3e}", flush=True)
     worst = float(errs.max())
     assert worst <= TOL, f"layer {int(errs.max(axis=1).argmax())}: {worst}"
     assert rel_err(got[sel], ref["final"]) <= TOL
-    print(f"llama70b B={BATCH}: sequences {sel}, worst per-layer max|err|/rms = {worst:.3e}")
+    print(f"llama70b B={BATCH}: all {len(sel)} sequences, worst per-layer max|err|/rms = {worst:.3e}")

@@ -22,6 +22,11 @@ def _etc():
     return etc
 
 
+def _b():
+    from paper_2604_13327_amd import binding
+    return binding
+
+
 def _launch(dec, model, step, step_index=0, kbk=False):
     import torch
     x = model.hidden(step_index, step.batch)
@@ -104,26 +109,37 @@ def check_moe_step(dec, model, s, step, tile_m, step_index=0, forced=None, layer
     return worst, routes, out
 
 
-def free_running_mismatches(s, model, step, routes, step_index=0, n_layers=None, margin=0.05):
-    """Free-running oracle vs GPU: every selection that differs must be a near tie in the oracle's own
-    logits (the gap between the two candidates below `margin`).  Returns the number of differing sets."""
+def free_running_mismatches(s, model, step, routes, step_index=0, n_layers=None):
+    """Free-running oracle vs GPU.  Tokens of a decoder step do not interact, so a token is followed until its
+    routing first differs (from then on the two sides legitimately compute different things for it).  Up to that
+    point the GPU's router logits of the token differ from the oracle's by rounding noise only, which is measured
+    here; a differing selection is accepted only as a near tie within that noise: every expert chosen by one side
+    alone is within 4 x max|logit_gpu - logit_oracle| (of this token, this layer) of every expert chosen by the
+    other side alone, and that noise itself is small against the logits.  Returns the number of differing sets."""
     import oracle
     n_layers = s.n_layers if n_layers is None else n_layers
     x = synth.hidden_f32(s, model.seed, step_index, step.batch)
     oshape = oracle.shape_of(s)
     n_diff = 0
+    diverged = np.zeros(step.batch, bool)
     for l in range(n_layers):
         w = synth.layer_weights_f32(s, model.seed, l)
         kp, vp = synth.kv_pool_f32(s, model.seed, l, model.n_pool_pages)
         ids, dbg = oracle.layer(oshape, x, w, kp, vp, step.kv_len, step.page_indptr, step.page_ids, debug=True)
         for b in range(step.batch):
+            if diverged[b]:
+                continue
+            lg = dbg["router_logits"][b].astype(np.float64)
+            noise = float(np.abs(routes[l]["logits"][b].astype(np.float64) - lg).max())
+            assert noise <= 2e-2 * float(np.sqrt(np.mean(lg ** 2))), f"layer {l} token {b}: router logits off by {noise}"
             a, g = set(ids[b].tolist()), set(routes[l]["ids"][b].tolist())
             if a != g:
                 n_diff += 1
-                lg = dbg["router_logits"][b]
+                diverged[b] = True
                 only_a, only_g = sorted(a - g), sorted(g - a)
                 gap = max(abs(float(lg[i]) - float(lg[j])) for i in only_a for j in only_g)
-                assert gap < margin, f"layer {l} token {b}: routing differs beyond a near tie (gap {gap})"
+                assert gap <= 4 * noise, (f"layer {l} token {b}: routing differs beyond a near tie "
+                                          f"(gap {gap:.3e}, measured logit noise {noise:.3e})")
     return n_diff
 
 
@@ -169,6 +185,26 @@ def test_tiny_moe_forced_routing_and_skewed_load(tiny_moe_model, kind):
     for l in range(s.n_layers):
         dec.force_routing(l, forced[l])
     check_moe_step(dec, m, s, step, tile_m, forced=forced)
+    # forced routing weights: the last layer's output is affine in them (x_mid + sum_k w_k y_k), so the output for
+    # the mean of two weight vectors is the mean of the two outputs; and forcing the weights the device computed
+    # itself changes nothing, bit for bit
+    last = s.n_layers - 1
+    w_dev = dec.routing_debug(_b().DBG_TOPK_W, last, (B, s.top_k), np.float32).copy()
+    base = dec.layer_hidden(last).copy()
+    outs = []
+    rng = np.random.default_rng(3)
+    wa, wb = rng.random((B, s.top_k), dtype=np.float32), rng.random((B, s.top_k), dtype=np.float32)
+    for wts in (w_dev, wa, wb, (0.5 * (wa.astype(np.float64) + wb)).astype(np.float32)):
+        dec.force_routing(last, forced[last], wts)
+        m.reset_pools()
+        dec.bind_step(step)
+        _launch(dec, m, step)
+        np.testing.assert_array_equal(dec.routing_debug(_b().DBG_TOPK_W, last, (B, s.top_k), np.float32), wts)
+        outs.append(dec.layer_hidden(last).copy())
+    np.testing.assert_array_equal(outs[0], base)
+    mean = 0.5 * (outs[1].astype(np.float64) + outs[2])
+    assert np.abs(outs[3] - mean).max() <= 1e-5 * np.sqrt(np.mean(mean ** 2)) + 1e-6
+    assert np.abs(outs[1] - outs[2]).max() > 1e-3           # the weights do reach the combine
     # removing the override restores the device top-k
     for l in range(s.n_layers):
         dec.force_routing(l, None)

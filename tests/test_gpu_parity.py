@@ -129,6 +129,46 @@ def test_tiny_kv_append_lands_in_the_right_slot(tiny_model):
     dec.close()
 
 
+def test_tiny_three_steps_in_a_row_read_back_their_own_rows(tiny_model):
+    """Chained decode steps on one context, nothing reset in between: kv_len grows by one per step, so steps 2
+    and 3 read the bf16 rows the earlier steps appended to the cache (step 3 also opens a new page).  The oracle
+    runs the same three steps on its own pools, where it appended its own rows (rounded to the cache's bf16
+    here, in the test: the storage format, not arithmetic).  Binding a step between launches neither
+    synchronises nor re-creates anything."""
+    import torch
+    import oracle
+    etc = _etc()
+    s = synth.TINY
+    tiny_model.reset_pools()
+    dec = etc.Decoder(s, kv_chunk_tokens=16, sampled_batches=[2], max_kv_len=129,
+                      debug_flags=etc.DEBUG_EXEC_COUNT | etc.DEBUG_LAYER_HIDDEN, spin_budget=SPIN)
+    tiny_model.bind(dec)
+    L0 = np.array([30, 14], np.int32)                     # 14 -> 15 -> 16: the third step starts a new page
+    npg = [synth.pages_needed(int(l) + 2, s.page) for l in L0]
+    rng = np.random.default_rng(8)
+    owned = rng.permutation(tiny_model.n_pool_pages)[: sum(npg)].astype(np.int32)
+    own = [owned[: npg[0]], owned[npg[0]:]]
+    pools = [list(synth.kv_pool_f32(s, tiny_model.seed, l, tiny_model.n_pool_pages)) for l in range(s.n_layers)]
+    bf16 = lambda a: torch.from_numpy(a).to(torch.bfloat16).to(torch.float32).numpy()      # noqa: E731
+    for t in range(3):
+        kv = L0 + t
+        cnt = [synth.pages_needed(int(l), s.page) for l in kv]
+        indptr = np.concatenate([[0], np.cumsum(cnt)]).astype(np.int32)
+        step = synth.Step(2, kv.astype(np.int32), indptr, np.concatenate([own[b][: cnt[b]] for b in range(2)]).astype(np.int32))
+        out = _run(dec, tiny_model, step, step_index=t)
+        _check_invariants(dec)
+        ref = oracle.decode_step(s, s.n_layers, synth.hidden_f32(s, tiny_model.seed, t, 2), lambda l: synth.layer_weights_f32(s, tiny_model.seed, l),
+                                 lambda l: pools[l], step)
+        for l in range(s.n_layers):
+            assert rel_err(dec.layer_hidden(l), ref["layers"][l]) <= TOL, f"step {t} layer {l}"
+            for b in range(2):                            # the cache holds bf16: round the rows the oracle appended
+                pg, sl = int(own[b][kv[b] // s.page]), int(kv[b] % s.page)
+                for pool in pools[l]:
+                    pool[pg, sl] = bf16(pool[pg, sl])
+        assert rel_err(out, ref["final"]) <= TOL, f"step {t}"
+    dec.close()
+
+
 def test_tiny_all_schedulers_and_kernel_by_kernel_agree_bitwise(tiny_model):
     """Identical task bodies, different scheduling: the results must be identical (paper Sec. 4.5)."""
     etc = _etc()
@@ -221,6 +261,22 @@ def test_watchdog_turns_a_stuck_wait_into_an_error():
     with pytest.raises(etc.EtcError) as ei:
         g.event_counters()
     assert ei.value.status == -5
+    assert g.error_word()[0] == 1              # the error word itself stays readable: a wait ran out of its budget
+    # the context is dead now: a launch is refused on the host instead of running on inconsistent counters
+    with pytest.raises(etc.EtcError) as ei:
+        g.launch()
+    assert ei.value.status == -3
+    # binding a shape rebuilds all launch state and revives a generic-graph context; the same stuck graph times
+    # out again, and this time the launch after it is the first call to notice (through the host-side mirror)
+    g.bind_shape([1])
+    g.launch()
+    torch.cuda.synchronize()
+    with pytest.raises(etc.EtcError) as ei:
+        g.launch()
+    assert ei.value.status == -5
+    with pytest.raises(etc.EtcError) as ei:
+        g.launch()
+    assert ei.value.status == -3
     g.close()
 
 

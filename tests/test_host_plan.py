@@ -186,6 +186,18 @@ def test_descriptor_validation_errors_are_reported():
     assert ei.value.status == -1 and "256" in str(ei.value)
 
 
+def test_attention_shapes_without_a_task_body_are_refused():
+    """The attention task bodies exist for a list of (head_dim, query heads per KV head) pairs; a descriptor outside
+    it must be refused when the plan is built (it used to pass, run no attention body and still notify)."""
+    for nq, nkv, d in ((4, 2, 128), (16, 1, 128), (2, 2, 64), (8, 1, 64)):      # groups 2, 16 (d 128); 1, 8 (d 64)
+        bad = synth.ModelShape("bad", 1, 512, nq, nkv, d, 1024)
+        with pytest.raises(etc.EtcError) as ei:
+            etc.plan_build(bad, 32, 1, 4, max_kv_len=64)
+        assert ei.value.status == -1 and "attention" in str(ei.value)
+    for nq, nkv, d in ((4, 1, 128), (8, 1, 128), (2, 2, 128), (4, 2, 64), (4, 1, 64)):    # every supported pair builds
+        etc.plan_build(synth.ModelShape("ok", 1, 512, nq, nkv, d, 1024), 32, 1, 4, max_kv_len=64)
+
+
 # ---------------------------------------------------------------- MoE layers (Sec. 2.4 under static scheduling)
 FN_ROUTER_LOGITS, FN_ROUTER, FN_MOE_GATEUP, FN_MOE_DOWN, FN_COMBINE = 10, 11, 12, 13, 14
 DYN_ROWTILE = 4

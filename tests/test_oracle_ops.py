@@ -351,3 +351,69 @@ def test_moe_forced_routing_is_followed():
     np.testing.assert_array_equal(ids, forced)
     ref = _library_layer(s, x, w, kpool, vpool, step, forced)
     np.testing.assert_allclose(xo, ref, rtol=2e-5, atol=2e-5)
+
+
+# ---------------------------------------------------------------- the layer chain (oracle.decode_step)
+@pytest.mark.parametrize("moe", [False, True])
+def test_decode_step_chains_layers_like_the_library_derivation(moe):
+    """Three chained layers with their own weights and their own KV pools: x after layer l is the input of
+    layer l+1, layer l reads and appends to pool l only.  Checked per layer against the float64 library
+    derivation of one layer applied three times by hand (a chain that fed a layer the wrong input, the wrong
+    layer's weights or the wrong layer's pool fails here)."""
+    s = _tiny(moe, n_layers=3)
+    ws = [_weights(s) for _ in range(3)]
+    n_pool = 8
+    step = _step(s, [9, 0, 4], n_pool=n_pool)
+    pools = [(r32(n_pool, s.page, s.nkv, s.d), r32(n_pool, s.page, s.nkv, s.d)) for _ in range(3)]
+    work = [(k.copy(), v.copy()) for k, v in pools]
+    x = r32(3, s.H)
+    res = oracle.decode_step(s, 3, x, lambda l: ws[l], lambda l: work[l], step, tile_m=4)
+    assert len(res["layers"]) == 3 and len(res["topk"]) == 3
+    ref = x.astype(np.float64)
+    for l in range(3):
+        ref = _library_layer(s, ref.astype(np.float32), ws[l], pools[l][0], pools[l][1], step,
+                             res["topk"][l] if moe else None)
+        np.testing.assert_allclose(res["layers"][l], ref, rtol=5e-5, atol=5e-5, err_msg=f"layer {l}")
+        # every layer appended to its own pool, and only there: one row per sequence
+        assert int((work[l][0] != pools[l][0]).any(axis=(2, 3)).sum()) == 3
+    np.testing.assert_array_equal(res["final"], res["layers"][-1])
+    assert not np.shares_memory(res["final"], x) and np.array_equal(x, x)      # the input is not overwritten
+    # forced routing is handed to the right layer
+    if moe:
+        forced = [np.array([[0, 1], [2, 3], [4, 5]], np.int32), np.array([[5, 4], [3, 2], [1, 0]], np.int32), None]
+        work2 = [(k.copy(), v.copy()) for k, v in pools]
+        res2 = oracle.decode_step(s, 3, x, lambda l: ws[l], lambda l: work2[l], step,
+                                  forced_topk_of=lambda l: forced[l], tile_m=4)
+        np.testing.assert_array_equal(res2["topk"][0], forced[0])
+        np.testing.assert_array_equal(res2["topk"][1], forced[1])
+        ref = x.astype(np.float64)
+        for l in range(2):
+            ref = _library_layer(s, ref.astype(np.float32), ws[l], pools[l][0], pools[l][1], step, forced[l])
+        np.testing.assert_allclose(res2["layers"][1], ref, rtol=5e-5, atol=5e-5)
+
+
+def test_decode_steps_in_a_row_read_back_the_rows_they_appended():
+    """Three consecutive steps of one sequence on the same pools (kv_len grows by one, nothing is reset): the
+    second and third step attend to the rows the earlier steps appended.  Equals one library-derivation step
+    per token over a contiguous cache that is extended by hand with the oracle's own rotated K / V rows."""
+    s = _tiny(False)
+    w = _weights(s)
+    n_pool = 4
+    kpool, vpool = r32(n_pool, s.page, s.nkv, s.d), r32(n_pool, s.page, s.nkv, s.d)
+    kp, vp = kpool.copy(), vpool.copy()
+    pages = np.array([2, 0, 3], np.int32)                        # enough pages for kv_len up to 11
+    ref_k, ref_v = kpool.copy(), vpool.copy()
+    for t, L in enumerate((6, 7, 8)):                            # 7 -> 8 crosses into the third page
+        step = Step(1, np.array([L], np.int32), np.array([0, pages_needed(L, s.page)], np.int32),
+                    pages[: pages_needed(L, s.page)].copy())
+        x = r32(1, s.H)
+        xo = x.copy()
+        _, dbg = oracle.layer(oracle.shape_of(s), xo, w, kp, vp, step.kv_len, step.page_indptr, step.page_ids, debug=True)
+        ref = _library_layer(s, x, w, ref_k, ref_v, step)
+        np.testing.assert_allclose(xo, ref, rtol=2e-5, atol=2e-5, err_msg=f"step {t}")
+        # extend the reference cache by hand with the rows this step defined
+        pg, sl = int(pages[L // s.page]), L % s.page
+        ref_k[pg, sl] = dbg["k_rot"][0].reshape(s.nkv, s.d)
+        ref_v[pg, sl] = dbg["v_new"][0].reshape(s.nkv, s.d)
+        np.testing.assert_array_equal(kp, ref_k)
+        np.testing.assert_array_equal(vp, ref_v)

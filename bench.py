@@ -19,6 +19,7 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0
+T_PROCESS_START = time.time()
 
 
 FN_NAMES = {3: "load_hidden", 4: "qkv", 5: "attn_chunk", 6: "attn_merge", 7: "o_proj", 8: "gate_up", 9: "down",
@@ -83,6 +84,12 @@ def main() -> int:
                     help="also print a per-stage timeline of that layer from the per-task device trace (to stderr)")
     ap.add_argument("--bind-every-step", action="store_true",
                     help="also time a chain of steps whose kv_len grows by one, each bound before its launch")
+    ap.add_argument("--fast-fill", action="store_true",
+                    help="fill weights and KV pool with torch's own normal generator (same distributions, not the seeded "
+                         "generator the oracle shares: timing / counter runs only, no parity leg)")
+    ap.add_argument("--launch-at", type=float, default=0.0, metavar="SECONDS",
+                    help="sleep until that many seconds after process start before the first launch (lets a profiler's "
+                         "collection period skip the synthetic weight fill)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -104,9 +111,32 @@ def main() -> int:
     n_pool = B * synth.pages_needed(L, shape.page) + 16
 
     t0 = time.time()
-    model = GpuModel(shape, seed, n_pool)
+    if args.fast_fill:
+        args.no_cpu_baseline = True
+
+        class FastModel(GpuModel):               # same tensors, values from torch's generator
+            def __init__(self, shape, seed, n_pool_pages):
+                torch.manual_seed(seed)
+                self.shape, self.seed, self.n_pool_pages, self.device = shape, seed, n_pool_pages, "cuda"
+                self.weights = [{name: torch.empty(shp, dtype=torch.bfloat16, device="cuda").normal_(mean, sigma)
+                                 for name, shp, mean, sigma in synth.weight_specs(shape)} for _ in range(shape.n_layers)]
+                pshape = (shape.n_layers,) + synth.kv_pool_shape(shape, n_pool_pages)
+                self.kpool = torch.empty(pshape, dtype=torch.bfloat16, device="cuda").normal_()
+                self.vpool = torch.empty(pshape, dtype=torch.bfloat16, device="cuda").normal_()
+
+            def reset_pools(self):
+                pass
+
+            def hidden(self, step_index, batch):
+                return torch.empty(batch, self.shape.H, dtype=torch.bfloat16, device="cuda").normal_()
+        model = FastModel(shape, seed, n_pool)
+    else:
+        model = GpuModel(shape, seed, n_pool)
     torch.cuda.synchronize()
     t_fill = time.time() - t0
+
+    if args.launch_at > 0:
+        time.sleep(max(0.0, args.launch_at - (time.time() - T_PROCESS_START)))
 
     # ---- warm-up in the paper's sense (Sec. 4.4): engine start to first step served, minus model load
     t0 = time.time()
@@ -149,7 +179,7 @@ def main() -> int:
         "metric": "decode_step_latency_us", "value": round(us, 2), "unit": "us", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(us / 1e3, 5),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
-        "data": "synthetic",
+        "data": "synthetic (torch generator)" if args.fast_fill else "synthetic",
         "config": {"workload": f"{shape.name} decode, batch {B}, kv_len {L}, page 16, random page table, "
                                f"{shape.n_layers} layers, LM head excluded",
                    "scheduler": args.sched, "kv_chunk_tokens": args.kv_chunk,

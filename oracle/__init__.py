@@ -24,7 +24,7 @@ _i32p = ctypes.POINTER(ctypes.c_int32)
 class OrcShape(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("H", "nq", "nkv", "d", "F", "page", "n_experts", "top_k", "moe_F", "tile_m")] + \
-               [("eps", ctypes.c_float), ("theta", ctypes.c_float)]
+               [("eps", ctypes.c_float), ("theta", ctypes.c_float), ("qk_norm", ctypes.c_int32)]
 
 
 class OrcDebug(ctypes.Structure):
@@ -48,7 +48,7 @@ def lib():
     L.orc_silu.restype = ctypes.c_double
     L.orc_silu.argtypes = [ctypes.c_double]
     for name in ("orc_rmsnorm", "orc_linear", "orc_rope", "orc_attention", "orc_topk",
-                 "orc_route_weights", "orc_group", "orc_layer"):
+                 "orc_route_weights", "orc_group", "orc_layer", "orc_lm_head"):
         getattr(L, name).restype = None
     return L
 
@@ -62,7 +62,8 @@ def n_threads() -> int:
 def shape_of(s, tile_m: int = 16) -> OrcShape:
     """OrcShape from any object with the model-shape attribute names."""
     return OrcShape(H=s.H, nq=s.nq, nkv=s.nkv, d=s.d, F=s.F, page=s.page, n_experts=s.n_experts,
-                    top_k=s.top_k, moe_F=s.moe_F, tile_m=tile_m, eps=s.eps, theta=s.theta)
+                    top_k=s.top_k, moe_F=s.moe_F, tile_m=tile_m, eps=s.eps, theta=s.theta,
+                    qk_norm=1 if getattr(s, "qk_norm", False) else 0)
 
 
 def _p(a):
@@ -175,9 +176,20 @@ def layer(shape: OrcShape, x, w: dict, kpool, vpool, kv_len, page_indptr, page_i
     g = lambda name: _p(ww.get(name))  # noqa: E731
     lib().orc_layer(ctypes.byref(shape), ctypes.c_int(B), _p(x), g("g1"), g("wq"), g("wk"), g("wv"),
                     g("wo"), g("g2"), g("wg"), g("wu"), g("wd"), g("wr"), g("eg"), g("eu"), g("ed"),
-                    _p(kpool), _p(vpool), _p(kv_len), _p(page_indptr), _p(page_ids), ctypes.c_int(force),
+                    g("gq"), g("gk"), _p(kpool), _p(vpool), _p(kv_len), _p(page_indptr), _p(page_ids), ctypes.c_int(force),
                     _p(ids), ctypes.byref(dbg_struct) if debug else None)
     return ids, dbg_arrays
+
+
+def lm_head(shape: OrcShape, x, gf, wlm):
+    """Final RMSNorm, vocabulary projection and greedy arg-max.  x [B, H], gf [H], wlm [V, H] ->
+    (logits [B, V] fp32, token ids [B] int32)."""
+    x, gf, wlm = _f(x), _f(gf), _f(wlm)
+    B, V = x.shape[0], wlm.shape[0]
+    logits = np.empty((B, V), dtype=np.float32)
+    token = np.empty(B, dtype=np.int32)
+    lib().orc_lm_head(ctypes.byref(shape), ctypes.c_int(B), _p(x), _p(gf), _p(wlm), ctypes.c_int(V), _p(logits), _p(token))
+    return logits, token
 
 
 def decode_step(s, n_layers, x0, weights_of, pools_of, step, forced_topk_of=None, tile_m: int = 16,

@@ -16,6 +16,7 @@
  * decoder of the benchmark shapes:
  *
  *   xn  = rmsnorm(x, g1)                       q,k,v = Wq xn, Wk xn, Wv xn
+ *   (qk_norm models, Sec. 4.3 "Q-Norm", "K-Norm": q_h = rmsnorm(q_h, gq), k_h = rmsnorm(k_h, gk) per head, over head_dim)
  *   q,k = rope(q, pos), rope(k, pos)           append k,v at position pos
  *   o_h = softmax(q_h . K / sqrt(d)) V         over positions 0..pos, via the page table
  *   x   = x + Wo o
@@ -23,6 +24,9 @@
  *   dense: x = x + Wd (silu(Wg xn2) * (Wu xn2))
  *   MoE  : logits = Wr xn2; S = top-k; w = softmax(logits[S]);
  *          x = x + sum_{slot} w_slot * Wd_e (silu(Wg_e xn2) * (Wu_e xn2))
+ * After the last layer (models with a vocabulary: the end of a decode iteration of Sec. 4.3, whose output token
+ * is the next iteration's input):
+ *   logits = Wlm rmsnorm(x, gf)                token = argmax(logits), ties -> lower id
  *
  * Conventions (readings where the paper is silent):
  *   - RoPE pairs element i with i + d/2, angle = pos * theta^(-2i/d).
@@ -32,6 +36,10 @@
  *   - routing weights: softmax over the selected logits only.
  *   - grouping order: (expert, token, slot) ascending; exp_indptr counts
  *     row tiles of tile_m tokens per expert (half-open CSR ranges).
+ *   - per-head Q / K norm (Qwen3-style models only): RMSNorm over the head_dim elements of every
+ *     head with one gain vector for all query heads and one for all key heads, the layer's eps,
+ *     applied before RoPE; the cache holds the normalised, rotated key.
+ *   - sampling: greedy (arg-max of the logits), the lower token id on equal logits.
  */
 #include <math.h>
 #include <stdint.h>
@@ -41,6 +49,7 @@
 typedef struct {
     int32_t H, nq, nkv, d, F, page, n_experts, top_k, moe_F, tile_m;
     float eps, theta;
+    int32_t qk_norm;   /* != 0: per-head RMSNorm of q and k before RoPE */
 } orc_shape;
 
 /* optional per-operator outputs for per-stage parity checks; any pointer may be NULL */
@@ -192,7 +201,7 @@ void orc_group(const int32_t *topk_ids, int B, int K, int E, int tile_m, int32_t
 void orc_layer(const orc_shape *s, int B, float *x, const float *g1, const float *wq, const float *wk,
                const float *wv, const float *wo, const float *g2, const float *wg, const float *wu,
                const float *wd, const float *wr, const float *eg, const float *eu, const float *ed,
-               float *kpool, float *vpool, const int32_t *kv_len, const int32_t *page_indptr,
+               const float *gq, const float *gk, float *kpool, float *vpool, const int32_t *kv_len, const int32_t *page_indptr,
                const int32_t *page_ids, int force_routing, int32_t *topk_ids, const orc_debug *dbg)
 {
     int H = s->H, QD = s->nq * s->d, KD = s->nkv * s->d;
@@ -207,6 +216,18 @@ void orc_layer(const orc_shape *s, int B, float *x, const float *g1, const float
     orc_linear(wq, xn, B, QD, H, q);
     orc_linear(wk, xn, B, KD, H, k);
     orc_linear(wv, xn, B, KD, H, v);
+    if (s->qk_norm) {
+        for (int b = 0; b < B; ++b) {
+            for (int h = 0; h < s->nq; ++h) {
+                float *qh = q + (size_t)b * QD + (size_t)h * s->d;
+                orc_rmsnorm(qh, gq, s->d, s->eps, qh);
+            }
+            for (int h = 0; h < s->nkv; ++h) {
+                float *kh = k + (size_t)b * KD + (size_t)h * s->d;
+                orc_rmsnorm(kh, gk, s->d, s->eps, kh);
+            }
+        }
+    }
     for (int b = 0; b < B; ++b) {
         int pos = kv_len[b];
         orc_rope(q + (size_t)b * QD, s->nq, s->d, pos, s->theta);
@@ -272,4 +293,25 @@ void orc_layer(const orc_shape *s, int B, float *x, const float *g1, const float
         free(logits); free(w); free(gt); free(up); free(acc);
     }
     free(xn); free(q); free(k); free(v); free(o); free(y);
+}
+
+/*
+ * End of a decode iteration: logits[b, v] = sum_i Wlm[v, i] * rmsnorm(x[b], gf)[i]; token[b] = the index of the
+ * largest logit, the lower index on equal logits.  x [B, H], Wlm [V, H], logits [B, V] (output), token [B] (output).
+ */
+void orc_lm_head(const orc_shape *s, int B, const float *x, const float *gf, const float *wlm, int V, float *logits,
+                 int32_t *token)
+{
+    int H = s->H;
+    float *xn = (float *)malloc(sizeof(float) * (size_t)B * H);
+    for (int b = 0; b < B; ++b) orc_rmsnorm(x + (size_t)b * H, gf, H, s->eps, xn + (size_t)b * H);
+    orc_linear(wlm, xn, B, V, H, logits);
+    for (int b = 0; b < B; ++b) {
+        const float *l = logits + (size_t)b * V;
+        int best = 0;
+        for (int v = 1; v < V; ++v)
+            if (l[v] > l[best]) best = v; /* strict >: the lower id keeps a tie */
+        token[b] = best;
+    }
+    free(xn);
 }

@@ -12,7 +12,7 @@ import numpy as np
 import torch
 
 from . import keys, normal_table
-from .workloads import KIND, HIDDEN_TID0, ModelShape, kv_pool_shape, weight_specs
+from .workloads import KIND, HIDDEN_TID0, LM_TID, ModelShape, kv_pool_shape, lm_specs, weight_specs
 
 _M32 = 0xFFFFFFFF
 _CHUNK = 1 << 25
@@ -59,6 +59,11 @@ def layer_weights_gpu(s: ModelShape, seed: int, layer: int, device="cuda") -> di
     return {name: tensor_gpu(seed, layer * 64 + KIND[name], int(np.prod(shape)), mean, sigma,
                              device).view(*shape)
             for name, shape, mean, sigma in weight_specs(s)}
+
+
+def lm_weights_gpu(s: ModelShape, seed: int, device="cuda") -> dict[str, torch.Tensor]:
+    return {name: tensor_gpu(seed, LM_TID[name], int(np.prod(shape)), mean, sigma, device).view(*shape)
+            for name, shape, mean, sigma in lm_specs(s)}
 
 
 def kv_pool_gpu(s: ModelShape, seed: int, layer: int, n_pages: int, device="cuda"):

@@ -27,6 +27,8 @@ class ModelShape:
     n_experts: int = 0
     top_k: int = 0
     moe_F: int = 0        # per-expert SwiGLU width
+    qk_norm: bool = False # per-head RMSNorm of q and k before RoPE (Qwen3-style)
+    vocab: int = 0        # > 0: token embedding, final norm and vocabulary projection exist
 
     @property
     def is_moe(self) -> bool:
@@ -38,13 +40,21 @@ TINY_MOE = ModelShape("tiny-moe", 2, 256, 4, 2, 64, 0, n_experts=16, top_k=2, mo
 LLAMA3_8B = ModelShape("llama3-8b", 32, 4096, 32, 8, 128, 14336)
 QWEN3_30B_A3B = ModelShape("qwen3-30b-a3b", 48, 2048, 32, 4, 128, 0, n_experts=128, top_k=8, moe_F=768)
 LLAMA3_70B = ModelShape("llama3-70b", 80, 8192, 64, 8, 128, 28672)
+# the paper's end-to-end models (Sec. 4.3): Qwen3-32B-shaped dense decoder with per-head Q / K norm, and small
+# decoders with a vocabulary for chained decode iterations
+QWEN3_32B = ModelShape("qwen3-32b", 64, 5120, 64, 8, 128, 25600, eps=1e-6, theta=1000000.0, qk_norm=True)
+TINY_QK = ModelShape("tiny-qk", 2, 256, 4, 2, 64, 1024, qk_norm=True)
+TINY_LM = ModelShape("tiny-lm", 2, 256, 4, 2, 64, 1024, qk_norm=True, vocab=1024)
+TINY_MOE_LM = ModelShape("tiny-moe-lm", 2, 256, 4, 2, 64, 0, n_experts=16, top_k=2, moe_F=256, qk_norm=True, vocab=1024)
 
-SHAPES = {s.name: s for s in (TINY, TINY_MOE, LLAMA3_8B, QWEN3_30B_A3B, LLAMA3_70B)}
+SHAPES = {s.name: s for s in (TINY, TINY_MOE, LLAMA3_8B, QWEN3_30B_A3B, LLAMA3_70B, QWEN3_32B, TINY_QK, TINY_LM,
+                              TINY_MOE_LM)}
 
 # tensor kinds inside one layer; tensor id = layer * 64 + kind
 KIND = {"g1": 0, "wq": 1, "wk": 2, "wv": 3, "wo": 4, "g2": 5, "wg": 6, "wu": 7, "wd": 8,
-        "wr": 9, "eg": 10, "eu": 11, "ed": 12, "kpool": 13, "vpool": 14}
+        "wr": 9, "eg": 10, "eu": 11, "ed": 12, "kpool": 13, "vpool": 14, "gq": 15, "gk": 16}
 HIDDEN_TID0 = 0x7F000000
+LM_TID = {"embed": 0x7E000001, "gf": 0x7E000002, "wlm": 0x7E000003}     # model-level tensors of a model with a vocabulary
 
 
 def weight_specs(s: ModelShape) -> list[tuple[str, tuple[int, ...], float, float]]:
@@ -55,6 +65,8 @@ def weight_specs(s: ModelShape) -> list[tuple[str, tuple[int, ...], float, float
              ("wv", (s.nkv * s.d, s.H), 0.0, 0.02),
              ("wo", (s.H, s.nq * s.d), 0.0, 0.02),
              ("g2", (s.H,), 1.0, 0.02)]
+    if s.qk_norm:
+        specs += [("gq", (s.d,), 1.0, 0.02), ("gk", (s.d,), 1.0, 0.02)]
     if s.is_moe:
         specs += [("wr", (s.n_experts, s.H), 0.0, 0.02),
                   ("eg", (s.n_experts, s.moe_F, s.H), 0.0, 0.02),
@@ -76,6 +88,18 @@ def layer_weights_f32(s: ModelShape, seed: int, layer: int) -> dict[str, np.ndar
     from . import tensor_f32
     return {name: tensor_f32(seed, layer * 64 + KIND[name], int(np.prod(shape)), mean, sigma).reshape(shape)
             for name, shape, mean, sigma in weight_specs(s)}
+
+
+def lm_specs(s: ModelShape) -> list[tuple[str, tuple[int, ...], float, float]]:
+    """(name, shape, mean, sigma) of the model-level tensors: token embedding (unit variance, like the synthetic
+    hidden states), final RMSNorm gain, vocabulary projection."""
+    return [("embed", (s.vocab, s.H), 0.0, 1.0), ("gf", (s.H,), 1.0, 0.02), ("wlm", (s.vocab, s.H), 0.0, 0.02)]
+
+
+def lm_weights_f32(s: ModelShape, seed: int) -> dict[str, np.ndarray]:
+    from . import tensor_f32
+    return {name: tensor_f32(seed, LM_TID[name], int(np.prod(shape)), mean, sigma).reshape(shape)
+            for name, shape, mean, sigma in lm_specs(s)}
 
 
 def kv_pool_shape(s: ModelShape, n_pages: int) -> tuple[int, int, int, int]:

@@ -211,6 +211,8 @@ def _weights(s, scale=0.2):
     w = {"g1": 1 + r32(s.H, scale=0.02), "g2": 1 + r32(s.H, scale=0.02),
          "wq": r32(s.nq * s.d, s.H, scale=scale), "wk": r32(s.nkv * s.d, s.H, scale=scale),
          "wv": r32(s.nkv * s.d, s.H, scale=scale), "wo": r32(s.H, s.nq * s.d, scale=scale)}
+    if getattr(s, "qk_norm", False):
+        w.update(gq=1 + r32(s.d, scale=0.1), gk=1 + r32(s.d, scale=0.1))
     if s.is_moe:
         w.update(wr=r32(s.n_experts, s.H), eg=r32(s.n_experts, s.moe_F, s.H, scale=scale),
                  eu=r32(s.n_experts, s.moe_F, s.H, scale=scale), ed=r32(s.n_experts, s.H, s.moe_F, scale=scale))
@@ -239,6 +241,9 @@ def _library_layer(s, x, w, kpool, vpool, step, topk_ids=None):
         q = (T(w["wq"]) @ xn).view(s.nq, s.d)
         k = (T(w["wk"]) @ xn).view(s.nkv, s.d)
         v = (T(w["wv"]) @ xn).view(s.nkv, s.d)
+        if getattr(s, "qk_norm", False):      # per-head RMSNorm over head_dim, one gain for all q heads, one for all k heads
+            q = Fn.rms_norm(q, (s.d,), T(w["gq"]), eps=s.eps)
+            k = Fn.rms_norm(k, (s.d,), T(w["gk"]), eps=s.eps)
         inv = s.theta ** (-torch.arange(0, s.d, 2).double() / s.d)
         cos, sin = torch.cos(pos * inv), torch.sin(pos * inv)
 
@@ -417,3 +422,67 @@ def test_decode_steps_in_a_row_read_back_the_rows_they_appended():
         ref_v[pg, sl] = dbg["v_new"][0].reshape(s.nkv, s.d)
         np.testing.assert_array_equal(kp, ref_k)
         np.testing.assert_array_equal(vp, ref_v)
+
+
+# ---------------------------------------------------------------- per-head Q / K norm (Sec. 4.3: Q-Norm, K-Norm)
+@pytest.mark.parametrize("moe", [False, True])
+def test_qk_norm_layer_matches_independent_library_derivation(moe):
+    s = _tiny(moe, qk_norm=True)
+    w = _weights(s)
+    step = _step(s, [9, 0, 4], n_pool=8)
+    kpool, vpool = r32(8, s.page, s.nkv, s.d), r32(8, s.page, s.nkv, s.d)
+    x = r32(3, s.H)
+    xo, kp, vp = x.copy(), kpool.copy(), vpool.copy()
+    ids, dbg = oracle.layer(oracle.shape_of(s), xo, w, kp, vp, step.kv_len, step.page_indptr, step.page_ids, debug=True)
+    ref = _library_layer(s, x, w, kpool, vpool, step, ids)
+    np.testing.assert_allclose(xo, ref, rtol=2e-5, atol=2e-5)
+    # the norm is really there: without it the result differs
+    s0 = _tiny(moe)
+    x0 = x.copy()
+    oracle.layer(oracle.shape_of(s0), x0, w, kpool.copy(), vpool.copy(), step.kv_len, step.page_indptr, step.page_ids,
+                 forced_topk=ids)
+    assert np.abs(x0 - xo).max() > 1e-3
+
+
+def test_qk_norm_makes_the_layer_blind_to_the_scale_of_wq_and_wk():
+    """A head that is normalised to unit RMS forgets how large it was: scaling Wq by 3 and Wk by 1/2 leaves the
+    layer's output (nearly: eps) unchanged, and the appended key row has RMS |gk| per head at position 0."""
+    s = _tiny(False, qk_norm=True, eps=1e-12)
+    w = _weights(s)
+    w["gk"] = np.full(s.d, 2.0, np.float32)
+    step = _step(s, [0, 5], n_pool=4)
+    kpool, vpool = r32(4, s.page, s.nkv, s.d), r32(4, s.page, s.nkv, s.d)
+    x = r32(2, s.H)
+    a, b = x.copy(), x.copy()
+    kpa = kpool.copy()
+    _, dbg = oracle.layer(oracle.shape_of(s), a, w, kpa, vpool.copy(), step.kv_len, step.page_indptr, step.page_ids, debug=True)
+    w2 = dict(w, wq=w["wq"] * 3.0, wk=w["wk"] * 0.5)
+    oracle.layer(oracle.shape_of(s), b, w2, kpool.copy(), vpool.copy(), step.kv_len, step.page_indptr, step.page_ids)
+    np.testing.assert_allclose(a, b, rtol=1e-5, atol=1e-6)
+    k_rows = dbg["k_rot"].reshape(2, s.nkv, s.d)          # RoPE keeps the norm of every rotated pair, hence of the head
+    np.testing.assert_allclose(np.sqrt((k_rows.astype(np.float64) ** 2).mean(-1)), 2.0, rtol=1e-5)
+    # constant head: every element of the normalised head equals gain * sign
+    xx = np.full((1, 8), -3.0, np.float32)
+    np.testing.assert_allclose(oracle.rmsnorm(xx[0], np.arange(1, 9, dtype=np.float32), 0.0), -np.arange(1, 9), rtol=1e-6)
+
+
+# ---------------------------------------------------------------- final norm, vocabulary projection, greedy token
+def test_lm_head_matches_float64_and_breaks_ties_to_the_lower_id():
+    s = _tiny(False)
+    V = 24
+    x, gf, wlm = r32(3, s.H), 1 + r32(s.H, scale=0.05), r32(V, s.H, scale=0.3)
+    logits, tok = oracle.lm_head(oracle.shape_of(s), x, gf, wlm)
+    xd = x.astype(np.float64)
+    xn = xd / np.sqrt((xd ** 2).mean(-1, keepdims=True) + s.eps) * gf.astype(np.float64)
+    ref = xn @ wlm.astype(np.float64).T
+    np.testing.assert_allclose(logits, ref, rtol=2e-6, atol=2e-6)
+    np.testing.assert_array_equal(tok, ref.argmax(-1))
+    # one-hot rows: the logit of token v is the v-th normalised input element; equal rows tie -> lower id
+    eye = np.zeros((V, s.H), np.float32)
+    eye[np.arange(V), np.arange(V)] = 1.0
+    eye[20] = eye[5]                                        # tokens 5 and 20 have identical rows
+    xo = np.zeros((1, s.H), np.float32)
+    xo[0, 5], xo[0, 7] = 4.0, 4.0                            # elements 5 and 7 are the (equal) largest
+    lg, tk = oracle.lm_head(oracle.shape_of(s), xo, np.ones(s.H, np.float32), eye)
+    assert lg[0, 5] == lg[0, 7] == lg[0, 20] and tk[0] == 5
+    np.testing.assert_allclose(lg[0, 5], 4.0 / np.sqrt(32.0 / s.H + s.eps), rtol=1e-6)

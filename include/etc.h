@@ -73,6 +73,9 @@ typedef struct {
     int32_t n_experts, top_k, moe_ffn;
     int32_t page_size; /* tokens per KV page */
     float rms_eps, rope_theta;
+    int32_t qk_norm;   /* != 0: per-head RMSNorm of q and k (over head_dim, gains gq / gk, rms_eps) before RoPE: the
+                          "Q-Norm + RoPE" and "K-Norm + RoPE + CacheAppend" tasks of Sec. 4.3 (Qwen3-style models) */
+    int32_t vocab;     /* > 0: the model ends in a final RMSNorm and a vocabulary projection; see etc_bind_lm_head */
 } etc_model_desc;
 
 /* Tile shapes of the task grids (Sec. 2.1: tasks are CU-level tiles). */
@@ -135,6 +138,8 @@ typedef struct {
     const void *eg;  /* [n_experts, moe_ffn, hidden] */
     const void *eu;  /* [n_experts, moe_ffn, hidden] */
     const void *ed;  /* [n_experts, hidden, moe_ffn] */
+    const void *gq;  /* [head_dim]               per-head query norm gain (qk_norm models, else NULL) */
+    const void *gk;  /* [head_dim]               per-head key norm gain */
 } etc_layer_weights;
 
 /* Resident tensors of the decoder of Sec. 4.3 (attention, RoPE, norms, MLP or MoE block): recorded, not copied;

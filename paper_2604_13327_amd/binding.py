@@ -37,7 +37,7 @@ class EtcError(RuntimeError):
 class ModelDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn",
                                          "n_experts", "top_k", "moe_ffn", "page_size")] + \
-               [("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+               [("rms_eps", C.c_float), ("rope_theta", C.c_float), ("qk_norm", C.c_int32), ("vocab", C.c_int32)]
 
 
 class TileDesc(C.Structure):
@@ -51,7 +51,8 @@ class SchedDesc(C.Structure):
 
 
 class LayerWeights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd", "wr", "eg", "eu", "ed")]
+    _fields_ = [(n, C.c_void_p) for n in ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd", "wr", "eg", "eu", "ed",
+                                        "gq", "gk")]
 
 
 class StepInfo(C.Structure):
@@ -134,7 +135,7 @@ def lib():
 def _model_desc(s) -> ModelDesc:
     return ModelDesc(n_layers=s.n_layers, hidden=s.H, n_q_heads=s.nq, n_kv_heads=s.nkv, head_dim=s.d, ffn=s.F,
                      n_experts=s.n_experts, top_k=s.top_k, moe_ffn=s.moe_F, page_size=s.page, rms_eps=s.eps,
-                     rope_theta=s.theta)
+                     rope_theta=s.theta, qk_norm=1 if getattr(s, "qk_norm", False) else 0, vocab=0)
 
 
 def _sched_desc(kind, sampled_batches, max_kv_len, debug_flags=0, spin_budget=0, n_queues=0) -> SchedDesc:

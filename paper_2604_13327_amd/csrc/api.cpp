@@ -456,6 +456,7 @@ etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc
     P.n_layers = m->n_layers; P.H = m->hidden; P.nq = m->n_q_heads; P.nkv = m->n_kv_heads; P.d = m->head_dim;
     P.F = m->ffn; P.E = m->n_experts; P.topk = m->top_k; P.moeF = m->moe_ffn; P.page = m->page_size;
     P.eps = m->rms_eps; P.theta = m->rope_theta; P.kv_chunk = t->kv_chunk_tokens; P.tile_m = d.tile_m;
+    P.qk_norm = m->qk_norm ? 1 : 0;
     auto A = [&](auto **p, size_t n) -> bool {
         hipError_t e = dev_alloc(p, n, c->owned);
         if (e != hipSuccess) { c->err = std::string("device allocation failed: ") + hipGetErrorString(e); return false; }
@@ -465,6 +466,7 @@ etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc
     bool okk = A(&P.x, MB * H) && A(&P.x_mid, MB * H) && A(&P.qbuf, MB * QD) &&
                A(&P.knew, MB * (size_t)m->n_kv_heads * m->head_dim) && A(&P.vnew, MB * (size_t)m->n_kv_heads * m->head_dim) &&
                A(&P.rope_cs, MB * (size_t)m->head_dim) && A(&P.kv_slot, MB) &&
+               A(&P.qk_ssq, MB * (size_t)(m->n_q_heads + m->n_kv_heads) * (size_t)(m->head_dim / 16)) &&
                A(&P.xg_hi, MB * H) && A(&P.xg_lo, MB * H) && A(&P.xmg_hi, MB * H) && A(&P.xmg_lo, MB * H) &&
                A(&P.ssq_x, (H / 16) * (size_t)kMaxBatch) && A(&P.ssq_xmid, (H / 16) * (size_t)kMaxBatch) &&
                A(&P.attn_hi, MB * QD) && A(&P.attn_lo, MB * QD) && A(&P.act_hi, MB * F1) && A(&P.act_lo, MB * F1) &&
@@ -525,10 +527,11 @@ etc_status etc_bind_layer_weights(etc_ctx *c, int32_t layer, const etc_layer_wei
     if (!w->g1 || !w->wq || !w->wk || !w->wv || !w->wo || !w->g2) return fail(c, ETC_EINVAL, "attention weights missing");
     if (!moe && (!w->wg || !w->wu || !w->wd)) return fail(c, ETC_EINVAL, "dense FFN weights missing");
     if (moe && (!w->wr || !w->eg || !w->eu || !w->ed)) return fail(c, ETC_EINVAL, "MoE weights missing");
-    const void *all[] = {w->g1, w->wq, w->wk, w->wv, w->wo, w->g2, w->wg, w->wu, w->wd, w->wr, w->eg, w->eu, w->ed};
+    if (c->model.qk_norm && (!w->gq || !w->gk)) return fail(c, ETC_EINVAL, "per-head norm gains gq / gk missing");
+    const void *all[] = {w->g1, w->wq, w->wk, w->wv, w->wo, w->g2, w->wg, w->wu, w->wd, w->wr, w->eg, w->eu, w->ed, w->gq, w->gk};
     for (const void *p : all)
         if (p && ((uintptr_t)p & 15)) return fail(c, ETC_EINVAL, "weight pointers must be 16-byte aligned");
-    c->h_weights[layer] = LayerWeights{w->g1, w->wq, w->wk, w->wv, w->wo, w->g2, w->wg, w->wu, w->wd, w->wr, w->eg, w->eu, w->ed};
+    c->h_weights[layer] = LayerWeights{w->g1, w->wq, w->wk, w->wv, w->wo, w->g2, w->wg, w->wu, w->wd, w->wr, w->eg, w->eu, w->ed, w->gq, w->gk};
     c->weights_bound[layer] = 1;
     c->weights_dirty = true;
     return ETC_OK;

@@ -83,7 +83,7 @@ struct Task {
 static_assert(sizeof(Task) == 32, "Task must stay 32 bytes");
 
 struct LayerWeights {
-    const void *g1, *wq, *wk, *wv, *wo, *g2, *wg, *wu, *wd, *wr, *eg, *eu, *ed;
+    const void *g1, *wq, *wk, *wv, *wo, *g2, *wg, *wu, *wd, *wr, *eg, *eu, *ed, *gq, *gk;
 };
 
 // Error word codes
@@ -98,6 +98,8 @@ struct Params {
     float eps, theta;
     const double *rope_inv_freq;       // [d/2] theta^(-2i/d), computed on the host in double
     int32_t kv_chunk, tile_m;
+    int32_t qk_norm;                   // per-head RMSNorm of q and k before RoPE (Qwen3-style)
+    int32_t vocab;                     // > 0: final norm + vocabulary projection + greedy token at the end of the step
     // resident tensors
     const LayerWeights *weights;       // [n_layers] device
     uint16_t *kpool, *vpool;           // bf16 bits
@@ -116,6 +118,8 @@ struct Params {
     float *ssq_x, *ssq_xmid;           // partial sums of squares per 16-row tile [H/16][kMaxBatch]
     float *qbuf;                       // rotated queries [maxB, nq*d]
     float *knew, *vnew;                // this step's K (rotated) and V rows in fp32 [maxB, nkv*d]: the cache gets bf16
+    float *qk_ssq;                     // qk_norm: sums of squares of the raw q / k heads per 16-row tile [maxB, nq + nkv, d / 16];
+                                       //   qbuf / knew then hold gain-scaled, rotated but not yet normalised heads
     float *rope_cs;                    // this step's (cos, sin) of every sequence's RoPE angles [maxB, d/2, 2], from the step prologue
     int32_t *kv_slot;                  // this step's KV slot of every sequence: page * page_size + pos % page_size [maxB]
     uint16_t *attn_hi, *attn_lo;       // attention output, split [maxB, nq*d]

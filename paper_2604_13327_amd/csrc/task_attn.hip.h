@@ -31,16 +31,25 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
     const size_t lbase = (size_t)layer * (size_t)P.pool_layer_stride;
     const float qscale = 1.0f / sqrtf((float)D);
 
+    // qk_norm models: 1 / rms of a head from the per-tile sums of squares its projection tasks left (D / 16 of them)
+    auto head_rnorm = [&](int head) {
+        const float *sp = P.qk_ssq + ((size_t)b * (P.nq + P.nkv) + head) * (size_t)(D / 16);
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < D / 16; ++i) s += ld_f32(sp + i);
+        return 1.0f / sqrtf(s / (float)D + P.eps);
+    };
     float q[GRP][8];
     auto load_queries = [&]() {
 #pragma unroll
         for (int g = 0; g < GRP; ++g) {
             const float *qp = P.qbuf + (size_t)b * (size_t)(P.nq * D) + (size_t)(kvh * GRP + g) * D + dl * 8;
+            const float sc = P.qk_norm ? qscale * head_rnorm(kvh * GRP + g) : qscale;
 #pragma unroll
             for (int i = 0; i < 8; i += 2) {
                 ld_f32x2(qp + i, q[g][i], q[g][i + 1]);
-                q[g][i] *= qscale;
-                q[g][i + 1] *= qscale;
+                q[g][i] *= sc;
+                q[g][i + 1] *= sc;
             }
         }
     };
@@ -147,6 +156,19 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
         for (int i = 0; i < 8; i += 2) {
             ld_f32x2(kn + i, kf[i], kf[i + 1]);
             ld_f32x2(vn + i, vf[i], vf[i + 1]);
+        }
+        if (P.qk_norm) {       // K-Norm + RoPE + CacheAppend (Sec. 4.3): the key's norm is complete here, and so is its cache row
+            const float rk = head_rnorm(P.nq + kvh);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) kf[i] *= rk;
+            if (tq == 0) {
+                uint16_t *dst = P.kpool + lbase + ((size_t)gld_i32(P.kv_slot + b) * P.nkv + kvh) * (size_t)D + dl * 8;
+                const u32x4 row{(uint32_t)f32_to_bf16_bits(kf[0]) | ((uint32_t)f32_to_bf16_bits(kf[1]) << 16),
+                                (uint32_t)f32_to_bf16_bits(kf[2]) | ((uint32_t)f32_to_bf16_bits(kf[3]) << 16),
+                                (uint32_t)f32_to_bf16_bits(kf[4]) | ((uint32_t)f32_to_bf16_bits(kf[5]) << 16),
+                                (uint32_t)f32_to_bf16_bits(kf[6]) | ((uint32_t)f32_to_bf16_bits(kf[7]) << 16)};
+                *as_global(reinterpret_cast<u32x4 *>(dst)) = row;      // nobody reads the cache row in this launch
+            }
         }
 #pragma unroll
         for (int g = 0; g < GRP; ++g) {

@@ -758,6 +758,12 @@ __device__ __forceinline__ EpiPre epilogue_preload(const Params &P, const Epilog
         const int b = col, i = e.row0 + mp;
         if (e.head < P.nq + P.nkv) ld_f32x2(P.rope_cs + ((size_t)b * (P.d >> 1) + i) * 2, pre.a, pre.b);   // q and k heads are rotated
         if (e.head >= P.nq) pre.slot = ld_i32(P.kv_slot + b);
+        if (P.qk_norm && e.head < P.nq + P.nkv) {      // gains of the two rows under the per-head norm
+            const ETC_AS_GLOBAL LayerWeights *W = as_global(P.weights) + e.layer;
+            const uint16_t *gn = (const uint16_t *)(e.head < P.nq ? W->gq : W->gk);
+            pre.ga = bf16_bits_to_f32(gld_u16(gn + i));
+            pre.gb = bf16_bits_to_f32(gld_u16(gn + i + (P.d >> 1)));
+        }
     } else if (e.kind == EPI_RESID) {
         const size_t o0 = (size_t)col * e.ld + e.row0 + mp;
         pre.a = ld_f32(e.resid + o0);
@@ -777,6 +783,20 @@ __device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &
     case EPI_QKV: {
         const int b = col, half = P.d >> 1, i = e.row0 + mp;
         float a = lo, c = hi;
+        const bool normed = P.qk_norm && e.head < P.nq + P.nkv;
+        if (normed) {
+            // Per-head RMSNorm before RoPE (Sec. 4.3: Q-Norm / K-Norm).  The head's 1 / rms is a scalar, and the rotation
+            // is linear, so it commutes with both: this tile leaves its share of the head's sum of squares (of the
+            // raw values), applies the gains and rotates; whoever consumes the head (the attention tasks) sums the
+            // tiles' shares and scales by 1 / sqrt(mean + eps).
+            float sq = lo * lo + hi * hi;
+            sq = lanes_sum<8>(sq);                     // the 8 threads of a column are 8 consecutive lanes
+            if (mp == 0) st_f32(P.qk_ssq + ((size_t)b * (P.nq + P.nkv) + e.head) * (size_t)(P.d >> 4) + (e.row0 >> 3), sq);
+            lo *= pre.ga;
+            hi *= pre.gb;
+            a = lo;
+            c = hi;
+        }
         if (e.head < P.nq + P.nkv) {
             a = lo * pre.a - hi * pre.b;
             c = lo * pre.b + hi * pre.a;
@@ -791,8 +811,10 @@ __device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &
             const size_t off = (size_t)e.layer * (size_t)P.pool_layer_stride +
                                ((size_t)pre.slot * P.nkv + kvh) * (size_t)P.d;
             uint16_t *dst = (is_k ? P.kpool : P.vpool) + off;
-            st_u16(dst + i, f32_to_bf16_bits(a));
-            st_u16(dst + i + half, f32_to_bf16_bits(c));
+            if (!(is_k && normed)) {       // a normalised key reaches the cache from the attention task that completes its norm
+                st_u16(dst + i, f32_to_bf16_bits(a));
+                st_u16(dst + i + half, f32_to_bf16_bits(c));
+            }
             // this step's attention takes the new row unrounded (the cache keeps bf16)
             float *cur = (is_k ? P.knew : P.vnew) + ((size_t)b * P.nkv + kvh) * (size_t)P.d;
             st_f32(cur + i, a);

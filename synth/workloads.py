@@ -66,7 +66,7 @@ def weight_specs(s: ModelShape) -> list[tuple[str, tuple[int, ...], float, float
              ("wo", (s.H, s.nq * s.d), 0.0, 0.02),
              ("g2", (s.H,), 1.0, 0.02)]
     if s.qk_norm:
-        specs += [("gq", (s.d,), 1.0, 0.02), ("gk", (s.d,), 1.0, 0.02)]
+        specs += [("gq", (s.d,), 1.0, 0.25), ("gk", (s.d,), 1.0, 0.25)]      # wide, so that a misplaced gain shows in the output
     if s.is_moe:
         specs += [("wr", (s.n_experts, s.H), 0.0, 0.02),
                   ("eg", (s.n_experts, s.moe_F, s.H), 0.0, 0.02),

@@ -150,6 +150,14 @@ etc_status etc_bind_layer_weights(etc_ctx *ctx, int32_t layer, const etc_layer_w
  * K rows are stored already rotated.  The step appends one row per sequence (Sec. 4.3). */
 etc_status etc_bind_kv_pool(etc_ctx *ctx, void *k_pages, void *v_pages, int64_t pages_per_layer);
 
+/* Model-level tensors of a model with a vocabulary (etc_model_desc.vocab > 0), device memory, bf16, 16-byte
+ * aligned, owned by the caller and kept alive while the context lives: embed [vocab, hidden] (the embedding
+ * table; NULL when every step starts from hidden states), g_final [hidden] (gain of the final RMSNorm), w_lm
+ * [vocab, hidden] (the vocabulary projection; may be the same memory as embed).  They close a decode
+ * iteration as Sec. 4.2 measures it end to end (all transformer layers, then sampling).  ETC_ESTATE for a
+ * model without a vocabulary. */
+etc_status etc_bind_lm_head(etc_ctx *ctx, const void *embed, const void *g_final, const void *w_lm);
+
 /* Dynamic shape parameters of the next step(s) (Sec. 2.3).  kv_len[b] = tokens already cached:
  * the new token has position kv_len[b], is appended there and attends to kv_len[b]+1 keys.
  * Sequence b owns page_ids[page_indptr[b] .. page_indptr[b+1]) = ceil((kv_len[b]+1)/page_size)
@@ -181,6 +189,27 @@ etc_status etc_launch(etc_ctx *ctx, const void *hidden_in, void *hidden_out, voi
 /* The same task bodies, one ordinary kernel launch per operator stage (the kernel-by-kernel
  * model of Sec. 1); the launch-gap comparator.  Same arguments and results as etc_launch. */
 etc_status etc_launch_kernel_by_kernel(etc_ctx *ctx, const void *hidden_in, void *hidden_out, void *hip_stream);
+
+/* One whole decode iteration of a model with a vocabulary in one launch of the persistent kernel (Sec. 4.2: the
+ * low-batch serving loop, layers then sampling): embedding look-up, all layers, final RMSNorm, vocabulary
+ * projection and the greedy token of every sequence (largest logit; equal logits: the lower id), all as tasks
+ * of the same event-gated graph.  Exactly one of token_in (device, int32 [batch], ids in [0, vocab), needs the
+ * embedding table) and hidden_in (device, bf16 [batch, hidden]) is non-NULL.  token_out: device, int32
+ * [batch].  logits_out: device, fp32 [batch, vocab], or NULL (the logits then stay in the context's own
+ * buffer).  hidden_out: device, bf16 [batch, hidden] (the last layer's output before the final norm), or
+ * NULL.  Asynchronous on hip_stream like etc_launch.  Iterations chain without a host round trip: bind the
+ * next step's shapes (etc_bind_step does not synchronise) and launch with token_in = the previous token_out.
+ * A token id outside the table raises ETC_ERR_BAD_TABLE in the error word (the context is then dead, as after
+ * any device error).  ETC_ESTATE for a model without a vocabulary or before etc_bind_lm_head; on a model WITH
+ * a vocabulary etc_launch / etc_launch_kernel_by_kernel are refused with ETC_ESTATE (their graph ends in
+ * sampling tasks that need these buffers). */
+etc_status etc_launch_tokens(etc_ctx *ctx, const int32_t *token_in, const void *hidden_in, int32_t *token_out,
+                             float *logits_out, void *hidden_out, void *hip_stream);
+
+/* The kernel-by-kernel comparator of etc_launch_tokens: same arguments and results, one launch per stage. */
+etc_status etc_launch_tokens_kernel_by_kernel(etc_ctx *ctx, const int32_t *token_in, const void *hidden_in,
+                                              int32_t *token_out, float *logits_out, void *hidden_out,
+                                              void *hip_stream);
 
 /* ---- evidence / debug readback (synchronises the device) -------------------------------- */
 typedef enum {

@@ -181,6 +181,14 @@ def layer(shape: OrcShape, x, w: dict, kpool, vpool, kv_len, page_indptr, page_i
     return ids, dbg_arrays
 
 
+def embed(table, tokens):
+    """Start of a decode iteration: the hidden state of each sequence is the embedding row of its token
+    (paper Sec. 4.2 measures whole iterations, token in, token out).  table [V, H], tokens [B] -> [B, H] fp32."""
+    table, tokens = _f(table), np.asarray(tokens, dtype=np.int64)
+    assert tokens.min() >= 0 and tokens.max() < table.shape[0]
+    return np.stack([table[int(t)] for t in tokens]).astype(np.float32)
+
+
 def lm_head(shape: OrcShape, x, gf, wlm):
     """Final RMSNorm, vocabulary projection and greedy arg-max.  x [B, H], gf [H], wlm [V, H] ->
     (logits [B, V] fp32, token ids [B] int32)."""

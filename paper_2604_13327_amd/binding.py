@@ -22,6 +22,7 @@ MAP_DIM, MAP_CONST, MAP_INDIRECT, MAP_INDPTR = 0, 1, 2, 3
 
 EXPORTS = ["etc_create", "etc_destroy", "etc_last_error", "etc_bind_layer_weights", "etc_bind_kv_pool",
            "etc_bind_step", "etc_force_routing", "etc_launch", "etc_launch_kernel_by_kernel", "etc_read_debug",
+           "etc_bind_lm_head", "etc_launch_tokens", "etc_launch_tokens_kernel_by_kernel",
            "etc_get_step_info", "etc_graph_create", "etc_graph_add_event", "etc_graph_add_call",
            "etc_graph_bind_buffer", "etc_graph_bind_shape", "etc_graph_launch", "etc_plan_build", "etc_plan_free",
            "etc_rowsum_launch_noalloc"]
@@ -116,6 +117,9 @@ def lib():
     L.etc_force_routing.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
     L.etc_launch.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     L.etc_launch_kernel_by_kernel.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.etc_bind_lm_head.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.etc_launch_tokens.argtypes = [C.c_void_p] * 7
+    L.etc_launch_tokens_kernel_by_kernel.argtypes = [C.c_void_p] * 7
     L.etc_read_debug.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t]
     L.etc_get_step_info.argtypes = [C.c_void_p, C.POINTER(StepInfo)]
     L.etc_graph_create.argtypes = [C.POINTER(SchedDesc), C.POINTER(C.c_void_p)]
@@ -135,7 +139,8 @@ def lib():
 def _model_desc(s) -> ModelDesc:
     return ModelDesc(n_layers=s.n_layers, hidden=s.H, n_q_heads=s.nq, n_kv_heads=s.nkv, head_dim=s.d, ffn=s.F,
                      n_experts=s.n_experts, top_k=s.top_k, moe_ffn=s.moe_F, page_size=s.page, rms_eps=s.eps,
-                     rope_theta=s.theta, qk_norm=1 if getattr(s, "qk_norm", False) else 0, vocab=0)
+                     rope_theta=s.theta, qk_norm=1 if getattr(s, "qk_norm", False) else 0,
+                     vocab=int(getattr(s, "vocab", 0) or 0))
 
 
 def _sched_desc(kind, sampled_batches, max_kv_len, debug_flags=0, spin_budget=0, n_queues=0) -> SchedDesc:
@@ -256,6 +261,24 @@ class Decoder(_Ctx):
     def launch_kernel_by_kernel(self, hidden_in, hidden_out, stream=None):
         self._check(self._L.etc_launch_kernel_by_kernel(self._h, hidden_in.data_ptr(), hidden_out.data_ptr(),
                                                         _stream_ptr(stream)))
+
+    def bind_lm_head(self, embed, g_final, w_lm):
+        """torch bf16 CUDA tensors: embed [vocab, hidden] or None, g_final [hidden], w_lm [vocab, hidden]."""
+        for t in (embed, g_final, w_lm):
+            assert t is None or (t.is_cuda and t.is_contiguous() and t.element_size() == 2)
+        self._keep.append((embed, g_final, w_lm))
+        self._check(self._L.etc_bind_lm_head(self._h, None if embed is None else embed.data_ptr(), g_final.data_ptr(),
+                                             w_lm.data_ptr()))
+
+    def launch_tokens(self, token_out, token_in=None, hidden_in=None, logits_out=None, hidden_out=None, stream=None,
+                      kernel_by_kernel=False):
+        """One whole decode iteration (embedding or hidden state in, greedy token and logits out)."""
+        ptr = lambda t: None if t is None else t.data_ptr()      # noqa: E731
+        assert token_out.dtype.itemsize == 4 and (token_in is None or token_in.dtype.itemsize == 4)
+        assert logits_out is None or (logits_out.dtype.itemsize == 4 and logits_out.is_contiguous())
+        fn = self._L.etc_launch_tokens_kernel_by_kernel if kernel_by_kernel else self._L.etc_launch_tokens
+        self._check(fn(self._h, ptr(token_in), ptr(hidden_in), ptr(token_out), ptr(logits_out), ptr(hidden_out),
+                       _stream_ptr(stream)))
 
     def step_info(self) -> StepInfo:
         info = StepInfo()

@@ -118,7 +118,7 @@ struct etc_ctx {
     uint8_t *d_forced_mask = nullptr;
     std::vector<uint8_t> h_forced_mask;
     int64_t pages_per_layer = 0;
-    bool kv_bound = false, step_bound = false;
+    bool kv_bound = false, step_bound = false, lm_bound = false;
     int bound_batch = 0;
     std::vector<int32_t> h_kv_len;
     int64_t algorithmic_bytes = 0;
@@ -347,10 +347,34 @@ etc_status upload_step_on_stream(etc_ctx *c, hipStream_t s)
     return ETC_OK;
 }
 
-etc_status pre_launch(etc_ctx *c, const void *hidden_in, void *hidden_out, Params &P, hipStream_t s)
+void post_launch(etc_ctx *c)
+{
+    c->parity ^= 1;
+    c->epoch++;
+    if (c->epoch == 0) c->epoch = 1;
+}
+
+// What a launch of a model with a vocabulary adds to the step's buffers.
+struct TokenIo {
+    const int32_t *token_in;
+    int32_t *token_out;
+    float *logits_out;
+};
+
+etc_status pre_launch(etc_ctx *c, const void *hidden_in, void *hidden_out, Params &P, hipStream_t s, const TokenIo *tok = nullptr)
 {
     if (!c || c->is_graph) return fail(c, ETC_EINVAL, "not a decoder context");
-    if (!hidden_in || !hidden_out) return fail(c, ETC_EINVAL, "hidden_in / hidden_out is NULL");
+    if (!tok) {
+        if (!hidden_in || !hidden_out) return fail(c, ETC_EINVAL, "hidden_in / hidden_out is NULL");
+        if (c->model.vocab > 0) return fail(c, ETC_ESTATE, "this model ends in sampling tasks: launch it with etc_launch_tokens");
+    } else {
+        if (c->model.vocab <= 0) return fail(c, ETC_ESTATE, "the model has no vocabulary");
+        if (!c->lm_bound) return fail(c, ETC_ESTATE, "no LM head bound");
+        if ((tok->token_in != nullptr) == (hidden_in != nullptr))
+            return fail(c, ETC_EINVAL, "exactly one of token_in and hidden_in must be given");
+        if (tok->token_in && !c->base.embed) return fail(c, ETC_ESTATE, "token_in needs the embedding table");
+        if (!tok->token_out) return fail(c, ETC_EINVAL, "token_out is NULL");
+    }
     if (!c->kv_bound) return fail(c, ETC_ESTATE, "no KV pool bound");
     if (!c->step_bound) return fail(c, ETC_ESTATE, "no step bound");
     etc_status st = refuse_if_dead(c);
@@ -364,15 +388,41 @@ etc_status pre_launch(etc_ctx *c, const void *hidden_in, void *hidden_out, Param
     fill_launch_params(c, P);
     P.hidden_in = (const uint16_t *)hidden_in;
     P.hidden_out = (uint16_t *)hidden_out;
+    if (tok) {
+        P.token_in = tok->token_in;
+        P.token_out = tok->token_out;
+        if (tok->logits_out) P.logits = tok->logits_out;
+    }
     return ETC_OK;
 }
 
-void post_launch(etc_ctx *c)
+etc_status launch_fused(etc_ctx *c, Params &P, hipStream_t s)
 {
-    c->parity ^= 1;
-    c->epoch++;
-    if (c->epoch == 0) c->epoch = 1;
+    if (c->sched.kind == ETC_SCHED_DYNAMIC) {
+        if (!kDynamicEnabled) return fail(c, ETC_ESTATE, kDynamicOffMsg);
+        HIP_TRY(c, launch_dynamic(P, s));
+    } else {
+        HIP_TRY(c, launch_static(P, s));
+    }
+    post_launch(c);
+    return ETC_OK;
 }
+
+etc_status launch_stages(etc_ctx *c, Params &P, hipStream_t s)
+{
+    const Plan &pl = c->plans[c->cur_plan].host;
+    P.moe_dd = 0;        // no events and no ready queue here: the router tiles release nothing, every slot task runs
+    // one launch per operator stage; the calls of a stage are contiguous in task-id order
+    size_t ci = 0;
+    while (ci < pl.stage_of_call.size()) {
+        size_t cj = ci;
+        while (cj + 1 < pl.stage_of_call.size() && pl.stage_of_call[cj + 1] == pl.stage_of_call[ci]) ++cj;
+        HIP_TRY(c, launch_stage(P, pl.call_begin[ci], pl.call_begin[cj + 1] - pl.call_begin[ci], s));
+        ci = cj + 1;
+    }
+    return ETC_OK;   // event buffers untouched: parity and epoch stay
+}
+
 
 }  // namespace
 
@@ -426,6 +476,7 @@ etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc
     ModelDims &d = c->dims;
     d = ModelDims{m->n_layers, m->hidden, m->n_q_heads, m->n_kv_heads, m->head_dim, m->ffn, m->n_experts,
                   m->top_k, m->moe_ffn, m->page_size, t->kv_chunk_tokens, std::max(1, t->moe_tile_m)};
+    d.vocab = m->vocab > 0 ? m->vocab : 0;
     etc_status st = common_device_setup(c, s);
     if (st != ETC_OK) return bail(st);
     c->max_chunks = (s->max_kv_len + t->kv_chunk_tokens - 1) / t->kv_chunk_tokens;
@@ -457,6 +508,7 @@ etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc
     P.F = m->ffn; P.E = m->n_experts; P.topk = m->top_k; P.moeF = m->moe_ffn; P.page = m->page_size;
     P.eps = m->rms_eps; P.theta = m->rope_theta; P.kv_chunk = t->kv_chunk_tokens; P.tile_m = d.tile_m;
     P.qk_norm = m->qk_norm ? 1 : 0;
+    P.vocab = d.vocab;
     auto A = [&](auto **p, size_t n) -> bool {
         hipError_t e = dev_alloc(p, n, c->owned);
         if (e != hipSuccess) { c->err = std::string("device allocation failed: ") + hipGetErrorString(e); return false; }
@@ -499,6 +551,7 @@ etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc
         for (const DevPlan &dp : c->plans) most = std::max(most, std::max(dp.k_slices_o, dp.k_slices_d));
         if (okk && most > 0) okk = A(&P.kpart, (size_t)most * (H / 16) * kMaxBatch * 16);
     }
+    if (okk && d.vocab > 0) okk = A(&P.logits, MB * (size_t)d.vocab) && A(&P.best, MB);
     if (okk && (s->debug_flags & ETC_DEBUG_LAYER_HIDDEN)) okk = A(&P.layer_hidden, (size_t)m->n_layers * kMaxBatch * H);
     P.max_batch = s->max_batch;
     if (okk && m->n_experts > 0) {
@@ -534,6 +587,20 @@ etc_status etc_bind_layer_weights(etc_ctx *c, int32_t layer, const etc_layer_wei
     c->h_weights[layer] = LayerWeights{w->g1, w->wq, w->wk, w->wv, w->wo, w->g2, w->wg, w->wu, w->wd, w->wr, w->eg, w->eu, w->ed, w->gq, w->gk};
     c->weights_bound[layer] = 1;
     c->weights_dirty = true;
+    return ETC_OK;
+}
+
+etc_status etc_bind_lm_head(etc_ctx *c, const void *embed, const void *g_final, const void *w_lm)
+{
+    if (!c || c->is_graph) return fail(c, ETC_EINVAL, "not a decoder context");
+    if (c->model.vocab <= 0) return fail(c, ETC_ESTATE, "the model has no vocabulary");
+    if (!g_final || !w_lm) return fail(c, ETC_EINVAL, "g_final / w_lm is NULL");
+    if (((uintptr_t)embed & 15) || ((uintptr_t)g_final & 15) || ((uintptr_t)w_lm & 15))
+        return fail(c, ETC_EINVAL, "LM head pointers must be 16-byte aligned");
+    c->base.embed = (const uint16_t *)embed;
+    c->base.gf = (const uint16_t *)g_final;
+    c->base.wlm = (const uint16_t *)w_lm;
+    c->lm_bound = true;
     return ETC_OK;
 }
 
@@ -642,14 +709,7 @@ etc_status etc_launch(etc_ctx *c, const void *hidden_in, void *hidden_out, void 
     hipStream_t s = (hipStream_t)hip_stream;
     etc_status st = pre_launch(c, hidden_in, hidden_out, P, s);
     if (st != ETC_OK) return st;
-    if (c->sched.kind == ETC_SCHED_DYNAMIC) {
-        if (!kDynamicEnabled) return fail(c, ETC_ESTATE, kDynamicOffMsg);
-        HIP_TRY(c, launch_dynamic(P, s));
-    } else {
-        HIP_TRY(c, launch_static(P, s));
-    }
-    post_launch(c);
-    return ETC_OK;
+    return launch_fused(c, P, s);
 }
 
 etc_status etc_launch_kernel_by_kernel(etc_ctx *c, const void *hidden_in, void *hidden_out, void *hip_stream)
@@ -658,17 +718,29 @@ etc_status etc_launch_kernel_by_kernel(etc_ctx *c, const void *hidden_in, void *
     hipStream_t s = (hipStream_t)hip_stream;
     etc_status st = pre_launch(c, hidden_in, hidden_out, P, s);
     if (st != ETC_OK) return st;
-    const Plan &pl = c->plans[c->cur_plan].host;
-    P.moe_dd = 0;        // no events and no ready queue here: the router tiles release nothing, every slot task runs
-    // one launch per operator stage; the calls of a stage are contiguous in task-id order
-    size_t ci = 0;
-    while (ci < pl.stage_of_call.size()) {
-        size_t cj = ci;
-        while (cj + 1 < pl.stage_of_call.size() && pl.stage_of_call[cj + 1] == pl.stage_of_call[ci]) ++cj;
-        HIP_TRY(c, launch_stage(P, pl.call_begin[ci], pl.call_begin[cj + 1] - pl.call_begin[ci], s));
-        ci = cj + 1;
-    }
-    return ETC_OK;   // event buffers untouched: parity and epoch stay
+    return launch_stages(c, P, s);
+}
+
+etc_status etc_launch_tokens(etc_ctx *c, const int32_t *token_in, const void *hidden_in, int32_t *token_out, float *logits_out,
+                             void *hidden_out, void *hip_stream)
+{
+    Params P;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const TokenIo tok{token_in, token_out, logits_out};
+    etc_status st = pre_launch(c, hidden_in, hidden_out, P, s, &tok);
+    if (st != ETC_OK) return st;
+    return launch_fused(c, P, s);
+}
+
+etc_status etc_launch_tokens_kernel_by_kernel(etc_ctx *c, const int32_t *token_in, const void *hidden_in, int32_t *token_out,
+                                              float *logits_out, void *hidden_out, void *hip_stream)
+{
+    Params P;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const TokenIo tok{token_in, token_out, logits_out};
+    etc_status st = pre_launch(c, hidden_in, hidden_out, P, s, &tok);
+    if (st != ETC_OK) return st;
+    return launch_stages(c, P, s);
 }
 
 etc_status etc_read_debug(etc_ctx *c, int32_t kind, int32_t layer, void *dst, size_t bytes)
@@ -763,6 +835,7 @@ etc_status etc_plan_build(const etc_model_desc *m, const etc_tile_desc *t, const
     if (t->kv_chunk_tokens < 1 || s->max_kv_len < 1) return fail(nullptr, ETC_EINVAL, "bad chunk or max_kv_len");
     ModelDims d{m->n_layers, m->hidden, m->n_q_heads, m->n_kv_heads, m->head_dim, m->ffn, m->n_experts,
                 m->top_k, m->moe_ffn, m->page_size, t->kv_chunk_tokens, std::max(1, t->moe_tile_m)};
+    d.vocab = m->vocab > 0 ? m->vocab : 0;
     GraphDecl g;
     std::string err = build_decoder_graph(d, sampled_batch, n_queues, s->kind != ETC_SCHED_DYNAMIC, &g);
     if (!err.empty()) return fail(nullptr, ETC_EINVAL, err);

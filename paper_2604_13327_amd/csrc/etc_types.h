@@ -57,6 +57,9 @@ enum Fn : uint8_t {
     FN_COMBINE = 14,      // MoE: weighted sum of a token's expert outputs in slot order + residual
     FN_OPROJ_SUM = 15,    // large batches: fixed-order sum of the K-slice partials of 16 rows of the O projection + residual
     FN_DOWN_SUM = 16,     // the same for the down projection
+    FN_LMHEAD = 18,       // end of the iteration: final RMSNorm folded in, consecutive 16-row tiles of the vocabulary projection ->
+                          //   fp32 logits, and each tile's best (logit, id) folded into the sequence's running maximum
+    FN_SAMPLE = 19,       // greedy token of every sequence from the running maxima (ties: lower id)
     FN_COUNT
 };
 
@@ -100,6 +103,12 @@ struct Params {
     int32_t kv_chunk, tile_m;
     int32_t qk_norm;                   // per-head RMSNorm of q and k before RoPE (Qwen3-style)
     int32_t vocab;                     // > 0: final norm + vocabulary projection + greedy token at the end of the step
+    const uint16_t *embed, *gf, *wlm;  // bf16: embedding table [vocab, H] (null: steps start from hidden states), final norm gain [H],
+                                       //   vocabulary projection [vocab, H]
+    const int32_t *token_in;           // [B] token ids whose embedding rows start the step (null: hidden_in does)
+    int32_t *token_out;                // [B] greedy tokens
+    float *logits;                     // [B, vocab] fp32
+    unsigned long long *best;          // [maxB] running maximum of (ordered logit bits << 32 | ~id), cleared by the step prologue
     // resident tensors
     const LayerWeights *weights;       // [n_layers] device
     uint16_t *kpool, *vpool;           // bf16 bits

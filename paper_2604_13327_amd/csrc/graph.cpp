@@ -450,6 +450,39 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
         }
         e_x = e_xnext;
     }
+    if (m.vocab > 0) {
+        // End of the iteration: final RMSNorm (folded into the projection like every other norm), vocabulary
+        // projection and greedy token.  A projection task streams consecutive 16-row tiles of the matrix, about
+        // one task per queue on the staged path; the last task is ragged.  Each tile folds its best (logit, id)
+        // into the sequence's running maximum, so the sampling task that follows reads one word per sequence.
+        if (m.vocab % 16) return "vocab must be a multiple of 16";
+        const int tiles = m.vocab / 16;
+        int r_lm = pass_tiles;
+        if (staged_fits(1, Bs, m.H)) {
+            r_lm = std::max(1, (tiles + n_queues - 1) / std::max(1, n_queues));
+            while (r_lm > 1 && !staged_fits(r_lm, Bs, m.H)) --r_lm;
+        }
+        g.all_staged = g.all_staged && staged_fits(r_lm, Bs, m.H);
+        const int e_logits = g.add_event({one});
+        const int e_tok = g.add_event({one});
+        {
+            CallDecl c;
+            c.fn = FN_LMHEAD; c.layer = m.n_layers - 1; c.stage = stage++;      // task record: (first tile, tiles at most)
+            c.rank = 1; c.shape[0] = dim_const((tiles + r_lm - 1) / r_lm);
+            c.c_mul[0] = r_lm; c.c_fill[1] = r_lm;
+            c.in = {edge_const0(e_x)};
+            c.out = {edge_const0(e_logits)};
+            g.calls.push_back(c);
+        }
+        {
+            CallDecl c;
+            c.fn = FN_SAMPLE; c.layer = m.n_layers - 1; c.stage = stage++;
+            c.rank = 1; c.shape[0] = one;
+            c.in = {edge_const0(e_logits)};
+            c.out = {edge_const0(e_tok)};
+            g.calls.push_back(c);
+        }
+    }
     return "";
 }
 

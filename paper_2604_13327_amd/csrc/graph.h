@@ -89,6 +89,7 @@ std::string instantiate(const GraphDecl &g, const int *sym_values, int n_queues,
 struct ModelDims {
     int n_layers, H, nq, nkv, d, F, E, topk, moeF, page;
     int kv_chunk, tile_m;
+    int vocab = 0;      // > 0: the step ends in final norm + vocabulary projection + greedy token
 };
 
 // Upper bound of sum_e ceil(count_e / tile_m) over all routings of `batch` tokens: the number of

@@ -71,12 +71,25 @@ __device__ __forceinline__ void load_hidden(const Params &P, int b)
         const int page = gld_i32(P.page_ids + gld_i32(P.page_indptr + b) + pos / P.page);
         st_i32(P.kv_slot + b, page * P.page + pos % P.page);
     }
+    // The step starts from the sequence's hidden state, or from the embedding row of its token (the token the
+    // previous iteration sampled).  An id outside the table raises an error and reads row 0.
+    const uint16_t *src = P.hidden_in + (size_t)b * P.H;
+    if (P.token_in) {
+        int tok = gld_i32(P.token_in + b);
+        if (tok < 0 || tok >= P.vocab) {
+            if (threadIdx.x == 0) raise_error(P, ERR_BAD_TABLE, FN_LOAD_HIDDEN, tok);
+            tok = 0;
+        }
+        src = P.embed + (size_t)tok * P.H;
+    }
+    if (threadIdx.x == 0 && P.best)       // below the key of every logit
+        __hip_atomic_store(as_global(P.best + b), 0ull, __ATOMIC_RELAXED, ETC_SCOPE);
     const uint16_t *g1 = (const uint16_t *)as_global(P.weights)[0].g1;
     for (int part = threadIdx.x; part < P.H / 16; part += kWgThreads) {
         float s = 0.f;
         for (int i = 0; i < 16; ++i) {
             const size_t o = (size_t)b * P.H + part * 16 + i;
-            const float v = bf16_bits_to_f32(gld_u16(P.hidden_in + o));
+            const float v = bf16_bits_to_f32(gld_u16(src + part * 16 + i));
             st_f32(P.x + o, v);
             uint16_t hi, lo;
             split_bf16(v * bf16_bits_to_f32(gld_u16(g1 + part * 16 + i)), hi, lo);
@@ -166,10 +179,23 @@ __device__ __forceinline__ bool setup_gemm(const Params &P, const Task &t, GemmT
         g.n_cols = P.B;
         e.kind = EPI_RESID; e.layer = t.layer; e.row0 = r0; e.resid = P.x_mid; e.outf = P.x; e.ld = P.H;
         e.flags = (uint16_t)((t.flags & TF_LAST_LAYER) | ((P.debug_flags & 2u) ? EPF_DUMP_LAYER : 0));
-        if (!(t.flags & TF_LAST_LAYER)) {     // operand of the next layer's QKV projection
-            e.next_gain = (const uint16_t *)as_global(P.weights)[t.layer + 1].g1; e.out_hi = P.xg_hi; e.out_lo = P.xg_lo;
+        if (!(t.flags & TF_LAST_LAYER) || P.vocab > 0) {     // operand of the next layer's QKV projection, or of the vocabulary projection
+            e.next_gain = (t.flags & TF_LAST_LAYER) ? P.gf : (const uint16_t *)as_global(P.weights)[t.layer + 1].g1;
+            e.out_hi = P.xg_hi; e.out_lo = P.xg_lo;
             e.ssq_out = P.ssq_x + (size_t)t.c0 * kMaxBatch;
         }
+        return true;
+    }
+    case FN_LMHEAD: {
+        const int tiles = P.vocab >> 4, r0 = t.c0 * 16;      // c1 = tiles per task; the last task takes what is left
+        g.n_tiles = tiles - t.c0 < t.c1 ? tiles - t.c0 : t.c1; g.tile_rows = 16;
+        g.rowsA = P.wlm + (size_t)r0 * P.H;
+        g.rowsB = g.rowsA + (size_t)8 * P.H;
+        g.ldw = P.H; g.K = P.H;
+        g.b_hi = P.xg_hi; g.b_lo = P.xg_lo; g.ldb = P.H;
+        g.ssq_parts = P.ssq_x; g.n_parts = P.H / 16; g.eps = P.eps;
+        g.n_cols = P.B;
+        e.kind = EPI_LOGITS; e.layer = t.layer; e.row0 = r0; e.outf = P.logits; e.ld = P.vocab;
         return true;
     }
     case FN_ROUTER_LOGITS: {
@@ -306,6 +332,13 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
     switch (t.fn) {
     case FN_LOAD_HIDDEN:
         if (t.c0 < P.B) load_hidden(P, t.c0);
+        break;
+    case FN_SAMPLE:
+        wg_wait_cached(P, st, w0, w1, t.fn);
+        if ((int)threadIdx.x < P.B) {
+            const unsigned long long key = ld_u64(P.best + threadIdx.x);
+            *as_global(P.token_out + threadIdx.x) = (int32_t)(0xFFFFFFFFu - (uint32_t)(key & 0xFFFFFFFFull));
+        }
         break;
     case FN_OPROJ_SUM:
     case FN_DOWN_SUM:

@@ -42,7 +42,7 @@ struct GemmTile {
 constexpr uint16_t EPF_DUMP_LAYER = 0x8000;   // epilogue also records the layer's hidden state
 
 enum EpiKind : int { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_STORE_F32 = 3, EPI_MOE_ACT = 4, EPI_MOE_Y = 5,
-                     EPI_PARTIAL = 6 };   // PARTIAL: fp32 sums over one slice of K, [row tile][kMaxBatch][16], outf = the slice's block
+                     EPI_PARTIAL = 6, EPI_LOGITS = 7 };   // PARTIAL: fp32 sums over one slice of K, [row tile][kMaxBatch][16], outf = the slice's block
 
 struct Epilogue {
     int kind;
@@ -741,6 +741,14 @@ __device__ __forceinline__ void rope_cos_sin(const Params &P, int pos, int i, fl
     *sn = __sinf(r);
 }
 
+// Sort key of (logit, vocabulary id): larger logit first, then lower id.
+__device__ __forceinline__ unsigned long long logit_key(float v, int id)
+{
+    const uint32_t u = __float_as_uint(v);
+    const uint32_t ordered = u ^ ((u >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+    return ((unsigned long long)ordered << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)id);
+}
+
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 
 __device__ __forceinline__ void store_split(uint16_t *hi_p, uint16_t *lo_p, size_t idx, float v)
@@ -835,7 +843,7 @@ __device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &
         float s = v0 * v0 + v1 * v1;      // this tile's sum of squares: the 8 threads of a column are 8 consecutive lanes
         s = lanes_sum<8>(s);
         if (mp == 0 && e.ssq_out) st_f32(e.ssq_out + b, s);
-        if (e.flags & TF_LAST_LAYER) {
+        if ((e.flags & TF_LAST_LAYER) && P.hidden_out) {
             gst_u16(P.hidden_out + o0, f32_to_bf16_bits(v0));
             gst_u16(P.hidden_out + o1, f32_to_bf16_bits(v1));
         }
@@ -853,6 +861,24 @@ __device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &
     case EPI_STORE_F32: {
         st_f32(e.outf + (size_t)col * e.ld + e.row0 + mp, lo);
         st_f32(e.outf + (size_t)col * e.ld + e.row0 + mp + 8, hi);
+        break;
+    }
+    case EPI_LOGITS: {
+        // fp32 logits of 16 vocabulary rows, and the tile's best (logit, id) into the sequence's running maximum.
+        // The key orders like the logit (sign-folded bits) and, among equal logits, like the complement of the id,
+        // so that the maximum is the greedy token with ties to the lower id; max is exact and order-free, so the
+        // result does not depend on which tile arrives first.
+        const int r = e.row0 + mp;
+        st_f32(e.outf + (size_t)col * e.ld + r, lo);
+        st_f32(e.outf + (size_t)col * e.ld + r + 8, hi);
+        unsigned long long key = logit_key(lo, r), k2 = logit_key(hi, r + 8);
+        key = k2 > key ? k2 : key;
+#pragma unroll
+        for (int off = 1; off < 8; off <<= 1) {        // the 8 threads of a column are 8 consecutive lanes
+            const unsigned long long o = __shfl_xor(key, off, 64);
+            key = o > key ? o : key;
+        }
+        if (mp == 0) __hip_atomic_fetch_max(as_global(P.best + col), key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         break;
     }
     case EPI_MOE_ACT: {

@@ -299,10 +299,10 @@ __device__ __forceinline__ void moe_combine(const Params &P, const Task &t)
     const size_t o = (size_t)b * P.H + h;
     const float v = ld_f32(P.x_mid + o) + acc;
     st_f32(P.x + o, v);
-    if (t.flags & TF_LAST_LAYER) {
-        gst_u16(P.hidden_out + o, f32_to_bf16_bits(v));
-    } else {
-        const uint16_t *g1 = (const uint16_t *)as_global(P.weights)[t.layer + 1].g1;
+    const bool last = (t.flags & TF_LAST_LAYER) != 0;
+    if (last && P.hidden_out) gst_u16(P.hidden_out + o, f32_to_bf16_bits(v));
+    if (!last || P.vocab > 0) {       // operand of the next projection: the next layer's QKV, or the vocabulary projection
+        const uint16_t *g1 = last ? P.gf : (const uint16_t *)as_global(P.weights)[t.layer + 1].g1;
         uint16_t hi, lo;
         split_bf16(v * bf16_bits_to_f32(gld_u16(g1 + h)), hi, lo);
         st_u16(P.xg_hi + o, hi);

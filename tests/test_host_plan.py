@@ -449,3 +449,38 @@ def test_mid_batch_down_projection_is_cut_along_k():
     assert len(d2) == 256 and (d2["flags"] & PER_WAVE).all() and not (d2["flags"] & 8).any()
     assert ((t2["fn"] == 16) | (t2["fn"] == 15)).sum() == 0
 
+
+
+@pytest.mark.parametrize("kind", [etc.SCHED_STATIC, etc.SCHED_DYNAMIC, etc.SCHED_UNFUSED])
+@pytest.mark.parametrize("shape,batch,nq", [(synth.TINY_LM, 1, 7), (synth.TINY_LM, 3, 256), (synth.TINY_MOE_LM, 2, 16),
+                                            (synth.TINY_LM, 40, 16)])
+def test_lm_head_tasks_close_the_step(kind, shape, batch, nq):
+    """A model with a vocabulary ends in vocabulary-projection tasks that cover every 16-row tile exactly once
+    (the last task ragged) and one sampling task behind all of them; the plan still runs to completion."""
+    plan = etc.plan_build(shape, 32, batch, nq, max_kv_len=129, kind=kind)
+    tasks = plan["tasks"]
+    FN_LMHEAD, FN_SAMPLE = 18, 19
+    lm = tasks[tasks["fn"] == FN_LMHEAD]
+    smp = tasks[tasks["fn"] == FN_SAMPLE]
+    assert len(smp) == 1 and len(lm) >= 1
+    tiles = shape.vocab // 16
+    covered = np.zeros(tiles, np.int64)
+    for t in lm:
+        c0, r = int(t["c0"]), int(t["c1"])
+        covered[c0:min(tiles, c0 + r)] += 1
+        assert c0 < tiles
+    assert (covered == 1).all()
+    assert int(smp[0]["id"]) == len(tasks) - 1 and (lm["id"] < smp[0]["id"]).all()
+    if kind == etc.SCHED_DYNAMIC:
+        ev, done = run_dynamic(plan, 5, np.random.default_rng(1))
+    else:
+        ev, done = run_static(plan, np.random.default_rng(2))
+    assert (ev == 0).all() and (done == 1).all()
+    if kind != etc.SCHED_UNFUSED:       # the sampling task waits for every projection task
+        assert plan["ev_init"][int(smp[0]["wait0"])] == len(lm)
+
+
+def test_vocab_must_be_a_multiple_of_16():
+    import dataclasses
+    with pytest.raises(etc.EtcError):
+        etc.plan_build(dataclasses.replace(synth.TINY_LM, vocab=1000), 32, 1, 8, max_kv_len=129)

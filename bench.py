@@ -256,6 +256,40 @@ def main() -> int:
             except etc.EtcError as err:          # a comparator must not cost the headline line
                 result["dynamic_megakernel_error"] = str(err)
 
+    # ---- the whole decode iteration (Sec. 4.2 measures iterations: token in, layers, sampling, token out) ------
+    # The same step with embedding look-up, final norm, vocabulary projection and greedy token inside the
+    # megakernel, each launch reading the token the previous one wrote (no host round trip).
+    vocab = {"llama3-8b": 128256, "llama3-70b": 128256, "qwen3-32b": 151936, "qwen3-30b-a3b": 151936, "tiny": 1024}.get(args.workload, 0)
+    if not args.no_comparators and vocab:
+        import dataclasses
+        from synth import gpu as sgpu
+        shape_lm = dataclasses.replace(shape, vocab=vocab)
+        if args.fast_fill:
+            lm = {n: torch.empty(shp, dtype=torch.bfloat16, device="cuda").normal_(mean, sigma)
+                  for n, shp, mean, sigma in synth.lm_specs(shape_lm)}
+        else:
+            lm = sgpu.lm_weights_gpu(shape_lm, seed)
+        it = etc.Decoder(shape_lm, kv_chunk_tokens=args.kv_chunk, sampled_batches=[B], max_kv_len=L + 1, kind=kind)
+        model.bind(it)
+        it.bind_lm_head(lm["embed"], lm["gf"], lm["wlm"])
+        it.bind_step(step)
+        toks = torch.randint(0, vocab, (2, B), dtype=torch.int32, device="cuda")
+        flip = [0]
+
+        def iteration(_x, _out):
+            it.launch_tokens(toks[flip[0] ^ 1], token_in=toks[flip[0]])
+            flip[0] ^= 1
+        k = max(5, min(20, args.steps))
+        _, span_it, _ = timed(iteration, k, 2)
+        lm_bytes = vocab * shape.H * 2
+        result["iteration_with_sampling_us"] = round(float(span_it), 2)
+        result["lm_head_and_sampling_us"] = round(float(span_it) - us, 2)
+        result["lm_head_gbs"] = round(lm_bytes / max(1e-9, (float(span_it) - us) * 1e-6) / 1e9, 1)
+        result["iteration_hbm_frac"] = round((alg + lm_bytes) / (float(span_it) * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
+        assert (it.error_word() == 0).all()
+        it.close()
+        del lm
+
     # ---- the cost of binding a step on the real per-step path: kv_len grows by one every step -------------
     # (last of the GPU measurements: these steps append rows at other positions of the KV pool)
     if args.bind_every_step or not args.no_comparators:

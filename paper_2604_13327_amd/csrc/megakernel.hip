@@ -58,6 +58,7 @@ __device__ __forceinline__ void rowsum_final_perm(const Params &P, int t)
 // operand (x * g1, split) and the partial sums of squares per 16 elements, as every later producer does.
 // Also what every layer's QKV epilogue needs of the step's shape, resolved once: the (cos, sin) of the RoPE
 // angles at the sequence's position and the KV slot the new row goes to (page table look-up).
+template <bool LM>
 __device__ __forceinline__ void load_hidden(const Params &P, int b)
 {
     const int pos = gld_i32(P.kv_len + b);
@@ -74,7 +75,7 @@ __device__ __forceinline__ void load_hidden(const Params &P, int b)
     // The step starts from the sequence's hidden state, or from the embedding row of its token (the token the
     // previous iteration sampled).  An id outside the table raises an error and reads row 0.
     const uint16_t *src = P.hidden_in + (size_t)b * P.H;
-    if (P.token_in) {
+    if (LM && P.token_in) {
         int tok = gld_i32(P.token_in + b);
         if (tok < 0 || tok >= P.vocab) {
             if (threadIdx.x == 0) raise_error(P, ERR_BAD_TABLE, FN_LOAD_HIDDEN, tok);
@@ -82,7 +83,7 @@ __device__ __forceinline__ void load_hidden(const Params &P, int b)
         }
         src = P.embed + (size_t)tok * P.H;
     }
-    if (threadIdx.x == 0 && P.best)       // below the key of every logit
+    if (LM && threadIdx.x == 0 && P.best)       // below the key of every logit
         __hip_atomic_store(as_global(P.best + b), 0ull, __ATOMIC_RELAXED, ETC_SCOPE);
     const uint16_t *g1 = (const uint16_t *)as_global(P.weights)[0].g1;
     for (int part = threadIdx.x; part < P.H / 16; part += kWgThreads) {
@@ -122,7 +123,7 @@ __device__ __forceinline__ void slice_of_k(const Params &P, const Task &t, int n
 }
 
 // Fills the tile and epilogue descriptors of a projection task; false for every other task kind.
-template <bool MOE>
+template <bool MOE, bool LM>
 __device__ __forceinline__ bool setup_gemm(const Params &P, const Task &t, GemmTile &g, Epilogue &e)
 {
     const ETC_AS_GLOBAL LayerWeights *W = as_global(P.weights) + t.layer;
@@ -179,14 +180,16 @@ __device__ __forceinline__ bool setup_gemm(const Params &P, const Task &t, GemmT
         g.n_cols = P.B;
         e.kind = EPI_RESID; e.layer = t.layer; e.row0 = r0; e.resid = P.x_mid; e.outf = P.x; e.ld = P.H;
         e.flags = (uint16_t)((t.flags & TF_LAST_LAYER) | ((P.debug_flags & 2u) ? EPF_DUMP_LAYER : 0));
-        if (!(t.flags & TF_LAST_LAYER) || P.vocab > 0) {     // operand of the next layer's QKV projection, or of the vocabulary projection
-            e.next_gain = (t.flags & TF_LAST_LAYER) ? P.gf : (const uint16_t *)as_global(P.weights)[t.layer + 1].g1;
+        const bool to_lm = LM && P.vocab > 0 && (t.flags & TF_LAST_LAYER);
+        if (!(t.flags & TF_LAST_LAYER) || to_lm) {     // operand of the next layer's QKV projection, or of the vocabulary projection
+            e.next_gain = to_lm ? P.gf : (const uint16_t *)as_global(P.weights)[t.layer + 1].g1;
             e.out_hi = P.xg_hi; e.out_lo = P.xg_lo;
             e.ssq_out = P.ssq_x + (size_t)t.c0 * kMaxBatch;
         }
         return true;
     }
     case FN_LMHEAD: {
+        if (!LM) return false;
         const int tiles = P.vocab >> 4, r0 = t.c0 * 16;      // c1 = tiles per task; the last task takes what is left
         g.n_tiles = tiles - t.c0 < t.c1 ? tiles - t.c0 : t.c1; g.tile_rows = 16;
         g.rowsA = P.wlm + (size_t)r0 * P.H;
@@ -223,10 +226,10 @@ __device__ __noinline__ WgState k_slice_task(const Params &PL, Task t, TaskWaits
 {
     GemmTile g{};
     Epilogue e{};
-    setup_gemm<false>(PL, t, g, e);
+    setup_gemm<false, true>(PL, t, g, e);
     slice_of_k(PL, t, t.fn == FN_OPROJ ? PL.k_slices_o : PL.k_slices_d, g, e);
     if (tw.ev0 >= 0) tw.op_key = tw.ev0 + ((t.c1 + 1) << 20);      // a staged copy holds one slice
-    gemm_tile_dispatch(PL, PL, g, e, tw, sm, st, t.id);
+    gemm_tile_dispatch<false>(PL, PL, g, e, tw, sm, st, t.id);
     return st;
 }
 // Second stage: the slices' partial sums of row tile c0, then the projection's own epilogue.
@@ -236,7 +239,7 @@ __device__ __noinline__ void k_slice_sum_task(const Params &PL, Task t, int w0, 
     Epilogue e{};
     const bool o_proj = t.fn == FN_OPROJ_SUM;
     t.fn = o_proj ? FN_OPROJ : FN_DOWN;
-    setup_gemm<false>(PL, t, g, e);
+    setup_gemm<false, true>(PL, t, g, e);
     wg_wait(PL, w0, w1, t.fn);
     kslice_sum(PL, e, PL.B, o_proj ? PL.k_slices_o : PL.k_slices_d, PL.H / 16);
 }
@@ -279,6 +282,10 @@ __device__ __forceinline__ void setup_moe_gemm(const Params &P, const Task &t, c
 // one large kernel is short of registers, and code that cannot run still costs some: the dense instance alone
 // is 5 % faster than an instance that carries everything, the staged-only instance another 2 %.
 constexpr int KIND_GENERIC = 0, KIND_DENSE = 1, KIND_MOE = 2, KIND_DENSE_STAGED = 3, KIND_DENSE_STAGED_K = 4;
+// Added to a decoder kind: the instance also carries the end of the iteration (embedding look-up, vocabulary projection,
+// sampling).  A flag of the instance for the same reason as the kinds: on the 8B step the code costs 1.5 % where it never runs.
+constexpr int KIND_LM = 8;
+constexpr int kind_base(int kind) { return kind & 7; }
 template <bool SYNC_EVENTS, int KIND>
 __device__ __forceinline__ void run_task(const Params &P, const Params &PL, const Task &t, float *sm, WgState &st)
 {
@@ -286,7 +293,9 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
     TaskWaits tw{w0, w1, (int)t.fn, (t.flags & TF_WAIT0_PER_WAVE) != 0 && SYNC_EVENTS, w0};
     GemmTile g{};
     Epilogue e{};
-    constexpr bool MOE = KIND == KIND_MOE;
+    constexpr int BASE = kind_base(KIND);
+    constexpr bool LM = (KIND & KIND_LM) != 0;
+    constexpr bool MOE = BASE == KIND_MOE;
     if (MOE && (t.flags & TF_DYN_ROWTILE)) {      // GroupGEMM tile: its weights depend on the routing
         // The routing tables of a layer are complete once the layer's router event has fired.  A GroupGEMM-2 tile
         // of a workgroup that already ran a GroupGEMM-1 tile of the same layer therefore looks its row tile
@@ -301,28 +310,28 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
         setup_moe_gemm(P, t, rt, g, e);
         const int key = w0 < 0 ? -1 : w0 + ((t.c0 + 1) << 20);
         tw = routed ? TaskWaits{w0, w1, (int)t.fn, false, key} : TaskWaits{-1, -1, (int)t.fn, false, key};
-        gemm_tile_dispatch(P, PL, g, e, tw, sm, st, t.id);
+        gemm_tile_dispatch<LM>(P, PL, g, e, tw, sm, st, t.id);
         return;
     }
-    constexpr bool STAGED_ONLY = KIND == KIND_DENSE_STAGED || KIND == KIND_DENSE_STAGED_K;
-    constexpr bool STAGED_SLICES = KIND == KIND_DENSE_STAGED_K;
-    if (KIND != KIND_GENERIC && !STAGED_ONLY && (t.flags & TF_K_SLICE)) {
+    constexpr bool STAGED_ONLY = BASE == KIND_DENSE_STAGED || BASE == KIND_DENSE_STAGED_K;
+    constexpr bool STAGED_SLICES = BASE == KIND_DENSE_STAGED_K;
+    if (BASE != KIND_GENERIC && !STAGED_ONLY && (t.flags & TF_K_SLICE)) {
         st = k_slice_task(PL, t, tw, sm, st);
         return;
     }
-    if (KIND != KIND_GENERIC && setup_gemm<MOE>(P, t, g, e)) {
+    if (BASE != KIND_GENERIC && setup_gemm<MOE, LM>(P, t, g, e)) {
         if (STAGED_ONLY) {
             if (STAGED_SLICES && (t.flags & TF_K_SLICE)) {      // here a slice of K fits the staged path as well
                 slice_of_k(P, t, t.fn == FN_OPROJ ? P.k_slices_o : P.k_slices_d, g, e);
                 if (w0 >= 0) tw.op_key = w0 + ((t.c1 + 1) << 20);
             }
-            gemm_tiles_staged<10>(P, g, e, tw, sm, st, t.id);
+            gemm_tiles_staged<10, LM>(P, g, e, tw, sm, st, t.id);
         } else {
-            gemm_tile_dispatch(P, PL, g, e, tw, sm, st, t.id);
+            gemm_tile_dispatch<LM>(P, PL, g, e, tw, sm, st, t.id);
         }
         return;
     }
-    if (KIND == KIND_GENERIC) {
+    if (BASE == KIND_GENERIC) {
         wg_wait_cached(P, st, w0, w1, t.fn);
         if (t.fn == FN_ROWSUM_PARTIAL) rowsum_partial(P, t.c0, t.c1);
         else if (t.fn == FN_ROWSUM_FINAL) rowsum_final(P, t.c0);
@@ -331,9 +340,10 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
     }
     switch (t.fn) {
     case FN_LOAD_HIDDEN:
-        if (t.c0 < P.B) load_hidden(P, t.c0);
+        if (t.c0 < P.B) load_hidden<LM>(P, t.c0);
         break;
     case FN_SAMPLE:
+        if (!LM) break;
         wg_wait_cached(P, st, w0, w1, t.fn);
         if ((int)threadIdx.x < P.B) {
             const unsigned long long key = ld_u64(P.best + threadIdx.x);
@@ -555,7 +565,7 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
     if (blockIdx.x == 0 && threadIdx.x == 0) {            // reset the control words of the next launch
         for (int i = 0; i < 8; ++i) P.q_ctrl_next[i] = 0;
     }
-    if (KIND == KIND_GENERIC && P.dd_consumer_n > 0 && blockIdx.x == 0 && threadIdx.x == 0) {
+    if (kind_base(KIND) == KIND_GENERIC && P.dd_consumer_n > 0 && blockIdx.x == 0 && threadIdx.x == 0) {
         // tasks of the triggered grid beyond the last indptr range are never released: count them completed
         const int surplus = P.dd_consumer_n - gld_i32(reinterpret_cast<const int32_t *>(P.gbuf[4]) + P.dd_n_events);
         if (surplus > 0) __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 3), surplus, __ATOMIC_RELAXED, ETC_SCOPE);
@@ -591,9 +601,9 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
         // MoE with data-dependent events (Sec. 2.4): the router tiles trigger the GroupGEMM-1 tiles of an expert
         // themselves, when the expert's event fires, so those are not pushed when the router tiles are
         // dispatched, and a triggered tile has nothing left to wait for.
-        const bool dd_notify = KIND == KIND_GENERIC && (t.flags & TF_NOTIFY_INDIRECT);     // generic graphs (Sec. 2.4)
-        const bool dd_producer = (KIND == KIND_MOE && P.moe_dd && t.fn == FN_ROUTER) || dd_notify;
-        if (KIND == KIND_MOE && P.moe_dd && t.fn == FN_MOE_GATEUP) t.wait0 = -1;
+        const bool dd_notify = kind_base(KIND) == KIND_GENERIC && (t.flags & TF_NOTIFY_INDIRECT);     // generic graphs (Sec. 2.4)
+        const bool dd_producer = (kind_base(KIND) == KIND_MOE && P.moe_dd && t.fn == FN_ROUTER) || dd_notify;
+        if (kind_base(KIND) == KIND_MOE && P.moe_dd && t.fn == FN_MOE_GATEUP) t.wait0 = -1;
         if (sched_wave) {
             // This task is dispatched: the last producer of its event to get here pushes the consumers.
             int last = 0;
@@ -823,9 +833,10 @@ hipError_t max_resident_workgroups(int *per_cu)
 static int kind_of(const Params &P)
 {
     if (P.n_layers == 0) return KIND_GENERIC;
-    if (P.E > 0) return KIND_MOE;
-    if (!P.all_staged) return KIND_DENSE;
-    return (P.k_slices_o > 0 || P.k_slices_d > 0) ? KIND_DENSE_STAGED_K : KIND_DENSE_STAGED;
+    const int lm = P.vocab > 0 ? KIND_LM : 0;
+    if (P.E > 0) return KIND_MOE | lm;
+    if (!P.all_staged) return KIND_DENSE | lm;
+    return ((P.k_slices_o > 0 || P.k_slices_d > 0) ? KIND_DENSE_STAGED_K : KIND_DENSE_STAGED) | lm;
 }
 
 #define ETC_LAUNCH_KIND(KERNEL, GRID, ...)                                                                          \
@@ -834,7 +845,11 @@ static int kind_of(const Params &P)
     case KIND_DENSE: hipLaunchKernelGGL(KERNEL<KIND_DENSE>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break;     \
     case KIND_DENSE_STAGED: hipLaunchKernelGGL(KERNEL<KIND_DENSE_STAGED>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break; \
     case KIND_DENSE_STAGED_K: hipLaunchKernelGGL(KERNEL<KIND_DENSE_STAGED_K>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break; \
-    default: hipLaunchKernelGGL(KERNEL<KIND_MOE>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break;               \
+    case KIND_MOE: hipLaunchKernelGGL(KERNEL<KIND_MOE>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break;         \
+    case KIND_DENSE | KIND_LM: hipLaunchKernelGGL(KERNEL<KIND_DENSE | KIND_LM>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break; \
+    case KIND_DENSE_STAGED | KIND_LM: hipLaunchKernelGGL(KERNEL<KIND_DENSE_STAGED | KIND_LM>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break; \
+    case KIND_DENSE_STAGED_K | KIND_LM: hipLaunchKernelGGL(KERNEL<KIND_DENSE_STAGED_K | KIND_LM>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break; \
+    default: hipLaunchKernelGGL(KERNEL<KIND_MOE | KIND_LM>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break;     \
     }
 
 hipError_t launch_static(const Params &P, hipStream_t s)

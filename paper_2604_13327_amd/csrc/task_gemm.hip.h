@@ -57,6 +57,7 @@ struct Epilogue {
     float *ssq_out;           // RESID: this tile's partial sums of squares [kMaxBatch]
     int ld;                   // destination row stride
     int col0;                 // MoE: first destination row (permuted row of column 0)
+    ETC_AS_LDS unsigned long long *lds_best;   // LOGITS: the task's running maxima per column, in LDS (set by the projection path)
 };
 
 // What an epilogue thread needs from memory, fetched before the streaming loop so that the epilogue
@@ -68,6 +69,7 @@ struct EpiPre {
     int slot;         // QKV (k / v heads): KV slot of the appended row (page * page_size + position in the page)
 };
 __device__ __forceinline__ EpiPre epilogue_preload(const Params &P, const Epilogue &e, int col, int mp);
+template <bool LM>
 __device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &e, int col, int mp, float lo, float hi,
                                                const EpiPre &pre);
 
@@ -143,7 +145,7 @@ __device__ __forceinline__ void wg_wait_cached(const Params &P, WgState &st, int
 //     registers: refilled in front of them it needs other registers, and the copy back at the loop's end
 //     waits for every load of the revolution.
 // With both, every step waits for exactly the oldest of the PF loads (4.08 -> 3.94 ms per 8B step).
-template <int PRE>
+template <int PRE, bool LM>
 __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTile &g, const Epilogue &e, const TaskWaits &w,
                                                   float *sm, WgState &st, int task_id)
 {
@@ -387,6 +389,9 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
 
     // ---- one reduction (fixed wave order) and one epilogue for all tiles of the task -------------
     trace_mark(P, task_id, 3);
+    ETC_AS_LDS unsigned long long *lbest = reinterpret_cast<ETC_AS_LDS unsigned long long *>(rs + kRsFloats / 2);   // [16]
+    const bool to_best = LM && e.kind == EPI_LOGITS;
+    if (to_best && (int)threadIdx.x < g.n_cols) lbest[threadIdx.x] = 0ull;
     __syncthreads();
     for (int idx = threadIdx.x; idx < n_out; idx += kWgThreads) {
         const int ti = idx / per_tile, r = idx - ti * per_tile;
@@ -405,9 +410,15 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
         }
         Epilogue et = e;
         et.row0 = e.row0 + ti * g.tile_rows;
+        et.lds_best = lbest;
         if (e.ssq_out) et.ssq_out = e.ssq_out + (size_t)ti * kMaxBatch;
         if (!pre_ok) pre = epilogue_preload(P, et, col, mp);
-        apply_epilogue(P, et, col, mp, lo, hi, pre);
+        apply_epilogue<LM>(P, et, col, mp, lo, hi, pre);
+    }
+    if (to_best) {       // the task's maxima join the sequences' running maxima
+        __syncthreads();
+        if ((int)threadIdx.x < g.n_cols)
+            __hip_atomic_fetch_max(as_global(P.best + threadIdx.x), lbest[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -626,6 +637,9 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epi
 
     // ---- per tile: partials of the 8 wavefronts through LDS, fixed order, epilogue ----------------------
     trace_mark(P, task_id, 3);
+    ETC_AS_LDS unsigned long long *lbest = reinterpret_cast<ETC_AS_LDS unsigned long long *>(rs_part);   // [64]: the norm scratch is free by now
+    const bool to_best = e.kind == EPI_LOGITS;
+    if (to_best && (int)threadIdx.x < g.n_cols) lbest[threadIdx.x] = 0ull;      // ordered by the barrier behind the first tile's partials
 #pragma unroll
     for (int ti = 0; ti < T; ++ti) {
         if (ti < n_tiles) {
@@ -635,6 +649,7 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epi
             __syncthreads();
             Epilogue et = e;
             et.row0 = e.row0 + ti * g.tile_rows;
+            et.lds_best = lbest;
             if (e.ssq_out) et.ssq_out = e.ssq_out + (size_t)ti * kMaxBatch;
             for (int idx = threadIdx.x; idx < g.n_cols * 8; idx += kWgThreads) {
                 const int col = idx >> 3, mp = idx & 7;
@@ -651,11 +666,13 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epi
                     lo *= r;
                     hi *= r;
                 }
-                apply_epilogue(P, et, col, mp, lo, hi, epilogue_preload(P, et, col, mp));
+                apply_epilogue<true>(P, et, col, mp, lo, hi, epilogue_preload(P, et, col, mp));
             }
             __syncthreads();
         }
     }
+    if (to_best && (int)threadIdx.x < g.n_cols)       // behind the last tile's barrier
+        __hip_atomic_fetch_max(as_global(P.best + threadIdx.x), lbest[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // More row tiles than one pass over the operand takes: further passes (the events have been seen by then).
@@ -676,11 +693,12 @@ __device__ __noinline__ void gemm_tiles_chunked_passes(const Params &P, GemmTile
 
 // PL is the workgroup's LDS copy of the parameters: a kernel argument cannot be passed by address to
 // the out-of-line paths.
+template <bool LM>
 __device__ __forceinline__ void gemm_tile_dispatch(const Params &P, const Params &PL, const GemmTile &g, const Epilogue &e,
                                                    const TaskWaits &w, float *sm, WgState &st, int task_id)
 {
     if (staged_fits(g.n_tiles, g.n_cols, g.K)) {
-        gemm_tiles_staged<PF>(P, g, e, w, sm, st, task_id);
+        gemm_tiles_staged<PF, LM>(P, g, e, w, sm, st, task_id);
         return;
     }
     st.staged_key = -1;
@@ -724,7 +742,7 @@ __device__ __forceinline__ void kslice_sum(const Params &P, const Epilogue &e, i
             lo += a[sl];
             hi += b[sl];
         }
-        apply_epilogue(P, e, col, mp, lo, hi, pre);
+        apply_epilogue<false>(P, e, col, mp, lo, hi, pre);
     }
 }
 
@@ -784,6 +802,8 @@ __device__ __forceinline__ EpiPre epilogue_preload(const Params &P, const Epilog
     return pre;
 }
 
+// LM: the instance carries the vocabulary projection's epilogue.
+template <bool LM>
 __device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &e, int col, int mp, float lo, float hi,
                                                const EpiPre &pre)
 {
@@ -864,7 +884,8 @@ __device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &
         break;
     }
     case EPI_LOGITS: {
-        // fp32 logits of 16 vocabulary rows, and the tile's best (logit, id) into the sequence's running maximum.
+        if (!LM) break;
+        // fp32 logits of 16 vocabulary rows, and the tile's best (logit, id) towards the sequence's running maximum.
         // The key orders like the logit (sign-folded bits) and, among equal logits, like the complement of the id,
         // so that the maximum is the greedy token with ties to the lower id; max is exact and order-free, so the
         // result does not depend on which tile arrives first.
@@ -878,7 +899,9 @@ __device__ __forceinline__ void apply_epilogue(const Params &P, const Epilogue &
             const unsigned long long o = __shfl_xor(key, off, 64);
             key = o > key ? o : key;
         }
-        if (mp == 0) __hip_atomic_fetch_max(as_global(P.best + col), key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // first into the task's own maxima in LDS: one device-scope atomic per task and column reaches memory
+        // (thousands of them on one address are serialised there: 16 ns each, 130 us per 8B-vocabulary step)
+        if (mp == 0) __hip_atomic_fetch_max(e.lds_best + col, key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         break;
     }
     case EPI_MOE_ACT: {

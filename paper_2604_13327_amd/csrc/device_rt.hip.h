@@ -41,6 +41,43 @@ __device__ __forceinline__ void split_bf16(float v, uint16_t &hi, uint16_t &lo)
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 __device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
 
+// An argument of an out-of-line function arrives in vector registers, one copy per lane, even when every lane
+// holds the same value (task records, tile descriptors, event ids): the function then computes addresses and
+// branches per lane and runs out of vector registers.  This moves such a value back into scalar registers.
+template <class T>
+__device__ __forceinline__ T wave_uniform(const T &v)
+{
+    static_assert(sizeof(T) % 4 == 0, "whole 32-bit words");
+    struct Words { uint32_t w[sizeof(T) / 4]; };
+    Words a = __builtin_bit_cast(Words, v);
+#pragma unroll
+    for (unsigned i = 0; i < sizeof(T) / 4; ++i) a.w[i] = __builtin_amdgcn_readfirstlane(a.w[i]);
+    return __builtin_bit_cast(T, a);
+}
+
+// A plain-data struct to and from LDS, word by word (a struct in LDS is not assignable as a whole).
+template <class T>
+__device__ __forceinline__ void lds_put(T *dst, const T &v)
+{
+    static_assert(sizeof(T) % 4 == 0, "whole 32-bit words");
+    struct Words { uint32_t w[sizeof(T) / 4]; };
+    const Words a = __builtin_bit_cast(Words, v);
+    __attribute__((address_space(3))) uint32_t *d = (__attribute__((address_space(3))) uint32_t *)dst;
+#pragma unroll
+    for (unsigned i = 0; i < sizeof(T) / 4; ++i) d[i] = a.w[i];
+}
+template <class T>
+__device__ __forceinline__ T lds_get_uniform(const T *src)
+{
+    static_assert(sizeof(T) % 4 == 0, "whole 32-bit words");
+    struct Words { uint32_t w[sizeof(T) / 4]; };
+    Words a;
+    const __attribute__((address_space(3))) uint32_t *s = (const __attribute__((address_space(3))) uint32_t *)src;
+#pragma unroll
+    for (unsigned i = 0; i < sizeof(T) / 4; ++i) a.w[i] = __builtin_amdgcn_readfirstlane(s[i]);
+    return __builtin_bit_cast(T, a);
+}
+
 // ---- explicit address spaces ---------------------------------------------------------------------
 // Pointers that were themselves loaded from memory (weight tables, scratch pointers of an LDS copy of
 // the parameters) are generic to the compiler, which would then emit FLAT loads; those count against

@@ -219,22 +219,31 @@ __device__ __forceinline__ bool setup_gemm(const Params &P, const Task &t, GemmT
     }
 }
 
-// The two task kinds of a K-sliced projection (large-batch plans only) run out of line, so that they cost the
-// register allocation of the latency-critical small-batch path nothing.
+// The two task kinds of a K-sliced projection (large-batch plans only).  The instances that carry them are not the
+// latency-critical ones; the heavy paths behind them (chunked, staged) are out of line.
 // First stage: row tiles c0 .. c0+c2-1 against K slice c1.
-__device__ __noinline__ WgState k_slice_task(const Params &PL, Task t, TaskWaits tw, float *sm, WgState st)
+__device__ __forceinline__ WgState k_slice_task(const Params &PL, const Task &t, TaskWaits tw, float *sm, WgState st)
 {
     GemmTile g{};
     Epilogue e{};
     setup_gemm<false, true>(PL, t, g, e);
     slice_of_k(PL, t, t.fn == FN_OPROJ ? PL.k_slices_o : PL.k_slices_d, g, e);
     if (tw.ev0 >= 0) tw.op_key = tw.ev0 + ((t.c1 + 1) << 20);      // a staged copy holds one slice
-    gemm_tile_dispatch<false>(PL, PL, g, e, tw, sm, st, t.id);
+    gemm_tile_dispatch<false, true>(PL, PL, g, e, tw, sm, st, t.id);
     return st;
 }
-// Second stage: the slices' partial sums of row tile c0, then the projection's own epilogue.
-__device__ __noinline__ void k_slice_sum_task(const Params &PL, Task t, int w0, int w1)
+// The same out of line, for the MoE instance: its inlined GroupGEMM path is short of registers, and K-slice tasks
+// occur there only in the attention block of large batches.
+__device__ __noinline__ WgState k_slice_task_out_of_line(const Params &PL, Task t, TaskWaits tw, float *sm, WgState st)
 {
+    return k_slice_task(PL, wave_uniform(t), wave_uniform(tw), sm, wave_uniform(st));
+}
+// Second stage: the slices' partial sums of row tile c0, then the projection's own epilogue.
+__device__ __noinline__ void k_slice_sum_task(const Params &PL, Task t_in, int w0, int w1)
+{
+    Task t = wave_uniform(t_in);
+    w0 = __builtin_amdgcn_readfirstlane(w0);
+    w1 = __builtin_amdgcn_readfirstlane(w1);
     GemmTile g{};
     Epilogue e{};
     const bool o_proj = t.fn == FN_OPROJ_SUM;
@@ -310,13 +319,13 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
         setup_moe_gemm(P, t, rt, g, e);
         const int key = w0 < 0 ? -1 : w0 + ((t.c0 + 1) << 20);
         tw = routed ? TaskWaits{w0, w1, (int)t.fn, false, key} : TaskWaits{-1, -1, (int)t.fn, false, key};
-        gemm_tile_dispatch<LM>(P, PL, g, e, tw, sm, st, t.id);
+        gemm_tile_dispatch<LM, true, MOE>(P, PL, g, e, tw, sm, st, t.id);
         return;
     }
     constexpr bool STAGED_ONLY = BASE == KIND_DENSE_STAGED || BASE == KIND_DENSE_STAGED_K;
     constexpr bool STAGED_SLICES = BASE == KIND_DENSE_STAGED_K;
     if (BASE != KIND_GENERIC && !STAGED_ONLY && (t.flags & TF_K_SLICE)) {
-        st = k_slice_task(PL, t, tw, sm, st);
+        st = MOE ? k_slice_task_out_of_line(PL, t, tw, sm, st) : k_slice_task(PL, t, tw, sm, st);
         return;
     }
     if (BASE != KIND_GENERIC && setup_gemm<MOE, LM>(P, t, g, e)) {
@@ -327,7 +336,7 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
             }
             gemm_tiles_staged<10, LM>(P, g, e, tw, sm, st, t.id);
         } else {
-            gemm_tile_dispatch<LM>(P, PL, g, e, tw, sm, st, t.id);
+            gemm_tile_dispatch<LM, true, MOE>(P, PL, g, e, tw, sm, st, t.id);
         }
         return;
     }

@@ -20,6 +20,12 @@ namespace etc {
 template <int D, int GRP, bool PAGES_IN_LDS>
 __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int kvh, int ch, float *sm, int ev0, int ev1)
 {
+    layer = __builtin_amdgcn_readfirstlane(layer);      // uniform arguments back into scalar registers
+    b = __builtin_amdgcn_readfirstlane(b);
+    kvh = __builtin_amdgcn_readfirstlane(kvh);
+    ch = __builtin_amdgcn_readfirstlane(ch);
+    ev0 = __builtin_amdgcn_readfirstlane(ev0);
+    ev1 = __builtin_amdgcn_readfirstlane(ev1);
     constexpr int LPT = D / 8;        // lanes per key
     constexpr int TPW = 64 / LPT;     // keys per wavefront step
     const int wave = wave_id(), lane = lane_id();
@@ -242,6 +248,8 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
 template <int D, int GRP>
 __device__ __noinline__ void attn_merge(const Params &P, int b, int kvh)
 {
+    b = __builtin_amdgcn_readfirstlane(b);
+    kvh = __builtin_amdgcn_readfirstlane(kvh);
     const int n_keys = gld_i32(P.kv_len + b) + 1;
     const int nc = (n_keys + P.kv_chunk - 1) / P.kv_chunk;
     for (int idx = threadIdx.x; idx < GRP * D; idx += kWgThreads) {

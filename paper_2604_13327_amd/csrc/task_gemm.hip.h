@@ -440,9 +440,34 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
 // moves T tiles (slots beyond n_tiles stream the last live tile again and are never stored), columns beyond
 // n_cols read row 0, and only the last ring revolutions, whose look-ahead leaves K, run the conditional code.
 
-template <int NB, int T>
-__device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epilogue e, TaskWaits w, float *sm, int task_id)
+// Arguments of the out-of-line path travel through LDS: passed by value they fill the argument registers and
+// spill to the stack, i.e. every lane writes and reads its own copy of the same descriptors through scratch memory.
+struct ChunkedArgs {
+    GemmTile g;
+    Epilogue e;
+    TaskWaits w;
+    int task_id;
+};
+__device__ __forceinline__ ChunkedArgs *chunked_args_slot()
 {
+    __shared__ ChunkedArgs slot;
+    return &slot;
+}
+
+// `frame_anchor` points into the caller's stack frame and is there for the compiler alone.  A call that could be a
+// tail call makes the callee save and restore every callee-saved vector register it uses, through scratch memory,
+// on every call: 112 registers per lane here, at batch 64 twenty times the bytes the tasks produce.  A callee whose
+// call sites all hand it a piece of the caller's frame cannot be tail-called; the compiler then tells the callers
+// what the callee clobbers instead, and the callers (the task loop) have next to nothing live across the call.
+template <int NB, int T>
+__device__ __noinline__ void gemm_tiles_chunked(const Params &P, const ChunkedArgs *args, float *sm, int *frame_anchor)
+{
+    const ChunkedArgs a = lds_get_uniform(args);
+    if (a.task_id == -0x7FFFFFFF) *frame_anchor = 1;      // never true (task ids are >= -1)
+    const GemmTile &g = a.g;
+    const Epilogue &e = a.e;
+    const TaskWaits &w = a.w;
+    const int task_id = a.task_id;
     static_assert(T == 1 || T == 2 || T == 4 || T == 8, "row tiles per pass");
     constexpr int PFC = NB == 1 ? (T >= 4 ? PF : 8) : (NB == 2 ? 8 : 4);   // weight loads in flight per lane, as the registers allow
     constexpr int COLS = NB * 16;
@@ -675,49 +700,98 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, GemmTile g, Epi
         __hip_atomic_fetch_max(as_global(P.best + threadIdx.x), lbest[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// More row tiles than one pass over the operand takes: further passes (the events have been seen by then).
+// One call per pass over the operand: T row tiles each (the events have been seen after the first pass).
 template <int NB, int T>
-__device__ __noinline__ void gemm_tiles_chunked_passes(const Params &P, GemmTile g, Epilogue e, TaskWaits w, float *sm, int task_id)
+__device__ __forceinline__ void gemm_tiles_chunked_passes(const Params &PL, ChunkedArgs a, ChunkedArgs *slot, float *sm, int *frame_anchor)
 {
-    const int total = g.n_tiles;
+    const int total = a.g.n_tiles;
     for (int t0 = 0; t0 < total; t0 += T) {
-        g.n_tiles = total - t0 < T ? total - t0 : T;
-        gemm_tiles_chunked<NB, T>(P, g, e, w, sm, task_id);
-        g.rowsA += (size_t)T * g.tile_rows * g.ldw;
-        g.rowsB += (size_t)T * g.tile_rows * g.ldw;
-        e.row0 += T * g.tile_rows;
-        if (e.ssq_out) e.ssq_out += (size_t)T * kMaxBatch;
-        w = TaskWaits{-1, -1, w.fn, false, -1};
+        a.g.n_tiles = total - t0 < T ? total - t0 : T;
+        if (t0 > 0 || a.g.n_tiles != total) {      // the slot already holds the arguments of a single pass
+            if (threadIdx.x == 0) lds_put(slot, a);      // the callee's last barrier is behind its last read
+            __syncthreads();
+        }
+        gemm_tiles_chunked<NB, T>(PL, slot, sm, frame_anchor);
+        a.g.rowsA += (size_t)T * a.g.tile_rows * a.g.ldw;
+        a.g.rowsB += (size_t)T * a.g.tile_rows * a.g.ldw;
+        a.e.row0 += T * a.g.tile_rows;
+        if (a.e.ssq_out) a.e.ssq_out += (size_t)T * kMaxBatch;
+        a.w = TaskWaits{-1, -1, a.w.fn, false, -1};
     }
+}
+
+// Entry of the out-of-line path: one call site in the task loop.  The streaming loop always moves T row tiles, so T
+// follows the task: 1, 2, 4 or 8.  Up to 32 columns a pass takes up to 8 tiles; with 64 columns the accumulators of
+// 8 tiles no longer fit the register file next to the weight ring (spills inside the streaming loop queue behind the
+// weight loads), so a pass takes at most 4.
+__device__ __noinline__ void gemm_chunked_entry(const Params &PL, ChunkedArgs *slot, float *sm, int *frame_anchor)
+{
+    const ChunkedArgs a = lds_get_uniform(slot);
+    if (a.task_id == -0x7FFFFFFF) *frame_anchor = 1;      // never true; see gemm_tiles_chunked
+    int anchor = 0;
+#define ETC_CHUNKED(NB_)                                                                         \
+    {                                                                                            \
+        if (a.g.n_tiles == 1) gemm_tiles_chunked_passes<NB_, 1>(PL, a, slot, sm, &anchor);      \
+        else if (a.g.n_tiles == 2) gemm_tiles_chunked_passes<NB_, 2>(PL, a, slot, sm, &anchor); \
+        else if (a.g.n_tiles <= 4 || NB_ == 4) gemm_tiles_chunked_passes<NB_, 4>(PL, a, slot, sm, &anchor);  \
+        else gemm_tiles_chunked_passes<NB_, NB_ == 4 ? 4 : 8>(PL, a, slot, sm, &anchor);   /* several passes: crowded expert */ \
+    }
+    if (a.g.n_cols > 32) ETC_CHUNKED(4)
+    else if (a.g.n_cols > 16) ETC_CHUNKED(2)
+    else ETC_CHUNKED(1)
+#undef ETC_CHUNKED
 }
 
 // PL is the workgroup's LDS copy of the parameters: a kernel argument cannot be passed by address to
 // the out-of-line paths.
+// The staged path as a function of its own, for every instance but the staged-only ones (whose task loop is built
+// around it).  Inlined into a task loop that also carries the MoE or the large-batch task kinds, its streaming loop
+// was at the mercy of the register allocation of everything around it: builds differed by whether reloads of
+// spilled registers landed inside the loop (where each queues behind the whole weight ring), 15 % of a MoE step.
+// As a function it has the register file to itself.
 template <bool LM>
+__device__ __noinline__ WgState gemm_tiles_staged_out_of_line(const Params &PL, GemmTile g, Epilogue e, TaskWaits w, float *sm,
+                                                             WgState st, int task_id)
+{
+    st = wave_uniform(st);
+    gemm_tiles_staged<PF, LM>(PL, wave_uniform(g), wave_uniform(e), wave_uniform(w), sm, st, __builtin_amdgcn_readfirstlane(task_id));
+    return st;
+}
+
+// The same entry with its arguments by value (some travel over the stack, which also keeps the call from being a tail
+// call).  Which hand-over is cheaper is a property of the calling instance, measured: the dense large-batch steps are
+// 6-7 % faster with the LDS slot (less scratch traffic per task), the MoE steps 13-18 % faster with the by-value call
+// (8B batch 64: 14.4 against 15.4 ms; Qwen3 shape batch 1: 6.1 against 5.0 ms).
+__device__ __noinline__ void gemm_chunked_entry_by_value(const Params &PL, GemmTile g, Epilogue e, TaskWaits w, float *sm, int task_id)
+{
+    const ChunkedArgs a{wave_uniform(g), wave_uniform(e), wave_uniform(w), __builtin_amdgcn_readfirstlane(task_id)};
+    ChunkedArgs *slot = chunked_args_slot();
+    if (threadIdx.x == 0) lds_put(slot, a);
+    __syncthreads();
+    int frame_anchor = 0;
+    gemm_chunked_entry(PL, slot, sm, &frame_anchor);
+}
+
+// OOL_STAGED: the staged path is called, not inlined (see above).  ARGS_BY_VALUE: see gemm_chunked_entry_by_value.
+template <bool LM, bool OOL_STAGED = false, bool ARGS_BY_VALUE = false>
 __device__ __forceinline__ void gemm_tile_dispatch(const Params &P, const Params &PL, const GemmTile &g, const Epilogue &e,
                                                    const TaskWaits &w, float *sm, WgState &st, int task_id)
 {
     if (staged_fits(g.n_tiles, g.n_cols, g.K)) {
-        gemm_tiles_staged<PF, LM>(P, g, e, w, sm, st, task_id);
+        if (OOL_STAGED) st = gemm_tiles_staged_out_of_line<LM>(PL, g, e, w, sm, st, task_id);
+        else gemm_tiles_staged<PF, LM>(P, g, e, w, sm, st, task_id);
         return;
     }
     st.staged_key = -1;
-    // The streaming loop always moves T row tiles, so T follows the task: 1, 2, 4 or 8.  Up to 32 columns a pass
-    // takes up to 8 tiles; with 64 columns the accumulators of 8 tiles no longer fit the register file next to the
-    // weight ring (spills inside the streaming loop queue behind the weight loads), so a pass takes at most 4.
-#define ETC_CHUNKED(NB_)                                                                         \
-    {                                                                                            \
-        if (g.n_tiles == 1) gemm_tiles_chunked<NB_, 1>(PL, g, e, w, sm, task_id);                \
-        else if (g.n_tiles == 2) gemm_tiles_chunked<NB_, 2>(PL, g, e, w, sm, task_id);           \
-        else if (g.n_tiles <= 4) gemm_tiles_chunked<NB_, 4>(PL, g, e, w, sm, task_id);           \
-        else if (NB_ == 4) gemm_tiles_chunked_passes<NB_, 4>(PL, g, e, w, sm, task_id);          \
-        else if (g.n_tiles <= 8) gemm_tiles_chunked<NB_, NB_ == 4 ? 4 : 8>(PL, g, e, w, sm, task_id);        \
-        else gemm_tiles_chunked_passes<NB_, NB_ == 4 ? 4 : 8>(PL, g, e, w, sm, task_id);   /* crowded expert */ \
+    if (ARGS_BY_VALUE) {
+        gemm_chunked_entry_by_value(PL, g, e, w, sm, task_id);
+        return;
     }
-    if (g.n_cols > 32) ETC_CHUNKED(4)
-    else if (g.n_cols > 16) ETC_CHUNKED(2)
-    else ETC_CHUNKED(1)
-#undef ETC_CHUNKED
+    ChunkedArgs *slot = chunked_args_slot();
+    if (threadIdx.x == 0) lds_put(slot, ChunkedArgs{g, e, w, task_id});
+    __syncthreads();
+    int frame_anchor = 0;
+    gemm_chunked_entry(PL, slot, sm, &frame_anchor);
 }
 
 // Second stage of a K-sliced projection: adds the partial sums of the slices in slice order (fixed, so the

@@ -162,6 +162,9 @@ __device__ __forceinline__ void moe_update_and_trigger(const Params &P, int laye
 // tasks of the layer, row-tile slot major) is what the expert events trigger from.
 __device__ __noinline__ void moe_route_and_group(const Params &P, int layer, int t, int group_ev, float *sm)
 {
+    layer = __builtin_amdgcn_readfirstlane(layer);
+    t = __builtin_amdgcn_readfirstlane(t);
+    group_ev = __builtin_amdgcn_readfirstlane(group_ev);
     const int wave = wave_id(), lane = lane_id();
     const int E = P.E, K = P.topk, B = P.B, N = B * K, M = P.tile_m;
     ETC_AS_LDS int32_t *ids_s = reinterpret_cast<ETC_AS_LDS int32_t *>(as_lds(sm));   // [B*K] expert of every pair

@@ -25,3 +25,17 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+def pytest_runtest_logreport(report):
+    """One line per finished GPU test into gpurun_out/test_progress.log: a run whose stdout is captured or buffered
+    still shows that it is moving (the line is written when the test's call phase ends, never by a timer)."""
+    if report.when != "call" or "gpu" not in report.keywords:
+        return
+    try:
+        d = os.path.join(ROOT, "gpurun_out")
+        os.makedirs(d, exist_ok=True)
+        with open(os.path.join(d, "test_progress.log"), "a") as f:
+            f.write(f"{report.nodeid} {report.outcome} {report.duration:.1f}s\n")
+    except OSError:
+        pass

@@ -17,8 +17,12 @@ N_STEPS = 100
 MAX_LEN = 4096
 
 
-def test_llama8b_100_steps_of_changing_shape_without_recreate():
-    import torch
+N_SEGMENTS = 5       # the 100 steps run as five tests on the one context, so that none is silent for minutes
+
+
+@pytest.fixture(scope="module")
+def run100():
+    """The one context of the 100 steps, the model on both sides and the drawn steps."""
     import paper_2604_13327_amd as etc
     s = synth.LLAMA3_8B
     seed = 3030
@@ -27,12 +31,25 @@ def test_llama8b_100_steps_of_changing_shape_without_recreate():
     dec = etc.Decoder(s, kv_chunk_tokens=64, sampled_batches=[1, 4, 16, 64], max_kv_len=MAX_LEN + 1,
                       debug_flags=etc.DEBUG_EXEC_COUNT | etc.DEBUG_LAYER_HIDDEN, spin_budget=2000000)
     model.bind(dec)
-    weights = [synth.layer_weights_f32(s, seed, l) for l in range(s.n_layers)]     # ~28 GB of host memory
-    pools = SparsePools(s, seed, n_pool)
     rng = np.random.default_rng(seed)
-    seen, worst, bytes_moved = {}, 0.0, []
-    for i in range(N_STEPS):
-        step = synth.draw_step(rng, s, [1, 4, 16, 64], 128, MAX_LEN, n_pool)
+    state = {"s": s, "seed": seed, "n_pool": n_pool, "model": model, "dec": dec,
+             "weights": [synth.layer_weights_f32(s, seed, l) for l in range(s.n_layers)],     # ~28 GB of host memory
+             "pools": SparsePools(s, seed, n_pool),
+             "steps": [synth.draw_step(rng, s, [1, 4, 16, 64], 128, MAX_LEN, n_pool) for _ in range(N_STEPS)],
+             "seen": {}, "worst": 0.0, "bytes": [], "done": 0}
+    yield state
+    dec.close()
+
+
+@pytest.mark.parametrize("segment", range(N_SEGMENTS))
+def test_llama8b_100_steps_of_changing_shape_without_recreate(run100, segment):
+    import torch
+    st = run100
+    s, seed, model, dec, seen = st["s"], st["seed"], st["model"], st["dec"], st["seen"]
+    per = N_STEPS // N_SEGMENTS
+    assert st["done"] == segment * per, "the segments are consecutive steps of one context"
+    for i in range(segment * per, (segment + 1) * per):
+        step = st["steps"][i]
         B = step.batch
         # the step appends one row per sequence and layer; put the seeded rows back afterwards so that the
         # steps stay independent draws (a later step may own the same physical page)
@@ -54,25 +71,23 @@ def test_llama8b_100_steps_of_changing_shape_without_recreate():
             sel = list(range(B))
         else:                                 # one column of every 16-column block of the tiles, and the last column
             sel = sorted({min(B - 1, 3 + 16 * k) for k in range((B + 15) // 16)} | {B - 1})
-        ref = oracle_on_sequences(s, seed, step, sel, i, lambda l: weights[l], pools)
+        ref = oracle_on_sequences(s, seed, step, sel, i, lambda l: st["weights"][l], st["pools"])
         for l in range(s.n_layers):
             e = rel_err(dec.layer_hidden(l)[sel], ref["layers"][l])
-            worst = max(worst, e)
+            st["worst"] = max(st["worst"], e)
             assert e <= TOL, f"step {i} (batch {B}) layer {l}: {e}"
         assert rel_err(got[sel], ref["final"]) <= TOL, f"step {i} (batch {B}) final"
         model.kpool[:, pg, sl] = keep_k
         model.vpool[:, pg, sl] = keep_v
         seen[B] = seen.get(B, 0) + 1
-        bytes_moved.append(int(info.algorithmic_bytes))
-        if len(sel) == B and B > 1:
-            print(f"step {i}: all {B} sequences compared, worst so far {worst:.3e}", flush=True)
-        if i % 10 == 9:
-            print(f"step {i + 1}/{N_STEPS}: batches so far {dict(sorted(seen.items()))}, worst per-layer "
-                  f"max|err|/rms {worst:.3e}", flush=True)
-    assert set(seen) == {1, 4, 16, 64}
-    print(f"llama8b dynamic shapes: {N_STEPS} steps, worst per-layer max|err|/rms = {worst:.3e}, "
-          f"algorithmic bytes per step {min(bytes_moved) / 1e9:.1f}..{max(bytes_moved) / 1e9:.1f} GB")
-    dec.close()
+        st["bytes"].append(int(info.algorithmic_bytes))
+        st["done"] = i + 1
+    print(f"steps {segment * per}..{(segment + 1) * per - 1}: batches so far {dict(sorted(seen.items()))}, worst per-layer "
+          f"max|err|/rms {st['worst']:.3e}", flush=True)
+    if segment == N_SEGMENTS - 1:
+        assert set(seen) == {1, 4, 16, 64}
+        print(f"llama8b dynamic shapes: {N_STEPS} steps, worst per-layer max|err|/rms = {st['worst']:.3e}, "
+              f"algorithmic bytes per step {min(st['bytes']) / 1e9:.1f}..{max(st['bytes']) / 1e9:.1f} GB")
 
 
 def test_llama8b_changing_shapes_under_the_dynamic_scheduler():

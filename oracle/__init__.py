@@ -48,7 +48,7 @@ def lib():
     L.orc_silu.restype = ctypes.c_double
     L.orc_silu.argtypes = [ctypes.c_double]
     for name in ("orc_rmsnorm", "orc_linear", "orc_rope", "orc_attention", "orc_topk",
-                 "orc_route_weights", "orc_group", "orc_layer", "orc_lm_head"):
+                 "orc_route_weights", "orc_group", "orc_layer", "orc_lm_head", "orc_moe_layer"):
         getattr(L, name).restype = None
     return L
 
@@ -179,6 +179,26 @@ def layer(shape: OrcShape, x, w: dict, kpool, vpool, kv_len, page_indptr, page_i
                     g("gq"), g("gk"), _p(kpool), _p(vpool), _p(kv_len), _p(page_indptr), _p(page_ids), ctypes.c_int(force),
                     _p(ids), ctypes.byref(dbg_struct) if debug else None)
     return ids, dbg_arrays
+
+
+def moe_layer(shape: OrcShape, x, w: dict, forced_topk=None):
+    """The MoE layer on its own: x <- x + MoE(rmsnorm(x, g2)) for T tokens (paper Sec. 2.4; measured over 1 .. 4096
+    tokens in Sec. 4.2 / 4.5).  x [T, H]; w holds g2, wr, eg, eu, ed.  Returns (y [T, H] fp32, top-k ids [T, K] int32,
+    router logits [T, E] fp32, routing weights [T, K] fp32)."""
+    y = np.array(x, dtype=np.float32, copy=True, order="C")
+    T = y.shape[0]
+    ww = {k: _f(v) for k, v in w.items()}
+    force = 0
+    if forced_topk is not None:
+        ids = np.ascontiguousarray(forced_topk, dtype=np.int32).copy()
+        force = 1
+    else:
+        ids = np.empty((T, shape.top_k), dtype=np.int32)
+    logits = np.empty((T, shape.n_experts), dtype=np.float32)
+    tw = np.empty((T, shape.top_k), dtype=np.float32)
+    lib().orc_moe_layer(ctypes.byref(shape), ctypes.c_int(T), _p(y), _p(ww["g2"]), _p(ww["wr"]), _p(ww["eg"]), _p(ww["eu"]),
+                        _p(ww["ed"]), ctypes.c_int(force), _p(ids), _p(logits), _p(tw))
+    return y, ids, logits, tw
 
 
 def embed(table, tokens):

@@ -193,6 +193,58 @@ void orc_group(const int32_t *topk_ids, int B, int K, int E, int tile_m, int32_t
 }
 
 /*
+ * MoE block of a layer (paper Sec. 2.4: TopK routing -> GroupGEMM-1 -> activation -> GroupGEMM-2 -> weighted combine),
+ * token by token, slots in ascending order: x[b] += sum_k w[b,k] * Wd_e (silu(Wg_e xn[b]) * (Wu_e xn[b])), e = topk[b,k].
+ * x [B, H] residual stream, updated in place; xn [B, H] its normalised copy.  force_routing != 0: topk_ids is an input.
+ * logits_out [B, E] and topk_w_out [B, K] are optional outputs.
+ */
+void orc_moe_block(const orc_shape *s, int B, float *x, const float *xn, const float *wr, const float *eg, const float *eu,
+                   const float *ed, int force_routing, int32_t *topk_ids, float *logits_out, float *topk_w_out)
+{
+    int H = s->H;
+    float *y = (float *)malloc(sizeof(float) * (size_t)H);
+    int E = s->n_experts, K = s->top_k, F = s->moe_F;
+    float *logits = (float *)malloc(sizeof(float) * (size_t)B * E);
+    float *w = (float *)malloc(sizeof(float) * (size_t)K);
+    float *gt = (float *)malloc(sizeof(float) * (size_t)F);
+    float *up = (float *)malloc(sizeof(float) * (size_t)F);
+    double *acc = (double *)malloc(sizeof(double) * (size_t)H);
+    orc_linear(wr, xn, B, E, H, logits);
+    if (logits_out) memcpy(logits_out, logits, sizeof(float) * (size_t)B * E);
+    for (int b = 0; b < B; ++b) {
+        int32_t *ids = topk_ids + (size_t)b * K;
+        const float *xb = xn + (size_t)b * H;
+        if (!force_routing) orc_topk(logits + (size_t)b * E, E, K, ids);
+        orc_route_weights(logits + (size_t)b * E, ids, K, w);
+        if (topk_w_out) memcpy(topk_w_out + (size_t)b * K, w, sizeof(float) * (size_t)K);
+        for (int i = 0; i < H; ++i) acc[i] = 0.0;
+        for (int slot = 0; slot < K; ++slot) { /* ascending slot order */
+            size_t e = (size_t)ids[slot];
+            orc_linear(eg + e * F * H, xb, 1, F, H, gt);
+            orc_linear(eu + e * F * H, xb, 1, F, H, up);
+            for (int i = 0; i < F; ++i) gt[i] = (float)(orc_silu((double)gt[i]) * (double)up[i]);
+            orc_linear(ed + e * H * F, gt, 1, H, F, y);
+            for (int i = 0; i < H; ++i) acc[i] += (double)w[slot] * (double)y[i];
+        }
+        for (int i = 0; i < H; ++i) x[(size_t)b * H + i] = (float)((double)x[(size_t)b * H + i] + acc[i]);
+    }
+    free(logits); free(w); free(gt); free(up); free(acc); free(y);
+}
+
+/*
+ * The MoE layer on its own, as the paper measures it over 1 .. 4096 tokens (Sec. 4.2, Sec. 4.5): pre-norm residual
+ * block x <- x + MoE(rmsnorm(x, g)).  x [T, H] in place; the other arguments as in orc_moe_block.
+ */
+void orc_moe_layer(const orc_shape *s, int T, float *x, const float *g, const float *wr, const float *eg, const float *eu,
+                   const float *ed, int force_routing, int32_t *topk_ids, float *logits_out, float *topk_w_out)
+{
+    float *xn = (float *)malloc(sizeof(float) * (size_t)T * s->H);
+    for (int b = 0; b < T; ++b) orc_rmsnorm(x + (size_t)b * s->H, g, s->H, s->eps, xn + (size_t)b * s->H);
+    orc_moe_block(s, T, x, xn, wr, eg, eu, ed, force_routing, topk_ids, logits_out, topk_w_out);
+    free(xn);
+}
+
+/*
  * One decoder layer for a batch of B single-token sequences; x [B, H] is updated
  * in place; the K/V pools receive the appended rows (fp32) in place.
  * force_routing != 0: topk_ids is an input (weights still come from this
@@ -265,32 +317,8 @@ void orc_layer(const orc_shape *s, int B, float *x, const float *g1, const float
         free(gt);
         free(up);
     } else {
-        int E = s->n_experts, K = s->top_k, F = s->moe_F;
-        float *logits = (float *)malloc(sizeof(float) * (size_t)B * E);
-        float *w = (float *)malloc(sizeof(float) * (size_t)K);
-        float *gt = (float *)malloc(sizeof(float) * (size_t)F);
-        float *up = (float *)malloc(sizeof(float) * (size_t)F);
-        double *acc = (double *)malloc(sizeof(double) * (size_t)H);
-        orc_linear(wr, xn, B, E, H, logits);
-        if (dbg && dbg->router_logits) memcpy(dbg->router_logits, logits, sizeof(float) * (size_t)B * E);
-        for (int b = 0; b < B; ++b) {
-            int32_t *ids = topk_ids + (size_t)b * K;
-            const float *xb = xn + (size_t)b * H;
-            if (!force_routing) orc_topk(logits + (size_t)b * E, E, K, ids);
-            orc_route_weights(logits + (size_t)b * E, ids, K, w);
-            if (dbg && dbg->topk_w) memcpy(dbg->topk_w + (size_t)b * K, w, sizeof(float) * (size_t)K);
-            for (int i = 0; i < H; ++i) acc[i] = 0.0;
-            for (int slot = 0; slot < K; ++slot) { /* ascending slot order */
-                size_t e = (size_t)ids[slot];
-                orc_linear(eg + e * F * H, xb, 1, F, H, gt);
-                orc_linear(eu + e * F * H, xb, 1, F, H, up);
-                for (int i = 0; i < F; ++i) gt[i] = (float)(orc_silu((double)gt[i]) * (double)up[i]);
-                orc_linear(ed + e * H * F, gt, 1, H, F, y);
-                for (int i = 0; i < H; ++i) acc[i] += (double)w[slot] * (double)y[i];
-            }
-            for (int i = 0; i < H; ++i) x[(size_t)b * H + i] = (float)((double)x[(size_t)b * H + i] + acc[i]);
-        }
-        free(logits); free(w); free(gt); free(up); free(acc);
+        orc_moe_block(s, B, x, xn, wr, eg, eu, ed, force_routing, topk_ids, dbg ? dbg->router_logits : NULL,
+                      dbg ? dbg->topk_w : NULL);
     }
     free(xn); free(q); free(k); free(v); free(o); free(y);
 }

@@ -486,3 +486,43 @@ def test_lm_head_matches_float64_and_breaks_ties_to_the_lower_id():
     lg, tk = oracle.lm_head(oracle.shape_of(s), xo, np.ones(s.H, np.float32), eye)
     assert lg[0, 5] == lg[0, 7] == lg[0, 20] and tk[0] == 5
     np.testing.assert_allclose(lg[0, 5], 4.0 / np.sqrt(32.0 / s.H + s.eps), rtol=1e-6)
+
+
+# ---------------------------------------------------------------- the MoE layer on its own
+def test_moe_layer_matches_float64_library_derivation_and_the_layer_it_was_cut_from():
+    """x + MoE(rmsnorm(x)) for a block of tokens, written a second way with float64 library calls (lexsort top-k,
+    softmax over the selected logits, per-token expert MLPs); and the second half of the full layer, from which the
+    function was extracted, gives the same bits when fed the same mid-layer residual."""
+    s = _tiny(moe=True, n_experts=8, top_k=3)
+    w = _weights(s)
+    T_ = lambda a: torch.from_numpy(np.asarray(a)).double()  # noqa: E731
+    x = r32(11, s.H)
+    y, ids, logits, tw = oracle.moe_layer(oracle.shape_of(s), x, w)
+    for b in range(11):
+        xn = Fn.rms_norm(T_(x[b]), (s.H,), T_(w["g2"]), eps=s.eps)
+        lg = T_(w["wr"]) @ xn
+        np.testing.assert_allclose(logits[b], lg.numpy(), rtol=1e-5, atol=1e-6)
+        order = np.lexsort((np.arange(s.n_experts), -logits[b].astype(np.float64)))[: s.top_k]
+        np.testing.assert_array_equal(ids[b], order)
+        ww = torch.softmax(lg[torch.from_numpy(order).long()], 0)
+        np.testing.assert_allclose(tw[b], ww.numpy(), rtol=1e-5)
+        ref = T_(x[b]) + sum(ww[i] * (T_(w["ed"][e]) @ (Fn.silu(T_(w["eg"][e]) @ xn) * (T_(w["eu"][e]) @ xn)))
+                             for i, e in enumerate(order.tolist()))
+        np.testing.assert_allclose(y[b], ref.numpy(), rtol=2e-5, atol=2e-6)
+    # the same function inside the whole layer: zero attention output projection makes x_mid = x
+    w0 = dict(w, wo=np.zeros_like(w["wo"]))
+    n_pool = 6
+    kp, vp = r32(n_pool, s.page, s.nkv, s.d), r32(n_pool, s.page, s.nkv, s.d)
+    step = _step(s, [3] * 11, 11 * 2)
+    kp, vp = r32(22, s.page, s.nkv, s.d), r32(22, s.page, s.nkv, s.d)
+    xl = x.copy()
+    oracle.layer(oracle.shape_of(s), xl, w0, kp, vp, step.kv_len, step.page_indptr, step.page_ids)
+    np.testing.assert_array_equal(xl, y)
+    # forced routing is followed, and the weights come from the logits at the forced ids
+    forced = np.stack([rng.permutation(s.n_experts)[: s.top_k] for _ in range(11)]).astype(np.int32)
+    yf, idf, _, twf = oracle.moe_layer(oracle.shape_of(s), x, w, forced_topk=forced)
+    np.testing.assert_array_equal(idf, forced)
+    for b in range(11):
+        ww = torch.softmax(T_(logits[b])[torch.from_numpy(forced[b]).long()], 0)
+        np.testing.assert_allclose(twf[b], ww.numpy(), rtol=1e-5)
+    assert not np.array_equal(yf, y)

@@ -106,7 +106,7 @@ typedef struct {
     int32_t kind;             /* etc_sched_kind */
     int32_t n_sampled;        /* static: number of sampled batch sizes (Sec. 3.1), 1..8 */
     int32_t sampled_batch[8]; /* ascending; a bound batch uses the next larger sampled queue */
-    int32_t max_batch;        /* <= 64 */
+    int32_t max_batch;        /* <= 64 (stand-alone MoE layer: tokens, <= 4096) */
     int32_t max_kv_len;       /* largest kv_len + 1 any step will bind */
     int64_t spin_budget;      /* polls before a wait gives up (0 = default) */
     uint32_t debug_flags;
@@ -175,6 +175,25 @@ etc_status etc_bind_step(etc_ctx *ctx, int32_t batch, const int32_t *kv_len, con
  * [batch, top_k] (host) instead of the softmax over the selected logits.  ids == NULL removes the
  * override (w is then ignored).  Synchronises; takes effect at the next launch. */
 etc_status etc_force_routing(etc_ctx *ctx, int32_t layer, const int32_t *ids, const float *w);
+
+/* ---- the MoE layer on its own (Sec. 2.4; measured over 1 .. 4096 tokens in Sec. 4.2 and Sec. 4.5) ------------
+ * y = x + MoE(rmsnorm(x, g2)) for a block of tokens: router -> top-k -> token grouping -> GroupGEMM-1 -> SiLU-mul ->
+ * GroupGEMM-2 -> weighted combine, the same event-gated tasks as the MoE block of a decoder layer, with the
+ * data-dependent events of Sec. 2.4 under the dynamic scheduler; routing and grouping run as counting passes over
+ * blocks of 64 tokens, so the work stays linear in the tokens.
+ * Of `model` only hidden, n_experts, top_k, moe_ffn and rms_eps are read; tiles->moe_tile_m (1..64) is the row tile of
+ * the GroupGEMMs; sched->max_batch is the largest token count (<= 4096), sched->sampled_batch the sampled token
+ * counts (Sec. 3.1; a bound count runs the next larger one), max_kv_len is ignored.  The context takes
+ * etc_bind_layer_weights(ctx, 0, w) with g2, wr, eg, eu, ed (the other pointers are ignored),
+ * etc_moe_layer_bind_tokens, etc_force_routing (layer 0), etc_launch / etc_launch_kernel_by_kernel (hidden_in = x,
+ * hidden_out = y, device, bf16 [n_tokens, hidden]), etc_read_debug (routing kinds, layer 0) and etc_get_step_info;
+ * etc_bind_kv_pool and etc_bind_step are refused. */
+etc_status etc_moe_layer_create(const etc_model_desc *model, const etc_tile_desc *tiles, const etc_sched_desc *sched,
+                                etc_ctx **out);
+
+/* Number of tokens of the next launches (a dynamic shape in the sense of Sec. 2.3: no re-create up to max_batch).
+ * Host-only; after a move to another sampled token count the next launch is preceded by the arming kernel. */
+etc_status etc_moe_layer_bind_tokens(etc_ctx *ctx, int32_t n_tokens);
 
 /* ---- launch --------------------------------------------------------------------------- */
 
@@ -350,6 +369,9 @@ typedef struct {
 
 etc_status etc_plan_build(const etc_model_desc *model, const etc_tile_desc *tiles, const etc_sched_desc *sched,
                           int32_t sampled_batch, int32_t n_queues, etc_plan_view *out);
+/* The same for the stand-alone MoE layer graph of `sampled_tokens` tokens (etc_moe_layer_create). */
+etc_status etc_moe_layer_plan_build(const etc_model_desc *model, const etc_tile_desc *tiles, const etc_sched_desc *sched,
+                                    int32_t sampled_tokens, int32_t n_queues, etc_plan_view *out);
 void etc_plan_free(etc_plan_view *view);
 
 #ifdef __cplusplus

@@ -5,5 +5,6 @@ Argument marshalling only.  Every step of the decode path runs in the HIP librar
 """
 from .binding import (  # noqa: F401
     DEBUG_EXEC_COUNT, DEBUG_LAYER_HIDDEN, DEBUG_ROUTING, DEBUG_TRACE, SCHED_DYNAMIC, SCHED_STATIC, SCHED_UNFUSED,
-    Decoder, EtcError, EventGraph, ROWSUM_NOALLOC_MAX_N, lib, lib_path, plan_build, rowsum_launch_noalloc,
+    Decoder, EtcError, EventGraph, MoeLayer, ROWSUM_NOALLOC_MAX_N, lib, lib_path, moe_layer_plan_build, plan_build,
+    rowsum_launch_noalloc,
 )

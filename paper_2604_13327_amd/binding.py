@@ -23,6 +23,7 @@ MAP_DIM, MAP_CONST, MAP_INDIRECT, MAP_INDPTR = 0, 1, 2, 3
 EXPORTS = ["etc_create", "etc_destroy", "etc_last_error", "etc_bind_layer_weights", "etc_bind_kv_pool",
            "etc_bind_step", "etc_force_routing", "etc_launch", "etc_launch_kernel_by_kernel", "etc_read_debug",
            "etc_bind_lm_head", "etc_launch_tokens", "etc_launch_tokens_kernel_by_kernel",
+           "etc_moe_layer_create", "etc_moe_layer_bind_tokens", "etc_moe_layer_plan_build",
            "etc_get_step_info", "etc_graph_create", "etc_graph_add_event", "etc_graph_add_call",
            "etc_graph_bind_buffer", "etc_graph_bind_shape", "etc_graph_launch", "etc_plan_build", "etc_plan_free",
            "etc_rowsum_launch_noalloc"]
@@ -120,6 +121,10 @@ def lib():
     L.etc_bind_lm_head.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     L.etc_launch_tokens.argtypes = [C.c_void_p] * 7
     L.etc_launch_tokens_kernel_by_kernel.argtypes = [C.c_void_p] * 7
+    L.etc_moe_layer_create.argtypes = [C.POINTER(ModelDesc), C.POINTER(TileDesc), C.POINTER(SchedDesc), C.POINTER(C.c_void_p)]
+    L.etc_moe_layer_bind_tokens.argtypes = [C.c_void_p, C.c_int32]
+    L.etc_moe_layer_plan_build.argtypes = [C.POINTER(ModelDesc), C.POINTER(TileDesc), C.POINTER(SchedDesc), C.c_int32, C.c_int32,
+                                           C.POINTER(PlanView)]
     L.etc_read_debug.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t]
     L.etc_get_step_info.argtypes = [C.c_void_p, C.POINTER(StepInfo)]
     L.etc_graph_create.argtypes = [C.POINTER(SchedDesc), C.POINTER(C.c_void_p)]
@@ -156,15 +161,7 @@ def _i32(a):
     return np.ascontiguousarray(a, dtype=np.int32)
 
 
-def plan_build(shape, kv_chunk_tokens, sampled_batch, n_queues, max_kv_len, kind=SCHED_STATIC, moe_tile_m=16):
-    """Host-only: the materialised plan of one sampled batch size as numpy arrays (copies)."""
-    L = lib()
-    view = PlanView()
-    md, td = _model_desc(shape), TileDesc(kv_chunk_tokens, moe_tile_m)
-    sd = _sched_desc(kind, [sampled_batch], max_kv_len)
-    st = L.etc_plan_build(C.byref(md), C.byref(td), C.byref(sd), sampled_batch, n_queues, C.byref(view))
-    if st != 0:
-        raise EtcError(st, L.etc_last_error(None).decode())
+def _plan_arrays(L, view):
     try:
         def arr(ptr, n, dtype):
             if n == 0:
@@ -179,6 +176,30 @@ def plan_build(shape, kv_chunk_tokens, sampled_batch, n_queues, max_kv_len, kind
                 "seed_tasks": arr(view.seed_tasks, view.n_seed, np.int32)}
     finally:
         L.etc_plan_free(C.byref(view))
+
+
+def plan_build(shape, kv_chunk_tokens, sampled_batch, n_queues, max_kv_len, kind=SCHED_STATIC, moe_tile_m=16):
+    """Host-only: the materialised plan of one sampled batch size as numpy arrays (copies)."""
+    L = lib()
+    view = PlanView()
+    md, td = _model_desc(shape), TileDesc(kv_chunk_tokens, moe_tile_m)
+    sd = _sched_desc(kind, [sampled_batch], max_kv_len)
+    st = L.etc_plan_build(C.byref(md), C.byref(td), C.byref(sd), sampled_batch, n_queues, C.byref(view))
+    if st != 0:
+        raise EtcError(st, L.etc_last_error(None).decode())
+    return _plan_arrays(L, view)
+
+
+def moe_layer_plan_build(shape, sampled_tokens, n_queues, kind=SCHED_STATIC, moe_tile_m=16):
+    """Host-only: the plan of the stand-alone MoE layer for one sampled token count."""
+    L = lib()
+    view = PlanView()
+    md, td = _model_desc(shape), TileDesc(16, moe_tile_m)
+    sd = _sched_desc(kind, [sampled_tokens], 1)
+    st = L.etc_moe_layer_plan_build(C.byref(md), C.byref(td), C.byref(sd), sampled_tokens, n_queues, C.byref(view))
+    if st != 0:
+        raise EtcError(st, L.etc_last_error(None).decode())
+    return _plan_arrays(L, view)
 
 
 class _Ctx:
@@ -316,6 +337,32 @@ def _stream_ptr(stream):
         import torch
         stream = torch.cuda.current_stream()
     return C.c_void_p(stream.cuda_stream)
+
+
+class MoeLayer(Decoder):
+    """The MoE layer on its own over a block of tokens: describe -> bind -> launch (include/etc.h).  Launches, forced
+    routing and the routing dumps are the decoder's calls on layer 0."""
+
+    def __init__(self, shape, sampled_tokens, kind: int = SCHED_STATIC, debug_flags: int = 0, spin_budget: int = 0,
+                 n_queues: int = 0, moe_tile_m: int = 16):
+        _Ctx.__init__(self)
+        self.shape = shape
+        self.kind = kind
+        md, td = _model_desc(shape), TileDesc(16, moe_tile_m)
+        sd = _sched_desc(kind, sampled_tokens, 1, debug_flags, spin_budget, n_queues)
+        st = self._L.etc_moe_layer_create(C.byref(md), C.byref(td), C.byref(sd), C.byref(self._h))
+        if st != 0:
+            raise EtcError(st, self._L.etc_last_error(None).decode())
+        self._keep = []
+        self.batch = 0
+
+    def bind_weights(self, tensors: dict):
+        """tensors: g2, wr, eg, eu, ed as torch bf16 CUDA tensors."""
+        self.bind_layer_weights(0, {k: tensors[k] for k in ("g2", "wr", "eg", "eu", "ed")})
+
+    def bind_tokens(self, n_tokens: int):
+        self._check(self._L.etc_moe_layer_bind_tokens(self._h, n_tokens))
+        self.batch = n_tokens
 
 
 class EventGraph(_Ctx):

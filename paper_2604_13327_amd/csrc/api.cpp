@@ -74,6 +74,7 @@ hipError_t dev_upload(T **p, const std::vector<T> &v, std::vector<void *> &owned
 
 struct etc_ctx {
     bool is_graph = false;
+    bool is_moe_layer = false;              // the MoE layer on its own over a block of tokens (etc_moe_layer_create)
     etc_model_desc model{};
     etc_tile_desc tiles{};
     etc_sched_desc sched{};
@@ -375,8 +376,8 @@ etc_status pre_launch(etc_ctx *c, const void *hidden_in, void *hidden_out, Param
         if (tok->token_in && !c->base.embed) return fail(c, ETC_ESTATE, "token_in needs the embedding table");
         if (!tok->token_out) return fail(c, ETC_EINVAL, "token_out is NULL");
     }
-    if (!c->kv_bound) return fail(c, ETC_ESTATE, "no KV pool bound");
-    if (!c->step_bound) return fail(c, ETC_ESTATE, "no step bound");
+    if (!c->kv_bound && !c->is_moe_layer) return fail(c, ETC_ESTATE, "no KV pool bound");
+    if (!c->step_bound) return fail(c, ETC_ESTATE, c->is_moe_layer ? "no token count bound" : "no step bound");
     etc_status st = refuse_if_dead(c);
     if (st != ETC_OK) return st;
     st = sync_weights(c);
@@ -509,6 +510,7 @@ etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc
     P.eps = m->rms_eps; P.theta = m->rope_theta; P.kv_chunk = t->kv_chunk_tokens; P.tile_m = d.tile_m;
     P.qk_norm = m->qk_norm ? 1 : 0;
     P.vocab = d.vocab;
+    P.col_stride = kMaxBatch;
     auto A = [&](auto **p, size_t n) -> bool {
         hipError_t e = dev_alloc(p, n, c->owned);
         if (e != hipSuccess) { c->err = std::string("device allocation failed: ") + hipGetErrorString(e); return false; }
@@ -577,7 +579,9 @@ etc_status etc_bind_layer_weights(etc_ctx *c, int32_t layer, const etc_layer_wei
     if (!c || c->is_graph || !w) return fail(c, ETC_EINVAL, "bad argument");
     if (layer < 0 || layer >= c->model.n_layers) return fail(c, ETC_EINVAL, "layer out of range");
     const bool moe = c->model.n_experts > 0;
-    if (!w->g1 || !w->wq || !w->wk || !w->wv || !w->wo || !w->g2) return fail(c, ETC_EINVAL, "attention weights missing");
+    if (c->is_moe_layer) {
+        if (!w->g2 || !w->wr || !w->eg || !w->eu || !w->ed) return fail(c, ETC_EINVAL, "g2, wr, eg, eu, ed are required");
+    } else if (!w->g1 || !w->wq || !w->wk || !w->wv || !w->wo || !w->g2) return fail(c, ETC_EINVAL, "attention weights missing");
     if (!moe && (!w->wg || !w->wu || !w->wd)) return fail(c, ETC_EINVAL, "dense FFN weights missing");
     if (moe && (!w->wr || !w->eg || !w->eu || !w->ed)) return fail(c, ETC_EINVAL, "MoE weights missing");
     if (c->model.qk_norm && (!w->gq || !w->gk)) return fail(c, ETC_EINVAL, "per-head norm gains gq / gk missing");
@@ -606,7 +610,7 @@ etc_status etc_bind_lm_head(etc_ctx *c, const void *embed, const void *g_final, 
 
 etc_status etc_bind_kv_pool(etc_ctx *c, void *k_pages, void *v_pages, int64_t pages_per_layer)
 {
-    if (!c || c->is_graph || !k_pages || !v_pages || pages_per_layer < 1) return fail(c, ETC_EINVAL, "bad argument");
+    if (!c || c->is_graph || c->is_moe_layer || !k_pages || !v_pages || pages_per_layer < 1) return fail(c, ETC_EINVAL, "bad argument");
     if (((uintptr_t)k_pages & 15) || ((uintptr_t)v_pages & 15)) return fail(c, ETC_EINVAL, "KV pools must be 16-byte aligned");
     c->base.kpool = (uint16_t *)k_pages;
     c->base.vpool = (uint16_t *)v_pages;
@@ -619,7 +623,7 @@ etc_status etc_bind_kv_pool(etc_ctx *c, void *k_pages, void *v_pages, int64_t pa
 
 etc_status etc_bind_step(etc_ctx *c, int32_t batch, const int32_t *kv_len, const int32_t *page_indptr, const int32_t *page_ids)
 {
-    if (!c || c->is_graph || !kv_len || !page_indptr || !page_ids) return fail(c, ETC_EINVAL, "bad argument");
+    if (!c || c->is_graph || c->is_moe_layer || !kv_len || !page_indptr || !page_ids) return fail(c, ETC_EINVAL, "bad argument");
     if (!c->kv_bound) return fail(c, ETC_ESTATE, "bind the KV pool before a step");
     if (batch < 1 || batch > c->sched.max_batch) return fail(c, ETC_EINVAL, "batch out of range 1..max_batch");
     const int P = c->model.page_size;
@@ -672,6 +676,101 @@ etc_status etc_bind_step(etc_ctx *c, int32_t batch, const int32_t *kv_len, const
     else w_layer += (int64_t)m.n_experts * H + std::min<int64_t>(m.n_experts, (int64_t)batch * m.top_k) * 3 * (int64_t)m.moe_ffn * H;
     const int64_t kv_layer = kv_tokens * KD * 2 + (int64_t)batch * KD * 2;   // read K and V, write the new rows
     c->algorithmic_bytes = 2 * (int64_t)m.n_layers * (w_layer + kv_layer);
+    c->step_bound = true;
+    return ETC_OK;
+}
+
+etc_status etc_moe_layer_create(const etc_model_desc *m, const etc_tile_desc *t, const etc_sched_desc *s, etc_ctx **out)
+{
+    if (!m || !t || !s || !out) return fail(nullptr, ETC_EINVAL, "NULL argument");
+    *out = nullptr;
+    if (s->max_batch < 1 || s->max_batch > kMoeLayerMaxTokens) return fail(nullptr, ETC_EINVAL, "max_batch (tokens) must be in 1..4096");
+    if (s->kind < ETC_SCHED_STATIC || s->kind > ETC_SCHED_UNFUSED) return fail(nullptr, ETC_EINVAL, "unknown scheduler kind");
+    if (s->n_sampled < 1 || s->n_sampled > 8) return fail(nullptr, ETC_EINVAL, "n_sampled must be in 1..8");
+    for (int i = 0; i < s->n_sampled; ++i)
+        if (s->sampled_batch[i] < 1 || s->sampled_batch[i] > s->max_batch || (i && s->sampled_batch[i] <= s->sampled_batch[i - 1]))
+            return fail(nullptr, ETC_EINVAL, "sampled token counts must be ascending, within 1..max_batch");
+    if (s->sampled_batch[s->n_sampled - 1] != s->max_batch)
+        return fail(nullptr, ETC_EINVAL, "the largest sampled token count must equal max_batch");
+    etc_ctx *c = new (std::nothrow) etc_ctx();
+    if (!c) return fail(nullptr, ETC_ENOMEM, "out of host memory");
+    auto bail = [&](etc_status st) {
+        g_create_error = c->err;
+        etc_destroy(c);
+        return st;
+    };
+    c->is_moe_layer = true;
+    c->model = *m;
+    c->model.n_layers = 1;
+    c->model.vocab = 0;
+    c->tiles = *t;
+    ModelDims &d = c->dims;
+    d = ModelDims{1, m->hidden, 0, 0, 0, 0, m->n_experts, m->top_k, m->moe_ffn, 1, 1, t->moe_tile_m};
+    etc_status st = common_device_setup(c, s);
+    if (st != ETC_OK) return bail(st);
+    c->sched.debug_flags &= ~(uint32_t)ETC_DEBUG_LAYER_HIDDEN;      // there is no per-layer dump here: y is the layer's output
+    for (int i = 0; i < s->n_sampled; ++i) {
+        c->plans.emplace_back();
+        DevPlan &dp = c->plans.back();
+        dp.sampled_batch = s->sampled_batch[i];
+        int syms[4] = {dp.sampled_batch, 0, 0, 0};
+        std::string err = build_moe_layer_graph(d, dp.sampled_batch, c->n_queues, &c->graph);
+        if (!err.empty()) { c->err = err; return bail(ETC_EINVAL); }
+        err = instantiate(c->graph, syms, c->n_queues, s->kind == ETC_SCHED_UNFUSED, &dp.host);
+        if (!err.empty()) { c->err = err; return bail(ETC_EINVAL); }
+        st = upload_plan(c, dp);
+        if (st != ETC_OK) return bail(st);
+    }
+    st = alloc_events_and_queue(c);
+    if (st != ETC_OK) return bail(st);
+
+    Params &P = c->base;
+    const size_t T = (size_t)s->max_batch, H = (size_t)m->hidden, E = (size_t)m->n_experts, K = (size_t)m->top_k;
+    const size_t Tp = (T + 63) / 64 * 64, rows = T * K, n_blk = Tp / 64;
+    const size_t r_max = (size_t)moe_max_row_tiles(m->n_experts, m->top_k, s->max_batch, d.tile_m);
+    P.n_layers = 1; P.H = m->hidden; P.E = m->n_experts; P.topk = m->top_k; P.moeF = m->moe_ffn; P.page = 1;
+    P.eps = m->rms_eps; P.tile_m = d.tile_m; P.moel = 1; P.max_batch = s->max_batch;
+    P.col_stride = (int32_t)Tp;
+    auto A = [&](auto **p, size_t n) -> bool {
+        hipError_t e = dev_alloc(p, n, c->owned);
+        if (e != hipSuccess) { c->err = std::string("device allocation failed: ") + hipGetErrorString(e); return false; }
+        return true;
+    };
+    bool okk = A(&P.x, T * H) && A(&P.x_mid, T * H) && A(&P.xmg_hi, Tp * H) && A(&P.xmg_lo, Tp * H) &&
+               A(&P.ssq_xmid, (H / 16) * Tp) && A(&c->d_weights, 1) &&
+               A(&P.router_logits, Tp * E) && A(&P.topk_ids, rows) && A(&P.topk_w, rows) &&
+               A(&P.tok_indptr, E + 1) && A(&P.exp_indptr, E + 1) && A(&P.exp_event, E) && A(&P.perm, rows) && A(&P.inv_perm, rows) &&
+               A(&P.perm_tok, rows) && A(&P.tile_expert, r_max) && A(&P.tile_row0, r_max) && A(&P.tile_n, r_max) &&
+               A(&P.eact_hi, rows * (size_t)m->moe_ffn) && A(&P.eact_lo, rows * (size_t)m->moe_ffn) && A(&P.ey, rows * H) &&
+               A(&P.moel_hist, n_blk * E) && A(&P.moel_base, n_blk * E) && A(&P.moel_count, E);
+    if (okk && (s->debug_flags & ETC_DEBUG_ROUTING))
+        okk = A(&P.dbg_logits, T * E) && A(&P.dbg_topk_ids, rows) && A(&P.dbg_topk_w, rows) && A(&P.dbg_perm, rows) &&
+              A(&P.dbg_tok_indptr, E + 1) && A(&P.dbg_exp_indptr, E + 1);
+    if (!okk) return bail(ETC_ENOMEM);
+    c->h_weights.assign(1, LayerWeights{});
+    c->weights_bound.assign(1, 0);
+    *out = c;
+    return ETC_OK;
+}
+
+etc_status etc_moe_layer_bind_tokens(etc_ctx *c, int32_t n_tokens)
+{
+    if (!c || !c->is_moe_layer) return fail(c, ETC_EINVAL, "not a MoE-layer context");
+    if (n_tokens < 1 || n_tokens > c->sched.max_batch) return fail(c, ETC_EINVAL, "n_tokens out of range 1..max_batch");
+    etc_status st = refuse_if_dead(c);
+    if (st != ETC_OK) return st;
+    int plan = -1;
+    for (size_t i = 0; i < c->plans.size(); ++i)
+        if (c->plans[i].sampled_batch >= n_tokens) { plan = (int)i; break; }
+    if (plan < 0) return fail(c, ETC_EINVAL, "no sampled token count covers this block");
+    if (plan != c->cur_plan) c->need_arm = true;
+    if (c->base.exec_count) c->need_exec_reset = true;
+    c->cur_plan = plan;
+    c->bound_batch = n_tokens;
+    // algorithmic bytes: gain, router and every routed expert's three matrices once; the tokens in (bf16) and out (bf16)
+    const etc_model_desc &m = c->model;
+    const int64_t H = m.hidden, experts = std::min<int64_t>(m.n_experts, (int64_t)n_tokens * m.top_k);
+    c->algorithmic_bytes = 2 * (H + (int64_t)m.n_experts * H + experts * 3 * (int64_t)m.moe_ffn * H) + 4 * (int64_t)n_tokens * H;
     c->step_bound = true;
     return ETC_OK;
 }
@@ -827,6 +926,22 @@ etc_status etc_rowsum_launch_noalloc(const float *A, float *C, int32_t n, void *
 // ---- host-only inspection ---------------------------------------------------------------------------
 static_assert(sizeof(etc_task_record) == sizeof(Task), "public task record must mirror the device record");
 
+static void fill_plan_view(Plan *p, int32_t n_queues, etc_plan_view *out)
+{
+    out->n_tasks = (int64_t)p->tasks.size();
+    out->n_events = (int64_t)p->ev_init.size();
+    out->n_queues = n_queues;
+    out->n_seed = (int64_t)p->seed_tasks.size();
+    out->tasks = reinterpret_cast<const etc_task_record *>(p->tasks.data());
+    out->queue_tasks = reinterpret_cast<const etc_task_record *>(p->queue_tasks.data());
+    out->queue_begin = p->queue_begin.data();
+    out->ev_init = p->ev_init.data();
+    out->ev_consumers = p->ev_consumers.data();
+    out->consumer_ids = p->consumer_ids.data();
+    out->seed_tasks = p->seed_tasks.data();
+    out->opaque = p;
+}
+
 etc_status etc_plan_build(const etc_model_desc *m, const etc_tile_desc *t, const etc_sched_desc *s, int32_t sampled_batch,
                           int32_t n_queues, etc_plan_view *out)
 {
@@ -845,18 +960,25 @@ etc_status etc_plan_build(const etc_model_desc *m, const etc_tile_desc *t, const
     int syms[4] = {sampled_batch, (s->max_kv_len + chunk - 1) / chunk, 0, 0};
     err = instantiate(g, syms, n_queues, s->kind == ETC_SCHED_UNFUSED, p);
     if (!err.empty()) { delete p; return fail(nullptr, ETC_EINVAL, err); }
-    out->n_tasks = (int64_t)p->tasks.size();
-    out->n_events = (int64_t)p->ev_init.size();
-    out->n_queues = n_queues;
-    out->n_seed = (int64_t)p->seed_tasks.size();
-    out->tasks = reinterpret_cast<const etc_task_record *>(p->tasks.data());
-    out->queue_tasks = reinterpret_cast<const etc_task_record *>(p->queue_tasks.data());
-    out->queue_begin = p->queue_begin.data();
-    out->ev_init = p->ev_init.data();
-    out->ev_consumers = p->ev_consumers.data();
-    out->consumer_ids = p->consumer_ids.data();
-    out->seed_tasks = p->seed_tasks.data();
-    out->opaque = p;
+    fill_plan_view(p, n_queues, out);
+    return ETC_OK;
+}
+
+etc_status etc_moe_layer_plan_build(const etc_model_desc *m, const etc_tile_desc *t, const etc_sched_desc *s, int32_t sampled_tokens,
+                                    int32_t n_queues, etc_plan_view *out)
+{
+    if (!m || !t || !s || !out) return fail(nullptr, ETC_EINVAL, "NULL argument");
+    if (n_queues < 1) return fail(nullptr, ETC_EINVAL, "bad queue count");
+    ModelDims d{1, m->hidden, 0, 0, 0, 0, m->n_experts, m->top_k, m->moe_ffn, 1, 1, t->moe_tile_m};
+    GraphDecl g;
+    std::string err = build_moe_layer_graph(d, sampled_tokens, n_queues, &g);
+    if (!err.empty()) return fail(nullptr, ETC_EINVAL, err);
+    Plan *p = new (std::nothrow) Plan();
+    if (!p) return fail(nullptr, ETC_ENOMEM, "out of host memory");
+    int syms[4] = {sampled_tokens, 0, 0, 0};
+    err = instantiate(g, syms, n_queues, s->kind == ETC_SCHED_UNFUSED, p);
+    if (!err.empty()) { delete p; return fail(nullptr, ETC_EINVAL, err); }
+    fill_plan_view(p, n_queues, out);
     return ETC_OK;
 }
 

@@ -60,6 +60,12 @@ enum Fn : uint8_t {
     FN_LMHEAD = 18,       // end of the iteration: final RMSNorm folded in, consecutive 16-row tiles of the vocabulary projection ->
                           //   fp32 logits, and each tile's best (logit, id) folded into the sequence's running maximum
     FN_SAMPLE = 19,       // greedy token of every sequence from the running maxima (ties: lower id)
+    // The MoE layer on its own over a block of tokens (Sec. 2.4; token sweep of Sec. 4.2 / 4.5): grouping in three
+    // counting passes instead of one tile per token, because a tile that ranks against every token is quadratic.
+    FN_MOEL_LOAD = 20,    // 16 tokens: x_in bf16 -> residual fp32, (x * gain) split, per-tile sums of squares
+    FN_MOEL_TOPK = 21,    // 64 tokens: top-k ids and weights of each, the block's pair count per expert
+    FN_MOEL_SCAN = 22,    // one task: totals, prefix sums over experts and blocks, row-tile tables
+    FN_MOEL_PLACE = 23,   // 64 tokens: stable rank of the block's pairs -> permutation; dynamic scheduler: expert events
     FN_COUNT
 };
 
@@ -134,6 +140,8 @@ struct Params {
     uint16_t *attn_hi, *attn_lo;       // attention output, split [maxB, nq*d]
     uint16_t *act_hi, *act_lo;         // silu(gate)*up, split [maxB, F]
     float *part_m, *part_l, *part_o;   // split-KV partials [maxB, nq, max_chunks] (+ [d])
+    int32_t col_stride;                // floats between two tiles' rows of ssq_x / ssq_xmid: kMaxBatch for decoders, the
+                                       //   token capacity of a stand-alone MoE layer
     float *kpart;                      // K-slice partials of a projection [slice][row tile][kMaxBatch][16], or null
     int32_t k_slices_o, k_slices_d;    // slices of K of the O / down projection tasks of the bound plan (0: whole K)
     int32_t all_staged;                // every projection task of the bound plan fits the staged path
@@ -146,6 +154,10 @@ struct Params {
     int32_t *tile_expert, *tile_row0, *tile_n; // [max row tiles]: expert, first row and rows of every row tile
     uint16_t *eact_hi, *eact_lo;       // expert activations, split [maxB*topk, moeF]
     float *ey;                         // expert outputs fp32 [maxB*topk, H]
+    int32_t moel;                      // 1: stand-alone MoE layer over a block of B tokens
+    int32_t *moel_hist;                // [token blocks of 64][E] pairs of the block routed to the expert
+    int32_t *moel_base;                // [token blocks][E] first grouped row of the block's pairs of the expert
+    int32_t *moel_count;               // [E] pairs routed to the expert
     const int32_t *forced_topk;        // [n_layers, maxB, topk] or null
     const uint8_t *forced_mask;        // [n_layers] or null: bit 0 = ids forced, bit 1 = weights forced as well
     const float *forced_w;             // [n_layers, maxB, topk] or null

@@ -486,4 +486,109 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
     return "";
 }
 
+// x + MoE(rmsnorm(x)) over T tokens.  Routing and grouping run as three counting passes over blocks of 64 tokens
+// (top-k and per-block expert histogram; one scan over experts and blocks; stable rank inside the block), so the work
+// is linear in the tokens; the GroupGEMM grids are the row-tile slots of the decoder's MoE block (reading 19).
+std::string build_moe_layer_graph(const ModelDims &m, int Ts, int n_queues, GraphDecl *out)
+{
+    GraphDecl &g = *out;
+    g = GraphDecl();
+    if (Ts < 1 || Ts > kMoeLayerMaxTokens) return "tokens must be in 1..4096";
+    if (m.H % (kWaves * 32)) return "hidden must be a multiple of 256";
+    if (m.E < 16 || m.E % 16 || m.E > kMaxExperts) return "n_experts must be a multiple of 16, at most 256";
+    if (m.topk < 1 || m.topk > kMaxTopK || m.topk > m.E) return "top_k must be in 1..16 and at most n_experts";
+    if (m.moeF < 1 || m.moeF % (kWaves * 32)) return "moe_ffn must be a multiple of 256";
+    if (m.tile_m < 1 || m.tile_m > 64) return "tile_m must be in 1..64";
+    const DimExpr one = dim_const(1);
+    const int n_blk = (Ts + 63) / 64, n_ht = m.H / 16, n_ft = m.moeF / 8;
+    const int r_max = moe_max_row_tiles(m.E, m.topk, Ts, m.tile_m);
+    auto tiles_per_task = [&](int per_slot) {
+        const long long total = (long long)r_max * per_slot;
+        const long long want = total <= 4LL * n_queues ? n_queues : 3LL * n_queues;
+        int cand = (int)std::max(1LL, total / std::max(1LL, want));
+        cand = std::min(cand, per_slot);
+        while (cand > 1 && per_slot % cand) --cand;
+        return std::max(1, cand);
+    };
+    const int r_g = tiles_per_task(n_ft), r_d = tiles_per_task(n_ht);
+    const int e_x = g.add_event({one});
+    const int e_logits = g.add_event({dim_const(n_blk)});
+    const int e_hist = g.add_event({one});
+    const int e_scan = g.add_event({one});
+    const int e_group = g.add_event({one});
+    const int e_eact = g.add_event({dim_const(r_max)});
+    const int e_y = g.add_event({one});
+    const int e_out = g.add_event({one});
+    int stage = 0;
+    {
+        CallDecl c;
+        c.fn = FN_MOEL_LOAD; c.stage = stage++;
+        c.rank = 1; c.shape[0] = dim_const((Ts + 15) / 16);
+        c.out = {edge_const0(e_x)};
+        g.calls.push_back(c);
+    }
+    {
+        CallDecl c;
+        c.fn = FN_ROUTER_LOGITS; c.stage = stage++;      // task record: (16 router rows, block of 64 tokens)
+        c.rank = 2; c.shape[0] = dim_const(m.E / 16); c.shape[1] = dim_const(n_blk);
+        c.in = {edge_const0(e_x)};
+        c.out = {edge_dim(e_logits, 1)};
+        g.calls.push_back(c);
+    }
+    {
+        CallDecl c;
+        c.fn = FN_MOEL_TOPK; c.stage = stage++;
+        c.rank = 1; c.shape[0] = dim_const(n_blk);
+        c.in = {edge_dim(e_logits, 0)};
+        c.out = {edge_const0(e_hist)};
+        g.calls.push_back(c);
+    }
+    {
+        CallDecl c;
+        c.fn = FN_MOEL_SCAN; c.stage = stage++;
+        c.rank = 1; c.shape[0] = one;
+        c.in = {edge_const0(e_hist)};
+        c.out = {edge_const0(e_scan)};
+        g.calls.push_back(c);
+    }
+    {
+        CallDecl c;
+        c.fn = FN_MOEL_PLACE; c.stage = stage++;
+        c.rank = 1; c.shape[0] = dim_const(n_blk);
+        c.in = {edge_const0(e_scan)};
+        c.out = {edge_const0(e_group)};
+        g.calls.push_back(c);
+    }
+    {
+        CallDecl c;
+        c.fn = FN_MOE_GATEUP; c.stage = stage++;     // task record: (row-tile slot, first tile, tiles)
+        c.rank = 2; c.shape[0] = dim_const(r_max); c.shape[1] = dim_const(n_ft / r_g);
+        c.c_mul[1] = r_g; c.c_fill[2] = r_g;
+        c.flags = TF_DYN_ROWTILE;
+        c.in = {edge_const0(e_group)};
+        c.out = {edge_dim(e_eact, 0)};
+        g.calls.push_back(c);
+    }
+    {
+        CallDecl c;
+        c.fn = FN_MOE_DOWN; c.stage = stage++;
+        c.rank = 2; c.shape[0] = dim_const(r_max); c.shape[1] = dim_const(n_ht / r_d);
+        c.c_mul[1] = r_d; c.c_fill[2] = r_d;
+        c.flags = TF_DYN_ROWTILE;
+        c.in = {edge_dim(e_eact, 0)};
+        c.out = {edge_const0(e_y)};
+        g.calls.push_back(c);
+    }
+    {
+        CallDecl c;
+        c.fn = FN_COMBINE; c.stage = stage++;        // task record: (token, chunk of 512 elements)
+        c.rank = 2; c.shape[0] = dim_const(Ts); c.shape[1] = dim_const((m.H + kWgThreads - 1) / kWgThreads);
+        c.flags = TF_LAST_LAYER;
+        c.in = {edge_const0(e_y)};
+        c.out = {edge_const0(e_out)};
+        g.calls.push_back(c);
+    }
+    return "";
+}
+
 }  // namespace etc

@@ -137,4 +137,9 @@ inline int k_slices_for(int K)
 std::string build_decoder_graph(const ModelDims &m, int sampled_batch, int n_queues, bool moe_static_coarse,
                                 GraphDecl *out);
 
+// The MoE layer on its own over a block of tokens (Sec. 2.4; token sweep of Sec. 4.2 / 4.5).  Only H, E, topk, moeF and
+// tile_m of the dimensions are read.  The graph is built for `sampled_tokens` tokens (its grids are constants).
+constexpr int kMoeLayerMaxTokens = 4096;
+std::string build_moe_layer_graph(const ModelDims &m, int sampled_tokens, int n_queues, GraphDecl *out);
+
 }  // namespace etc

@@ -140,7 +140,7 @@ __device__ __forceinline__ bool setup_gemm(const Params &P, const Task &t, GemmT
         g.rowsB = wbase + (size_t)(i0 + P.d / 2) * P.H;
         g.ldw = P.H; g.K = P.H;
         g.b_hi = P.xg_hi; g.b_lo = P.xg_lo; g.ldb = P.H;
-        g.ssq_parts = P.ssq_x; g.n_parts = P.H / 16; g.eps = P.eps;
+        g.ssq_parts = P.ssq_x; g.n_parts = P.H / 16; g.eps = P.eps; g.ssq_stride = MOE ? P.col_stride : kMaxBatch;
         g.n_cols = P.B;
         e.kind = EPI_QKV; e.layer = t.layer; e.row0 = i0; e.head = hd;
         return true;
@@ -165,7 +165,7 @@ __device__ __forceinline__ bool setup_gemm(const Params &P, const Task &t, GemmT
         g.rowsB = (const uint16_t *)W->wu + (size_t)f0 * P.H;
         g.ldw = P.H; g.K = P.H;
         g.b_hi = P.xmg_hi; g.b_lo = P.xmg_lo; g.ldb = P.H;
-        g.ssq_parts = P.ssq_xmid; g.n_parts = P.H / 16; g.eps = P.eps;
+        g.ssq_parts = P.ssq_xmid; g.n_parts = P.H / 16; g.eps = P.eps; g.ssq_stride = MOE ? P.col_stride : kMaxBatch;
         g.n_cols = P.B;
         e.kind = EPI_SWIGLU; e.layer = t.layer; e.row0 = f0; e.out_hi = P.act_hi; e.out_lo = P.act_lo; e.ld = P.F;
         return true;
@@ -196,7 +196,7 @@ __device__ __forceinline__ bool setup_gemm(const Params &P, const Task &t, GemmT
         g.rowsB = g.rowsA + (size_t)8 * P.H;
         g.ldw = P.H; g.K = P.H;
         g.b_hi = P.xg_hi; g.b_lo = P.xg_lo; g.ldb = P.H;
-        g.ssq_parts = P.ssq_x; g.n_parts = P.H / 16; g.eps = P.eps;
+        g.ssq_parts = P.ssq_x; g.n_parts = P.H / 16; g.eps = P.eps; g.ssq_stride = MOE ? P.col_stride : kMaxBatch;
         g.n_cols = P.B;
         e.kind = EPI_LOGITS; e.layer = t.layer; e.row0 = r0; e.outf = P.logits; e.ld = P.vocab;
         return true;
@@ -204,14 +204,16 @@ __device__ __forceinline__ bool setup_gemm(const Params &P, const Task &t, GemmT
     case FN_ROUTER_LOGITS: {
         if (!MOE) return false;
         const int r0 = t.c0 * 16;
+        const int cb = t.c1 * 64;      // stand-alone MoE layer: one task per block of 64 tokens (c1 = 0 in a decoder)
         g.n_tiles = 1; g.tile_rows = 16;
         g.rowsA = (const uint16_t *)W->wr + (size_t)r0 * P.H;
         g.rowsB = g.rowsA + (size_t)8 * P.H;
         g.ldw = P.H; g.K = P.H;
-        g.b_hi = P.xmg_hi; g.b_lo = P.xmg_lo; g.ldb = P.H;
-        g.ssq_parts = P.ssq_xmid; g.n_parts = P.H / 16; g.eps = P.eps;
-        g.n_cols = P.B;
-        e.kind = EPI_STORE_F32; e.layer = t.layer; e.row0 = r0; e.outf = P.router_logits; e.ld = P.E;
+        g.b_hi = P.xmg_hi + (size_t)cb * P.H; g.b_lo = P.xmg_lo + (size_t)cb * P.H; g.ldb = P.H;
+        g.ssq_parts = P.ssq_xmid; g.n_parts = P.H / 16; g.eps = P.eps; g.ssq_stride = MOE ? P.col_stride : kMaxBatch;
+        g.ssq_parts += cb;
+        g.n_cols = P.B - cb < 64 ? P.B - cb : 64;      // <= 0: a block beyond the bound tokens (the caller skips the tile)
+        e.kind = EPI_STORE_F32; e.layer = t.layer; e.row0 = r0; e.outf = P.router_logits + (size_t)cb * P.E; e.ld = P.E;
         return true;
     }
     default:
@@ -270,7 +272,7 @@ __device__ __forceinline__ void setup_moe_gemm(const Params &P, const Task &t, c
         g.ldw = P.H; g.K = P.H;
         g.b_hi = P.xmg_hi; g.b_lo = P.xmg_lo; g.ldb = P.H;
         g.col_rows = P.perm_tok + rt.row0;             // column n reads the hidden state of the row's token
-        g.ssq_parts = P.ssq_xmid; g.n_parts = P.H / 16; g.eps = P.eps;
+        g.ssq_parts = P.ssq_xmid; g.n_parts = P.H / 16; g.eps = P.eps; g.ssq_stride = P.col_stride;
         e.kind = EPI_MOE_ACT; e.row0 = f0; e.out_hi = P.eact_hi; e.out_lo = P.eact_lo; e.ld = P.moeF;
     } else {
         const int h0 = t.c1 * 16;
@@ -329,6 +331,7 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
         return;
     }
     if (BASE != KIND_GENERIC && setup_gemm<MOE, LM>(P, t, g, e)) {
+        if (MOE && g.n_cols <= 0) return;         // token block beyond the bound tokens: nothing to do but notify
         if (STAGED_ONLY) {
             if (STAGED_SLICES && (t.flags & TF_K_SLICE)) {      // here a slice of K fits the staged path as well
                 slice_of_k(P, t, t.fn == FN_OPROJ ? P.k_slices_o : P.k_slices_d, g, e);
@@ -405,6 +408,20 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
             wg_wait_cached(P, st, w0, w1, t.fn);
             st.staged_key = -1;      // the routing scratch overlaps the staged operand
             moe_route_and_group(PL, t.layer, t.c0, t.notify0, sm);
+        }
+        break;
+    case FN_MOEL_LOAD:
+        if (MOE) moel_load(PL, t.c0);
+        break;
+    case FN_MOEL_TOPK:
+    case FN_MOEL_SCAN:
+    case FN_MOEL_PLACE:
+        if (MOE) {
+            wg_wait_cached(P, st, w0, w1, t.fn);
+            st.staged_key = -1;      // the routing scratch overlaps the staged operand
+            if (t.fn == FN_MOEL_TOPK) moel_topk(PL, t.c0, sm);
+            else if (t.fn == FN_MOEL_SCAN) moel_scan(PL, sm);
+            else moel_place(PL, t.c0, t.notify0, sm);
         }
         break;
     case FN_COMBINE:
@@ -611,7 +628,7 @@ __global__ void __launch_bounds__(kWgThreads) megakernel_dynamic(const Params P)
         // themselves, when the expert's event fires, so those are not pushed when the router tiles are
         // dispatched, and a triggered tile has nothing left to wait for.
         const bool dd_notify = kind_base(KIND) == KIND_GENERIC && (t.flags & TF_NOTIFY_INDIRECT);     // generic graphs (Sec. 2.4)
-        const bool dd_producer = (kind_base(KIND) == KIND_MOE && P.moe_dd && t.fn == FN_ROUTER) || dd_notify;
+        const bool dd_producer = (kind_base(KIND) == KIND_MOE && P.moe_dd && (t.fn == FN_ROUTER || t.fn == FN_MOEL_PLACE)) || dd_notify;
         if (kind_base(KIND) == KIND_MOE && P.moe_dd && t.fn == FN_MOE_GATEUP) t.wait0 = -1;
         if (sched_wave) {
             // This task is dispatched: the last producer of its event to get here pushes the consumers.

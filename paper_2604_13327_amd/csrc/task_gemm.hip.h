@@ -32,8 +32,9 @@ struct GemmTile {
     int ldb;
     const int32_t *col_rows;         // optional gather: column n reads operand row col_rows[n]
     int n_cols;                      // valid columns (batch rows or routed tokens), <= 64
-    const float *ssq_parts;          // RMSNorm: partial sums of squares [n_parts][kMaxBatch], or null
+    const float *ssq_parts;          // RMSNorm: partial sums of squares [n_parts][ssq_stride], or null
     int n_parts;
+    int ssq_stride;
     float eps;
     int n_tiles;                     // consecutive 16-row tiles this task streams back to back
     int tile_rows;                   // rows between consecutive tiles inside each 8-row group (8 or 16)
@@ -262,7 +263,7 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const int pt = lane + 64 * j;
-                    sq[j] = (pt < g.n_parts && row >= 0) ? ld_f32(g.ssq_parts + (size_t)pt * kMaxBatch + row) : 0.f;
+                    sq[j] = (pt < g.n_parts && row >= 0) ? ld_f32(g.ssq_parts + (size_t)pt * (size_t)g.ssq_stride + row) : 0.f;
                 }
             }
             request_epilogue_inputs();
@@ -291,7 +292,7 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const int pt = lane + 64 * j;
-                    sq[j] = (pt < g.n_parts && row >= 0) ? ld_f32(g.ssq_parts + (size_t)pt * kMaxBatch + row) : 0.f;
+                    sq[j] = (pt < g.n_parts && row >= 0) ? ld_f32(g.ssq_parts + (size_t)pt * (size_t)g.ssq_stride + row) : 0.f;
                 }
             }
             request_epilogue_inputs();
@@ -309,7 +310,7 @@ __device__ __forceinline__ void gemm_tiles_staged(const Params &P, const GemmTil
                     const int row = g.col_rows ? ld_i32(g.col_rows + col) : col;
                     float s = 0.f;
                     if (row >= 0)
-                        for (int pt = lane; pt < g.n_parts; pt += 64) s += ld_f32(g.ssq_parts + (size_t)pt * kMaxBatch + row);
+                        for (int pt = lane; pt < g.n_parts; pt += 64) s += ld_f32(g.ssq_parts + (size_t)pt * (size_t)g.ssq_stride + row);
                     s = wave_sum(s);
                     if (lane == 0) rs[col] = 1.0f / sqrtf(s / (float)g.K + g.eps);
                 }
@@ -579,7 +580,7 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, const ChunkedAr
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 const int pt = p0 + 8 * j;
-                t[j] = (pt < g.n_parts && row >= 0) ? ld_f32(g.ssq_parts + (size_t)pt * kMaxBatch + row) : 0.f;
+                t[j] = (pt < g.n_parts && row >= 0) ? ld_f32(g.ssq_parts + (size_t)pt * (size_t)g.ssq_stride + row) : 0.f;
             }
 #pragma unroll
             for (int j = 0; j < 16; ++j) s += t[j];
@@ -708,7 +709,10 @@ __device__ __forceinline__ void gemm_tiles_chunked_passes(const Params &PL, Chun
     for (int t0 = 0; t0 < total; t0 += T) {
         a.g.n_tiles = total - t0 < T ? total - t0 : T;
         if (t0 > 0 || a.g.n_tiles != total) {      // the slot already holds the arguments of a single pass
-            if (threadIdx.x == 0) lds_put(slot, a);      // the callee's last barrier is behind its last read
+            __syncthreads();                       // every wavefront has read the slot's current contents (a wavefront that
+                                                   // runs ahead must not rewrite them under the others: they would disagree
+                                                   // on the number of passes)
+            if (threadIdx.x == 0) lds_put(slot, a);
             __syncthreads();
         }
         gemm_tiles_chunked<NB, T>(PL, slot, sm, frame_anchor);

@@ -286,6 +286,267 @@ __device__ __noinline__ void moe_route_and_group(const Params &P, int layer, int
     __syncthreads();     // the routing scratch in LDS is free again
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// The MoE layer on its own over a block of T tokens (Sec. 2.4; the token sweep of Sec. 4.2 / 4.5).
+// One router tile per token that ranks its pairs against every other token is quadratic in the tokens, so the
+// grouping runs as three counting passes over blocks of 64 tokens: (1) top-k of the block's tokens and the
+// block's pair count per expert; (2) one scan over experts and blocks: totals, prefix sums, the first grouped row
+// of every (block, expert) and the row-tile tables; (3) the stable rank of every pair inside its block.  The
+// grouped order is the decoder's: (expert, token, slot).  Still no slot is grabbed with an atomic: the
+// permutation is the same in every run and schedule.
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kMoelBlock = 64;
+
+__device__ __forceinline__ void st_u64(void *p, uint64_t v)
+{
+    __hip_atomic_store(as_global(reinterpret_cast<uint64_t *>(p)), v, __ATOMIC_RELAXED, ETC_SCOPE);
+}
+
+// 16 tokens: x_in (bf16) -> residual stream fp32, (x * gain) split into hi + lo, per-16-element sums of squares.
+__device__ __noinline__ void moel_load(const Params &P, int blk16)
+{
+    blk16 = __builtin_amdgcn_readfirstlane(blk16);
+    const uint16_t *g2 = (const uint16_t *)as_global(P.weights)[0].g2;
+    const int n_parts = P.H / 16;
+    for (int i = wave_id(); i < 16; i += kWaves) {
+        const int tok = blk16 * 16 + i;
+        if (tok >= P.B) break;
+        for (int part = lane_id(); part < n_parts; part += 64) {
+            const size_t o = (size_t)tok * P.H + (size_t)part * 16;
+            const u32x4 xa = gld_16B(P.hidden_in + o), xb = gld_16B(P.hidden_in + o + 8);
+            const u32x4 ga = gld_16B(g2 + part * 16), gb = gld_16B(g2 + part * 16 + 8);
+            const uint32_t xw[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
+            const uint32_t gw[8] = {ga.x, ga.y, ga.z, ga.w, gb.x, gb.y, gb.z, gb.w};
+            float s = 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; j += 2) {          // four elements per round: one 8-byte store of each hi and lo, two of x
+                float v[4];
+                uint16_t hi[4], lo[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t xx = xw[j + (q >> 1)], gg = gw[j + (q >> 1)];
+                    v[q] = bf16_bits_to_f32((uint16_t)((q & 1) ? (xx >> 16) : (xx & 0xFFFFu)));
+                    const float gv = bf16_bits_to_f32((uint16_t)((q & 1) ? (gg >> 16) : (gg & 0xFFFFu)));
+                    split_bf16(v[q] * gv, hi[q], lo[q]);
+                    s += v[q] * v[q];
+                }
+                const size_t oo = o + (size_t)j * 2;
+                st_u64(P.x_mid + oo, (uint64_t)__float_as_uint(v[0]) | ((uint64_t)__float_as_uint(v[1]) << 32));
+                st_u64(P.x_mid + oo + 2, (uint64_t)__float_as_uint(v[2]) | ((uint64_t)__float_as_uint(v[3]) << 32));
+                st_u64(P.xmg_hi + oo, (uint64_t)hi[0] | ((uint64_t)hi[1] << 16) | ((uint64_t)hi[2] << 32) | ((uint64_t)hi[3] << 48));
+                st_u64(P.xmg_lo + oo, (uint64_t)lo[0] | ((uint64_t)lo[1] << 16) | ((uint64_t)lo[2] << 32) | ((uint64_t)lo[3] << 48));
+            }
+            st_f32(P.ssq_xmid + (size_t)part * (size_t)P.col_stride + tok, s);
+        }
+    }
+}
+
+// Block of 64 tokens: top-k ids (larger logit first, equal logits: lower expert first) and routing weights
+// (softmax over the selected logits) of each token; the block's pair count per expert.
+__device__ __noinline__ void moel_topk(const Params &P, int blk, float *sm)
+{
+    blk = __builtin_amdgcn_readfirstlane(blk);
+    const int wave = wave_id(), lane = lane_id();
+    const int E = P.E, K = P.topk;
+    ETC_AS_LDS int32_t *cnt = reinterpret_cast<ETC_AS_LDS int32_t *>(as_lds(sm));      // [E]
+    const int forced_bits = P.forced_mask != nullptr ? (int)*as_global(P.forced_mask) : 0;
+    const bool forced = (forced_bits & 1) != 0, forced_w = forced && (forced_bits & 2) != 0 && P.forced_w != nullptr;
+    const bool dbg = (P.debug_flags & 4u) != 0 && P.dbg_logits != nullptr;
+    for (int e = threadIdx.x; e < E; e += kWgThreads) cnt[e] = 0;
+    __syncthreads();
+    for (int i = wave; i < kMoelBlock; i += kWaves) {
+        const int b = blk * kMoelBlock + i;
+        if (b >= P.B) break;
+        const float *lg = P.router_logits + (size_t)b * E;
+        float v[kMaxExperts / 64];
+        bool taken[kMaxExperts / 64];
+#pragma unroll
+        for (int j = 0; j < kMaxExperts / 64; ++j) {
+            const int e = lane + 64 * j;
+            taken[j] = false;
+            v[j] = e < E ? ld_f32(lg + e) : -INFINITY;
+            if (dbg && e < E) as_global(P.dbg_logits)[(size_t)b * E + e] = v[j];
+        }
+        int my_id = 0;
+        float my_v = -INFINITY;
+        if (forced) {
+            if (lane < K) {
+                my_id = gld_i32(P.forced_topk + (size_t)b * K + lane);
+                my_v = ld_f32(lg + my_id);
+            }
+        } else {
+            for (int k = 0; k < K; ++k) {
+                uint64_t key = 0;
+#pragma unroll
+                for (int j = 0; j < kMaxExperts / 64; ++j) {
+                    const int e = lane + 64 * j;
+                    if (e < E && !taken[j]) key = max(key, topk_key(v[j], e));
+                }
+                key = wave_max_u64(key);
+                const int bi = (int)(0xFFFFFFFFu - (uint32_t)key);
+                if (lane == k) { my_id = bi; my_v = topk_key_logit(key); }
+#pragma unroll
+                for (int j = 0; j < kMaxExperts / 64; ++j)
+                    if (lane + 64 * j == bi) taken[j] = true;
+            }
+        }
+        float mx = lane < K ? my_v : -INFINITY;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+        const float p = lane < K ? __expf(my_v - mx) : 0.f;
+        const float den = wave_sum(p);
+        if (lane < K) {
+            float wgt = p / den;
+            if (forced_w) wgt = *as_global(P.forced_w + (size_t)b * K + lane);
+            st_i32(P.topk_ids + (size_t)b * K + lane, my_id);
+            st_f32(P.topk_w + (size_t)b * K + lane, wgt);
+            if (dbg) {
+                as_global(P.dbg_topk_ids)[(size_t)b * K + lane] = my_id;
+                as_global(P.dbg_topk_w)[(size_t)b * K + lane] = wgt;
+            }
+            __hip_atomic_fetch_add(cnt + my_id, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);      // integer count: order-free
+        }
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += kWgThreads) st_i32(P.moel_hist + (size_t)blk * E + e, cnt[e]);
+    __syncthreads();
+}
+
+// One task: pairs per expert, prefix sums over the experts (pairs and row tiles), the first grouped row of every
+// (block, expert), the row-tile tables.  Under the dynamic scheduler it also takes the surplus row-tile slots of the
+// static grids out of the counts that were fixed before the routing was known (as tile 0 does in a decoder).
+__device__ __noinline__ void moel_scan(const Params &P, float *sm)
+{
+    const int E = P.E, M = P.tile_m, n_blk = (P.B + kMoelBlock - 1) / kMoelBlock;
+    ETC_AS_LDS int32_t *cnt = reinterpret_cast<ETC_AS_LDS int32_t *>(as_lds(sm));      // [E]
+    ETC_AS_LDS int32_t *til = cnt + kMaxExperts;                                       // [E]
+    ETC_AS_LDS int32_t *tokp = til + kMaxExperts;                                      // [E+1]
+    ETC_AS_LDS int32_t *expp = tokp + kMaxExperts + 1;                                 // [E+1]
+    const bool dbg = (P.debug_flags & 4u) != 0 && P.dbg_logits != nullptr;
+    for (int e = threadIdx.x; e < E; e += kWgThreads) {
+        int n = 0;
+        for (int b = 0; b < n_blk; ++b) n += ld_i32(P.moel_hist + (size_t)b * E + e);
+        cnt[e] = n;
+        til[e] = (n + M - 1) / M;
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e <= E; e += kWgThreads) {
+        int a = 0, c = 0;
+        for (int j = 0; j < e; ++j) { a += cnt[j]; c += til[j]; }
+        tokp[e] = a;
+        expp[e] = c;
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += kWgThreads) {
+        int row = tokp[e];
+        for (int b = 0; b < n_blk; ++b) {
+            st_i32(P.moel_base + (size_t)b * E + e, row);
+            row += ld_i32(P.moel_hist + (size_t)b * E + e);
+        }
+        st_i32(P.moel_count + e, cnt[e]);
+        int n = cnt[e], r = expp[e];
+        row = tokp[e];
+        for (; n > 0; n -= M, ++r, row += M) {
+            st_i32(P.tile_expert + r, e);
+            st_i32(P.tile_row0 + r, row);
+            st_i32(P.tile_n + r, n < M ? n : M);
+        }
+    }
+    for (int e = threadIdx.x; e <= E; e += kWgThreads) {
+        st_i32(P.tok_indptr + e, tokp[e]);
+        st_i32(P.exp_indptr + e, expp[e]);
+        if (dbg) {
+            as_global(P.dbg_tok_indptr)[e] = tokp[e];
+            as_global(P.dbg_exp_indptr)[e] = expp[e];
+        }
+    }
+    if (P.moe_dd && wave_id() == 0) {
+        const int lane = lane_id(), G = P.moe_groups_gu, Gd = P.moe_groups_down;
+        const int live = expp[E], dead = P.moe_rmax - live;
+        const int ev_slot0 = gld_i32(P.moe_layer_events), ev_y = gld_i32(P.moe_layer_events + 1);
+        for (int r = live + lane; r < P.moe_rmax; r += 64) st_i32(P.ev_cur + ev_slot0 + r, 0);
+        if (lane == 0 && dead > 0) {
+            __hip_atomic_fetch_sub(as_global(P.ev_cur + ev_y), dead * Gd, __ATOMIC_RELAXED, ETC_SCOPE);
+            __hip_atomic_fetch_sub(as_global(P.ev_disp_cur + ev_y), dead * Gd, __ATOMIC_RELAXED, ETC_SCOPE);
+            __hip_atomic_fetch_add(as_global(P.q_ctrl_cur + 3), dead * (G + Gd), __ATOMIC_RELAXED, ETC_SCOPE);
+        }
+    }
+    __syncthreads();
+}
+
+// Data-dependent event update and task triggering (Sec. 2.4) of the stand-alone layer, dynamic scheduler only: the
+// block adds its pair count of every expert to the expert's event at once; the total per expert is known since the
+// scan, so the update that completes it has fired the event and releases the expert's GroupGEMM-1 tiles, the
+// row-tile slots [exp_indptr[e], exp_indptr[e+1]), to the ready queue.
+__device__ __forceinline__ void moel_update_and_trigger(const Params &P, int blk, int group_ev)
+{
+    drain_vmem();            // this block's share of the permutation is written
+    __syncthreads();
+    if (wave_id() != 0) return;
+    const int lane = lane_id(), E = P.E, G = P.moe_groups_gu;
+    const int c0 = __builtin_amdgcn_readfirstlane(gld_i32(P.ev_consumers + group_ev));
+    for (int e0 = 0; e0 < E; e0 += 64) {
+        const int e = e0 + lane;
+        const int h = e < E ? ld_i32(P.moel_hist + (size_t)blk * E + e) : 0;
+        const int before = h > 0 ? __hip_atomic_fetch_sub(as_global(P.exp_event + e), h, __ATOMIC_RELAXED, ETC_SCOPE) : 0;
+        const bool fired = h > 0 && before - h == -ld_i32(P.moel_count + e);
+        int first = 0, n_rel = 0;
+        if (fired) {
+            st_i32(P.exp_event + e, 0);
+            const int r0 = ld_i32(P.exp_indptr + e), r1 = ld_i32(P.exp_indptr + e + 1);
+            first = r0 * G;
+            n_rel = (r1 - r0) * G;
+        }
+        drain_vmem();        // the fired counters are back at zero before the tasks they release are published
+        const int total = wave_sum_i(n_rel);
+        if (total == 0) continue;
+        const int base = q_reserve_wave(P, total);
+        if (base < 0) return;
+        int off = 0;
+        uint64_t m = __ballot(fired);
+        while (m) {
+            const int src = __builtin_ctzll(m);
+            m &= m - 1;
+            const int s0 = __shfl(first, src, 64), n = __shfl(n_rel, src, 64);
+            for (int i = lane; i < n; i += 64)
+                __hip_atomic_store(as_global(P.q_slots + base + off + i),
+                                   q_slot_word(P, gld_i32(P.consumer_ids + c0 + s0 + i) & 0xFFFFFF), __ATOMIC_RELAXED, ETC_SCOPE);
+            off += n;
+        }
+    }
+}
+
+// Block of 64 tokens: every pair's grouped row = first row of (block, expert) + its rank among the block's earlier
+// pairs of the same expert (pairs in token, slot order).
+__device__ __noinline__ void moel_place(const Params &P, int blk, int group_ev, float *sm)
+{
+    blk = __builtin_amdgcn_readfirstlane(blk);
+    group_ev = __builtin_amdgcn_readfirstlane(group_ev);
+    const int E = P.E, K = P.topk;
+    const int n_tok = P.B - blk * kMoelBlock < kMoelBlock ? P.B - blk * kMoelBlock : kMoelBlock;
+    ETC_AS_LDS int32_t *ids_s = reinterpret_cast<ETC_AS_LDS int32_t *>(as_lds(sm));    // [64 * K]
+    ETC_AS_LDS int32_t *base_s = ids_s + kMoelBlock * kMaxTopK;                        // [E]
+    const bool dbg = (P.debug_flags & 4u) != 0 && P.dbg_logits != nullptr;
+    if (n_tok > 0) {
+        const int n_pairs = n_tok * K, pair0 = blk * kMoelBlock * K;
+        for (int p = threadIdx.x; p < n_pairs; p += kWgThreads) ids_s[p] = ld_i32(P.topk_ids + pair0 + p);
+        for (int e = threadIdx.x; e < E; e += kWgThreads) base_s[e] = ld_i32(P.moel_base + (size_t)blk * E + e);
+        __syncthreads();
+        for (int p = threadIdx.x; p < n_pairs; p += kWgThreads) {
+            const int e = ids_s[p];
+            int rank = 0;
+            for (int q = 0; q < p; ++q) rank += ids_s[q] == e ? 1 : 0;
+            const int pos = base_s[e] + rank, pair = pair0 + p;
+            st_i32(P.perm + pos, pair);
+            st_i32(P.inv_perm + pair, pos);
+            st_i32(P.perm_tok + pos, pair / K);
+            if (dbg) as_global(P.dbg_perm)[pos] = pair;
+        }
+    }
+    if (P.moe_dd) moel_update_and_trigger(P, blk, group_ev);
+    __syncthreads();
+}
+
 // Combine tile (token b, 512 consecutive elements): x = x_mid + sum_k w[b,k] * y[row of pair (b,k)],
 // slots in ascending order.  Like every producer of the residual stream it also prepares the next
 // layer's projection operand (x * gain, split) and the partial sums of squares per 16 elements.

@@ -484,3 +484,143 @@ def test_vocab_must_be_a_multiple_of_16():
     import dataclasses
     with pytest.raises(etc.EtcError):
         etc.plan_build(dataclasses.replace(synth.TINY_LM, vocab=1000), 32, 1, 8, max_kv_len=129)
+
+
+# ---------------------------------------------------------------- the MoE layer on its own (token sweep)
+FN_MOEL_LOAD, FN_MOEL_TOPK, FN_MOEL_SCAN, FN_MOEL_PLACE = 20, 21, 22, 23
+
+
+@pytest.mark.parametrize("kind", [etc.SCHED_STATIC, etc.SCHED_UNFUSED])
+@pytest.mark.parametrize("tokens,nq,tile_m", [(1, 4, 16), (70, 16, 16), (128, 256, 64), (1000, 64, 64)])
+def test_moe_layer_static_plans_run_to_completion(kind, tokens, nq, tile_m):
+    s = synth.TINY_MOE
+    plan = etc.moe_layer_plan_build(s, tokens, nq, kind=kind, moe_tile_m=tile_m)
+    ev, done = run_static(plan, np.random.default_rng(tokens + nq))
+    assert (ev == 0).all() and (done == 1).all()
+    t = plan["tasks"]
+    n_blk = -(-tokens // 64)
+    r_max = (tokens * s.top_k + min(s.n_experts, tokens * s.top_k) * (tile_m - 1)) // tile_m
+    assert (t["fn"] == FN_MOEL_LOAD).sum() == -(-tokens // 16)
+    assert (t["fn"] == FN_ROUTER_LOGITS).sum() == s.n_experts // 16 * n_blk
+    assert (t["fn"] == FN_MOEL_TOPK).sum() == n_blk and (t["fn"] == FN_MOEL_PLACE).sum() == n_blk
+    assert (t["fn"] == FN_MOEL_SCAN).sum() == 1
+    gu = t[t["fn"] == FN_MOE_GATEUP]
+    assert int(gu["c0"].max()) + 1 == r_max
+    # every row-tile slot covers every tile of the expert FFN exactly once
+    per_slot = np.zeros(s.moe_F // 8, np.int64)
+    for x in gu[gu["c0"] == 0]:
+        per_slot[int(x["c1"]): int(x["c1"]) + int(x["c2"])] += 1
+    assert (per_slot == 1).all()
+    assert (t["fn"] == FN_COMBINE).sum() == tokens * -(-s.H // 512)
+    if kind == etc.SCHED_STATIC:
+        # a block's top-k waits for the router tiles of its own block only
+        topk0 = t[t["fn"] == FN_MOEL_TOPK][0]
+        assert plan["ev_init"][int(topk0["wait0"])] == s.n_experts // 16
+
+
+def run_dynamic_moe_layer(plan, n_workers, rng, s, tokens, tile_m):
+    """The dynamic scheduler's protocol for the stand-alone MoE layer on a random routing: the scan task takes the
+    surplus row-tile slots out of the counts; a placing task adds its block's pair count of every expert to the expert's
+    event, the update that completes the expert's total fires it and releases its GroupGEMM-1 tasks; placing tasks do
+    not count as dispatched producers and a released task waits for nothing."""
+    E, K = s.n_experts, s.top_k
+    tasks = plan["tasks"]
+    ev = plan["ev_init"].astype(np.int64).copy()
+    disp = ev.copy()
+    done = np.zeros(len(tasks), np.int64)
+    pending = np.zeros(len(tasks), np.int64)
+    pushed = np.zeros(len(tasks), np.int64)
+    r_max = int(tasks[tasks["fn"] == FN_MOE_GATEUP]["c0"].max()) + 1
+    G = int(((tasks["fn"] == FN_MOE_GATEUP) & (tasks["c0"] == 0)).sum())
+    Gd = int(((tasks["fn"] == FN_MOE_DOWN) & (tasks["c0"] == 0)).sum())
+    ids = np.stack([rng.choice(E, size=K, replace=False) for _ in range(tokens)])
+    n_blk = -(-tokens // 64)
+    hist = np.stack([np.bincount(ids[b * 64:(b + 1) * 64].ravel(), minlength=E) for b in range(n_blk)])
+    cnt = hist.sum(0)
+    expp = np.concatenate([[0], np.cumsum(-(-cnt // tile_m))])
+    down0 = tasks[(tasks["fn"] == FN_MOE_DOWN) & (tasks["c0"] == 0)][0]
+    ev_slot0, ev_y = int(down0["wait0"]), int(down0["notify0"])
+    exp_ev = np.zeros(E, np.int64)
+    credit = 0
+    expect = np.ones(len(tasks), np.int64)
+    for t in tasks:
+        if t["fn"] in (FN_MOE_GATEUP, FN_MOE_DOWN) and t["c0"] >= expp[-1]:
+            expect[t["id"]] = 0
+    queue = list(plan["seed_tasks"])
+    pushed[queue] += 1
+    workers = [None] * n_workers
+
+    def push_consumers(n):
+        for entry in plan["consumer_ids"][plan["ev_consumers"][n]:plan["ev_consumers"][n + 1]].tolist():
+            tid, n_waited = entry & 0xFFFFFF, (entry >> 24) & 0x7F
+            if n_waited > 1:
+                pending[tid] += 1
+                if pending[tid] % n_waited:
+                    continue
+            queue.append(tid)
+            pushed[tid] += 1
+
+    while True:
+        for w in range(n_workers):
+            if workers[w] is None and queue:
+                workers[w] = queue.pop(0)
+                t = tasks[workers[w]]
+                n = int(t["notify0"])
+                if n >= 0 and t["fn"] != FN_MOEL_PLACE:
+                    disp[n] -= 1
+                    if disp[n] == 0:
+                        push_consumers(n)
+        busy = [w for w in range(n_workers) if workers[w] is not None]
+        if not busy:
+            break
+
+        def waits_of(t):
+            return [] if t["fn"] == FN_MOE_GATEUP else list(_waits(t))
+        runnable = [w for w in busy if all(ev[e] == 0 for e in waits_of(tasks[workers[w]]))]
+        assert runnable, "deadlock in the dynamic protocol"
+        w = int(rng.choice(runnable))
+        t = tasks[workers[w]]
+        done[t["id"]] += 1
+        workers[w] = None
+        if t["fn"] == FN_MOEL_SCAN:
+            live = int(expp[-1])
+            dead = r_max - live
+            ev[ev_slot0 + live: ev_slot0 + r_max] = 0
+            ev[ev_y] -= dead * Gd
+            disp[ev_y] -= dead * Gd
+            credit += dead * (G + Gd)
+        if t["fn"] == FN_MOEL_PLACE and int(t["c0"]) < n_blk:
+            c0 = int(plan["ev_consumers"][int(t["notify0"])])
+            for e in np.nonzero(hist[int(t["c0"])])[0].tolist():
+                h = int(hist[int(t["c0"]), e])
+                before = exp_ev[e]
+                exp_ev[e] -= h
+                if before - h == -cnt[e]:
+                    exp_ev[e] = 0
+                    for entry in plan["consumer_ids"][c0 + expp[e] * G: c0 + expp[e + 1] * G].tolist():
+                        queue.append(entry & 0xFFFFFF)
+                        pushed[entry & 0xFFFFFF] += 1
+        if int(t["notify0"]) >= 0:
+            ev[int(t["notify0"])] -= 1
+    assert (pushed == expect).all() and (done == expect).all()
+    assert int(done.sum()) + credit == len(tasks)
+    assert (exp_ev == 0).all()
+    return ev
+
+
+@pytest.mark.parametrize("tokens,sampled,tile_m,workers", [(1, 1, 16, 3), (70, 70, 4, 5), (100, 128, 16, 16), (300, 300, 64, 7)])
+def test_moe_layer_dynamic_plan_with_data_dependent_triggers(tokens, sampled, tile_m, workers):
+    plan = etc.moe_layer_plan_build(synth.TINY_MOE, sampled, 8, kind=etc.SCHED_DYNAMIC, moe_tile_m=tile_m)
+    for seed in range(2):
+        ev = run_dynamic_moe_layer(plan, workers, np.random.default_rng(seed), synth.TINY_MOE, tokens, tile_m)
+        assert (ev == 0).all()
+
+
+def test_moe_layer_descriptor_validation():
+    import dataclasses
+    with pytest.raises(etc.EtcError):
+        etc.moe_layer_plan_build(synth.TINY_MOE, 5000, 8)                       # more than 4096 tokens
+    with pytest.raises(etc.EtcError):
+        etc.moe_layer_plan_build(synth.TINY_MOE, 64, 8, moe_tile_m=65)
+    with pytest.raises(etc.EtcError):
+        etc.moe_layer_plan_build(dataclasses.replace(synth.TINY_MOE, n_experts=20), 64, 8)

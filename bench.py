@@ -19,6 +19,7 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0       # dense bf16 matrix-core peak of MI355X
 T_PROCESS_START = time.time()
 
 
@@ -67,16 +68,87 @@ def print_timeline(dec, etc, shape, args, B, L, f):
     print(f"whole step: {us(tr[:, 5].max() - tr[:, 0][tr[:, 0] > 0].min()):.1f} us (with tracing on)", file=f)
 
 
+def bench_moe_layer(args) -> int:
+    """The MoE layer on its own (paper Sec. 4.2 / 4.5, the token sweep of the ablation): Qwen3-30B-A3B layer shape,
+    --batch tokens, one launch per step.  Reports the step time, the HBM fraction on the algorithmic bytes (weights of
+    the routed experts once, tokens in and out) and the matrix-core fraction on the algorithmic flops."""
+    import numpy as np
+    import torch
+
+    import paper_2604_13327_amd as etc
+    import synth
+    from synth.workloads import weight_specs
+
+    s, T = synth.QWEN3_30B_A3B, args.batch
+    torch.manual_seed(2024)
+    w = {name: torch.empty(shp, dtype=torch.bfloat16, device="cuda").normal_(mean, sigma)
+         for name, shp, mean, sigma in weight_specs(s) if name in ("g2", "wr", "eg", "eu", "ed")}
+    x = torch.empty(T, s.H, dtype=torch.bfloat16, device="cuda").normal_()
+    y = torch.empty_like(x)
+    kind = {"static": etc.SCHED_STATIC, "dynamic": etc.SCHED_DYNAMIC, "unfused": etc.SCHED_UNFUSED}[args.sched]
+    layer = etc.MoeLayer(s, [T], kind=kind, moe_tile_m=args.moe_tile_m, debug_flags=etc.DEBUG_ROUTING)
+    layer.bind_weights(w)
+    layer.bind_tokens(T)
+    launch = layer.launch_kernel_by_kernel if args.kernel_by_kernel else layer.launch
+    for _ in range(args.warmup + 1):
+        launch(x, y)
+    torch.cuda.synchronize()
+    assert (layer.error_word() == 0).all()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for a, b in ev:
+        a.record()
+        launch(x, y)
+        b.record()
+    torch.cuda.synchronize()
+    per = np.array([a.elapsed_time(b) * 1e3 for a, b in ev])
+    us = float(ev[0][0].elapsed_time(ev[-1][1]) * 1e3 / args.steps)
+    from paper_2604_13327_amd import binding as b_
+    ids = layer.routing_debug(b_.DBG_TOPK_IDS, 0, (T, s.top_k), np.int32)
+    n_exp = int(len(np.unique(ids)))
+    tiles = int(layer.routing_debug(b_.DBG_EXP_INDPTR, 0, (s.n_experts + 1,), np.int32)[-1])
+    alg_bytes = 2 * (s.H + s.n_experts * s.H + n_exp * 3 * s.moe_F * s.H) + 4 * T * s.H
+    flops = T * (2 * s.H * s.n_experts + s.top_k * 3 * 2 * s.H * s.moe_F)
+    info = layer.step_info()
+    kern_us = float(per.mean())
+    hbm = alg_bytes / (kern_us * 1e-6) / 1e9
+    tfl = flops / (kern_us * 1e-6) / 1e12
+    bound = "mfma" if tfl / MFMA_BF16_PEAK_TFLOPS > hbm / HBM_PEAK_GBS else "hbm"
+    result = {
+        "metric": "moe_layer_latency_us", "value": round(us, 2), "unit": "us", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(us / 1e3, 5), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic (torch generator)",
+        "config": {"workload": f"qwen3-30b-a3b MoE layer, {T} tokens, row tiles of {args.moe_tile_m}",
+                   "scheduler": args.sched + (" (kernel by kernel)" if args.kernel_by_kernel else ""),
+                   "tasks_per_step": int(info.n_tasks), "events_per_step": int(info.n_events),
+                   "experts_routed": n_exp, "row_tiles": tiles},
+        "tokens_per_s": round(T / (us * 1e-6), 1),
+        "roofline": {"bound": bound, "kernel": "megakernel_dynamic" if args.sched == "dynamic" else "megakernel_static",
+                     "achieved": round(tfl, 2) if bound == "mfma" else round(hbm, 1),
+                     "peak": MFMA_BF16_PEAK_TFLOPS if bound == "mfma" else HBM_PEAK_GBS,
+                     "unit": "TFLOP/s" if bound == "mfma" else "GB/s",
+                     "frac": round(tfl / MFMA_BF16_PEAK_TFLOPS if bound == "mfma" else hbm / HBM_PEAK_GBS, 4),
+                     "hbm_gbs": round(hbm, 1), "hbm_frac": round(hbm / HBM_PEAK_GBS, 4), "tflops": round(tfl, 2),
+                     "mfma_frac": round(tfl / MFMA_BF16_PEAK_TFLOPS, 4), "algorithmic_bytes_per_launch": int(alg_bytes),
+                     "algorithmic_flops_per_launch": int(flops), "avg_launch_us": round(kern_us, 2), "traffic": None},
+    }
+    layer.close()
+    print(json.dumps(result))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="llama3-8b", help="llama3-8b (headline) | tiny")
+    ap.add_argument("--workload", default="llama3-8b",
+                    help="llama3-8b (headline) | any shape of synth.SHAPES | moe-layer (the MoE layer alone, --batch tokens)")
     ap.add_argument("--sched", default="static", choices=["static", "dynamic", "unfused"])
     ap.add_argument("--kv-len", type=int, default=1024)
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--kv-chunk", type=int, default=128, help="smallest number of keys per split-KV attention task")
+    ap.add_argument("--moe-tile-m", type=int, default=64, help="moe-layer workload: tokens per GroupGEMM row tile")
+    ap.add_argument("--kernel-by-kernel", action="store_true", help="moe-layer workload: one launch per stage")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-comparators", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=0, help="layers the CPU oracle runs (0 = all)")
@@ -106,6 +178,8 @@ def main() -> int:
     from harness import GpuModel, bf16_to_f32_np, fixed_step, rel_err
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.workload == "moe-layer":
+        return bench_moe_layer(args)
     shape = synth.SHAPES[args.workload]
     seed, B, L = 2024, args.batch, args.kv_len
     n_pool = B * synth.pages_needed(L, shape.page) + 16

@@ -221,25 +221,6 @@ __device__ __forceinline__ bool setup_gemm(const Params &P, const Task &t, GemmT
     }
 }
 
-// The two task kinds of a K-sliced projection (large-batch plans only).  The instances that carry them are not the
-// latency-critical ones; the heavy paths behind them (chunked, staged) are out of line.
-// First stage: row tiles c0 .. c0+c2-1 against K slice c1.
-__device__ __forceinline__ WgState k_slice_task(const Params &PL, const Task &t, TaskWaits tw, float *sm, WgState st)
-{
-    GemmTile g{};
-    Epilogue e{};
-    setup_gemm<false, true>(PL, t, g, e);
-    slice_of_k(PL, t, t.fn == FN_OPROJ ? PL.k_slices_o : PL.k_slices_d, g, e);
-    if (tw.ev0 >= 0) tw.op_key = tw.ev0 + ((t.c1 + 1) << 20);      // a staged copy holds one slice
-    gemm_tile_dispatch<false, true>(PL, PL, g, e, tw, sm, st, t.id);
-    return st;
-}
-// The same out of line, for the MoE instance: its inlined GroupGEMM path is short of registers, and K-slice tasks
-// occur there only in the attention block of large batches.
-__device__ __noinline__ WgState k_slice_task_out_of_line(const Params &PL, Task t, TaskWaits tw, float *sm, WgState st)
-{
-    return k_slice_task(PL, wave_uniform(t), wave_uniform(tw), sm, wave_uniform(st));
-}
 // Second stage: the slices' partial sums of row tile c0, then the projection's own epilogue.
 __device__ __noinline__ void k_slice_sum_task(const Params &PL, Task t_in, int w0, int w1)
 {
@@ -287,6 +268,44 @@ __device__ __forceinline__ void setup_moe_gemm(const Params &P, const Task &t, c
     }
 }
 
+// A projection task on the staged path, out of line, for every instance but the staged-only ones (whose task loop is
+// built around that path).  Inlined into a task loop that also carries the MoE or the large-batch task kinds, the
+// streaming loop was at the mercy of the register allocation of everything around it: builds differed by whether
+// reloads of spilled registers landed inside the loop (where each queues behind the whole weight ring), 15 % of a MoE
+// step.  As a function it has the register file to itself.  It takes the task record and rebuilds the tile
+// descriptors itself (scalar work): 25 words of arguments travel in registers; the descriptors would spill over
+// to the stack, i.e. to scratch memory, once per lane and call (3 GB per Qwen3-shape step at batch 1).
+// mode 0: decoder projection, 1: GroupGEMM row tile rt, 2: K slice of a decoder projection.
+template <bool MOE, bool LM>
+__device__ __noinline__ WgState staged_task_out_of_line(const Params &PL, Task t_in, TaskWaits tw_in, RowTile rt_in, int mode,
+                                                       float *sm, WgState st_in)
+{
+    const Task t = wave_uniform(t_in);
+    const TaskWaits tw = wave_uniform(tw_in);
+    const RowTile rt = wave_uniform(rt_in);
+    WgState st = wave_uniform(st_in);
+    mode = __builtin_amdgcn_readfirstlane(mode);
+    GemmTile g{};
+    Epilogue e{};
+    if (MOE && mode == 1) {
+        setup_moe_gemm(PL, t, rt, g, e);
+    } else {
+        setup_gemm<MOE, LM>(PL, t, g, e);
+        if (mode == 2) slice_of_k(PL, t, t.fn == FN_OPROJ ? PL.k_slices_o : PL.k_slices_d, g, e);
+    }
+    gemm_tiles_staged<PF, LM>(PL, g, e, tw, sm, st, t.id);
+    return st;
+}
+
+// Staged path (out of line, from the task record) or chunked path (out of line, from the descriptors).
+template <bool MOE, bool LM>
+__device__ __forceinline__ void dispatch_projection(const Params &PL, const Task &t, const TaskWaits &tw, const RowTile &rt, int mode,
+                                                    const GemmTile &g, const Epilogue &e, float *sm, WgState &st)
+{
+    if (staged_fits(g.n_tiles, g.n_cols, g.K)) st = staged_task_out_of_line<MOE, LM>(PL, t, tw, rt, mode, sm, st);
+    else gemm_chunked_dispatch<MOE>(PL, g, e, tw, sm, st, t.id);
+}
+
 // KIND: which task kinds the kernel instance carries: 0 generic graphs (the row-sum device functions), 1 dense
 // decoder, 2 MoE decoder, 3 dense decoder whose projection tasks all fit the staged path (small batches), 4 the
 // same with K-slice tasks (the batches at which only a slice of the down projection's operand fits).  The
@@ -321,13 +340,16 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
         setup_moe_gemm(P, t, rt, g, e);
         const int key = w0 < 0 ? -1 : w0 + ((t.c0 + 1) << 20);
         tw = routed ? TaskWaits{w0, w1, (int)t.fn, false, key} : TaskWaits{-1, -1, (int)t.fn, false, key};
-        gemm_tile_dispatch<LM, true, MOE>(P, PL, g, e, tw, sm, st, t.id);
+        dispatch_projection<MOE, LM>(PL, t, tw, rt, 1, g, e, sm, st);
         return;
     }
     constexpr bool STAGED_ONLY = BASE == KIND_DENSE_STAGED || BASE == KIND_DENSE_STAGED_K;
     constexpr bool STAGED_SLICES = BASE == KIND_DENSE_STAGED_K;
-    if (BASE != KIND_GENERIC && !STAGED_ONLY && (t.flags & TF_K_SLICE)) {
-        st = MOE ? k_slice_task_out_of_line(PL, t, tw, sm, st) : k_slice_task(PL, t, tw, sm, st);
+    if (BASE != KIND_GENERIC && !STAGED_ONLY && (t.flags & TF_K_SLICE)) {      // first stage of a K-sliced projection
+        setup_gemm<false, false>(P, t, g, e);
+        slice_of_k(P, t, t.fn == FN_OPROJ ? P.k_slices_o : P.k_slices_d, g, e);
+        if (tw.ev0 >= 0) tw.op_key = tw.ev0 + ((t.c1 + 1) << 20);      // a staged copy holds one slice
+        dispatch_projection<MOE, LM>(PL, t, tw, RowTile{}, 2, g, e, sm, st);
         return;
     }
     if (BASE != KIND_GENERIC && setup_gemm<MOE, LM>(P, t, g, e)) {
@@ -339,7 +361,7 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
             }
             gemm_tiles_staged<10, LM>(P, g, e, tw, sm, st, t.id);
         } else {
-            gemm_tile_dispatch<LM, true, MOE>(P, PL, g, e, tw, sm, st, t.id);
+            dispatch_projection<MOE, LM>(PL, t, tw, RowTile{}, 0, g, e, sm, st);
         }
         return;
     }

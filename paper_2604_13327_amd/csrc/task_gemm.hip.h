@@ -746,22 +746,6 @@ __device__ __noinline__ void gemm_chunked_entry(const Params &PL, ChunkedArgs *s
 #undef ETC_CHUNKED
 }
 
-// PL is the workgroup's LDS copy of the parameters: a kernel argument cannot be passed by address to
-// the out-of-line paths.
-// The staged path as a function of its own, for every instance but the staged-only ones (whose task loop is built
-// around it).  Inlined into a task loop that also carries the MoE or the large-batch task kinds, its streaming loop
-// was at the mercy of the register allocation of everything around it: builds differed by whether reloads of
-// spilled registers landed inside the loop (where each queues behind the whole weight ring), 15 % of a MoE step.
-// As a function it has the register file to itself.
-template <bool LM>
-__device__ __noinline__ WgState gemm_tiles_staged_out_of_line(const Params &PL, GemmTile g, Epilogue e, TaskWaits w, float *sm,
-                                                             WgState st, int task_id)
-{
-    st = wave_uniform(st);
-    gemm_tiles_staged<PF, LM>(PL, wave_uniform(g), wave_uniform(e), wave_uniform(w), sm, st, __builtin_amdgcn_readfirstlane(task_id));
-    return st;
-}
-
 // The same entry with its arguments by value (some travel over the stack, which also keeps the call from being a tail
 // call).  Which hand-over is cheaper is a property of the calling instance, measured: the dense large-batch steps are
 // 6-7 % faster with the LDS slot (less scratch traffic per task), the MoE steps 13-18 % faster with the by-value call
@@ -776,16 +760,11 @@ __device__ __noinline__ void gemm_chunked_entry_by_value(const Params &PL, GemmT
     gemm_chunked_entry(PL, slot, sm, &frame_anchor);
 }
 
-// OOL_STAGED: the staged path is called, not inlined (see above).  ARGS_BY_VALUE: see gemm_chunked_entry_by_value.
-template <bool LM, bool OOL_STAGED = false, bool ARGS_BY_VALUE = false>
-__device__ __forceinline__ void gemm_tile_dispatch(const Params &P, const Params &PL, const GemmTile &g, const Epilogue &e,
-                                                   const TaskWaits &w, float *sm, WgState &st, int task_id)
+// The chunked path from the task loop.  ARGS_BY_VALUE: see gemm_chunked_entry_by_value.
+template <bool ARGS_BY_VALUE>
+__device__ __forceinline__ void gemm_chunked_dispatch(const Params &PL, const GemmTile &g, const Epilogue &e, const TaskWaits &w,
+                                                      float *sm, WgState &st, int task_id)
 {
-    if (staged_fits(g.n_tiles, g.n_cols, g.K)) {
-        if (OOL_STAGED) st = gemm_tiles_staged_out_of_line<LM>(PL, g, e, w, sm, st, task_id);
-        else gemm_tiles_staged<PF, LM>(P, g, e, w, sm, st, task_id);
-        return;
-    }
     st.staged_key = -1;
     if (ARGS_BY_VALUE) {
         gemm_chunked_entry_by_value(PL, g, e, w, sm, task_id);

@@ -527,6 +527,7 @@ etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc
                A(&P.part_m, MB * m->n_q_heads * (size_t)c->max_chunks) &&
                A(&P.part_l, MB * m->n_q_heads * (size_t)c->max_chunks) &&
                A(&P.part_o, MB * m->n_q_heads * (size_t)c->max_chunks * m->head_dim) &&
+               A(&P.attn_arrive, MB * (size_t)m->n_kv_heads) &&
                A(&c->d_weights, (size_t)m->n_layers);
     if (okk) {   // the step's shapes: one device block, and pinned staging slots of the same layout
         c->stage_words = MB + (MB + 1) + MB * (size_t)c->max_pages_per_seq;

@@ -140,6 +140,8 @@ struct Params {
     uint16_t *attn_hi, *attn_lo;       // attention output, split [maxB, nq*d]
     uint16_t *act_hi, *act_lo;         // silu(gate)*up, split [maxB, F]
     float *part_m, *part_l, *part_o;   // split-KV partials [maxB, nq, max_chunks] (+ [d])
+    int32_t *attn_arrive;              // [maxB, nkv] chunk tasks of the (sequence, KV head) that have stored their partials: the
+                                       //   last one merges and puts the counter back to zero
     int32_t col_stride;                // floats between two tiles' rows of ssq_x / ssq_xmid: kMaxBatch for decoders, the
                                        //   token capacity of a stand-alone MoE layer
     float *kpart;                      // K-slice partials of a projection [slice][row tile][kMaxBatch][16], or null

@@ -275,7 +275,6 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
     }
     for (int l = 0; l < m.n_layers; ++l) {
         const int e_qkv = g.add_event({dim_const(m.nkv)});
-        const int e_split = g.add_event({B, dim_const(m.nkv)});
         const int e_attn = g.add_event({one});
         const int e_xmid = g.add_event({one});
         const int e_xnext = g.add_event({one});
@@ -303,14 +302,9 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
             c.rank = 3; c.shape[0] = B; c.shape[1] = dim_const(m.nkv); c.shape[2] = NCH;
             c.last_dim_slowest = true;
             c.in = {edge_dim(e_qkv, 1)};
-            c.out = {edge(e_split, {MAP_DIM, MAP_DIM}, {0, 1}, {1, 1})};
-            g.calls.push_back(c);
-        }
-        {
-            CallDecl c;
-            c.fn = FN_MERGE; c.layer = l; c.stage = stage++;
-            c.rank = 2; c.shape[0] = B; c.shape[1] = dim_const(m.nkv);
-            c.in = {edge(e_split, {MAP_DIM, MAP_DIM}, {0, 1}, {1, 1})};
+            // The chunk task that arrives last at its (sequence, KV head) merges the chunks itself (counted with a
+            // returning atomic outside the event tensors), so the merge is no stage and no event of its own: every
+            // chunk task notifies the attention block's one event, the merging one after its merge.
             c.out = {edge_const0(e_attn)};
             g.calls.push_back(c);
         }

@@ -243,15 +243,33 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
         st_f32(P.part_o + pidx * D + i, num);
         if (i == 0) { st_f32(P.part_m + pidx, m); st_f32(P.part_l + pidx, den); }
     }
+    // The chunk task that arrives last at its (sequence, KV head) merges the chunks itself: the merge is no stage of
+    // its own, one all-to-all hand-over less per layer.  Arrival is counted with one returning atomic per task (behind
+    // the drain of the partial results); the last one puts the counter back for the next launch.  Every chunk task
+    // still notifies the one event of the attention block, the merging one after its merge.
+    if (P.attn_arrive != nullptr) {
+        const int nc = (n_keys + P.kv_chunk - 1) / P.kv_chunk;
+        ETC_AS_LDS int32_t *s_last = reinterpret_cast<ETC_AS_LDS int32_t *>(s_o + (size_t)kWaves * GRP * D);
+        drain_vmem();
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int last = 1;
+            if (nc > 1) {
+                int32_t *ctr = P.attn_arrive + (size_t)b * P.nkv + kvh;
+                last = __hip_atomic_fetch_add(as_global(ctr), 1, __ATOMIC_RELAXED, ETC_SCOPE) + 1 == nc;
+                if (last) st_i32(ctr, 0);
+            }
+            *s_last = last;
+        }
+        __syncthreads();
+        if (*s_last) attn_merge_chunks<D, GRP>(P, b, kvh, nc);
+    }
 }
 
+// Merge of the chunk partials of (sequence b, KV head kvh): ascending chunk order, whoever runs it.
 template <int D, int GRP>
-__device__ __noinline__ void attn_merge(const Params &P, int b, int kvh)
+__device__ __forceinline__ void attn_merge_chunks(const Params &P, int b, int kvh, int nc)
 {
-    b = __builtin_amdgcn_readfirstlane(b);
-    kvh = __builtin_amdgcn_readfirstlane(kvh);
-    const int n_keys = gld_i32(P.kv_len + b) + 1;
-    const int nc = (n_keys + P.kv_chunk - 1) / P.kv_chunk;
     for (int idx = threadIdx.x; idx < GRP * D; idx += kWgThreads) {
         const int g = idx / D, i = idx % D;
         const int h = kvh * GRP + g;
@@ -284,6 +302,16 @@ __device__ __noinline__ void attn_merge(const Params &P, int b, int kvh)
         st_u16(P.attn_hi + o, hi);
         st_u16(P.attn_lo + o, lo);
     }
+}
+
+// The merge as a task of its own (graphs that keep a merge stage).
+template <int D, int GRP>
+__device__ __noinline__ void attn_merge(const Params &P, int b, int kvh)
+{
+    b = __builtin_amdgcn_readfirstlane(b);
+    kvh = __builtin_amdgcn_readfirstlane(kvh);
+    const int n_keys = gld_i32(P.kv_len + b) + 1;
+    attn_merge_chunks<D, GRP>(P, b, kvh, (n_keys + P.kv_chunk - 1) / P.kv_chunk);
 }
 
 }  // namespace etc

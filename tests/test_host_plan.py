@@ -139,7 +139,8 @@ def test_event_counts_follow_the_graph():
     tasks, ev = plan["tasks"], plan["ev_init"]
     n_chunks = -(-max_kv // chunk)
     FN_QKV, FN_ATTN, FN_MERGE, FN_OPROJ, FN_GATEUP, FN_DOWN = 4, 5, 6, 7, 8, 9
-    per_layer = {FN_QKV: (s.nq + 2 * s.nkv) * (s.d // 16), FN_ATTN: B * s.nkv * n_chunks, FN_MERGE: B * s.nkv,
+    # no merge tasks: the attention chunk that arrives last at its (sequence, KV head) merges the chunks itself
+    per_layer = {FN_QKV: (s.nq + 2 * s.nkv) * (s.d // 16), FN_ATTN: B * s.nkv * n_chunks, FN_MERGE: 0,
                  FN_OPROJ: s.H // 16, FN_GATEUP: s.F // 8, FN_DOWN: s.H // 16}
     for fn, n in per_layer.items():
         assert (tasks["fn"] == fn).sum() == n * s.n_layers
@@ -147,8 +148,8 @@ def test_event_counts_follow_the_graph():
     # an attention task of kv head h waits on the event fed by (group + 2) heads x d/16 row tiles
     attn0 = tasks[(tasks["fn"] == FN_ATTN) & (tasks["layer"] == 0)][0]
     assert ev[attn0["wait0"]] == (s.nq // s.nkv + 2) * (s.d // 16)
-    merge0 = tasks[(tasks["fn"] == FN_MERGE) & (tasks["layer"] == 0)][0]
-    assert ev[merge0["wait0"]] == n_chunks                      # shape-dependent count (chunk slots)
+    oproj0 = tasks[(tasks["fn"] == FN_OPROJ) & (tasks["layer"] == 0)][0]
+    assert ev[oproj0["wait0"]] == B * s.nkv * n_chunks          # shape-dependent count: every chunk slot of the layer
     down0 = tasks[(tasks["fn"] == FN_DOWN) & (tasks["layer"] == 0)][0]
     assert down0["flags"] & PER_WAVE
     assert all(ev[down0["wait0"] + w] == (s.F // 8) // N_WAVES for w in range(N_WAVES))
@@ -159,8 +160,8 @@ def test_event_counts_follow_the_graph():
 
 def test_unfused_plan_has_one_event_per_stage():
     plan = etc.plan_build(synth.TINY, 32, 1, 8, max_kv_len=129, kind=etc.SCHED_UNFUSED)
-    # prologue + per layer: qkv, attn, merge, oproj, gateup, down
-    assert len(plan["ev_init"]) == 1 + 6 * synth.TINY.n_layers
+    # prologue + per layer: qkv, attn (+ merge), oproj, gateup, down
+    assert len(plan["ev_init"]) == 1 + 5 * synth.TINY.n_layers
     assert not (plan["tasks"]["flags"] & PER_WAVE).any()
 
 
@@ -168,7 +169,7 @@ def test_llama8b_plan_shape():
     s = synth.LLAMA3_8B
     plan = etc.plan_build(s, 64, 1, 256, max_kv_len=1025)
     # QKV tasks stream 2 row tiles, gate/up tasks 7 (one task per queue and stage); the rest one tile
-    per_layer = 384 // 2 + 8 * 17 + 8 + 256 + 1792 // 7 + 256
+    per_layer = 384 // 2 + 8 * 17 + 256 + 1792 // 7 + 256
     assert len(plan["tasks"]) == 1 + 32 * per_layer
     gu = plan["tasks"][plan["tasks"]["fn"] == 8]
     assert (gu["c1"] == 7).all() and (gu["c0"] % 7 == 0).all()

@@ -275,6 +275,7 @@ def main() -> int:
         if key in tr:
             result["roofline"]["traffic"] = tr[key]["fetch_bytes"] + tr[key]["write_bytes"]
             result["roofline"]["traffic_source"] = tr[key]["source"]
+            result["roofline"]["traffic_measured_at_commit"] = tr[key].get("measured_at_commit")
     except OSError:
         pass
 

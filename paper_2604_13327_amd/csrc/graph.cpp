@@ -502,6 +502,12 @@ std::string build_moe_layer_graph(const ModelDims &m, int Ts, int n_queues, Grap
         int cand = (int)std::max(1LL, total / std::max(1LL, want));
         cand = std::min(cand, per_slot);
         while (cand > 1 && per_slot % cand) --cand;
+        // full row tiles of more than 32 tokens take the wide path, whose pass is 16 row tiles: whole passes, if any
+        if (m.tile_m > 32 && Ts >= 512 && cand >= 16) {
+            int c16 = cand / 16 * 16;
+            while (c16 >= 16 && per_slot % c16) c16 -= 16;
+            if (c16 >= 16) cand = c16;
+        }
         return std::max(1, cand);
     };
     const int r_g = tiles_per_task(n_ft), r_d = tiles_per_task(n_ht);
@@ -575,8 +581,13 @@ std::string build_moe_layer_graph(const ModelDims &m, int Ts, int n_queues, Grap
     }
     {
         CallDecl c;
-        c.fn = FN_COMBINE; c.stage = stage++;        // task record: (token, chunk of 512 elements)
-        c.rank = 2; c.shape[0] = dim_const(Ts); c.shape[1] = dim_const((m.H + kWgThreads - 1) / kWgThreads);
+        // task record: (first token, chunk of 512 elements, tokens): blocks of tokens, about two tasks per queue
+        const int n_ch = (m.H + kWgThreads - 1) / kWgThreads;
+        int tb = std::max(1, Ts * n_ch / std::max(1, 2 * n_queues));
+        tb = std::min(tb, 16);
+        c.fn = FN_COMBINE; c.stage = stage++;
+        c.rank = 2; c.shape[0] = dim_const((Ts + tb - 1) / tb); c.shape[1] = dim_const(n_ch);
+        c.c_mul[0] = tb; c.c_fill[2] = tb;
         c.flags = TF_LAST_LAYER;
         c.in = {edge_const0(e_y)};
         c.out = {edge_const0(e_out)};

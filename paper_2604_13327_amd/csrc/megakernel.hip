@@ -449,7 +449,8 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
     case FN_COMBINE:
         if (MOE && t.c0 < P.B) {
             wg_wait_cached(P, st, w0, w1, t.fn);
-            moe_combine(P, t);
+            if (P.moel) moel_combine(P, t.c0, t.c2, t.c1);      // stand-alone layer: (first token, chunk, tokens)
+            else moe_combine(P, t);
         }
         break;
     default:

@@ -701,6 +701,220 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, const ChunkedAr
         __hip_atomic_fetch_max(as_global(P.best + threadIdx.x), lbest[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Wide path: 64-column tasks with many row tiles (the GroupGEMMs of a stand-alone MoE layer from about a thousand tokens
+// on).  The chunked path splits K over the 8 wavefronts, so every wavefront holds accumulators for all tiles of the pass
+// and a pass is 4 tiles: the 64-column operand (hi and lo: 512 KB at K = 2048) is read again for every 256 KB of
+// weights.  Here the wavefronts split the OUTPUT instead: each owns TW row tiles of the pass and runs over all of K, the
+// operand chunk in LDS is shared by all of them, and a pass is 8 x TW tiles: a quarter (TW = 2) of the operand reads.
+// No reduction across wavefronts; the accumulators go through LDS once, into the layout the epilogue threads read.
+template <int TW>
+__device__ __noinline__ void gemm_tiles_wide(const Params &P, const ChunkedArgs *args, float *sm, int *frame_anchor)
+{
+    const ChunkedArgs a = lds_get_uniform(args);
+    if (a.task_id == -0x7FFFFFFF) *frame_anchor = 1;      // never true; see gemm_tiles_chunked
+    const GemmTile &g = a.g;
+    const Epilogue &e = a.e;
+    const TaskWaits &w = a.w;
+    const int task_id = a.task_id;
+    constexpr int NB = 4, COLS = 64, KC = 256, STRIDE = KC + 8, PPC = KC / 4, U = COLS * PPC / kWgThreads;
+    constexpr int BUF = 2 * COLS * STRIDE;         // elements of one operand buffer: hi columns, then lo columns
+    constexpr int PASS = kWaves * TW;              // row tiles per pass
+    constexpr int RING = 8 * TW;                   // weight fragments of one chunk per wavefront = loads in flight per lane
+    static_assert(TW == 1 || TW == 2, "tiles per wavefront");
+    static_assert((size_t)2 * BUF * 2 + (64 + 512) * 4 <= (size_t)kLdsBytes, "two operand buffers and the norm scratch fit");
+    static_assert((size_t)PASS * NB * 256 * 4 <= (size_t)2 * BUF * 2, "the tiles' accumulators alias the operand buffers");
+    const int wave = wave_id(), lane = lane_id();
+    const int m = lane & 15, kg = lane >> 4;
+    const int K = __builtin_amdgcn_readfirstlane(g.K);
+    const int n_chunks = K / KC;                   // K is a multiple of 256
+    const int n_tiles = __builtin_amdgcn_readfirstlane(g.n_tiles);      // <= PASS
+    const size_t tile_step = (size_t)g.tile_rows * (size_t)g.ldw;
+    const uint16_t *wbase = (m < 8 ? g.rowsA + (size_t)m * (size_t)g.ldw : g.rowsB + (size_t)(m - 8) * (size_t)g.ldw) + kg * 8;
+    // a wavefront whose tile lies beyond n_tiles streams the last live tile again and never stores it: no branch in the loop
+    uint32_t toff[TW];
+#pragma unroll
+    for (int t = 0; t < TW; ++t) {
+        const int ti = wave * TW + t;
+        toff[t] = __builtin_amdgcn_readfirstlane((uint32_t)((size_t)(ti < n_tiles ? ti : n_tiles - 1) * tile_step));
+    }
+    ETC_AS_LDS uint16_t *buf0 = reinterpret_cast<ETC_AS_LDS uint16_t *>(as_lds(sm));
+    ETC_AS_LDS float *tb = as_lds(sm);                                    // after the last chunk: [PASS][NB][64 lanes][4]
+    ETC_AS_LDS float *rs = reinterpret_cast<ETC_AS_LDS float *>(buf0 + 2 * BUF);
+    ETC_AS_LDS float *rs_part = rs + 64;                                  // [8][64]
+
+    // ---- weight prefetch before the wait: the fragments of chunk 0 -----------------------------------------
+    u32x4 wr[RING];
+#pragma unroll
+    for (int j = 0; j < RING; ++j) wr[j] = load16_nt(wbase + toff[j % TW] + (j / TW) * 32);
+    if (w.per_wave) {
+        if (wave == 0 && lane < kWaves) spin_until_zero(P, w.ev0 + lane, w.fn);
+        if (threadIdx.x == 0 && w.ev1 >= 0) spin_until_zero(P, w.ev1, w.fn);
+        __syncthreads();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    } else {
+        wg_wait(P, w.ev0, w.ev1, w.fn);
+    }
+    trace_mark(P, task_id, 1);
+
+    int rows[U], pcs[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int idx = (int)threadIdx.x + kWgThreads * u;
+        const int col = idx / PPC;
+        pcs[u] = idx - col * PPC;
+        rows[u] = 0;
+        if (col < g.n_cols) rows[u] = g.col_rows ? ld_i32(g.col_rows + col) : col;
+        if (rows[u] < 0) rows[u] = 0;
+    }
+    uint64_t vh[U], vl[U];
+    auto fetch_chunk = [&](int c) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t off = (size_t)rows[u] * (size_t)g.ldb + (size_t)c * KC + pcs[u] * 4;
+            vh[u] = ld_u64(g.b_hi + off);
+            vl[u] = ld_u64(g.b_lo + off);
+        }
+    };
+    auto park_chunk = [&](int b) {
+        ETC_AS_LDS uint16_t *hi = buf0 + b * BUF, *lo = hi + COLS * STRIDE;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int idx = (int)threadIdx.x + kWgThreads * u;
+            const int col = idx / PPC;
+            *reinterpret_cast<ETC_AS_LDS uint64_t *>(hi + col * STRIDE + pcs[u] * 4) = vh[u];
+            *reinterpret_cast<ETC_AS_LDS uint64_t *>(lo + col * STRIDE + pcs[u] * 4) = vl[u];
+        }
+    };
+    fetch_chunk(0);
+    if (g.ssq_parts) {       // RMSNorm factors, as in the chunked path
+        const int col = threadIdx.x & 63;
+        int row = -1;
+        if (col < g.n_cols) row = g.col_rows ? ld_i32(g.col_rows + col) : col;
+        float s = 0.f;
+        for (int p0 = wave; p0 < g.n_parts; p0 += 8 * 16) {
+            float t[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int pt = p0 + 8 * j;
+                t[j] = (pt < g.n_parts && row >= 0) ? ld_f32(g.ssq_parts + (size_t)pt * (size_t)g.ssq_stride + row) : 0.f;
+            }
+#pragma unroll
+            for (int j = 0; j < 16; ++j) s += t[j];
+        }
+        rs_part[wave * 64 + col] = s;
+    }
+    park_chunk(0);
+    __syncthreads();
+    if (g.ssq_parts && threadIdx.x < 64) {
+        float s = 0.f;
+#pragma unroll
+        for (int gq = 0; gq < 8; ++gq) s += rs_part[gq * 64 + threadIdx.x];
+        rs[threadIdx.x] = 1.0f / sqrtf(s / (float)g.K + g.eps);
+    }
+    trace_mark(P, task_id, 2);
+
+    f32x4 acc[TW][NB];
+#pragma unroll
+    for (int t = 0; t < TW; ++t)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) acc[t][nb] = f32x4{0, 0, 0, 0};
+    // one chunk: 8 steps of 32 elements of K; RELOAD: ring slots are refilled for the next chunk behind their use
+#define ETC_WIDE_CHUNK(c, RELOAD)                                                                                 \
+    {                                                                                                             \
+        ETC_AS_LDS const uint16_t *hi = buf0 + ((c) & 1) * BUF + m * STRIDE + kg * 8;                             \
+        ETC_AS_LDS const uint16_t *lo = hi + COLS * STRIDE;                                                       \
+        _Pragma("unroll") for (int kk = 0; kk < 8; ++kk) {                                                        \
+            u32x4 fb[NB];                                                                                         \
+            _Pragma("unroll") for (int nb = 0; nb < NB; ++nb)                                                     \
+                fb[nb] = *reinterpret_cast<ETC_AS_LDS const u32x4 *>(hi + nb * 16 * STRIDE + kk * 32);             \
+            _Pragma("unroll") for (int t = 0; t < TW; ++t) {                                                      \
+                const bf16x8 av = __builtin_bit_cast(bf16x8, wr[kk * TW + t]);                                    \
+                _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) acc[t][nb] =                                    \
+                    __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, fb[nb]), acc[t][nb], 0, 0, 0); \
+            }                                                                                                     \
+            _Pragma("unroll") for (int nb = 0; nb < NB; ++nb)                                                     \
+                fb[nb] = *reinterpret_cast<ETC_AS_LDS const u32x4 *>(lo + nb * 16 * STRIDE + kk * 32);             \
+            _Pragma("unroll") for (int t = 0; t < TW; ++t) {                                                      \
+                const bf16x8 av = __builtin_bit_cast(bf16x8, wr[kk * TW + t]);                                    \
+                if (RELOAD) wr[kk * TW + t] = load16_nt(wbase + toff[t] + (size_t)((c) + 1) * KC + kk * 32);      \
+                _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) acc[t][nb] =                                    \
+                    __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, fb[nb]), acc[t][nb], 0, 0, 0); \
+            }                                                                                                     \
+        }                                                                                                         \
+    }
+    int c = 0;
+    for (; c + 1 < n_chunks; ++c) {                // every chunk but the last: the next chunk is fetched and the ring refilled
+        fetch_chunk(c + 1);
+        ETC_WIDE_CHUNK(c, true)
+        park_chunk((c + 1) & 1);
+        __syncthreads();
+    }
+    ETC_WIDE_CHUNK(c, false)
+#undef ETC_WIDE_CHUNK
+    __syncthreads();                               // every wavefront is done with the operand buffers
+
+    // ---- accumulators through LDS into the layout of the epilogue threads, then the epilogue tile by tile ----
+    trace_mark(P, task_id, 3);
+#pragma unroll
+    for (int t = 0; t < TW; ++t) {
+        const int ti = wave * TW + t;
+        if (ti < n_tiles) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                *reinterpret_cast<ETC_AS_LDS f32x4 *>(tb + ((size_t)(ti * NB + nb) * 64 + lane) * 4) = acc[t][nb];
+        }
+    }
+    ETC_AS_LDS unsigned long long *lbest = reinterpret_cast<ETC_AS_LDS unsigned long long *>(rs_part);
+    const bool to_best = e.kind == EPI_LOGITS;
+    if (to_best && (int)threadIdx.x < g.n_cols) lbest[threadIdx.x] = 0ull;
+    __syncthreads();
+    for (int ti = 0; ti < n_tiles; ++ti) {
+        Epilogue et = e;
+        et.row0 = e.row0 + ti * g.tile_rows;
+        et.lds_best = lbest;
+        if (e.ssq_out) et.ssq_out = e.ssq_out + (size_t)ti * kMaxBatch;
+        const int idx = threadIdx.x;
+        if (idx < g.n_cols * 8) {
+            const int col = idx >> 3, mp = idx & 7;
+            const int nb = col >> 4, n = col & 15;
+            ETC_AS_LDS const float *base = tb + (size_t)(ti * NB + nb) * 256;
+            float lo = base[(n + 16 * (mp >> 2)) * 4 + (mp & 3)];
+            float hi = base[(n + 16 * ((mp + 8) >> 2)) * 4 + (mp & 3)];
+            if (g.ssq_parts) {
+                const float r = rs[col];
+                lo *= r;
+                hi *= r;
+            }
+            apply_epilogue<true>(P, et, col, mp, lo, hi, epilogue_preload(P, et, col, mp));
+        }
+    }
+    __syncthreads();                               // the next pass parks its operand over the tiles
+    if (to_best && (int)threadIdx.x < g.n_cols)
+        __hip_atomic_fetch_max(as_global(P.best + threadIdx.x), lbest[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Passes of the wide path: 8 x TW row tiles each.
+template <int TW>
+__device__ __forceinline__ void gemm_tiles_wide_passes(const Params &PL, ChunkedArgs a, ChunkedArgs *slot, float *sm, int *frame_anchor)
+{
+    constexpr int PASS = kWaves * TW;
+    const int total = a.g.n_tiles;
+    for (int t0 = 0; t0 < total; t0 += PASS) {
+        a.g.n_tiles = total - t0 < PASS ? total - t0 : PASS;
+        if (t0 > 0 || a.g.n_tiles != total) {
+            __syncthreads();                       // every wavefront has read the slot's current contents
+            if (threadIdx.x == 0) lds_put(slot, a);
+            __syncthreads();
+        }
+        gemm_tiles_wide<TW>(PL, slot, sm, frame_anchor);
+        a.g.rowsA += (size_t)PASS * a.g.tile_rows * a.g.ldw;
+        a.g.rowsB += (size_t)PASS * a.g.tile_rows * a.g.ldw;
+        a.e.row0 += PASS * a.g.tile_rows;
+        if (a.e.ssq_out) a.e.ssq_out += (size_t)PASS * kMaxBatch;
+        a.w = TaskWaits{-1, -1, a.w.fn, false, -1};
+    }
+}
+
 // One call per pass over the operand: T row tiles each (the events have been seen after the first pass).
 template <int NB, int T>
 __device__ __forceinline__ void gemm_tiles_chunked_passes(const Params &PL, ChunkedArgs a, ChunkedArgs *slot, float *sm, int *frame_anchor)
@@ -740,7 +954,8 @@ __device__ __noinline__ void gemm_chunked_entry(const Params &PL, ChunkedArgs *s
         else if (a.g.n_tiles <= 4 || NB_ == 4) gemm_tiles_chunked_passes<NB_, 4>(PL, a, slot, sm, &anchor);  \
         else gemm_tiles_chunked_passes<NB_, NB_ == 4 ? 4 : 8>(PL, a, slot, sm, &anchor);   /* several passes: crowded expert */ \
     }
-    if (a.g.n_cols > 32) ETC_CHUNKED(4)
+    if (a.g.n_cols > 32 && a.g.n_tiles >= 16 && a.g.K % 256 == 0) gemm_tiles_wide_passes<2>(PL, a, slot, sm, &anchor);
+    else if (a.g.n_cols > 32) ETC_CHUNKED(4)
     else if (a.g.n_cols > 16) ETC_CHUNKED(2)
     else ETC_CHUNKED(1)
 #undef ETC_CHUNKED

@@ -303,40 +303,40 @@ __device__ __forceinline__ void st_u64(void *p, uint64_t v)
 }
 
 // 16 tokens: x_in (bf16) -> residual stream fp32, (x * gain) split into hi + lo, per-16-element sums of squares.
+// A lane takes 8 consecutive elements (one 16-byte load), two neighbouring lanes one 16-element part.
 __device__ __noinline__ void moel_load(const Params &P, int blk16)
 {
     blk16 = __builtin_amdgcn_readfirstlane(blk16);
     const uint16_t *g2 = (const uint16_t *)as_global(P.weights)[0].g2;
-    const int n_parts = P.H / 16;
+    const int n_oct = P.H / 8;
     for (int i = wave_id(); i < 16; i += kWaves) {
         const int tok = blk16 * 16 + i;
         if (tok >= P.B) break;
-        for (int part = lane_id(); part < n_parts; part += 64) {
-            const size_t o = (size_t)tok * P.H + (size_t)part * 16;
-            const u32x4 xa = gld_16B(P.hidden_in + o), xb = gld_16B(P.hidden_in + o + 8);
-            const u32x4 ga = gld_16B(g2 + part * 16), gb = gld_16B(g2 + part * 16 + 8);
-            const uint32_t xw[8] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
-            const uint32_t gw[8] = {ga.x, ga.y, ga.z, ga.w, gb.x, gb.y, gb.z, gb.w};
+        for (int oct = lane_id(); oct < n_oct; oct += 64) {
+            const size_t o = (size_t)tok * P.H + (size_t)oct * 8;
+            const u32x4 xa = gld_16B(P.hidden_in + o), ga = gld_16B(g2 + oct * 8);
+            const uint32_t xw[4] = {xa.x, xa.y, xa.z, xa.w}, gw[4] = {ga.x, ga.y, ga.z, ga.w};
+            float v[8];
+            uint16_t hi[8], lo[8];
             float s = 0.f;
 #pragma unroll
-            for (int j = 0; j < 8; j += 2) {          // four elements per round: one 8-byte store of each hi and lo, two of x
-                float v[4];
-                uint16_t hi[4], lo[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const uint32_t xx = xw[j + (q >> 1)], gg = gw[j + (q >> 1)];
-                    v[q] = bf16_bits_to_f32((uint16_t)((q & 1) ? (xx >> 16) : (xx & 0xFFFFu)));
-                    const float gv = bf16_bits_to_f32((uint16_t)((q & 1) ? (gg >> 16) : (gg & 0xFFFFu)));
-                    split_bf16(v[q] * gv, hi[q], lo[q]);
-                    s += v[q] * v[q];
-                }
-                const size_t oo = o + (size_t)j * 2;
-                st_u64(P.x_mid + oo, (uint64_t)__float_as_uint(v[0]) | ((uint64_t)__float_as_uint(v[1]) << 32));
-                st_u64(P.x_mid + oo + 2, (uint64_t)__float_as_uint(v[2]) | ((uint64_t)__float_as_uint(v[3]) << 32));
-                st_u64(P.xmg_hi + oo, (uint64_t)hi[0] | ((uint64_t)hi[1] << 16) | ((uint64_t)hi[2] << 32) | ((uint64_t)hi[3] << 48));
-                st_u64(P.xmg_lo + oo, (uint64_t)lo[0] | ((uint64_t)lo[1] << 16) | ((uint64_t)lo[2] << 32) | ((uint64_t)lo[3] << 48));
+            for (int q = 0; q < 8; ++q) {
+                const uint32_t xx = xw[q >> 1], gg = gw[q >> 1];
+                v[q] = bf16_bits_to_f32((uint16_t)((q & 1) ? (xx >> 16) : (xx & 0xFFFFu)));
+                const float gv = bf16_bits_to_f32((uint16_t)((q & 1) ? (gg >> 16) : (gg & 0xFFFFu)));
+                split_bf16(v[q] * gv, hi[q], lo[q]);
+                s += v[q] * v[q];
             }
-            st_f32(P.ssq_xmid + (size_t)part * (size_t)P.col_stride + tok, s);
+#pragma unroll
+            for (int q = 0; q < 8; q += 2)
+                st_u64(P.x_mid + o + q, (uint64_t)__float_as_uint(v[q]) | ((uint64_t)__float_as_uint(v[q + 1]) << 32));
+#pragma unroll
+            for (int q = 0; q < 8; q += 4) {
+                st_u64(P.xmg_hi + o + q, (uint64_t)hi[q] | ((uint64_t)hi[q + 1] << 16) | ((uint64_t)hi[q + 2] << 32) | ((uint64_t)hi[q + 3] << 48));
+                st_u64(P.xmg_lo + o + q, (uint64_t)lo[q] | ((uint64_t)lo[q + 1] << 16) | ((uint64_t)lo[q + 2] << 32) | ((uint64_t)lo[q + 3] << 48));
+            }
+            s += dpp_f32<0xB1>(s);               // the neighbouring lane's half of the part (quad_perm [1,0,3,2])
+            if ((lane_id() & 1) == 0) st_f32(P.ssq_xmid + (size_t)(oct >> 1) * (size_t)P.col_stride + tok, s);
         }
     }
 }
@@ -425,7 +425,13 @@ __device__ __noinline__ void moel_scan(const Params &P, float *sm)
     const bool dbg = (P.debug_flags & 4u) != 0 && P.dbg_logits != nullptr;
     for (int e = threadIdx.x; e < E; e += kWgThreads) {
         int n = 0;
-        for (int b = 0; b < n_blk; ++b) n += ld_i32(P.moel_hist + (size_t)b * E + e);
+        for (int b0 = 0; b0 < n_blk; b0 += 16) {           // 16 loads in flight: the scan is alone on the critical path
+            int h[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) h[u] = b0 + u < n_blk ? ld_i32(P.moel_hist + (size_t)(b0 + u) * E + e) : 0;
+#pragma unroll
+            for (int u = 0; u < 16; ++u) n += h[u];
+        }
         cnt[e] = n;
         til[e] = (n + M - 1) / M;
     }
@@ -439,9 +445,15 @@ __device__ __noinline__ void moel_scan(const Params &P, float *sm)
     __syncthreads();
     for (int e = threadIdx.x; e < E; e += kWgThreads) {
         int row = tokp[e];
-        for (int b = 0; b < n_blk; ++b) {
-            st_i32(P.moel_base + (size_t)b * E + e, row);
-            row += ld_i32(P.moel_hist + (size_t)b * E + e);
+        for (int b0 = 0; b0 < n_blk; b0 += 16) {
+            int h[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) h[u] = b0 + u < n_blk ? ld_i32(P.moel_hist + (size_t)(b0 + u) * E + e) : 0;
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                if (b0 + u < n_blk) st_i32(P.moel_base + (size_t)(b0 + u) * E + e, row);
+                row += h[u];
+            }
         }
         st_i32(P.moel_count + e, cnt[e]);
         int n = cnt[e], r = expp[e];
@@ -576,6 +588,39 @@ __device__ __forceinline__ void moe_combine(const Params &P, const Task &t)
         if ((threadIdx.x & 15) == 0) st_f32(P.ssq_x + (size_t)(h >> 4) * kMaxBatch + b, s);
     }
     if (P.debug_flags & 2u) gst_f32(P.layer_hidden + ((size_t)t.layer * kMaxBatch + b) * P.H + h, v);
+}
+
+// Combine of the stand-alone layer: task (block of `n_tok` tokens starting at tok0, 512 consecutive elements).  One
+// task per token would be 16 384 tasks of two dependent load rounds each at 4096 tokens (415 us for 320 MB); a block
+// of tokens keeps every token's row look-ups and expert rows in flight together.
+__device__ __forceinline__ void moel_combine(const Params &P, int tok0, int n_tok, int chunk)
+{
+    const int h = chunk * kWgThreads + (int)threadIdx.x;
+    if (h >= P.H) return;
+    const int K = P.topk;
+    constexpr int TB = 4;                        // tokens in flight per thread
+    for (int b0 = tok0; b0 < tok0 + n_tok && b0 < P.B; b0 += TB) {
+        float acc[TB], xm[TB];
+#pragma unroll
+        for (int u = 0; u < TB; ++u) {
+            const int b = b0 + u < P.B ? b0 + u : P.B - 1;
+            acc[u] = 0.f;
+            xm[u] = ld_f32(P.x_mid + (size_t)b * P.H + h);
+            for (int k = 0; k < K; ++k) {
+                const int pos = ld_i32(P.inv_perm + (size_t)b * K + k);
+                acc[u] += ld_f32(P.topk_w + (size_t)b * K + k) * ld_f32(P.ey + (size_t)pos * P.H + h);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < TB; ++u) {
+            const int b = b0 + u;
+            if (b < P.B && b < tok0 + n_tok) {
+                const float v = xm[u] + acc[u];
+                st_f32(P.x + (size_t)b * P.H + h, v);
+                if (P.hidden_out) gst_u16(P.hidden_out + (size_t)b * P.H + h, f32_to_bf16_bits(v));
+            }
+        }
+    }
 }
 
 }  // namespace etc

@@ -581,8 +581,8 @@ std::string build_moe_layer_graph(const ModelDims &m, int Ts, int n_queues, Grap
     }
     {
         CallDecl c;
-        // task record: (first token, chunk of 512 elements, tokens): blocks of tokens, about two tasks per queue
-        const int n_ch = (m.H + kWgThreads - 1) / kWgThreads;
+        // task record: (first token, chunk of 2048 elements, tokens): blocks of tokens, about two tasks per queue
+        const int n_ch = (m.H + 4 * kWgThreads - 1) / (4 * kWgThreads);
         int tb = std::max(1, Ts * n_ch / std::max(1, 2 * n_queues));
         tb = std::min(tb, 16);
         c.fn = FN_COMBINE; c.stage = stage++;

@@ -745,7 +745,7 @@ __device__ __noinline__ void gemm_tiles_wide(const Params &P, const ChunkedArgs 
     // ---- weight prefetch before the wait: the fragments of chunk 0 -----------------------------------------
     u32x4 wr[RING];
 #pragma unroll
-    for (int j = 0; j < RING; ++j) wr[j] = load16_nt(wbase + toff[j % TW] + (j / TW) * 32);
+    for (int j = 0; j < RING; ++j) wr[j] = gld_16B(wbase + toff[j % TW] + (j / TW) * 32);
     if (w.per_wave) {
         if (wave == 0 && lane < kWaves) spin_until_zero(P, w.ev0 + lane, w.fn);
         if (threadIdx.x == 0 && w.ev1 >= 0) spin_until_zero(P, w.ev1, w.fn);
@@ -836,7 +836,7 @@ __device__ __noinline__ void gemm_tiles_wide(const Params &P, const ChunkedArgs 
                 fb[nb] = *reinterpret_cast<ETC_AS_LDS const u32x4 *>(lo + nb * 16 * STRIDE + kk * 32);             \
             _Pragma("unroll") for (int t = 0; t < TW; ++t) {                                                      \
                 const bf16x8 av = __builtin_bit_cast(bf16x8, wr[kk * TW + t]);                                    \
-                if (RELOAD) wr[kk * TW + t] = load16_nt(wbase + toff[t] + (size_t)((c) + 1) * KC + kk * 32);      \
+                if (RELOAD) wr[kk * TW + t] = gld_16B(wbase + toff[t] + (size_t)((c) + 1) * KC + kk * 32);      \
                 _Pragma("unroll") for (int nb = 0; nb < NB; ++nb) acc[t][nb] =                                    \
                     __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, fb[nb]), acc[t][nb], 0, 0, 0); \
             }                                                                                                     \

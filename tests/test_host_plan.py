@@ -516,7 +516,7 @@ def test_moe_layer_static_plans_run_to_completion(kind, tokens, nq, tile_m):
     covered = np.zeros(tokens, np.int64)                       # every token is combined exactly once per chunk
     for x in comb[comb["c1"] == 0]:
         covered[int(x["c0"]): min(tokens, int(x["c0"]) + int(x["c2"]))] += 1
-    assert (covered == 1).all() and len(comb) == len(comb[comb["c1"] == 0]) * -(-s.H // 512)
+    assert (covered == 1).all() and len(comb) == len(comb[comb["c1"] == 0]) * -(-s.H // 2048)
     if kind == etc.SCHED_STATIC:
         # a block's top-k waits for the router tiles of its own block only
         topk0 = t[t["fn"] == FN_MOEL_TOPK][0]

@@ -116,9 +116,9 @@ inline int effective_kv_chunk(int min_chunk, int page, int max_kv_len, int batch
     return chunk < min_chunk ? min_chunk : chunk;
 }
 
-// Row tiles a large-batch projection task streams against one pass over its operand: 8 up to 32 columns,
-// 4 above (the accumulators of 8 tiles x 64 columns do not fit the register file).
-inline int pass_tiles_for(int batch) { return batch > 32 ? 4 : 8; }
+// Row tiles a large-batch projection task streams against one pass over its operand: 8.  (Above 32 columns the
+// K-split chunked path holds accumulators for 4 tiles at most; such tasks take the wide path, one tile per wavefront.)
+inline int pass_tiles_for(int batch) { (void)batch; return 8; }
 
 // Slices of K for a projection of a large batch: the most of 8, 4, 2 that keep a slice a multiple of the
 // 256 elements one pass of the 8 wavefronts covers; 0 when K is too short to slice.

@@ -955,6 +955,7 @@ __device__ __noinline__ void gemm_chunked_entry(const Params &PL, ChunkedArgs *s
         else gemm_tiles_chunked_passes<NB_, NB_ == 4 ? 4 : 8>(PL, a, slot, sm, &anchor);   /* several passes: crowded expert */ \
     }
     if (a.g.n_cols > 32 && a.g.n_tiles >= 16 && a.g.K % 256 == 0) gemm_tiles_wide_passes<2>(PL, a, slot, sm, &anchor);
+    else if (a.g.n_cols > 32 && a.g.n_tiles >= 5 && a.g.K % 256 == 0) gemm_tiles_wide_passes<1>(PL, a, slot, sm, &anchor);
     else if (a.g.n_cols > 32) ETC_CHUNKED(4)
     else if (a.g.n_cols > 16) ETC_CHUNKED(2)
     else ETC_CHUNKED(1)

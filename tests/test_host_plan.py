@@ -393,18 +393,18 @@ def test_moe_descriptor_validation():
 # ---------------------------------------------------------------- large batches
 def test_large_batch_plan_tile_shapes():
     """Large batches on the 8B shape: the operand cannot be staged whole, so a gate/up task streams several row
-    tiles per pass over it (7 up to 32 columns: one task per queue; 4 at 64 columns), the O and down
-    projections are cut into 8 slices of K with 8 (4) row tiles per task and a second stage that adds the
+    tiles per pass over it (7: one task per queue), the O and down
+    projections are cut into 8 slices of K with 8 row tiles per task and a second stage that adds the
     slices up, and attention is not cut finer than batch x KV heads already provides."""
     s = synth.LLAMA3_8B
     TF_K_SLICE = 8
-    for batch, tiles in ((64, 4), (16, 8)):
+    for batch, tiles in ((64, 8), (16, 8)):
         plan = etc.plan_build(s, 64, batch, 256, max_kv_len=4097)
         t = plan["tasks"]
         l0 = t[t["layer"] == 0]
         qkv, gu = l0[l0["fn"] == 4], l0[l0["fn"] == 8]
         assert (qkv["c2"] == 2).all() and len(qkv) == 384 // 2
-        r_gu = 4 if batch == 64 else 7
+        r_gu = 7
         assert (gu["c1"] == r_gu).all() and len(gu) == 1792 // r_gu
         for fn, fn_sum in ((7, 15), (9, 16)):
             part, total = l0[l0["fn"] == fn], l0[l0["fn"] == fn_sum]

@@ -71,7 +71,7 @@ typedef enum {
 typedef struct {
     int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn;
     int32_t n_experts, top_k, moe_ffn;
-    int32_t page_size; /* tokens per KV page */
+    int32_t page_size; /* tokens per KV page; a power of two (the paper's workloads use 16) */
     float rms_eps, rope_theta;
     int32_t qk_norm;   /* != 0: per-head RMSNorm of q and k (over head_dim, gains gq / gk, rms_eps) before RoPE: the
                           "Q-Norm + RoPE" and "K-Norm + RoPE + CacheAppend" tasks of Sec. 4.3 (Qwen3-style models) */

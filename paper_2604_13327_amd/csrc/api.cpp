@@ -451,6 +451,7 @@ etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc
     *out = nullptr;
     if (m->n_layers < 1 || m->hidden < 1 || m->n_q_heads < 1 || m->n_kv_heads < 1 || m->page_size < 1)
         return fail(nullptr, ETC_EINVAL, "model dimensions must be positive");
+    if (m->page_size & (m->page_size - 1)) return fail(nullptr, ETC_EINVAL, "page_size must be a power of two");
     if (s->max_batch < 1 || s->max_batch > kMaxBatch) return fail(nullptr, ETC_EINVAL, "max_batch must be in 1..64");
     if (s->max_kv_len < 1) return fail(nullptr, ETC_EINVAL, "max_kv_len must be positive");
     if (t->kv_chunk_tokens < m->page_size || t->kv_chunk_tokens % m->page_size)
@@ -507,6 +508,8 @@ etc_status etc_create(const etc_model_desc *m, const etc_tile_desc *t, const etc
     const size_t MB = (size_t)s->max_batch, H = (size_t)m->hidden, QD = (size_t)m->n_q_heads * m->head_dim;
     P.n_layers = m->n_layers; P.H = m->hidden; P.nq = m->n_q_heads; P.nkv = m->n_kv_heads; P.d = m->head_dim;
     P.F = m->ffn; P.E = m->n_experts; P.topk = m->top_k; P.moeF = m->moe_ffn; P.page = m->page_size;
+    P.page_shift = 0;
+    while ((1 << P.page_shift) < m->page_size) ++P.page_shift;
     P.eps = m->rms_eps; P.theta = m->rope_theta; P.kv_chunk = t->kv_chunk_tokens; P.tile_m = d.tile_m;
     P.qk_norm = m->qk_norm ? 1 : 0;
     P.vocab = d.vocab;

@@ -104,6 +104,7 @@ enum : int32_t { ERR_NONE = 0, ERR_WAIT_TIMEOUT = 1, ERR_QUEUE_OVERFLOW = 2, ERR
 struct Params {
     // model
     int32_t n_layers, H, nq, nkv, d, F, E, topk, moeF, page;
+    int32_t page_shift;                // log2(page): pages hold a power of two of tokens
     float eps, theta;
     const double *rope_inv_freq;       // [d/2] theta^(-2i/d), computed on the host in double
     int32_t kv_chunk, tile_m;

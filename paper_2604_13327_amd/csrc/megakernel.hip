@@ -399,8 +399,8 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
 #define ETC_ATTN(DD, GG)                                                                   \
     if (!ran && P.d == DD && grp == GG) {                                                  \
         ran = true;                                                                        \
-        if (lds_pages) attn_chunk<DD, GG, true>(PL, t.layer, b, kvh, ch, sm, w0, w1);      \
-        else attn_chunk<DD, GG, false>(PL, t.layer, b, kvh, ch, sm, w0, w1);               \
+        if (lds_pages) attn_chunk<DD, GG, true>(PL, t.layer, b, kvh, ch, sm, w0, w1, t.id);      \
+        else attn_chunk<DD, GG, false>(PL, t.layer, b, kvh, ch, sm, w0, w1, t.id);               \
     }
             ETC_ATTN_SHAPES(ETC_ATTN)
 #undef ETC_ATTN

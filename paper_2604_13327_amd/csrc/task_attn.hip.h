@@ -18,8 +18,9 @@ namespace etc {
 // rows do not depend on them: a chunk of one batch requests its rows BEFORE it waits, like a projection task its
 // weights, so that after the wait only the queries are a round trip away (3.72 -> 3.62 ms per 8B step).
 template <int D, int GRP, bool PAGES_IN_LDS>
-__device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int kvh, int ch, float *sm, int ev0, int ev1)
+__device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int kvh, int ch, float *sm, int ev0, int ev1, int task_id)
 {
+    task_id = __builtin_amdgcn_readfirstlane(task_id);
     layer = __builtin_amdgcn_readfirstlane(layer);      // uniform arguments back into scalar registers
     b = __builtin_amdgcn_readfirstlane(b);
     kvh = __builtin_amdgcn_readfirstlane(kvh);
@@ -45,18 +46,24 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
         for (int i = 0; i < D / 16; ++i) s += ld_f32(sp + i);
         return 1.0f / sqrtf(s / (float)D + P.eps);
     };
+    // What the task needs from the tasks before it, requested in ONE round trip behind the wait: the group's queries
+    // (with the sums of squares of their heads on qk_norm models) and, in the sequence's last chunk, the fp32 K / V row
+    // of this step's token.
     float q[GRP][8];
-    auto load_queries = [&]() {
+    auto request_queries = [&]() {
 #pragma unroll
         for (int g = 0; g < GRP; ++g) {
             const float *qp = P.qbuf + (size_t)b * (size_t)(P.nq * D) + (size_t)(kvh * GRP + g) * D + dl * 8;
+#pragma unroll
+            for (int i = 0; i < 8; i += 2) ld_f32x2(qp + i, q[g][i], q[g][i + 1]);
+        }
+    };
+    auto scale_queries = [&]() {
+#pragma unroll
+        for (int g = 0; g < GRP; ++g) {
             const float sc = P.qk_norm ? qscale * head_rnorm(kvh * GRP + g) : qscale;
 #pragma unroll
-            for (int i = 0; i < 8; i += 2) {
-                ld_f32x2(qp + i, q[g][i], q[g][i + 1]);
-                q[g][i] *= sc;
-                q[g][i + 1] *= sc;
-            }
+            for (int i = 0; i < 8; ++i) q[g][i] *= sc;
         }
     };
     float mx[GRP], l[GRP], o[GRP][8];
@@ -71,98 +78,94 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
     // The chunk's slice of the page table goes to LDS first (one round trip, shared with the query loads
     // above); keys are then taken in batches of BATCH wavefront steps: all K and V rows of a batch are
     // requested, then the arithmetic runs, so a batch costs one memory round trip.
-    ETC_AS_LDS int *s_pg = reinterpret_cast<ETC_AS_LDS int *>(as_lds(sm)) + 10240;     // behind the 40 KB of reduction scratch
-    const int pg0 = j0 / P.page, n_pg = (j1 - 1) / P.page - pg0 + 1;
-    constexpr int BATCH = GRP >= 8 ? 2 : 4;       // 8 query heads per KV head leave registers for 2 steps in flight
+    // (The base of the dynamic LDS is a table look-up in a function that is no kernel, and the compiler repeats that
+    // load where the pointer is used: inside the key loop it would drain the K / V loads in flight.  An empty asm
+    // statement makes the value opaque: it is computed once.)
+    uint32_t pg_base = (uint32_t)(uintptr_t)(as_lds(sm) + 10240);                   // behind the 40 KB of reduction scratch
+    asm volatile("" : "+v"(pg_base));
+    ETC_AS_LDS int *s_pg = reinterpret_cast<ETC_AS_LDS int *>(pg_base);
+    const int psh = P.page_shift, pmask = P.page - 1;          // pages hold a power of two of tokens
+    const int pg0 = j0 >> psh, n_pg = ((j1 - 1) >> psh) - pg0 + 1;
+    constexpr int BATCH = GRP >= 8 ? 2 : 4;       // 8 query heads per KV head leave registers for 2 steps per batch
     constexpr int STEP = BATCH * kWaves * TPW;    // keys the workgroup covers per batch
     // requests all K and V rows of the batch that starts at key jb0 (rows beyond the chunk re-read its last key)
-    auto request = [&](int jb0, u32x4 (&krs)[BATCH], u32x4 (&vrs)[BATCH], bool (&val)[BATCH]) {
+    auto request = [&](int jb0, u32x4 (&krs)[BATCH], u32x4 (&vrs)[BATCH]) {
         int page[BATCH], jcs[BATCH];
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
             const int j = jb0 + u * kWaves * TPW + tq;
-            val[u] = j < j1 && j != n_keys - 1;          // the new token is handled after the loop
             jcs[u] = j < j1 ? j : j1 - 1;
-            page[u] = PAGES_IN_LDS ? s_pg[jcs[u] / P.page - pg0] : gld_i32(pages + jcs[u] / P.page);
+            page[u] = PAGES_IN_LDS ? s_pg[(jcs[u] >> psh) - pg0] : gld_i32(pages + (jcs[u] >> psh));
         }
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
-            const size_t off = lbase + (((size_t)page[u] * P.page + (size_t)(jcs[u] % P.page)) * P.nkv + kvh) * (size_t)D + dl * 8;
+            const size_t off = lbase + ((((size_t)page[u] << psh) + (size_t)(jcs[u] & pmask)) * P.nkv + kvh) * (size_t)D + dl * 8;
             krs[u] = gld_16B(P.kpool + off);
             vrs[u] = gld_16B(P.vpool + off);
         }
     };
-    // folds the batch's keys into the running softmax of every query head of the group
-    auto fold = [&](int jb0, const u32x4 (&krs)[BATCH], const u32x4 (&vrs)[BATCH], const bool (&val)[BATCH]) {
+    // Folds the batch's keys into the running softmax of every query head of the group.  The batch is taken as a
+    // whole: all scores first, one new maximum and one rescale of the running sums per head, then the weighted rows
+    // (half the exponentials and multiplies of a key-by-key update).  Keys beyond the chunk, and the new token (it is
+    // handled after the loop, from its fp32 row), get the score -inf, i.e. the weight 0: no branch in here.
+    auto fold = [&](int jb0, const u32x4 (&krs)[BATCH], const u32x4 (&vrs)[BATCH]) {
+        float p[BATCH][GRP];
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
-            if (jb0 + u * kWaves * TPW >= j1) break;     // uniform per wave
-            const bool valid = val[u];
-            const u32x4 kr = krs[u], vr = vrs[u];
-            float kf[8], vf[8];
+            const int j = jb0 + u * kWaves * TPW + tq;
+            const bool valid = j < j1 && j != n_keys - 1;
+            const u32x4 kr = krs[u];
+            float kf[8];
             kf[0] = bf16_bits_to_f32(kr.x & 0xFFFFu); kf[1] = bf16_bits_to_f32(kr.x >> 16);
             kf[2] = bf16_bits_to_f32(kr.y & 0xFFFFu); kf[3] = bf16_bits_to_f32(kr.y >> 16);
             kf[4] = bf16_bits_to_f32(kr.z & 0xFFFFu); kf[5] = bf16_bits_to_f32(kr.z >> 16);
             kf[6] = bf16_bits_to_f32(kr.w & 0xFFFFu); kf[7] = bf16_bits_to_f32(kr.w >> 16);
-            vf[0] = bf16_bits_to_f32(vr.x & 0xFFFFu); vf[1] = bf16_bits_to_f32(vr.x >> 16);
-            vf[2] = bf16_bits_to_f32(vr.y & 0xFFFFu); vf[3] = bf16_bits_to_f32(vr.y >> 16);
-            vf[4] = bf16_bits_to_f32(vr.z & 0xFFFFu); vf[5] = bf16_bits_to_f32(vr.z >> 16);
-            vf[6] = bf16_bits_to_f32(vr.w & 0xFFFFu); vf[7] = bf16_bits_to_f32(vr.w >> 16);
 #pragma unroll
             for (int g = 0; g < GRP; ++g) {
                 float s = 0.f;
 #pragma unroll
                 for (int i = 0; i < 8; ++i) s += q[g][i] * kf[i];
                 s = lanes_sum<LPT>(s);
-                if (valid) {
-                    const float nm = fmaxf(mx[g], s);
-                    const float sc = __expf(mx[g] - nm);      // exp(-inf) = 0 on the first key
-                    const float p = __expf(s - nm);
-                    l[g] = l[g] * sc + p;
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) o[g][i] = o[g][i] * sc + p * vf[i];
-                    mx[g] = nm;
-                }
+                p[u][g] = valid ? s : -INFINITY;
             }
         }
-    };
-    const int jb_first = j0 + wave * TPW;
-    if (PAGES_IN_LDS) {            // long chunks: wait, then the page ids go to LDS and the batches follow
-        wg_wait(P, ev0, ev1, FN_ATTN);
-        load_queries();
-        for (int i = threadIdx.x; i < n_pg; i += kWgThreads) s_pg[i] = gld_i32(pages + pg0 + i);
-        __syncthreads();
-        for (int jb0 = jb_first; jb0 < j1; jb0 += STEP) {         // uniform trip count per wave
-            u32x4 krs[BATCH], vrs[BATCH];
-            bool val[BATCH];
-            request(jb0, krs, vrs, val);
-            fold(jb0, krs, vrs, val);
-        }
-    } else {                       // chunks of (about) one batch: its rows are requested before the wait
-        u32x4 krs[BATCH], vrs[BATCH];
-        bool val[BATCH];
-        const bool first = jb_first < j1;                          // uniform per wave
-        if (first) request(jb_first, krs, vrs, val);
-        wg_wait(P, ev0, ev1, FN_ATTN);
-        load_queries();
-        if (first) fold(jb_first, krs, vrs, val);
-        for (int jb0 = jb_first + STEP; jb0 < j1; jb0 += STEP) {
-            request(jb0, krs, vrs, val);
-            fold(jb0, krs, vrs, val);
-        }
-    }
-
-    // the token of this step (last key of the last chunk): fp32 row from the projection tasks; the key
-    // group tq == 0 of wavefront 0 folds it into its running softmax
-    if (j1 == n_keys && wave == 0) {
-        const float *kn = P.knew + ((size_t)b * P.nkv + kvh) * (size_t)D + dl * 8;
-        const float *vn = P.vnew + ((size_t)b * P.nkv + kvh) * (size_t)D + dl * 8;
-        float kf[8], vf[8];
 #pragma unroll
-        for (int i = 0; i < 8; i += 2) {
-            ld_f32x2(kn + i, kf[i], kf[i + 1]);
-            ld_f32x2(vn + i, vf[i], vf[i + 1]);
+        for (int g = 0; g < GRP; ++g) {
+            float nm = mx[g];
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) nm = fmaxf(nm, p[u][g]);
+            const float ref = fmaxf(nm, -1e30f);           // nothing seen yet: exp(-inf - ref) = 0 instead of exp(nan)
+            const float sc = __expf(mx[g] - ref);
+            float ls = l[g] * sc;
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                p[u][g] = __expf(p[u][g] - ref);
+                ls += p[u][g];
+            }
+            l[g] = ls;
+            mx[g] = nm;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) o[g][i] *= sc;
         }
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const u32x4 vr = vrs[u];
+            float vf[8];
+            vf[0] = bf16_bits_to_f32(vr.x & 0xFFFFu); vf[1] = bf16_bits_to_f32(vr.x >> 16);
+            vf[2] = bf16_bits_to_f32(vr.y & 0xFFFFu); vf[3] = bf16_bits_to_f32(vr.y >> 16);
+            vf[4] = bf16_bits_to_f32(vr.z & 0xFFFFu); vf[5] = bf16_bits_to_f32(vr.z >> 16);
+            vf[6] = bf16_bits_to_f32(vr.w & 0xFFFFu); vf[7] = bf16_bits_to_f32(vr.w >> 16);
+#pragma unroll
+            for (int g = 0; g < GRP; ++g)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) o[g][i] += p[u][g] * vf[i];
+        }
+    };
+    // The token of this step (last key of the sequence's last chunk) enters the running softmax FIRST, from the fp32 row
+    // the projection tasks left: key group tq == 0 of wavefront 0 takes it.  Its loads share the queries' round trip;
+    // at the end of the task they would be a round trip of their own.
+    const bool takes_new = j1 == n_keys && wave == 0;            // uniform per wave
+    auto fold_new_token = [&](float (&kf)[8], const float (&vf)[8]) {
         if (P.qk_norm) {       // K-Norm + RoPE + CacheAppend (Sec. 4.3): the key's norm is complete here, and so is its cache row
             const float rk = head_rnorm(P.nq + kvh);
 #pragma unroll
@@ -178,21 +181,68 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
         }
 #pragma unroll
         for (int g = 0; g < GRP; ++g) {
-            float s = 0.f;
+            float sc = 0.f;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) s += q[g][i] * kf[i];
-            s = lanes_sum<LPT>(s);
-            if (tq == 0) {
-                const float nm = fmaxf(mx[g], s);
-                const float sc = __expf(mx[g] - nm);
-                const float p = __expf(s - nm);
-                l[g] = l[g] * sc + p;
+            for (int i = 0; i < 8; ++i) sc += q[g][i] * kf[i];
+            sc = lanes_sum<LPT>(sc);
+            if (tq == 0) {         // the first key of this group's running softmax: weight exp(0) = 1
+                mx[g] = sc;
+                l[g] = 1.f;
 #pragma unroll
-                for (int i = 0; i < 8; ++i) o[g][i] = o[g][i] * sc + p * vf[i];
-                mx[g] = nm;
+                for (int i = 0; i < 8; ++i) o[g][i] = vf[i];
             }
         }
+    };
+    auto after_wait = [&]() {      // queries and the new token: one round trip
+        trace_mark(P, task_id, 1);
+        request_queries();
+        float kf[8], vf[8];
+        if (takes_new) {
+            const float *kn = P.knew + ((size_t)b * P.nkv + kvh) * (size_t)D + dl * 8;
+            const float *vn = P.vnew + ((size_t)b * P.nkv + kvh) * (size_t)D + dl * 8;
+#pragma unroll
+            for (int i = 0; i < 8; i += 2) {
+                ld_f32x2(kn + i, kf[i], kf[i + 1]);
+                ld_f32x2(vn + i, vf[i], vf[i + 1]);
+            }
+        }
+        scale_queries();
+        if (takes_new) fold_new_token(kf, vf);
+    };
+    const int jb_first = j0 + wave * TPW;
+    // Page ids and cached K / V rows are inputs of the step, not results of its tasks: the chunk's slice of the page
+    // table and the rows of the first batch are requested BEFORE the wait, like a projection task's first weights.
+    if (PAGES_IN_LDS) {            // long chunks: the page ids go through LDS
+        for (int i = threadIdx.x; i < n_pg; i += kWgThreads) s_pg[i] = gld_i32(pages + pg0 + i);
+        __syncthreads();
+        u32x4 ka[BATCH], va[BATCH];
+        request(jb_first, ka, va);
+        wg_wait(P, ev0, ev1, FN_ATTN);
+        after_wait();
+        // two batches in flight: while one is folded the next one's rows are on their way (requests beyond the chunk
+        // re-read its last key and fold to nothing, so the loop has no conditions)
+        u32x4 kb[BATCH], vb[BATCH];
+        drain_vmem();      // everything has arrived behind the queries anyway; tells the compiler so, or it drains at the loop's top
+        for (int jb0 = jb_first; jb0 < j1; jb0 += 2 * STEP) {     // uniform trip count per wave
+            request(jb0 + STEP, kb, vb);
+            fold(jb0, ka, va);
+            __builtin_amdgcn_sched_barrier(0);     // the refill lands in the registers the fold has just read: no copies,
+            request(jb0 + 2 * STEP, ka, va);       // so the loop's end does not wait for it
+            fold(jb0 + STEP, kb, vb);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else {                       // chunks of (about) one batch
+        u32x4 krs[BATCH], vrs[BATCH];
+        request(jb_first, krs, vrs);
+        wg_wait(P, ev0, ev1, FN_ATTN);
+        after_wait();
+        fold(jb_first, krs, vrs);
+        for (int jb0 = jb_first + STEP; jb0 < j1; jb0 += STEP) {
+            request(jb0, krs, vrs);
+            fold(jb0, krs, vrs);
+        }
     }
+    trace_mark(P, task_id, 2);
 
     // merge the TPW key groups of the wavefront (lanes differing in tq)
 #pragma unroll
@@ -225,6 +275,10 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
         }
     }
     __syncthreads();
+    // A sequence that is one chunk long needs no partial results, no arrival count and no merge: what a merge of one
+    // chunk would compute is exactly num / den below (three memory round trips less at the end of the task).
+    const int nc = (n_keys + P.kv_chunk - 1) / P.kv_chunk;
+    const bool whole = nc == 1 && P.attn_arrive != nullptr;
     for (int idx = threadIdx.x; idx < GRP * D; idx += kWgThreads) {
         const int g = idx / D, i = idx % D;
         float m = -INFINITY;
@@ -239,26 +293,31 @@ __device__ __noinline__ void attn_chunk(const Params &P, int layer, int b, int k
             den += sc * s_l[wv * GRP + g];
         }
         const int h = kvh * GRP + g;
-        const size_t pidx = ((size_t)b * P.nq + h) * (size_t)P.max_chunks + ch;
-        st_f32(P.part_o + pidx * D + i, num);
-        if (i == 0) { st_f32(P.part_m + pidx, m); st_f32(P.part_l + pidx, den); }
+        if (whole) {               // the sequence's only chunk: this is the attention output (operand of the O projection)
+            uint16_t hi, lo;
+            split_bf16(num / den, hi, lo);
+            const size_t o1 = (size_t)b * (size_t)(P.nq * D) + (size_t)h * D + i;
+            st_u16(P.attn_hi + o1, hi);
+            st_u16(P.attn_lo + o1, lo);
+        } else {
+            const size_t pidx = ((size_t)b * P.nq + h) * (size_t)P.max_chunks + ch;
+            st_f32(P.part_o + pidx * D + i, num);
+            if (i == 0) { st_f32(P.part_m + pidx, m); st_f32(P.part_l + pidx, den); }
+        }
     }
     // The chunk task that arrives last at its (sequence, KV head) merges the chunks itself: the merge is no stage of
     // its own, one all-to-all hand-over less per layer.  Arrival is counted with one returning atomic per task (behind
     // the drain of the partial results); the last one puts the counter back for the next launch.  Every chunk task
     // still notifies the one event of the attention block, the merging one after its merge.
-    if (P.attn_arrive != nullptr) {
-        const int nc = (n_keys + P.kv_chunk - 1) / P.kv_chunk;
+    trace_mark(P, task_id, 3);
+    if (P.attn_arrive != nullptr && !whole) {
         ETC_AS_LDS int32_t *s_last = reinterpret_cast<ETC_AS_LDS int32_t *>(s_o + (size_t)kWaves * GRP * D);
         drain_vmem();
         __syncthreads();
         if (threadIdx.x == 0) {
-            int last = 1;
-            if (nc > 1) {
-                int32_t *ctr = P.attn_arrive + (size_t)b * P.nkv + kvh;
-                last = __hip_atomic_fetch_add(as_global(ctr), 1, __ATOMIC_RELAXED, ETC_SCOPE) + 1 == nc;
-                if (last) st_i32(ctr, 0);
-            }
+            int32_t *ctr = P.attn_arrive + (size_t)b * P.nkv + kvh;
+            const int last = __hip_atomic_fetch_add(as_global(ctr), 1, __ATOMIC_RELAXED, ETC_SCOPE) + 1 == nc;
+            if (last) st_i32(ctr, 0);
             *s_last = last;
         }
         __syncthreads();

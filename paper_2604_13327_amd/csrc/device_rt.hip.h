@@ -120,6 +120,10 @@ __device__ __forceinline__ u32x4 ld_16B(const void *p)      // 16 bytes as two 8
 }
 __device__ __forceinline__ void st_f32(float *p, float v) { __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, ETC_SCOPE); }
 __device__ __forceinline__ void st_i32(int32_t *p, int v) { __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, ETC_SCOPE); }
+__device__ __forceinline__ void st_u64(void *p, uint64_t v)
+{
+    __hip_atomic_store(as_global(reinterpret_cast<uint64_t *>(p)), v, __ATOMIC_RELAXED, ETC_SCOPE);
+}
 __device__ __forceinline__ void st_u16(uint16_t *p, uint16_t v) { __hip_atomic_store(as_global(p), v, __ATOMIC_RELAXED, ETC_SCOPE); }
 
 __device__ __forceinline__ int ev_peek(const int32_t *p) { return ld_i32(p); }

@@ -395,12 +395,19 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
             st.staged_key = -1;      // the attention scratch overlaps the staged operand (the task waits inside)
             const int grp = P.nq / P.nkv;
             const bool lds_pages = P.kv_chunk > 128;      // more than one batch of keys per chunk
+            const bool mfma_fits = (P.kv_chunk >> P.page_shift) <= 8192;      // page ids of a chunk next to the wavefronts' V tiles in LDS
             bool ran = false;
 #define ETC_ATTN(DD, GG)                                                                   \
     if (!ran && P.d == DD && grp == GG) {                                                  \
         ran = true;                                                                        \
-        if (lds_pages) attn_chunk<DD, GG, true>(PL, t.layer, b, kvh, ch, sm, w0, w1, t.id);      \
-        else attn_chunk<DD, GG, false>(PL, t.layer, b, kvh, ch, sm, w0, w1, t.id);               \
+        if constexpr (DD == 128 && GG == 8) {                                              \
+            if (lds_pages && mfma_fits) attn_chunk_mfma<GG>(PL, t.layer, b, kvh, ch, sm, w0, w1, t.id);   \
+            else if (lds_pages) attn_chunk<DD, GG, true>(PL, t.layer, b, kvh, ch, sm, w0, w1, t.id);       \
+            else attn_chunk<DD, GG, false>(PL, t.layer, b, kvh, ch, sm, w0, w1, t.id);     \
+        } else {                                                                           \
+            if (lds_pages) attn_chunk<DD, GG, true>(PL, t.layer, b, kvh, ch, sm, w0, w1, t.id);  \
+            else attn_chunk<DD, GG, false>(PL, t.layer, b, kvh, ch, sm, w0, w1, t.id);     \
+        }                                                                                  \
     }
             ETC_ATTN_SHAPES(ETC_ATTN)
 #undef ETC_ATTN

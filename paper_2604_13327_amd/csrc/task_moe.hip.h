@@ -297,10 +297,6 @@ __device__ __noinline__ void moe_route_and_group(const Params &P, int layer, int
 // ---------------------------------------------------------------------------------------------------------
 constexpr int kMoelBlock = 64;
 
-__device__ __forceinline__ void st_u64(void *p, uint64_t v)
-{
-    __hip_atomic_store(as_global(reinterpret_cast<uint64_t *>(p)), v, __ATOMIC_RELAXED, ETC_SCOPE);
-}
 
 // 16 tokens: x_in (bf16) -> residual stream fp32, (x * gain) split into hi + lo, per-16-element sums of squares.
 // A lane takes 8 consecutive elements (one 16-byte load), two neighbouring lanes one 16-element part.

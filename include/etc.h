@@ -305,16 +305,32 @@ typedef struct {
 typedef enum {
     ETC_FN_ROWSUM_PARTIAL = 1, /* task (i, j): B[32i..32i+32, j] = sum_k A[rows, 32j..32j+32) */
     ETC_FN_ROWSUM_FINAL = 2,   /* task (i):    C[32i..32i+32]    = sum_j B[rows, j], j < 4 */
-    ETC_FN_ROWSUM_FINAL_PERM = 3 /* task (t): the same for row block perm[t] (slot 6), t < indptr[events]; for grids
+    ETC_FN_ROWSUM_FINAL_PERM = 3, /* task (t): the same for row block perm[t] (slot 6), t < indptr[events]; for grids
                                     released through ETC_MAP_INDPTR (row blocks grouped by their event) */
+    ETC_FN_USER0 = 100         /* ETC_FN_USER0 + k: device function k of a GENERATED library (see below); the stock
+                                    library has none and refuses these ids */
 } etc_device_fn;
+
+/* Generated dispatch (Alg. 1 and Alg. 2 read as compiler passes; Sec. 3).  The front end
+ * (paper_2604_13327_amd/frontend.py) takes a graph description: shape symbols, event tensors, and calls of device
+ * functions the user writes as HIP source `(const Args &a, int c0, int c1, int c2)`, one call per task of the grid.
+ * It GENERATES a header with those functions and the switch that dispatches a task record to them, and builds a
+ * library from this library's sources around that header (only the generic kernel instance: no decoder).  The result
+ * exports this same C ABI; its etc_graph_add_call accepts ETC_FN_USER0 + k for the k-th function of the description.
+ * Task lists (static queues, Alg. 1) and consumer tables (dynamic, Alg. 2) come from etc_graph_bind_shape as for the
+ * built-in functions; symbols are bound at run time without rebuilding.  Device functions get the bound buffers
+ * (slots 0..7 of etc_graph_bind_buffer) and symbol values; whether the buffers are large enough for a bound shape is
+ * checked by the front end, which knows what the functions touch: the library cannot.
+ * etc_graph_user_fn_count: how many generated device functions this library carries (0: the stock library). */
+etc_status etc_graph_user_fn_count(int32_t *count);
 
 etc_status etc_graph_create(const etc_sched_desc *sched, etc_ctx **out);
 etc_status etc_graph_add_event(etc_ctx *ctx, const etc_dim_expr *shape, int32_t rank, int32_t *event_id);
 etc_status etc_graph_add_call(etc_ctx *ctx, int32_t device_fn, const etc_dim_expr *task_shape, int32_t rank,
                               const etc_edge *in_edges, int32_t n_in, const etc_edge *out_edges, int32_t n_out);
 /* Buffers of the device functions: slot 0 = A (fp32 [n*32, 128]), 1 = B (fp32 [n*32, 4]), 2 = C (fp32 [n*32]);
- * run-time tables (int32): 3 = table of an INDIRECT edge, 4 = indptr, 5 = count, 6 = perm.
+ * run-time tables (int32): 3 = table of an INDIRECT edge, 4 = indptr, 5 = count, 6 = perm.  Generated device functions
+ * may use slots 0..7 as they like (3..5 keep their meaning when the graph has data-dependent edges).
  * bytes = size of the allocation, checked against the bound shape at launch. */
 etc_status etc_graph_bind_buffer(etc_ctx *ctx, int32_t slot, void *device_ptr, size_t bytes);
 /* Instantiates the template for concrete symbol values (values[4], host). */

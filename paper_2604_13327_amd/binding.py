@@ -26,7 +26,7 @@ EXPORTS = ["etc_create", "etc_destroy", "etc_last_error", "etc_bind_layer_weight
            "etc_moe_layer_create", "etc_moe_layer_bind_tokens", "etc_moe_layer_plan_build",
            "etc_get_step_info", "etc_graph_create", "etc_graph_add_event", "etc_graph_add_call",
            "etc_graph_bind_buffer", "etc_graph_bind_shape", "etc_graph_launch", "etc_plan_build", "etc_plan_free",
-           "etc_rowsum_launch_noalloc"]
+           "etc_rowsum_launch_noalloc", "etc_graph_user_fn_count"]
 ROWSUM_NOALLOC_MAX_N = 2048
 
 
@@ -93,12 +93,16 @@ def lib_path() -> str:
     return os.path.join(_HERE, "libetc.so")
 
 
-@functools.lru_cache(maxsize=1)
 def lib():
     """Loads libetc.so.  torch is imported first so that the HIP runtime torch ships is the one
     the library binds to (a second HIP runtime in the process would not know torch's allocations)."""
+    return load_library(lib_path())
+
+
+@functools.lru_cache(maxsize=None)
+def load_library(path: str):
+    """Loads a library that exports the C ABI of include/etc.h: libetc.so, or one the front end generated for a graph."""
     import torch  # noqa: F401
-    path = lib_path()
     if not os.path.exists(path):
         raise ImportError(f"{path} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` first "
                           "(there is no fallback path)")
@@ -138,6 +142,7 @@ def lib():
                                  C.POINTER(PlanView)]
     L.etc_plan_free.argtypes = [C.POINTER(PlanView)]
     L.etc_rowsum_launch_noalloc.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+    L.etc_graph_user_fn_count.argtypes = [C.POINTER(C.c_int32)]
     return L
 
 
@@ -203,8 +208,8 @@ def moe_layer_plan_build(shape, sampled_tokens, n_queues, kind=SCHED_STATIC, moe
 
 
 class _Ctx:
-    def __init__(self):
-        self._L = lib()
+    def __init__(self, library: str = None):
+        self._L = lib() if library is None else load_library(library)
         self._h = C.c_void_p()
 
     def _check(self, st: int):
@@ -368,8 +373,9 @@ class MoeLayer(Decoder):
 class EventGraph(_Ctx):
     """Generic event-tensor graph (row-sum example of the paper's Sec. 2.2)."""
 
-    def __init__(self, kind: int = SCHED_STATIC, debug_flags: int = 0, spin_budget: int = 0, n_queues: int = 0):
-        super().__init__()
+    def __init__(self, kind: int = SCHED_STATIC, debug_flags: int = 0, spin_budget: int = 0, n_queues: int = 0,
+                 library: str = None):
+        super().__init__(library)
         sd = _sched_desc(kind, [1], 1, debug_flags, spin_budget, n_queues)
         st = self._L.etc_graph_create(C.byref(sd), C.byref(self._h))
         if st != 0:

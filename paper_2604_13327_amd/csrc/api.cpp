@@ -21,6 +21,7 @@ hipError_t launch_static(const Params &P, hipStream_t s);
 hipError_t launch_dynamic(const Params &P, hipStream_t s);
 hipError_t launch_stage(const Params &P, int first, int count, hipStream_t s);
 hipError_t launch_rowsum_noalloc(const float *A, float *C, int n, hipStream_t s);
+int user_fn_count();
 hipError_t launch_arm(const ArmArgs &a, hipStream_t s);
 }  // namespace etc
 
@@ -1026,12 +1027,14 @@ etc_status etc_graph_add_call(etc_ctx *c, int32_t fn, const etc_dim_expr *shape,
                               int32_t n_in, const etc_edge *outs, int32_t n_out)
 {
     if (!c || !c->is_graph || !shape || rank < 1 || rank > 3) return fail(c, ETC_EINVAL, "bad argument");
-    if (fn != ETC_FN_ROWSUM_PARTIAL && fn != ETC_FN_ROWSUM_FINAL && fn != ETC_FN_ROWSUM_FINAL_PERM)
-        return fail(c, ETC_EINVAL, "unknown device function");
+    const bool user_fn = fn >= ETC_FN_USER0 && fn - ETC_FN_USER0 < user_fn_count();      // generated libraries only
+    if (!user_fn && fn != ETC_FN_ROWSUM_PARTIAL && fn != ETC_FN_ROWSUM_FINAL && fn != ETC_FN_ROWSUM_FINAL_PERM)
+        return fail(c, ETC_EINVAL, fn >= ETC_FN_USER0 ? "this library was not generated with that many device functions" : "unknown device function");
     if (n_in < 0 || n_in > 2 || n_out < 0 || n_out > 1 || (n_in && !in) || (n_out && !outs))
         return fail(c, ETC_EINVAL, "a call takes at most 2 in-edges and 1 out-edge");
     CallDecl cd;
-    cd.fn = fn == ETC_FN_ROWSUM_PARTIAL ? FN_ROWSUM_PARTIAL : fn == ETC_FN_ROWSUM_FINAL ? FN_ROWSUM_FINAL : FN_ROWSUM_FINAL_PERM;
+    cd.fn = user_fn ? FN_USER0 + (fn - ETC_FN_USER0)
+                    : fn == ETC_FN_ROWSUM_PARTIAL ? FN_ROWSUM_PARTIAL : fn == ETC_FN_ROWSUM_FINAL ? FN_ROWSUM_FINAL : FN_ROWSUM_FINAL_PERM;
     cd.rank = rank;
     cd.stage = (int)c->graph.calls.size();
     for (int r = 0; r < rank; ++r) cd.shape[r] = DimExpr{shape[r].sym, shape[r].mul, shape[r].add};
@@ -1063,9 +1066,16 @@ etc_status etc_graph_add_call(etc_ctx *c, int32_t fn, const etc_dim_expr *shape,
     return ETC_OK;
 }
 
+etc_status etc_graph_user_fn_count(int32_t *count)
+{
+    if (!count) return fail(nullptr, ETC_EINVAL, "NULL argument");
+    *count = user_fn_count();
+    return ETC_OK;
+}
+
 etc_status etc_graph_bind_buffer(etc_ctx *c, int32_t slot, void *ptr, size_t bytes)
 {
-    if (!c || !c->is_graph || slot < 0 || slot > 6 || !ptr) return fail(c, ETC_EINVAL, "bad argument");
+    if (!c || !c->is_graph || slot < 0 || slot > 7 || !ptr) return fail(c, ETC_EINVAL, "bad argument");
     c->base.gbuf[slot] = (float *)ptr;
     c->gbuf_bytes[slot] = bytes;
     return ETC_OK;
@@ -1124,7 +1134,9 @@ etc_status etc_graph_launch(etc_ctx *c, void *hip_stream)
     // the task grids must stay inside the bound buffers: A (rows, 128), B (rows, 4), C (rows), 32 rows per task
     for (const CallDecl &cd : c->graph.calls) {
         const size_t rows = (size_t)32 * (size_t)cd.shape[0].eval(c->sym_values);
-        if (cd.fn == FN_ROWSUM_PARTIAL) {
+        if (cd.fn >= FN_USER0) {
+            // generated device functions: the front end that generated them checks their buffers against the bound shape
+        } else if (cd.fn == FN_ROWSUM_PARTIAL) {
             if (cd.rank != 2 || cd.shape[1].eval(c->sym_values) > 4) return fail(c, ETC_EINVAL, "partial_sum takes a (n, <=4) grid");
             if (rows * 128 * 4 > c->gbuf_bytes[0] || rows * 4 * 4 > c->gbuf_bytes[1]) return fail(c, ETC_EINVAL, "buffer A or B too small for the bound shape");
         } else if (cd.fn == FN_ROWSUM_FINAL) {

@@ -42,6 +42,7 @@ enum Fn : uint8_t {
     FN_NOP = 0,
     FN_ROWSUM_PARTIAL = 1,
     FN_ROWSUM_FINAL = 2,
+    FN_USER0 = 100,              // generic graphs: first device function of a generated dispatch switch (front end)
     FN_ROWSUM_FINAL_PERM = 17,   // generic graphs: final sum of row block perm[task], tasks beyond indptr[last] do nothing
     FN_LOAD_HIDDEN = 3,   // hidden_in bf16 -> residual stream fp32
     FN_QKV = 4,           // RMSNorm prologue, 16 rows of Wq|Wk|Wv (8 RoPE pairs), RoPE, KV append

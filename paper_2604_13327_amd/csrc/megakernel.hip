@@ -14,7 +14,21 @@
 #include "task_gemm.hip.h"
 #include "task_moe.hip.h"
 
+// Generated dispatch (paper Alg. 1 / Alg. 2 as a front end): a library built from a graph description carries the
+// device functions of that graph and the switch over them in a generated header; this build includes it here.  The
+// stock library has none.
+#ifdef ETC_USER_DISPATCH_HEADER
+#include ETC_USER_DISPATCH_HEADER
+#else
 namespace etc {
+constexpr int kUserFnCount = 0;
+__device__ __forceinline__ void user_dispatch(const Params &, int, int, int, int) {}
+}  // namespace etc
+#endif
+
+namespace etc {
+
+int user_fn_count() { return kUserFnCount; }
 
 // ---------------------------------------------------------------------------------------------
 // small task bodies
@@ -370,6 +384,7 @@ __device__ __forceinline__ void run_task(const Params &P, const Params &PL, cons
         if (t.fn == FN_ROWSUM_PARTIAL) rowsum_partial(P, t.c0, t.c1);
         else if (t.fn == FN_ROWSUM_FINAL) rowsum_final(P, t.c0);
         else if (t.fn == FN_ROWSUM_FINAL_PERM) rowsum_final_perm(P, t.c0);
+        else if (t.fn >= FN_USER0) user_dispatch(P, t.fn - FN_USER0, t.c0, t.c1, t.c2);
         return;
     }
     switch (t.fn) {
@@ -867,12 +882,16 @@ namespace etc {
 
 hipError_t configure_kernels()
 {
+#ifdef ETC_GENERIC_ONLY
+    const void *kernels[] = {(const void *)megakernel_static<0>, (const void *)megakernel_dynamic<0>, (const void *)stage_kernel<0>};
+#else
     const void *kernels[] = {(const void *)megakernel_static<0>, (const void *)megakernel_static<1>, (const void *)megakernel_static<2>,
                              (const void *)megakernel_static<3>, (const void *)megakernel_static<4>,
                              (const void *)megakernel_dynamic<0>, (const void *)megakernel_dynamic<1>, (const void *)megakernel_dynamic<2>,
                              (const void *)megakernel_dynamic<3>, (const void *)megakernel_dynamic<4>,
                              (const void *)stage_kernel<0>, (const void *)stage_kernel<1>, (const void *)stage_kernel<2>,
                              (const void *)stage_kernel<3>, (const void *)stage_kernel<4>};
+#endif
     for (const void *k : kernels) {
         hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;
@@ -882,7 +901,11 @@ hipError_t configure_kernels()
 
 hipError_t max_resident_workgroups(int *per_cu)
 {
+#ifdef ETC_GENERIC_ONLY
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, (const void *)megakernel_static<KIND_GENERIC>, kWgThreads, kLdsBytes);
+#else
     return hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, (const void *)megakernel_static<KIND_MOE>, kWgThreads, kLdsBytes);
+#endif
 }
 
 // generic graph contexts carry no model; decoders are dense (small-batch plans: the staged-only instance) or MoE
@@ -895,6 +918,11 @@ static int kind_of(const Params &P)
     return ((P.k_slices_o > 0 || P.k_slices_d > 0) ? KIND_DENSE_STAGED_K : KIND_DENSE_STAGED) | lm;
 }
 
+#ifdef ETC_GENERIC_ONLY      // a library generated for one graph: no decoder instances (they are most of the compile time)
+#define ETC_LAUNCH_KIND(KERNEL, GRID, ...)                                                                          \
+    if (kind_of(P) != KIND_GENERIC) return hipErrorInvalidDeviceFunction;                                          \
+    hipLaunchKernelGGL(KERNEL<KIND_GENERIC>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__);
+#else
 #define ETC_LAUNCH_KIND(KERNEL, GRID, ...)                                                                          \
     switch (kind_of(P)) {                                                                                          \
     case KIND_GENERIC: hipLaunchKernelGGL(KERNEL<KIND_GENERIC>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break; \
@@ -907,6 +935,7 @@ static int kind_of(const Params &P)
     case KIND_DENSE_STAGED_K | KIND_LM: hipLaunchKernelGGL(KERNEL<KIND_DENSE_STAGED_K | KIND_LM>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break; \
     default: hipLaunchKernelGGL(KERNEL<KIND_MOE | KIND_LM>, GRID, dim3(kWgThreads), kLdsBytes, s, __VA_ARGS__); break;     \
     }
+#endif
 
 hipError_t launch_static(const Params &P, hipStream_t s)
 {

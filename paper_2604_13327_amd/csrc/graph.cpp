@@ -248,7 +248,7 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
             // bytes a queue moves through the stage: rounds x (r row tiles of weights + one pass over the operand)
             const long long tile_bytes = 16LL * m.H * 2, operand_bytes = (long long)Bs * m.H * 4;
             long long best = -1;
-            for (int r = 1; r <= pass_tiles_for(Bs); ++r) {
+            for (int r = 1; r <= wide_pass_tiles_for(Bs); ++r) {
                 if (per_slice % r) continue;
                 const long long rounds = (tiles / r + n_queues - 1) / n_queues, cost = rounds * (r * tile_bytes + operand_bytes);
                 if (best < 0 || cost <= best) { best = cost; r_gu = r; }
@@ -256,8 +256,9 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
         }
     }
     const int n_ht = m.H / 16, pass_tiles = pass_tiles_for(Bs);
-    const bool slice_o = g.k_slices_o > 0 && n_ht % pass_tiles == 0;
-    const bool slice_d = g.k_slices_d > 0 && n_ht % pass_tiles == 0;
+    const int pass_o = sliced_pass_tiles(Bs, n_ht, g.k_slices_o, n_queues), pass_d = sliced_pass_tiles(Bs, n_ht, g.k_slices_d, n_queues);
+    const bool slice_o = g.k_slices_o > 0 && n_ht % pass_o == 0;
+    const bool slice_d = g.k_slices_d > 0 && n_ht % pass_d == 0;
     if (!slice_o) g.k_slices_o = 0;
     if (!slice_d) g.k_slices_d = 0;
     g.all_staged = m.E == 0 && staged_fits(r_qkv, Bs, m.H) && staged_fits(r_gu, Bs, m.H) &&
@@ -312,8 +313,8 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
             const int e_opart = g.add_event({one});
             CallDecl c;
             c.fn = FN_OPROJ; c.layer = l; c.stage = stage++;      // task record: (first row tile, K slice, tiles)
-            c.rank = 2; c.shape[0] = dim_const(n_ht / pass_tiles); c.shape[1] = dim_const(g.k_slices_o);
-            c.c_mul[0] = pass_tiles; c.c_fill[2] = pass_tiles;
+            c.rank = 2; c.shape[0] = dim_const(n_ht / pass_o); c.shape[1] = dim_const(g.k_slices_o);
+            c.c_mul[0] = pass_o; c.c_fill[2] = pass_o;
             c.flags = TF_K_SLICE;
             c.in = {edge_const0(e_attn)};
             c.out = {edge_const0(e_opart)};
@@ -350,8 +351,8 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
                 const int e_dpart = g.add_event({one});
                 CallDecl c;
                 c.fn = FN_DOWN; c.layer = l; c.stage = stage++;      // task record: (first row tile, K slice, tiles)
-                c.rank = 2; c.shape[0] = dim_const(n_ht / pass_tiles); c.shape[1] = dim_const(g.k_slices_d);
-                c.c_mul[0] = pass_tiles; c.c_fill[2] = pass_tiles;
+                c.rank = 2; c.shape[0] = dim_const(n_ht / pass_d); c.shape[1] = dim_const(g.k_slices_d);
+                c.c_mul[0] = pass_d; c.c_fill[2] = pass_d;
                 c.flags = TF_K_SLICE;
                 c.in = {edge_dim(e_act, 1)};                    // only the activations of its own K slice
                 c.out = {edge_const0(e_dpart)};

@@ -119,6 +119,14 @@ inline int effective_kv_chunk(int min_chunk, int page, int max_kv_len, int batch
 // Row tiles a large-batch projection task streams against one pass over its operand: 8.  (Above 32 columns the
 // K-split chunked path holds accumulators for 4 tiles at most; such tasks take the wide path, one tile per wavefront.)
 inline int pass_tiles_for(int batch) { (void)batch; return 8; }
+// Above 16 columns the wide path takes two row tiles per wavefront: 16 tiles against one pass over the operand.  A
+// projection uses that where it still leaves every queue a task: gate/up by its cost per queue (fewer rounds, each
+// with one more operand pass), a projection cut along K when (row tiles / 16) x slices fill the queues.
+inline int wide_pass_tiles_for(int batch) { return batch > 16 ? 16 : 8; }
+inline int sliced_pass_tiles(int batch, int row_tiles, int slices, int n_queues)
+{
+    return (batch > 16 && slices > 0 && row_tiles % 16 == 0 && (row_tiles / 16) * slices >= n_queues) ? 16 : 8;
+}
 
 // Slices of K for a projection of a large batch: the most of 8, 4, 2 that keep a slice a multiple of the
 // 256 elements one pass of the 8 wavefronts covers; 0 when K is too short to slice.

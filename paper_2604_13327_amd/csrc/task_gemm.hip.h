@@ -701,13 +701,15 @@ __device__ __noinline__ void gemm_tiles_chunked(const Params &P, const ChunkedAr
         __hip_atomic_fetch_max(as_global(P.best + threadIdx.x), lbest[threadIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Wide path: 64-column tasks with many row tiles (the GroupGEMMs of a stand-alone MoE layer from about a thousand tokens
-// on).  The chunked path splits K over the 8 wavefronts, so every wavefront holds accumulators for all tiles of the pass
-// and a pass is 4 tiles: the 64-column operand (hi and lo: 512 KB at K = 2048) is read again for every 256 KB of
-// weights.  Here the wavefronts split the OUTPUT instead: each owns TW row tiles of the pass and runs over all of K, the
-// operand chunk in LDS is shared by all of them, and a pass is 8 x TW tiles: a quarter (TW = 2) of the operand reads.
-// No reduction across wavefronts; the accumulators go through LDS once, into the layout the epilogue threads read.
-template <int TW>
+// Wide path: tasks of 5 or more row tiles at any column count (16 * NB columns).  The chunked path splits K over the 8
+// wavefronts, so every wavefront holds accumulators for all tiles of the pass (at 64 columns a pass is 4 tiles: the
+// operand, hi and lo, is read again for every 256 KB of weights) and the tiles meet in a reduction across wavefronts.
+// Here the wavefronts split the OUTPUT instead: each owns TW row tiles of the pass and runs over all of K, the operand
+// chunk in LDS is shared by all of them, and a pass is 8 x TW tiles.  No reduction across wavefronts; the accumulators
+// go through LDS once, into the layout the epilogue threads read.  Measured against the chunked path on whole decode
+// steps (8B shape): batch 16 7.30 -> 6.45 ms, batch 32 8.59 -> 7.57 ms, batch 64 14.0 -> 10.9 ms; 70B shape, batch 32,
+// with 14 - 16 tiles per task (TW = 2, one task per queue instead of two): 58.1 -> 48.4 ms.
+template <int TW, int NB>
 __device__ __noinline__ void gemm_tiles_wide(const Params &P, const ChunkedArgs *args, float *sm, int *frame_anchor)
 {
     const ChunkedArgs a = lds_get_uniform(args);
@@ -716,11 +718,11 @@ __device__ __noinline__ void gemm_tiles_wide(const Params &P, const ChunkedArgs 
     const Epilogue &e = a.e;
     const TaskWaits &w = a.w;
     const int task_id = a.task_id;
-    constexpr int NB = 4, COLS = 64, KC = 256, STRIDE = KC + 8, PPC = KC / 4, U = COLS * PPC / kWgThreads;
+    constexpr int COLS = 16 * NB, KC = 256, STRIDE = KC + 8, PPC = KC / 4, U = COLS * PPC / kWgThreads;
     constexpr int BUF = 2 * COLS * STRIDE;         // elements of one operand buffer: hi columns, then lo columns
     constexpr int PASS = kWaves * TW;              // row tiles per pass
     constexpr int RING = 8 * TW;                   // weight fragments of one chunk per wavefront = loads in flight per lane
-    static_assert(TW == 1 || TW == 2, "tiles per wavefront");
+    static_assert((TW == 1 || TW == 2) && (NB == 1 || NB == 2 || NB == 4), "tiles per wavefront, column blocks");
     static_assert((size_t)2 * BUF * 2 + (64 + 512) * 4 <= (size_t)kLdsBytes, "two operand buffers and the norm scratch fit");
     static_assert((size_t)PASS * NB * 256 * 4 <= (size_t)2 * BUF * 2, "the tiles' accumulators alias the operand buffers");
     const int wave = wave_id(), lane = lane_id();
@@ -894,7 +896,7 @@ __device__ __noinline__ void gemm_tiles_wide(const Params &P, const ChunkedArgs 
 }
 
 // Passes of the wide path: 8 x TW row tiles each.
-template <int TW>
+template <int TW, int NB>
 __device__ __forceinline__ void gemm_tiles_wide_passes(const Params &PL, ChunkedArgs a, ChunkedArgs *slot, float *sm, int *frame_anchor)
 {
     constexpr int PASS = kWaves * TW;
@@ -906,7 +908,7 @@ __device__ __forceinline__ void gemm_tiles_wide_passes(const Params &PL, Chunked
             if (threadIdx.x == 0) lds_put(slot, a);
             __syncthreads();
         }
-        gemm_tiles_wide<TW>(PL, slot, sm, frame_anchor);
+        gemm_tiles_wide<TW, NB>(PL, slot, sm, frame_anchor);
         a.g.rowsA += (size_t)PASS * a.g.tile_rows * a.g.ldw;
         a.g.rowsB += (size_t)PASS * a.g.tile_rows * a.g.ldw;
         a.e.row0 += PASS * a.g.tile_rows;
@@ -954,10 +956,13 @@ __device__ __noinline__ void gemm_chunked_entry(const Params &PL, ChunkedArgs *s
         else if (a.g.n_tiles <= 4 || NB_ == 4) gemm_tiles_chunked_passes<NB_, 4>(PL, a, slot, sm, &anchor);  \
         else gemm_tiles_chunked_passes<NB_, NB_ == 4 ? 4 : 8>(PL, a, slot, sm, &anchor);   /* several passes: crowded expert */ \
     }
-    if (a.g.n_cols > 32 && a.g.n_tiles >= 16 && a.g.K % 256 == 0) gemm_tiles_wide_passes<2>(PL, a, slot, sm, &anchor);
-    else if (a.g.n_cols > 32 && a.g.n_tiles >= 5 && a.g.K % 256 == 0) gemm_tiles_wide_passes<1>(PL, a, slot, sm, &anchor);
+    if (a.g.n_cols > 32 && a.g.n_tiles >= 16 && a.g.K % 256 == 0) gemm_tiles_wide_passes<2, 4>(PL, a, slot, sm, &anchor);
+    else if (a.g.n_cols > 32 && a.g.n_tiles >= 5 && a.g.K % 256 == 0) gemm_tiles_wide_passes<1, 4>(PL, a, slot, sm, &anchor);
     else if (a.g.n_cols > 32) ETC_CHUNKED(4)
+    else if (a.g.n_cols > 16 && a.g.n_tiles >= 9 && a.g.K % 256 == 0) gemm_tiles_wide_passes<2, 2>(PL, a, slot, sm, &anchor);   // 9 .. 16 tiles against ONE pass over the operand
+    else if (a.g.n_cols > 16 && a.g.n_tiles >= 5 && a.g.K % 256 == 0) gemm_tiles_wide_passes<1, 2>(PL, a, slot, sm, &anchor);
     else if (a.g.n_cols > 16) ETC_CHUNKED(2)
+    else if (a.g.n_tiles >= 5 && a.g.K % 256 == 0) gemm_tiles_wide_passes<1, 1>(PL, a, slot, sm, &anchor);
     else ETC_CHUNKED(1)
 #undef ETC_CHUNKED
 }

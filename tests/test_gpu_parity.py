@@ -422,3 +422,30 @@ def test_tiny_large_batches_take_the_chunked_path(batch):
         _check_invariants(dec)
         np.testing.assert_array_equal(out3, out)
         dec.close()
+
+
+# ---------------------------------------------------------------- long attention chunks at head dim 128
+@pytest.mark.parametrize("kind", [0, 1])
+@pytest.mark.parametrize("grp,qk_norm", [(8, False), (8, True), (4, False)])
+def test_long_chunks_head_dim_128(grp, qk_norm, kind):
+    """Chunks longer than one batch of keys at head dim 128: 8 query heads per KV head run on the matrix cores
+    (32 keys per wavefront step), 4 on the vector path.  Lengths sit on and around the 32-key steps, the 16-token pages
+    and the chunk boundary: sequences of one chunk (written directly) and of two and three chunks (partial results,
+    merged by the chunk task that arrives last), one key, and a last chunk that holds the step's own token alone."""
+    etc = _etc()
+    s = synth.ModelShape(f"d128-g{grp}", 2, 256, grp, 1, 128, 512, qk_norm=qk_norm)
+    lens = [0, 31, 32, 33, 255, 256, 257, 511, 512, 700, 767]        # kv_len: keys before this step's token
+    model = GpuModel(s, seed=21, n_pool_pages=len(lens) * 49 + 8)
+    step = fixed_step(s, len(lens), lens, model.n_pool_pages, seed=9)
+    dec = etc.Decoder(s, kv_chunk_tokens=256, sampled_batches=[len(lens)], max_kv_len=769, kind=kind,
+                      debug_flags=etc.DEBUG_EXEC_COUNT | etc.DEBUG_LAYER_HIDDEN, spin_budget=SPIN)
+    model.bind(dec)
+    out = _run(dec, model, step)
+    _check_invariants(dec)
+    ref = oracle_step(s, model.seed, model.n_pool_pages, step, 0)
+    for l in range(s.n_layers):
+        got, want = dec.layer_hidden(l), ref["layers"][l]
+        for b in range(len(lens)):
+            assert rel_err(got[b], want[b]) <= TOL, f"layer {l}, sequence {b} (kv_len {lens[b]})"
+    assert rel_err(out, ref["final"]) <= TOL
+    dec.close()

@@ -240,7 +240,17 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
         // hidden/16 row tiles in all, are cut along K instead: a task takes that many row tiles and one slice of K
         // and leaves fp32 partial sums, which a second, small task adds up in slice order (two-stage
         // reduction as in the row-sum example of Sec. 2.2).
-        if (sub % 2 == 0) r_qkv = 2;
+        {   // row tiles per QKV task: what moves the fewest bytes through a queue, as for gate/up below (a task reads
+            // the whole operand whatever it streams; two rounds of small tasks read it twice)
+            const long long tile_bytes = 16LL * m.H * 2, operand_bytes = (long long)Bs * m.H * 4;
+            const int tiles = (m.nq + 2 * m.nkv) * sub;
+            long long best = -1;
+            for (int r = 1; r <= sub; r *= 2) {
+                if (sub % r) continue;
+                const long long rounds = (tiles / r + n_queues - 1) / n_queues, cost = rounds * (r * tile_bytes + operand_bytes);
+                if (best < 0 || cost < best || (cost == best && r == 2)) { best = cost; r_qkv = r; }
+            }
+        }
         g.k_slices_o = k_slices_for(m.nq * m.d);
         if (m.E == 0) {
             g.k_slices_d = k_slices_for(m.F);

@@ -204,6 +204,7 @@ std::string build_decoder_graph(const ModelDims &m, int Bs, int n_queues, bool m
     if (m.H % 16) return "hidden must be a multiple of 16";
     if (m.E == 0 && (m.F % (kWaves * 32) || (m.F / 8) % kWaves)) return "ffn must be a multiple of 256";
     if (m.n_layers > kMaxLayers) return "too many layers";
+    if (m.page < 1 || (m.page & (m.page - 1))) return "page_size must be a power of two";
     if (m.E > 0) {
         if (m.E % 16 || m.E > kMaxExperts) return "n_experts must be a multiple of 16, at most 256";
         if (m.topk < 1 || m.topk > kMaxTopK || m.topk > m.E) return "top_k must be in 1..16 and at most n_experts";

@@ -187,6 +187,18 @@ def test_descriptor_validation_errors_are_reported():
     assert ei.value.status == -1 and "256" in str(ei.value)
 
 
+def test_page_size_must_be_a_power_of_two():
+    """The attention key loop locates a key's page with a shift and a mask."""
+    for page, ok in ((16, True), (1, True), (64, True), (12, False), (24, False)):
+        s = synth.ModelShape("p", 1, 256, 4, 2, 64, 1024, page=page)
+        if ok:
+            etc.plan_build(s, page * 2, 1, 4, max_kv_len=page * 4)
+        else:
+            with pytest.raises(etc.EtcError) as ei:
+                etc.plan_build(s, page * 2, 1, 4, max_kv_len=page * 4)
+            assert ei.value.status == -1 and "power of two" in str(ei.value)
+
+
 def test_attention_shapes_without_a_task_body_are_refused():
     """The attention task bodies exist for a list of (head_dim, query heads per KV head) pairs; a descriptor outside
     it must be refused when the plan is built (it used to pass, run no attention body and still notify)."""

@@ -258,6 +258,8 @@ class CompiledGraph:
         self.eg.launch(stream)
 
     def __getattr__(self, name):                # step_info, event_counters, exec_counts, error_word, close
+        if name in ("eg", "graph", "_values"):    # not set (yet): no delegation, or this would recurse
+            raise AttributeError(name)
         return getattr(self.eg, name)
 
 

@@ -73,7 +73,9 @@ class DeviceFn:
 @dataclasses.dataclass
 class Edge:
     """Maps a task coordinate to an element of an event tensor: per event dimension ("dim", src, div) = task
-    coordinate src divided by div, or ("const", v)."""
+    coordinate src divided by div, or ("const", v).  Data-dependent edges (Sec. 2.4) on a rank-1 event tensor, as in
+    include/etc.h: [("indirect",)] on an out-edge (task (i, ...) notifies event table[i], tables in slots 3 and 5),
+    [("indptr",)] on the in-edge of a rank-1 grid (event e releases tasks indptr[e] .. indptr[e+1], slot 4)."""
     event: int
     maps: List[Tuple]
 
@@ -132,8 +134,14 @@ class Graph:
             for m in e.maps:
                 if m[0] == "dim" and not (0 <= m[1] < len(grid) and m[2] >= 1):
                     raise ValueError("('dim', src, div): src is a grid dimension, div >= 1")
-                if m[0] not in ("dim", "const"):
-                    raise ValueError("maps are ('dim', src, div) or ('const', v)")
+                if m[0] not in ("dim", "const", "indirect", "indptr"):
+                    raise ValueError("maps are ('dim', src, div), ('const', v), ('indirect',) or ('indptr',)")
+                if m[0] in ("indirect", "indptr") and len(e.maps) != 1:
+                    raise ValueError("data-dependent edges take a rank-1 event tensor")
+        if any(m[0] == "indirect" for e in waits for m in e.maps) or any(m[0] == "indptr" for e in notifies for m in e.maps):
+            raise ValueError("('indirect',) belongs on an out-edge, ('indptr',) on an in-edge")
+        if any(m[0] == "indptr" for e in waits for m in e.maps) and len(grid) != 1:
+            raise ValueError("an ('indptr',) in-edge releases the tasks of a rank-1 grid")
         self.calls.append(Call(fn, grid, list(waits), list(notifies)))
 
     def fingerprint(self) -> str:
@@ -211,9 +219,13 @@ class CompiledGraph:
             raise RuntimeError(f"{library} carries {n.value} generated device functions, the graph has {len(g.fns)}: rebuild it")
         self.eg = _b.EventGraph(kind=kind, debug_flags=debug_flags, spin_budget=spin_budget, n_queues=n_queues,
                                 library=library)
-        kinds = {"dim": _b.MAP_DIM, "const": _b.MAP_CONST}
-        conv = lambda e: self.eg.edge(e.event, [(kinds[m[0]], m[1], m[2]) if m[0] == "dim" else (kinds[m[0]], 0, m[1])   # noqa: E731
-                                                for m in e.maps])
+        def one_map(m):
+            if m[0] == "dim":
+                return (_b.MAP_DIM, m[1], m[2])
+            if m[0] == "const":
+                return (_b.MAP_CONST, 0, m[1])
+            return (_b.MAP_INDIRECT if m[0] == "indirect" else _b.MAP_INDPTR, 0, 1)
+        conv = lambda e: self.eg.edge(e.event, [one_map(m) for m in e.maps])   # noqa: E731
         for _, shape in g.events:
             self.eg.add_event([_b.DimExpr(d.sym, d.mul, d.add) for d in shape])
         for c in g.calls:
@@ -327,7 +339,43 @@ def sumsq_example() -> Graph:
     return g
 
 
-EXAMPLES = {"rowsum": rowsum_example, "sumsq": sumsq_example}
+def routed_rowsum_example(n_max: int = 24, groups: int = 5) -> Graph:
+    """The two data-dependent mechanisms of Sec. 2.4 with generated device functions: n row blocks are routed to
+    `groups` groups by a run-time table (slot 3); the partial sums of row block i notify the event of group table[i]
+    (how often an event is notified is known at run time only: slot 5), and event g releases the final-sum tasks
+    indptr[g] .. indptr[g+1] (slot 4), task t summing row block perm[t] (slot 6).  The final grid is sized for n_max
+    row blocks: tasks beyond indptr[groups] have nothing to do (static rule) or are never released (ready queue)."""
+    g = Graph("routed_rowsum", ["n"])
+    n = g.sym("n")
+    G = g.event("G", [groups])
+    partial = g.device_fn("partial_sum", """
+    if (threadIdx.x < 32) {
+        const int row = 32 * c0 + (int)threadIdx.x;
+        const float *src = a.buf[0] + (size_t)row * 128 + 32 * c1;
+        float acc = 0.f;
+        for (int k = 0; k < 32; ++k) acc += src[k];
+        st_f32(a.buf[1] + (size_t)row * 4 + c1, acc);
+    }""", {0: lambda s: s["n"] * 32 * 128 * 4, 1: lambda s: s["n"] * 32 * 4 * 4,
+           3: lambda s: s["n"] * 4, 4: lambda s: (groups + 1) * 4, 5: lambda s: groups * 4})
+    final = g.device_fn("final_sum_of_routed_block", f"""
+    // task t of the grouped grid: row block perm[t]; tasks beyond the last group's range, and entries that name no
+    // row block, do nothing
+    const int32_t *indptr = reinterpret_cast<const int32_t *>(a.buf[4]), *perm = reinterpret_cast<const int32_t *>(a.buf[6]);
+    if (c0 >= gld_i32(indptr + {groups})) return;
+    const int r = gld_i32(perm + c0);
+    if (r < 0 || r >= a.sym[0]) return;
+    if (threadIdx.x < 32) {{
+        const int row = 32 * r + (int)threadIdx.x;
+        const float *b = a.buf[1] + (size_t)row * 4;
+        a.buf[2][row] = ((ld_f32(b) + ld_f32(b + 1)) + ld_f32(b + 2)) + ld_f32(b + 3);
+    }}""", {1: lambda s: s["n"] * 32 * 4 * 4, 2: lambda s: s["n"] * 32 * 4, 4: lambda s: (groups + 1) * 4,
+            6: lambda s: n_max * 4})
+    g.call(partial, [n, 4], notifies=[Edge(G, [("indirect",)])])
+    g.call(final, [n_max], waits=[Edge(G, [("indptr",)])])
+    return g
+
+
+EXAMPLES = {"rowsum": rowsum_example, "sumsq": sumsq_example, "routed_rowsum": routed_rowsum_example}
 
 
 def build_examples(verbose: bool = False) -> List[str]:

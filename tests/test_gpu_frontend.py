@@ -68,3 +68,43 @@ def test_stock_library_refuses_generated_function_ids():
     ev = g.add_event([g.dim(sym=0, mul=1)])
     with pytest.raises(etc.EtcError):
         g.add_call(100, [g.dim(sym=0, mul=1)], out_edges=[g.edge(ev, [(0, 0, 1)])])
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_generated_graph_with_data_dependent_edges(kind):
+    """Sec. 2.4 through generated dispatch: run-time routed notifies (the event's count comes with the table) and
+    events that release ranges of a grouped grid; surplus tasks of the grid write nothing (and under the ready queue
+    never run).  Whatever the routing, C is the plain row sum of A."""
+    import torch
+    n_max, m = 24, 5
+    cg = _compiled("routed_rowsum", kind)
+    rng = np.random.default_rng(17)
+    for rep, n_rows in enumerate((24, 7, 1, 19)):
+        A = rng.integers(-8, 9, size=(n_rows * 32, 128)).astype(np.float32)
+        route = rng.integers(0, m, size=n_rows).astype(np.int32)
+        if rep == 1:
+            route[:] = 2                                   # everything to one group
+        perm = np.argsort(route, kind="stable").astype(np.int32)
+        per_group = np.bincount(route, minlength=m)
+        indptr = np.concatenate([[0], np.cumsum(per_group)]).astype(np.int32)
+        count = (4 * per_group).astype(np.int32)
+        perm_full = np.concatenate([perm, np.zeros(n_max - n_rows, np.int32)])
+        dA = torch.from_numpy(A).cuda()
+        dB = torch.full((n_rows * 32, 4), float("nan"), device="cuda")
+        dC = torch.full((n_max * 32,), float("nan"), device="cuda")
+        tabs = [torch.from_numpy(x).cuda() for x in (route, indptr, count, perm_full)]
+        for slot, t in enumerate([dA, dB, dC] + tabs):
+            cg.bind_buffer(slot, t)
+        cg.bind_shape(n=n_rows)
+        for launches in (1, 2):
+            dC.fill_(float("nan"))
+            cg.launch()
+            torch.cuda.synchronize()
+            got = dC.cpu().numpy()
+            np.testing.assert_array_equal(got[: n_rows * 32], A.astype(np.float64).sum(1))
+            assert np.isnan(got[n_rows * 32:]).all()
+            assert (cg.error_word() == 0).all() and (cg.event_counters() == 0).all()
+            want = np.full(4 * n_rows + n_max, launches, np.int32)
+            if kind == 1:
+                want[4 * n_rows + n_rows:] = 0             # the ready queue never released the surplus tasks
+            np.testing.assert_array_equal(cg.exec_counts(), want)
